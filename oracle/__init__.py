@@ -1,0 +1,222 @@
+"""CPU oracle for SBNet's tiled sparse convolution (arXiv 1801.02108).
+
+TEST INFRASTRUCTURE ONLY: a plain, slow, fp64 statement of what the method computes.
+Only the tests, the smoke check and the benchmark's CPU-baseline leg may import it; the
+GPU library never does, and the two share no code.
+
+The arithmetic lives in ``sbnet_oracle.c`` (direct loops in double precision).  This
+module marshals numpy arrays into it and composes the steps in the order the paper gives
+them (Fig. 1: reduce mask -> gather -> convolution -> scatter; Fig. 4 / Sec. 3.3: a whole
+residual unit between one gather and one scatter-add).  Every function is pinned by
+``tests/test_oracle_pins.py`` to facts that do not come from this code.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sbnet_oracle.c")
+_LIB = os.path.join(_HERE, "libsbnet_oracle.so")
+
+POOL_MAX = 0
+POOL_AVG = 1
+
+
+def build(force=False):
+    """Compile the C oracle with gcc (no tuning flags beyond -O2)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-shared", "-fPIC", "-o", _LIB, _SRC])
+    return _LIB
+
+
+class Geom(ctypes.Structure):
+    """Block geometry: extent, stride, origin and count of blocks along h and w."""
+    _fields_ = [(n, ctypes.c_int) for n in (
+        "size_h", "size_w", "stride_h", "stride_w", "off_h", "off_w", "count_h", "count_w")]
+
+    def astuple(self):
+        return tuple(getattr(self, n) for n, _ in self._fields_)
+
+
+_lib = None
+
+
+def _c():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_reduce_mask.restype = ctypes.c_int
+    return _lib
+
+
+def _d(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+# ---------------------------------------------------------------------------------------
+# geometry (Sec. 3.1, Fig. 3)
+# ---------------------------------------------------------------------------------------
+def conv_out_size(h, k, s, pad=0):
+    """Output extent of a convolution: floor((h + 2 pad - k) / s) + 1."""
+    return (h + 2 * pad - k) // s + 1
+
+
+def geometry(H, W, k, s, bo):
+    """Input-tile and output-block geometry for a k x k, stride-s, SAME convolution whose
+    output is cut into bo x bo blocks.  Returns (g_in, g_out, H_out, W_out)."""
+    p = (k - 1) // 2
+    H_out, W_out = conv_out_size(H, k, s, p), conv_out_size(W, k, s, p)
+    bh, bw = -(-H_out // bo), -(-W_out // bo)
+    bsize = (bo - 1) * s + k
+    g_in = Geom(bsize, bsize, bo * s, bo * s, -p, -p, bh, bw)
+    g_out = Geom(bo, bo, bo, bo, 0, 0, bh, bw)
+    return g_in, g_out, H_out, W_out
+
+
+# ---------------------------------------------------------------------------------------
+# the four steps
+# ---------------------------------------------------------------------------------------
+def reduce_mask(mask, g, pool=POOL_AVG, threshold=0.0):
+    """mask [N,H,W] -> int32 [B,3] active block coordinates (n, by, bx), lexicographic."""
+    mask, pm = _d(mask)
+    N, H, W = mask.shape
+    cap = N * g.count_h * g.count_w
+    idx = np.zeros((max(cap, 1), 3), dtype=np.int32)
+    cnt = _c().orc_reduce_mask(pm, N, H, W, ctypes.byref(g), int(pool),
+                               ctypes.c_double(float(threshold)),
+                               idx.ctypes.data_as(ctypes.c_void_p), cap)
+    return idx[:cnt].copy()
+
+
+def gather(x, idx, g):
+    """x [N,H,W,C], idx [B,3] -> tiles [B, size_h, size_w, C]; zero outside the image."""
+    x, px = _d(x)
+    idx, pi = _i(idx)
+    N, H, W, C = x.shape
+    B = idx.shape[0]
+    tiles = np.zeros((B, g.size_h, g.size_w, C), dtype=np.float64)
+    _c().orc_gather(px, N, H, W, C, pi, B, ctypes.byref(g), tiles.ctypes.data_as(ctypes.c_void_p))
+    return tiles
+
+
+def scatter(tiles, idx, g, y, add=False):
+    """Write (or add) tiles [B, size_h, size_w, C] into a copy of y [N,H,W,C]; returns it."""
+    tiles, pt = _d(tiles)
+    idx, pi = _i(idx)
+    y = np.array(y, dtype=np.float64, order="C", copy=True)
+    N, H, W, C = y.shape
+    B = idx.shape[0]
+    assert tiles.shape == (B, g.size_h, g.size_w, C), (tiles.shape, (B, g.size_h, g.size_w, C))
+    _c().orc_scatter(pt, pi, B, ctypes.byref(g), y.ctypes.data_as(ctypes.c_void_p), N, H, W, C,
+                     int(bool(add)))
+    return y
+
+
+def conv_valid(tiles, w, bias=None, stride=1, relu=False):
+    """Unpadded cross-correlation on a tile stack; w is HWIO [kh,kw,Cin,Cout]."""
+    tiles, pt = _d(tiles)
+    w, pw = _d(w)
+    B, h, wi, Cin = tiles.shape
+    kh, kw, Cin2, Cout = w.shape
+    assert Cin == Cin2
+    pb = None
+    if bias is not None:
+        bias, pb = _d(bias)
+        assert bias.shape == (Cout,)
+    ho, wo = conv_out_size(h, kh, stride), conv_out_size(wi, kw, stride)
+    out = np.zeros((B, ho, wo, Cout), dtype=np.float64)
+    _c().orc_conv_valid(pt, B, h, wi, Cin, pw, pb, kh, kw, stride, stride, Cout, int(bool(relu)),
+                        out.ctypes.data_as(ctypes.c_void_p))
+    return out
+
+
+def conv_dense(x, w, bias=None, stride=1, relu=False):
+    """Zero-padded (SAME, pad = (k-1)/2) cross-correlation of the whole feature map."""
+    x, px = _d(x)
+    w, pw = _d(w)
+    N, H, W, Cin = x.shape
+    kh, kw, Cin2, Cout = w.shape
+    assert Cin == Cin2
+    ph, pwd = (kh - 1) // 2, (kw - 1) // 2
+    pb = None
+    if bias is not None:
+        bias, pb = _d(bias)
+    Ho, Wo = conv_out_size(H, kh, stride, ph), conv_out_size(W, kw, stride, pwd)
+    out = np.zeros((N, Ho, Wo, Cout), dtype=np.float64)
+    _c().orc_conv_dense(px, N, H, W, Cin, pw, pb, kh, kw, stride, stride, ph, pwd, Cout,
+                        int(bool(relu)), out.ctypes.data_as(ctypes.c_void_p))
+    return out
+
+
+def zero_outside(tiles, idx, g, H, W):
+    """Copy of tiles with every position outside the H x W image set to zero."""
+    tiles = np.array(tiles, dtype=np.float64, order="C", copy=True)
+    idx, pi = _i(idx)
+    B, h, w, C = tiles.shape
+    assert (h, w) == (g.size_h, g.size_w)
+    _c().orc_zero_outside(tiles.ctypes.data_as(ctypes.c_void_p), pi, B, ctypes.byref(g), H, W, C)
+    return tiles
+
+
+def block_mask(idx, g_out, N, H_out, W_out):
+    """Boolean [N,H_out,W_out]: pixel lies in one of the listed output blocks."""
+    m = np.zeros((N, H_out, W_out), dtype=bool)
+    for n, by, bx in np.asarray(idx).reshape(-1, 3):
+        y0, x0 = g_out.off_h + by * g_out.stride_h, g_out.off_w + bx * g_out.stride_w
+        m[n, max(y0, 0):y0 + g_out.size_h, max(x0, 0):x0 + g_out.size_w] = True
+    return m
+
+
+# ---------------------------------------------------------------------------------------
+# compositions
+# ---------------------------------------------------------------------------------------
+def sparse_conv_tiled(x, idx, g_in, g_out, w, bias, y, stride=1, relu=False, add=False):
+    """The method, step by step (Fig. 1): gather -> valid conv -> scatter (or scatter-add)."""
+    tiles = gather(x, idx, g_in)
+    out = conv_valid(tiles, w, bias, stride=stride, relu=relu)
+    return scatter(out, idx, g_out, y, add=add)
+
+
+def sparse_conv_dense(x, idx, g_out, w, bias, y, stride=1, relu=False, add=False):
+    """What the method must equal (Sec. 3.2): the dense zero-padded convolution on the
+    pixels of active blocks, y unchanged elsewhere."""
+    d = conv_dense(x, w, bias, stride=stride, relu=relu)
+    y = np.asarray(y, dtype=np.float64)
+    m = block_mask(idx, g_out, *d.shape[:3])[..., None]
+    return np.where(m, y + d if add else d, y)
+
+
+def bottleneck_on_tiles(tiles, idx, g_in, H, W, w1, b1, w2, b2, w3, b3):
+    """Residual branch of a bottleneck unit on gathered tiles (Sec. 3.3, Fig. 4, BN folded
+    into w, b): 1x1 + ReLU on the whole tile, zero outside the image, valid 3x3 + ReLU,
+    1x1.  Returns [B, bo, bo, Cout]."""
+    t1 = conv_valid(tiles, w1, b1, relu=True)
+    t1 = zero_outside(t1, idx, g_in, H, W)
+    t2 = conv_valid(t1, w2, b2, relu=True)
+    return conv_valid(t2, w3, b3, relu=False)
+
+
+def sparse_bottleneck_tiled(x, idx, g_in, g_out, w1, b1, w2, b2, w3, b3):
+    """One sparse residual unit: one gather, three convolutions, one scatter-add onto x."""
+    x = np.asarray(x, dtype=np.float64)
+    tiles = gather(x, idx, g_in)
+    t3 = bottleneck_on_tiles(tiles, idx, g_in, x.shape[1], x.shape[2], w1, b1, w2, b2, w3, b3)
+    return scatter(t3, idx, g_out, x, add=True)
+
+
+def sparse_bottleneck_dense(x, idx, g_out, w1, b1, w2, b2, w3, b3):
+    """Dense residual unit, residual branch kept only on active blocks."""
+    x = np.asarray(x, dtype=np.float64)
+    t1 = conv_dense(x, w1, b1, relu=True)
+    t2 = conv_dense(t1, w2, b2, relu=True)
+    t3 = conv_dense(t2, w3, b3, relu=False)
+    m = block_mask(idx, g_out, *x.shape[:3])[..., None]
+    return x + np.where(m, t3, 0.0)

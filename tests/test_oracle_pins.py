@@ -1,0 +1,411 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something that does
+not come from the oracle itself -- values printed in the paper (tests/golden), library
+routines written by someone else (torch's CPU conv2d / pooling, numpy.pad), closed forms,
+brute force on tiny inputs, and the method's own invariants (Sec. 3.1-3.4 of the paper).
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle as orc
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+rng0 = np.random.default_rng(20180102)
+
+
+def _torch_conv(x, w, b, stride, pad, relu=False):
+    """torch CPU conv2d in fp64: x NHWC, w HWIO."""
+    xt = torch.from_numpy(np.ascontiguousarray(x)).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(np.ascontiguousarray(w)).permute(3, 2, 0, 1)
+    bt = None if b is None else torch.from_numpy(np.ascontiguousarray(b))
+    o = F.conv2d(xt, wt, bt, stride=stride, padding=pad)
+    if relu:
+        o = torch.relu(o)
+    return o.permute(0, 2, 3, 1).contiguous().numpy()
+
+
+# ------------------------------------------------------------------ geometry
+def _read_golden(name):
+    d = {}
+    for line in open(os.path.join(GOLD, name)):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            d[k] = int(v)
+    return d
+
+
+def test_geometry_fig3_toy():
+    t = _read_golden("fig3_toy_geometry.txt")
+    g_in, g_out, H_out, _ = orc.geometry(17, 17, t["kernel"], t["kernel_stride"], t["outputs_per_block"])
+    assert g_in.size_h == g_in.size_w == t["block"]
+    assert g_in.stride_h == t["block_stride"]
+    assert g_in.size_h - g_in.stride_h == t["overlap"] == t["kernel"] - t["kernel_stride"]
+    assert orc.conv_out_size(t["block"], t["kernel"], t["kernel_stride"]) == t["outputs_per_block"]
+    assert g_out.size_h == g_out.stride_h == t["outputs_per_block"]
+
+
+@pytest.mark.parametrize("h,k", [(18, 3), (10, 3), (5, 1), (34, 3), (7, 5)])
+def test_out_size_stride1_is_h_minus_k_plus_1(h, k):
+    # Sec. 3.2: h' = (h - k + 1) / s; exact for s = 1
+    assert orc.conv_out_size(h, k, 1) == h - k + 1
+
+
+@pytest.mark.parametrize("H,W,k,s,bo", [(64, 64, 3, 1, 8), (13, 11, 3, 1, 4), (17, 9, 3, 2, 2),
+                                        (12, 12, 1, 1, 3), (800, 704, 3, 1, 16)])
+def test_geometry_output_blocks_partition_the_output(H, W, k, s, bo):
+    g_in, g_out, Ho, Wo = orc.geometry(H, W, k, s, bo)
+    cover = np.zeros((Ho, Wo), dtype=int)
+    for by in range(g_out.count_h):
+        for bx in range(g_out.count_w):
+            cover[by * bo:(by + 1) * bo, bx * bo:(bx + 1) * bo] += 1
+    assert (cover == 1).all()          # non-overlapping writes (Sec. 3.1)
+    # the input tile of a block is exactly the receptive field of its output block
+    assert g_in.size_h == (bo - 1) * s + k and g_in.stride_h == bo * s
+    assert g_in.size_h - g_in.stride_h == k - s
+    assert orc.conv_out_size(g_in.size_h, k, s) == bo
+
+
+# ------------------------------------------------------------------ reduce_mask
+def test_reduce_mask_all_ones_and_all_zeros():
+    g_in, g_out, _, _ = orc.geometry(24, 16, 3, 1, 8)
+    ones = np.ones((2, 24, 16))
+    idx = orc.reduce_mask(ones, g_in, orc.POOL_AVG, 0.0)
+    expect = np.array(list(itertools.product(range(2), range(3), range(2))), dtype=np.int32)
+    assert idx.dtype == np.int32 and np.array_equal(idx, expect)      # lexicographic (n,by,bx)
+    assert np.array_equal(orc.reduce_mask(ones, g_in, orc.POOL_MAX, 0.5), expect)
+    for pool in (orc.POOL_MAX, orc.POOL_AVG):
+        assert orc.reduce_mask(np.zeros((2, 24, 16)), g_in, pool, 0.0).shape == (0, 3)
+
+
+@pytest.mark.parametrize("window", ["tile", "block"])
+def test_reduce_mask_single_pixel_brute_force(window):
+    H, W, bo = 12, 16, 4
+    g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    g = g_in if window == "tile" else g_out
+    seen_counts = set()
+    for y in range(H):
+        for x in range(W):
+            m = np.zeros((1, H, W))
+            m[0, y, x] = 1
+            got = {tuple(r) for r in orc.reduce_mask(m, g, orc.POOL_MAX, 0.0)}
+            want = set()
+            for by in range(g.count_h):
+                for bx in range(g.count_w):
+                    y0, x0 = g.off_h + by * g.stride_h, g.off_w + bx * g.stride_w
+                    if y0 <= y < y0 + g.size_h and x0 <= x < x0 + g.size_w:
+                        want.add((0, by, bx))
+            assert got == want
+            seen_counts.add(len(got))
+    # with the halo in the window a pixel can switch on 1, 2 or 4 blocks; without it exactly 1
+    assert seen_counts == ({1, 2, 4} if window == "tile" else {1})
+
+
+@pytest.mark.parametrize("a,b", [(1, 1), (8, 8), (7, 9), (16, 23), (17, 24), (32, 32)])
+def test_reduce_mask_top_left_rectangle_closed_form(a, b):
+    # the paper's synthetic masks: a top-left sub-region (Sec. 4.3).  A block whose window
+    # starts at by*bo - 1 is active iff by*bo - 1 <= a - 1, i.e. by <= a/bo.
+    H = W = 32
+    bo = 8
+    g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    m = np.zeros((1, H, W))
+    m[0, :a, :b] = 1
+    rows = min(a // bo + 1, H // bo)
+    cols = min(b // bo + 1, W // bo)
+    idx = orc.reduce_mask(m, g_in, orc.POOL_AVG, 0.0)
+    assert len(idx) == rows * cols
+    assert np.array_equal(idx, np.array([(0, r, c) for r in range(rows) for c in range(cols)], dtype=np.int32))
+    # window = output block only: ceil(a/bo) * ceil(b/bo)
+    idx2 = orc.reduce_mask(m, g_out, orc.POOL_AVG, 0.0)
+    assert len(idx2) == -(-a // bo) * -(-b // bo)
+
+
+def test_reduce_mask_matches_torch_pooling():
+    # library special case: pooling with kernel=bsize, stride=bo, padding=1 (zeros)
+    N, H, W, bo = 3, 40, 24, 8
+    g_in, _, _, _ = orc.geometry(H, W, 3, 1, bo)
+    m = (rng0.random((N, H, W)) < 0.02).astype(np.float64)
+    real = rng0.random((N, H, W)) * m
+    mt = torch.from_numpy(real)[:, None]
+    avg = F.avg_pool2d(mt, g_in.size_h, stride=bo, padding=1, count_include_pad=True)[:, 0, :H // bo, :W // bo]
+    mx = F.max_pool2d(mt, g_in.size_h, stride=bo, padding=1)[:, 0, :H // bo, :W // bo]
+    for thr in (0.0, 0.001, 0.004, 0.3):
+        want = np.argwhere(avg.numpy() > thr).astype(np.int32)
+        assert np.array_equal(orc.reduce_mask(real, g_in, orc.POOL_AVG, thr), want)
+        want = np.argwhere(mx.numpy() > thr).astype(np.int32)
+        assert np.array_equal(orc.reduce_mask(real, g_in, orc.POOL_MAX, thr), want)
+
+
+def test_reduce_mask_threshold_is_strict_and_avg_divides_by_full_window():
+    g = orc.Geom(2, 2, 2, 2, 0, 0, 1, 2)
+    m = np.zeros((1, 2, 4))
+    m[0, 0, 0] = 1; m[0, 1, 1] = 1          # block 0: mean 0.5 ; block 1: mean 0
+    assert len(orc.reduce_mask(m, g, orc.POOL_AVG, 0.5)) == 0          # 0.5 > 0.5 is false
+    assert np.array_equal(orc.reduce_mask(m, g, orc.POOL_AVG, 0.49), [[0, 0, 0]])
+    # window partly outside the image still divides by the full 3x3 area
+    g = orc.Geom(3, 3, 2, 2, -1, -1, 1, 1)
+    m = np.ones((1, 2, 2))                   # 4 ones in a 9-cell window: mean 4/9
+    assert len(orc.reduce_mask(m, g, orc.POOL_AVG, 0.45)) == 0
+    assert len(orc.reduce_mask(m, g, orc.POOL_AVG, 0.44)) == 1
+
+
+def test_reduce_mask_max_equals_avg_at_zero_threshold_on_binary_masks():
+    g_in, _, _, _ = orc.geometry(48, 40, 3, 1, 8)
+    for seed in range(5):
+        m = (np.random.default_rng(seed).random((2, 48, 40)) < 0.01).astype(np.float64)
+        assert np.array_equal(orc.reduce_mask(m, g_in, orc.POOL_MAX, 0.0),
+                              orc.reduce_mask(m, g_in, orc.POOL_AVG, 0.0))
+
+
+def test_reduce_mask_sample_order_independence():
+    g_in, _, _, _ = orc.geometry(32, 32, 3, 1, 8)
+    m = (rng0.random((3, 32, 32)) < 0.01).astype(np.float64)
+    full = orc.reduce_mask(m, g_in)
+    for n in range(3):
+        one = orc.reduce_mask(m[n:n + 1], g_in)
+        assert np.array_equal(full[full[:, 0] == n][:, 1:], one[:, 1:])
+
+
+# ------------------------------------------------------------------ gather / scatter
+@pytest.mark.parametrize("H,W,C,k,s,bo", [(16, 24, 3, 3, 1, 8), (13, 10, 2, 3, 1, 4), (17, 17, 1, 3, 2, 2),
+                                          (9, 9, 4, 5, 1, 3), (8, 8, 5, 1, 1, 4)])
+def test_gather_equals_pad_and_slice(H, W, C, k, s, bo):
+    g_in, g_out, Ho, Wo = orc.geometry(H, W, k, s, bo)
+    x = rng0.standard_normal((2, H, W, C))
+    idx = orc.reduce_mask(np.ones((2, H, W)), g_in)
+    tiles = orc.gather(x, idx, g_in)
+    P = g_in.size_h + max(g_in.stride_h * g_in.count_h, g_in.stride_w * g_in.count_w)
+    xp = np.pad(x, ((0, 0), (P, P), (P, P), (0, 0)))
+    for b, (n, by, bx) in enumerate(idx):
+        y0 = g_in.off_h + by * g_in.stride_h + P
+        x0 = g_in.off_w + bx * g_in.stride_w + P
+        assert np.array_equal(tiles[b], xp[n, y0:y0 + g_in.size_h, x0:x0 + g_in.size_w])
+    # first tile: its top row and left column lie outside the image for k = 3
+    if k == 3:
+        assert (tiles[0, 0] == 0).all() and (tiles[0, :, 0] == 0).all()
+        assert np.array_equal(tiles[0, 1, 1], x[0, 0, 0])
+
+
+def test_gather_delta_input_lands_where_predicted():
+    H, W, bo = 12, 12, 4
+    g_in, _, _, _ = orc.geometry(H, W, 3, 1, bo)
+    idx = orc.reduce_mask(np.ones((1, H, W)), g_in)
+    x = np.zeros((1, H, W, 2))
+    x[0, 4, 7, 1] = 5.0        # row 4 is the first row of block-row 1 and the halo of block-row 0
+    tiles = orc.gather(x, idx, g_in)
+    hits = {(int(b), int(i), int(j), int(c)) for b, i, j, c in np.argwhere(tiles != 0)}
+    # block (by,bx) has origin (4by-1, 4bx-1); pixel (4,7) sits at (4-4by+1, 7-4bx+1)
+    want = set()
+    for b, (n, by, bx) in enumerate(idx):
+        i, j = 4 - (4 * by - 1), 7 - (4 * bx - 1)
+        if 0 <= i < 6 and 0 <= j < 6:
+            want.add((b, i, j, 1))
+    assert hits == want and len(want) == 4
+
+
+def test_scatter_invariants():
+    H, W, C, bo = 20, 12, 3, 4
+    g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    x = rng0.standard_normal((2, H, W, C))
+    y0 = rng0.standard_normal((2, H, W, C))
+    all_idx = orc.reduce_mask(np.ones((2, H, W)), g_in)
+    # (1) empty index list: y untouched
+    assert np.array_equal(orc.scatter(np.zeros((0, bo, bo, C)), np.zeros((0, 3), np.int32), g_out, y0), y0)
+    # (2) round trip with every block active: scatter(interior(gather(x))) == x
+    tiles = orc.gather(x, all_idx, g_in)
+    assert np.array_equal(orc.scatter(tiles[:, 1:-1, 1:-1], all_idx, g_out, np.zeros_like(x)), x)
+    # (3) add onto zeros equals plain write; add onto y0 equals y0 + write-onto-zeros
+    m = (rng0.random((2, H, W)) < 0.02).astype(float)
+    idx = orc.reduce_mask(m, g_in)
+    assert 0 < len(idx) < len(all_idx)
+    t = rng0.standard_normal((len(idx), bo, bo, C))
+    w0 = orc.scatter(t, idx, g_out, np.zeros_like(x))
+    assert np.array_equal(orc.scatter(t, idx, g_out, np.zeros_like(x), add=True), w0)
+    assert np.array_equal(orc.scatter(t, idx, g_out, y0, add=True), y0 + w0)
+    # (4) written set == union of active blocks, each pixel written exactly once
+    hits = orc.scatter(np.ones_like(t), idx, g_out, np.zeros_like(x), add=True)
+    bm = orc.block_mask(idx, g_out, 2, H, W)
+    assert np.array_equal(hits[..., 0], bm.astype(float)) and hits.max() == 1.0
+    # (5) plain write leaves pixels of inactive blocks bit-identical
+    out = orc.scatter(t, idx, g_out, y0)
+    assert np.array_equal(out[~bm], y0[~bm])
+    # (6) ragged edge: blocks hanging over the image are clipped
+    g_in2, g_out2, _, _ = orc.geometry(10, 10, 3, 1, 4)
+    idx2 = orc.reduce_mask(np.ones((1, 10, 10)), g_in2)
+    assert len(idx2) == 9
+    full = orc.scatter(np.ones((9, 4, 4, 1)), idx2, g_out2, np.zeros((1, 10, 10, 1)), add=True)
+    assert (full == 1).all()
+
+
+# ------------------------------------------------------------------ convolution
+@pytest.mark.parametrize("k,s,Cin,Cout", [(3, 1, 4, 5), (1, 1, 6, 3), (3, 2, 3, 4), (5, 1, 2, 2)])
+def test_conv_matches_torch_fp64(k, s, Cin, Cout):
+    x = rng0.standard_normal((2, 11, 9, Cin))
+    w = rng0.standard_normal((k, k, Cin, Cout))
+    b = rng0.standard_normal(Cout)
+    for relu in (False, True):
+        np.testing.assert_allclose(orc.conv_valid(x, w, b, stride=s, relu=relu),
+                                   _torch_conv(x, w, b, s, 0, relu), rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(orc.conv_dense(x, w, b, stride=s, relu=relu),
+                                   _torch_conv(x, w, b, s, (k - 1) // 2, relu), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(orc.conv_dense(x, w, None, stride=s), _torch_conv(x, w, None, s, (k - 1) // 2),
+                               rtol=1e-12, atol=1e-12)
+
+
+def test_conv_ones_closed_form():
+    # all-ones input and kernel: each output counts the taps that fall inside the image
+    Cin = 3
+    out = orc.conv_dense(np.ones((1, 5, 6, Cin)), np.ones((3, 3, Cin, 2)))
+    assert out.shape == (1, 5, 6, 2)
+    assert out[0, 0, 0, 0] == 4 * Cin and out[0, 0, 2, 1] == 6 * Cin and out[0, 2, 2, 0] == 9 * Cin
+    assert out[0, 4, 5, 1] == 4 * Cin
+    assert (orc.conv_valid(np.ones((1, 5, 6, Cin)), np.ones((3, 3, Cin, 2))) == 9 * Cin).all()
+
+
+def test_conv_identity_and_shift_taps():
+    x = rng0.standard_normal((1, 7, 8, 3))
+    eye = np.eye(3)
+    w = np.zeros((3, 3, 3, 3)); w[1, 1] = eye
+    assert np.array_equal(orc.conv_dense(x, w), x)
+    # tap (r,t) = (0,2): out[y,x] = in[y-1, x+1] (cross-correlation: no kernel flip)
+    w = np.zeros((3, 3, 3, 3)); w[0, 2] = eye
+    out = orc.conv_dense(x, w)
+    assert np.array_equal(out[0, 1:, :-1], x[0, :-1, 1:])
+    assert (out[0, 0] == 0).all() and (out[0, :, -1] == 0).all()
+    # channel mixing orientation: w[r,t,c,o] maps input channel c to output channel o
+    w = np.zeros((1, 1, 3, 2)); w[0, 0, 2, 1] = 1.0
+    out = orc.conv_valid(x, w)
+    assert np.array_equal(out[..., 1], x[..., 2]) and (out[..., 0] == 0).all()
+
+
+def test_conv_linearity():
+    x1, x2 = rng0.standard_normal((2, 1, 6, 6, 2))
+    w1, w2 = rng0.standard_normal((2, 3, 3, 2, 3))
+    np.testing.assert_allclose(orc.conv_valid(2 * x1 - x2, w1), 2 * orc.conv_valid(x1, w1) - orc.conv_valid(x2, w1),
+                               atol=1e-12)
+    np.testing.assert_allclose(orc.conv_valid(x1, w1 + 3 * w2), orc.conv_valid(x1, w1) + 3 * orc.conv_valid(x1, w2),
+                               atol=1e-12)
+
+
+# ------------------------------------------------------------------ the method == dense conv on active blocks
+@pytest.mark.parametrize("H,W,C,K,k,s,bo", [(16, 16, 3, 4, 3, 1, 4), (13, 10, 2, 3, 3, 1, 4), (17, 17, 2, 2, 3, 2, 2),
+                                            (12, 12, 3, 2, 1, 1, 3), (10, 12, 1, 1, 3, 1, 2), (11, 9, 2, 2, 5, 1, 3)])
+def test_all_ones_mask_equals_dense_conv(H, W, C, K, k, s, bo):
+    g_in, g_out, Ho, Wo = orc.geometry(H, W, k, s, bo)
+    x = rng0.standard_normal((2, H, W, C))
+    w = rng0.standard_normal((k, k, C, K))
+    b = rng0.standard_normal(K)
+    idx = orc.reduce_mask(np.ones((2, H, W)), g_in)
+    y = orc.sparse_conv_tiled(x, idx, g_in, g_out, w, b, np.full((2, Ho, Wo, K), 7.0), stride=s)
+    np.testing.assert_allclose(y, _torch_conv(x, w, b, s, (k - 1) // 2), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_tiled_equals_dense_on_active_blocks_brute_force(seed):
+    r = np.random.default_rng(seed)
+    H, W = int(r.integers(6, 13)), int(r.integers(6, 13))
+    C, K = int(r.integers(1, 4)), int(r.integers(1, 4))
+    k = int(r.choice([1, 3])); s = int(r.choice([1, 2])); bo = int(r.choice([2, 3, 4]))
+    g_in, g_out, Ho, Wo = orc.geometry(H, W, k, s, bo)
+    x = r.standard_normal((2, H, W, C)); w = r.standard_normal((k, k, C, K)); b = r.standard_normal(K)
+    m = (r.random((2, H, W)) < 0.05).astype(float)
+    idx = orc.reduce_mask(m, g_in)
+    y0 = r.standard_normal((2, Ho, Wo, K))
+    for add in (False, True):
+        tiled = orc.sparse_conv_tiled(x, idx, g_in, g_out, w, b, y0, stride=s, add=add)
+        dense = orc.sparse_conv_dense(x, idx, g_out, w, b, y0, stride=s, add=add)
+        np.testing.assert_allclose(tiled, dense, rtol=1e-12, atol=1e-12)
+        bm = orc.block_mask(idx, g_out, 2, Ho, Wo)
+        assert np.array_equal(tiled[~bm], y0[~bm])            # inactive pixels bit-identical
+        ref = _torch_conv(x, w, b, s, (k - 1) // 2)
+        np.testing.assert_allclose(tiled[bm], (y0 + ref if add else ref)[bm], rtol=1e-12, atol=1e-12)
+
+
+def test_mask_off_leaves_y_untouched():
+    g_in, g_out, Ho, Wo = orc.geometry(8, 8, 3, 1, 4)
+    idx = orc.reduce_mask(np.zeros((1, 8, 8)), g_in)
+    y0 = rng0.standard_normal((1, 8, 8, 2))
+    y = orc.sparse_conv_tiled(rng0.standard_normal((1, 8, 8, 2)), idx, g_in, g_out,
+                              rng0.standard_normal((3, 3, 2, 2)), None, y0)
+    assert np.array_equal(y, y0)
+
+
+# ------------------------------------------------------------------ residual unit
+def _bneck_weights(r, C, Cm):
+    return (r.standard_normal((1, 1, C, Cm)), r.standard_normal(Cm), r.standard_normal((3, 3, Cm, Cm)),
+            r.standard_normal(Cm), r.standard_normal((1, 1, Cm, C)), r.standard_normal(C))
+
+
+def _torch_bottleneck(x, w1, b1, w2, b2, w3, b3):
+    t1 = _torch_conv(x, w1, b1, 1, 0, relu=True)
+    t2 = _torch_conv(t1, w2, b2, 1, 1, relu=True)
+    return x + _torch_conv(t2, w3, b3, 1, 0)
+
+
+@pytest.mark.parametrize("H,W,bo", [(8, 8, 4), (10, 7, 3), (12, 12, 2)])
+def test_bottleneck_all_ones_equals_dense_unit(H, W, bo):
+    r = np.random.default_rng(H * 100 + W)
+    C, Cm = 4, 3
+    ws = _bneck_weights(r, C, Cm)
+    x = r.standard_normal((2, H, W, C))
+    g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    idx = orc.reduce_mask(np.ones((2, H, W)), g_in)
+    y = orc.sparse_bottleneck_tiled(x, idx, g_in, g_out, *ws)
+    np.testing.assert_allclose(y, _torch_bottleneck(x, *ws), rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(orc.sparse_bottleneck_dense(x, idx, g_out, *ws), _torch_bottleneck(x, *ws),
+                               rtol=1e-11, atol=1e-11)
+
+
+def test_bottleneck_partial_mask_and_special_cases():
+    r = np.random.default_rng(5)
+    H, W, C, Cm, bo = 12, 16, 4, 3, 4
+    w1, b1, w2, b2, w3, b3 = _bneck_weights(r, C, Cm)
+    x = r.standard_normal((2, H, W, C))
+    g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    m = (r.random((2, H, W)) < 0.02).astype(float)
+    idx = orc.reduce_mask(m, g_in)
+    bm = orc.block_mask(idx, g_out, 2, H, W)
+    assert 0 < bm.mean() < 1
+    y = orc.sparse_bottleneck_tiled(x, idx, g_in, g_out, w1, b1, w2, b2, w3, b3)
+    ref = _torch_bottleneck(x, w1, b1, w2, b2, w3, b3)
+    np.testing.assert_allclose(y[bm], ref[bm], rtol=1e-11, atol=1e-11)
+    assert np.array_equal(y[~bm], x[~bm])
+    np.testing.assert_allclose(y, orc.sparse_bottleneck_dense(x, idx, g_out, w1, b1, w2, b2, w3, b3), atol=1e-11)
+    # last conv zero: the unit is the identity
+    y = orc.sparse_bottleneck_tiled(x, idx, g_in, g_out, w1, b1, w2, b2, 0 * w3, 0 * b3)
+    assert np.array_equal(y, x)
+    # first conv output forced to zero (w1 = 0, b1 <= 0): away from the image border the
+    # branch is the constant relu(b2) @ w3 + b3
+    y = orc.sparse_bottleneck_tiled(x, idx, g_in, g_out, 0 * w1, -np.abs(b1), w2, b2, w3, b3)
+    const = np.maximum(b2, 0) @ w3[0, 0] + b3
+    np.testing.assert_allclose((y - x)[bm], np.broadcast_to(const, x.shape)[bm], atol=1e-12)
+    # two units sharing one index list == applying the unit twice
+    ws2 = _bneck_weights(r, C, Cm)
+    y1 = orc.sparse_bottleneck_tiled(x, idx, g_in, g_out, w1, b1, w2, b2, w3, b3)
+    y2 = orc.sparse_bottleneck_tiled(y1, idx, g_in, g_out, *ws2)
+    d1 = orc.sparse_bottleneck_dense(x, idx, g_out, w1, b1, w2, b2, w3, b3)
+    d2 = orc.sparse_bottleneck_dense(d1, idx, g_out, *ws2)
+    # (dense form of a stack differs from the tiled one on halo pixels of inactive blocks only
+    #  through t1/t2 of inactive pixels, which the dense form also computes from the current map)
+    np.testing.assert_allclose(y2, d2, atol=1e-10)
+
+
+def test_bottleneck_border_needs_zeroed_t1():
+    # without zeroing t1 outside the image, relu(b1) leaks into the 3x3 at the border and the
+    # all-ones result no longer equals the dense unit: shows the border rule is load-bearing
+    r = np.random.default_rng(9)
+    w1, b1, w2, b2, w3, b3 = _bneck_weights(r, 3, 2)
+    b1 = np.abs(b1) + 0.5
+    x = r.standard_normal((1, 8, 8, 3))
+    g_in, g_out, _, _ = orc.geometry(8, 8, 3, 1, 4)
+    idx = orc.reduce_mask(np.ones((1, 8, 8)), g_in)
+    tiles = orc.gather(x, idx, g_in)
+    t1 = orc.conv_valid(tiles, w1, b1, relu=True)          # NOT zeroed outside
+    t3 = orc.conv_valid(orc.conv_valid(t1, w2, b2, relu=True), w3, b3)
+    leaky = orc.scatter(t3, idx, g_out, x, add=True)
+    ref = _torch_bottleneck(x, w1, b1, w2, b2, w3, b3)
+    assert np.abs(leaky - ref)[0, 0].max() > 1e-3                  # border row differs
+    np.testing.assert_allclose(leaky[0, 1:-1, 1:-1], ref[0, 1:-1, 1:-1], atol=1e-11)   # interior agrees
