@@ -1,0 +1,155 @@
+/*
+ * sbnet.h -- C ABI of the MI355X (gfx950) tiled sparse convolution library.
+ *
+ * The calls follow the problem statement of "SBNet: Sparse Blocks Network for Fast
+ * Inference" (arXiv 1801.02108): a binary computation mask is reduced to a list of active
+ * blocks (Sec. 3.1), overlapping input tiles are gathered into a dense stack (Sec. 3.2),
+ * a regular unpadded convolution -- or a whole residual unit (Sec. 3.3) -- runs on the
+ * stack, and the results are scattered or scatter-added back (Sec. 3.2, Sec. 3.4).
+ *
+ * Conventions shared by every call
+ *  - All tensor pointers are DEVICE pointers unless a comment says "host".  The caller owns
+ *    every buffer; the library allocates nothing and keeps no pointer after a call returns.
+ *  - Feature maps are dense NHWC; tile stacks are [cap][tile_h][tile_w][C]; the element
+ *    type is given by an sbnet_dtype.  Base pointers must be 16-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work; they never synchronise, except sbnet_read_count.
+ *  - The number of active blocks lives on the device: `count` points to one int32 written
+ *    by sbnet_reduce_mask.  Later calls read it on the device and process
+ *    min(*count, cap) blocks, so no host round trip is needed between the steps.
+ *  - `indices` is int32 [cap][3] = (n, by, bx): sample and block-grid coordinates, in
+ *    lexicographic order.  Pixel origins follow from an sbnet_geom.
+ *  - Return value: SBNET_OK, or an error detected on the host before anything is enqueued
+ *    (bad argument, unsupported combination) or reported by the HIP runtime at launch.
+ *    sbnet_last_error() gives a thread-local description of the last failure.
+ */
+#ifndef SBNET_H
+#define SBNET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SBNET_OK = 0,
+    SBNET_EINVAL = 1,       /* null pointer, non-positive size, inconsistent geometry      */
+    SBNET_ECAP = 2,         /* more active blocks than `cap` (sbnet_read_count only)       */
+    SBNET_EUNSUPPORTED = 3, /* valid request the library has no kernel for                 */
+    SBNET_EHIP = 4          /* the HIP runtime reported an error                           */
+} sbnet_status;
+
+typedef enum { SBNET_F32 = 0, SBNET_BF16 = 1, SBNET_F16 = 2, SBNET_U8 = 3 } sbnet_dtype;
+typedef enum { SBNET_POOL_MAX = 0, SBNET_POOL_AVG = 1 } sbnet_pool;
+
+/*
+ * Block geometry in pixels of the tensor an operation touches (Sec. 3.1, Fig. 3).  Block
+ * (by, bx) covers rows [boffset_h + by*bstride_h, +bsize_h) and the analogous columns.
+ * Input side of a k x k, stride-s, SAME convolution with bo x bo output blocks:
+ * bsize = (bo-1)*s + k, bstride = bo*s, boffset = -(k-1)/2 (tiles overlap by k - s).
+ * Output side: bsize = bstride = bo, boffset = 0 (blocks do not overlap).
+ */
+typedef struct {
+    int bsize_h, bsize_w;
+    int bstride_h, bstride_w;
+    int boffset_h, boffset_w;
+    int bcount_h, bcount_w;
+} sbnet_geom;
+
+/* Last error text of the calling thread (host pointer, valid until the next failing call). */
+const char *sbnet_last_error(void);
+
+/*
+ * Host helper: fill the input-tile geometry g_in, the output-block geometry g_out and the
+ * output extent of a kh x kw convolution with strides (sh, sw) and SAME padding (k-1)/2 on
+ * an H x W map cut into bo_h x bo_w output blocks (Sec. 3.1; output extent per Sec. 3.2
+ * read as floor((H + 2p - k)/s) + 1).  All pointers are host pointers.
+ */
+sbnet_status sbnet_geometry(int H, int W, int kh, int kw, int sh, int sw, int bo_h, int bo_w,
+                            sbnet_geom *g_in, sbnet_geom *g_out, int *H_out, int *W_out);
+
+/* Bytes of device scratch sbnet_reduce_mask needs for N samples and geometry g (host call). */
+size_t sbnet_workspace_bytes(int N, const sbnet_geom *g);
+
+/*
+ * Reduce mask to indices (Sec. 3.1; Sec. 3.4 "fused downsample and indexing").
+ * mask: [N][H][W], SBNET_U8 or SBNET_F32.  For every block window of g (pixels outside the
+ * image count as 0) the mask is max- or average-pooled (average divides by the full window
+ * area) and the block is active when pooled > threshold (strict).  Writes the active
+ * (n, by, bx) triples in lexicographic order to indices[0 .. min(count, cap)) and the true
+ * number of active blocks to *count (count is overwritten, not accumulated).
+ * workspace: device scratch of at least sbnet_workspace_bytes(N, g); contents are don't-care
+ * on entry and exit.
+ */
+sbnet_status sbnet_reduce_mask(const void *mask, sbnet_dtype mask_dtype, int N, int H, int W,
+                               const sbnet_geom *g, sbnet_pool pool, float threshold,
+                               int32_t *indices, int32_t *count, int cap, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
+/*
+ * Synchronising helper: copies *count to the host after waiting for `stream`.  Returns
+ * SBNET_ECAP (and still stores the true count) when it exceeds cap.
+ */
+sbnet_status sbnet_read_count(const int32_t *count, int cap, int *host_count, void *stream);
+
+/*
+ * Gather (Sec. 3.2 "Gather kernel"): tiles[b][i][j][c] = x[n_b][y0_b + i][x0_b + j][c], zero
+ * where the position is outside the H x W image, for b < min(*count, cap).
+ * x: [N][H][W][C]; tiles: [cap][g->bsize_h][g->bsize_w][C]; same dtype (F32, BF16 or F16).
+ * Rows of tiles beyond the active count are not written.  The copy is bit-exact.
+ */
+sbnet_status sbnet_sparse_gather(const void *x, sbnet_dtype dtype, int N, int H, int W, int C,
+                                 const int32_t *indices, const int32_t *count, int cap,
+                                 const sbnet_geom *g, void *tiles, void *stream);
+
+/*
+ * Scatter / scatter-add (Sec. 3.2 "Scatter kernel"; Sec. 3.4 "fused scatter-add"):
+ * y[n_b][y0_b + i][x0_b + j][c] = (add ? y[...] : 0) + tiles[b][i][j][c] for positions inside
+ * the image; nothing else in y is read or written (y is not cleared).  g must describe
+ * non-overlapping blocks (bstride >= bsize), otherwise SBNET_EINVAL.  The sum is formed in
+ * fp32 and rounded to the storage type (round to nearest even).
+ */
+sbnet_status sbnet_sparse_scatter(const void *tiles, sbnet_dtype dtype, const int32_t *indices,
+                                  const int32_t *count, int cap, const sbnet_geom *g, void *y,
+                                  int N, int H, int W, int C, int add, void *stream);
+
+/*
+ * Re-pack convolution weights once for the kernels below.  w_hwio: device, [kh][kw][Cin][Cout]
+ * in `dtype` (the filter bank as a (kh*kw*Cin) x Cout matrix, Sec. 2).  With w_packed == NULL
+ * only *bytes (host) is set to the size the packed copy needs.  The packed layout is private
+ * to the library and depends only on (dtype, kh, kw, Cin, Cout).
+ */
+sbnet_status sbnet_pack_weights(const void *w_hwio, sbnet_dtype dtype, int kh, int kw, int Cin,
+                                int Cout, void *w_packed, size_t *bytes, void *stream);
+
+/*
+ * Regular unpadded convolution on the tile stack (Sec. 3.2): cross-correlation,
+ * out[b][i][j][o] = act(bias[o] + sum_{r,t,c} in[b][i*sh + r][j*sw + t][c] * w[r][t][c][o]),
+ * output extent floor((th - kh)/sh) + 1 by floor((tw - kw)/sw) + 1, act = ReLU when relu != 0.
+ * tiles_in: [cap][th][tw][Cin]; tiles_out: [cap][th'][tw'][Cout]; both `dtype`.
+ * bias: device float32 [Cout] or NULL.  Products are accumulated in fp32.
+ */
+sbnet_status sbnet_conv_on_tiles(const void *tiles_in, sbnet_dtype dtype, const int32_t *count,
+                                 int cap, int th, int tw, int Cin, const void *w_packed,
+                                 const float *bias, int kh, int kw, int sh, int sw, int Cout,
+                                 int relu, void *tiles_out, void *stream);
+
+/*
+ * Fused gather -> convolution -> scatter(-add) (Fig. 1 in one kernel): same result as
+ * sbnet_sparse_gather with g_in, sbnet_conv_on_tiles, sbnet_sparse_scatter with g_out,
+ * without the intermediate tile stacks.  x: [N][H][W][Cin]; y: [N][H_out][W_out][Cout].
+ * g_in/g_out as produced by sbnet_geometry for this convolution.  y must not alias x.
+ */
+sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int N, int H, int W, int Cin,
+                               const int32_t *indices, const int32_t *count, int cap,
+                               const sbnet_geom *g_in, const sbnet_geom *g_out,
+                               const void *w_packed, const float *bias, int kh, int kw, int sh,
+                               int sw, int Cout, int relu, void *y, int H_out, int W_out,
+                               int add, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SBNET_H */

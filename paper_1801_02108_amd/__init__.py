@@ -1,0 +1,215 @@
+"""Thin Python binding of libsbnet_hip.so (see include/sbnet.h for the contract of every call).
+
+Argument marshalling only: torch tensors supply device memory and the current stream; every
+step of the path runs in the library's HIP kernels.  There is no CPU or PyTorch fallback: if
+the shared library is missing, importing a symbol from it raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsbnet_hip.so")
+
+F32, BF16, F16, U8 = 0, 1, 2, 3
+POOL_MAX, POOL_AVG = 0, 1
+OK, EINVAL, ECAP, EUNSUPPORTED, EHIP = 0, 1, 2, 3, 4
+
+_DTYPES = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16, torch.uint8: U8}
+
+
+class SbnetError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("sbnet status %d: %s" % (code, text))
+        self.code = code
+
+
+class Geom(ctypes.Structure):
+    """sbnet_geom: block extent, stride, origin and count along h and w."""
+    _fields_ = [(n, ctypes.c_int) for n in (
+        "bsize_h", "bsize_w", "bstride_h", "bstride_w", "boffset_h", "boffset_w", "bcount_h", "bcount_w")]
+
+    def astuple(self):
+        return tuple(getattr(self, n) for n, _ in self._fields_)
+
+
+_lib = None
+_vp, _ci, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+_gp = ctypes.POINTER(Geom)
+
+_SIGNATURES = {
+    "sbnet_last_error": (ctypes.c_char_p, []),
+    "sbnet_geometry": (_ci, [_ci] * 8 + [_gp, _gp, ctypes.POINTER(_ci), ctypes.POINTER(_ci)]),
+    "sbnet_workspace_bytes": (_sz, [_ci, _gp]),
+    "sbnet_reduce_mask": (_ci, [_vp, _ci, _ci, _ci, _ci, _gp, _ci, ctypes.c_float, _vp, _vp, _ci, _vp, _sz, _vp]),
+    "sbnet_read_count": (_ci, [_vp, _ci, ctypes.POINTER(_ci), _vp]),
+    "sbnet_sparse_gather": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp]),
+    "sbnet_sparse_scatter": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _ci, _vp]),
+    "sbnet_pack_weights": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
+    "sbnet_conv_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp]),
+    "sbnet_sparse_conv": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp,
+                                _ci, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _vp]),
+}
+
+
+def exported_symbols():
+    """Names include/sbnet.h declares; the loader resolves each of them."""
+    return sorted(_SIGNATURES)
+
+
+def lib():
+    """Load libsbnet_hip.so (built by build.py / __graft_entry__.build()); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s not found: run `python -m paper_1801_02108_amd.build` first" % LIB_PATH)
+        l = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def _check(code):
+    if code != OK:
+        raise SbnetError(code, lib().sbnet_last_error().decode())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _dev(t, name, dtype=None):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous device tensor" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s" % (name, dtype))
+    return t
+
+
+def _dt(t):
+    try:
+        return _DTYPES[t.dtype]
+    except KeyError:
+        raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+# ---------------------------------------------------------------------------------------------
+def geometry(H, W, k, s, bo):
+    """(g_in, g_out, H_out, W_out) for a k x k, stride-s SAME convolution with bo x bo output blocks."""
+    g_in, g_out, ho, wo = Geom(), Geom(), _ci(), _ci()
+    _check(lib().sbnet_geometry(H, W, k, k, s, s, bo, bo, g_in, g_out, ho, wo))
+    return g_in, g_out, ho.value, wo.value
+
+
+def workspace_bytes(N, g):
+    return int(lib().sbnet_workspace_bytes(N, g))
+
+
+def reduce_mask(mask, g, pool=POOL_AVG, threshold=0.0, indices=None, count=None, workspace=None):
+    """mask [N,H,W] u8/f32 -> (indices int32 [cap,3], count int32 [1]) on the device."""
+    _dev(mask, "mask")
+    N, H, W = mask.shape
+    cap = N * g.bcount_h * g.bcount_w if indices is None else indices.shape[0]
+    if indices is None:
+        indices = torch.empty((cap, 3), dtype=torch.int32, device=mask.device)
+    if count is None:
+        count = torch.empty((1,), dtype=torch.int32, device=mask.device)
+    need = workspace_bytes(N, g)
+    if workspace is None:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=mask.device)
+    _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32), _dev(workspace, "workspace")
+    _check(lib().sbnet_reduce_mask(_ptr(mask), _dt(mask), N, H, W, g, pool, float(threshold), _ptr(indices),
+                                   _ptr(count), cap, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream()))
+    return indices, count
+
+
+def read_count(count, cap):
+    out = _ci()
+    _check(lib().sbnet_read_count(_ptr(count), cap, out, _stream()))
+    return out.value
+
+
+def sparse_gather(x, indices, count, g, tiles=None):
+    """x [N,H,W,C] -> tiles [cap, bsize_h, bsize_w, C]; rows beyond the active count are untouched."""
+    _dev(x, "x"), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    N, H, W, C = x.shape
+    cap = indices.shape[0]
+    if tiles is None:
+        tiles = torch.empty((cap, g.bsize_h, g.bsize_w, C), dtype=x.dtype, device=x.device)
+    _dev(tiles, "tiles", x.dtype)
+    assert tiles.shape == (cap, g.bsize_h, g.bsize_w, C)
+    _check(lib().sbnet_sparse_gather(_ptr(x), _dt(x), N, H, W, C, _ptr(indices), _ptr(count), cap, g, _ptr(tiles),
+                                     _stream()))
+    return tiles
+
+
+def sparse_scatter(tiles, indices, count, g, y, add=False):
+    """tiles [cap, bsize_h, bsize_w, C] -> written or added into y [N,H,W,C] in place; returns y."""
+    _dev(tiles, "tiles"), _dev(y, "y", tiles.dtype)
+    _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    N, H, W, C = y.shape
+    cap = indices.shape[0]
+    assert tiles.shape == (cap, g.bsize_h, g.bsize_w, C), (tuple(tiles.shape), (cap, g.bsize_h, g.bsize_w, C))
+    _check(lib().sbnet_sparse_scatter(_ptr(tiles), _dt(tiles), _ptr(indices), _ptr(count), cap, g, _ptr(y), N, H, W,
+                                      C, int(bool(add)), _stream()))
+    return y
+
+
+class PackedWeights:
+    """Device buffer in the library's private weight layout plus the shape it was packed for."""
+
+    def __init__(self, buf, shape, dtype):
+        self.buf, self.shape, self.dtype = buf, tuple(shape), dtype
+
+
+def pack_weights(w_hwio):
+    """w [kh,kw,Cin,Cout] device tensor -> opaque packed device buffer for the conv calls."""
+    _dev(w_hwio, "w_hwio")
+    kh, kw, Cin, Cout = w_hwio.shape
+    nbytes = _sz()
+    _check(lib().sbnet_pack_weights(None, _dt(w_hwio), kh, kw, Cin, Cout, None, nbytes, None))
+    buf = torch.empty((nbytes.value,), dtype=torch.uint8, device=w_hwio.device)
+    _check(lib().sbnet_pack_weights(_ptr(w_hwio), _dt(w_hwio), kh, kw, Cin, Cout, _ptr(buf), nbytes, _stream()))
+    return PackedWeights(buf, (kh, kw, Cin, Cout), w_hwio.dtype)
+
+
+def conv_on_tiles(tiles, count, w_packed, bias=None, stride=1, relu=False, out=None):
+    """Valid convolution on a tile stack [cap,th,tw,Cin] -> [cap,th',tw',Cout]."""
+    _dev(tiles, "tiles"), _dev(count, "count", torch.int32)
+    kh, kw, Cin, Cout = w_packed.shape
+    cap, th, tw, C = tiles.shape
+    assert C == Cin and w_packed.dtype == tiles.dtype
+    oh, ow = (th - kh) // stride + 1, (tw - kw) // stride + 1
+    if out is None:
+        out = torch.empty((cap, oh, ow, Cout), dtype=tiles.dtype, device=tiles.device)
+    _dev(out, "out", tiles.dtype)
+    if bias is not None:
+        _dev(bias, "bias", torch.float32)
+    _check(lib().sbnet_conv_on_tiles(_ptr(tiles), _dt(tiles), _ptr(count), cap, th, tw, Cin, _ptr(w_packed.buf),
+                                     _ptr(bias), kh, kw, stride, stride, Cout, int(bool(relu)), _ptr(out), _stream()))
+    return out
+
+
+def sparse_conv(x, indices, count, g_in, g_out, w_packed, bias, y, stride=1, relu=False, add=False):
+    """Fused gather -> valid conv -> scatter(-add) into y [N,H_out,W_out,Cout] in place; returns y."""
+    _dev(x, "x"), _dev(y, "y", x.dtype)
+    _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    kh, kw, Cin, Cout = w_packed.shape
+    N, H, W, C = x.shape
+    assert C == Cin and w_packed.dtype == x.dtype
+    Ny, Ho, Wo, Cy = y.shape
+    assert Ny == N and Cy == Cout
+    if bias is not None:
+        _dev(bias, "bias", torch.float32)
+    _check(lib().sbnet_sparse_conv(_ptr(x), _dt(x), N, H, W, Cin, _ptr(indices), _ptr(count), indices.shape[0],
+                                   g_in, g_out, _ptr(w_packed.buf), _ptr(bias), kh, kw, stride, stride, Cout,
+                                   int(bool(relu)), _ptr(y), Ho, Wo, int(bool(add)), _stream()))
+    return y

@@ -1,0 +1,502 @@
+// Convolution on gathered tiles and its fused form (Fig. 1 and Sec. 3.2 of arXiv 1801.02108):
+// a regular unpadded convolution runs on every active tile; in the fused entry point the
+// gather of the input tile and the scatter (or scatter-add, Sec. 3.4) of the output block
+// happen inside the same kernel, so the tile stacks never reach HBM.
+//
+// Two kernels:
+//   conv_direct  any shape, any of f32/bf16/f16: one thread per output element, fp32 FMA chain.
+//                Used for f32 (there is no fp32 MFMA worth using at these sizes) and for channel
+//                counts the MFMA path does not take.
+//   conv_mfma    bf16/f16 with Cin % 8 == 0 and Cout % 8 == 0: implicit GEMM on the matrix cores.
+//                Per workgroup: up to 256 output pixels x 64 output channels, fp32 accumulators in
+//                registers.  The input rows those pixels need are staged in LDS in channel chunks
+//                (pixel stride padded by 16 B so the 16-byte operand reads of 16 neighbouring pixels
+//                fall in distinct banks); the nine taps are nine uniform offsets into that one LDS
+//                copy, so no im2col matrix is ever materialised (the lowering the paper argues
+//                against in Sec. 2).  Weights are pre-packed into MFMA operand order and stream from
+//                L2 as one coalesced 1 KB read per fragment.
+//                The weights are the MFMA "A" operand (rows = output channels) and the pixels the
+//                "B" operand (columns = pixels), so each lane ends up with 16 consecutive output
+//                channels of one pixel and writes them as two 16-byte NHWC stores.
+#include "common.h"
+
+namespace sbnet {
+
+// ------------------------------------------------------------------------------------------
+// element helpers
+// ------------------------------------------------------------------------------------------
+template <int DT> struct Elem;
+template <> struct Elem<SBNET_F32> {
+    typedef float T;
+    static __device__ __forceinline__ float load(const T *p) { return *p; }
+    static __device__ __forceinline__ void store(T *p, float v) { *p = v; }
+};
+template <> struct Elem<SBNET_BF16> {
+    typedef uint16_t T;
+    static __device__ __forceinline__ float load(const T *p) { return bf16_bits_to_float(*p); }
+    static __device__ __forceinline__ void store(T *p, float v) { *p = (uint16_t)float_to_bf16_bits(v); }
+};
+template <> struct Elem<SBNET_F16> {
+    typedef _Float16 T;
+    static __device__ __forceinline__ float load(const T *p) { return (float)*p; }
+    static __device__ __forceinline__ void store(T *p, float v) { *p = (_Float16)v; }
+};
+
+struct ConvParams {
+    const void *in;          // tile stack [cap][th][tw][Cin]   or feature map [N][H][W][Cin]
+    void *out;               // tile stack [cap][oh][ow][Cout]  or feature map [N][Ho][Wo][Cout]
+    const void *w;           // packed weights
+    const float *bias;       // [Cout] or null
+    const int32_t *indices;  // fused form only
+    const int32_t *count;
+    int cap;
+    int th, tw, oh, ow;
+    int Cin, Cout;
+    int kh, kw, sh, sw;
+    int relu, add;
+    sbnet_geom g_in, g_out;  // fused form only
+    int H, W, Ho, Wo;        // fused form only
+    // MFMA path work decomposition
+    int CinP;                // Cin rounded up to 32
+    int CC;                  // channels per LDS chunk (multiple of 32)
+    int nchunks;
+    int mpasses;             // passes of 256 output pixels per tile
+    int ngroups;             // groups of 64 output channels
+    int lds_rows;            // input rows held in LDS per pass (upper bound)
+    FastDiv div_ow, div_tw, div_cv, div_cv_last, div_pn, div_ng;
+};
+
+// ------------------------------------------------------------------------------------------
+// direct kernel
+// ------------------------------------------------------------------------------------------
+template <int DT, bool FUSED>
+__global__ __launch_bounds__(256) void conv_direct(ConvParams p) {
+    typedef typename Elem<DT>::T T;
+    const T *in = (const T *)p.in;
+    T *out = (T *)p.out;
+    const T *w = (const T *)p.w;  // HWIO
+    const int nact = min(*p.count, p.cap);
+    const uint32_t per_tile = (uint32_t)p.oh * p.ow * p.Cout;
+    const FastDiv div_cout = p.div_cv;  // reused: divides by Cout in this kernel
+    for (int b = blockIdx.y; b < nact; b += gridDim.y) {
+        int n = 0, y0 = 0, x0 = 0, oy0 = 0, ox0 = 0;
+        if (FUSED) {
+            n = p.indices[3 * b];
+            const int by = p.indices[3 * b + 1], bx = p.indices[3 * b + 2];
+            y0 = p.g_in.boffset_h + by * p.g_in.bstride_h;
+            x0 = p.g_in.boffset_w + bx * p.g_in.bstride_w;
+            oy0 = p.g_out.boffset_h + by * p.g_out.bstride_h;
+            ox0 = p.g_out.boffset_w + bx * p.g_out.bstride_w;
+        }
+        for (uint32_t e = blockIdx.x * 256 + threadIdx.x; e < per_tile; e += gridDim.x * 256) {
+            const uint32_t pix = fdiv(e, div_cout);
+            const int o = (int)(e - pix * p.Cout);
+            const int i = (int)fdiv(pix, p.div_ow), j = (int)pix - i * p.ow;
+            float acc = p.bias ? p.bias[o] : 0.f;
+            for (int r = 0; r < p.kh; ++r)
+                for (int t = 0; t < p.kw; ++t) {
+                    const int yy = i * p.sh + r, xx = j * p.sw + t;
+                    const T *src;
+                    if (FUSED) {
+                        const int gy = y0 + yy, gx = x0 + xx;
+                        if (gy < 0 || gy >= p.H || gx < 0 || gx >= p.W) continue;  // zero padding
+                        src = in + (((size_t)n * p.H + gy) * p.W + gx) * p.Cin;
+                    } else {
+                        src = in + (((size_t)b * p.th + yy) * p.tw + xx) * p.Cin;
+                    }
+                    const T *wp = w + ((size_t)(r * p.kw + t) * p.Cin) * p.Cout + o;
+                    for (int c = 0; c < p.Cin; ++c) acc = fmaf(Elem<DT>::load(src + c), Elem<DT>::load(wp + (size_t)c * p.Cout), acc);
+                }
+            if (p.relu) acc = fmaxf(acc, 0.f);
+            if (FUSED) {
+                const int gy = oy0 + i, gx = ox0 + j;
+                if (gy < 0 || gy >= p.Ho || gx < 0 || gx >= p.Wo) continue;
+                T *dst = out + (((size_t)n * p.Ho + gy) * p.Wo + gx) * p.Cout + o;
+                if (p.add) acc += Elem<DT>::load(dst);
+                Elem<DT>::store(dst, acc);
+            } else {
+                Elem<DT>::store(out + ((size_t)b * p.oh * p.ow + pix) * p.Cout + o, acc);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// MFMA kernel
+// ------------------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+template <int DT>
+__device__ __forceinline__ f32x4 mfma16x16x32(uint4 a, uint4 b, f32x4 c) {
+    if (DT == SBNET_BF16) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    if (DT == SBNET_BF16) return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
+    union { _Float16 h[2]; uint32_t u; } v;
+    v.h[0] = (_Float16)lo;
+    v.h[1] = (_Float16)hi;
+    return v.u;
+}
+template <int DT>
+__device__ __forceinline__ float unpack_lo(uint32_t w) {
+    if (DT == SBNET_BF16) return bf16_bits_to_float(w & 0xffffu);
+    union { _Float16 h[2]; uint32_t u; } v;
+    v.u = w;
+    return (float)v.h[0];
+}
+template <int DT>
+__device__ __forceinline__ float unpack_hi(uint32_t w) {
+    if (DT == SBNET_BF16) return bf16_bits_to_float(w >> 16);
+    union { _Float16 h[2]; uint32_t u; } v;
+    v.u = w;
+    return (float)v.h[1];
+}
+
+constexpr int kMB = 4;  // 16-pixel blocks per wave
+constexpr int kNB = 4;  // 16-channel blocks per wave (64 output channels per workgroup)
+
+// Weight packing for conv_mfma.  Packed element (((ng*KS + ks)*4 + nb)*64 + lane)*8 + e holds
+// w[tap][c][o] with ks = tap*(CinP/32) + c/32, c = (ks % (CinP/32))*32 + (lane/16)*8 + e and
+// o = ng*64 + ((lane%16)/4)*16 + nb*4 + (lane%16)%4, zero where c >= Cin or o >= Cout.  The
+// permutation of o makes the four accumulator fragments of a lane cover 16 consecutive channels.
+template <typename T>
+__global__ void pack_mfma_weights(const T *__restrict__ w, T *__restrict__ packed, int taps, int Cin, int Cout,
+                                  int CinP, int ngroups) {
+    const int KS = taps * (CinP / 32);
+    const size_t total = (size_t)ngroups * KS * kNB * 64 * 8;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int e = (int)(idx & 7);
+        const int lane = (int)((idx >> 3) & 63);
+        const int nb = (int)((idx >> 9) & 3);
+        const size_t rest = idx >> 11;
+        const int ks = (int)(rest % KS), ng = (int)(rest / KS);
+        const int tap = ks / (CinP / 32);
+        const int c = (ks % (CinP / 32)) * 32 + (lane >> 4) * 8 + e;
+        const int rho = lane & 15;
+        const int o = ng * 64 + (rho >> 2) * 16 + nb * 4 + (rho & 3);
+        T v = 0;
+        if (c < Cin && o < Cout) v = w[((size_t)tap * Cin + c) * Cout + o];
+        packed[idx] = v;
+    }
+}
+
+template <typename T>
+__global__ void copy_weights(const T *__restrict__ w, T *__restrict__ packed, size_t total) {
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x)
+        packed[idx] = w[idx];
+}
+
+template <int DT, bool FUSED>
+__global__ __launch_bounds__(256) void conv_mfma(ConvParams p) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint16_t *in = (const uint16_t *)p.in;
+    uint16_t *out = (uint16_t *)p.out;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = lane >> 4, l16 = lane & 15;
+    const int nact = min(*p.count, p.cap);
+    const int M = p.oh * p.ow;
+    const int pix_stride = (p.CC + 8) * 2;  // bytes between pixels in LDS
+    const int c32_total = p.CinP / 32;
+    const int KS = p.kh * p.kw * c32_total;
+    const uint32_t per_tile = (uint32_t)p.mpasses * p.ngroups;
+    const uint32_t items = (uint32_t)nact * per_tile;
+
+    for (uint32_t item = blockIdx.x; item < items; item += gridDim.x) {
+        const uint32_t b = fdiv(item, p.div_pn);
+        const uint32_t rest = item - b * per_tile;
+        const int pass = (int)fdiv(rest, p.div_ng);
+        const int ng = (int)rest - pass * p.ngroups;
+
+        int n = 0, y0 = 0, x0 = 0, oy0 = 0, ox0 = 0;
+        if (FUSED) {
+            n = p.indices[3 * b];
+            const int by = p.indices[3 * b + 1], bx = p.indices[3 * b + 2];
+            y0 = p.g_in.boffset_h + by * p.g_in.bstride_h;
+            x0 = p.g_in.boffset_w + bx * p.g_in.bstride_w;
+            oy0 = p.g_out.boffset_h + by * p.g_out.bstride_h;
+            ox0 = p.g_out.boffset_w + bx * p.g_out.bstride_w;
+        }
+
+        // output pixels of this pass and the input rows they need
+        const int p_lo = pass * 256, p_hi = min(p_lo + 256, M);
+        const int i_lo = (int)fdiv(p_lo, p.div_ow), i_hi = (int)fdiv(p_hi - 1, p.div_ow);
+        const int r_lo = i_lo * p.sh;
+        const int nrows = (i_hi - i_lo) * p.sh + p.kh;
+
+        // per-lane LDS byte offset of each of this wave's pixel blocks (tap (0,0), channel 0)
+        int xbase[kMB];
+        int pixel[kMB];
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb) {
+            int px = p_lo + (wave * kMB + mb) * 16 + l16;
+            pixel[mb] = px;
+            px = min(px, M - 1);
+            const int i = (int)fdiv(px, p.div_ow), j = px - i * p.ow;
+            xbase[mb] = ((i * p.sh - r_lo) * p.tw + j * p.sw) * pix_stride + q * 16;
+        }
+
+        f32x4 acc[kMB][kNB];
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < kNB; ++nb) acc[mb][nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+        for (int chunk = 0; chunk < p.nchunks; ++chunk) {
+            const int c0 = chunk * p.CC;
+            const int cc = min(p.CC, p.CinP - c0);      // channels in this chunk (multiple of 32)
+            const int cv = cc >> 3;                     // 16-byte vectors per pixel
+            const FastDiv dcv = (chunk == p.nchunks - 1) ? p.div_cv_last : p.div_cv;
+            __syncthreads();                            // previous chunk / item fully consumed
+            const uint32_t nvec = (uint32_t)nrows * p.tw * cv;
+            for (uint32_t v = threadIdx.x; v < nvec; v += 256) {
+                const uint32_t px = fdiv(v, dcv);
+                const int c8 = (int)(v - px * cv);
+                const int row = (int)fdiv(px, p.div_tw), col = (int)px - row * p.tw;
+                const int c = c0 + c8 * 8;
+                uint4 val = make_uint4(0, 0, 0, 0);
+                if (c < p.Cin) {
+                    if (FUSED) {
+                        const int gy = y0 + r_lo + row, gx = x0 + col;
+                        if (gy >= 0 && gy < p.H && gx >= 0 && gx < p.W)
+                            val = *(const uint4 *)(in + (((size_t)n * p.H + gy) * p.W + gx) * p.Cin + c);
+                    } else {
+                        val = *(const uint4 *)(in + (((size_t)b * p.th + r_lo + row) * p.tw + col) * p.Cin + c);
+                    }
+                }
+                *(uint4 *)(lds + (size_t)px * pix_stride + c8 * 16) = val;
+            }
+            __syncthreads();
+
+            const int steps = cc >> 5;
+            for (int r = 0; r < p.kh; ++r)
+                for (int t = 0; t < p.kw; ++t) {
+                    const int tap_off = (r * p.tw + t) * pix_stride;
+                    const int ks0 = (r * p.kw + t) * c32_total + (c0 >> 5);
+                    const uint4 *wp = (const uint4 *)p.w + ((size_t)(ng * KS + ks0) * kNB) * 64 + lane;
+                    for (int s = 0; s < steps; ++s) {
+                        uint4 wf[kNB], xf[kMB];
+#pragma unroll
+                        for (int nb = 0; nb < kNB; ++nb) wf[nb] = wp[(size_t)(s * kNB + nb) * 64];
+#pragma unroll
+                        for (int mb = 0; mb < kMB; ++mb) xf[mb] = *(const uint4 *)(lds + xbase[mb] + tap_off + s * 64);
+#pragma unroll
+                        for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+                            for (int nb = 0; nb < kNB; ++nb) acc[mb][nb] = mfma16x16x32<DT>(wf[nb], xf[mb], acc[mb][nb]);
+                    }
+                }
+        }
+
+        // epilogue: lane holds channels ng*64 + q*16 + [0,16) of pixel (mb, l16)
+        const int o0 = ng * 64 + q * 16;
+        float bias[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) bias[k] = (p.bias && o0 + k < p.Cout) ? p.bias[o0 + k] : 0.f;
+#pragma unroll
+        for (int mb = 0; mb < kMB; ++mb) {
+            const int px = pixel[mb];
+            if (px >= p_hi) continue;
+            const int i = (int)fdiv(px, p.div_ow), j = px - i * p.ow;
+            uint16_t *dst;
+            if (FUSED) {
+                const int gy = oy0 + i, gx = ox0 + j;
+                if (gy < 0 || gy >= p.Ho || gx < 0 || gx >= p.Wo) continue;
+                dst = out + (((size_t)n * p.Ho + gy) * p.Wo + gx) * p.Cout + o0;
+            } else {
+                dst = out + ((size_t)b * M + px) * p.Cout + o0;
+            }
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                if (o0 + half * 8 >= p.Cout) continue;   // Cout % 8 == 0: a vector is all in or all out
+                float v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int kk = half * 8 + k;
+                    float a = acc[mb][kk >> 2][kk & 3] + bias[kk];
+                    v[k] = p.relu ? fmaxf(a, 0.f) : a;
+                }
+                uint4 *d4 = (uint4 *)(dst + half * 8);
+                if (FUSED && p.add) {
+                    const uint4 old = *d4;
+                    v[0] += unpack_lo<DT>(old.x); v[1] += unpack_hi<DT>(old.x);
+                    v[2] += unpack_lo<DT>(old.y); v[3] += unpack_hi<DT>(old.y);
+                    v[4] += unpack_lo<DT>(old.z); v[5] += unpack_hi<DT>(old.z);
+                    v[6] += unpack_lo<DT>(old.w); v[7] += unpack_hi<DT>(old.w);
+                }
+                *d4 = make_uint4(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]), pack2<DT>(v[4], v[5]), pack2<DT>(v[6], v[7]));
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+static bool use_mfma(sbnet_dtype dt, int Cin, int Cout) {
+    return (dt == SBNET_BF16 || dt == SBNET_F16) && Cin % 8 == 0 && Cout % 8 == 0;
+}
+
+static size_t packed_elems(sbnet_dtype dt, int kh, int kw, int Cin, int Cout) {
+    if (use_mfma(dt, Cin, Cout)) {
+        const size_t CinP = ((size_t)Cin + 31) / 32 * 32, CoutP = ((size_t)Cout + 63) / 64 * 64;
+        return (size_t)kh * kw * CinP * CoutP;
+    }
+    return (size_t)kh * kw * Cin * Cout;
+}
+
+static sbnet_status check_conv_shape(const char *who, sbnet_dtype dt, int cap, int th, int tw, int Cin, int kh,
+                                     int kw, int sh, int sw, int Cout) {
+    if (!is_float_dtype(dt)) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be f32, bf16 or f16", who);
+    if (cap < 0 || th <= 0 || tw <= 0 || Cin <= 0 || Cout <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0)
+        return fail(SBNET_EINVAL, "%s: bad sizes", who);
+    if (kh > th || kw > tw) return fail(SBNET_EINVAL, "%s: kernel larger than tile", who);
+    return SBNET_OK;
+}
+
+static const int kLdsBudget = 64 * 1024;      // preferred: two workgroups per CU
+static const int kLdsMax = 160 * 1024;        // gfx950 LDS per workgroup
+
+template <bool FUSED>
+static sbnet_status run_conv(const char *who, sbnet_dtype dt, ConvParams &p, hipStream_t s) {
+    if (p.cap == 0) return SBNET_OK;
+    p.oh = (p.th - p.kh) / p.sh + 1;
+    p.ow = (p.tw - p.kw) / p.sw + 1;
+    const long long M = (long long)p.oh * p.ow;
+    if (M * p.Cout >= (1LL << 31) || (long long)p.th * p.tw * p.Cin >= (1LL << 31))
+        return fail(SBNET_EUNSUPPORTED, "%s: tile too large", who);
+    p.div_ow = make_fastdiv(p.ow);
+    p.div_tw = make_fastdiv(p.tw);
+
+    if (!use_mfma(dt, p.Cin, p.Cout)) {
+        p.div_cv = make_fastdiv(p.Cout);
+        const long long per_tile = M * p.Cout;
+        dim3 grid((unsigned)((per_tile + 255) / 256 > 64 ? 64 : (per_tile + 255) / 256), (unsigned)(p.cap > 4096 ? 4096 : p.cap));
+#define SBNET_DIRECT(DT) hipLaunchKernelGGL((conv_direct<DT, FUSED>), grid, dim3(256), 0, s, p)
+        if (dt == SBNET_F32) SBNET_DIRECT(SBNET_F32);
+        else if (dt == SBNET_BF16) SBNET_DIRECT(SBNET_BF16);
+        else SBNET_DIRECT(SBNET_F16);
+#undef SBNET_DIRECT
+        return launch_status(who);
+    }
+
+    p.CinP = (p.Cin + 31) / 32 * 32;
+    p.mpasses = (int)((M + 255) / 256);
+    p.ngroups = (p.Cout + 63) / 64;
+    // rows of input a pass of 256 consecutive output pixels can touch
+    int out_rows = (256 + p.ow - 1) / p.ow + ((256 % p.ow) ? 1 : 0);
+    if (out_rows > p.oh) out_rows = p.oh;
+    int lds_rows = (out_rows - 1) * p.sh + p.kh;
+    if (lds_rows > p.th) lds_rows = p.th;
+    p.lds_rows = lds_rows;
+    const long long px = (long long)lds_rows * p.tw;
+    int CC = p.CinP;
+    while (CC > 32 && px * (CC + 8) * 2 > kLdsBudget) CC -= 32;
+    const long long lds_bytes = px * (CC + 8) * 2;
+    if (lds_bytes > kLdsMax) return fail(SBNET_EUNSUPPORTED, "%s: tile rows do not fit in LDS", who);
+    p.CC = CC;
+    p.nchunks = (p.CinP + CC - 1) / CC;
+    p.div_cv = make_fastdiv(CC / 8);
+    p.div_cv_last = make_fastdiv((p.CinP - (p.nchunks - 1) * CC) / 8);
+    p.div_pn = make_fastdiv((uint32_t)p.mpasses * p.ngroups);
+    p.div_ng = make_fastdiv(p.ngroups);
+    const long long items = (long long)p.cap * p.mpasses * p.ngroups;
+    if (items >= (1LL << 31)) return fail(SBNET_EUNSUPPORTED, "%s: too many work items", who);
+    const int grid = (int)(items < 8192 ? items : 8192);
+
+#define SBNET_MFMA(DT)                                                                                         \
+    do {                                                                                                       \
+        if (lds_bytes > 48 * 1024)                                                                             \
+            (void)hipFuncSetAttribute((const void *)conv_mfma<DT, FUSED>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                      (int)lds_bytes);                                                         \
+        hipLaunchKernelGGL((conv_mfma<DT, FUSED>), dim3(grid), dim3(256), (size_t)lds_bytes, s, p);            \
+    } while (0)
+    if (dt == SBNET_BF16) SBNET_MFMA(SBNET_BF16);
+    else SBNET_MFMA(SBNET_F16);
+#undef SBNET_MFMA
+    return launch_status(who);
+}
+
+}  // namespace sbnet
+
+using namespace sbnet;
+
+extern "C" sbnet_status sbnet_pack_weights(const void *w_hwio, sbnet_dtype dtype, int kh, int kw, int Cin, int Cout,
+                                           void *w_packed, size_t *bytes, void *stream) {
+    if (!is_float_dtype(dtype)) return fail(SBNET_EUNSUPPORTED, "sbnet_pack_weights: dtype must be f32, bf16 or f16");
+    if (kh <= 0 || kw <= 0 || Cin <= 0 || Cout <= 0) return fail(SBNET_EINVAL, "sbnet_pack_weights: bad sizes");
+    const size_t elems = packed_elems(dtype, kh, kw, Cin, Cout);
+    if (bytes) *bytes = elems * elem_bytes(dtype);
+    if (!w_packed) {
+        if (!bytes) return fail(SBNET_EINVAL, "sbnet_pack_weights: nothing to do");
+        return SBNET_OK;
+    }
+    if (!w_hwio) return fail(SBNET_EINVAL, "sbnet_pack_weights: null weights");
+    hipStream_t s = (hipStream_t)stream;
+    const int grid = (int)((elems + 255) / 256 < 4096 ? (elems + 255) / 256 : 4096);
+    if (use_mfma(dtype, Cin, Cout)) {
+        const int CinP = (Cin + 31) / 32 * 32, ngroups = (Cout + 63) / 64;
+        hipLaunchKernelGGL(pack_mfma_weights<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)w_hwio,
+                           (uint16_t *)w_packed, kh * kw, Cin, Cout, CinP, ngroups);
+    } else if (dtype == SBNET_F32) {
+        hipLaunchKernelGGL(copy_weights<uint32_t>, dim3(grid), dim3(256), 0, s, (const uint32_t *)w_hwio,
+                           (uint32_t *)w_packed, elems);
+    } else {
+        hipLaunchKernelGGL(copy_weights<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)w_hwio,
+                           (uint16_t *)w_packed, elems);
+    }
+    return launch_status("sbnet_pack_weights");
+}
+
+extern "C" sbnet_status sbnet_conv_on_tiles(const void *tiles_in, sbnet_dtype dtype, const int32_t *count, int cap,
+                                            int th, int tw, int Cin, const void *w_packed, const float *bias, int kh,
+                                            int kw, int sh, int sw, int Cout, int relu, void *tiles_out,
+                                            void *stream) {
+    const char *who = "sbnet_conv_on_tiles";
+    if (!tiles_in || !count || !w_packed || !tiles_out) return fail(SBNET_EINVAL, "%s: null pointer", who);
+    sbnet_status st = check_conv_shape(who, dtype, cap, th, tw, Cin, kh, kw, sh, sw, Cout);
+    if (st != SBNET_OK) return st;
+    if (((uintptr_t)tiles_in | (uintptr_t)tiles_out | (uintptr_t)w_packed) & 15)
+        return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    ConvParams p = {};
+    p.in = tiles_in; p.out = tiles_out; p.w = w_packed; p.bias = bias;
+    p.count = count; p.cap = cap;
+    p.th = th; p.tw = tw; p.Cin = Cin; p.Cout = Cout;
+    p.kh = kh; p.kw = kw; p.sh = sh; p.sw = sw; p.relu = relu ? 1 : 0;
+    return run_conv<false>(who, dtype, p, (hipStream_t)stream);
+}
+
+extern "C" sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int N, int H, int W, int Cin,
+                                          const int32_t *indices, const int32_t *count, int cap,
+                                          const sbnet_geom *g_in, const sbnet_geom *g_out, const void *w_packed,
+                                          const float *bias, int kh, int kw, int sh, int sw, int Cout, int relu,
+                                          void *y, int H_out, int W_out, int add, void *stream) {
+    const char *who = "sbnet_sparse_conv";
+    if (!x || !indices || !count || !w_packed || !y) return fail(SBNET_EINVAL, "%s: null pointer", who);
+    if (N <= 0 || H <= 0 || W <= 0 || H_out <= 0 || W_out <= 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
+    if (!geom_ok(g_in) || !geom_ok(g_out)) return fail(SBNET_EINVAL, "%s: bad geometry", who);
+    sbnet_status st = check_conv_shape(who, dtype, cap, g_in->bsize_h, g_in->bsize_w, Cin, kh, kw, sh, sw, Cout);
+    if (st != SBNET_OK) return st;
+    if ((g_in->bsize_h - kh) / sh + 1 != g_out->bsize_h || (g_in->bsize_w - kw) / sw + 1 != g_out->bsize_w)
+        return fail(SBNET_EINVAL, "%s: output block does not match the convolution of the input tile", who);
+    if (g_out->bstride_h < g_out->bsize_h || g_out->bstride_w < g_out->bsize_w)
+        return fail(SBNET_EINVAL, "%s: output blocks must not overlap", who);
+    if (x == y) return fail(SBNET_EINVAL, "%s: y must not alias x", who);
+    if (((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_packed) & 15)
+        return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    ConvParams p = {};
+    p.in = x; p.out = y; p.w = w_packed; p.bias = bias;
+    p.indices = indices; p.count = count; p.cap = cap;
+    p.th = g_in->bsize_h; p.tw = g_in->bsize_w; p.Cin = Cin; p.Cout = Cout;
+    p.kh = kh; p.kw = kw; p.sh = sh; p.sw = sw; p.relu = relu ? 1 : 0; p.add = add ? 1 : 0;
+    p.g_in = *g_in; p.g_out = *g_out;
+    p.H = H; p.W = W; p.Ho = H_out; p.Wo = W_out;
+    return run_conv<true>(who, dtype, p, (hipStream_t)stream);
+}

@@ -1,0 +1,64 @@
+// Host-only entry points: error text, block geometry (Sec. 3.1, Fig. 3 of arXiv 1801.02108)
+// and the synchronising read-back of the active-block counter.
+#include "common.h"
+
+namespace sbnet {
+
+char *error_buffer() {
+    static thread_local char buf[512] = "";
+    return buf;
+}
+
+sbnet_status fail(sbnet_status code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(error_buffer(), 512, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+}  // namespace sbnet
+
+using namespace sbnet;
+
+extern "C" const char *sbnet_last_error(void) { return error_buffer(); }
+
+extern "C" sbnet_status sbnet_geometry(int H, int W, int kh, int kw, int sh, int sw, int bo_h, int bo_w,
+                                       sbnet_geom *g_in, sbnet_geom *g_out, int *H_out, int *W_out) {
+    if (H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || bo_h <= 0 || bo_w <= 0)
+        return fail(SBNET_EINVAL, "sbnet_geometry: sizes must be positive");
+    if (!g_in || !g_out) return fail(SBNET_EINVAL, "sbnet_geometry: null geometry pointer");
+    int ph = (kh - 1) / 2, pw = (kw - 1) / 2;
+    int Ho = (H + 2 * ph - kh) / sh + 1, Wo = (W + 2 * pw - kw) / sw + 1;
+    if (Ho <= 0 || Wo <= 0) return fail(SBNET_EINVAL, "sbnet_geometry: empty output");
+    int bh = (Ho + bo_h - 1) / bo_h, bw = (Wo + bo_w - 1) / bo_w;
+    // input tile = receptive field of one output block; neighbours overlap by k - s pixels
+    g_in->bsize_h = (bo_h - 1) * sh + kh;
+    g_in->bsize_w = (bo_w - 1) * sw + kw;
+    g_in->bstride_h = bo_h * sh;
+    g_in->bstride_w = bo_w * sw;
+    g_in->boffset_h = -ph;
+    g_in->boffset_w = -pw;
+    g_in->bcount_h = bh;
+    g_in->bcount_w = bw;
+    // output blocks tile the output without overlap
+    g_out->bsize_h = g_out->bstride_h = bo_h;
+    g_out->bsize_w = g_out->bstride_w = bo_w;
+    g_out->boffset_h = g_out->boffset_w = 0;
+    g_out->bcount_h = bh;
+    g_out->bcount_w = bw;
+    if (H_out) *H_out = Ho;
+    if (W_out) *W_out = Wo;
+    return SBNET_OK;
+}
+
+extern "C" sbnet_status sbnet_read_count(const int32_t *count, int cap, int *host_count, void *stream) {
+    if (!count || !host_count) return fail(SBNET_EINVAL, "sbnet_read_count: null pointer");
+    int32_t v = 0;
+    hipError_t e = hipMemcpyAsync(&v, count, sizeof(v), hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return fail(SBNET_EHIP, "sbnet_read_count: %s", hipGetErrorString(e));
+    *host_count = v;
+    if (v > cap) return fail(SBNET_ECAP, "sbnet_read_count: %d active blocks exceed cap %d", v, cap);
+    return SBNET_OK;
+}

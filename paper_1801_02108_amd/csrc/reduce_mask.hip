@@ -1,0 +1,181 @@
+// reduce_mask: binary computation mask -> ordered list of active blocks
+// (Sec. 3.1 "Reduce mask to indices" and Sec. 3.4 "Fused downsample and indexing kernel" of
+// arXiv 1801.02108).
+//
+// The paper appends indices with a global atomic counter, which gives an arbitrary order.
+// Here the list is produced in lexicographic (n, by, bx) order without atomics:
+//   pass 1  one workgroup per block row: coalesced column pooling of the window rows into LDS,
+//           then one thread per block pools its window columns, thresholds, stores a flag byte
+//           and the row's number of active blocks;
+//   pass 2  one workgroup per block row: exclusive prefix over the row counts, then wavefront
+//           ballot + popcount compaction of the row's flags into the index list.
+#include "common.h"
+
+namespace sbnet {
+
+constexpr int kRmThreads = 256;
+
+__device__ __forceinline__ int wave_sum(int v) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+
+// sum over the workgroup, result valid in every thread
+__device__ __forceinline__ int block_sum(int v, int *lds /* >= 4 ints */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) lds[wave] = v;
+    __syncthreads();
+    return lds[0] + lds[1] + lds[2] + lds[3];
+}
+
+template <typename T, typename Acc, int POOL>
+__global__ __launch_bounds__(kRmThreads) void rm_pool_rows(const T *__restrict__ mask, int H, int W,
+                                                            sbnet_geom g, double threshold,
+                                                            int32_t *__restrict__ rowcount,
+                                                            uint8_t *__restrict__ flags) {
+    extern __shared__ __align__(8) unsigned char lds_raw[];
+    Acc *col = reinterpret_cast<Acc *>(lds_raw);
+    __shared__ int red[4];
+
+    const int row = blockIdx.x;
+    const int n = row / g.bcount_h, by = row - n * g.bcount_h;
+    const int y0 = g.boffset_h + by * g.bstride_h;
+    const int ylo = max(y0, 0), yhi = min(y0 + g.bsize_h, H);
+    const bool rows_clipped = (y0 < 0) || (y0 + g.bsize_h > H);
+
+    // pool the window rows of every image column (consecutive threads -> consecutive columns)
+    for (int x = threadIdx.x; x < W; x += kRmThreads) {
+        const T *p = mask + ((size_t)n * H + ylo) * W + x;
+        Acc a = 0;
+        bool first = true;
+        for (int y = ylo; y < yhi; ++y, p += W) {
+            Acc v = (Acc)*p;
+            if (POOL == SBNET_POOL_AVG) a += v;
+            else { a = (first || v > a) ? v : a; first = false; }
+        }
+        if (POOL == SBNET_POOL_MAX && rows_clipped) a = (first || a < (Acc)0) ? (Acc)0 : a;  // outside counts as 0
+        col[x] = a;
+    }
+    __syncthreads();
+
+    int mine = 0;
+    const double area = (double)g.bsize_h * (double)g.bsize_w;
+    for (int bx = threadIdx.x; bx < g.bcount_w; bx += kRmThreads) {
+        const int x0 = g.boffset_w + bx * g.bstride_w;
+        const int xlo = max(x0, 0), xhi = min(x0 + g.bsize_w, W);
+        const bool cols_clipped = (x0 < 0) || (x0 + g.bsize_w > W);
+        Acc a = 0;
+        bool first = true;
+        for (int x = xlo; x < xhi; ++x) {
+            Acc v = col[x];
+            if (POOL == SBNET_POOL_AVG) a += v;
+            else { a = (first || v > a) ? v : a; first = false; }
+        }
+        if (POOL == SBNET_POOL_MAX && cols_clipped) a = (first || a < (Acc)0) ? (Acc)0 : a;
+        const double pooled = POOL == SBNET_POOL_AVG ? (double)a / area : (double)a;
+        const int active = pooled > threshold ? 1 : 0;
+        flags[(size_t)row * g.bcount_w + bx] = (uint8_t)active;
+        mine += active;
+    }
+    const int total = block_sum(mine, red);
+    if (threadIdx.x == 0) rowcount[row] = total;
+}
+
+__global__ __launch_bounds__(kRmThreads) void rm_compact(const int32_t *__restrict__ rowcount,
+                                                          const uint8_t *__restrict__ flags, int rows,
+                                                          int bcount_h, int bcount_w,
+                                                          int32_t *__restrict__ indices,
+                                                          int32_t *__restrict__ count, int cap) {
+    __shared__ int red[4];
+    __shared__ int wave_cnt[4];
+    const int row = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    int part = 0;
+    for (int r = threadIdx.x; r < row; r += kRmThreads) part += rowcount[r];
+    int base = block_sum(part, red);   // active blocks in all earlier rows
+
+    const int n = row / bcount_h, by = row - n * bcount_h;
+    for (int b0 = 0; b0 < bcount_w; b0 += kRmThreads) {
+        const int bx = b0 + threadIdx.x;
+        const bool on = bx < bcount_w && flags[(size_t)row * bcount_w + bx] != 0;
+        const unsigned long long ballot = __ballot(on);
+        __syncthreads();
+        if (lane == 0) wave_cnt[wave] = __popcll(ballot);
+        __syncthreads();
+        int before = 0;
+        for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+        if (on) {
+            const int pos = base + before + __popcll(ballot & ((1ull << lane) - 1ull));
+            if (pos < cap) {
+                indices[3 * (size_t)pos + 0] = n;
+                indices[3 * (size_t)pos + 1] = by;
+                indices[3 * (size_t)pos + 2] = bx;
+            }
+        }
+        base += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    }
+    if (row == rows - 1 && threadIdx.x == 0) *count = base;
+}
+
+}  // namespace sbnet
+
+using namespace sbnet;
+
+static size_t rowcount_bytes(int rows) { return (((size_t)rows * 4) + 15) & ~(size_t)15; }
+
+extern "C" size_t sbnet_workspace_bytes(int N, const sbnet_geom *g) {
+    if (N <= 0 || !geom_ok(g)) return 0;
+    const size_t rows = (size_t)N * g->bcount_h;
+    return rowcount_bytes((int)rows) + ((rows * g->bcount_w + 15) & ~(size_t)15);
+}
+
+extern "C" sbnet_status sbnet_reduce_mask(const void *mask, sbnet_dtype mdt, int N, int H, int W,
+                                          const sbnet_geom *g, sbnet_pool pool, float threshold,
+                                          int32_t *indices, int32_t *count, int cap, void *workspace,
+                                          size_t ws_bytes, void *stream) {
+    if (!mask || !indices || !count || !workspace) return fail(SBNET_EINVAL, "sbnet_reduce_mask: null pointer");
+    if (N <= 0 || H <= 0 || W <= 0 || cap < 0) return fail(SBNET_EINVAL, "sbnet_reduce_mask: bad sizes");
+    if (!geom_ok(g)) return fail(SBNET_EINVAL, "sbnet_reduce_mask: bad geometry");
+    if (pool != SBNET_POOL_MAX && pool != SBNET_POOL_AVG) return fail(SBNET_EINVAL, "sbnet_reduce_mask: bad pool");
+    if (mdt != SBNET_U8 && mdt != SBNET_F32)
+        return fail(SBNET_EUNSUPPORTED, "sbnet_reduce_mask: mask must be u8 or f32");
+    if (ws_bytes < sbnet_workspace_bytes(N, g)) return fail(SBNET_EINVAL, "sbnet_reduce_mask: workspace too small");
+    const long long rows_ll = (long long)N * g->bcount_h;
+    if (rows_ll * g->bcount_w > 0x7fffffffLL || rows_ll > 0x7fffffffLL)
+        return fail(SBNET_EUNSUPPORTED, "sbnet_reduce_mask: more than 2^31 blocks");
+    const int rows = (int)rows_ll;
+    const size_t acc_bytes = mdt == SBNET_U8 ? 4 : 8;
+    const size_t lds = (size_t)W * acc_bytes;
+    if (lds > 128 * 1024) return fail(SBNET_EUNSUPPORTED, "sbnet_reduce_mask: W too large for the column buffer");
+
+    int32_t *rowcount = (int32_t *)workspace;
+    uint8_t *flags = (uint8_t *)workspace + rowcount_bytes(rows);
+    hipStream_t s = (hipStream_t)stream;
+    const double thr = (double)threshold;
+
+#define SBNET_RM_LAUNCH(T, ACC, P)                                                                      \
+    do {                                                                                                \
+        if (lds > 48 * 1024)                                                                            \
+            (void)hipFuncSetAttribute((const void *)rm_pool_rows<T, ACC, P>,                            \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
+        hipLaunchKernelGGL((rm_pool_rows<T, ACC, P>), dim3(rows), dim3(kRmThreads), lds, s,             \
+                           (const T *)mask, H, W, *g, thr, rowcount, flags);                            \
+    } while (0)
+
+    if (mdt == SBNET_U8) {
+        if (pool == SBNET_POOL_MAX) SBNET_RM_LAUNCH(uint8_t, int, SBNET_POOL_MAX);
+        else SBNET_RM_LAUNCH(uint8_t, int, SBNET_POOL_AVG);
+    } else {
+        if (pool == SBNET_POOL_MAX) SBNET_RM_LAUNCH(float, double, SBNET_POOL_MAX);
+        else SBNET_RM_LAUNCH(float, double, SBNET_POOL_AVG);
+    }
+#undef SBNET_RM_LAUNCH
+    sbnet_status st = launch_status("sbnet_reduce_mask(pool)");
+    if (st != SBNET_OK) return st;
+    hipLaunchKernelGGL(rm_compact, dim3(rows), dim3(kRmThreads), 0, s, rowcount, flags, rows, g->bcount_h,
+                       g->bcount_w, indices, count, cap);
+    return launch_status("sbnet_reduce_mask(compact)");
+}

@@ -1,0 +1,66 @@
+"""The C-ABI library loads and exports every symbol include/sbnet.h declares; host-only entry
+points (geometry, size queries, argument checks that return before any launch) behave as the
+header says.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle as orc
+import paper_1801_02108_amd as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sbnet.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sbnet_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 10
+    raw = ctypes.CDLL(sb.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), "missing export " + n
+    assert names == sb.exported_symbols()       # the binding wraps exactly the declared set
+
+
+@pytest.mark.parametrize("H,W,k,s,bo", [(64, 64, 3, 1, 8), (800, 704, 3, 1, 16), (400, 352, 3, 1, 16), (13, 10, 3, 1, 4),
+                                        (17, 17, 3, 2, 2), (12, 12, 1, 1, 3), (50, 88, 3, 1, 32), (9, 9, 5, 1, 3)])
+def test_geometry_host_call_matches_oracle(H, W, k, s, bo):
+    g_in, g_out, ho, wo = sb.geometry(H, W, k, s, bo)
+    og_in, og_out, oho, owo = orc.geometry(H, W, k, s, bo)
+    assert g_in.astuple() == og_in.astuple() and g_out.astuple() == og_out.astuple() and (ho, wo) == (oho, owo)
+
+
+def test_geometry_rejects_bad_sizes():
+    with pytest.raises(sb.SbnetError) as e:
+        sb.geometry(0, 4, 3, 1, 2)
+    assert e.value.code == sb.EINVAL and "positive" in str(e.value)
+
+
+def test_size_queries():
+    g_in, _, _, _ = sb.geometry(800, 704, 3, 1, 16)
+    ws = sb.workspace_bytes(8, g_in)
+    assert ws >= 8 * 50 * 44 + 4 * 8 * 50 and ws % 16 == 0
+    nbytes = ctypes.c_size_t()
+    lib = sb.lib()
+    assert lib.sbnet_pack_weights(None, sb.BF16, 3, 3, 64, 64, None, nbytes, None) == sb.OK
+    assert nbytes.value == 3 * 3 * 64 * 64 * 2
+    assert lib.sbnet_pack_weights(None, sb.BF16, 3, 3, 24, 40, None, nbytes, None) == sb.OK
+    assert nbytes.value == 3 * 3 * 32 * 64 * 2          # channels padded to the MFMA tile
+    assert lib.sbnet_pack_weights(None, sb.F32, 3, 3, 16, 16, None, nbytes, None) == sb.OK
+    assert nbytes.value == 3 * 3 * 16 * 16 * 4
+
+
+def test_null_pointers_are_rejected_before_any_launch():
+    lib = sb.lib()
+    g_in, g_out, _, _ = sb.geometry(16, 16, 3, 1, 4)
+    assert lib.sbnet_reduce_mask(None, sb.U8, 1, 16, 16, g_in, 1, 0.0, None, None, 16, None, 0, None) == sb.EINVAL
+    assert b"null" in lib.sbnet_last_error()
+    assert lib.sbnet_sparse_gather(None, sb.BF16, 1, 16, 16, 8, None, None, 4, g_in, None, None) == sb.EINVAL
+    assert lib.sbnet_sparse_scatter(None, sb.BF16, None, None, 4, g_out, None, 1, 16, 16, 8, 0, None) == sb.EINVAL
+    assert lib.sbnet_conv_on_tiles(None, sb.BF16, None, 4, 6, 6, 8, None, None, 3, 3, 1, 1, 8, 0, None, None) == sb.EINVAL

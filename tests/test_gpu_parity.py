@@ -1,0 +1,312 @@
+"""GPU parity: every entry point of libsbnet_hip.so, called through the C ABI, against the
+fp64 CPU oracle on the same seeded inputs.  Indices, gather and scatter must match bit for
+bit; convolution outputs within the stated relative tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_1801_02108_amd as sb
+from paper_1801_02108_amd import inputs as gen
+from util import CONV_TOL, TORCH_DT, assert_close, round_like, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def step(msg):
+    print("[case] " + msg, flush=True)
+
+
+def ogeom(g):
+    """binding geometry -> oracle geometry (same eight integers, separately defined structs)."""
+    return orc.Geom(*g.astuple())
+
+
+def dev_indices(idx_np, cap=None):
+    cap = max(len(idx_np), 1) if cap is None else cap
+    buf = np.zeros((cap, 3), dtype=np.int32)
+    buf[:len(idx_np)] = idx_np
+    return torch.from_numpy(buf).cuda(), torch.tensor([len(idx_np)], dtype=torch.int32).cuda()
+
+
+# --------------------------------------------------------------------------- geometry
+@pytest.mark.parametrize("H,W,k,s,bo", [(64, 64, 3, 1, 8), (800, 704, 3, 1, 16), (13, 10, 3, 1, 4), (17, 17, 3, 2, 2),
+                                        (12, 12, 1, 1, 3), (50, 88, 3, 1, 32)])
+def test_geometry_matches_oracle(H, W, k, s, bo):
+    g_in, g_out, ho, wo = sb.geometry(H, W, k, s, bo)
+    og_in, og_out, oho, owo = orc.geometry(H, W, k, s, bo)
+    assert g_in.astuple() == og_in.astuple() and g_out.astuple() == og_out.astuple() and (ho, wo) == (oho, owo)
+
+
+# --------------------------------------------------------------------------- reduce_mask
+def _reduce_case(mask_np, g, pool, thr, mdt):
+    m = torch.from_numpy(mask_np.astype(np.uint8 if mdt == "u8" else np.float32)).cuda()
+    idx, cnt = sb.reduce_mask(m, g, pool, thr)
+    n = sb.read_count(cnt, idx.shape[0])
+    want = orc.reduce_mask(mask_np, ogeom(g), pool, float(np.float32(thr)))
+    assert n == len(want), (n, len(want))
+    assert np.array_equal(idx[:n].cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("H,W,bo,N", [(64, 64, 8, 1), (48, 80, 16, 3), (37, 29, 4, 2), (100, 176, 32, 2), (33, 1000, 8, 1)])
+@pytest.mark.parametrize("mdt", ["u8", "f32"])
+def test_reduce_mask_binary(H, W, bo, N, mdt):
+    step("reduce_mask binary H=%d W=%d bo=%d N=%d %s" % (H, W, bo, N, mdt))
+    r = gen.rng_for(1, H * W + bo)
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    for dens in (0.0, 0.002, 0.05, 1.0):
+        mask = (r.random((N, H, W)) < dens).astype(np.float32)
+        for g in (g_in, g_out):
+            for pool in (sb.POOL_MAX, sb.POOL_AVG):
+                _reduce_case(mask, g, pool, 0.0, mdt)
+        _reduce_case(mask, g_in, sb.POOL_AVG, 0.01, mdt)
+
+
+def test_reduce_mask_real_valued_max_and_avg():
+    step("reduce_mask real-valued")
+    r = gen.rng_for(1, 77)
+    H, W, bo = 60, 44, 4
+    g_in, _, _, _ = sb.geometry(H, W, 3, 1, bo)
+    mask = (r.random((2, H, W)) * (r.random((2, H, W)) < 0.1)).astype(np.float32)
+    for thr in (0.0, 0.25, 0.9):
+        _reduce_case(mask, g_in, sb.POOL_MAX, thr, "f32")
+    # average pooling on real values: summation order may flip a block sitting on the threshold,
+    # so blocks whose pooled value is within 1e-6 of it are left out of the comparison
+    for thr in (0.01, 0.03):
+        m = torch.from_numpy(mask).cuda()
+        idx, cnt = sb.reduce_mask(m, g_in, sb.POOL_AVG, thr)
+        n = sb.read_count(cnt, idx.shape[0])
+        got = {tuple(x) for x in idx[:n].cpu().numpy()}
+        og = ogeom(g_in)
+        t32 = float(np.float32(thr))
+        sure_on = {tuple(x) for x in orc.reduce_mask(mask, og, orc.POOL_AVG, t32 + 1e-6)}
+        maybe_on = {tuple(x) for x in orc.reduce_mask(mask, og, orc.POOL_AVG, t32 - 1e-6)}
+        assert sure_on <= got <= maybe_on
+        assert list(map(tuple, idx[:n].cpu().numpy())) == sorted(got)
+
+
+def test_reduce_mask_negative_values_max_pool_counts_outside_as_zero():
+    step("reduce_mask negative values")
+    H, W, bo = 16, 16, 4
+    g_in, _, _, _ = sb.geometry(H, W, 3, 1, bo)
+    mask = -np.ones((1, H, W), dtype=np.float32)
+    _reduce_case(mask, g_in, sb.POOL_MAX, -0.5, "f32")     # only border windows see a 0 > -0.5
+
+
+def test_reduce_mask_cap_smaller_than_count():
+    step("reduce_mask cap")
+    H, W, bo = 64, 64, 8
+    g_in, _, _, _ = sb.geometry(H, W, 3, 1, bo)
+    mask = np.ones((1, H, W), dtype=np.uint8)
+    idx = torch.full((10, 3), -7, dtype=torch.int32).cuda()
+    _, cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in, indices=idx)
+    with pytest.raises(sb.SbnetError) as e:
+        sb.read_count(cnt, 10)
+    assert e.value.code == sb.ECAP
+    assert int(cnt.item()) == 64
+    assert np.array_equal(idx.cpu().numpy(), orc.reduce_mask(mask, ogeom(g_in))[:10])
+
+
+def test_reduce_mask_repeatable_and_overwrites_count():
+    step("reduce_mask repeat")
+    r = gen.rng_for(1, 5)
+    H, W, bo = 96, 128, 8
+    g_in, _, _, _ = sb.geometry(H, W, 3, 1, bo)
+    m = torch.from_numpy((r.random((2, H, W)) < 0.01).astype(np.uint8)).cuda()
+    idx0, cnt0 = sb.reduce_mask(m, g_in)
+    ref_i, ref_c = idx0.clone(), cnt0.clone()
+    for _ in range(20):
+        idx, cnt = sb.reduce_mask(m, g_in, indices=idx0, count=cnt0)
+        assert torch.equal(cnt, ref_c) and torch.equal(idx[:int(ref_c)], ref_i[:int(ref_c)])
+
+
+# --------------------------------------------------------------------------- gather / scatter
+GS_CASES = [
+    # H, W, C, k, s, bo, N, dtype
+    (64, 64, 16, 3, 1, 8, 1, "f32"),
+    (48, 80, 64, 3, 1, 16, 2, "bf16"),
+    (37, 29, 3, 3, 1, 4, 2, "bf16"),       # odd channel count: 2-byte vectors, ragged blocks
+    (37, 29, 5, 3, 1, 4, 1, "f32"),
+    (40, 40, 12, 5, 1, 8, 1, "f16"),       # 8-byte vectors, halo 2
+    (33, 47, 256, 3, 1, 16, 1, "bf16"),
+    (35, 35, 8, 3, 2, 4, 2, "f16"),        # strided geometry
+    (24, 24, 6, 1, 1, 3, 1, "bf16"),       # 1x1: no halo
+]
+
+
+@pytest.mark.parametrize("H,W,C,k,s,bo,N,dtype", GS_CASES)
+def test_gather_bit_exact(H, W, C, k, s, bo, N, dtype):
+    step("gather %s" % ((H, W, C, k, s, bo, N, dtype),))
+    r = gen.rng_for(2, H * 1000 + W + C)
+    g_in, g_out, _, _ = sb.geometry(H, W, k, s, bo)
+    x = gen.activations(r, (N, H, W, C), dtype)
+    for dens in (0.004, 1.0):
+        mask = (r.random((N, H, W)) < dens).astype(np.float32)
+        idx = orc.reduce_mask(mask, ogeom(g_in))
+        cap = len(idx) + 3
+        d_idx, d_cnt = dev_indices(idx, cap)
+        tiles = torch.full((cap, g_in.bsize_h, g_in.bsize_w, C), 9.0, dtype=TORCH_DT[dtype]).cuda()
+        sb.sparse_gather(to_dev(x, dtype), d_idx, d_cnt, g_in, tiles)
+        got = to_host(tiles)
+        assert np.array_equal(got[:len(idx)], orc.gather(x, idx, ogeom(g_in)))
+        assert (got[len(idx):] == 9.0).all()          # rows beyond the count are not written
+
+
+@pytest.mark.parametrize("H,W,C,k,s,bo,N,dtype", GS_CASES)
+@pytest.mark.parametrize("add", [False, True])
+def test_scatter_bit_exact(H, W, C, k, s, bo, N, dtype, add):
+    step("scatter add=%s %s" % (add, (H, W, C, k, s, bo, N, dtype)))
+    r = gen.rng_for(3, H * 1000 + W + C)
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, k, s, bo)
+    y0 = gen.activations(r, (N, Ho, Wo, C), dtype)
+    for dens in (0.0, 0.004, 1.0):
+        mask = (r.random((N, H, W)) < dens).astype(np.float32)
+        idx = orc.reduce_mask(mask, ogeom(g_in))
+        cap = len(idx) + 2
+        d_idx, d_cnt = dev_indices(idx, cap)
+        t = gen.activations(r, (cap, bo, bo, C), dtype)
+        y = to_dev(y0, dtype)
+        sb.sparse_scatter(to_dev(t, dtype), d_idx, d_cnt, g_out, y, add=add)
+        want = round_like(orc.scatter(t[:len(idx)], idx, ogeom(g_out), y0, add=add), dtype)
+        assert np.array_equal(to_host(y), want)
+
+
+def test_gather_scatter_round_trip_all_blocks():
+    step("gather/scatter round trip")
+    r = gen.rng_for(3, 1)
+    H, W, C, bo = 48, 32, 32, 8
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    x = to_dev(gen.activations(r, (2, H, W, C), "bf16"), "bf16")
+    idx, cnt = sb.reduce_mask(torch.ones((2, H, W), dtype=torch.uint8).cuda(), g_in)
+    tiles = sb.sparse_gather(x, idx, cnt, g_in)
+    y = torch.zeros_like(x)
+    sb.sparse_scatter(tiles[:, 1:-1, 1:-1].contiguous(), idx, cnt, g_out, y)
+    assert torch.equal(x, y)
+
+
+# --------------------------------------------------------------------------- convolution on tiles
+CONV_CASES = [
+    # B, th, tw, Cin, Cout, k, s, dtype, relu, bias
+    (7, 10, 10, 16, 16, 3, 1, "f32", False, False),     # the small fp32 configuration
+    (5, 18, 18, 64, 64, 3, 1, "bf16", False, True),     # headline tile shape
+    (3, 18, 18, 64, 64, 3, 1, "f16", True, True),
+    (3, 18, 18, 256, 64, 1, 1, "bf16", True, True),     # bottleneck conv1 shape: channel chunks in LDS
+    (3, 16, 16, 64, 256, 1, 1, "bf16", False, True),    # bottleneck conv3 shape: four channel groups
+    (2, 34, 34, 32, 64, 3, 1, "bf16", True, False),     # several 256-pixel passes per tile
+    (4, 10, 10, 24, 40, 3, 1, "bf16", False, True),     # channel counts padded inside the MFMA path
+    (4, 11, 9, 8, 8, 3, 2, "f16", True, True),          # strided, ragged pixel blocks
+    (3, 7, 7, 5, 3, 3, 1, "bf16", False, True),         # odd channels: direct kernel in bf16
+    (3, 9, 9, 4, 6, 5, 2, "f32", True, True),
+    (2, 6, 12, 96, 96, 1, 1, "bf16", False, False),
+]
+
+
+@pytest.mark.parametrize("B,th,tw,Cin,Cout,k,s,dtype,relu,bias", CONV_CASES)
+def test_conv_on_tiles(B, th, tw, Cin, Cout, k, s, dtype, relu, bias):
+    step("conv_on_tiles %s" % ((B, th, tw, Cin, Cout, k, s, dtype, relu, bias),))
+    r = gen.rng_for(4, th * 100 + Cin + Cout)
+    t = gen.activations(r, (B + 1, th, tw, Cin), dtype)
+    w = gen.conv_weights(r, k, k, Cin, Cout, dtype, unit_variance=(dtype == "f32"))
+    b = gen.bias_vector(r, Cout, 0.5) if bias else None
+    wp = sb.pack_weights(to_dev(w, dtype))
+    cnt = torch.tensor([B], dtype=torch.int32).cuda()
+    oh, ow = (th - k) // s + 1, (tw - k) // s + 1
+    out = torch.full((B + 1, oh, ow, Cout), 5.0, dtype=TORCH_DT[dtype]).cuda()
+    sb.conv_on_tiles(to_dev(t, dtype), cnt, wp, None if b is None else torch.from_numpy(b).cuda(), stride=s, relu=relu,
+                     out=out)
+    ref = orc.conv_valid(t[:B], w, b, stride=s, relu=relu)
+    got = to_host(out)
+    assert_close(got[:B], ref, CONV_TOL[dtype], "conv_on_tiles")
+    assert (got[B] == 5.0).all()
+
+
+# --------------------------------------------------------------------------- fused sparse conv
+SPARSE_CASES = [
+    # N, H, W, Cin, Cout, k, s, bo, dtype
+    (1, 64, 64, 16, 16, 3, 1, 8, "f32"),
+    (2, 48, 80, 64, 64, 3, 1, 16, "bf16"),
+    (1, 37, 29, 32, 16, 3, 1, 4, "bf16"),      # ragged: blocks hang over the image edge
+    (1, 40, 40, 64, 64, 3, 1, 32, "f16"),
+    (2, 35, 35, 8, 8, 3, 2, 4, "bf16"),        # strided convolution
+    (1, 24, 24, 6, 5, 3, 1, 8, "f32"),
+    (1, 32, 32, 64, 256, 1, 1, 16, "bf16"),
+]
+
+
+@pytest.mark.parametrize("N,H,W,Cin,Cout,k,s,bo,dtype", SPARSE_CASES)
+@pytest.mark.parametrize("add", [False, True])
+def test_sparse_conv_fused_and_unfused(N, H, W, Cin, Cout, k, s, bo, dtype, add):
+    step("sparse_conv add=%s %s" % (add, (N, H, W, Cin, Cout, k, s, bo, dtype)))
+    r = gen.rng_for(5, H * 100 + Cin + bo)
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, k, s, bo)
+    x = gen.activations(r, (N, H, W, Cin), dtype)
+    w = gen.conv_weights(r, k, k, Cin, Cout, dtype, unit_variance=(dtype == "f32"))
+    b = gen.bias_vector(r, Cout, 0.5)
+    y0 = gen.activations(r, (N, Ho, Wo, Cout), dtype)
+    wp = sb.pack_weights(to_dev(w, dtype))
+    d_b = torch.from_numpy(b).cuda()
+    for dens in (0.0, 0.003, 1.0):
+        mask = (r.random((N, H, W)) < dens).astype(np.uint8)
+        d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in)
+        idx = orc.reduce_mask(mask, ogeom(g_in))
+        ref = orc.sparse_conv_dense(x, idx, ogeom(g_out), w, b, y0, stride=s, relu=True, add=add)
+        bm = orc.block_mask(idx, ogeom(g_out), N, Ho, Wo)
+        # fused kernel
+        y = to_dev(y0, dtype)
+        sb.sparse_conv(to_dev(x, dtype), d_idx, d_cnt, g_in, g_out, wp, d_b, y, stride=s, relu=True, add=add)
+        got = to_host(y)
+        assert_close(got, ref, CONV_TOL[dtype], "fused")
+        assert np.array_equal(got[~bm], y0[~bm])                  # inactive pixels bit-identical
+        # four separate calls
+        y = to_dev(y0, dtype)
+        tiles = sb.sparse_gather(to_dev(x, dtype), d_idx, d_cnt, g_in)
+        out = sb.conv_on_tiles(tiles, d_cnt, wp, d_b, stride=s, relu=True)
+        sb.sparse_scatter(out, d_idx, d_cnt, g_out, y, add=add)
+        got = to_host(y)
+        assert_close(got, ref, CONV_TOL[dtype], "unfused")
+        assert np.array_equal(got[~bm], y0[~bm])
+
+
+def test_config1_end_to_end():
+    """Small fp32 configuration: 64x64x16 -> 16, three-rectangle mask (~10 % ones), 8x8 blocks,
+    average pooling with threshold 0, plain scatter into a zeroed output."""
+    step("config 1 end to end")
+    r = gen.rng_for(1)
+    H = W = 64
+    C = 16
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, 1, 8)
+    mask = gen.rect_mask(r, H, W, 3, 0.10)
+    x = gen.activations(r, (1, H, W, C), "f32")
+    w = gen.conv_weights(r, 3, 3, C, C, "f32", unit_variance=True)
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in, sb.POOL_AVG, 0.0)
+    idx = orc.reduce_mask(mask, ogeom(g_in), orc.POOL_AVG, 0.0)
+    n = sb.read_count(d_cnt, d_idx.shape[0])
+    assert 0 < n < 64 and np.array_equal(d_idx[:n].cpu().numpy(), idx)
+    y = torch.zeros((1, Ho, Wo, C), dtype=torch.float32).cuda()
+    sb.sparse_conv(to_dev(x, "f32"), d_idx, d_cnt, g_in, g_out, sb.pack_weights(to_dev(w, "f32")), None, y)
+    ref = orc.sparse_conv_tiled(x, idx, ogeom(g_in), ogeom(g_out), w, None, np.zeros((1, Ho, Wo, C)))
+    assert_close(to_host(y), ref, CONV_TOL["f32"], "config 1")
+    np.testing.assert_allclose(ref, orc.sparse_conv_dense(x, idx, ogeom(g_out), w, None, np.zeros((1, Ho, Wo, C))),
+                               atol=1e-10)
+
+
+# --------------------------------------------------------------------------- error paths (host-side checks)
+def test_bad_arguments_are_reported_not_launched():
+    step("error paths")
+    g_in, g_out, _, _ = sb.geometry(16, 16, 3, 1, 4)
+    x = torch.zeros((1, 16, 16, 8), dtype=torch.bfloat16).cuda()
+    idx, cnt = dev_indices(np.zeros((0, 3), np.int32), 4)
+    with pytest.raises(sb.SbnetError) as e:          # overlapping blocks cannot be scattered
+        sb.sparse_scatter(torch.zeros((4, 6, 6, 8), dtype=torch.bfloat16).cuda(), idx, cnt, g_in, x)
+    assert e.value.code == sb.EINVAL
+    with pytest.raises(sb.SbnetError) as e:          # integer feature maps are not supported
+        sb.sparse_gather(torch.zeros((1, 16, 16, 8), dtype=torch.uint8).cuda(), idx, cnt, g_in,
+                         torch.zeros((4, 6, 6, 8), dtype=torch.uint8).cuda())
+    assert e.value.code == sb.EUNSUPPORTED
+    with pytest.raises(sb.SbnetError) as e:          # bf16 masks are not supported
+        sb.reduce_mask(torch.zeros((1, 16, 16), dtype=torch.bfloat16).cuda(), g_in)
+    assert e.value.code == sb.EUNSUPPORTED
+    wp = sb.pack_weights(torch.zeros((3, 3, 8, 8), dtype=torch.bfloat16).cuda())
+    with pytest.raises(sb.SbnetError) as e:          # in-place fused convolution would race
+        sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, None, x)
+    assert e.value.code == sb.EINVAL
