@@ -1,0 +1,299 @@
+#!/usr/bin/env python3
+"""Benchmark of the tiled sparse convolution hot path on one MI355X.
+
+Workload (headline): one sparse 3x3 convolution, stride 1, SAME padding, bf16 NHWC with fp32
+accumulation, N=1, H=800, W=704, 64 -> 64 channels, 16x16 output blocks with a one-pixel halo,
+synthetic road-band mask calibrated to 10 % active blocks.  One step = the whole path on inputs
+already resident in HBM: reduce_mask (mask -> index list, count stays on the device) followed by
+the fused gather -> MFMA convolution -> scatter kernel.  Steps are replayed from one HIP graph
+so that host launch overhead does not hide the GPU time; the eager (Python-driven) figure is
+reported next to it.
+
+Prints ONE JSON line.  Extra keys: per-kernel times, the four-call (unfused) path, the same
+path with every block active (the build's own dense baseline), MIOpen's dense convolution, the
+density sweep 5/10/20/40 %, the roofline of the dominant kernel and the CPU oracle's time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+H, W, C, K, BO, KS = 800, 704, 64, 64, 16, 3
+TILE_FLOPS = 2 * BO * BO * KS * KS * C * K                       # 18 874 368 per active tile
+TILE_BYTES = ((BO + 2) ** 2 * C + BO * BO * K) * 2               # read tile + write block, bf16
+PEAK_BF16_TFLOPS = 2500.0                                        # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--density", type=float, default=0.10, help="target active-block fraction of the headline run")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip sweep, dense and MIOpen comparisons")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); the path shards by blocks or samples "
+                 "without collectives, see DESIGN.md")
+    import numpy as np
+    import torch
+    import paper_1801_02108_amd as sb
+    from paper_1801_02108_amd import inputs as gen
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    sb.lib()                                                      # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    # ------------------------------------------------------------------ inputs (seeded, synthetic)
+    r = gen.rng_for(2)
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, KS, 1, BO)
+    total_blocks = g_in.bcount_h * g_in.bcount_w
+    x_np = gen.activations(r, (1, H, W, C), "bf16")
+    w_np = gen.conv_weights(r, KS, KS, C, K, "bf16")
+    b_np = gen.bias_vector(r, K)
+    x = torch.from_numpy(x_np).to(torch.bfloat16).to(dev)
+    wp = sb.pack_weights(torch.from_numpy(w_np).to(torch.bfloat16).to(dev))
+    bias = torch.from_numpy(b_np).to(dev)
+    y = torch.zeros((1, Ho, Wo, K), dtype=torch.bfloat16, device=dev)
+    fields = gen.road_band_fields(r, H, W, 3)
+
+    idx = torch.empty((total_blocks, 3), dtype=torch.int32, device=dev)
+    cnt = torch.empty((1,), dtype=torch.int32, device=dev)
+    ws = torch.empty((sb.workspace_bytes(1, g_in),), dtype=torch.uint8, device=dev)
+
+    def count_active(mask_np):
+        sb.reduce_mask(torch.from_numpy(mask_np).to(dev), g_in, sb.POOL_AVG, 0.0, idx, cnt, ws)
+        return sb.read_count(cnt, total_blocks)
+
+    def mask_for(target):
+        if target >= 1.0:
+            m = np.ones((1, H, W), dtype=np.uint8)
+            return m, 1.0
+        m, _, frac = gen.calibrate(lambda s: gen.road_band_mask(fields, s), count_active, total_blocks, target, 0.0, 12.0)
+        return m, frac
+
+    def step_fused(mask_d):
+        sb.reduce_mask(mask_d, g_in, sb.POOL_AVG, 0.0, idx, cnt, ws)
+        sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y)
+
+    tiles_buf = [None, None]
+
+    def step_unfused(mask_d):
+        sb.reduce_mask(mask_d, g_in, sb.POOL_AVG, 0.0, idx, cnt, ws)
+        sb.sparse_gather(x, idx, cnt, g_in, tiles_buf[0])
+        sb.conv_on_tiles(tiles_buf[0], cnt, wp, bias, out=tiles_buf[1])
+        sb.sparse_scatter(tiles_buf[1], idx, cnt, g_out, y)
+
+    def graph_of(fn, reps=1):
+        """HIP graph holding `reps` back-to-back calls of fn() (captured on a side stream)."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()                                                   # warm-up outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(reps):
+                fn()
+        return g
+
+    def time_kernel(fn, reps=20, replays=10):
+        """Average device milliseconds of one call of fn(): HIP events on the launch stream around
+        `replays` replays of a graph of `reps` calls, so host launch cost is not in the figure."""
+        g = graph_of(fn, reps)
+        g.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(replays):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * replays)
+
+    def time_events(fn, iters, warm=5):
+        """average milliseconds per eager call of fn() (HIP events; includes host launch cost)"""
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    def time_steps(fn, steps, warmup):
+        """wall-clock ms per call over exactly `steps` calls bracketed by device synchronisation"""
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def time_step_graph(fn, steps, warmup):
+        """ms per step with `steps` steps replayed from graphs of `inner` steps each"""
+        inner = 10 if steps % 10 == 0 and warmup % 10 == 0 else 1
+        g = graph_of(fn, inner)
+        return time_steps(g.replay, steps // inner, max(warmup // inner, 1)) / inner, inner
+
+    # ------------------------------------------------------------------ headline: 10 % active blocks
+    mask_np, frac = mask_for(args.density)
+    mask_d = torch.from_numpy(mask_np).to(dev)
+    nact = count_active(mask_np)
+    pix_density = float(mask_np.mean())
+
+    eager_ms = time_steps(lambda: step_fused(mask_d), args.steps, args.warmup)
+    graph_ok, inner = True, 1
+    try:
+        ms_per_step, inner = time_step_graph(lambda: step_fused(mask_d), args.steps, args.warmup)
+        single_graph_ms = time_steps(graph_of(lambda: step_fused(mask_d), 1).replay, 100, 10)
+    except Exception as e:                                         # pragma: no cover
+        graph_ok = False
+        sys.stderr.write("graph capture failed (%s); reporting eager timing\n" % e)
+        ms_per_step = single_graph_ms = eager_ms
+
+    # per-kernel device time: graphs of 20 back-to-back launches of one entry point, HIP events
+    tk = time_kernel if graph_ok else (lambda fn: time_events(fn, 200))
+    conv_ms = tk(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y))
+    reduce_ms = tk(lambda: sb.reduce_mask(mask_d, g_in, sb.POOL_AVG, 0.0, idx, cnt, ws))
+    count_active(mask_np)                                          # leave idx/cnt consistent
+
+    flops = TILE_FLOPS * nact
+    achieved_tflops = flops / (conv_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("conv16_kernel_fused/cfg2_10pct")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "sparse_conv_ms_at_10pct_active_blocks",
+        "value": round(ms_per_step, 6),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "cfg2: sparse 3x3 conv bf16 NHWC, N=1 H=800 W=704 C=64->64, block 16x16 + halo 1, "
+                               "road-band mask", "target_active_block_fraction": args.density,
+                   "active_blocks": nact, "total_blocks": total_blocks, "active_block_fraction": round(frac, 4),
+                   "mask_pixel_density": round(pix_density, 4), "step": "reduce_mask + fused gather/conv/scatter",
+                   "timing": ("%d steps per HIP graph replay, wall clock between device syncs" % inner) if graph_ok
+                   else "eager launches, wall clock between device syncs"},
+        "ms_per_step_eager": round(eager_ms, 6),
+        "ms_per_step_one_graph_per_step": round(single_graph_ms, 6),
+        "kernel_ms": {"reduce_mask(2 kernels)": round(reduce_ms, 6), "sparse_conv(fused mfma)": round(conv_ms, 6)},
+        "effective_tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 3),
+        "roofline": {"bound": "mfma", "kernel": "conv16_kernel<bf16,64,fused>", "achieved": round(achieved_tflops, 3),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 5),
+                     "traffic": traffic,
+                     "hbm_GBps_algorithmic": round(TILE_BYTES * nact / (conv_ms * 1e-3) / 1e9, 2)},
+    }
+
+    # ------------------------------------------------------------------ extras
+    if not args.no_extras:
+        sweep = []
+        dense_ms = None
+        for target in (0.05, 0.10, 0.20, 0.40, 1.0):
+            m_np, fr = mask_for(target)
+            m_d = torch.from_numpy(m_np).to(dev)
+            n = count_active(m_np)
+            t_step = time_step_graph(lambda: step_fused(m_d), 100, 10)[0] if graph_ok else \
+                time_steps(lambda: step_fused(m_d), 100, 10)
+            t_conv = tk(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y))
+            tiles_buf[0] = torch.empty((n, BO + 2, BO + 2, C), dtype=torch.bfloat16, device=dev)
+            tiles_buf[1] = torch.empty((n, BO, BO, K), dtype=torch.bfloat16, device=dev)
+            idx_small = idx[:n]
+            t_gather = tk(lambda: sb.sparse_gather(x, idx_small, cnt, g_in, tiles_buf[0]))
+            t_tconv = tk(lambda: sb.conv_on_tiles(tiles_buf[0], cnt, wp, bias, out=tiles_buf[1]))
+            t_scatter = tk(lambda: sb.sparse_scatter(tiles_buf[1], idx_small, cnt, g_out, y))
+            tile_in_b = (BO + 2) ** 2 * C * 2
+            tile_out_b = BO * BO * K * 2
+            row = {"target": target, "active_blocks": n, "step_ms": round(t_step, 5), "fused_conv_ms": round(t_conv, 5),
+                   "fused_conv_tflops": round(TILE_FLOPS * n / t_conv / 1e9, 2),
+                   "gather_ms": round(t_gather, 5), "gather_GBps": round(2 * tile_in_b * n / t_gather / 1e6, 1),
+                   "conv_on_tiles_ms": round(t_tconv, 5), "conv_on_tiles_tflops": round(TILE_FLOPS * n / t_tconv / 1e9, 2),
+                   "scatter_ms": round(t_scatter, 5), "scatter_GBps": round(2 * tile_out_b * n / t_scatter / 1e6, 1),
+                   "unfused_sum_ms": round(t_gather + t_tconv + t_scatter, 5)}
+            if target >= 1.0:
+                dense_ms = t_step
+            sweep.append(row)
+            tiles_buf[0] = tiles_buf[1] = None
+        for row in sweep:
+            row["speedup_vs_own_dense"] = round(dense_ms / row["step_ms"], 3)
+            row["ideal_speedup"] = round(total_blocks / max(row["active_blocks"], 1), 3)
+        out["sweep"] = sweep
+        out["own_dense_ms"] = round(dense_ms, 5)
+        out["speedup_vs_own_dense"] = round(dense_ms / ms_per_step, 3)
+        # MIOpen dense convolution through torch (channels-last bf16), an external baseline only
+        try:
+            xt = x.permute(0, 3, 1, 2)                              # NCHW view of NHWC memory = channels_last
+            wt = torch.from_numpy(w_np).to(torch.bfloat16).to(dev).permute(3, 2, 0, 1).contiguous(
+                memory_format=torch.channels_last)
+            fn = lambda: torch.nn.functional.conv2d(xt, wt, bias.to(torch.bfloat16), padding=1)
+            miopen_ms = time_events(fn, 30, warm=5)
+            out["miopen_dense_ms"] = round(miopen_ms, 5)
+            out["speedup_vs_miopen_dense"] = round(miopen_ms / ms_per_step, 3)
+        except Exception as e:                                     # pragma: no cover
+            out["miopen_dense_ms"] = None
+            sys.stderr.write("MIOpen dense baseline failed: %s\n" % e)
+        count_active(mask_np)
+
+    # ------------------------------------------------------------------ CPU oracle on the same workload
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        og_in, og_out = orc.Geom(*g_in.astuple()), orc.Geom(*g_out.astuple())
+        x64 = x_np.astype(np.float64)
+        w64 = w_np.astype(np.float64)
+        b64 = b_np.astype(np.float64)
+        m64 = mask_np.astype(np.float64)
+        y64 = np.zeros((1, Ho, Wo, K))
+        t0 = time.perf_counter()
+        oidx = orc.reduce_mask(m64, og_in, orc.POOL_AVG, 0.0)
+        yref = orc.sparse_conv_tiled(x64, oidx, og_in, og_out, w64, b64, y64)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(cpu_s * 1e3, 3), "unit": "ms", "cores": 1, "kind": "oracle",
+                               "sample": "the whole step (reduce_mask, gather, valid conv, scatter) on all %d active "
+                                         "tiles of the headline mask, fp64 direct loops, single thread; host has %d "
+                                         "cores" % (len(oidx), os.cpu_count() or 0),
+                               "gflops": round(TILE_FLOPS * len(oidx) / cpu_s / 1e9, 3)}
+        # while the reference is here: check the GPU result of the headline step against it
+        y.zero_()
+        step_fused(mask_d)
+        torch.cuda.synchronize()
+        got = y.to(torch.float64).cpu().numpy()
+        rms = float(np.sqrt(np.mean(yref * yref)))
+        bad = np.abs(got - yref) > 2e-2 * np.abs(yref) + 2e-2 * rms
+        out["parity_vs_oracle"] = {"elements": int(got.size), "out_of_tolerance": int(bad.sum()),
+                                   "indices_equal": bool(nact == len(oidx) and np.array_equal(idx[:nact].cpu().numpy(), oidx))}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

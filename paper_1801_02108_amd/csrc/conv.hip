@@ -18,53 +18,9 @@
 //                The weights are the MFMA "A" operand (rows = output channels) and the pixels the
 //                "B" operand (columns = pixels), so each lane ends up with 16 consecutive output
 //                channels of one pixel and writes them as two 16-byte NHWC stores.
-#include "common.h"
+#include "conv_common.h"
 
 namespace sbnet {
-
-// ------------------------------------------------------------------------------------------
-// element helpers
-// ------------------------------------------------------------------------------------------
-template <int DT> struct Elem;
-template <> struct Elem<SBNET_F32> {
-    typedef float T;
-    static __device__ __forceinline__ float load(const T *p) { return *p; }
-    static __device__ __forceinline__ void store(T *p, float v) { *p = v; }
-};
-template <> struct Elem<SBNET_BF16> {
-    typedef uint16_t T;
-    static __device__ __forceinline__ float load(const T *p) { return bf16_bits_to_float(*p); }
-    static __device__ __forceinline__ void store(T *p, float v) { *p = (uint16_t)float_to_bf16_bits(v); }
-};
-template <> struct Elem<SBNET_F16> {
-    typedef _Float16 T;
-    static __device__ __forceinline__ float load(const T *p) { return (float)*p; }
-    static __device__ __forceinline__ void store(T *p, float v) { *p = (_Float16)v; }
-};
-
-struct ConvParams {
-    const void *in;          // tile stack [cap][th][tw][Cin]   or feature map [N][H][W][Cin]
-    void *out;               // tile stack [cap][oh][ow][Cout]  or feature map [N][Ho][Wo][Cout]
-    const void *w;           // packed weights
-    const float *bias;       // [Cout] or null
-    const int32_t *indices;  // fused form only
-    const int32_t *count;
-    int cap;
-    int th, tw, oh, ow;
-    int Cin, Cout;
-    int kh, kw, sh, sw;
-    int relu, add;
-    sbnet_geom g_in, g_out;  // fused form only
-    int H, W, Ho, Wo;        // fused form only
-    // MFMA path work decomposition
-    int CinP;                // Cin rounded up to 32
-    int CC;                  // channels per LDS chunk (multiple of 32)
-    int nchunks;
-    int mpasses;             // passes of 256 output pixels per tile
-    int ngroups;             // groups of 64 output channels
-    int lds_rows;            // input rows held in LDS per pass (upper bound)
-    FastDiv div_ow, div_tw, div_cv, div_cv_last, div_pn, div_ng;
-};
 
 // ------------------------------------------------------------------------------------------
 // direct kernel
@@ -124,49 +80,15 @@ __global__ __launch_bounds__(256) void conv_direct(ConvParams p) {
 // ------------------------------------------------------------------------------------------
 // MFMA kernel
 // ------------------------------------------------------------------------------------------
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-
-template <int DT>
-__device__ __forceinline__ f32x4 mfma16x16x32(uint4 a, uint4 b, f32x4 c) {
-    if (DT == SBNET_BF16) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    } else {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-}
-
-template <int DT>
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    if (DT == SBNET_BF16) return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
-    union { _Float16 h[2]; uint32_t u; } v;
-    v.h[0] = (_Float16)lo;
-    v.h[1] = (_Float16)hi;
-    return v.u;
-}
-template <int DT>
-__device__ __forceinline__ float unpack_lo(uint32_t w) {
-    if (DT == SBNET_BF16) return bf16_bits_to_float(w & 0xffffu);
-    union { _Float16 h[2]; uint32_t u; } v;
-    v.u = w;
-    return (float)v.h[0];
-}
-template <int DT>
-__device__ __forceinline__ float unpack_hi(uint32_t w) {
-    if (DT == SBNET_BF16) return bf16_bits_to_float(w >> 16);
-    union { _Float16 h[2]; uint32_t u; } v;
-    v.u = w;
-    return (float)v.h[1];
-}
-
 constexpr int kMB = 4;  // 16-pixel blocks per wave
 constexpr int kNB = 4;  // 16-channel blocks per wave (64 output channels per workgroup)
 
 // Weight packing for conv_mfma.  Packed element (((ng*KS + ks)*4 + nb)*64 + lane)*8 + e holds
 // w[tap][c][o] with ks = tap*(CinP/32) + c/32, c = (ks % (CinP/32))*32 + (lane/16)*8 + e and
-// o = ng*64 + ((lane%16)/4)*16 + nb*4 + (lane%16)%4, zero where c >= Cin or o >= Cout.  The
-// permutation of o makes the four accumulator fragments of a lane cover 16 consecutive channels.
+// o = ng*64 + (nb/2)*32 + ((lane%16)/4)*8 + (nb%2)*4 + (lane%16)%4, zero where c >= Cin or
+// o >= Cout.  With this permutation of o the accumulator fragments nb = 2h, 2h+1 of a lane hold 8
+// consecutive channels (one 16-byte store), and the four lanes sharing a pixel cover 32
+// consecutive channels per half h.
 template <typename T>
 __global__ void pack_mfma_weights(const T *__restrict__ w, T *__restrict__ packed, int taps, int Cin, int Cout,
                                   int CinP, int ngroups) {
@@ -181,7 +103,33 @@ __global__ void pack_mfma_weights(const T *__restrict__ w, T *__restrict__ packe
         const int tap = ks / (CinP / 32);
         const int c = (ks % (CinP / 32)) * 32 + (lane >> 4) * 8 + e;
         const int rho = lane & 15;
-        const int o = ng * 64 + (rho >> 2) * 16 + nb * 4 + (rho & 3);
+        const int o = ng * 64 + (nb >> 1) * 32 + (rho >> 2) * 8 + (nb & 1) * 4 + (rho & 3);
+        T v = 0;
+        if (c < Cin && o < Cout) v = w[((size_t)tap * Cin + c) * Cout + o];
+        packed[idx] = v;
+    }
+}
+
+// Second copy of the weights in 32x32x16 operand order (used by the register-stationary 3x3
+// kernel).  Packed element (((ng*KS + ks)*2 + nb)*64 + lane)*8 + e holds w[tap][c][o] with
+// ks = tap*(CinP/16) + c/16, c = (ks % (CinP/16))*16 + (lane/32)*8 + e and, with rho = lane%32,
+// o = ng*64 + nb*32 + ((rho/4)%2)*16 + (rho/8)*4 + rho%4: the 16 accumulator registers of a lane
+// then hold 16 consecutive output channels.
+template <typename T>
+__global__ void pack_mfma32_weights(const T *__restrict__ w, T *__restrict__ packed, int taps, int Cin, int Cout,
+                                    int CinP, int ngroups) {
+    const int KS = taps * (CinP / 16);
+    const size_t total = (size_t)ngroups * KS * 2 * 64 * 8;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int e = (int)(idx & 7);
+        const int lane = (int)((idx >> 3) & 63);
+        const int nb = (int)((idx >> 9) & 1);
+        const size_t rest = idx >> 10;
+        const int ks = (int)(rest % KS), ng = (int)(rest / KS);
+        const int tap = ks / (CinP / 16);
+        const int c = (ks % (CinP / 16)) * 16 + (lane >> 5) * 8 + e;
+        const int rho = lane & 31;
+        const int o = ng * 64 + nb * 32 + ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
         T v = 0;
         if (c < Cin && o < Cout) v = w[((size_t)tap * Cin + c) * Cout + o];
         packed[idx] = v;
@@ -256,50 +204,77 @@ __global__ __launch_bounds__(256) void conv_mfma(ConvParams p) {
             const FastDiv dcv = (chunk == p.nchunks - 1) ? p.div_cv_last : p.div_cv;
             __syncthreads();                            // previous chunk / item fully consumed
             const uint32_t nvec = (uint32_t)nrows * p.tw * cv;
-            for (uint32_t v = threadIdx.x; v < nvec; v += 256) {
-                const uint32_t px = fdiv(v, dcv);
-                const int c8 = (int)(v - px * cv);
-                const int row = (int)fdiv(px, p.div_tw), col = (int)px - row * p.tw;
-                const int c = c0 + c8 * 8;
-                uint4 val = make_uint4(0, 0, 0, 0);
-                if (c < p.Cin) {
-                    if (FUSED) {
-                        const int gy = y0 + r_lo + row, gx = x0 + col;
-                        if (gy >= 0 && gy < p.H && gx >= 0 && gx < p.W)
-                            val = *(const uint4 *)(in + (((size_t)n * p.H + gy) * p.W + gx) * p.Cin + c);
-                    } else {
-                        val = *(const uint4 *)(in + (((size_t)b * p.th + r_lo + row) * p.tw + col) * p.Cin + c);
+            // four independent global loads in flight per thread before the LDS stores
+            for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += 256 * 4) {
+                uint4 val[4];
+                uint32_t dst[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t v = v0 + u * 256;
+                    const uint32_t px = fdiv(v, dcv);
+                    const int c8 = (int)(v - px * cv);
+                    const int row = (int)fdiv(px, p.div_tw), col = (int)px - row * p.tw;
+                    const int c = c0 + c8 * 8;
+                    val[u] = make_uint4(0, 0, 0, 0);
+                    dst[u] = px * pix_stride + c8 * 16;
+                    if (v < nvec && c < p.Cin) {
+                        if (FUSED) {
+                            const int gy = y0 + r_lo + row, gx = x0 + col;
+                            if (gy >= 0 && gy < p.H && gx >= 0 && gx < p.W)
+                                val[u] = *(const uint4 *)(in + (((size_t)n * p.H + gy) * p.W + gx) * p.Cin + c);
+                        } else {
+                            val[u] = *(const uint4 *)(in + (((size_t)b * p.th + r_lo + row) * p.tw + col) * p.Cin + c);
+                        }
                     }
                 }
-                *(uint4 *)(lds + (size_t)px * pix_stride + c8 * 16) = val;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (v0 + u * 256 < nvec) *(uint4 *)(lds + dst[u]) = val[u];
             }
             __syncthreads();
 
+            // k loop over (tap row, tap column, 32-channel step); the weight fragments of the next
+            // step are fetched from L2 while the matrix cores work on the current one
             const int steps = cc >> 5;
-            for (int r = 0; r < p.kh; ++r)
-                for (int t = 0; t < p.kw; ++t) {
-                    const int tap_off = (r * p.tw + t) * pix_stride;
-                    const int ks0 = (r * p.kw + t) * c32_total + (c0 >> 5);
-                    const uint4 *wp = (const uint4 *)p.w + ((size_t)(ng * KS + ks0) * kNB) * 64 + lane;
-                    for (int s = 0; s < steps; ++s) {
-                        uint4 wf[kNB], xf[kMB];
+            const int nit = p.kh * p.kw * steps;
+            const uint4 *wbase = (const uint4 *)p.w + ((size_t)ng * KS + (c0 >> 5)) * kNB * 64 + lane;
+            int r = 0, t = 0, st = 0;
+            uint4 wf[kNB];
 #pragma unroll
-                        for (int nb = 0; nb < kNB; ++nb) wf[nb] = wp[(size_t)(s * kNB + nb) * 64];
+            for (int nb = 0; nb < kNB; ++nb) wf[nb] = wbase[(size_t)nb * 64];
+            for (int it = 0; it < nit; ++it) {
+                int st2 = st + 1, t2 = t, r2 = r;
+                if (st2 == steps) { st2 = 0; if (++t2 == p.kw) { t2 = 0; ++r2; } }
+                uint4 wn[kNB];
+                if (it + 1 < nit) {
+                    const uint4 *wp = wbase + ((size_t)((r2 * p.kw + t2) * c32_total + st2) * kNB) * 64;
 #pragma unroll
-                        for (int mb = 0; mb < kMB; ++mb) xf[mb] = *(const uint4 *)(lds + xbase[mb] + tap_off + s * 64);
+                    for (int nb = 0; nb < kNB; ++nb) wn[nb] = wp[(size_t)nb * 64];
+                } else {
 #pragma unroll
-                        for (int mb = 0; mb < kMB; ++mb)
-#pragma unroll
-                            for (int nb = 0; nb < kNB; ++nb) acc[mb][nb] = mfma16x16x32<DT>(wf[nb], xf[mb], acc[mb][nb]);
-                    }
+                    for (int nb = 0; nb < kNB; ++nb) wn[nb] = wf[nb];
                 }
+                const int off = (r * p.tw + t) * pix_stride + st * 64;
+                uint4 xf[kMB];
+#pragma unroll
+                for (int mb = 0; mb < kMB; ++mb) xf[mb] = *(const uint4 *)(lds + xbase[mb] + off);
+#pragma unroll
+                for (int mb = 0; mb < kMB; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < kNB; ++nb) acc[mb][nb] = mfma16x16x32<DT>(wf[nb], xf[mb], acc[mb][nb]);
+#pragma unroll
+                for (int nb = 0; nb < kNB; ++nb) wf[nb] = wn[nb];
+                r = r2; t = t2; st = st2;
+            }
         }
 
-        // epilogue: lane holds channels ng*64 + q*16 + [0,16) of pixel (mb, l16)
-        const int o0 = ng * 64 + q * 16;
+        // epilogue: lane holds channels ng*64 + h*32 + q*8 + [0,8), h = 0,1, of pixel (mb, l16)
         float bias[16];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) bias[k] = (p.bias && o0 + k < p.Cout) ? p.bias[o0 + k] : 0.f;
+        for (int k = 0; k < 16; ++k) {
+            const int o = ng * 64 + (k >> 3) * 32 + q * 8 + (k & 7);
+            bias[k] = (p.bias && o < p.Cout) ? p.bias[o] : 0.f;
+        }
 #pragma unroll
         for (int mb = 0; mb < kMB; ++mb) {
             const int px = pixel[mb];
@@ -309,21 +284,21 @@ __global__ __launch_bounds__(256) void conv_mfma(ConvParams p) {
             if (FUSED) {
                 const int gy = oy0 + i, gx = ox0 + j;
                 if (gy < 0 || gy >= p.Ho || gx < 0 || gx >= p.Wo) continue;
-                dst = out + (((size_t)n * p.Ho + gy) * p.Wo + gx) * p.Cout + o0;
+                dst = out + (((size_t)n * p.Ho + gy) * p.Wo + gx) * p.Cout;
             } else {
-                dst = out + ((size_t)b * M + px) * p.Cout + o0;
+                dst = out + ((size_t)b * M + px) * p.Cout;
             }
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                if (o0 + half * 8 >= p.Cout) continue;   // Cout % 8 == 0: a vector is all in or all out
+                const int o0 = ng * 64 + half * 32 + q * 8;
+                if (o0 >= p.Cout) continue;   // Cout % 8 == 0: a vector is all in or all out
                 float v[8];
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    const int kk = half * 8 + k;
-                    float a = acc[mb][kk >> 2][kk & 3] + bias[kk];
+                    float a = acc[mb][half * 2 + (k >> 2)][k & 3] + bias[half * 8 + k];
                     v[k] = p.relu ? fmaxf(a, 0.f) : a;
                 }
-                uint4 *d4 = (uint4 *)(dst + half * 8);
+                uint4 *d4 = (uint4 *)(dst + o0);
                 if (FUSED && p.add) {
                     const uint4 old = *d4;
                     v[0] += unpack_lo<DT>(old.x); v[1] += unpack_hi<DT>(old.x);
@@ -347,7 +322,7 @@ static bool use_mfma(sbnet_dtype dt, int Cin, int Cout) {
 static size_t packed_elems(sbnet_dtype dt, int kh, int kw, int Cin, int Cout) {
     if (use_mfma(dt, Cin, Cout)) {
         const size_t CinP = ((size_t)Cin + 31) / 32 * 32, CoutP = ((size_t)Cout + 63) / 64 * 64;
-        return (size_t)kh * kw * CinP * CoutP;
+        return 2 * (size_t)kh * kw * CinP * CoutP;      // 16x16x32 operand order, then 32x32x16 operand order
     }
     return (size_t)kh * kw * Cin * Cout;
 }
@@ -374,6 +349,10 @@ static sbnet_status run_conv(const char *who, sbnet_dtype dt, ConvParams &p, hip
         return fail(SBNET_EUNSUPPORTED, "%s: tile too large", who);
     p.div_ow = make_fastdiv(p.ow);
     p.div_tw = make_fastdiv(p.tw);
+
+    if (use_mfma(dt, p.Cin, p.Cout)) p.w32_offset = packed_elems(dt, p.kh, p.kw, p.Cin, p.Cout) / 2 / 8;
+    sbnet_status st16 = SBNET_OK;
+    if (conv16_try(dt, FUSED, p, s, &st16, who)) return st16;
 
     if (!use_mfma(dt, p.Cin, p.Cout)) {
         p.div_cv = make_fastdiv(p.Cout);
@@ -445,6 +424,8 @@ extern "C" sbnet_status sbnet_pack_weights(const void *w_hwio, sbnet_dtype dtype
         const int CinP = (Cin + 31) / 32 * 32, ngroups = (Cout + 63) / 64;
         hipLaunchKernelGGL(pack_mfma_weights<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)w_hwio,
                            (uint16_t *)w_packed, kh * kw, Cin, Cout, CinP, ngroups);
+        hipLaunchKernelGGL(pack_mfma32_weights<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)w_hwio,
+                           (uint16_t *)w_packed + elems / 2, kh * kw, Cin, Cout, CinP, ngroups);
     } else if (dtype == SBNET_F32) {
         hipLaunchKernelGGL(copy_weights<uint32_t>, dim3(grid), dim3(256), 0, s, (const uint32_t *)w_hwio,
                            (uint32_t *)w_packed, elems);

@@ -113,14 +113,19 @@ __global__ __launch_bounds__(kCopyThreads) void tile_copy(V *__restrict__ img, V
                 for (int u = 0; u < kCopyUnroll; ++u)
                     if (live[u]) tile[v0 + u * kCopyThreads] = val[u];
             } else {
+                // tile reads depend only on `live`, so all of them are issued before any store
 #pragma unroll
-                for (int u = 0; u < kCopyUnroll; ++u)
-                    if (inside[u]) val[u] = tile[v0 + u * kCopyThreads];
+                for (int u = 0; u < kCopyUnroll; ++u) {
+                    vzero(val[u]);
+                    if (live[u]) val[u] = tile[v0 + u * kCopyThreads];
+                }
                 if (MODE == 2) {
                     V old[kCopyUnroll];
 #pragma unroll
-                    for (int u = 0; u < kCopyUnroll; ++u)
+                    for (int u = 0; u < kCopyUnroll; ++u) {
+                        vzero(old[u]);
                         if (inside[u]) old[u] = img[src[u]];
+                    }
 #pragma unroll
                     for (int u = 0; u < kCopyUnroll; ++u)
                         if (inside[u]) val[u] = vadd<DT>(old[u], val[u]);

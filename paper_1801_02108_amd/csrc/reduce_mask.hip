@@ -4,7 +4,8 @@
 //
 // The paper appends indices with a global atomic counter, which gives an arbitrary order.
 // Here the list is produced in lexicographic (n, by, bx) order without atomics:
-//   pass 1  one workgroup per block row: coalesced column pooling of the window rows into LDS,
+//   pass 1  one workgroup per block row: coalesced column pooling of the window rows into LDS
+//           (four columns per thread and eight rows in flight, so a row costs one memory latency),
 //           then one thread per block pools its window columns, thresholds, stores a flag byte
 //           and the row's number of active blocks;
 //   pass 2  one workgroup per block row: exclusive prefix over the row counts, then wavefront
@@ -30,7 +31,19 @@ __device__ __forceinline__ int block_sum(int v, int *lds /* >= 4 ints */) {
     return lds[0] + lds[1] + lds[2] + lds[3];
 }
 
-template <typename T, typename Acc, int POOL>
+template <typename T> struct Vec4;
+template <> struct Vec4<uint8_t> { typedef uchar4 type; };
+template <> struct Vec4<float> { typedef float4 type; };
+
+template <typename Acc> __device__ __forceinline__ Acc lowest_of();
+template <> __device__ __forceinline__ int lowest_of<int>() { return (int)0x80000000; }
+template <> __device__ __forceinline__ double lowest_of<double>() { return -__builtin_huge_val(); }
+
+constexpr int kRmRows = 8;   // window rows loaded per batch: that many independent loads in flight
+
+// VEC = 4: every thread pools four neighbouring columns with one 4-element load per row (needs
+// W % 4 == 0); VEC = 1: any W.
+template <typename T, typename Acc, int POOL, int VEC>
 __global__ __launch_bounds__(kRmThreads) void rm_pool_rows(const T *__restrict__ mask, int H, int W,
                                                             sbnet_geom g, double threshold,
                                                             int32_t *__restrict__ rowcount,
@@ -44,19 +57,43 @@ __global__ __launch_bounds__(kRmThreads) void rm_pool_rows(const T *__restrict__
     const int y0 = g.boffset_h + by * g.bstride_h;
     const int ylo = max(y0, 0), yhi = min(y0 + g.bsize_h, H);
     const bool rows_clipped = (y0 < 0) || (y0 + g.bsize_h > H);
+    const Acc neutral = POOL == SBNET_POOL_AVG ? (Acc)0 : lowest_of<Acc>();
 
     // pool the window rows of every image column (consecutive threads -> consecutive columns)
-    for (int x = threadIdx.x; x < W; x += kRmThreads) {
-        const T *p = mask + ((size_t)n * H + ylo) * W + x;
-        Acc a = 0;
-        bool first = true;
-        for (int y = ylo; y < yhi; ++y, p += W) {
-            Acc v = (Acc)*p;
-            if (POOL == SBNET_POOL_AVG) a += v;
-            else { a = (first || v > a) ? v : a; first = false; }
+    for (int x = threadIdx.x * VEC; x < W; x += kRmThreads * VEC) {
+        Acc a[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) a[k] = neutral;
+        for (int yb = ylo; yb < yhi; yb += kRmRows) {
+            Acc v[kRmRows][VEC];
+#pragma unroll
+            for (int u = 0; u < kRmRows; ++u) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) v[u][k] = neutral;
+                if (yb + u < yhi) {
+                    const T *p = mask + ((size_t)n * H + yb + u) * W + x;
+                    if (VEC == 4) {
+                        const typename Vec4<T>::type q = *reinterpret_cast<const typename Vec4<T>::type *>(p);
+                        v[u][0] = (Acc)q.x; v[u][VEC > 1 ? 1 : 0] = (Acc)q.y;
+                        v[u][VEC > 2 ? 2 : 0] = (Acc)q.z; v[u][VEC > 3 ? 3 : 0] = (Acc)q.w;
+                    } else {
+                        v[u][0] = (Acc)*p;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kRmRows; ++u)
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) {
+                    if (POOL == SBNET_POOL_AVG) a[k] += v[u][k];
+                    else a[k] = v[u][k] > a[k] ? v[u][k] : a[k];
+                }
         }
-        if (POOL == SBNET_POOL_MAX && rows_clipped) a = (first || a < (Acc)0) ? (Acc)0 : a;  // outside counts as 0
-        col[x] = a;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            if (POOL == SBNET_POOL_MAX && rows_clipped) a[k] = a[k] < (Acc)0 ? (Acc)0 : a[k];  // outside counts as 0
+            col[x + k] = a[k];
+        }
     }
     __syncthreads();
 
@@ -66,14 +103,13 @@ __global__ __launch_bounds__(kRmThreads) void rm_pool_rows(const T *__restrict__
         const int x0 = g.boffset_w + bx * g.bstride_w;
         const int xlo = max(x0, 0), xhi = min(x0 + g.bsize_w, W);
         const bool cols_clipped = (x0 < 0) || (x0 + g.bsize_w > W);
-        Acc a = 0;
-        bool first = true;
+        Acc a = neutral;
         for (int x = xlo; x < xhi; ++x) {
-            Acc v = col[x];
+            const Acc v = col[x];
             if (POOL == SBNET_POOL_AVG) a += v;
-            else { a = (first || v > a) ? v : a; first = false; }
+            else a = v > a ? v : a;
         }
-        if (POOL == SBNET_POOL_MAX && cols_clipped) a = (first || a < (Acc)0) ? (Acc)0 : a;
+        if (POOL == SBNET_POOL_MAX && cols_clipped) a = a < (Acc)0 ? (Acc)0 : a;
         const double pooled = POOL == SBNET_POOL_AVG ? (double)a / area : (double)a;
         const int active = pooled > threshold ? 1 : 0;
         flags[(size_t)row * g.bcount_w + bx] = (uint8_t)active;
@@ -156,13 +192,19 @@ extern "C" sbnet_status sbnet_reduce_mask(const void *mask, sbnet_dtype mdt, int
     hipStream_t s = (hipStream_t)stream;
     const double thr = (double)threshold;
 
-#define SBNET_RM_LAUNCH(T, ACC, P)                                                                      \
+    const bool vec4 = (W % 4 == 0) && (((uintptr_t)mask) % 16 == 0);
+#define SBNET_RM_LAUNCH1(T, ACC, P, V)                                                                  \
     do {                                                                                                \
         if (lds > 48 * 1024)                                                                            \
-            (void)hipFuncSetAttribute((const void *)rm_pool_rows<T, ACC, P>,                            \
+            (void)hipFuncSetAttribute((const void *)rm_pool_rows<T, ACC, P, V>,                         \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
-        hipLaunchKernelGGL((rm_pool_rows<T, ACC, P>), dim3(rows), dim3(kRmThreads), lds, s,             \
+        hipLaunchKernelGGL((rm_pool_rows<T, ACC, P, V>), dim3(rows), dim3(kRmThreads), lds, s,          \
                            (const T *)mask, H, W, *g, thr, rowcount, flags);                            \
+    } while (0)
+#define SBNET_RM_LAUNCH(T, ACC, P)                                                                      \
+    do {                                                                                                \
+        if (vec4) SBNET_RM_LAUNCH1(T, ACC, P, 4);                                                       \
+        else SBNET_RM_LAUNCH1(T, ACC, P, 1);                                                            \
     } while (0)
 
     if (mdt == SBNET_U8) {
@@ -173,6 +215,7 @@ extern "C" sbnet_status sbnet_reduce_mask(const void *mask, sbnet_dtype mdt, int
         else SBNET_RM_LAUNCH(float, double, SBNET_POOL_AVG);
     }
 #undef SBNET_RM_LAUNCH
+#undef SBNET_RM_LAUNCH1
     sbnet_status st = launch_status("sbnet_reduce_mask(pool)");
     if (st != SBNET_OK) return st;
     hipLaunchKernelGGL(rm_compact, dim3(rows), dim3(kRmThreads), 0, s, rowcount, flags, rows, g->bcount_h,

@@ -49,9 +49,9 @@ def test_size_queries():
     nbytes = ctypes.c_size_t()
     lib = sb.lib()
     assert lib.sbnet_pack_weights(None, sb.BF16, 3, 3, 64, 64, None, nbytes, None) == sb.OK
-    assert nbytes.value == 3 * 3 * 64 * 64 * 2
+    assert nbytes.value == 2 * 3 * 3 * 64 * 64 * 2         # two operand orders
     assert lib.sbnet_pack_weights(None, sb.BF16, 3, 3, 24, 40, None, nbytes, None) == sb.OK
-    assert nbytes.value == 3 * 3 * 32 * 64 * 2          # channels padded to the MFMA tile
+    assert nbytes.value == 2 * 3 * 3 * 32 * 64 * 2      # channels padded to the MFMA tile
     assert lib.sbnet_pack_weights(None, sb.F32, 3, 3, 16, 16, None, nbytes, None) == sb.OK
     assert nbytes.value == 3 * 3 * 16 * 16 * 4
 

@@ -198,6 +198,9 @@ CONV_CASES = [
     (3, 7, 7, 5, 3, 3, 1, "bf16", False, True),         # odd channels: direct kernel in bf16
     (3, 9, 9, 4, 6, 5, 2, "f32", True, True),
     (2, 6, 12, 96, 96, 1, 1, "bf16", False, False),
+    (3, 18, 18, 32, 128, 3, 1, "bf16", True, True),     # register-stationary 3x3 kernel: two channel groups
+    (2, 34, 18, 64, 24, 3, 1, "f16", False, True),      # ... two sub-tiles per tile, partial channel group
+    (2, 18, 50, 32, 64, 3, 1, "bf16", True, False),     # ... three sub-tiles side by side
 ]
 
 
@@ -265,6 +268,33 @@ def test_sparse_conv_fused_and_unfused(N, H, W, Cin, Cout, k, s, bo, dtype, add)
         got = to_host(y)
         assert_close(got, ref, CONV_TOL[dtype], "unfused")
         assert np.array_equal(got[~bm], y0[~bm])
+
+
+@pytest.mark.parametrize("dens", [1.0, 0.35])
+def test_sparse_conv_more_tiles_than_workgroups(dens):
+    """Persistent kernel: 342 tiles on at most 256 workgroups, so the double-buffered tile loop
+    and its prefetch run several iterations per workgroup."""
+    step("sparse_conv persistent loop dens=%s" % dens)
+    r = gen.rng_for(5, 999)
+    N, H, W, Cin, Cout, bo = 1, 288, 304, 32, 64, 16
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, 1, bo)
+    x = gen.activations(r, (N, H, W, Cin), "bf16")
+    w = gen.conv_weights(r, 3, 3, Cin, Cout, "bf16")
+    b = gen.bias_vector(r, Cout, 0.5)
+    y0 = gen.activations(r, (N, Ho, Wo, Cout), "bf16")
+    blocks = (r.random((N, H // bo, W // bo)) < dens).astype(np.uint8)
+    mask = np.repeat(np.repeat(blocks, bo, axis=1), bo, axis=2)
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_out)      # window = output block
+    idx = orc.reduce_mask(mask, ogeom(g_out))
+    assert len(idx) > 100 and sb.read_count(d_cnt, d_idx.shape[0]) == len(idx)
+    y = to_dev(y0, "bf16")
+    sb.sparse_conv(to_dev(x, "bf16"), d_idx, d_cnt, g_in, g_out, sb.pack_weights(to_dev(w, "bf16")),
+                   torch.from_numpy(b).cuda(), y, relu=False, add=True)
+    ref = orc.sparse_conv_tiled(x, idx, ogeom(g_in), ogeom(g_out), w, b, y0, add=True)
+    got = to_host(y)
+    assert_close(got, ref, CONV_TOL["bf16"], "persistent")
+    bm = orc.block_mask(idx, ogeom(g_out), N, Ho, Wo)
+    assert np.array_equal(got[~bm], y0[~bm])
 
 
 def test_config1_end_to_end():
