@@ -138,8 +138,9 @@ sbnet_status sbnet_conv_on_tiles(const void *tiles_in, sbnet_dtype dtype, const 
 
 /*
  * Fused gather -> convolution -> scatter(-add) (Fig. 1 in one kernel): same result as
- * sbnet_sparse_gather with g_in, sbnet_conv_on_tiles, sbnet_sparse_scatter with g_out,
- * without the intermediate tile stacks.  x: [N][H][W][Cin]; y: [N][H_out][W_out][Cout].
+ * sbnet_sparse_gather with g_in, sbnet_conv_on_tiles, sbnet_sparse_scatter with g_out, except
+ * that the convolution result is not rounded to `dtype` before the add; the intermediate tile
+ * stacks never exist.  x: [N][H][W][Cin]; y: [N][H_out][W_out][Cout].
  * g_in/g_out as produced by sbnet_geometry for this convolution.  y must not alias x.
  */
 sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int N, int H, int W, int Cin,
@@ -148,6 +149,57 @@ sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int N, int H, i
                                const void *w_packed, const float *bias, int kh, int kw, int sh,
                                int sw, int Cout, int relu, void *y, int H_out, int W_out,
                                int add, void *stream);
+
+/*
+ * Set every tile position that lies outside the H x W image to zero, in place.  Needed when a
+ * residual unit is composed from single sbnet_conv_on_tiles calls: after the first convolution
+ * the halo positions beyond the image border hold act(bias), but the next convolution's zero
+ * padding applies to that activation (Sec. 3.3 leaves the image border implicit).
+ * tiles: [cap][g->bsize_h][g->bsize_w][C].
+ */
+sbnet_status sbnet_zero_outside(void *tiles, sbnet_dtype dtype, int H, int W, int C,
+                                const int32_t *indices, const int32_t *count, int cap,
+                                const sbnet_geom *g, void *stream);
+
+/*
+ * Residual branch of a sparse bottleneck unit on gathered tiles (Sec. 3.3, Fig. 4; batch norm
+ * folded into weights and biases): t1 = ReLU(W1 x + b1) (1x1, C -> Cm) on the whole input tile,
+ * set to zero at tile positions outside the H x W image (the 3x3 of the dense network pads its
+ * own input with zeros); t2 = ReLU(W2 * t1 + b2) (3x3 unpadded, Cm -> Cm); t3 = W3 t2 + b3
+ * (1x1, Cm -> C).  tiles_in: [cap][g_in->bsize_h][g_in->bsize_w][C] as written by
+ * sbnet_sparse_gather; tiles_out: [cap][g_out->bsize_h][g_out->bsize_w][C] receives t3, ready for
+ * sbnet_sparse_scatter with add = 1.  indices and the geometries locate each tile in the image
+ * for the border rule.  w1, w2, w3 come from sbnet_pack_weights (shapes [1][1][C][Cm],
+ * [3][3][Cm][Cm], [1][1][Cm][C]); b1, b2, b3 are device float32 and required.  t1 and t2 are
+ * rounded to `dtype` between the layers; sums are fp32.
+ * Supported: bf16 / f16, Cm = 64, C in {64, 128, 256}, block sides multiples of 16, input tile =
+ * block + one-pixel halo; anything else returns SBNET_EUNSUPPORTED (compose the unit from
+ * sbnet_conv_on_tiles instead).
+ */
+sbnet_status sbnet_bottleneck_on_tiles(const void *tiles_in, sbnet_dtype dtype, int H, int W, int C,
+                                       int Cm, const int32_t *indices, const int32_t *count, int cap,
+                                       const sbnet_geom *g_in, const sbnet_geom *g_out,
+                                       const void *w1, const float *b1, const void *w2,
+                                       const float *b2, const void *w3, const float *b3,
+                                       void *tiles_out, void *stream);
+
+/*
+ * Whole sparse residual unit in one kernel: one gather, three convolutions, one scatter-add
+ * (Sec. 3.3, Sec. 3.4): y = x + t3 on the pixels of active blocks, with t3 as defined above.
+ * x, y: [N][H][W][C].  Pixels of inactive blocks of y are neither read nor written.
+ * The paper adds the result onto the input tensor in place; a single fused kernel cannot,
+ * because a block's halo overlaps its neighbours' output pixels.  y must therefore be a second
+ * buffer (SBNET_EINVAL if y == x).  For a stack of units sharing one index list, initialise
+ * both buffers with the input once and alternate them: inactive pixels never change, and every
+ * active pixel of the buffer being read was written by the previous unit.
+ * Same support matrix as sbnet_bottleneck_on_tiles.
+ */
+sbnet_status sbnet_sparse_bottleneck(const void *x, sbnet_dtype dtype, int N, int H, int W, int C,
+                                     int Cm, const int32_t *indices, const int32_t *count, int cap,
+                                     const sbnet_geom *g_in, const sbnet_geom *g_out,
+                                     const void *w1, const float *b1, const void *w2,
+                                     const float *b2, const void *w3, const float *b3, void *y,
+                                     void *stream);
 
 #ifdef __cplusplus
 }

@@ -50,6 +50,11 @@ _SIGNATURES = {
     "sbnet_conv_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp]),
     "sbnet_sparse_conv": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp,
                                 _ci, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _vp]),
+    "sbnet_zero_outside": (_ci, [_vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp]),
+    "sbnet_bottleneck_on_tiles": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp,
+                                        _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "sbnet_sparse_bottleneck": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp,
+                                      _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
 }
 
 
@@ -213,3 +218,48 @@ def sparse_conv(x, indices, count, g_in, g_out, w_packed, bias, y, stride=1, rel
                                    g_in, g_out, _ptr(w_packed.buf), _ptr(bias), kh, kw, stride, stride, Cout,
                                    int(bool(relu)), _ptr(y), Ho, Wo, int(bool(add)), _stream()))
     return y
+
+
+def _unit_args(weights):
+    """(w1p, b1, w2p, b2, w3p, b3) -> checked pointers plus (C, Cm)."""
+    w1, b1, w2, b2, w3, b3 = weights
+    _, _, C, Cm = w1.shape
+    assert w2.shape == (3, 3, Cm, Cm) and w3.shape == (1, 1, Cm, C), (w1.shape, w2.shape, w3.shape)
+    for b, n in ((b1, Cm), (b2, Cm), (b3, C)):
+        _dev(b, "bias", torch.float32)
+        assert b.numel() == n
+    return (_ptr(w1.buf), _ptr(b1), _ptr(w2.buf), _ptr(b2), _ptr(w3.buf), _ptr(b3)), C, Cm
+
+
+def bottleneck_on_tiles(tiles, indices, count, g_in, g_out, H, W, weights, out=None):
+    """Residual branch (1x1+ReLU, 3x3+ReLU, 1x1) on gathered tiles [cap,h,w,C] -> t3 [cap,bo,bo,C]."""
+    _dev(tiles, "tiles"), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    ptrs, C, Cm = _unit_args(weights)
+    cap = indices.shape[0]
+    assert tiles.shape == (cap, g_in.bsize_h, g_in.bsize_w, C)
+    if out is None:
+        out = torch.empty((cap, g_out.bsize_h, g_out.bsize_w, C), dtype=tiles.dtype, device=tiles.device)
+    _dev(out, "out", tiles.dtype)
+    _check(lib().sbnet_bottleneck_on_tiles(_ptr(tiles), _dt(tiles), H, W, C, Cm, _ptr(indices), _ptr(count), cap,
+                                           g_in, g_out, *ptrs, _ptr(out), _stream()))
+    return out
+
+
+def sparse_bottleneck(x, indices, count, g_in, g_out, weights, y):
+    """Fused sparse residual unit: y[active] = x[active] + branch(x); y is a second buffer. Returns y."""
+    _dev(x, "x"), _dev(y, "y", x.dtype), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    ptrs, C, Cm = _unit_args(weights)
+    N, H, W, Cx = x.shape
+    assert Cx == C and y.shape == x.shape
+    _check(lib().sbnet_sparse_bottleneck(_ptr(x), _dt(x), N, H, W, C, Cm, _ptr(indices), _ptr(count),
+                                         indices.shape[0], g_in, g_out, *ptrs, _ptr(y), _stream()))
+    return y
+
+
+def zero_outside(tiles, indices, count, g, H, W):
+    """Zero, in place, the positions of tiles [cap,h,w,C] that lie outside the H x W image."""
+    _dev(tiles, "tiles"), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    cap, h, w, C = tiles.shape
+    assert (h, w) == (g.bsize_h, g.bsize_w) and cap == indices.shape[0]
+    _check(lib().sbnet_zero_outside(_ptr(tiles), _dt(tiles), H, W, C, _ptr(indices), _ptr(count), cap, g, _stream()))
+    return tiles

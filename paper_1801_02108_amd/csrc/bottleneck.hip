@@ -1,0 +1,408 @@
+// Sparse residual (bottleneck) unit on tiles (Sec. 3.3, Fig. 4 of arXiv 1801.02108): the three
+// convolutions of a ResNet bottleneck (1x1 C->64 + ReLU, 3x3 64->64 + ReLU, 1x1 64->C; batch norm
+// folded into weights and bias) share one gather and one scatter-add (Sec. 3.4).  The receptive
+// field of the whole unit is that of its single 3x3, so the input tile is block + 1-pixel halo.
+//
+// One kernel per unit; per 16x16 output sub-tile and workgroup (4 waves, one per SIMD, weights of
+// all three convolutions resident in registers for the life of the workgroup):
+//   P1  t1 = ReLU(W1 x + b1) on the 18x18 input sub-tile.  x streams from global memory straight
+//       into MFMA operand registers (each element is used by exactly one pixel row of the GEMM, so
+//       staging it in LDS would only add traffic); t1 goes to LDS as bf16/f16.  Positions outside
+//       the image are forced to zero: the dense network pads the 3x3's input, i.e. t1, with
+//       zeros, and ReLU(b1) is not zero.
+//   P2  t2 = ReLU(W2 * t1 + b2), the 3x3 as nine shifted reads of the LDS copy of t1 (same scheme
+//       as the stand-alone 3x3 tile kernel); t2 goes to LDS.
+//   P3  t3 = W3 t2 + b3; fused form: y = x + t3 on the block's pixels (the residual x is re-read
+//       from global memory, where it was fetched moments ago for P1); on-tiles form: t3 is stored.
+// HBM traffic per sub-tile is the input tile once and the output block once.
+#include "conv_common.h"
+
+namespace sbnet {
+
+constexpr int kBT = 18;                  // input sub-tile side
+constexpr int kBTPx = kBT * kBT;         // 324 pixels
+constexpr int kCm = 64;                  // bottleneck width
+constexpr int kPS = (kCm + 8) * 2;       // LDS bytes per pixel of t1 / t2 (16 B pad)
+
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16b;
+
+template <int DT>
+__device__ __forceinline__ f32x16b mfma32(uint4 a, uint4 b, f32x16b c) {
+    if (DT == SBNET_BF16) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+}
+
+struct BneckParams {
+    const void *in;              // fused: x [N][H][W][C]; on-tiles: tiles [cap][th][tw][C]
+    void *out;                   // fused: y [N][H][W][C]; on-tiles: t3 tiles [cap][bo_h][bo_w][C]
+    const void *w1, *w2, *w3;    // packed weights (32x32x16 operand copies are used)
+    size_t w1_off, w2_off, w3_off;   // start of those copies, in 16-byte units
+    const float *b1, *b2, *b3;
+    const int32_t *indices, *count;
+    int cap;
+    int th, tw, oh, ow;          // tile and output block extents
+    int H, W;                    // image extent (border zeroing; fused addressing)
+    sbnet_geom g_in, g_out;
+    int sub_h, sub_w;
+    FastDiv div_sub, div_subw;
+};
+
+struct BItem {
+    uint32_t b;
+    int si, sj, n, by, bx;
+};
+
+__device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v), 0); }
+
+template <int DT, int C, bool FUSED>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void bottleneck16_kernel(BneckParams p) {
+    constexpr int K1 = C / 16;           // k-steps of conv1
+    constexpr int NB3 = C / 32;          // 32-channel output blocks of conv3
+    constexpr int NBW = (NB3 + 3) / 4;   // ... per wave
+    constexpr int NBLK1 = (kBTPx + 31) / 32;   // 11 pixel blocks in P1
+    __shared__ __align__(16) unsigned char t1s[kBTPx * kPS];
+    __shared__ __align__(16) unsigned char t2s[256 * kPS];
+
+    const uint16_t *in = (const uint16_t *)p.in;
+    uint16_t *out = (uint16_t *)p.out;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int g = lane >> 5, m = lane & 31;
+    const int prow = m >> 4, pcol = m & 15;
+    const int rh = wave >> 1, nh = wave & 1;
+    const uint32_t per_block = (uint32_t)p.sub_h * p.sub_w;
+    const uint32_t G = gridDim.x;
+    const uint32_t first = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
+
+    auto decode = [&](uint32_t it) {
+        BItem c;
+        c.b = fdiv(it, p.div_sub);
+        const uint32_t sidx = it - c.b * per_block;
+        c.si = (int)fdiv(sidx, p.div_subw);
+        c.sj = (int)sidx - c.si * p.sub_w;
+        c.n = p.indices[3 * c.b];
+        c.by = p.indices[3 * c.b + 1];
+        c.bx = p.indices[3 * c.b + 2];
+        return c;
+    };
+
+    const int nact_raw = *p.count;
+    BItem cur = decode(min(first, (uint32_t)p.cap * per_block - 1u));
+    const uint32_t items = (uint32_t)min(nact_raw, p.cap) * per_block;
+    if (first >= items) return;
+
+    // ---- weights resident in registers
+    uint4 w1r[K1];                       // conv1: this wave's 32 of the 64 mid channels
+    uint4 w2r[36];                       // conv2: 9 taps x 4 k-steps, this wave's 32 output channels
+    uint4 w3r[4][NBW];                   // conv3: 4 k-steps x this wave's output blocks
+    {
+        const uint4 *wp = (const uint4 *)p.w1 + p.w1_off + (size_t)nh * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < K1; ++ks) w1r[ks] = wp[(size_t)ks * 128];
+        wp = (const uint4 *)p.w2 + p.w2_off + (size_t)nh * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < 36; ++ks) w2r[ks] = wp[(size_t)ks * 128];
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) {
+            const int nbg = wave + 4 * j;            // global 32-channel block of conv3's output
+            if (nbg < NB3) {
+                wp = (const uint4 *)p.w3 + p.w3_off + ((size_t)(nbg >> 1) * 4 * 2 + (nbg & 1)) * 64 + lane;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = wp[(size_t)ks * 128];
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    }
+    auto load_bias16 = [&](const float *b, int c0) {
+        f32x16b v;
+        const float4 q0 = *(const float4 *)(b + c0), q1 = *(const float4 *)(b + c0 + 4);
+        const float4 q2 = *(const float4 *)(b + c0 + 8), q3 = *(const float4 *)(b + c0 + 12);
+        v[0] = q0.x; v[1] = q0.y; v[2] = q0.z; v[3] = q0.w; v[4] = q1.x; v[5] = q1.y; v[6] = q1.z; v[7] = q1.w;
+        v[8] = q2.x; v[9] = q2.y; v[10] = q2.z; v[11] = q2.w; v[12] = q3.x; v[13] = q3.y; v[14] = q3.z; v[15] = q3.w;
+        return v;
+    };
+    const int cm0 = nh * 32 + g * 16;                // this lane's 16 mid channels in P1 / P2
+    const f32x16b bias1 = load_bias16(p.b1, cm0), bias2 = load_bias16(p.b2, cm0);
+
+    const long long row_stride = (long long)(FUSED ? p.W : p.tw) * C;    // elements between rows of the input
+
+    for (uint32_t it = first; it < items; it += G) {
+        // geometry of this sub-tile
+        const int ty0 = cur.si * 16, tx0 = cur.sj * 16;                  // sub-tile origin inside the tile
+        const int gy0 = p.g_in.boffset_h + cur.by * p.g_in.bstride_h + ty0;   // ... in image coordinates
+        const int gx0 = p.g_in.boffset_w + cur.bx * p.g_in.bstride_w + tx0;
+        // rows / columns of the sub-tile that exist in the tile and lie inside the image
+        const int rlo = max(0, -gy0), rhi = min(min(kBT, p.th - ty0), p.H - gy0);
+        const int clo = max(0, -gx0), chi = min(min(kBT, p.tw - tx0), p.W - gx0);
+        const uint16_t *xin;
+        if (FUSED) xin = in + ((long long)cur.n * p.H + gy0) * row_stride + (long long)gx0 * C;
+        else xin = in + ((long long)cur.b * p.th + ty0) * row_stride + (long long)tx0 * C;
+
+        // ================= P1: t1 = ReLU(W1 x + b1), zero outside the image =================
+        {
+            const int mh = wave >> 1;                                    // pixel blocks mh, mh+2, ...
+            uint4 xa[2][K1];
+            auto load_block = [&](int blk, uint4 (&xr)[K1], bool &inside) {
+                const int pi = blk * 32 + m;
+                const int row = pi / kBT, col = pi - row * kBT;
+                inside = pi < kBTPx && row >= rlo && row < rhi && col >= clo && col < chi;
+                const uint16_t *src = xin + row * row_stride + col * C + g * 8;
+#pragma unroll
+                for (int ks = 0; ks < K1; ++ks) {
+                    xr[ks] = make_uint4(0, 0, 0, 0);
+                    if (inside) xr[ks] = *(const uint4 *)(src + ks * 16);
+                }
+            };
+            bool ins[2];
+            load_block(mh, xa[0], ins[0]);
+#pragma unroll
+            for (int jb = 0; jb < (NBLK1 + 1) / 2; ++jb) {
+                const int blk = mh + 2 * jb;
+                if (blk >= NBLK1) break;
+                if (blk + 2 < NBLK1) load_block(blk + 2, xa[(jb + 1) & 1], ins[(jb + 1) & 1]);
+                f32x16b acc = bias1;
+#pragma unroll
+                for (int ks = 0; ks < K1; ++ks) acc = mfma32<DT>(w1r[ks], xa[jb & 1][ks], acc);
+                const int pi = blk * 32 + m;
+                if (pi < kBTPx) {
+                    const bool inside = ins[jb & 1];
+                    uint32_t w[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k)
+                        w[k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc[2 * k])), __int_as_float(relu_bits(acc[2 * k + 1]))) : 0u;
+                    uint4 *d = (uint4 *)(t1s + pi * kPS + cm0 * 2);
+                    d[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                    d[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ================= P2: t2 = ReLU(W2 * t1 + b2) =================
+        {
+            f32x16b acc[4];
+            const unsigned char *L = t1s + ((rh * 8 + prow) * kBT + pcol) * kPS + g * 16;
+            uint4 xf[2][9];
+#pragma unroll
+            for (int j = 0; j < 9; ++j) xf[0][j] = *(const uint4 *)(L + (j * kBT) * kPS);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int st = 0; st < 12; ++st) {
+                const int t = st / 4, kc = st % 4;
+                const int tn = (st + 1) / 4, kcn = (st + 1) % 4;
+#pragma unroll
+                for (int mm = 0; mm < 12; ++mm) {
+                    const int r = mm >> 2, P = mm & 3;
+                    acc[P] = mfma32<DT>(w2r[(r * 3 + t) * 4 + kc], xf[st & 1][2 * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
+                    if (mm < 9 && st + 1 < 12)
+                        xf[(st + 1) & 1][mm] = *(const uint4 *)(L + (mm * kBT + tn) * kPS + kcn * 32);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#pragma unroll
+            for (int P = 0; P < 4; ++P) {
+                const int po = (rh * 8 + 2 * P + prow) * 16 + pcol;
+                uint32_t w[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    w[k] = pack2<DT>(__int_as_float(relu_bits(acc[P][2 * k])), __int_as_float(relu_bits(acc[P][2 * k + 1])));
+                uint4 *d = (uint4 *)(t2s + po * kPS + cm0 * 2);
+                d[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                d[1] = make_uint4(w[4], w[5], w[6], w[7]);
+            }
+        }
+        __syncthreads();
+
+        // next item's indices while P3 runs
+        const uint32_t nit = it + G;
+        BItem nxt = cur;
+        if (nit < items) nxt = decode(nit);
+
+        // ================= P3: t3 = W3 t2 + b3 (+ x), two pixel blocks at a time =================
+        {
+            // conv3's bias is only live in this phase: re-read it per tile (cache hit) rather than
+            // holding 16*NBW registers through P1 and P2
+            f32x16b bias3[NBW];
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) {
+                const int nbg = wave + 4 * j;
+                bias3[j] = load_bias16(p.b3, (nbg < NB3 ? nbg : 0) * 32 + g * 16);
+            }
+            // output addressing of this lane's pixel in a pixel block: rows 2*blk + prow, column pcol
+            const int ocol = tx0 + pcol;
+            int rmin = 0, rlim = p.oh;
+            bool col_ok = ocol < p.ow;
+            uint16_t *obase;
+            const uint16_t *rbase = nullptr;
+            long long orow_stride;
+            if (FUSED) {
+                const int oy0 = p.g_out.boffset_h + cur.by * p.g_out.bstride_h;
+                const int gx = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + ocol;
+                col_ok = col_ok && gx >= 0 && gx < p.W;
+                rmin = max(0, -oy0);
+                rlim = min(rlim, p.H - oy0);
+                orow_stride = (long long)p.W * C;
+                obase = out + ((long long)cur.n * p.H + oy0) * orow_stride + (long long)gx * C + g * 16;
+                rbase = in + ((long long)cur.n * p.H + oy0) * orow_stride + (long long)gx * C + g * 16;
+            } else {
+                orow_stride = (long long)p.ow * C;
+                obase = out + (long long)cur.b * p.oh * orow_stride + (long long)ocol * C + g * 16;
+            }
+#pragma unroll
+            for (int bp = 0; bp < 4; ++bp) {                              // pixel blocks 2bp, 2bp+1
+                uint4 tf[2][4];
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        tf[u][ks] = *(const uint4 *)(t2s + ((2 * bp + u) * 32 + m) * kPS + ks * 32 + g * 16);
+                bool ok[2];
+                long long ooff[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int orow = ty0 + (2 * bp + u) * 2 + prow;
+                    ok[u] = col_ok && orow >= rmin && orow < rlim;
+                    ooff[u] = orow * orow_stride;
+                }
+                // residual x for the fused form, fetched before the matrix work
+                uint4 res[2][NBW][2];
+                if (FUSED) {
+#pragma unroll
+                    for (int u = 0; u < 2; ++u)
+#pragma unroll
+                        for (int j = 0; j < NBW; ++j) {
+                            const int nbg = wave + 4 * j;
+                            res[u][j][0] = res[u][j][1] = make_uint4(0, 0, 0, 0);
+                            if (ok[u] && nbg < NB3) {
+                                const uint4 *r4 = (const uint4 *)(rbase + ooff[u] + nbg * 32);
+                                res[u][j][0] = r4[0];
+                                res[u][j][1] = r4[1];
+                            }
+                        }
+                }
+                f32x16b acc[2][NBW];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int u = 0; u < 2; ++u)
+#pragma unroll
+                        for (int j = 0; j < NBW; ++j)
+                            acc[u][j] = mfma32<DT>(w3r[ks][j], tf[u][ks], ks == 0 ? bias3[j] : acc[u][j]);
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int j = 0; j < NBW; ++j) {
+                        const int nbg = wave + 4 * j;
+                        if (!(ok[u] && nbg < NB3)) continue;
+                        uint32_t w[8];
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            float lo = acc[u][j][2 * k], hi = acc[u][j][2 * k + 1];
+                            if (FUSED) {
+                                const uint4 rv = res[u][j][k >> 2];
+                                const uint32_t rw = (k & 3) == 0 ? rv.x : (k & 3) == 1 ? rv.y : (k & 3) == 2 ? rv.z : rv.w;
+                                lo += unpack_lo<DT>(rw);
+                                hi += unpack_hi<DT>(rw);
+                            }
+                            w[k] = pack2<DT>(lo, hi);
+                        }
+                        uint4 *d = (uint4 *)(obase + ooff[u] + nbg * 32);
+                        d[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                        d[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                    }
+            }
+        }
+        cur = nxt;
+    }
+}
+
+}  // namespace sbnet
+
+using namespace sbnet;
+
+static bool packed_is_mfma(sbnet_dtype dt, int Cin, int Cout) {
+    return (dt == SBNET_BF16 || dt == SBNET_F16) && Cin % 8 == 0 && Cout % 8 == 0;
+}
+static size_t w32_off(int taps, int Cin, int Cout) {     // 16-byte units, same rule as sbnet_pack_weights
+    const size_t CinP = ((size_t)Cin + 31) / 32 * 32, CoutP = ((size_t)Cout + 63) / 64 * 64;
+    return taps * CinP * CoutP / 8;
+}
+
+template <int DT, bool FUSED>
+static sbnet_status launch_bneck(int C, const BneckParams &p, dim3 grid, hipStream_t s, const char *who) {
+    switch (C) {
+        case 64: hipLaunchKernelGGL((bottleneck16_kernel<DT, 64, FUSED>), grid, dim3(256), 0, s, p); break;
+        case 128: hipLaunchKernelGGL((bottleneck16_kernel<DT, 128, FUSED>), grid, dim3(256), 0, s, p); break;
+        case 256: hipLaunchKernelGGL((bottleneck16_kernel<DT, 256, FUSED>), grid, dim3(256), 0, s, p); break;
+        default: return fail(SBNET_EUNSUPPORTED, "%s: C must be 64, 128 or 256", who);
+    }
+    return launch_status(who);
+}
+
+static sbnet_status bneck_entry(const char *who, bool fused, const void *in, void *out, sbnet_dtype dt, int N, int H,
+                                int W, int C, int Cm, const int32_t *indices, const int32_t *count, int cap,
+                                const sbnet_geom *g_in, const sbnet_geom *g_out, const void *w1, const float *b1,
+                                const void *w2, const float *b2, const void *w3, const float *b3, void *stream) {
+    if (!in || !out || !indices || !count || !w1 || !w2 || !w3 || !b1 || !b2 || !b3)
+        return fail(SBNET_EINVAL, "%s: null pointer (biases are required)", who);
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || Cm <= 0 || cap < 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
+    if (!geom_ok(g_in) || !geom_ok(g_out)) return fail(SBNET_EINVAL, "%s: bad geometry", who);
+    if (g_in->bsize_h - 2 != g_out->bsize_h || g_in->bsize_w - 2 != g_out->bsize_w)
+        return fail(SBNET_EINVAL, "%s: input tile must be the output block plus a one-pixel halo", who);
+    if (g_out->bstride_h < g_out->bsize_h || g_out->bstride_w < g_out->bsize_w)
+        return fail(SBNET_EINVAL, "%s: output blocks must not overlap", who);
+    if (fused && in == out) return fail(SBNET_EINVAL, "%s: y must not alias x (use two buffers, see header)", who);
+    if (((uintptr_t)in | (uintptr_t)out | (uintptr_t)w1 | (uintptr_t)w2 | (uintptr_t)w3) & 15)
+        return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    if (dt != SBNET_BF16 && dt != SBNET_F16) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be bf16 or f16", who);
+    if (Cm != kCm) return fail(SBNET_EUNSUPPORTED, "%s: bottleneck width must be 64", who);
+    if (g_out->bsize_h % 16 || g_out->bsize_w % 16)
+        return fail(SBNET_EUNSUPPORTED, "%s: block sides must be multiples of 16", who);
+    if (!packed_is_mfma(dt, C, Cm)) return fail(SBNET_EUNSUPPORTED, "%s: channel counts must be multiples of 8", who);
+    if (cap == 0) return SBNET_OK;
+    if (18LL * (fused ? W : g_in->bsize_w) * C >= (1LL << 30)) return fail(SBNET_EUNSUPPORTED, "%s: rows too long", who);
+
+    BneckParams p = {};
+    p.in = in; p.out = out;
+    p.w1 = w1; p.w2 = w2; p.w3 = w3;
+    p.w1_off = w32_off(1, C, Cm); p.w2_off = w32_off(9, Cm, Cm); p.w3_off = w32_off(1, Cm, C);
+    p.b1 = b1; p.b2 = b2; p.b3 = b3;
+    p.indices = indices; p.count = count; p.cap = cap;
+    p.th = g_in->bsize_h; p.tw = g_in->bsize_w; p.oh = g_out->bsize_h; p.ow = g_out->bsize_w;
+    p.H = H; p.W = W;
+    p.g_in = *g_in; p.g_out = *g_out;
+    p.sub_h = p.oh / 16; p.sub_w = p.ow / 16;
+    p.div_sub = make_fastdiv((uint32_t)p.sub_h * p.sub_w);
+    p.div_subw = make_fastdiv((uint32_t)p.sub_w);
+    const long long items = (long long)cap * p.sub_h * p.sub_w;
+    if (items >= (1LL << 31)) return fail(SBNET_EUNSUPPORTED, "%s: too many work items", who);
+    long long gx = (items + 7) / 8 * 8;
+    if (gx > 256) gx = 256;
+    dim3 grid((unsigned)gx);
+    hipStream_t s = (hipStream_t)stream;
+    if (dt == SBNET_BF16) return fused ? launch_bneck<SBNET_BF16, true>(C, p, grid, s, who) : launch_bneck<SBNET_BF16, false>(C, p, grid, s, who);
+    return fused ? launch_bneck<SBNET_F16, true>(C, p, grid, s, who) : launch_bneck<SBNET_F16, false>(C, p, grid, s, who);
+}
+
+extern "C" sbnet_status sbnet_bottleneck_on_tiles(const void *tiles_in, sbnet_dtype dtype, int H, int W, int C, int Cm,
+                                                  const int32_t *indices, const int32_t *count, int cap,
+                                                  const sbnet_geom *g_in, const sbnet_geom *g_out, const void *w1,
+                                                  const float *b1, const void *w2, const float *b2, const void *w3,
+                                                  const float *b3, void *tiles_out, void *stream) {
+    return bneck_entry("sbnet_bottleneck_on_tiles", false, tiles_in, tiles_out, dtype, 1, H, W, C, Cm, indices, count,
+                       cap, g_in, g_out, w1, b1, w2, b2, w3, b3, stream);
+}
+
+extern "C" sbnet_status sbnet_sparse_bottleneck(const void *x, sbnet_dtype dtype, int N, int H, int W, int C, int Cm,
+                                                const int32_t *indices, const int32_t *count, int cap,
+                                                const sbnet_geom *g_in, const sbnet_geom *g_out, const void *w1,
+                                                const float *b1, const void *w2, const float *b2, const void *w3,
+                                                const float *b3, void *y, void *stream) {
+    return bneck_entry("sbnet_sparse_bottleneck", true, x, y, dtype, N, H, W, C, Cm, indices, count, cap, g_in, g_out,
+                       w1, b1, w2, b2, w3, b3, stream);
+}

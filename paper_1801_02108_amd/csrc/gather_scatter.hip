@@ -69,7 +69,8 @@ __device__ __forceinline__ void vzero(uint2 &v) { v = make_uint2(0, 0); }
 __device__ __forceinline__ void vzero(uint32_t &v) { v = 0; }
 __device__ __forceinline__ void vzero(uint16_t &v) { v = 0; }
 
-// MODE 0: gather (image -> tiles, zero fill), 1: scatter (tiles -> image), 2: scatter-add.
+// MODE 0: gather (image -> tiles, zero fill), 1: scatter (tiles -> image), 2: scatter-add,
+// 3: zero the tile positions that lie outside the image (img is not touched).
 template <typename V, int MODE, int DT>
 __global__ __launch_bounds__(kCopyThreads) void tile_copy(V *__restrict__ img, V *__restrict__ tiles,
                                                            const int32_t *__restrict__ indices,
@@ -103,7 +104,13 @@ __global__ __launch_bounds__(kCopyThreads) void tile_copy(V *__restrict__ img, V
                 inside[u] = live[u] && yy >= 0 && yy < p.H && rem >= rem_lo && rem < rem_hi;
                 src[u] = img_base + (long long)yy * p.W * p.pix_vecs + rem;
             }
-            if (MODE == 0) {
+            if (MODE == 3) {
+#pragma unroll
+                for (int u = 0; u < kCopyUnroll; ++u) {
+                    vzero(val[u]);
+                    if (live[u] && !inside[u]) tile[v0 + u * kCopyThreads] = val[u];
+                }
+            } else if (MODE == 0) {
 #pragma unroll
                 for (int u = 0; u < kCopyUnroll; ++u) {
                     vzero(val[u]);
@@ -170,7 +177,7 @@ static sbnet_status tile_copy_entry(const char *who, int mode, void *img, void *
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || cap < 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
     if (!geom_ok(g)) return fail(SBNET_EINVAL, "%s: bad geometry", who);
     if (!is_float_dtype(dt)) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be f32, bf16 or f16", who);
-    if (mode != 0 && (g->bstride_h < g->bsize_h || g->bstride_w < g->bsize_w))
+    if ((mode == 1 || mode == 2) && (g->bstride_h < g->bsize_h || g->bstride_w < g->bsize_w))
         return fail(SBNET_EINVAL, "%s: scatter needs non-overlapping blocks (bstride >= bsize)", who);
     if (((uintptr_t)img | (uintptr_t)tiles) & 15) return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
     if (cap == 0) return SBNET_OK;
@@ -208,6 +215,7 @@ static sbnet_status tile_copy_entry(const char *who, int mode, void *img, void *
                         : dispatch_vec<MODE, SBNET_F16>(vec, img, tiles, indices, count, p, s))
     if (mode == 0) return SBNET_COPY_DT(0);
     if (mode == 1) return SBNET_COPY_DT(1);
+    if (mode == 3) return SBNET_COPY_DT(3);
     return SBNET_COPY_DT(2);
 #undef SBNET_COPY_DT
 }
@@ -221,6 +229,12 @@ extern "C" sbnet_status sbnet_sparse_gather(const void *x, sbnet_dtype dtype, in
                                             const sbnet_geom *g, void *tiles, void *stream) {
     return tile_copy_entry("sbnet_sparse_gather", 0, const_cast<void *>(x), tiles, dtype, N, H, W, C, indices,
                            count, cap, g, stream);
+}
+
+extern "C" sbnet_status sbnet_zero_outside(void *tiles, sbnet_dtype dtype, int H, int W, int C, const int32_t *indices,
+                                           const int32_t *count, int cap, const sbnet_geom *g, void *stream) {
+    // the image pointer is only checked for null and alignment in this mode: pass the tile stack
+    return tile_copy_entry("sbnet_zero_outside", 3, tiles, tiles, dtype, 1, H, W, C, indices, count, cap, g, stream);
 }
 
 extern "C" sbnet_status sbnet_sparse_scatter(const void *tiles, sbnet_dtype dtype, const int32_t *indices,

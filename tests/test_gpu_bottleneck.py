@@ -1,0 +1,170 @@
+"""GPU parity of the sparse residual (bottleneck) unit against the fp64 oracle: the branch on
+gathered tiles, the fused one-kernel unit, stacks with two alternating buffers, and the unit
+composed from single calls for block sizes the fused kernel does not take."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_1801_02108_amd as sb
+from paper_1801_02108_amd import inputs as gen
+from util import CONV_TOL, TORCH_DT, assert_close, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def step(msg):
+    print("[case] " + msg, flush=True)
+
+
+def ogeom(g):
+    return orc.Geom(*g.astuple())
+
+
+def dev_weights(ws, dtype):
+    w1, b1, w2, b2, w3, b3 = ws
+    return (sb.pack_weights(to_dev(w1, dtype)), torch.from_numpy(b1).cuda(), sb.pack_weights(to_dev(w2, dtype)),
+            torch.from_numpy(b2).cuda(), sb.pack_weights(to_dev(w3, dtype)), torch.from_numpy(b3).cuda())
+
+
+def block_aligned_mask(r, N, H, W, bo, dens):
+    """Mask made of whole bo x bo blocks (ragged last blocks included) with the given block density."""
+    bh, bw = -(-H // bo), -(-W // bo)
+    blocks = (r.random((N, bh, bw)) < dens).astype(np.uint8)
+    return np.repeat(np.repeat(blocks, bo, axis=1), bo, axis=2)[:, :H, :W].copy()
+
+
+UNIT_CASES = [
+    # N, H, W, C, bo, dtype
+    (2, 48, 48, 256, 16, "bf16"),
+    (1, 40, 56, 128, 16, "bf16"),     # ragged: 40 = 2*16 + 8
+    (1, 64, 32, 64, 16, "f16"),
+    (1, 64, 96, 256, 32, "bf16"),     # four 16x16 sub-tiles per block
+    (1, 40, 40, 64, 32, "f16"),       # sub-tiles hanging over the image edge
+]
+
+
+@pytest.mark.parametrize("N,H,W,C,bo,dtype", UNIT_CASES)
+def test_bottleneck_on_tiles_and_fused(N, H, W, C, bo, dtype):
+    step("bottleneck %s" % ((N, H, W, C, bo, dtype),))
+    r = gen.rng_for(3, H * 100 + C + bo)
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    x = gen.activations(r, (N, H, W, C), dtype)
+    ws = gen.bottleneck_weights(r, C, 64, dtype)
+    dws = dev_weights(ws, dtype)
+    dx = to_dev(x, dtype)
+    for dens in (1.0, 0.3, 0.0):
+        mask = block_aligned_mask(r, N, H, W, bo, dens)
+        d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_out)
+        idx = orc.reduce_mask(mask, ogeom(g_out))
+        assert sb.read_count(d_cnt, d_idx.shape[0]) == len(idx)
+        # --- branch on gathered tiles
+        tiles = sb.sparse_gather(dx, d_idx, d_cnt, g_in)
+        t3 = torch.full((d_idx.shape[0], bo, bo, C), 3.0, dtype=TORCH_DT[dtype]).cuda()
+        sb.bottleneck_on_tiles(tiles, d_idx, d_cnt, g_in, g_out, H, W, dws, out=t3)
+        ref_t3 = orc.bottleneck_on_tiles(orc.gather(x, idx, ogeom(g_in)), idx, ogeom(g_in), H, W, *ws)
+        got = to_host(t3)
+        assert_close(got[:len(idx)], ref_t3, CONV_TOL[dtype], "bottleneck_on_tiles")
+        assert (got[len(idx):] == 3.0).all()
+        # --- separate scatter-add onto a copy of x (the paper's in-place form)
+        y = dx.clone()
+        sb.sparse_scatter(t3, d_idx, d_cnt, g_out, y, add=True)
+        ref = orc.sparse_bottleneck_tiled(x, idx, ogeom(g_in), ogeom(g_out), *ws)
+        assert_close(to_host(y), ref, CONV_TOL[dtype], "unfused unit")
+        # --- fused unit into a second buffer holding other values at inactive pixels
+        y0 = gen.activations(r, (N, H, W, C), dtype)
+        y = to_dev(y0, dtype)
+        sb.sparse_bottleneck(dx, d_idx, d_cnt, g_in, g_out, dws, y)
+        got = to_host(y)
+        bm = orc.block_mask(idx, ogeom(g_out), N, H, W)
+        assert np.array_equal(got[~bm], y0[~bm])                   # inactive pixels neither read nor written
+        assert_close(got[bm], ref[bm], CONV_TOL[dtype], "fused unit")
+        if dens == 1.0:                                            # every block active: the dense unit
+            assert_close(got, orc.sparse_bottleneck_dense(x, idx, ogeom(g_out), *ws), CONV_TOL[dtype], "dense unit")
+
+
+def test_bottleneck_border_rule_matters_on_gpu_inputs():
+    """With a large positive b1 the value ReLU(b1) would leak into the 3x3 at the image border if t1
+    were not zeroed there; the GPU result must follow the dense unit (which pads t1 with zeros)."""
+    step("bottleneck border rule")
+    r = gen.rng_for(3, 4242)
+    N, H, W, C, bo = 1, 32, 32, 64, 16
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    x = gen.activations(r, (N, H, W, C), "bf16")
+    w1, b1, w2, b2, w3, b3 = gen.bottleneck_weights(r, C, 64, "bf16")
+    b1 = (np.abs(b1) + 2.0).astype(np.float32)
+    ws = (w1, b1, w2, b2, w3, b3)
+    d_idx, d_cnt = sb.reduce_mask(torch.ones((N, H, W), dtype=torch.uint8).cuda(), g_out)
+    idx = orc.reduce_mask(np.ones((N, H, W)), ogeom(g_out))
+    y = torch.zeros((N, H, W, C), dtype=torch.bfloat16).cuda()
+    sb.sparse_bottleneck(to_dev(x, "bf16"), d_idx, d_cnt, g_in, g_out, dev_weights(ws, "bf16"), y)
+    assert_close(to_host(y), orc.sparse_bottleneck_dense(x, idx, ogeom(g_out), *ws), CONV_TOL["bf16"], "border")
+
+
+def test_stack_of_units_with_two_buffers():
+    """Three units sharing one index list, alternating two buffers that both start as the input."""
+    step("bottleneck stack")
+    r = gen.rng_for(5, 31)
+    N, H, W, C, bo = 2, 48, 64, 128, 16
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    x = gen.activations(r, (N, H, W, C), "bf16")
+    units = [gen.bottleneck_weights(r, C, 64, "bf16") for _ in range(3)]
+    mask = block_aligned_mask(r, N, H, W, bo, 0.4)
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_out)
+    idx = orc.reduce_mask(mask, ogeom(g_out))
+    a = to_dev(x, "bf16")
+    b = a.clone()
+    ref = x.astype(np.float64)
+    for ws in units:
+        sb.sparse_bottleneck(a, d_idx, d_cnt, g_in, g_out, dev_weights(ws, "bf16"), b)
+        a, b = b, a
+        # the oracle consumes what the GPU actually fed the next unit (bf16-rounded activations)
+        ref = orc.sparse_bottleneck_tiled(ref, idx, ogeom(g_in), ogeom(g_out), *ws)
+    # three units: rounding of the running sum to bf16 after each unit adds ~2^-9 relative per unit
+    assert_close(to_host(a), ref, 3e-2, "stack of 3")
+    bm = orc.block_mask(idx, ogeom(g_out), N, H, W)
+    assert np.array_equal(to_host(a)[~bm], x[~bm])
+
+
+def test_unit_composed_from_single_calls_for_small_blocks():
+    """Block size 8 is not taken by the fused kernel (SBNET_EUNSUPPORTED); the unit composed of
+    gather, three conv_on_tiles calls, zero_outside and scatter-add gives the oracle's result."""
+    step("bottleneck composed, bo=8")
+    r = gen.rng_for(4, 8)
+    N, H, W, C, bo = 1, 40, 24, 64, 8
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    x = gen.activations(r, (N, H, W, C), "bf16")
+    ws = gen.bottleneck_weights(r, C, 64, "bf16")
+    w1p, b1, w2p, b2, w3p, b3 = dev_weights(ws, "bf16")
+    mask = block_aligned_mask(r, N, H, W, bo, 0.6)
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_out)
+    idx = orc.reduce_mask(mask, ogeom(g_out))
+    dx = to_dev(x, "bf16")
+    with pytest.raises(sb.SbnetError) as e:
+        sb.sparse_bottleneck(dx, d_idx, d_cnt, g_in, g_out, (w1p, b1, w2p, b2, w3p, b3), dx.clone())
+    assert e.value.code == sb.EUNSUPPORTED
+    tiles = sb.sparse_gather(dx, d_idx, d_cnt, g_in)
+    t1 = sb.conv_on_tiles(tiles, d_cnt, w1p, b1, relu=True)
+    sb.zero_outside(t1, d_idx, d_cnt, g_in, H, W)
+    t2 = sb.conv_on_tiles(t1, d_cnt, w2p, b2, relu=True)
+    t3 = sb.conv_on_tiles(t2, d_cnt, w3p, b3)
+    y = dx.clone()
+    sb.sparse_scatter(t3, d_idx, d_cnt, g_out, y, add=True)
+    assert_close(to_host(y), orc.sparse_bottleneck_tiled(x, idx, ogeom(g_in), ogeom(g_out), *ws), CONV_TOL["bf16"],
+                 "composed unit")
+
+
+def test_zero_outside_bit_exact():
+    step("zero_outside")
+    r = gen.rng_for(4, 9)
+    N, H, W, C, bo = 2, 21, 13, 6, 4
+    g_in, _, _, _ = sb.geometry(H, W, 3, 1, bo)
+    mask = (r.random((N, H, W)) < 0.2).astype(np.uint8)
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in)
+    idx = orc.reduce_mask(mask, ogeom(g_in))
+    t = gen.activations(r, (d_idx.shape[0], g_in.bsize_h, g_in.bsize_w, C), "bf16")
+    dt = to_dev(t, "bf16")
+    sb.zero_outside(dt, d_idx, d_cnt, g_in, H, W)
+    got = to_host(dt)
+    assert np.array_equal(got[:len(idx)], orc.zero_outside(t[:len(idx)], idx, ogeom(g_in), H, W))
+    assert np.array_equal(got[len(idx):], t[len(idx):])
