@@ -37,7 +37,172 @@ def parse():
     ap.add_argument("--density", type=float, default=0.10, help="target active-block fraction of the headline run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip sweep, dense and MIOpen comparisons")
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"],
+                    help="cfg2 (default) is the headline single 3x3 conv; cfg3/4/5 are the residual-unit workloads")
     return ap.parse_args()
+
+
+# ---------------------------------------------------------------------------------------------------
+# residual-unit workloads (configs 3-5): sparse bottleneck 256 -> 64 -> 64 -> 256, bf16
+# ---------------------------------------------------------------------------------------------------
+def unit_flops(bo, C=256, Cm=64):
+    """FLOPs the method performs per active block, halo recompute of the first 1x1 included."""
+    sub = (bo // 16) ** 2 if bo % 16 == 0 else None
+    t = 18 if sub else bo + 2
+    o = 16 if sub else bo
+    per = 2 * (t * t * C * Cm + o * o * 9 * Cm * Cm + o * o * Cm * C)
+    return per * (sub or 1)
+
+
+def unit_bytes(bo, C=256):
+    """Algorithmic HBM bytes per active block: input tile once, output block once (bf16)."""
+    return ((bo + 2) ** 2 + bo * bo) * C * 2
+
+
+def run_units(args):
+    import numpy as np
+    import torch
+    import paper_1801_02108_amd as sb
+    from paper_1801_02108_amd import inputs as gen
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    cfg = args.workload
+    C, Cm = 256, 64
+    if cfg == "cfg3":
+        N, H, W, bos, targets, n_units, kind = 1, 400, 352, [16], [0.10, 0.30, 1.0], 1, "road"
+    elif cfg == "cfg4":
+        N, H, W, bos, n_units, kind = 4, 800, 704, [16, 32], 1, "blob"
+        targets = [0.01, 0.02, 0.05, 0.10, 0.20, 0.30, 0.50, 0.70, 0.85, 1.0]
+    else:
+        N, H, W, bos, targets, n_units, kind = 8, 800, 704, [16], [0.15, 1.0], 8, "lowres"
+    r = gen.rng_for(int(cfg[-1]))
+    tg = torch.Generator(device=dev)
+    tg.manual_seed(gen.BASE_SEED + int(cfg[-1]))
+    x = torch.randn((N, H, W, C), generator=tg, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    bufs = [x.clone(), x.clone()]
+    units = []
+    for _ in range(n_units):
+        w1, b1, w2, b2, w3, b3 = gen.bottleneck_weights(r, C, Cm, "bf16")
+        units.append((sb.pack_weights(torch.from_numpy(w1).to(torch.bfloat16).to(dev)), torch.from_numpy(b1).to(dev),
+                      sb.pack_weights(torch.from_numpy(w2).to(torch.bfloat16).to(dev)), torch.from_numpy(b2).to(dev),
+                      sb.pack_weights(torch.from_numpy(w3).to(torch.bfloat16).to(dev)), torch.from_numpy(b3).to(dev)))
+    if kind == "road":
+        fields = gen.road_band_fields(r, H, W, 3)
+    elif kind == "blob":
+        field = gen.smooth_noise(r, N, H, W, 24.0)
+    else:
+        logits_np = gen.smooth_noise(r, N, H // 8, W // 8, 2.0)      # low-passed so 15 % of blocks is reachable
+        logits = torch.from_numpy(logits_np).to(dev)
+
+    rows = []
+    for bo in bos:
+        g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+        total = N * g_in.bcount_h * g_in.bcount_w
+        idx = torch.empty((total, 3), dtype=torch.int32, device=dev)
+        cnt = torch.empty((1,), dtype=torch.int32, device=dev)
+        ws = torch.empty((sb.workspace_bytes(N, g_in),), dtype=torch.uint8, device=dev)
+
+        def count_active(m_np):
+            sb.reduce_mask(torch.from_numpy(m_np).to(dev), g_in, sb.POOL_AVG, 0.0, idx, cnt, ws)
+            return sb.read_count(cnt, total)
+
+        dense_ms = None
+        for target in sorted(targets, reverse=True):
+            thr_t = None
+            if target >= 1.0:
+                m_np = np.ones((N, H, W), dtype=np.uint8)
+            elif kind == "road":
+                m_np = gen.calibrate(lambda s_: np.repeat(gen.road_band_mask(fields, s_), N, axis=0), count_active, total,
+                                     target, 0.0, 12.0)[0]
+            elif kind == "blob":
+                m_np = gen.calibrate(lambda t_: gen.blob_mask(field, t_), count_active, total, target, -4.0, 4.0,
+                                     increasing=False)[0]
+            else:
+                m_np, thr_t, _ = gen.calibrate(lambda t_: gen.lowres_mask(logits_np, t_), count_active, total, target, -4.0,
+                                               4.0, increasing=False)
+            m_d = torch.from_numpy(m_np).to(dev)
+            n = count_active(m_np)
+
+            def step():
+                if thr_t is not None:   # dynamic mask: threshold the low-resolution logits, upsample x8 (mask source)
+                    md = (logits > thr_t).to(torch.uint8).repeat_interleave(8, 1).repeat_interleave(8, 2)
+                else:
+                    md = m_d
+                sb.reduce_mask(md, g_in, sb.POOL_AVG, 0.0, idx, cnt, ws)
+                a, b = bufs
+                for u in units:
+                    sb.sparse_bottleneck(a, idx, cnt, g_in, g_out, u, b)
+                    a, b = b, a
+
+            for _ in range(3):
+                step()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            iters = max(3, min(50, int(2000 / max(n * n_units, 1)) + 3))
+            e0.record()
+            for _ in range(iters):
+                step()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / iters
+            # the unit kernel alone
+            u0 = units[0]
+            for _ in range(2):
+                sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1])
+            e0.record()
+            for _ in range(iters):
+                sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1])
+            e1.record()
+            torch.cuda.synchronize()
+            k_ms = e0.elapsed_time(e1) / iters
+            if target >= 1.0:
+                dense_ms = ms
+            rows.append({"block": bo, "target": target, "active_blocks": n, "total_blocks": total,
+                         "step_ms": round(ms, 5), "unit_kernel_ms": round(k_ms, 5),
+                         "unit_tflops": round(unit_flops(bo) * n / k_ms / 1e9, 2),
+                         "unit_hbm_GBps_algorithmic": round(unit_bytes(bo) * n / k_ms / 1e6, 1),
+                         "speedup_vs_own_dense": round(dense_ms / ms, 3), "ideal_speedup": round(total / max(n, 1), 2)})
+            bufs[1].copy_(bufs[0])
+    # MIOpen dense unit through torch, external baseline only (3 convs + ReLUs + add)
+    miopen_ms = None
+    try:
+        xt = x.permute(0, 3, 1, 2)
+        rr = gen.rng_for(int(cfg[-1]), 7)
+        tw = [torch.from_numpy(w).to(torch.bfloat16).to(dev).permute(3, 2, 0, 1).contiguous(memory_format=torch.channels_last)
+              for w in gen.bottleneck_weights(rr, C, Cm, "bf16")[0::2]]
+        F = torch.nn.functional
+
+        def dense_unit():
+            t = F.relu(F.conv2d(xt, tw[0]))
+            t = F.relu(F.conv2d(t, tw[1], padding=1))
+            return xt + F.conv2d(t, tw[2])
+        for _ in range(3):
+            dense_unit()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            dense_unit()
+        e1.record()
+        torch.cuda.synchronize()
+        miopen_ms = e0.elapsed_time(e1) / 5 * n_units
+    except Exception as e:                                         # pragma: no cover
+        sys.stderr.write("MIOpen dense unit failed: %s\n" % e)
+    head = rows[-1] if cfg != "cfg4" else [r_ for r_ in rows if r_["block"] == 16 and r_["target"] == 0.10][0]
+    if cfg == "cfg5":
+        head = [r_ for r_ in rows if r_["target"] == 0.15][0]
+    elif cfg == "cfg3":
+        head = [r_ for r_ in rows if r_["target"] == 0.10][0]
+    out = {"metric": "sparse_residual_unit_ms", "value": head["step_ms"], "unit": "ms", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["step_ms"], "higher_is_better": False,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "%s: %d sparse bottleneck unit(s) 256->64->64->256 bf16, N=%d H=%d W=%d, %s mask" % (
+               cfg, n_units, N, H, W, kind), "headline_row": head},
+           "rows": rows, "miopen_dense_units_ms": None if miopen_ms is None else round(miopen_ms, 4),
+           "roofline": {"bound": "hbm", "kernel": "bottleneck16_kernel<bf16,256,fused>",
+                        "achieved": head["unit_hbm_GBps_algorithmic"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": round(head["unit_hbm_GBps_algorithmic"] / PEAK_HBM_GBS, 4), "traffic": None}}
+    print(json.dumps(out))
 
 
 def main():
@@ -53,6 +218,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     sb.lib()                                                      # fail loudly if the HIP library is missing
+    if args.workload != "cfg2":
+        return run_units(args)
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 

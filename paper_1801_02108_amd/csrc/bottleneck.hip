@@ -3,11 +3,14 @@
 // folded into weights and bias) share one gather and one scatter-add (Sec. 3.4).  The receptive
 // field of the whole unit is that of its single 3x3, so the input tile is block + 1-pixel halo.
 //
-// One kernel per unit; per 16x16 output sub-tile and workgroup (4 waves, one per SIMD, weights of
-// all three convolutions resident in registers for the life of the workgroup):
+// One kernel per unit; per 16x16 output sub-tile and workgroup (4 waves, one per SIMD).  The
+// weights stay on chip for the life of the workgroup: W2 (the 3x3) in registers, W1 and W3 in LDS
+// in MFMA operand order:
 //   P1  t1 = ReLU(W1 x + b1) on the 18x18 input sub-tile.  x streams from global memory straight
 //       into MFMA operand registers (each element is used by exactly one pixel row of the GEMM, so
-//       staging it in LDS would only add traffic); t1 goes to LDS as bf16/f16.  Positions outside
+//       staging it in LDS would only add traffic); a wave issues the loads of all its pixel blocks
+//       (up to 3 x 16 KB) before the first MFMA, so the whole input tile is in flight at once;
+//       t1 goes to LDS as bf16/f16.  Positions outside
 //       the image are forced to zero: the dense network pads the 3x3's input, i.e. t1, with
 //       zeros, and ReLU(b1) is not zero.
 //   P2  t2 = ReLU(W2 * t1 + b2), the 3x3 as nine shifted reads of the LDS copy of t1 (same scheme
@@ -55,6 +58,11 @@ struct BItem {
     int si, sj, n, by, bx;
 };
 
+// 32 bytes of zeros: lanes whose pixel lies outside the image load from here instead of branching
+// around the load, so every load of a tile is issued back to back.  Deliberately not const: a
+// constant-address-space object would turn the selected pointer, and with it the loads, into flat ones.
+__device__ __align__(16) uint4 g_zero32[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+
 __device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v), 0); }
 
 template <int DT, int C, bool FUSED>
@@ -64,8 +72,11 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NB3 = C / 32;          // 32-channel output blocks of conv3
     constexpr int NBW = (NB3 + 3) / 4;   // ... per wave
     constexpr int NBLK1 = (kBTPx + 31) / 32;   // 11 pixel blocks in P1
+    constexpr int NBPW1 = (NBLK1 + 3) / 4;     // pixel blocks per wave in P1
     __shared__ __align__(16) unsigned char t1s[kBTPx * kPS];
     __shared__ __align__(16) unsigned char t2s[256 * kPS];
+    __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];          // conv1 weights, 32x32x16 operand order
+    __shared__ __align__(16) uint4 w3s[NB3 * 4 * 64];         // conv3 weights, [block of 32 outputs][k-step][lane]
 
     const uint16_t *in = (const uint16_t *)p.in;
     uint16_t *out = (uint16_t *)p.out;
@@ -94,29 +105,29 @@ void bottleneck16_kernel(BneckParams p) {
     const uint32_t items = (uint32_t)min(nact_raw, p.cap) * per_block;
     if (first >= items) return;
 
-    // ---- weights resident in registers
-    uint4 w1r[K1];                       // conv1: this wave's 32 of the 64 mid channels
-    uint4 w2r[36];                       // conv2: 9 taps x 4 k-steps, this wave's 32 output channels
-    uint4 w3r[4][NBW];                   // conv3: 4 k-steps x this wave's output blocks
+    // ---- weights: W2 in registers (this wave's 32 output channels), W1 and W3 in LDS
+    uint4 w2r[36];
     {
-        const uint4 *wp = (const uint4 *)p.w1 + p.w1_off + (size_t)nh * 64 + lane;
-#pragma unroll
-        for (int ks = 0; ks < K1; ++ks) w1r[ks] = wp[(size_t)ks * 128];
-        wp = (const uint4 *)p.w2 + p.w2_off + (size_t)nh * 64 + lane;
+        const uint4 *wp = (const uint4 *)p.w2 + p.w2_off + (size_t)nh * 64 + lane;
 #pragma unroll
         for (int ks = 0; ks < 36; ++ks) w2r[ks] = wp[(size_t)ks * 128];
+        // all loads first, then all LDS stores: one memory latency for both weight sets
+        const uint4 *w1g = (const uint4 *)p.w1 + p.w1_off;       // [ks][nb][lane], one group of 64 outputs
+        const uint4 *w3g = (const uint4 *)p.w3 + p.w3_off;       // [ng][ks][nb][lane] -> [ng*2+nb][ks][lane]
+        constexpr int N1 = K1 * 2 * 64 / 256, N3 = NB3 * 4 * 64 / 256;
+        uint4 t1v[N1], t3v[N3];
 #pragma unroll
-        for (int j = 0; j < NBW; ++j) {
-            const int nbg = wave + 4 * j;            // global 32-channel block of conv3's output
-            if (nbg < NB3) {
-                wp = (const uint4 *)p.w3 + p.w3_off + ((size_t)(nbg >> 1) * 4 * 2 + (nbg & 1)) * 64 + lane;
+        for (int k = 0; k < N1; ++k) t1v[k] = w1g[threadIdx.x + k * 256];
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = wp[(size_t)ks * 128];
-            } else {
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = make_uint4(0, 0, 0, 0);
-            }
+        for (int k = 0; k < N3; ++k) {
+            const int i = threadIdx.x + k * 256;
+            const int ln = i & 63, ks = (i >> 6) & 3, nbg = i >> 8;
+            t3v[k] = w3g[(((size_t)(nbg >> 1) * 4 + ks) * 2 + (nbg & 1)) * 64 + ln];
         }
+#pragma unroll
+        for (int k = 0; k < N1; ++k) w1s[threadIdx.x + k * 256] = t1v[k];
+#pragma unroll
+        for (int k = 0; k < N3; ++k) w3s[threadIdx.x + k * 256] = t3v[k];
     }
     auto load_bias16 = [&](const float *b, int c0) {
         f32x16b v;
@@ -126,8 +137,9 @@ void bottleneck16_kernel(BneckParams p) {
         v[8] = q2.x; v[9] = q2.y; v[10] = q2.z; v[11] = q2.w; v[12] = q3.x; v[13] = q3.y; v[14] = q3.z; v[15] = q3.w;
         return v;
     };
-    const int cm0 = nh * 32 + g * 16;                // this lane's 16 mid channels in P1 / P2
-    const f32x16b bias1 = load_bias16(p.b1, cm0), bias2 = load_bias16(p.b2, cm0);
+    const int cm0 = nh * 32 + g * 16;                // this lane's 16 mid channels in P2
+    const f32x16b bias1[2] = {load_bias16(p.b1, g * 16), load_bias16(p.b1, 32 + g * 16)};   // P1: both halves
+    const f32x16b bias2 = load_bias16(p.b2, cm0);
 
     const long long row_stride = (long long)(FUSED ? p.W : p.tw) * C;    // elements between rows of the input
 
@@ -145,43 +157,105 @@ void bottleneck16_kernel(BneckParams p) {
 
         // ================= P1: t1 = ReLU(W1 x + b1), zero outside the image =================
         {
-            const int mh = wave >> 1;                                    // pixel blocks mh, mh+2, ...
-            uint4 xa[2][K1];
-            auto load_block = [&](int blk, uint4 (&xr)[K1], bool &inside) {
-                const int pi = blk * 32 + m;
+            // wave w takes pixel blocks w, w+4, w+8 (32 pixels each, row-major over the 18x18 tile);
+            // the x operands of all of them are requested before the first MFMA
+            uint4 xa[NBPW1][K1];
+            bool ins[NBPW1];
+            auto load_block = [&](int j) {
+                const int pi = (wave + 4 * j) * 32 + m;
                 const int row = pi / kBT, col = pi - row * kBT;
-                inside = pi < kBTPx && row >= rlo && row < rhi && col >= clo && col < chi;
-                const uint16_t *src = xin + row * row_stride + col * C + g * 8;
+                const bool in_img = pi < kBTPx && row >= rlo && row < rhi && col >= clo && col < chi;
+                ins[j] = in_img;
+                // outside the image: read zeros (stride 0) instead of skipping the load
+                const uint16_t *src = in_img ? xin + row * row_stride + col * C + g * 8 : (const uint16_t *)g_zero32;
+                const int kstep = in_img ? 16 : 0;
+#pragma unroll
+                for (int ks = 0; ks < K1; ++ks) xa[j][ks] = *(const uint4 *)(src + ks * kstep);
+            };
+#pragma unroll
+            for (int j = 0; j < NBPW1; ++j) load_block(j);
+            if (it == first) __syncthreads();                            // W1 / W3 have landed in LDS
+#pragma unroll
+            for (int j = 0; j < NBPW1; ++j) {
+                const int blk = wave + 4 * j;
+                if (blk >= NBLK1) break;
+                f32x16b acc0 = bias1[0], acc1 = bias1[1];
+                // weight fragments come from LDS two k-steps ahead of the MFMAs that use them
+                uint4 af[3][2];
+#pragma unroll
+                for (int pre = 0; pre < 2 && pre < K1; ++pre) {
+                    af[pre][0] = w1s[(pre * 2 + 0) * 64 + lane];
+                    af[pre][1] = w1s[(pre * 2 + 1) * 64 + lane];
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int ks = 0; ks < K1; ++ks) {
-                    xr[ks] = make_uint4(0, 0, 0, 0);
-                    if (inside) xr[ks] = *(const uint4 *)(src + ks * 16);
+                    if (ks + 2 < K1) {
+                        af[(ks + 2) % 3][0] = w1s[((ks + 2) * 2 + 0) * 64 + lane];
+                        af[(ks + 2) % 3][1] = w1s[((ks + 2) * 2 + 1) * 64 + lane];
+                    }
+                    acc0 = mfma32<DT>(af[ks % 3][0], xa[j][ks], acc0);
+                    acc1 = mfma32<DT>(af[ks % 3][1], xa[j][ks], acc1);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-            };
-            bool ins[2];
-            load_block(mh, xa[0], ins[0]);
-#pragma unroll
-            for (int jb = 0; jb < (NBLK1 + 1) / 2; ++jb) {
-                const int blk = mh + 2 * jb;
-                if (blk >= NBLK1) break;
-                if (blk + 2 < NBLK1) load_block(blk + 2, xa[(jb + 1) & 1], ins[(jb + 1) & 1]);
-                f32x16b acc = bias1;
-#pragma unroll
-                for (int ks = 0; ks < K1; ++ks) acc = mfma32<DT>(w1r[ks], xa[jb & 1][ks], acc);
+                const bool inside = ins[j];
                 const int pi = blk * 32 + m;
                 if (pi < kBTPx) {
-                    const bool inside = ins[jb & 1];
-                    uint32_t w[8];
+                    uint32_t w[16];
 #pragma unroll
-                    for (int k = 0; k < 8; ++k)
-                        w[k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc[2 * k])), __int_as_float(relu_bits(acc[2 * k + 1]))) : 0u;
-                    uint4 *d = (uint4 *)(t1s + pi * kPS + cm0 * 2);
+                    for (int k = 0; k < 8; ++k) {
+                        w[k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc0[2 * k])), __int_as_float(relu_bits(acc0[2 * k + 1]))) : 0u;
+                        w[8 + k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc1[2 * k])), __int_as_float(relu_bits(acc1[2 * k + 1]))) : 0u;
+                    }
+                    uint4 *d = (uint4 *)(t1s + pi * kPS + g * 32);
                     d[0] = make_uint4(w[0], w[1], w[2], w[3]);
                     d[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                    d[4] = make_uint4(w[8], w[9], w[10], w[11]);         // +64 B: channels 32..63
+                    d[5] = make_uint4(w[12], w[13], w[14], w[15]);
                 }
             }
         }
         __syncthreads();
+
+        // ---- output addressing of this lane's pixels (pixel block k: rows 2k + prow, column pcol) and,
+        //      for the fused form, the residual x of the whole block: requested here so that its
+        //      latency hides behind the matrix work of P2
+        const int ocol = tx0 + pcol;
+        int rmin = 0, rlim = p.oh;
+        bool col_ok = ocol < p.ow;
+        uint16_t *obase;
+        const uint16_t *rbase = nullptr;
+        long long orow_stride;
+        if (FUSED) {
+            const int oy0 = p.g_out.boffset_h + cur.by * p.g_out.bstride_h;
+            const int gx = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + ocol;
+            col_ok = col_ok && gx >= 0 && gx < p.W;
+            rmin = max(0, -oy0);
+            rlim = min(rlim, p.H - oy0);
+            orow_stride = (long long)p.W * C;
+            obase = out + ((long long)cur.n * p.H + oy0) * orow_stride + (long long)gx * C + g * 16;
+            rbase = in + ((long long)cur.n * p.H + oy0) * orow_stride + (long long)gx * C + g * 16;
+        } else {
+            orow_stride = (long long)p.ow * C;
+            obase = out + (long long)cur.b * p.oh * orow_stride + (long long)ocol * C + g * 16;
+        }
+        bool ok[8];
+        uint4 res[8][NBW][2];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int orow = ty0 + 2 * k + prow;
+            ok[k] = col_ok && orow >= rmin && orow < rlim;
+            if (FUSED) {
+#pragma unroll
+                for (int j = 0; j < NBW; ++j) {
+                    const int nbg = wave + 4 * j;
+                    const bool ld = ok[k] && nbg < NB3;
+                    const uint4 *r4 = ld ? (const uint4 *)(rbase + orow * orow_stride + nbg * 32) : (const uint4 *)g_zero32;
+                    res[k][j][0] = r4[0];
+                    res[k][j][1] = r4[1];
+                }
+            }
+        }
 
         // ================= P2: t2 = ReLU(W2 * t1 + b2) =================
         {
@@ -228,30 +302,13 @@ void bottleneck16_kernel(BneckParams p) {
             // conv3's bias is only live in this phase: re-read it per tile (cache hit) rather than
             // holding 16*NBW registers through P1 and P2
             f32x16b bias3[NBW];
+            uint4 w3r[4][NBW];
 #pragma unroll
             for (int j = 0; j < NBW; ++j) {
-                const int nbg = wave + 4 * j;
-                bias3[j] = load_bias16(p.b3, (nbg < NB3 ? nbg : 0) * 32 + g * 16);
-            }
-            // output addressing of this lane's pixel in a pixel block: rows 2*blk + prow, column pcol
-            const int ocol = tx0 + pcol;
-            int rmin = 0, rlim = p.oh;
-            bool col_ok = ocol < p.ow;
-            uint16_t *obase;
-            const uint16_t *rbase = nullptr;
-            long long orow_stride;
-            if (FUSED) {
-                const int oy0 = p.g_out.boffset_h + cur.by * p.g_out.bstride_h;
-                const int gx = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + ocol;
-                col_ok = col_ok && gx >= 0 && gx < p.W;
-                rmin = max(0, -oy0);
-                rlim = min(rlim, p.H - oy0);
-                orow_stride = (long long)p.W * C;
-                obase = out + ((long long)cur.n * p.H + oy0) * orow_stride + (long long)gx * C + g * 16;
-                rbase = in + ((long long)cur.n * p.H + oy0) * orow_stride + (long long)gx * C + g * 16;
-            } else {
-                orow_stride = (long long)p.ow * C;
-                obase = out + (long long)cur.b * p.oh * orow_stride + (long long)ocol * C + g * 16;
+                const int nbg = min(wave + 4 * j, NB3 - 1);
+                bias3[j] = load_bias16(p.b3, nbg * 32 + g * 16);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];
             }
 #pragma unroll
             for (int bp = 0; bp < 4; ++bp) {                              // pixel blocks 2bp, 2bp+1
@@ -261,30 +318,6 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks)
                         tf[u][ks] = *(const uint4 *)(t2s + ((2 * bp + u) * 32 + m) * kPS + ks * 32 + g * 16);
-                bool ok[2];
-                long long ooff[2];
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int orow = ty0 + (2 * bp + u) * 2 + prow;
-                    ok[u] = col_ok && orow >= rmin && orow < rlim;
-                    ooff[u] = orow * orow_stride;
-                }
-                // residual x for the fused form, fetched before the matrix work
-                uint4 res[2][NBW][2];
-                if (FUSED) {
-#pragma unroll
-                    for (int u = 0; u < 2; ++u)
-#pragma unroll
-                        for (int j = 0; j < NBW; ++j) {
-                            const int nbg = wave + 4 * j;
-                            res[u][j][0] = res[u][j][1] = make_uint4(0, 0, 0, 0);
-                            if (ok[u] && nbg < NB3) {
-                                const uint4 *r4 = (const uint4 *)(rbase + ooff[u] + nbg * 32);
-                                res[u][j][0] = r4[0];
-                                res[u][j][1] = r4[1];
-                            }
-                        }
-                }
                 f32x16b acc[2][NBW];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
@@ -298,20 +331,21 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
                     for (int j = 0; j < NBW; ++j) {
                         const int nbg = wave + 4 * j;
-                        if (!(ok[u] && nbg < NB3)) continue;
+                        const int kblk = 2 * bp + u;
+                        if (!(ok[kblk] && nbg < NB3)) continue;
                         uint32_t w[8];
 #pragma unroll
                         for (int k = 0; k < 8; ++k) {
                             float lo = acc[u][j][2 * k], hi = acc[u][j][2 * k + 1];
                             if (FUSED) {
-                                const uint4 rv = res[u][j][k >> 2];
+                                const uint4 rv = res[kblk][j][k >> 2];
                                 const uint32_t rw = (k & 3) == 0 ? rv.x : (k & 3) == 1 ? rv.y : (k & 3) == 2 ? rv.z : rv.w;
                                 lo += unpack_lo<DT>(rw);
                                 hi += unpack_hi<DT>(rw);
                             }
                             w[k] = pack2<DT>(lo, hi);
                         }
-                        uint4 *d = (uint4 *)(obase + ooff[u] + nbg * 32);
+                        uint4 *d = (uint4 *)(obase + (ty0 + 2 * kblk + prow) * orow_stride + nbg * 32);
                         d[0] = make_uint4(w[0], w[1], w[2], w[3]);
                         d[1] = make_uint4(w[4], w[5], w[6], w[7]);
                     }
