@@ -37,6 +37,11 @@ def parse():
     ap.add_argument("--density", type=float, default=0.10, help="target active-block fraction of the headline run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip sweep, dense and MIOpen comparisons")
+    ap.add_argument("--eager-kernel-timing", action="store_true",
+                    help="time single kernels with eager launches instead of graph replays (use under rocprofv3, whose "
+                         "per-node instrumentation inflates kernels replayed from a graph)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy: a known-size reference for scaling HBM byte counters")
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"],
                     help="cfg2 (default) is the headline single 3x3 conv; cfg3/4/5 are the residual-unit workloads")
     return ap.parse_args()
@@ -218,6 +223,12 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     sb.lib()                                                      # fail loudly if the HIP library is missing
+    if args.calibration_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.workload != "cfg2":
         return run_units(args)
     torch.cuda.set_device(0)
@@ -330,6 +341,8 @@ def main():
     eager_ms = time_steps(lambda: step_fused(mask_d), args.steps, args.warmup)
     graph_ok, inner = True, 1
     try:
+        if args.eager_kernel_timing:
+            raise RuntimeError("eager timing requested")
         ms_per_step, inner = time_step_graph(lambda: step_fused(mask_d), args.steps, args.warmup)
         single_graph_ms = time_steps(graph_of(lambda: step_fused(mask_d), 1).replay, 100, 10)
     except Exception as e:                                         # pragma: no cover
@@ -338,7 +351,7 @@ def main():
         ms_per_step = single_graph_ms = eager_ms
 
     # per-kernel device time: graphs of 20 back-to-back launches of one entry point, HIP events
-    tk = time_kernel if graph_ok else (lambda fn: time_events(fn, 200))
+    tk = time_kernel if (graph_ok and not args.eager_kernel_timing) else (lambda fn: time_events(fn, 200))
     conv_ms = tk(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y))
     reduce_ms = tk(lambda: sb.reduce_mask(mask_d, g_in, sb.POOL_AVG, 0.0, idx, cnt, ws))
     count_active(mask_np)                                          # leave idx/cnt consistent

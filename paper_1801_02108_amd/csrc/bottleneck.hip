@@ -77,6 +77,7 @@ void bottleneck16_kernel(BneckParams p) {
     __shared__ __align__(16) unsigned char t2s[256 * kPS];
     __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];          // conv1 weights, 32x32x16 operand order
     __shared__ __align__(16) uint4 w3s[NB3 * 4 * 64];         // conv3 weights, [block of 32 outputs][k-step][lane]
+    __shared__ __align__(16) float bias_s[2 * kCm + C];       // b1 | b2 | b3: accumulators start from these
 
     const uint16_t *in = (const uint16_t *)p.in;
     uint16_t *out = (uint16_t *)p.out;
@@ -128,18 +129,19 @@ void bottleneck16_kernel(BneckParams p) {
         for (int k = 0; k < N1; ++k) w1s[threadIdx.x + k * 256] = t1v[k];
 #pragma unroll
         for (int k = 0; k < N3; ++k) w3s[threadIdx.x + k * 256] = t3v[k];
+        for (int i = threadIdx.x; i < 2 * kCm + C; i += 256)
+            bias_s[i] = i < kCm ? p.b1[i] : i < 2 * kCm ? p.b2[i - kCm] : p.b3[i - 2 * kCm];
     }
-    auto load_bias16 = [&](const float *b, int c0) {
+    // 16 consecutive biases from LDS as an accumulator-shaped vector
+    auto load_bias16 = [&](int i0) {
         f32x16b v;
-        const float4 q0 = *(const float4 *)(b + c0), q1 = *(const float4 *)(b + c0 + 4);
-        const float4 q2 = *(const float4 *)(b + c0 + 8), q3 = *(const float4 *)(b + c0 + 12);
+        const float4 q0 = *(const float4 *)(bias_s + i0), q1 = *(const float4 *)(bias_s + i0 + 4);
+        const float4 q2 = *(const float4 *)(bias_s + i0 + 8), q3 = *(const float4 *)(bias_s + i0 + 12);
         v[0] = q0.x; v[1] = q0.y; v[2] = q0.z; v[3] = q0.w; v[4] = q1.x; v[5] = q1.y; v[6] = q1.z; v[7] = q1.w;
         v[8] = q2.x; v[9] = q2.y; v[10] = q2.z; v[11] = q2.w; v[12] = q3.x; v[13] = q3.y; v[14] = q3.z; v[15] = q3.w;
         return v;
     };
     const int cm0 = nh * 32 + g * 16;                // this lane's 16 mid channels in P2
-    const f32x16b bias1[2] = {load_bias16(p.b1, g * 16), load_bias16(p.b1, 32 + g * 16)};   // P1: both halves
-    const f32x16b bias2 = load_bias16(p.b2, cm0);
 
     const long long row_stride = (long long)(FUSED ? p.W : p.tw) * C;    // elements between rows of the input
 
@@ -174,12 +176,13 @@ void bottleneck16_kernel(BneckParams p) {
             };
 #pragma unroll
             for (int j = 0; j < NBPW1; ++j) load_block(j);
+            __builtin_amdgcn_sched_barrier(0);                           // all loads issued before any use
             if (it == first) __syncthreads();                            // W1 / W3 have landed in LDS
 #pragma unroll
             for (int j = 0; j < NBPW1; ++j) {
                 const int blk = wave + 4 * j;
                 if (blk >= NBLK1) break;
-                f32x16b acc0 = bias1[0], acc1 = bias1[1];
+                f32x16b acc0 = load_bias16(g * 16), acc1 = load_bias16(32 + g * 16);
                 // weight fragments come from LDS two k-steps ahead of the MFMAs that use them
                 uint4 af[3][2];
 #pragma unroll
@@ -257,9 +260,11 @@ void bottleneck16_kernel(BneckParams p) {
             }
         }
 
+        __builtin_amdgcn_sched_barrier(0);                               // residual loads stay ahead of P2
         // ================= P2: t2 = ReLU(W2 * t1 + b2) =================
         {
             f32x16b acc[4];
+            const f32x16b bias2 = load_bias16(kCm + cm0);
             const unsigned char *L = t1s + ((rh * 8 + prow) * kBT + pcol) * kPS + g * 16;
             uint4 xf[2][9];
 #pragma unroll
@@ -306,7 +311,7 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
             for (int j = 0; j < NBW; ++j) {
                 const int nbg = min(wave + 4 * j, NB3 - 1);
-                bias3[j] = load_bias16(p.b3, nbg * 32 + g * 16);
+                bias3[j] = load_bias16(2 * kCm + nbg * 32 + g * 16);
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];
             }

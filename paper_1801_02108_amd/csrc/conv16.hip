@@ -30,11 +30,6 @@ struct Sub16 {
     FastDiv div_sub, div_subw;
 };
 
-// 16 bytes of zeros: staging lanes whose pixel lies outside the image load from here instead of
-// branching around the load, so all loads of a tile are issued back to back (not const: see the
-// note on address spaces in bottleneck.hip).
-__device__ __align__(16) uint4 g_zero16 = {0u, 0u, 0u, 0u};
-
 // one work item: a 16x16 output sub-tile of an active block
 struct Item16 {
     uint32_t b;         // position in the index list
@@ -153,8 +148,11 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
             const int row = rowcol[k] & 0xff, col = rowcol[k] >> 8;
-            const bool ok = row >= rlo && row < rhi && col >= clo && col < chi;
-            stage[k] = *(ok ? (const uint4 *)(base + goff[k]) : &g_zero16);
+            // A predicated load on purpose: written as an unconditional load from a selected address
+            // (tile or a zero buffer) the compiler sinks every load down to its LDS store and a tile
+            // costs NV memory round trips instead of one.
+            stage[k] = make_uint4(0, 0, 0, 0);
+            if (row >= rlo && row < rhi && col >= clo && col < chi) stage[k] = *(const uint4 *)(base + goff[k]);
         }
     };
     auto stash = [&](int buf) {

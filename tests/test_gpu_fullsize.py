@@ -1,0 +1,165 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times (device-side count, cap = all blocks, fused kernels).  The oracle cannot run these sizes
+whole in seconds, so it computes a seeded sample of active tiles one by one (every image-border
+tile among the active ones is in the sample); properties that hold at any size cover the rest:
+the index list is checked whole and pixels of inactive blocks must be bit-identical."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_1801_02108_amd as sb
+from paper_1801_02108_amd import inputs as gen
+from util import CONV_TOL, assert_close, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def step(msg):
+    print("[case] " + msg, flush=True)
+
+
+def ogeom(g):
+    return orc.Geom(*g.astuple())
+
+
+def sample_tiles(idx, g, r, n_interior=12):
+    """Rows of idx to check: all active tiles touching the image border plus a random few others."""
+    border = (idx[:, 1] == 0) | (idx[:, 2] == 0) | (idx[:, 1] == g.bcount_h - 1) | (idx[:, 2] == g.bcount_w - 1)
+    b = np.flatnonzero(border)
+    if len(b) > 24:
+        b = r.choice(b, 24, replace=False)
+    rest = np.flatnonzero(~border)
+    pick = r.choice(rest, min(n_interior, len(rest)), replace=False) if len(rest) else rest
+    return np.sort(np.concatenate([b, pick]))
+
+
+def blocks_of(y_np, idx_rows, g_out):
+    """Stack the output blocks of the listed tiles out of a full [N,H,W,C] array (clipped blocks padded with 0)."""
+    out = np.zeros((len(idx_rows), g_out.bsize_h, g_out.bsize_w, y_np.shape[-1]))
+    for k, (n, by, bx) in enumerate(idx_rows):
+        y0, x0 = by * g_out.bstride_h, bx * g_out.bstride_w
+        blk = y_np[n, y0:y0 + g_out.bsize_h, x0:x0 + g_out.bsize_w]
+        out[k, :blk.shape[0], :blk.shape[1]] = blk
+    return out
+
+
+def road_mask(r, H, W, g_in, N, target):
+    fields = gen.road_band_fields(r, H, W, 3)
+    og = ogeom(g_in)
+    total = N * g_in.bcount_h * g_in.bcount_w
+    m, _, frac = gen.calibrate(lambda s: np.repeat(gen.road_band_mask(fields, s), N, axis=0),
+                               lambda mm: len(orc.reduce_mask(mm, og)), total, target, 0.0, 12.0)
+    return m, frac
+
+
+def test_config2_full_size_sampled():
+    """800 x 704 x 64 -> 64, bf16, 16 x 16 blocks, road-band mask at 10 % active blocks."""
+    step("config 2 full size")
+    r = gen.rng_for(2)
+    N, H, W, C, K, bo = 1, 800, 704, 64, 64, 16
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, 1, bo)
+    x = gen.activations(r, (N, H, W, C), "bf16")
+    w = gen.conv_weights(r, 3, 3, C, K, "bf16")
+    b = gen.bias_vector(r, K)
+    mask, frac = road_mask(r, H, W, g_in, N, 0.10)
+    assert abs(frac - 0.10) < 0.01
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in, sb.POOL_AVG, 0.0)
+    idx = orc.reduce_mask(mask, ogeom(g_in), orc.POOL_AVG, 0.0)
+    n = sb.read_count(d_cnt, d_idx.shape[0])
+    assert n == len(idx) and np.array_equal(d_idx[:n].cpu().numpy(), idx)          # whole index list
+    y0 = gen.activations(r, (N, Ho, Wo, K), "bf16")
+    y = to_dev(y0, "bf16")
+    sb.sparse_conv(to_dev(x, "bf16"), d_idx, d_cnt, g_in, g_out, sb.pack_weights(to_dev(w, "bf16")),
+                   torch.from_numpy(b).cuda(), y)
+    got = to_host(y)
+    bm = orc.block_mask(idx, ogeom(g_out), N, Ho, Wo)
+    assert np.array_equal(got[~bm], y0[~bm])                                        # inactive pixels untouched
+    rows = sample_tiles(idx, g_in, r)
+    ref = orc.conv_valid(orc.gather(x, idx[rows], ogeom(g_in)), w, b)
+    assert_close(blocks_of(got, idx[rows], g_out), ref, CONV_TOL["bf16"], "config 2 sampled tiles")
+
+
+@pytest.mark.parametrize("target", [0.10, 0.30])
+def test_config3_full_size_sampled(target):
+    """Bottleneck 256 -> 64 -> 64 -> 256 on 400 x 352, bf16, 16 x 16 blocks, road-band mask."""
+    step("config 3 full size target=%s" % target)
+    r = gen.rng_for(3, int(target * 100))
+    N, H, W, C, bo = 1, 400, 352, 256, 16
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    x = gen.activations(r, (N, H, W, C), "bf16")
+    ws = gen.bottleneck_weights(r, C, 64, "bf16")
+    mask, frac = road_mask(r, H, W, g_in, N, target)
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in, sb.POOL_AVG, 0.0)
+    idx = orc.reduce_mask(mask, ogeom(g_in), orc.POOL_AVG, 0.0)
+    n = sb.read_count(d_cnt, d_idx.shape[0])
+    assert n == len(idx) and np.array_equal(d_idx[:n].cpu().numpy(), idx)
+    dws = (sb.pack_weights(to_dev(ws[0], "bf16")), torch.from_numpy(ws[1]).cuda(), sb.pack_weights(to_dev(ws[2], "bf16")),
+           torch.from_numpy(ws[3]).cuda(), sb.pack_weights(to_dev(ws[4], "bf16")), torch.from_numpy(ws[5]).cuda())
+    dx = to_dev(x, "bf16")
+    y = dx.clone()
+    sb.sparse_bottleneck(dx, d_idx, d_cnt, g_in, g_out, dws, y)
+    got = to_host(y)
+    bm = orc.block_mask(idx, ogeom(g_out), N, H, W)
+    assert np.array_equal(got[~bm], x[~bm])
+    rows = sample_tiles(idx, g_in, r, 6)
+    t3 = orc.bottleneck_on_tiles(orc.gather(x, idx[rows], ogeom(g_in)), idx[rows], ogeom(g_in), H, W, *ws)
+    ref = blocks_of(x.astype(np.float64), idx[rows], g_out) + t3
+    assert_close(blocks_of(got, idx[rows], g_out), ref, CONV_TOL["bf16"], "config 3 sampled tiles")
+
+
+def test_stack_shape_batch_of_samples_sampled():
+    """The shape of the batched configurations at a size the test can hold: N = 4 samples of
+    800 x 704 x 256 with a per-sample low-resolution mask (about 15 % active blocks), two units
+    sharing one index list and alternating two buffers."""
+    step("batched stack, sampled")
+    r = gen.rng_for(5)
+    N, H, W, C, bo = 4, 800, 704, 256, 16
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    dev = torch.device("cuda:0")
+    tg = torch.Generator(device=dev)
+    tg.manual_seed(1234)
+    a = torch.randn((N, H, W, C), generator=tg, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    b = a.clone()
+    x0 = a.clone()
+    logits = gen.smooth_noise(r, N, H // 8, W // 8, 2.0)
+    og = ogeom(g_in)
+    total = N * g_in.bcount_h * g_in.bcount_w
+    mask, thr, frac = gen.calibrate(lambda t: gen.lowres_mask(logits, t), lambda mm: len(orc.reduce_mask(mm, og)), total,
+                                    0.15, -4.0, 4.0, increasing=False)
+    assert abs(frac - 0.15) < 0.01
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).to(dev), g_in)
+    idx = orc.reduce_mask(mask, og)
+    n = sb.read_count(d_cnt, d_idx.shape[0])
+    assert n == len(idx) and np.array_equal(d_idx[:n].cpu().numpy(), idx)
+    units = [gen.bottleneck_weights(r, C, 64, "bf16") for _ in range(2)]
+    for ws in units:
+        dws = (sb.pack_weights(to_dev(ws[0], "bf16")), torch.from_numpy(ws[1]).to(dev), sb.pack_weights(to_dev(ws[2], "bf16")),
+               torch.from_numpy(ws[3]).to(dev), sb.pack_weights(to_dev(ws[4], "bf16")), torch.from_numpy(ws[5]).to(dev))
+        sb.sparse_bottleneck(a, d_idx, d_cnt, g_in, g_out, dws, b)
+        a, b = b, a
+    # inactive pixels never change (checked on the device: the tensors are large)
+    bm = torch.from_numpy(orc.block_mask(idx, ogeom(g_out), N, H, W)).to(dev)
+    assert torch.equal(a[~bm], x0[~bm])
+    # Sampled tiles.  The second unit reads the first unit's output on the tile's halo, so the oracle runs
+    # both units on a window of 3 x 3 blocks around each sampled block (clipped at the image edge), treated
+    # as an image of its own.  The window's artificial border is a whole block (16 px) away from the centre
+    # block, while two stacked units only reach 2 px, so the centre block of the window result is exact.
+    rows = r.choice(len(idx), 8, replace=False)
+    for k in rows:
+        n_, by, bx = (int(v) for v in idx[k])
+        gy_lo, gx_lo = max(by - 1, 0) * bo, max(bx - 1, 0) * bo
+        gy_hi, gx_hi = min((by + 2) * bo, H), min((bx + 2) * bo, W)
+        win = x0[n_, gy_lo:gy_hi, gx_lo:gx_hi].to(torch.float64).cpu().numpy()[None]
+        wg_in, wg_out, _, _ = orc.geometry(win.shape[1], win.shape[2], 3, 1, bo)
+        sel = idx[(idx[:, 0] == n_) & (idx[:, 1] * bo >= gy_lo) & (idx[:, 1] * bo < gy_hi) &
+                  (idx[:, 2] * bo >= gx_lo) & (idx[:, 2] * bo < gx_hi)].copy()
+        sel[:, 0] = 0
+        sel[:, 1] -= gy_lo // bo
+        sel[:, 2] -= gx_lo // bo
+        ref = win
+        for ws in units:
+            ref = orc.sparse_bottleneck_tiled(ref, sel, wg_in, wg_out, *ws)
+        cy, cx = by * bo - gy_lo, bx * bo - gx_lo
+        got = a[n_, by * bo:by * bo + bo, bx * bo:bx * bo + bo].to(torch.float64).cpu().numpy()
+        assert_close(got, ref[0, cy:cy + bo, cx:cx + bo], 3e-2, "stack tile %d" % k)
