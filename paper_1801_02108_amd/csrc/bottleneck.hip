@@ -4,12 +4,13 @@
 // field of the whole unit is that of its single 3x3, so the input tile is block + 1-pixel halo.
 //
 // One kernel per unit; per 16x16 output sub-tile and workgroup (4 waves, one per SIMD).  The
-// weights stay on chip for the life of the workgroup: W2 (the 3x3) in registers, W1 and W3 in LDS
-// in MFMA operand order:
-//   P1  t1 = ReLU(W1 x + b1) on the 18x18 input sub-tile.  x streams from global memory straight
-//       into MFMA operand registers (each element is used by exactly one pixel row of the GEMM, so
-//       staging it in LDS would only add traffic); a wave issues the loads of all its pixel blocks
-//       (up to 3 x 16 KB) before the first MFMA, so the whole input tile is in flight at once;
+// 1x1 weights W1, W3 and the biases stay in LDS for the life of the workgroup (MFMA operand order);
+// W2 (the 3x3, 72 KB) is re-read from L2 into registers once per tile while P1 runs:
+//   P1  t1 = ReLU(W1 x + b1) on the 18x18 input sub-tile.  x passes through LDS in 64-channel
+//       chunks: eight lanes read one pixel's 128 contiguous bytes (8 full cache lines per wave
+//       instruction; loading the 32x32x16 B operand directly touches 32 lines for the same 1 KB and
+//       runs at the L1 tag rate), two chunks are in flight in registers, and the first two chunks of
+//       the NEXT tile are requested before P3 so that HBM stays busy during the matrix phases;
 //       t1 goes to LDS as bf16/f16.  Positions outside
 //       the image are forced to zero: the dense network pads the 3x3's input, i.e. t1, with
 //       zeros, and ReLU(b1) is not zero.
@@ -18,6 +19,8 @@
 //   P3  t3 = W3 t2 + b3; fused form: y = x + t3 on the block's pixels (the residual x is re-read
 //       from global memory, where it was fetched moments ago for P1); on-tiles form: t3 is stored.
 // HBM traffic per sub-tile is the input tile once and the output block once.
+#include <type_traits>
+
 #include "conv_common.h"
 
 namespace sbnet {
@@ -58,9 +61,9 @@ struct BItem {
     int si, sj, n, by, bx;
 };
 
-// 32 bytes of zeros: lanes whose pixel lies outside the image load from here instead of branching
-// around the load, so every load of a tile is issued back to back.  Deliberately not const: a
-// constant-address-space object would turn the selected pointer, and with it the loads, into flat ones.
+// 32 bytes of zeros for lanes whose pixel lies outside the image: they load from here, so the loads of a tile
+// need no branches (straight-line code keeps the compiler's wait counts exact).  Deliberately not const: a
+// constant-address-space object would turn the selected pointers, and with them the loads, into flat ones.
 __device__ __align__(16) uint4 g_zero32[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
 
 __device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v), 0); }
@@ -68,20 +71,23 @@ __device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v)
 template <int DT, int C, bool FUSED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void bottleneck16_kernel(BneckParams p) {
-    constexpr int K1 = C / 16;           // k-steps of conv1
-    constexpr int NB3 = C / 32;          // 32-channel output blocks of conv3
-    constexpr int NBW = (NB3 + 3) / 4;   // ... per wave
+    constexpr int K1 = C / 16;                 // k-steps of conv1
+    constexpr int NCH = C / 64;                // 64-channel chunks of the input tile
+    constexpr int NB3 = C / 32;                // 32-channel output blocks of conv3
+    constexpr int NBW = (NB3 + 3) / 4;         // ... per wave
     constexpr int NBLK1 = (kBTPx + 31) / 32;   // 11 pixel blocks in P1
-    constexpr int NBPW1 = (NBLK1 + 3) / 4;     // pixel blocks per wave in P1
+    constexpr int NBPW1 = (NBLK1 + 3) / 4;     // ... per wave
+    constexpr int NVX = (kBTPx * 8 + 255) / 256;   // 16-byte staging vectors per thread and chunk
     __shared__ __align__(16) unsigned char t1s[kBTPx * kPS];
-    __shared__ __align__(16) unsigned char t2s[256 * kPS];
-    __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];          // conv1 weights, 32x32x16 operand order
-    __shared__ __align__(16) uint4 w3s[NB3 * 4 * 64];         // conv3 weights, [block of 32 outputs][k-step][lane]
-    __shared__ __align__(16) float bias_s[2 * kCm + C];       // b1 | b2 | b3: accumulators start from these
+    __shared__ __align__(16) unsigned char xs[kBTPx * kPS];      // one 64-channel chunk of x in P1, t2 afterwards
+    __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];             // conv1 weights, 32x32x16 operand order
+    __shared__ __align__(16) uint4 w3s[NB3 * 4 * 64];            // conv3 weights, [block of 32 outputs][k-step][lane]
+    __shared__ __align__(16) float bias_s[2 * kCm + C];          // b1 | b2 | b3: accumulators start from these
 
     const uint16_t *in = (const uint16_t *)p.in;
     uint16_t *out = (uint16_t *)p.out;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: lives in a scalar register
     const int g = lane >> 5, m = lane & 31;
     const int prow = m >> 4, pcol = m & 15;
     const int rh = wave >> 1, nh = wave & 1;
@@ -89,7 +95,10 @@ void bottleneck16_kernel(BneckParams p) {
     const uint32_t G = gridDim.x;
     const uint32_t first = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
 
-    auto decode = [&](uint32_t it) {
+    // Addressing convention of this kernel: a wave-uniform 64-bit base plus an unsigned 32-bit per-lane element
+    // offset, so that loads and stores use one scalar base and one VGPR instead of a 64-bit VGPR pair per access
+    // (36 + 22 + 32 such pairs would otherwise be kept, or spilled, across the tile loop).
+    auto decode = [&](uint32_t it) __attribute__((always_inline)) {
         BItem c;
         c.b = fdiv(it, p.div_sub);
         const uint32_t sidx = it - c.b * per_block;
@@ -106,13 +115,68 @@ void bottleneck16_kernel(BneckParams p) {
     const uint32_t items = (uint32_t)min(nact_raw, p.cap) * per_block;
     if (first >= items) return;
 
-    // ---- weights: W2 in registers (this wave's 32 output channels), W1 and W3 in LDS
-    uint4 w2r[36];
-    {
-        const uint4 *wp = (const uint4 *)p.w2 + p.w2_off + (size_t)nh * 64 + lane;
+    // ---- geometry of a sub-tile: origin in memory and the rows / columns that exist and lie inside the image
+    struct TileGeo {
+        const uint16_t *xin;
+        int rlo, rhi, clo, chi, ty0, tx0;
+    };
+    const int row_stride = (FUSED ? p.W : p.tw) * C;                      // elements between rows of the input
+    auto geometry_of = [&](const BItem &c) __attribute__((always_inline)) {
+        TileGeo t;
+        t.ty0 = c.si * 16;
+        t.tx0 = c.sj * 16;
+        const int gy0 = p.g_in.boffset_h + c.by * p.g_in.bstride_h + t.ty0;   // sub-tile origin in image coordinates
+        const int gx0 = p.g_in.boffset_w + c.bx * p.g_in.bstride_w + t.tx0;
+        t.rlo = max(0, -gy0);
+        t.rhi = min(min(kBT, p.th - t.ty0), p.H - gy0);
+        t.clo = max(0, -gx0);
+        t.chi = min(min(kBT, p.tw - t.tx0), p.W - gx0);
+        if (FUSED) t.xin = in + ((long long)c.n * p.H + gy0) * row_stride + (long long)gx0 * C;
+        else t.xin = in + ((long long)c.b * p.th + t.ty0) * row_stride + (long long)t.tx0 * C;
+        return t;
+    };
+
+    // ---- staging of one 64-channel chunk: vector v = tid + 256 k covers pixel v / 8, channels (v % 8) * 8 .. + 8.
+    //      Eight neighbouring lanes read one pixel's 128 contiguous bytes, so a wave instruction touches 8 full
+    //      cache lines.  Offsets are recomputed per use: keeping them would cost 2 registers per vector.
+    uint4 sx0[NVX], sx1[NVX];                                             // two chunks in flight (slot 0 / slot 1)
+    auto fetch_chunk = [&](const TileGeo &t, int chunk, auto slot_tag) __attribute__((always_inline)) {
+        constexpr int slot = decltype(slot_tag)::value;
+        int tid = (int)threadIdx.x;
+        asm volatile("" : "+v"(tid));     // opaque: otherwise the per-vector offsets are hoisted out of the tile loop and spilled
 #pragma unroll
-        for (int ks = 0; ks < 36; ++ks) w2r[ks] = wp[(size_t)ks * 128];
-        // all loads first, then all LDS stores: one memory latency for both weight sets
+        for (int k = 0; k < NVX; ++k) {
+            const int v = tid + k * 256;
+            const int px = v >> 3, c8 = v & 7;
+            const int row = px / kBT, col = px - row * kBT;
+            const uint32_t off = (uint32_t)(row * row_stride + col * C + c8 * 8 + chunk * 64);
+            const bool ok = v < kBTPx * 8 && row >= t.rlo && row < t.rhi && col >= t.clo && col < t.chi;
+            // no branch: positions outside the image (and the unused tail of the last vector) read zeros
+            const uint4 val = *(ok ? (const uint4 *)(t.xin + off) : (const uint4 *)g_zero32);
+            if (slot == 0) sx0[k] = val;
+            else sx1[k] = val;
+        }
+        __builtin_amdgcn_sched_barrier(0);                                // all loads issued here, in this order
+    };
+    auto stash_chunk = [&](auto slot_tag) __attribute__((always_inline)) {
+        constexpr int slot = decltype(slot_tag)::value;
+#pragma unroll
+        for (int k = 0; k < NVX; ++k) {
+            const int v = (int)threadIdx.x + k * 256;
+            // the tail beyond the last pixel goes to the 16 pad bytes of the last pixel: no branch
+            const int dst = v < kBTPx * 8 ? (v >> 3) * kPS + (v & 7) * 16 : (kBTPx - 1) * kPS + kCm * 2;
+            *(uint4 *)(xs + dst) = slot == 0 ? sx0[k] : sx1[k];
+        }
+    };
+
+    TileGeo geo = geometry_of(cur);
+    using Slot0 = std::integral_constant<int, 0>;
+    using Slot1 = std::integral_constant<int, 1>;
+    fetch_chunk(geo, 0, Slot0{});
+    if (NCH > 1) fetch_chunk(geo, 1, Slot1{});
+
+    // ---- W1, W3 and the biases go to LDS once per workgroup (all loads first, then all LDS stores)
+    {
         const uint4 *w1g = (const uint4 *)p.w1 + p.w1_off;       // [ks][nb][lane], one group of 64 outputs
         const uint4 *w3g = (const uint4 *)p.w3 + p.w3_off;       // [ng][ks][nb][lane] -> [ng*2+nb][ks][lane]
         constexpr int N1 = K1 * 2 * 64 / 256, N3 = NB3 * 4 * 64 / 256;
@@ -133,7 +197,7 @@ void bottleneck16_kernel(BneckParams p) {
             bias_s[i] = i < kCm ? p.b1[i] : i < 2 * kCm ? p.b2[i - kCm] : p.b3[i - 2 * kCm];
     }
     // 16 consecutive biases from LDS as an accumulator-shaped vector
-    auto load_bias16 = [&](int i0) {
+    auto load_bias16 = [&](int i0) __attribute__((always_inline)) {
         f32x16b v;
         const float4 q0 = *(const float4 *)(bias_s + i0), q1 = *(const float4 *)(bias_s + i0 + 4);
         const float4 q2 = *(const float4 *)(bias_s + i0 + 8), q3 = *(const float4 *)(bias_s + i0 + 12);
@@ -142,126 +206,143 @@ void bottleneck16_kernel(BneckParams p) {
         return v;
     };
     const int cm0 = nh * 32 + g * 16;                // this lane's 16 mid channels in P2
-
-    const long long row_stride = (long long)(FUSED ? p.W : p.tw) * C;    // elements between rows of the input
+    __syncthreads();                                 // weights and biases visible to every wave
 
     for (uint32_t it = first; it < items; it += G) {
-        // geometry of this sub-tile
-        const int ty0 = cur.si * 16, tx0 = cur.sj * 16;                  // sub-tile origin inside the tile
-        const int gy0 = p.g_in.boffset_h + cur.by * p.g_in.bstride_h + ty0;   // ... in image coordinates
-        const int gx0 = p.g_in.boffset_w + cur.bx * p.g_in.bstride_w + tx0;
-        // rows / columns of the sub-tile that exist in the tile and lie inside the image
-        const int rlo = max(0, -gy0), rhi = min(min(kBT, p.th - ty0), p.H - gy0);
-        const int clo = max(0, -gx0), chi = min(min(kBT, p.tw - tx0), p.W - gx0);
-        const uint16_t *xin;
-        if (FUSED) xin = in + ((long long)cur.n * p.H + gy0) * row_stride + (long long)gx0 * C;
-        else xin = in + ((long long)cur.b * p.th + ty0) * row_stride + (long long)tx0 * C;
+        uint4 w2r[36];     // conv2's weights for this tile, requested during the last chunk of P1 (see there)
 
         // ================= P1: t1 = ReLU(W1 x + b1), zero outside the image =================
+        // x passes through LDS in 64-channel chunks: coalesced global loads -> registers -> xs -> MFMA B operands.
+        // Wave w owns pixel blocks w, w+4, w+8 (32 pixels each, row-major over the 18x18 tile) and all 64 outputs.
         {
-            // wave w takes pixel blocks w, w+4, w+8 (32 pixels each, row-major over the 18x18 tile);
-            // the x operands of all of them are requested before the first MFMA
-            uint4 xa[NBPW1][K1];
-            bool ins[NBPW1];
-            auto load_block = [&](int j) {
-                const int pi = (wave + 4 * j) * 32 + m;
-                const int row = pi / kBT, col = pi - row * kBT;
-                const bool in_img = pi < kBTPx && row >= rlo && row < rhi && col >= clo && col < chi;
-                ins[j] = in_img;
-                // outside the image: read zeros (stride 0) instead of skipping the load
-                const uint16_t *src = in_img ? xin + row * row_stride + col * C + g * 8 : (const uint16_t *)g_zero32;
-                const int kstep = in_img ? 16 : 0;
-#pragma unroll
-                for (int ks = 0; ks < K1; ++ks) xa[j][ks] = *(const uint4 *)(src + ks * kstep);
-            };
-#pragma unroll
-            for (int j = 0; j < NBPW1; ++j) load_block(j);
-            __builtin_amdgcn_sched_barrier(0);                           // all loads issued before any use
-            if (it == first) __syncthreads();                            // W1 / W3 have landed in LDS
+            f32x16b acc[NBPW1][2];
 #pragma unroll
             for (int j = 0; j < NBPW1; ++j) {
-                const int blk = wave + 4 * j;
-                if (blk >= NBLK1) break;
-                f32x16b acc0 = load_bias16(g * 16), acc1 = load_bias16(32 + g * 16);
-                // weight fragments come from LDS two k-steps ahead of the MFMAs that use them
-                uint4 af[3][2];
+                acc[j][0] = load_bias16(g * 16);
+                acc[j][1] = load_bias16(32 + g * 16);
+            }
+            int boff[NBPW1];                                             // LDS byte offset of this lane's pixel
 #pragma unroll
-                for (int pre = 0; pre < 2 && pre < K1; ++pre) {
-                    af[pre][0] = w1s[(pre * 2 + 0) * 64 + lane];
-                    af[pre][1] = w1s[(pre * 2 + 1) * 64 + lane];
+            for (int j = 0; j < NBPW1; ++j) boff[j] = min((wave + 4 * j) * 32 + m, kBTPx - 1) * kPS + g * 16;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                if (c & 1) stash_chunk(Slot1{});
+                else stash_chunk(Slot0{});
+                __syncthreads();                                         // chunk c visible
+                if (c + 2 < NCH) {
+                    if (c & 1) fetch_chunk(geo, c + 2, Slot1{});
+                    else fetch_chunk(geo, c + 2, Slot0{});
                 }
+                if (c == NCH - 1) {
+                    // conv2's weights (this wave's 32 output channels) come from L2 while the last chunk and the
+                    // t1 epilogue run.  They are not kept across tiles: the registers hold the next tile's input
+                    // during P3.  Requested only now so that no input chunk is queued behind them.
+                    const uint4 *wp = (const uint4 *)p.w2 + p.w2_off + (size_t)nh * 64;      // wave-uniform
+                    asm volatile("" : "+s"(wp));      // opaque per iteration: keeps the loads inside the tile loop
+#pragma unroll
+                    for (int ks = 0; ks < 36; ++ks) w2r[ks] = (wp + ks * 128)[(uint32_t)lane];
+                }
+                // fragments of k-step k4+1 are read from LDS while the MFMAs of k-step k4 run
+                uint4 af[2][2], bf[2][NBPW1];
+                af[0][0] = w1s[((c * 4) * 2 + 0) * 64 + lane];
+                af[0][1] = w1s[((c * 4) * 2 + 1) * 64 + lane];
+#pragma unroll
+                for (int j = 0; j < NBPW1; ++j) bf[0][j] = *(const uint4 *)(xs + boff[j]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int ks = 0; ks < K1; ++ks) {
-                    if (ks + 2 < K1) {
-                        af[(ks + 2) % 3][0] = w1s[((ks + 2) * 2 + 0) * 64 + lane];
-                        af[(ks + 2) % 3][1] = w1s[((ks + 2) * 2 + 1) * 64 + lane];
+                for (int k4 = 0; k4 < 4; ++k4) {
+                    if (k4 + 1 < 4) {
+                        af[(k4 + 1) & 1][0] = w1s[((c * 4 + k4 + 1) * 2 + 0) * 64 + lane];
+                        af[(k4 + 1) & 1][1] = w1s[((c * 4 + k4 + 1) * 2 + 1) * 64 + lane];
+#pragma unroll
+                        for (int j = 0; j < NBPW1; ++j) bf[(k4 + 1) & 1][j] = *(const uint4 *)(xs + boff[j] + (k4 + 1) * 32);
                     }
-                    acc0 = mfma32<DT>(af[ks % 3][0], xa[j][ks], acc0);
-                    acc1 = mfma32<DT>(af[ks % 3][1], xa[j][ks], acc1);
+#pragma unroll
+                    for (int j = 0; j < NBPW1; ++j) {
+                        // (wave 3's third block does not exist: it recomputes pixel 323 and the result is dropped;
+                        //  a branch here would cost a copy of every accumulator per step)
+                        acc[j][0] = mfma32<DT>(af[k4 & 1][0], bf[k4 & 1][j], acc[j][0]);
+                        acc[j][1] = mfma32<DT>(af[k4 & 1][1], bf[k4 & 1][j], acc[j][1]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                const bool inside = ins[j];
-                const int pi = blk * 32 + m;
-                if (pi < kBTPx) {
-                    uint32_t w[16];
+                if (c + 1 < NCH) __syncthreads();                        // everyone done with xs before the next chunk
+            }
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        w[k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc0[2 * k])), __int_as_float(relu_bits(acc0[2 * k + 1]))) : 0u;
-                        w[8 + k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc1[2 * k])), __int_as_float(relu_bits(acc1[2 * k + 1]))) : 0u;
-                    }
-                    uint4 *d = (uint4 *)(t1s + pi * kPS + g * 32);
-                    d[0] = make_uint4(w[0], w[1], w[2], w[3]);
-                    d[1] = make_uint4(w[4], w[5], w[6], w[7]);
-                    d[4] = make_uint4(w[8], w[9], w[10], w[11]);         // +64 B: channels 32..63
-                    d[5] = make_uint4(w[12], w[13], w[14], w[15]);
+            for (int j = 0; j < NBPW1; ++j) {
+                // lanes past the last pixel were fed pixel 323's operands: they write pixel 323's values again
+                const int pi = min((wave + 4 * j) * 32 + m, kBTPx - 1);
+                const int row = pi / kBT, col = pi - row * kBT;
+                const bool inside = row >= geo.rlo && row < geo.rhi && col >= geo.clo && col < geo.chi;
+                uint32_t w[16];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    w[k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc[j][0][2 * k])), __int_as_float(relu_bits(acc[j][0][2 * k + 1]))) : 0u;
+                    w[8 + k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc[j][1][2 * k])), __int_as_float(relu_bits(acc[j][1][2 * k + 1]))) : 0u;
                 }
+                uint4 *d = (uint4 *)(t1s + pi * kPS + g * 32);
+                d[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                d[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                d[4] = make_uint4(w[8], w[9], w[10], w[11]);             // +64 B: channels 32..63
+                d[5] = make_uint4(w[12], w[13], w[14], w[15]);
             }
         }
         __syncthreads();
 
         // ---- output addressing of this lane's pixels (pixel block k: rows 2k + prow, column pcol) and,
-        //      for the fused form, the residual x of the whole block: requested here so that its
-        //      latency hides behind the matrix work of P2
-        const int ocol = tx0 + pcol;
+        //      for the fused form, the loader of the residual x
+        const int ocol = geo.tx0 + pcol;
         int rmin = 0, rlim = p.oh;
         bool col_ok = ocol < p.ow;
-        uint16_t *obase;
-        const uint16_t *rbase = nullptr;
-        long long orow_stride;
+        uint16_t *obase;                  // wave-uniform: output row 0 of this block, column 0, channel 0
+        const uint16_t *rbase = nullptr;  // same position in x (residual)
+        uint32_t orow_stride;             // elements between output rows
         if (FUSED) {
             const int oy0 = p.g_out.boffset_h + cur.by * p.g_out.bstride_h;
-            const int gx = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + ocol;
-            col_ok = col_ok && gx >= 0 && gx < p.W;
+            const int ox0 = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w;
+            col_ok = col_ok && (ox0 + ocol) >= 0 && (ox0 + ocol) < p.W;
             rmin = max(0, -oy0);
             rlim = min(rlim, p.H - oy0);
-            orow_stride = (long long)p.W * C;
-            obase = out + ((long long)cur.n * p.H + oy0) * orow_stride + (long long)gx * C + g * 16;
-            rbase = in + ((long long)cur.n * p.H + oy0) * orow_stride + (long long)gx * C + g * 16;
+            orow_stride = (uint32_t)p.W * C;
+            const long long org = (((long long)cur.n * p.H + oy0) * p.W + ox0) * C;
+            obase = out + org;
+            rbase = in + org;
         } else {
-            orow_stride = (long long)p.ow * C;
-            obase = out + (long long)cur.b * p.oh * orow_stride + (long long)ocol * C + g * 16;
+            orow_stride = (uint32_t)p.ow * C;
+            obase = out + (long long)cur.b * p.oh * orow_stride;
+        }
+        // per-lane element offset of pixel (row ty0 + prow, column ocol), channel g*16; blocks add 2k rows, 32 nbg channels
+        const uint32_t lane_off = (uint32_t)(geo.ty0 + prow) * orow_stride + (uint32_t)ocol * C + g * 16;
+        // Everything this tile stores is inside the block and the image (true except at ragged image edges):
+        // then residual loads and stores need no predication and P3 is straight-line code.
+        bool all_ok = geo.tx0 + 16 <= p.ow && geo.ty0 + 16 <= rlim && rmin <= geo.ty0;
+        if (FUSED) {
+            const int ox = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + geo.tx0;
+            all_ok = all_ok && ox >= 0 && ox + 16 <= p.W;
         }
         bool ok[8];
-        uint4 res[8][NBW][2];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int orow = ty0 + 2 * k + prow;
-            ok[k] = col_ok && orow >= rmin && orow < rlim;
-            if (FUSED) {
+        for (int k = 0; k < 8; ++k) ok[k] = col_ok && (geo.ty0 + 2 * k + prow) >= rmin && (geo.ty0 + 2 * k + prow) < rlim;
+        // residual x of the block (fused form): pixel blocks 0-3 are requested before P2, whose matrix work hides
+        // the latency; blocks 4-7 at the start of P3, ahead of the next tile's input so that they return first
+        uint4 res[8][NBW][2];
+        auto fetch_residual = [&](int k0) __attribute__((always_inline)) {
+            if (!FUSED) return;
+#pragma unroll
+            for (int k = k0; k < k0 + 4; ++k)
 #pragma unroll
                 for (int j = 0; j < NBW; ++j) {
-                    const int nbg = wave + 4 * j;
-                    const bool ld = ok[k] && nbg < NB3;
-                    const uint4 *r4 = ld ? (const uint4 *)(rbase + orow * orow_stride + nbg * 32) : (const uint4 *)g_zero32;
+                    const int nbg = min(wave + 4 * j, NB3 - 1);
+                    const uint4 *r4 = (ok[k] || all_ok) ? (const uint4 *)(rbase + (lane_off + 2 * k * orow_stride + nbg * 32))
+                                                        : (const uint4 *)g_zero32;
                     res[k][j][0] = r4[0];
                     res[k][j][1] = r4[1];
                 }
-            }
-        }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        fetch_residual(0);
 
-        __builtin_amdgcn_sched_barrier(0);                               // residual loads stay ahead of P2
-        // ================= P2: t2 = ReLU(W2 * t1 + b2) =================
+        // ================= P2: t2 = ReLU(W2 * t1 + b2) -> xs =================
         {
             f32x16b acc[4];
             const f32x16b bias2 = load_bias16(kCm + cm0);
@@ -290,22 +371,28 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
                 for (int k = 0; k < 8; ++k)
                     w[k] = pack2<DT>(__int_as_float(relu_bits(acc[P][2 * k])), __int_as_float(relu_bits(acc[P][2 * k + 1])));
-                uint4 *d = (uint4 *)(t2s + po * kPS + cm0 * 2);
+                uint4 *d = (uint4 *)(xs + po * kPS + cm0 * 2);
                 d[0] = make_uint4(w[0], w[1], w[2], w[3]);
                 d[1] = make_uint4(w[4], w[5], w[6], w[7]);
             }
         }
         __syncthreads();
 
-        // next item's indices while P3 runs
+        // ---- the next tile's first two input chunks are requested now and land during P3
         const uint32_t nit = it + G;
         BItem nxt = cur;
-        if (nit < items) nxt = decode(nit);
+        TileGeo ngeo = geo;
+        fetch_residual(4);
+        if (nit < items) {
+            nxt = decode(nit);
+            ngeo = geometry_of(nxt);
+            fetch_chunk(ngeo, 0, Slot0{});
+            if (NCH > 1) fetch_chunk(ngeo, 1, Slot1{});
+        }
 
         // ================= P3: t3 = W3 t2 + b3 (+ x), two pixel blocks at a time =================
-        {
-            // conv3's bias is only live in this phase: re-read it per tile (cache hit) rather than
-            // holding 16*NBW registers through P1 and P2
+        auto p3 = [&](auto fast_tag) __attribute__((always_inline)) {
+            constexpr bool FAST = decltype(fast_tag)::value;
             f32x16b bias3[NBW];
             uint4 w3r[4][NBW];
 #pragma unroll
@@ -322,7 +409,7 @@ void bottleneck16_kernel(BneckParams p) {
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks)
-                        tf[u][ks] = *(const uint4 *)(t2s + ((2 * bp + u) * 32 + m) * kPS + ks * 32 + g * 16);
+                        tf[u][ks] = *(const uint4 *)(xs + ((2 * bp + u) * 32 + m) * kPS + ks * 32 + g * 16);
                 f32x16b acc[2][NBW];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
@@ -337,7 +424,8 @@ void bottleneck16_kernel(BneckParams p) {
                     for (int j = 0; j < NBW; ++j) {
                         const int nbg = wave + 4 * j;
                         const int kblk = 2 * bp + u;
-                        if (!(ok[kblk] && nbg < NB3)) continue;
+                        if (nbg >= NB3) continue;                          // wave-uniform (C = 64 only)
+                        if (!FAST && !ok[kblk]) continue;
                         uint32_t w[8];
 #pragma unroll
                         for (int k = 0; k < 8; ++k) {
@@ -350,13 +438,17 @@ void bottleneck16_kernel(BneckParams p) {
                             }
                             w[k] = pack2<DT>(lo, hi);
                         }
-                        uint4 *d = (uint4 *)(obase + (ty0 + 2 * kblk + prow) * orow_stride + nbg * 32);
+                        uint4 *d = (uint4 *)(obase + (lane_off + 2 * kblk * orow_stride + nbg * 32));
                         d[0] = make_uint4(w[0], w[1], w[2], w[3]);
                         d[1] = make_uint4(w[4], w[5], w[6], w[7]);
                     }
             }
-        }
+        };
+        if (all_ok) p3(std::true_type{});
+        else p3(std::false_type{});
+        __syncthreads();                                                  // t2 (in xs) consumed before the next tile's chunk 0
         cur = nxt;
+        geo = ngeo;
     }
 }
 
