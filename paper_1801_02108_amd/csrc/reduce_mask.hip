@@ -5,7 +5,8 @@
 // The paper appends indices with a global atomic counter, which gives an arbitrary order.
 // Here the list is produced in lexicographic (n, by, bx) order without atomics:
 //   pass 1  one workgroup per block row: coalesced column pooling of the window rows into LDS
-//           (four columns per thread and eight rows in flight, so a row costs one memory latency),
+//           (four columns per thread and all rows of a window in flight, so the window costs one
+//           memory latency),
 //           then one thread per block pools its window columns, thresholds, stores a flag byte
 //           and the row's number of active blocks;
 //   pass 2  one workgroup per block row: exclusive prefix over the row counts, then wavefront
@@ -39,7 +40,8 @@ template <typename Acc> __device__ __forceinline__ Acc lowest_of();
 template <> __device__ __forceinline__ int lowest_of<int>() { return (int)0x80000000; }
 template <> __device__ __forceinline__ double lowest_of<double>() { return -__builtin_huge_val(); }
 
-constexpr int kRmRows = 8;   // window rows loaded per batch: that many independent loads in flight
+constexpr int kRmRows = 20;  // window rows loaded per batch: that many independent loads in flight
+constexpr int kRmCols = 8;   // window columns read from LDS per batch
 
 // VEC = 4: every thread pools four neighbouring columns with one 4-element load per row (needs
 // W % 4 == 0); VEC = 1: any W.
@@ -51,6 +53,7 @@ __global__ __launch_bounds__(kRmThreads) void rm_pool_rows(const T *__restrict__
     extern __shared__ __align__(8) unsigned char lds_raw[];
     Acc *col = reinterpret_cast<Acc *>(lds_raw);
     __shared__ int red[4];
+    typedef typename Vec4<T>::type V4;
 
     const int row = blockIdx.x;
     const int n = row / g.bcount_h, by = row - n * g.bcount_h;
@@ -64,30 +67,30 @@ __global__ __launch_bounds__(kRmThreads) void rm_pool_rows(const T *__restrict__
         Acc a[VEC];
 #pragma unroll
         for (int k = 0; k < VEC; ++k) a[k] = neutral;
-        for (int yb = ylo; yb < yhi; yb += kRmRows) {
-            Acc v[kRmRows][VEC];
+        const T *p0 = mask + ((size_t)n * H + ylo) * W + x;
+        for (int yb = ylo; yb < yhi; yb += kRmRows, p0 += (size_t)kRmRows * W) {
+            V4 q[kRmRows];
+            T q1[kRmRows];
 #pragma unroll
             for (int u = 0; u < kRmRows; ++u) {
-#pragma unroll
-                for (int k = 0; k < VEC; ++k) v[u][k] = neutral;
                 if (yb + u < yhi) {
-                    const T *p = mask + ((size_t)n * H + yb + u) * W + x;
-                    if (VEC == 4) {
-                        const typename Vec4<T>::type q = *reinterpret_cast<const typename Vec4<T>::type *>(p);
-                        v[u][0] = (Acc)q.x; v[u][VEC > 1 ? 1 : 0] = (Acc)q.y;
-                        v[u][VEC > 2 ? 2 : 0] = (Acc)q.z; v[u][VEC > 3 ? 3 : 0] = (Acc)q.w;
-                    } else {
-                        v[u][0] = (Acc)*p;
-                    }
+                    if (VEC == 4) q[u] = *reinterpret_cast<const V4 *>(p0 + (size_t)u * W);
+                    else q1[u] = p0[(size_t)u * W];
                 }
             }
 #pragma unroll
-            for (int u = 0; u < kRmRows; ++u)
+            for (int u = 0; u < kRmRows; ++u) {
+                if (yb + u < yhi) {
+                    Acc v[4];
+                    if (VEC == 4) { v[0] = (Acc)q[u].x; v[1] = (Acc)q[u].y; v[2] = (Acc)q[u].z; v[3] = (Acc)q[u].w; }
+                    else v[0] = (Acc)q1[u];
 #pragma unroll
-                for (int k = 0; k < VEC; ++k) {
-                    if (POOL == SBNET_POOL_AVG) a[k] += v[u][k];
-                    else a[k] = v[u][k] > a[k] ? v[u][k] : a[k];
+                    for (int k = 0; k < VEC; ++k) {
+                        if (POOL == SBNET_POOL_AVG) a[k] += v[k];
+                        else a[k] = v[k] > a[k] ? v[k] : a[k];
+                    }
                 }
+            }
         }
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
@@ -104,10 +107,17 @@ __global__ __launch_bounds__(kRmThreads) void rm_pool_rows(const T *__restrict__
         const int xlo = max(x0, 0), xhi = min(x0 + g.bsize_w, W);
         const bool cols_clipped = (x0 < 0) || (x0 + g.bsize_w > W);
         Acc a = neutral;
-        for (int x = xlo; x < xhi; ++x) {
-            const Acc v = col[x];
-            if (POOL == SBNET_POOL_AVG) a += v;
-            else a = v > a ? v : a;
+        for (int xb = xlo; xb < xhi; xb += kRmCols) {
+            Acc v[kRmCols];
+#pragma unroll
+            for (int u = 0; u < kRmCols; ++u) v[u] = col[min(xb + u, xhi - 1)];
+#pragma unroll
+            for (int u = 0; u < kRmCols; ++u) {
+                if (xb + u < xhi) {
+                    if (POOL == SBNET_POOL_AVG) a += v[u];
+                    else a = v[u] > a ? v[u] : a;
+                }
+            }
         }
         if (POOL == SBNET_POOL_MAX && cols_clipped) a = a < (Acc)0 ? (Acc)0 : a;
         const double pooled = POOL == SBNET_POOL_AVG ? (double)a / area : (double)a;
@@ -129,6 +139,8 @@ __global__ __launch_bounds__(kRmThreads) void rm_compact(const int32_t *__restri
     const int row = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
+    // the first batch of flags travels together with the row counts
+    const bool on0 = (int)threadIdx.x < bcount_w && flags[(size_t)row * bcount_w + threadIdx.x] != 0;
     int part = 0;
     for (int r = threadIdx.x; r < row; r += kRmThreads) part += rowcount[r];
     int base = block_sum(part, red);   // active blocks in all earlier rows
@@ -136,7 +148,7 @@ __global__ __launch_bounds__(kRmThreads) void rm_compact(const int32_t *__restri
     const int n = row / bcount_h, by = row - n * bcount_h;
     for (int b0 = 0; b0 < bcount_w; b0 += kRmThreads) {
         const int bx = b0 + threadIdx.x;
-        const bool on = bx < bcount_w && flags[(size_t)row * bcount_w + bx] != 0;
+        const bool on = b0 == 0 ? on0 : (bx < bcount_w && flags[(size_t)row * bcount_w + bx] != 0);
         const unsigned long long ballot = __ballot(on);
         __syncthreads();
         if (lane == 0) wave_cnt[wave] = __popcll(ballot);

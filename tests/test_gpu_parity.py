@@ -120,6 +120,37 @@ def test_reduce_mask_repeatable_and_overwrites_count():
         assert torch.equal(cnt, ref_c) and torch.equal(idx[:int(ref_c)], ref_i[:int(ref_c)])
 
 
+@pytest.mark.parametrize("fill", [0x00, 0xff, 0x5b])
+def test_reduce_mask_reuses_one_workspace_whatever_it_held(fill):
+    """The same scratch buffer serves a sequence of different problems; its first contents are arbitrary."""
+    step("reduce_mask shared workspace fill=%#x" % fill)
+    r = gen.rng_for(1, 9)
+    cases = [(1, 64, 64, 8), (3, 48, 80, 4), (2, 100, 176, 16), (1, 64, 64, 8)]
+    geoms = [sb.geometry(H, W, 3, 1, bo)[0] for (_, H, W, bo) in cases]
+    need = max(sb.workspace_bytes(c[0], g) for c, g in zip(cases, geoms))
+    ws = torch.full((need,), fill, dtype=torch.uint8).cuda()
+    for rep in range(2):
+        for (N, H, W, bo), g in zip(cases, geoms):
+            mask = (r.random((N, H, W)) < 0.03).astype(np.uint8)
+            idx, cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g, workspace=ws)
+            want = orc.reduce_mask(mask, ogeom(g))
+            n = sb.read_count(cnt, idx.shape[0])
+            assert n == len(want) and np.array_equal(idx[:n].cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("N,H,W,bo,dens", [(4, 800, 704, 16, None),     # the batched configurations' block grid
+                                           (2, 512, 512, 4, None),      # 256 block rows of 128 blocks
+                                           (1, 4200, 40, 1, 0.3)])      # 4200 block rows: long prefix over row counts
+def test_reduce_mask_many_blocks(N, H, W, bo, dens):
+    step("reduce_mask many blocks N=%d H=%d W=%d bo=%d" % (N, H, W, bo))
+    r = gen.rng_for(1, 11 + bo)
+    g_in, _, _, _ = sb.geometry(H, W, 3, 1, bo)
+    mask = gen.lowres_mask(gen.smooth_noise(r, N, H // 8, W // 8, 2.0), 1.0) if bo > 1 else r.random((N, H, W)) < dens
+    for pool in (sb.POOL_MAX, sb.POOL_AVG):
+        _reduce_case(np.asarray(mask, dtype=np.float32), g_in, pool, 0.0, "u8")
+    _reduce_case(np.ones((N, H, W), dtype=np.float32), g_in, sb.POOL_AVG, 0.0, "f32")
+
+
 # --------------------------------------------------------------------------- gather / scatter
 GS_CASES = [
     # H, W, C, k, s, bo, N, dtype
