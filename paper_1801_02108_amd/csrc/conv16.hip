@@ -9,9 +9,17 @@
 //   * weights stay in registers for the life of the workgroup: wave (rh, nh) owns output rows
 //     rh*8..rh*8+7 of a 16x16 output sub-tile and output channels nh*32..nh*32+31 of the
 //     workgroup's 64, i.e. 9*CIN/16 k-steps x 4 VGPRs (144 VGPRs at CIN = 64);
-//   * the 18x18xCIN input sub-tile (block + halo) is double-buffered in LDS: the global loads of
-//     the next tile are issued before the matrix work of the current one and written to the
-//     other buffer after it, so HBM latency hides behind the MFMAs;
+//   * global memory is reached through buffer descriptors that cover one sample (or one tile):
+//     a halo pixel above or below the image lands outside the descriptor, one to the left or
+//     right gets an out-of-range offset on purpose, and the hardware returns zeros for such loads
+//     and drops such stores.  The tile loop therefore has no branch and no predicate around any
+//     memory operation, and the compiler's wait counts stay exact (with branches they turn into
+//     full waits and every load or store then costs its own memory round trip);
+//   * the 18x18xCIN input sub-tile (block + halo) is double-buffered in LDS and software-pipelined
+//     two tiles deep: while the matrix cores work on tile i, the same wave, between its MFMAs,
+//     writes tile i+1 (loaded during tile i-1) to the other LDS buffer and issues the loads of
+//     tile i+2 into the registers this frees.  The index triple of tile i+3 is requested at the
+//     same time.  No load waits on another load and none of this costs matrix-core time;
 //   * an LDS fragment is 32 pixels (two consecutive input rows x 16 columns) x 16 channels; the
 //     pixel stride is padded by 16 B, which makes the two rows of a fragment fall on disjoint
 //     bank groups.  A fragment starting on an even row is used for tap rows 0 and 2 of two
@@ -24,6 +32,9 @@ namespace sbnet {
 
 constexpr int kT16 = 18;                 // input sub-tile side: 16 + 3 - 1
 constexpr int kT16Px = kT16 * kT16;
+constexpr uint32_t kBufWord3 = 0x00020000u;      // raw buffer descriptor, 32-bit data format
+constexpr uint32_t kOutOfRange = 0x80000000u;    // offset beyond any descriptor this kernel builds
+constexpr int kOutPs = 80;                       // LDS bytes per pixel of a wave's results: 32 channels + 16 B pad
 
 struct Sub16 {
     int sub_h, sub_w;                    // 16x16 sub-tiles per block
@@ -38,6 +49,7 @@ struct Item16 {
 };
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 template <int DT>
 __device__ __forceinline__ f32x16 mfma32x32x16(uint4 a, uint4 b, f32x16 c) {
@@ -48,21 +60,39 @@ __device__ __forceinline__ f32x16 mfma32x32x16(uint4 a, uint4 b, f32x16 c) {
     }
 }
 
-template <int DT, int CIN, bool FUSED>
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, uint32_t off, uint4 d) {
+    u32x4 v;
+    v[0] = d.x; v[1] = d.y; v[2] = d.z; v[3] = d.w;
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 0);
+}
+
+// ADD (fused form only): the results are added to what the output holds.  A template parameter rather than a
+// branch on p.add: with two paths that issue different numbers of memory operations the compiler's wait counts
+// after the join are those of the shorter path, and the first LDS write of the next tile then waits for this
+// tile's stores to be acknowledged.
+template <int DT, int CIN, bool FUSED, bool ADD>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void conv16_kernel(ConvParams p, Sub16 sp) {
+    static_assert(FUSED || !ADD, "adding into the output is part of the fused form");
     constexpr int KC = CIN / 16;                     // 16-channel k-steps per tap
     constexpr int CV = CIN / 8;                      // 16-byte vectors per pixel
     constexpr int PS = (CIN + 8) * 2;                // LDS bytes per pixel
     constexpr int NVEC = kT16Px * CV;
     constexpr int NV = (NVEC + 255) / 256;           // staging vectors per thread
+    constexpr int PXK = 256 / CV;                    // pixels between a thread's consecutive vectors
+    constexpr int LPX = NV * PXK;                    // pixels per LDS buffer: every staging vector has a slot
     constexpr int KS = 9 * KC;
     constexpr int NST = 3 * KC;                      // pipeline stages: (tap column, channel step)
-    __shared__ __align__(16) unsigned char lds[2][kT16Px * PS];
+    static_assert(NV <= NST, "one staging vector per pipeline stage");
+    __shared__ __align__(16) unsigned char lds[2][LPX * PS];
+    __shared__ __align__(16) unsigned char ostage[4][8 * 16 * kOutPs];       // per wave: 8 rows x 16 pixels of results
 
-    const uint16_t *in = (const uint16_t *)p.in;
-    uint16_t *out = (uint16_t *)p.out;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 5, m = lane & 31;          // k-group / channel group, pixel within a fragment
     const int prow = m >> 4, pcol = m & 15;
     const int rh = wave >> 1, nh = wave & 1;
@@ -72,7 +102,13 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
     // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of items
     const uint32_t first = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
 
-    auto decode = [&](uint32_t it) {
+    // A work item's index triple is requested well before it is needed.  The address is the same in
+    // every lane, but the loads are issued as per-lane loads and left in vector registers (the opaque
+    // zero hides the uniformity): a value the compiler knows to be uniform is moved to a scalar
+    // register right after the load, which would stall the wave for the memory round trip on the spot.
+    int lane_zero = 0;
+    asm volatile("" : "+v"(lane_zero));
+    auto request = [&](uint32_t it) __attribute__((always_inline)) {
         Item16 c;
         c.b = fdiv(it, sp.div_sub);
         const uint32_t sidx = it - c.b * per_block;
@@ -80,19 +116,90 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
         c.sj = (int)sidx - c.si * sp.sub_w;
         c.n = c.by = c.bx = 0;
         if (FUSED) {
-            c.n = p.indices[3 * c.b];
-            c.by = p.indices[3 * c.b + 1];
-            c.bx = p.indices[3 * c.b + 2];
+            const int32_t *t = p.indices + 3 * (size_t)c.b + lane_zero;
+            c.n = t[0];
+            c.by = t[1];
+            c.bx = t[2];
         }
         return c;
     };
+    auto resolve = [&](const Item16 &c) __attribute__((always_inline)) {
+        Item16 r = c;
+        if (FUSED) {
+            r.n = __builtin_amdgcn_readfirstlane(c.n);
+            r.by = __builtin_amdgcn_readfirstlane(c.by);
+            r.bx = __builtin_amdgcn_readfirstlane(c.bx);
+        }
+        return r;
+    };
 
     // The count and the first index triple are independent loads (the index is clamped into the
-    // buffer), so their latencies overlap instead of chaining.
+    // buffer), so their latencies overlap instead of chaining.  Items past the end repeat the last
+    // one: its loads are harmless and nothing is stored for it (the loop has ended by then).
     const int nact_raw = *p.count;
-    Item16 cur = decode(min(first, (uint32_t)p.cap * per_block - 1u));
-    const uint32_t items = (uint32_t)min(nact_raw, p.cap) * per_block;
+    Item16 cur = request(min(first, (uint32_t)p.cap * per_block - 1u));
+    const uint32_t items = (uint32_t)max(min(nact_raw, p.cap), 0) * per_block;
     if (first >= items) return;
+    const uint32_t last = items - 1u;
+    Item16 nx1 = request(min(first + G, last));
+    Item16 nx2 = request(min(first + 2 * G, last));
+    cur = resolve(cur);
+
+    // ---- staging plan, the same for every tile: vector k of this thread is 16 bytes of pixel px0 + k*PXK
+    //      of the 18x18 sub-tile (LDS has slots for the few pixel numbers past the end).
+    const int in_w = FUSED ? p.W : p.tw;                         // pixels per row of the addressed array
+    const uint32_t in_bytes = (uint32_t)(FUSED ? p.H : p.th) * in_w * CIN * 2u;      // one sample / one tile
+    uint32_t delta[NV];                                          // byte offset from the sub-tile origin
+    int colk[NV];                                                // column inside the sub-tile
+    {
+        const int px0 = threadIdx.x / CV, c8 = threadIdx.x % CV;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int px = px0 + k * PXK;
+            const int row = px / kT16, col = px % kT16;
+            delta[k] = (uint32_t)((row * in_w + col) * CIN + c8 * 8) * 2u;
+            colk[k] = col;
+        }
+    }
+    struct Src {
+        __amdgpu_buffer_rsrc_t rsrc;     // the sample (fused) or tile that holds the sub-tile
+        uint32_t origin;                 // byte offset of the sub-tile's pixel (0, 0); wraps below zero above / left of the image
+        int gx0;                         // image column of sub-tile column 0
+    };
+    auto source = [&](const Item16 &c) __attribute__((always_inline)) {
+        Src s;
+        const uint16_t *base = (const uint16_t *)p.in;
+        int y0, x0;
+        if (FUSED) {
+            y0 = p.g_in.boffset_h + c.by * p.g_in.bstride_h + c.si * 16;
+            x0 = p.g_in.boffset_w + c.bx * p.g_in.bstride_w + c.sj * 16;
+            base += (long long)c.n * p.H * p.W * CIN;
+        } else {
+            y0 = c.si * 16;
+            x0 = c.sj * 16;
+            base += (long long)c.b * p.th * p.tw * CIN;
+        }
+        s.rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)in_bytes, (int)kBufWord3);
+        s.origin = (uint32_t)((y0 * in_w + x0) * CIN) * 2u;
+        s.gx0 = x0;
+        return s;
+    };
+    // Rows outside the image fall outside the descriptor by themselves; columns outside would wrap
+    // into the neighbouring row, so they get the out-of-range offset.  Either way the load returns zeros.
+    uint4 stage[NV];
+    auto fetch1 = [&](const Src &s, int k) __attribute__((always_inline)) {
+        const bool col_ok = !FUSED || (uint32_t)(s.gx0 + colk[k]) < (uint32_t)p.W;
+        stage[k] = buf_load16(s.rsrc, col_ok ? s.origin + delta[k] : kOutOfRange);
+    };
+    const uint32_t stash_off = (threadIdx.x / CV) * PS + (threadIdx.x % CV) * 16;
+    auto stash1 = [&](int buf, int k) __attribute__((always_inline)) {
+        *(uint4 *)(&lds[buf][stash_off + k * PXK * PS]) = stage[k];
+    };
+
+    Src src = source(cur);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) fetch1(src, k);     // first: the longest latency of the prologue
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- weights of this wave: every k-step of its 32 output channels
     uint4 wreg[KS];
@@ -116,72 +223,47 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
     }
     // ReLU as an integer max on the float bits (negative floats are negative integers); without
     // ReLU the floor is INT_MIN and the max is the identity.  One VALU op, no NaN canonicalisation.
-    const int floor_i = p.relu ? 0 : (int)0x80000000;
+    int floor_i = p.relu ? 0 : (int)0x80000000;
+    asm volatile("" : "+s"(floor_i));                // opaque: otherwise the max is split into a max with 0 and a select
 
-    // ---- per-thread staging plan, the same for every tile: element offset from the tile origin,
-    //      (row, col) for the bounds test
-    const int row_stride = (FUSED ? p.W : p.tw) * CIN;           // elements between tile rows in memory
-    int goff[NV], rowcol[NV];
-#pragma unroll
-    for (int k = 0; k < NV; ++k) {
-        const int v = (int)threadIdx.x + k * 256;
-        const int px = v / CV, c8 = v % CV;
-        const int row = px / kT16, col = px % kT16;
-        goff[k] = row * row_stride + col * CIN + c8 * 8;
-        rowcol[k] = v < NVEC ? (row | (col << 8)) : 0xffff;      // row 255 never passes the test
-    }
+    // ---- output plan: this lane stores pixel (rh*8 + 2P + prow, pcol) of the sub-tile, channels ch0 .. ch0+15
+    const int out_w = FUSED ? p.Wo : p.ow;
+    const uint32_t out_bytes = (uint32_t)(FUSED ? p.Ho : p.oh) * out_w * p.Cout * 2u;
+    const uint32_t out_lane = (uint32_t)(((rh * 8 + prow) * out_w + pcol) * p.Cout + ch0) * 2u;
+    const uint32_t out_pair = (uint32_t)(2 * out_w * p.Cout) * 2u;          // two rows down
+    const bool chan_ok[2] = {ch0 < p.Cout, ch0 + 8 < p.Cout};
+    // ... and after the transpose through LDS: pixel (rh*8 + j, lane / 4), 16 bytes number lane % 4 of the
+    // wave's 32 channels
+    const uint32_t out_row = (uint32_t)(out_w * p.Cout) * 2u;
+    const uint32_t out_lane2 = (uint32_t)((rh * 8 * out_w + (lane >> 2)) * p.Cout + ng * 64 + nh * 32 + (lane & 3) * 8) * 2u;
+    const bool chan_ok2 = ng * 64 + nh * 32 + (lane & 3) * 8 < p.Cout;
+    const uint32_t ost_w = (prow * 16 + pcol) * kOutPs + g * 32;           // MFMA layout -> LDS (+ row pair, half)
+    const uint32_t ost_r = (lane >> 2) * kOutPs + (lane & 3) * 16;          // LDS -> store layout (+ row)
 
-    uint4 stage[NV];
-    auto fetch = [&](const Item16 &c) {
-        // valid rows / columns of this sub-tile: inside the tile and (fused) inside the image
-        int rlo = 0, rhi = min(kT16, p.th - c.si * 16), clo = 0, chi = min(kT16, p.tw - c.sj * 16);
-        const uint16_t *base;
-        if (FUSED) {
-            const int gy0 = p.g_in.boffset_h + c.by * p.g_in.bstride_h + c.si * 16;
-            const int gx0 = p.g_in.boffset_w + c.bx * p.g_in.bstride_w + c.sj * 16;
-            rlo = max(0, -gy0); rhi = min(rhi, p.H - gy0);
-            clo = max(0, -gx0); chi = min(chi, p.W - gx0);
-            base = in + ((long long)c.n * p.H + gy0) * row_stride + (long long)gx0 * CIN;
-        } else {
-            base = in + ((long long)c.b * p.th + c.si * 16) * row_stride + (long long)c.sj * 16 * CIN;
-        }
+    nx1 = resolve(nx1);
 #pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            const int row = rowcol[k] & 0xff, col = rowcol[k] >> 8;
-            // A predicated load on purpose: written as an unconditional load from a selected address
-            // (tile or a zero buffer) the compiler sinks every load down to its LDS store and a tile
-            // costs NV memory round trips instead of one.
-            stage[k] = make_uint4(0, 0, 0, 0);
-            if (row >= rlo && row < rhi && col >= clo && col < chi) stage[k] = *(const uint4 *)(base + goff[k]);
-        }
-    };
-    auto stash = [&](int buf) {
+    for (int k = 0; k < NV; ++k) stash1(0, k);
+    src = source(nx1);
 #pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            const int v = (int)threadIdx.x + k * 256;
-            if (v < NVEC) *(uint4 *)(&lds[buf][(v / CV) * PS + (v % CV) * 16]) = stage[k];
-        }
-    };
-
-    fetch(cur);
-    stash(0);
+    for (int k = 0; k < NV; ++k) fetch1(src, k);     // tile 1 (or a repeat of the last tile) rides through tile 0's matrix work
+    // Every load of the prologue but those has landed before the loop is entered: the loop's wait counts are then
+    // exact from the first iteration on.
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (NV & 15) | ((NV >> 4) << 14));      // vmcnt(NV)
     __syncthreads();
 
     int buf = 0;
     for (uint32_t it = first; it < items; it += G) {
-        const uint32_t nit = it + G;
-        const bool more = nit < items;
-        Item16 nxt = cur;
-        if (more) {
-            nxt = decode(nit);
-            fetch(nxt);
-        }
+        const Item16 nx3 = request(min(it + 3 * G, last));       // used two iterations from now
+        nx2 = resolve(nx2);
+        src = source(nx2);
 
         // ---- 16x16 outputs x 64 channels; this wave: 4 output row pairs x 32 channels.
         // Fragment j of a stage holds input rows rh*8 + j, rh*8 + j + 1 (j = 0..8) at tap column t;
         // output row pair P with tap row r reads fragment 2P + r.  Stages are software-pipelined:
         // while the matrix cores consume the nine fragments of one stage, the nine of the next are
-        // read from LDS into the other register set; the scheduling barriers keep that interleaving.
+        // read from LDS into the other register set.  Between the last MFMAs of stage k the wave also
+        // moves staging vector k of the next tile to LDS and reloads it with the tile after that.
+        // The scheduling barriers keep all of this interleaved as written.
         f32x16 acc[4];      // first MFMA of each accumulator starts from the bias
         const unsigned char *L = &lds[buf][((rh * 8 + prow) * kT16 + pcol) * PS + g * 16];
         uint4 xf[2][9];
@@ -199,67 +281,83 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
                                           (st == 0 && r == 0) ? biasv : acc[P]);
                 if (mm < 9 && st + 1 < NST)
                     xf[(st + 1) & 1][mm] = *(const uint4 *)(L + (mm * kT16 + tn) * PS + kcn * 32);
+                if (mm == 9 && st < NV) stash1(buf ^ 1, st);
+                if (mm == 10 && st < NV) fetch1(src, st);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
 
-        // The next tile goes to the other LDS buffer before this tile's stores are issued: the
-        // wait for its loads (issued a whole tile ago) is then not held up by store acknowledgements.
-        if (more) stash(buf ^ 1);
-
-        // ---- epilogue: ReLU, optional add, two 16-byte NHWC stores per pixel and lane
+        // ---- epilogue: ReLU, optional add, NHWC stores.  In the MFMA result layout a lane holds 16 channels of
+        //      one pixel and neighbouring lanes hold neighbouring pixels, so storing from it would scatter 16-byte
+        //      pieces over 32 cache lines per instruction.  The wave instead transposes its 8 rows x 16 pixels x
+        //      32 channels through a private LDS area: afterwards four neighbouring lanes hold the 64 contiguous
+        //      bytes of one pixel and a store instruction covers one output row of the wave.
+        //      Rows outside the image are outside the descriptor; columns outside and channels past Cout get the
+        //      out-of-range offset; the hardware drops those stores (and returns zeros for those loads).
         {
-            const int ocol = cur.sj * 16 + pcol;
-            uint16_t *obase;
-            long long orow_stride;
-            bool col_ok = ocol < p.ow;
-            int rlim = p.oh;                                   // rows [rmin, rlim) of the block are stored
-            int rmin = 0;
+            uint16_t *obase = (uint16_t *)p.out;
+            int y0, x0;
             if (FUSED) {
-                const int gy0 = p.g_out.boffset_h + cur.by * p.g_out.bstride_h;
-                const int gx = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + ocol;
-                col_ok = col_ok && gx >= 0 && gx < p.Wo;
-                rlim = min(rlim, p.Ho - gy0);
-                rmin = max(0, -gy0);
-                orow_stride = (long long)p.Wo * p.Cout;
-                obase = out + ((long long)cur.n * p.Ho + gy0) * orow_stride + (long long)gx * p.Cout + ch0;
+                y0 = p.g_out.boffset_h + cur.by * p.g_out.bstride_h + cur.si * 16;
+                x0 = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + cur.sj * 16;
+                obase += (long long)cur.n * p.Ho * p.Wo * p.Cout;
             } else {
-                orow_stride = (long long)p.ow * p.Cout;
-                obase = out + (long long)cur.b * p.oh * orow_stride + (long long)ocol * p.Cout + ch0;
+                y0 = cur.si * 16;
+                x0 = cur.sj * 16;
+                obase += (long long)cur.b * p.oh * p.ow * p.Cout;
             }
+            const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc((void *)obase, 0, (int)out_bytes, (int)kBufWord3);
+            const uint32_t origin = (uint32_t)((y0 * out_w + x0) * p.Cout) * 2u;
+            uint4 old[4][2];
+            if (ADD) {       // read in the MFMA layout, so that the sum is formed in fp32 and rounded once
+                const bool col_ok = (uint32_t)(x0 + pcol) < (uint32_t)p.Wo;
 #pragma unroll
-            for (int P = 0; P < 4; ++P) {
-                const int orow = cur.si * 16 + rh * 8 + 2 * P + prow;
-                if (!(col_ok && orow >= rmin && orow < rlim)) continue;
+                for (int P = 0; P < 4; ++P)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+                        old[P][h] = buf_load16(orsrc, (col_ok && chan_ok[h]) ? origin + out_lane + P * out_pair + h * 16 : kOutOfRange);
+            }
+            unsigned char *os = ostage[wave];
+#pragma unroll
+            for (int P = 0; P < 4; ++P)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    if (ch0 + h * 8 >= p.Cout) continue;       // Cout % 8 == 0: a vector is all in or all out
                     float v[8];
 #pragma unroll
                     for (int k = 0; k < 8; ++k) v[k] = __int_as_float(max(__float_as_int(acc[P][h * 8 + k]), floor_i));
-                    uint4 *d4 = (uint4 *)(obase + orow * orow_stride + h * 8);
-                    if (FUSED && p.add) {
-                        const uint4 old = *d4;
-                        v[0] += unpack_lo<DT>(old.x); v[1] += unpack_hi<DT>(old.x);
-                        v[2] += unpack_lo<DT>(old.y); v[3] += unpack_hi<DT>(old.y);
-                        v[4] += unpack_lo<DT>(old.z); v[5] += unpack_hi<DT>(old.z);
-                        v[6] += unpack_lo<DT>(old.w); v[7] += unpack_hi<DT>(old.w);
+                    if (ADD) {
+                        const uint4 o = old[P][h];
+                        v[0] += unpack_lo<DT>(o.x); v[1] += unpack_hi<DT>(o.x);
+                        v[2] += unpack_lo<DT>(o.y); v[3] += unpack_hi<DT>(o.y);
+                        v[4] += unpack_lo<DT>(o.z); v[5] += unpack_hi<DT>(o.z);
+                        v[6] += unpack_lo<DT>(o.w); v[7] += unpack_hi<DT>(o.w);
                     }
-                    *d4 = make_uint4(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]), pack2<DT>(v[4], v[5]), pack2<DT>(v[6], v[7]));
+                    *(uint4 *)(os + ost_w + P * (2 * 16 * kOutPs) + h * 16) =
+                        make_uint4(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]), pack2<DT>(v[4], v[5]), pack2<DT>(v[6], v[7]));
                 }
+            __builtin_amdgcn_wave_barrier();     // LDS serves one wave's accesses in order: no wait, only no reordering
+            const bool ok2 = chan_ok2 && (!FUSED || (uint32_t)(x0 + (lane >> 2)) < (uint32_t)p.Wo);
+            const uint32_t off2 = ok2 ? origin + out_lane2 : kOutOfRange;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint4 v = *(const uint4 *)(os + ost_r + j * (16 * kOutPs));
+                buf_store16(orsrc, ok2 ? off2 + j * out_row : kOutOfRange, v);
             }
         }
 
         __syncthreads();
         buf ^= 1;
-        cur = nxt;
+        cur = nx1;
+        nx1 = nx2;
+        nx2 = nx3;
     }
 }
 
 template <int DT, int CIN>
 static void launch16(bool fused, const ConvParams &p, const Sub16 &sp, dim3 grid, hipStream_t s) {
-    if (fused) hipLaunchKernelGGL((conv16_kernel<DT, CIN, true>), grid, dim3(256), 0, s, p, sp);
-    else hipLaunchKernelGGL((conv16_kernel<DT, CIN, false>), grid, dim3(256), 0, s, p, sp);
+    if (fused && p.add) hipLaunchKernelGGL((conv16_kernel<DT, CIN, true, true>), grid, dim3(256), 0, s, p, sp);
+    else if (fused) hipLaunchKernelGGL((conv16_kernel<DT, CIN, true, false>), grid, dim3(256), 0, s, p, sp);
+    else hipLaunchKernelGGL((conv16_kernel<DT, CIN, false, false>), grid, dim3(256), 0, s, p, sp);
 }
 
 bool conv16_try(sbnet_dtype dt, bool fused, const ConvParams &p, hipStream_t s, sbnet_status *st, const char *who) {
@@ -274,8 +372,10 @@ bool conv16_try(sbnet_dtype dt, bool fused, const ConvParams &p, hipStream_t s, 
     sp.div_subw = make_fastdiv((uint32_t)sp.sub_w);
     const long long items = (long long)p.cap * sp.sub_h * sp.sub_w;
     if (items >= (1LL << 31)) return false;
-    // staging offsets inside one sub-tile are kept in 32-bit registers
-    if (18LL * (fused ? p.W : p.tw) * p.Cin >= (1LL << 30)) return false;
+    // byte offsets inside one sample (fused) or one tile are kept in 32 bits and checked by the hardware
+    // against a buffer descriptor of that size
+    if ((fused ? (long long)p.H * p.W : (long long)p.th * p.tw) * p.Cin >= (1LL << 30)) return false;
+    if ((fused ? (long long)p.Ho * p.Wo : (long long)p.oh * p.ow) * p.Cout >= (1LL << 30)) return false;
     long long g = (items + 7) / 8 * 8;
     if (g > 256) g = 256;                             // one persistent workgroup per CU
     dim3 grid((unsigned)g, (unsigned)((p.Cout + 63) / 64));
