@@ -3,7 +3,9 @@
 // folded into weights and bias) share one gather and one scatter-add (Sec. 3.4).  The receptive
 // field of the whole unit is that of its single 3x3, so the input tile is block + 1-pixel halo.
 //
-// One kernel per unit; per 16x16 output sub-tile and workgroup (4 waves, one per SIMD).  The
+// One kernel per unit; per TS x TS output sub-tile (TS = 16, or 8 for blocks that are no multiple of 16
+// and for problems with too few 16x16 sub-tiles to occupy the device) and workgroup (4 waves, one per
+// SIMD).  The
 // 1x1 weights W1, W3 and the biases stay in LDS for the life of the workgroup (MFMA operand order);
 // W2 (the 3x3, 72 KB) is re-read from L2 into registers once per tile while P1 runs:
 //   P1  t1 = ReLU(W1 x + b1) on the 18x18 input sub-tile.  x passes through LDS in 64-channel
@@ -25,8 +27,6 @@
 
 namespace sbnet {
 
-constexpr int kBT = 18;                  // input sub-tile side
-constexpr int kBTPx = kBT * kBT;         // 324 pixels
 constexpr int kCm = 64;                  // bottleneck width
 constexpr int kPS = (kCm + 8) * 2;       // LDS bytes per pixel of t1 / t2 (16 B pad)
 
@@ -54,6 +54,11 @@ struct BneckParams {
     sbnet_geom g_in, g_out;
     int sub_h, sub_w;
     FastDiv div_sub, div_subw;
+    // The launch does its work only if lo <= (active blocks) * per16 <= hi, else every workgroup returns at once:
+    // the host cannot see the device-side count, so it launches the 16- and the 8-pixel sub-tile variants with
+    // complementary ranges and the count picks one.
+    int per16;
+    long long lo, hi;
 };
 
 struct BItem {
@@ -68,9 +73,17 @@ __device__ __align__(16) uint4 g_zero32[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}
 
 __device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v), 0); }
 
-template <int DT, int C, bool FUSED>
+template <int DT, int C, bool FUSED, int TS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void bottleneck16_kernel(BneckParams p) {
+    static_assert(TS == 16 || TS == 8, "output sub-tile side");
+    constexpr int kBT = TS + 2;                // input sub-tile side
+    constexpr int kBTPx = kBT * kBT;           // 324 or 100 pixels
+    constexpr int LOGTS = TS == 16 ? 4 : 3;
+    constexpr int RPF = 32 / TS;               // sub-tile rows covered by one 32-pixel MFMA block (2 or 4)
+    constexpr int NPB = TS * TS / 32;          // 32-pixel blocks of the output sub-tile (8 or 2)
+    constexpr int NP = NPB / 2;                // ... per wave in P2: waves split the rows in two halves (4 or 1)
+    constexpr int NF = RPF * (NP - 1) + 3;     // LDS fragments per P2 stage (9 or 3)
     constexpr int K1 = C / 16;                 // k-steps of conv1
     constexpr int NCH = C / 64;                // 64-channel chunks of the input tile
     constexpr int NB3 = C / 32;                // 32-channel output blocks of conv3
@@ -89,7 +102,7 @@ void bottleneck16_kernel(BneckParams p) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: lives in a scalar register
     const int g = lane >> 5, m = lane & 31;
-    const int prow = m >> 4, pcol = m & 15;
+    const int prow = m >> LOGTS, pcol = m & (TS - 1);
     const int rh = wave >> 1, nh = wave & 1;
     const uint32_t per_block = (uint32_t)p.sub_h * p.sub_w;
     const uint32_t G = gridDim.x;
@@ -112,8 +125,10 @@ void bottleneck16_kernel(BneckParams p) {
 
     const int nact_raw = *p.count;
     BItem cur = decode(min(first, (uint32_t)p.cap * per_block - 1u));
-    const uint32_t items = (uint32_t)min(nact_raw, p.cap) * per_block;
-    if (first >= items) return;
+    const int nact = max(min(nact_raw, p.cap), 0);
+    const uint32_t items = (uint32_t)nact * per_block;
+    const long long work16 = (long long)nact * p.per16;
+    if (first >= items || work16 < p.lo || work16 > p.hi) return;
 
     // ---- geometry of a sub-tile: origin in memory and the rows / columns that exist and lie inside the image
     struct TileGeo {
@@ -123,8 +138,8 @@ void bottleneck16_kernel(BneckParams p) {
     const int row_stride = (FUSED ? p.W : p.tw) * C;                      // elements between rows of the input
     auto geometry_of = [&](const BItem &c) __attribute__((always_inline)) {
         TileGeo t;
-        t.ty0 = c.si * 16;
-        t.tx0 = c.sj * 16;
+        t.ty0 = c.si * TS;
+        t.tx0 = c.sj * TS;
         const int gy0 = p.g_in.boffset_h + c.by * p.g_in.bstride_h + t.ty0;   // sub-tile origin in image coordinates
         const int gx0 = p.g_in.boffset_w + c.bx * p.g_in.bstride_w + t.tx0;
         t.rlo = max(0, -gy0);
@@ -311,29 +326,30 @@ void bottleneck16_kernel(BneckParams p) {
             orow_stride = (uint32_t)p.ow * C;
             obase = out + (long long)cur.b * p.oh * orow_stride;
         }
-        // per-lane element offset of pixel (row ty0 + prow, column ocol), channel g*16; blocks add 2k rows, 32 nbg channels
+        // per-lane element offset of pixel (row ty0 + prow, column ocol), channel g*16; blocks add RPF*k rows, 32 nbg channels
         const uint32_t lane_off = (uint32_t)(geo.ty0 + prow) * orow_stride + (uint32_t)ocol * C + g * 16;
         // Everything this tile stores is inside the block and the image (true except at ragged image edges):
         // then residual loads and stores need no predication and P3 is straight-line code.
-        bool all_ok = geo.tx0 + 16 <= p.ow && geo.ty0 + 16 <= rlim && rmin <= geo.ty0;
+        bool all_ok = geo.tx0 + TS <= p.ow && geo.ty0 + TS <= rlim && rmin <= geo.ty0;
         if (FUSED) {
             const int ox = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + geo.tx0;
-            all_ok = all_ok && ox >= 0 && ox + 16 <= p.W;
+            all_ok = all_ok && ox >= 0 && ox + TS <= p.W;
         }
-        bool ok[8];
+        bool ok[NPB];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) ok[k] = col_ok && (geo.ty0 + 2 * k + prow) >= rmin && (geo.ty0 + 2 * k + prow) < rlim;
-        // residual x of the block (fused form): pixel blocks 0-3 are requested before P2, whose matrix work hides
-        // the latency; blocks 4-7 at the start of P3, ahead of the next tile's input so that they return first
-        uint4 res[8][NBW][2];
+        for (int k = 0; k < NPB; ++k) ok[k] = col_ok && (geo.ty0 + RPF * k + prow) >= rmin && (geo.ty0 + RPF * k + prow) < rlim;
+        // residual x of the block (fused form): the first half of the pixel blocks is requested before P2, whose
+        // matrix work hides the latency; the second half at the start of P3, ahead of the next tile's input so
+        // that they return first
+        uint4 res[NPB][NBW][2];
         auto fetch_residual = [&](int k0) __attribute__((always_inline)) {
             if (!FUSED) return;
 #pragma unroll
-            for (int k = k0; k < k0 + 4; ++k)
+            for (int k = k0; k < k0 + NPB / 2; ++k)
 #pragma unroll
                 for (int j = 0; j < NBW; ++j) {
                     const int nbg = min(wave + 4 * j, NB3 - 1);
-                    const uint4 *r4 = (ok[k] || all_ok) ? (const uint4 *)(rbase + (lane_off + 2 * k * orow_stride + nbg * 32))
+                    const uint4 *r4 = (ok[k] || all_ok) ? (const uint4 *)(rbase + (lane_off + RPF * k * orow_stride + nbg * 32))
                                                         : (const uint4 *)g_zero32;
                     res[k][j][0] = r4[0];
                     res[k][j][1] = r4[1];
@@ -344,29 +360,32 @@ void bottleneck16_kernel(BneckParams p) {
 
         // ================= P2: t2 = ReLU(W2 * t1 + b2) -> xs =================
         {
-            f32x16b acc[4];
+            // wave (rh, nh): output rows rh*TS/2 .. + TS/2 (NP pixel blocks of RPF rows), mid channels nh*32 .. + 32.
+            // Fragment j of a stage holds input rows rh*TS/2 + j .. + RPF at tap column t; pixel block P with tap row r
+            // reads fragment RPF*P + r.
+            f32x16b acc[NP];
             const f32x16b bias2 = load_bias16(kCm + cm0);
-            const unsigned char *L = t1s + ((rh * 8 + prow) * kBT + pcol) * kPS + g * 16;
-            uint4 xf[2][9];
+            const unsigned char *L = t1s + ((rh * (TS / 2) + prow) * kBT + pcol) * kPS + g * 16;
+            uint4 xf[2][NF];
 #pragma unroll
-            for (int j = 0; j < 9; ++j) xf[0][j] = *(const uint4 *)(L + (j * kBT) * kPS);
+            for (int j = 0; j < NF; ++j) xf[0][j] = *(const uint4 *)(L + (j * kBT) * kPS);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int st = 0; st < 12; ++st) {
                 const int t = st / 4, kc = st % 4;
                 const int tn = (st + 1) / 4, kcn = (st + 1) % 4;
 #pragma unroll
-                for (int mm = 0; mm < 12; ++mm) {
-                    const int r = mm >> 2, P = mm & 3;
-                    acc[P] = mfma32<DT>(w2r[(r * 3 + t) * 4 + kc], xf[st & 1][2 * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
-                    if (mm < 9 && st + 1 < 12)
+                for (int mm = 0; mm < 3 * NP; ++mm) {
+                    const int r = mm / NP, P = mm % NP;
+                    acc[P] = mfma32<DT>(w2r[(r * 3 + t) * 4 + kc], xf[st & 1][RPF * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
+                    if (mm < NF && st + 1 < 12)
                         xf[(st + 1) & 1][mm] = *(const uint4 *)(L + (mm * kBT + tn) * kPS + kcn * 32);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
 #pragma unroll
-            for (int P = 0; P < 4; ++P) {
-                const int po = (rh * 8 + 2 * P + prow) * 16 + pcol;
+            for (int P = 0; P < NP; ++P) {
+                const int po = (rh * (TS / 2) + RPF * P + prow) * TS + pcol;
                 uint32_t w[8];
 #pragma unroll
                 for (int k = 0; k < 8; ++k)
@@ -382,7 +401,7 @@ void bottleneck16_kernel(BneckParams p) {
         const uint32_t nit = it + G;
         BItem nxt = cur;
         TileGeo ngeo = geo;
-        fetch_residual(4);
+        fetch_residual(NPB / 2);
         if (nit < items) {
             nxt = decode(nit);
             ngeo = geometry_of(nxt);
@@ -403,7 +422,7 @@ void bottleneck16_kernel(BneckParams p) {
                 for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];
             }
 #pragma unroll
-            for (int bp = 0; bp < 4; ++bp) {                              // pixel blocks 2bp, 2bp+1
+            for (int bp = 0; bp < NPB / 2; ++bp) {                        // pixel blocks 2bp, 2bp+1
                 uint4 tf[2][4];
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
@@ -438,7 +457,7 @@ void bottleneck16_kernel(BneckParams p) {
                             }
                             w[k] = pack2<DT>(lo, hi);
                         }
-                        uint4 *d = (uint4 *)(obase + (lane_off + 2 * kblk * orow_stride + nbg * 32));
+                        uint4 *d = (uint4 *)(obase + (lane_off + RPF * kblk * orow_stride + nbg * 32));
                         d[0] = make_uint4(w[0], w[1], w[2], w[3]);
                         d[1] = make_uint4(w[4], w[5], w[6], w[7]);
                     }
@@ -464,15 +483,19 @@ static size_t w32_off(int taps, int Cin, int Cout) {     // 16-byte units, same 
     return taps * CinP * CoutP / 8;
 }
 
-template <int DT, bool FUSED>
+template <int DT, bool FUSED, int TS>
 static sbnet_status launch_bneck(int C, const BneckParams &p, dim3 grid, hipStream_t s, const char *who) {
     switch (C) {
-        case 64: hipLaunchKernelGGL((bottleneck16_kernel<DT, 64, FUSED>), grid, dim3(256), 0, s, p); break;
-        case 128: hipLaunchKernelGGL((bottleneck16_kernel<DT, 128, FUSED>), grid, dim3(256), 0, s, p); break;
-        case 256: hipLaunchKernelGGL((bottleneck16_kernel<DT, 256, FUSED>), grid, dim3(256), 0, s, p); break;
+        case 64: hipLaunchKernelGGL((bottleneck16_kernel<DT, 64, FUSED, TS>), grid, dim3(256), 0, s, p); break;
+        case 128: hipLaunchKernelGGL((bottleneck16_kernel<DT, 128, FUSED, TS>), grid, dim3(256), 0, s, p); break;
+        case 256: hipLaunchKernelGGL((bottleneck16_kernel<DT, 256, FUSED, TS>), grid, dim3(256), 0, s, p); break;
         default: return fail(SBNET_EUNSUPPORTED, "%s: C must be 64, 128 or 256", who);
     }
     return launch_status(who);
+}
+template <int DT, bool FUSED>
+static sbnet_status launch_bneck_ts(int ts, int C, const BneckParams &p, dim3 grid, hipStream_t s, const char *who) {
+    return ts == 16 ? launch_bneck<DT, FUSED, 16>(C, p, grid, s, who) : launch_bneck<DT, FUSED, 8>(C, p, grid, s, who);
 }
 
 static sbnet_status bneck_entry(const char *who, bool fused, const void *in, void *out, sbnet_dtype dt, int N, int H,
@@ -492,8 +515,8 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
         return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
     if (dt != SBNET_BF16 && dt != SBNET_F16) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be bf16 or f16", who);
     if (Cm != kCm) return fail(SBNET_EUNSUPPORTED, "%s: bottleneck width must be 64", who);
-    if (g_out->bsize_h % 16 || g_out->bsize_w % 16)
-        return fail(SBNET_EUNSUPPORTED, "%s: block sides must be multiples of 16", who);
+    if (g_out->bsize_h % 8 || g_out->bsize_w % 8)
+        return fail(SBNET_EUNSUPPORTED, "%s: block sides must be multiples of 8", who);
     if (!packed_is_mfma(dt, C, Cm)) return fail(SBNET_EUNSUPPORTED, "%s: channel counts must be multiples of 8", who);
     if (cap == 0) return SBNET_OK;
     if (18LL * (fused ? W : g_in->bsize_w) * C >= (1LL << 30)) return fail(SBNET_EUNSUPPORTED, "%s: rows too long", who);
@@ -507,17 +530,36 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
     p.th = g_in->bsize_h; p.tw = g_in->bsize_w; p.oh = g_out->bsize_h; p.ow = g_out->bsize_w;
     p.H = H; p.W = W;
     p.g_in = *g_in; p.g_out = *g_out;
-    p.sub_h = p.oh / 16; p.sub_w = p.ow / 16;
-    p.div_sub = make_fastdiv((uint32_t)p.sub_h * p.sub_w);
-    p.div_subw = make_fastdiv((uint32_t)p.sub_w);
-    const long long items = (long long)cap * p.sub_h * p.sub_w;
-    if (items >= (1LL << 31)) return fail(SBNET_EUNSUPPORTED, "%s: too many work items", who);
-    long long gx = (items + 7) / 8 * 8;
-    if (gx > 256) gx = 256;
-    dim3 grid((unsigned)gx);
+    // Sub-tile side: 16 where the block allows it and the active blocks give at least half of the CUs a
+    // sub-tile of that size; otherwise 8, which quadruples the number of work items at 1.56x the halo overhead
+    // and shortens the latency chain of each.  Only the device knows the active count, so both variants are
+    // launched with complementary ranges of it and one of them returns at once (a few microseconds).
+    const bool can16 = g_out->bsize_h % 16 == 0 && g_out->bsize_w % 16 == 0;
+    const long long kSmall = 128;
     hipStream_t s = (hipStream_t)stream;
-    if (dt == SBNET_BF16) return fused ? launch_bneck<SBNET_BF16, true>(C, p, grid, s, who) : launch_bneck<SBNET_BF16, false>(C, p, grid, s, who);
-    return fused ? launch_bneck<SBNET_F16, true>(C, p, grid, s, who) : launch_bneck<SBNET_F16, false>(C, p, grid, s, who);
+    for (int ts = 16; ts >= 8; ts -= 8) {
+        if (ts == 16 && !can16) continue;
+        p.per16 = can16 ? (p.oh / 16) * (p.ow / 16) : 0;
+        if (ts == 16) { p.lo = kSmall + 1; p.hi = (1LL << 62); }
+        else { p.lo = 0; p.hi = can16 ? kSmall : (1LL << 62); }
+        if (can16 && ts == 16 && (long long)cap * p.per16 <= kSmall) continue;       // can never be chosen
+        p.sub_h = p.oh / ts; p.sub_w = p.ow / ts;
+        p.div_sub = make_fastdiv((uint32_t)p.sub_h * p.sub_w);
+        p.div_subw = make_fastdiv((uint32_t)p.sub_w);
+        const long long items = (long long)cap * p.sub_h * p.sub_w;
+        if (items >= (1LL << 31)) return fail(SBNET_EUNSUPPORTED, "%s: too many work items", who);
+        long long gx = (items + 7) / 8 * 8;
+        if (gx > 256) gx = 256;
+        if (ts == 8 && can16 && gx > (kSmall * 4 + 7) / 8 * 8) gx = (kSmall * 4 + 7) / 8 * 8;   // never more items than that
+        dim3 grid((unsigned)gx);
+        sbnet_status st;
+        if (dt == SBNET_BF16)
+            st = fused ? launch_bneck_ts<SBNET_BF16, true>(ts, C, p, grid, s, who) : launch_bneck_ts<SBNET_BF16, false>(ts, C, p, grid, s, who);
+        else
+            st = fused ? launch_bneck_ts<SBNET_F16, true>(ts, C, p, grid, s, who) : launch_bneck_ts<SBNET_F16, false>(ts, C, p, grid, s, who);
+        if (st != SBNET_OK) return st;
+    }
+    return SBNET_OK;
 }
 
 extern "C" sbnet_status sbnet_bottleneck_on_tiles(const void *tiles_in, sbnet_dtype dtype, int H, int W, int C, int Cm,

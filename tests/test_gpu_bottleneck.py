@@ -41,6 +41,10 @@ UNIT_CASES = [
     (1, 64, 32, 64, 16, "f16"),
     (1, 64, 96, 256, 32, "bf16"),     # four 16x16 sub-tiles per block
     (1, 40, 40, 64, 32, "f16"),       # sub-tiles hanging over the image edge
+    (2, 40, 24, 256, 8, "bf16"),      # 8 x 8 blocks: the 8-pixel sub-tile variant
+    (1, 37, 29, 64, 8, "f16"),        # ... with ragged image edges
+    (1, 48, 72, 128, 24, "bf16"),     # block side a multiple of 8 only: nine 8 x 8 sub-tiles per block
+    (3, 160, 192, 64, 16, "bf16"),    # 360 blocks: at density 1.0 and 0.3 the device picks different variants
 ]
 
 
@@ -127,11 +131,11 @@ def test_stack_of_units_with_two_buffers():
 
 
 def test_unit_composed_from_single_calls_for_small_blocks():
-    """Block size 8 is not taken by the fused kernel (SBNET_EUNSUPPORTED); the unit composed of
-    gather, three conv_on_tiles calls, zero_outside and scatter-add gives the oracle's result."""
-    step("bottleneck composed, bo=8")
+    """Blocks whose sides are no multiple of 8 are not taken by the fused kernel (SBNET_EUNSUPPORTED); the unit
+    composed of gather, three conv_on_tiles calls, zero_outside and scatter-add gives the oracle's result."""
+    step("bottleneck composed, bo=4")
     r = gen.rng_for(4, 8)
-    N, H, W, C, bo = 1, 40, 24, 64, 8
+    N, H, W, C, bo = 1, 40, 24, 64, 4
     g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
     x = gen.activations(r, (N, H, W, C), "bf16")
     ws = gen.bottleneck_weights(r, C, 64, "bf16")
