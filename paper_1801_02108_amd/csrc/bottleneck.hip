@@ -20,6 +20,16 @@
 //       as the stand-alone 3x3 tile kernel); t2 goes to LDS.
 //   P3  t3 = W3 t2 + b3; fused form: y = x + t3 on the block's pixels (the residual x is re-read
 //       from global memory, where it was fetched moments ago for P1); on-tiles form: t3 is stored.
+//       A wave owns 64 (or 32) neighbouring output channels.  In the MFMA result layout a lane holds
+//       16 channels of one pixel, so loads and stores from it would be 16-byte pieces 2*C bytes
+//       apart, one memory request each.  t3 is therefore rounded to the storage type (as the tile
+//       stack of the unfused path would hold it) and transposed through a wave-private LDS area
+//       (the space of t1, dead by then): eight neighbouring lanes then hold the wave's 128 contiguous
+//       bytes of one pixel, the residual is read and the sum stored in that layout, whole cache lines
+//       per request.  Fused and unfused paths thereby give bit-identical results.
+// Global memory is reached through buffer descriptors that cover one sample (or one tile): rows outside
+// the image fall outside the descriptor, columns outside get an out-of-range offset, and the hardware
+// returns zeros for such loads and drops such stores, so no memory operation needs a branch or predicate.
 // HBM traffic per sub-tile is the input tile once and the output block once.
 #include <type_traits>
 
@@ -66,10 +76,18 @@ struct BItem {
     int si, sj, n, by, bx;
 };
 
-// 32 bytes of zeros for lanes whose pixel lies outside the image: they load from here, so the loads of a tile
-// need no branches (straight-line code keeps the compiler's wait counts exact).  Deliberately not const: a
-// constant-address-space object would turn the selected pointers, and with them the loads, into flat ones.
-__device__ __align__(16) uint4 g_zero32[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+constexpr uint32_t kBufWord3B = 0x00020000u;     // raw buffer descriptor, 32-bit data format
+constexpr uint32_t kOutOfRangeB = 0x80000000u;   // offset beyond any descriptor this kernel builds
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4b;
+__device__ __forceinline__ uint4 bload16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    const u32x4b v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void bstore16(__amdgpu_buffer_rsrc_t r, uint32_t off, uint4 d) {
+    u32x4b v;
+    v[0] = d.x; v[1] = d.y; v[2] = d.z; v[3] = d.w;
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 0);
+}
 
 __device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v), 0); }
 
@@ -91,7 +109,12 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NBLK1 = (kBTPx + 31) / 32;   // 11 pixel blocks in P1
     constexpr int NBPW1 = (NBLK1 + 3) / 4;     // ... per wave
     constexpr int NVX = (kBTPx * 8 + 255) / 256;   // 16-byte staging vectors per thread and chunk
-    __shared__ __align__(16) unsigned char t1s[kBTPx * kPS];
+    constexpr int OPS = NBW * 64 + 16;         // LDS bytes per pixel of a wave's P3 results (+16 B pad)
+    constexpr int CPP = NBW * 4;               // 16-byte pieces per pixel of those
+    constexpr int PPI = 64 / CPP;              // pixels per wave instruction in the store layout
+    constexpr int NI = 64 / PPI;               // instructions per pass (64 pixels)
+    constexpr int T1B = kBTPx * kPS > 4 * 64 * OPS ? kBTPx * kPS : 4 * 64 * OPS;
+    __shared__ __align__(16) unsigned char t1s[T1B];             // t1; in P3 the four waves' result staging
     __shared__ __align__(16) unsigned char xs[kBTPx * kPS];      // one 64-channel chunk of x in P1, t2 afterwards
     __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];             // conv1 weights, 32x32x16 operand order
     __shared__ __align__(16) uint4 w3s[NB3 * 4 * 64];            // conv3 weights, [block of 32 outputs][k-step][lane]
@@ -132,10 +155,14 @@ void bottleneck16_kernel(BneckParams p) {
 
     // ---- geometry of a sub-tile: origin in memory and the rows / columns that exist and lie inside the image
     struct TileGeo {
-        const uint16_t *xin;
+        __amdgpu_buffer_rsrc_t xrs;     // the sample (fused) or tile that holds the sub-tile
+        uint32_t xorg;                  // byte offset of the sub-tile's pixel (0, 0) in it; wraps below zero above / left of the image
+        int gx0;                        // image column of sub-tile column 0 (on tiles: tile column)
         int rlo, rhi, clo, chi, ty0, tx0;
     };
-    const int row_stride = (FUSED ? p.W : p.tw) * C;                      // elements between rows of the input
+    const int in_w = FUSED ? p.W : p.tw;                                  // pixels per row of the addressed array
+    const int row_stride = in_w * C;                                      // elements between rows of the input
+    const uint32_t in_bytes = (uint32_t)(FUSED ? p.H : p.th) * row_stride * 2u;
     auto geometry_of = [&](const BItem &c) __attribute__((always_inline)) {
         TileGeo t;
         t.ty0 = c.si * TS;
@@ -146,8 +173,11 @@ void bottleneck16_kernel(BneckParams p) {
         t.rhi = min(min(kBT, p.th - t.ty0), p.H - gy0);
         t.clo = max(0, -gx0);
         t.chi = min(min(kBT, p.tw - t.tx0), p.W - gx0);
-        if (FUSED) t.xin = in + ((long long)c.n * p.H + gy0) * row_stride + (long long)gx0 * C;
-        else t.xin = in + ((long long)c.b * p.th + t.ty0) * row_stride + (long long)t.tx0 * C;
+        const uint16_t *base = FUSED ? in + (long long)c.n * p.H * row_stride : in + (long long)c.b * p.th * row_stride;
+        const int y0 = FUSED ? gy0 : t.ty0, x0 = FUSED ? gx0 : t.tx0;
+        t.xrs = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)in_bytes, (int)kBufWord3B);
+        t.xorg = (uint32_t)(y0 * row_stride + x0 * C) * 2u;
+        t.gx0 = x0;
         return t;
     };
 
@@ -164,10 +194,11 @@ void bottleneck16_kernel(BneckParams p) {
             const int v = tid + k * 256;
             const int px = v >> 3, c8 = v & 7;
             const int row = px / kBT, col = px - row * kBT;
-            const uint32_t off = (uint32_t)(row * row_stride + col * C + c8 * 8 + chunk * 64);
-            const bool ok = v < kBTPx * 8 && row >= t.rlo && row < t.rhi && col >= t.clo && col < t.chi;
-            // no branch: positions outside the image (and the unused tail of the last vector) read zeros
-            const uint4 val = *(ok ? (const uint4 *)(t.xin + off) : (const uint4 *)g_zero32);
+            const uint32_t off = t.xorg + (uint32_t)(row * row_stride + col * C + c8 * 8 + chunk * 64) * 2u;
+            // rows outside the image are outside the descriptor; columns outside would wrap into the neighbouring
+            // row, so they (and the unused tail of the last vector) get the out-of-range offset: zeros either way
+            const bool ok = v < kBTPx * 8 && (uint32_t)(t.gx0 + col) < (uint32_t)in_w;
+            const uint4 val = bload16(t.xrs, ok ? off : kOutOfRangeB);
             if (slot == 0) sx0[k] = val;
             else sx1[k] = val;
         }
@@ -304,59 +335,54 @@ void bottleneck16_kernel(BneckParams p) {
         }
         __syncthreads();
 
-        // ---- output addressing of this lane's pixels (pixel block k: rows 2k + prow, column pcol) and,
-        //      for the fused form, the loader of the residual x
-        const int ocol = geo.tx0 + pcol;
-        int rmin = 0, rlim = p.oh;
-        bool col_ok = ocol < p.ow;
-        uint16_t *obase;                  // wave-uniform: output row 0 of this block, column 0, channel 0
-        const uint16_t *rbase = nullptr;  // same position in x (residual)
-        uint32_t orow_stride;             // elements between output rows
-        if (FUSED) {
-            const int oy0 = p.g_out.boffset_h + cur.by * p.g_out.bstride_h;
-            const int ox0 = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w;
-            col_ok = col_ok && (ox0 + ocol) >= 0 && (ox0 + ocol) < p.W;
-            rmin = max(0, -oy0);
-            rlim = min(rlim, p.H - oy0);
-            orow_stride = (uint32_t)p.W * C;
-            const long long org = (((long long)cur.n * p.H + oy0) * p.W + ox0) * C;
-            obase = out + org;
-            rbase = in + org;
-        } else {
-            orow_stride = (uint32_t)p.ow * C;
-            obase = out + (long long)cur.b * p.oh * orow_stride;
+        // ---- where this tile's results go and, for the fused form, where the residual x comes from.  Layout of
+        //      P3's memory accesses: instruction i of a pass (64 pixels = pixel blocks 2bp, 2bp+1) covers pixels
+        //      i*PPI + lane/CPP of the pass, 16-byte piece lane%CPP of the wave's channels.
+        const int out_w = FUSED ? p.W : p.ow;
+        __amdgpu_buffer_rsrc_t yrs;
+        uint32_t yorg;                   // byte offset of the sub-tile's output pixel (0, 0), first channel of the wave
+        int ox;                          // image column of sub-tile column 0 (on tiles: block column)
+        {
+            uint16_t *ybase = out;
+            int oy;
+            if (FUSED) {
+                oy = p.g_out.boffset_h + cur.by * p.g_out.bstride_h + geo.ty0;
+                ox = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + geo.tx0;
+                ybase += (long long)cur.n * p.H * p.W * C;
+            } else {
+                oy = geo.ty0;
+                ox = geo.tx0;
+                ybase += (long long)cur.b * p.oh * p.ow * C;
+            }
+            const uint32_t ybytes = (uint32_t)(FUSED ? p.H : p.oh) * out_w * C * 2u;
+            yrs = __builtin_amdgcn_make_buffer_rsrc((void *)ybase, 0, (int)ybytes, (int)kBufWord3B);
+            yorg = (uint32_t)((oy * out_w + ox) * C + wave * NBW * 32) * 2u;
         }
-        // per-lane element offset of pixel (row ty0 + prow, column ocol), channel g*16; blocks add RPF*k rows, 32 nbg channels
-        const uint32_t lane_off = (uint32_t)(geo.ty0 + prow) * orow_stride + (uint32_t)ocol * C + g * 16;
-        // Everything this tile stores is inside the block and the image (true except at ragged image edges):
-        // then residual loads and stores need no predication and P3 is straight-line code.
-        bool all_ok = geo.tx0 + TS <= p.ow && geo.ty0 + TS <= rlim && rmin <= geo.ty0;
-        if (FUSED) {
-            const int ox = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + geo.tx0;
-            all_ok = all_ok && ox >= 0 && ox + TS <= p.W;
-        }
-        bool ok[NPB];
-#pragma unroll
-        for (int k = 0; k < NPB; ++k) ok[k] = col_ok && (geo.ty0 + RPF * k + prow) >= rmin && (geo.ty0 + RPF * k + prow) < rlim;
-        // residual x of the block (fused form): the first half of the pixel blocks is requested before P2, whose
-        // matrix work hides the latency; the second half at the start of P3, ahead of the next tile's input so
-        // that they return first
-        uint4 res[NPB][NBW][2];
-        auto fetch_residual = [&](int k0) __attribute__((always_inline)) {
+        // Rows below the image are outside the descriptors by themselves; columns outside and (C = 64) the channel
+        // blocks of waves without work get the out-of-range offset.
+        auto out_offset = [&](int bp, int i) __attribute__((always_inline)) {
+            int ln = lane;
+            asm volatile("" : "+v"(ln));     // opaque: recomputed at every use; kept, the 4 * NI offsets would be spilled
+            const int q = i * PPI + ln / CPP;                      // pixel of the pass
+            const int row = RPF * (2 * bp + (q >> 5)) + ((q & 31) >> LOGTS), col = q & (TS - 1);
+            const bool ok = wave * NBW < NB3 && (uint32_t)(ox + col) < (uint32_t)out_w;
+            return ok ? yorg + (uint32_t)((row * out_w + col) * C) * 2u + (ln % CPP) * 16 : kOutOfRangeB;
+        };
+        // residual x of the block (fused form), in that layout: the passes of the first half are requested before P2,
+        // whose matrix work hides the latency; the rest at the start of P3, ahead of the next tile's input so that
+        // they return first
+        constexpr int NPASS = NPB / 2;
+        constexpr int NPASS0 = (NPASS + 1) / 2;
+        uint4 rres[NPASS][NI];
+        auto fetch_residual = [&](int bp0, int bp1) __attribute__((always_inline)) {
             if (!FUSED) return;
 #pragma unroll
-            for (int k = k0; k < k0 + NPB / 2; ++k)
+            for (int bp = bp0; bp < bp1; ++bp)
 #pragma unroll
-                for (int j = 0; j < NBW; ++j) {
-                    const int nbg = min(wave + 4 * j, NB3 - 1);
-                    const uint4 *r4 = (ok[k] || all_ok) ? (const uint4 *)(rbase + (lane_off + RPF * k * orow_stride + nbg * 32))
-                                                        : (const uint4 *)g_zero32;
-                    res[k][j][0] = r4[0];
-                    res[k][j][1] = r4[1];
-                }
+                for (int i = 0; i < NI; ++i) rres[bp][i] = bload16(geo.xrs, out_offset(bp, i));     // x and y have one shape
             __builtin_amdgcn_sched_barrier(0);
         };
-        fetch_residual(0);
+        fetch_residual(0, NPASS0);
 
         // ================= P2: t2 = ReLU(W2 * t1 + b2) -> xs =================
         {
@@ -401,7 +427,7 @@ void bottleneck16_kernel(BneckParams p) {
         const uint32_t nit = it + G;
         BItem nxt = cur;
         TileGeo ngeo = geo;
-        fetch_residual(NPB / 2);
+        fetch_residual(NPASS0, NPASS);
         if (nit < items) {
             nxt = decode(nit);
             ngeo = geometry_of(nxt);
@@ -409,63 +435,67 @@ void bottleneck16_kernel(BneckParams p) {
             if (NCH > 1) fetch_chunk(ngeo, 1, Slot1{});
         }
 
-        // ================= P3: t3 = W3 t2 + b3 (+ x), two pixel blocks at a time =================
-        auto p3 = [&](auto fast_tag) __attribute__((always_inline)) {
-            constexpr bool FAST = decltype(fast_tag)::value;
-            f32x16b bias3[NBW];
+        // ================= P3: t3 = W3 t2 + b3 (+ x), two pixel blocks (64 pixels) per pass =================
+        {
             uint4 w3r[4][NBW];
 #pragma unroll
             for (int j = 0; j < NBW; ++j) {
-                const int nbg = min(wave + 4 * j, NB3 - 1);
-                bias3[j] = load_bias16(2 * kCm + nbg * 32 + g * 16);
+                const int nbg = min(wave * NBW + j, NB3 - 1);             // this wave's neighbouring blocks of 32 channels
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];
             }
+            unsigned char *ost = t1s + wave * (64 * OPS);                 // t1 is dead: the wave's private staging area
 #pragma unroll
-            for (int bp = 0; bp < NPB / 2; ++bp) {                        // pixel blocks 2bp, 2bp+1
+            for (int bp = 0; bp < NPASS; ++bp) {
                 uint4 tf[2][4];
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks)
                         tf[u][ks] = *(const uint4 *)(xs + ((2 * bp + u) * 32 + m) * kPS + ks * 32 + g * 16);
-                f32x16b acc[2][NBW];
+                f32x16b acc[2][NBW];     // start from the bias (re-read from LDS per pass: holding it would cost 32 registers)
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int j = 0; j < NBW; ++j) {
+                        int bi = 2 * kCm + min(wave * NBW + j, NB3 - 1) * 32 + g * 16;
+                        asm volatile("" : "+v"(bi));                      // opaque: one read per use, not one copy kept
+                        acc[u][j] = load_bias16(bi);
+                    }
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
                     for (int u = 0; u < 2; ++u)
 #pragma unroll
-                        for (int j = 0; j < NBW; ++j)
-                            acc[u][j] = mfma32<DT>(w3r[ks][j], tf[u][ks], ks == 0 ? bias3[j] : acc[u][j]);
+                        for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(w3r[ks][j], tf[u][ks], acc[u][j]);
+                // MFMA layout -> LDS: lane (g, m) holds channels j*32 + g*16 .. + 16 of pixel u*32 + m
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int j = 0; j < NBW; ++j) {
-                        const int nbg = wave + 4 * j;
-                        const int kblk = 2 * bp + u;
-                        if (nbg >= NB3) continue;                          // wave-uniform (C = 64 only)
-                        if (!FAST && !ok[kblk]) continue;
                         uint32_t w[8];
 #pragma unroll
-                        for (int k = 0; k < 8; ++k) {
-                            float lo = acc[u][j][2 * k], hi = acc[u][j][2 * k + 1];
-                            if (FUSED) {
-                                const uint4 rv = res[kblk][j][k >> 2];
-                                const uint32_t rw = (k & 3) == 0 ? rv.x : (k & 3) == 1 ? rv.y : (k & 3) == 2 ? rv.z : rv.w;
-                                lo += unpack_lo<DT>(rw);
-                                hi += unpack_hi<DT>(rw);
-                            }
-                            w[k] = pack2<DT>(lo, hi);
-                        }
-                        uint4 *d = (uint4 *)(obase + (lane_off + RPF * kblk * orow_stride + nbg * 32));
+                        for (int k = 0; k < 8; ++k) w[k] = pack2<DT>(acc[u][j][2 * k], acc[u][j][2 * k + 1]);
+                        uint4 *d = (uint4 *)(ost + (u * 32 + m) * OPS + j * 64 + g * 32);
                         d[0] = make_uint4(w[0], w[1], w[2], w[3]);
                         d[1] = make_uint4(w[4], w[5], w[6], w[7]);
                     }
+                // LDS -> store layout (LDS serves one wave's accesses in order: no wait between the two), add, store
+#pragma unroll
+                for (int i = 0; i < NI; ++i) {
+                    uint4 v = *(const uint4 *)(ost + (i * PPI + lane / CPP) * OPS + (lane % CPP) * 16);
+                    if (FUSED) {
+                        const uint4 rv = rres[bp][i];
+                        v.x = pack2<DT>(unpack_lo<DT>(v.x) + unpack_lo<DT>(rv.x), unpack_hi<DT>(v.x) + unpack_hi<DT>(rv.x));
+                        v.y = pack2<DT>(unpack_lo<DT>(v.y) + unpack_lo<DT>(rv.y), unpack_hi<DT>(v.y) + unpack_hi<DT>(rv.y));
+                        v.z = pack2<DT>(unpack_lo<DT>(v.z) + unpack_lo<DT>(rv.z), unpack_hi<DT>(v.z) + unpack_hi<DT>(rv.z));
+                        v.w = pack2<DT>(unpack_lo<DT>(v.w) + unpack_lo<DT>(rv.w), unpack_hi<DT>(v.w) + unpack_hi<DT>(rv.w));
+                    }
+                    bstore16(yrs, out_offset(bp, i), v);
+                }
             }
-        };
-        if (all_ok) p3(std::true_type{});
-        else p3(std::false_type{});
-        __syncthreads();                                                  // t2 (in xs) consumed before the next tile's chunk 0
+        }
+        __syncthreads();                                                  // t2 (in xs) and the staging area (t1s) free for the next tile
         cur = nxt;
         geo = ngeo;
     }
@@ -519,7 +549,10 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
         return fail(SBNET_EUNSUPPORTED, "%s: block sides must be multiples of 8", who);
     if (!packed_is_mfma(dt, C, Cm)) return fail(SBNET_EUNSUPPORTED, "%s: channel counts must be multiples of 8", who);
     if (cap == 0) return SBNET_OK;
-    if (18LL * (fused ? W : g_in->bsize_w) * C >= (1LL << 30)) return fail(SBNET_EUNSUPPORTED, "%s: rows too long", who);
+    // byte offsets inside one sample (fused) or one tile are kept in 32 bits and checked by the hardware against
+    // a buffer descriptor of that size
+    if ((fused ? (long long)H * W : (long long)g_in->bsize_h * g_in->bsize_w) * C >= (1LL << 30))
+        return fail(SBNET_EUNSUPPORTED, "%s: a sample (or tile) must stay below 2^30 elements", who);
 
     BneckParams p = {};
     p.in = in; p.out = out;

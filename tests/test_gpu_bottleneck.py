@@ -74,7 +74,8 @@ def test_bottleneck_on_tiles_and_fused(N, H, W, C, bo, dtype):
         y = dx.clone()
         sb.sparse_scatter(t3, d_idx, d_cnt, g_out, y, add=True)
         ref = orc.sparse_bottleneck_tiled(x, idx, ogeom(g_in), ogeom(g_out), *ws)
-        assert_close(to_host(y), ref, CONV_TOL[dtype], "unfused unit")
+        unfused = to_host(y)
+        assert_close(unfused, ref, CONV_TOL[dtype], "unfused unit")
         # --- fused unit into a second buffer holding other values at inactive pixels
         y0 = gen.activations(r, (N, H, W, C), dtype)
         y = to_dev(y0, dtype)
@@ -83,6 +84,8 @@ def test_bottleneck_on_tiles_and_fused(N, H, W, C, bo, dtype):
         bm = orc.block_mask(idx, ogeom(g_out), N, H, W)
         assert np.array_equal(got[~bm], y0[~bm])                   # inactive pixels neither read nor written
         assert_close(got[bm], ref[bm], CONV_TOL[dtype], "fused unit")
+        # the fused kernel rounds t3 to the storage type before the add, as the tile stack of the unfused path does
+        assert np.array_equal(got[bm], unfused[bm])
         if dens == 1.0:                                            # every block active: the dense unit
             assert_close(got, orc.sparse_bottleneck_dense(x, idx, ogeom(g_out), *ws), CONV_TOL[dtype], "dense unit")
 
