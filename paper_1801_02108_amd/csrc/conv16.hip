@@ -201,15 +201,8 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
     for (int k = 0; k < NV; ++k) fetch1(src, k);     // first: the longest latency of the prologue
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- weights of this wave: every k-step of its 32 output channels
-    uint4 wreg[KS];
-    {
-        const uint4 *wp = (const uint4 *)p.w + p.w32_offset + ((size_t)ng * KS * 2 + nh) * 64 + lane;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) wreg[ks] = wp[(size_t)ks * 128];
-    }
     const int ch0 = ng * 64 + nh * 32 + g * 16;      // first of this lane's 16 output channels
-    f32x16 biasv;
+    f32x16 biasv;           // requested before the weights: the first MFMA needs it, and loads return in order
 #pragma unroll
     for (int k = 0; k < 16; ++k) biasv[k] = 0.f;
     if (p.bias) {                                    // Cout % 8 == 0: eight at a time
@@ -219,6 +212,20 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
                 const float4 b0 = *(const float4 *)(p.bias + ch0 + h * 8), b1 = *(const float4 *)(p.bias + ch0 + h * 8 + 4);
                 biasv[h * 8 + 0] = b0.x; biasv[h * 8 + 1] = b0.y; biasv[h * 8 + 2] = b0.z; biasv[h * 8 + 3] = b0.w;
                 biasv[h * 8 + 4] = b1.x; biasv[h * 8 + 5] = b1.y; biasv[h * 8 + 6] = b1.z; biasv[h * 8 + 7] = b1.w;
+            }
+    }
+    // ---- weights of this wave: every k-step of its 32 output channels, requested in the order the stages of a tile
+    //      use them: the first tile's matrix work starts when the first of them have landed and runs while the
+    //      rest stream in
+    uint4 wreg[KS];
+    {
+        const uint4 *wp = (const uint4 *)p.w + p.w32_offset + ((size_t)ng * KS * 2 + nh) * 64 + lane;
+#pragma unroll
+        for (int st = 0; st < NST; ++st)
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const int ks = (r * 3 + st / KC) * KC + st % KC;
+                wreg[ks] = wp[(size_t)ks * 128];
             }
     }
     // ReLU as an integer max on the float bits (negative floats are negative integers); without
@@ -243,19 +250,20 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
     nx1 = resolve(nx1);
 #pragma unroll
     for (int k = 0; k < NV; ++k) stash1(0, k);
-    src = source(nx1);
-#pragma unroll
-    for (int k = 0; k < NV; ++k) fetch1(src, k);     // tile 1 (or a repeat of the last tile) rides through tile 0's matrix work
-    // Every load of the prologue but those has landed before the loop is entered: the loop's wait counts are then
-    // exact from the first iteration on.
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (NV & 15) | ((NV >> 4) << 14));      // vmcnt(NV)
-    __syncthreads();
 
+    // One tile.  A workgroup that has a single tile (the usual case below one tile per CU) runs a copy of this
+    // code of its own (SINGLE) that does no staging work for following tiles and is entered while the weights are
+    // still on their way: loads return in order and they were requested in the order of use, so the matrix work
+    // of a stage waits only for its own weights and overlaps the arrival of the rest.
     int buf = 0;
-    for (uint32_t it = first; it < items; it += G) {
-        const Item16 nx3 = request(min(it + 3 * G, last));       // used two iterations from now
-        nx2 = resolve(nx2);
-        src = source(nx2);
+    auto tile = [&](uint32_t it, auto single_tag) __attribute__((always_inline)) {
+        constexpr bool SINGLE = decltype(single_tag)::value;
+        Item16 nx3 = nx2;
+        if (!SINGLE) {
+            nx3 = request(min(it + 3 * G, last));                // used two iterations from now
+            nx2 = resolve(nx2);
+            src = source(nx2);
+        }
 
         // ---- 16x16 outputs x 64 channels; this wave: 4 output row pairs x 32 channels.
         // Fragment j of a stage holds input rows rh*8 + j, rh*8 + j + 1 (j = 0..8) at tap column t;
@@ -281,8 +289,10 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
                                           (st == 0 && r == 0) ? biasv : acc[P]);
                 if (mm < 9 && st + 1 < NST)
                     xf[(st + 1) & 1][mm] = *(const uint4 *)(L + (mm * kT16 + tn) * PS + kcn * 32);
-                if (mm == 9 && st < NV) stash1(buf ^ 1, st);
-                if (mm == 10 && st < NV) fetch1(src, st);
+                if (!SINGLE) {
+                    if (mm == 9 && st < NV) stash1(buf ^ 1, st);
+                    if (mm == 10 && st < NV) fetch1(src, st);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -345,12 +355,27 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
             }
         }
 
+        if (!SINGLE) {
+            __syncthreads();
+            buf ^= 1;
+            cur = nx1;
+            nx1 = nx2;
+            nx2 = nx3;
+        }
+    };
+    if (first + G >= items) {                    // workgroup-uniform
         __syncthreads();
-        buf ^= 1;
-        cur = nx1;
-        nx1 = nx2;
-        nx2 = nx3;
+        tile(first, std::true_type{});
+        return;
     }
+    src = source(nx1);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) fetch1(src, k);     // tile 1 rides through tile 0's matrix work
+    // Every load of the prologue but those has landed before the loop is entered: the loop's wait counts then do
+    // not have to allow for prologue loads still in flight.
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (NV & 15) | ((NV >> 4) << 14));      // vmcnt(NV)
+    __syncthreads();
+    for (uint32_t it = first; it < items; it += G) tile(it, std::false_type{});
 }
 
 template <int DT, int CIN>
