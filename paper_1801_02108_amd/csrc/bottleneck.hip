@@ -86,7 +86,9 @@ __device__ __forceinline__ uint4 bload16(__amdgpu_buffer_rsrc_t r, uint32_t off)
 __device__ __forceinline__ void bstore16(__amdgpu_buffer_rsrc_t r, uint32_t off, uint4 d) {
     u32x4b v;
     v[0] = d.x; v[1] = d.y; v[2] = d.z; v[3] = d.w;
-    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 0);
+    // non-temporal: the results are not read again by this kernel and should not push the input, whose block
+    // pixels are read a second time as the residual, out of L2
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 2);
 }
 
 __device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v), 0); }
