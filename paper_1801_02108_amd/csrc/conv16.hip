@@ -67,7 +67,9 @@ __device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t o
 __device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, uint32_t off, uint4 d) {
     u32x4 v;
     v[0] = d.x; v[1] = d.y; v[2] = d.z; v[3] = d.w;
-    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 0);
+    // non-temporal: the results are not read again here and should not push input lines, which neighbouring
+    // tiles read again for their halos, out of L2
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 2);
 }
 
 // ADD (fused form only): the results are added to what the output holds.  A template parameter rather than a
