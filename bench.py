@@ -76,7 +76,7 @@ def run_units(args):
     if cfg == "cfg3":
         N, H, W, bos, targets, n_units, kind = 1, 400, 352, [16], [0.10, 0.30, 1.0], 1, "road"
     elif cfg == "cfg4":
-        N, H, W, bos, n_units, kind = 4, 800, 704, [16, 32], 1, "blob"
+        N, H, W, bos, n_units, kind = 4, 800, 704, [8, 16, 32], 1, "blob"
         targets = [0.01, 0.02, 0.05, 0.10, 0.20, 0.30, 0.50, 0.70, 0.85, 1.0]
     else:
         N, H, W, bos, targets, n_units, kind = 8, 800, 704, [16], [0.15, 1.0], 8, "lowres"
@@ -198,15 +198,29 @@ def run_units(args):
         head = [r_ for r_ in rows if r_["target"] == 0.15][0]
     elif cfg == "cfg3":
         head = [r_ for r_ in rows if r_["target"] == 0.10][0]
+    traffic = None
+    if cfg == "cfg5":
+        try:
+            traffic = json.load(open(os.path.join(ROOT, "profiles", "traffic.json"))).get("bottleneck16_kernel_fused/cfg5_15pct")
+        except Exception:
+            traffic = None
+    # crossover against the dense path (all blocks active), per block size: the smallest density of the sweep at
+    # which the sparse step is no faster than the dense one; null when it is faster at every density below 100 %
+    crossover = {}
+    for bo in bos:
+        rb = [r_ for r_ in rows if r_["block"] == bo]
+        dense_b = [r_["step_ms"] for r_ in rb if r_["target"] >= 1.0][0]
+        slow = sorted(r_["target"] for r_ in rb if r_["target"] < 1.0 and r_["step_ms"] >= dense_b)
+        crossover[str(bo)] = slow[0] if slow else None
     out = {"metric": "sparse_residual_unit_ms", "value": head["step_ms"], "unit": "ms", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["step_ms"], "higher_is_better": False,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "%s: %d sparse bottleneck unit(s) 256->64->64->256 bf16, N=%d H=%d W=%d, %s mask" % (
                cfg, n_units, N, H, W, kind), "headline_row": head},
-           "rows": rows, "miopen_dense_units_ms": None if miopen_ms is None else round(miopen_ms, 4),
+           "rows": rows, "crossover": crossover, "miopen_dense_units_ms": None if miopen_ms is None else round(miopen_ms, 4),
            "roofline": {"bound": "hbm", "kernel": "bottleneck16_kernel<bf16,256,fused>",
                         "achieved": head["unit_hbm_GBps_algorithmic"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                        "frac": round(head["unit_hbm_GBps_algorithmic"] / PEAK_HBM_GBS, 4), "traffic": None}}
+                        "frac": round(head["unit_hbm_GBps_algorithmic"] / PEAK_HBM_GBS, 4), "traffic": traffic}}
     print(json.dumps(out))
 
 

@@ -108,13 +108,14 @@ def test_config3_full_size_sampled(target):
     assert_close(blocks_of(got, idx[rows], g_out), ref, CONV_TOL["bf16"], "config 3 sampled tiles")
 
 
-def test_stack_shape_batch_of_samples_sampled():
+@pytest.mark.parametrize("bo", [16, 8])
+def test_stack_shape_batch_of_samples_sampled(bo):
     """The shape of the batched configurations at a size the test can hold: N = 4 samples of
     800 x 704 x 256 with a per-sample low-resolution mask (about 15 % active blocks), two units
-    sharing one index list and alternating two buffers."""
-    step("batched stack, sampled")
-    r = gen.rng_for(5)
-    N, H, W, C, bo = 4, 800, 704, 256, 16
+    sharing one index list and alternating two buffers; 16 x 16 and 8 x 8 blocks."""
+    step("batched stack, sampled, bo=%d" % bo)
+    r = gen.rng_for(5, bo)
+    N, H, W, C = 4, 800, 704, 256
     g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
     dev = torch.device("cuda:0")
     tg = torch.Generator(device=dev)
