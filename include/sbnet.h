@@ -172,9 +172,9 @@ sbnet_status sbnet_zero_outside(void *tiles, sbnet_dtype dtype, int H, int W, in
  * for the border rule.  w1, w2, w3 come from sbnet_pack_weights (shapes [1][1][C][Cm],
  * [3][3][Cm][Cm], [1][1][Cm][C]); b1, b2, b3 are device float32 and required.  t1 and t2 are
  * rounded to `dtype` between the layers; sums are fp32.
- * Supported: bf16 / f16, Cm = 64, C in {64, 128, 256}, block sides multiples of 16, input tile =
- * block + one-pixel halo; anything else returns SBNET_EUNSUPPORTED (compose the unit from
- * sbnet_conv_on_tiles instead).
+ * Supported: bf16 / f16, Cm = 64, C in {64, 128, 256}, block sides multiples of 8, input tile =
+ * block + one-pixel halo, one tile below 2^30 elements; anything else returns SBNET_EUNSUPPORTED
+ * (compose the unit from sbnet_conv_on_tiles instead).
  */
 sbnet_status sbnet_bottleneck_on_tiles(const void *tiles_in, sbnet_dtype dtype, int H, int W, int C,
                                        int Cm, const int32_t *indices, const int32_t *count, int cap,
@@ -192,7 +192,9 @@ sbnet_status sbnet_bottleneck_on_tiles(const void *tiles_in, sbnet_dtype dtype, 
  * buffer (SBNET_EINVAL if y == x).  For a stack of units sharing one index list, initialise
  * both buffers with the input once and alternate them: inactive pixels never change, and every
  * active pixel of the buffer being read was written by the previous unit.
- * Same support matrix as sbnet_bottleneck_on_tiles.
+ * t3 is rounded to `dtype` before the add, as the tile stack between sbnet_bottleneck_on_tiles and
+ * sbnet_sparse_scatter holds it: both routes give the same bits.
+ * Same support matrix as sbnet_bottleneck_on_tiles, with one sample (H * W * C) below 2^30 elements.
  */
 sbnet_status sbnet_sparse_bottleneck(const void *x, sbnet_dtype dtype, int N, int H, int W, int C,
                                      int Cm, const int32_t *indices, const int32_t *count, int cap,
