@@ -104,6 +104,8 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NPB = TS * TS / 32;          // 32-pixel blocks of the output sub-tile (8 or 2)
     constexpr int NP = NPB / 2;                // ... per wave in P2: waves split the rows in two halves (4 or 1)
     constexpr int NF = RPF * (NP - 1) + 3;     // LDS fragments per P2 stage (9 or 3)
+    constexpr int W2D = TS == 16 ? 7 : 12;     // stages of conv2 weights requested ahead
+    constexpr int W2R = W2D < 12 ? W2D : 12;   // ... and ring slots holding them
     constexpr int K1 = C / 16;                 // k-steps of conv1
     constexpr int NCH = C / 64;                // 64-channel chunks of the input tile
     constexpr int NB3 = C / 32;                // 32-channel output blocks of conv3
@@ -257,7 +259,65 @@ void bottleneck16_kernel(BneckParams p) {
     __syncthreads();                                 // weights and biases visible to every wave
 
     for (uint32_t it = first; it < items; it += G) {
-        uint4 w2r[36];     // conv2's weights for this tile, requested during the last chunk of P1 (see there)
+        // conv2's weights for this wave's 32 output channels are re-read from L2 for every tile, three fragments per
+        // stage of P2.  16-pixel sub-tiles: a ring of W2R stages, W2D stages requested ahead (holding all 36 fragments
+        // would cost 144 registers that the residual needs); 8-pixel sub-tiles: a stage is too short for that,
+        // everything is requested before P2.
+        uint4 w2s[W2R][3];
+        const uint4 *w2p = (const uint4 *)p.w2 + p.w2_off + (size_t)nh * 64;      // wave-uniform
+        asm volatile("" : "+s"(w2p));      // opaque per iteration: keeps the loads inside the tile loop
+        auto fetch_w2 = [&](int st) __attribute__((always_inline)) {
+#pragma unroll
+            for (int r = 0; r < 3; ++r) w2s[st % W2R][r] = (w2p + ((r * 3 + st / 4) * 4 + st % 4) * 128)[(uint32_t)lane];
+        };
+
+        // ---- where this tile's results go and, for the fused form, where the residual x comes from.  Layout of
+        //      P3's memory accesses: instruction i of a pass (64 pixels = pixel blocks 2bp, 2bp+1) covers pixels
+        //      i*PPI + lane/CPP of the pass, 16-byte piece lane%CPP of the wave's channels.
+        const int out_w = FUSED ? p.W : p.ow;
+        __amdgpu_buffer_rsrc_t yrs;
+        uint32_t yorg;                   // byte offset of the sub-tile's output pixel (0, 0), first channel of the wave
+        int ox;                          // image column of sub-tile column 0 (on tiles: block column)
+        {
+            uint16_t *ybase = out;
+            int oy;
+            if (FUSED) {
+                oy = p.g_out.boffset_h + cur.by * p.g_out.bstride_h + geo.ty0;
+                ox = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + geo.tx0;
+                ybase += (long long)cur.n * p.H * p.W * C;
+            } else {
+                oy = geo.ty0;
+                ox = geo.tx0;
+                ybase += (long long)cur.b * p.oh * p.ow * C;
+            }
+            const uint32_t ybytes = (uint32_t)(FUSED ? p.H : p.oh) * out_w * C * 2u;
+            yrs = __builtin_amdgcn_make_buffer_rsrc((void *)ybase, 0, (int)ybytes, (int)kBufWord3B);
+            yorg = (uint32_t)((oy * out_w + ox) * C + wave * NBW * 32) * 2u;
+        }
+        // Rows below the image are outside the descriptors by themselves; columns outside and (C = 64) the channel
+        // blocks of waves without work get the out-of-range offset.
+        auto out_offset = [&](int bp, int i) __attribute__((always_inline)) {
+            int ln = lane;
+            asm volatile("" : "+v"(ln));     // opaque: recomputed at every use; kept, the 4 * NI offsets would be spilled
+            const int q = i * PPI + ln / CPP;                      // pixel of the pass
+            const int row = RPF * (2 * bp + (q >> 5)) + ((q & 31) >> LOGTS), col = q & (TS - 1);
+            const bool ok = wave * NBW < NB3 && (uint32_t)(ox + col) < (uint32_t)out_w;
+            return ok ? yorg + (uint32_t)((row * out_w + col) * C) * 2u + (ln % CPP) * 16 : kOutOfRangeB;
+        };
+        // residual x of the block (fused form), in that layout.  It is requested in the middle of P1, when half of the
+        // tile's chunks have just come through L2 and the other half is about to: each of its cache lines then crosses
+        // the memory fabric once.  (Requested after P1, half of the block had been evicted again: L2 holds about
+        // 3 microseconds of this kernel's traffic, P1 alone takes 7.)
+        constexpr int NPASS = NPB / 2;
+        uint4 rres[NPASS][NI];
+        auto fetch_residual = [&](int bp0, int bp1) __attribute__((always_inline)) {
+            if (!FUSED) return;
+#pragma unroll
+            for (int bp = bp0; bp < bp1; ++bp)
+#pragma unroll
+                for (int i = 0; i < NI; ++i) rres[bp][i] = bload16(geo.xrs, out_offset(bp, i));     // x and y have one shape
+            __builtin_amdgcn_sched_barrier(0);
+        };
 
         // ================= P1: t1 = ReLU(W1 x + b1), zero outside the image =================
         // x passes through LDS in 64-channel chunks: coalesced global loads -> registers -> xs -> MFMA B operands.
@@ -281,14 +341,12 @@ void bottleneck16_kernel(BneckParams p) {
                     if (c & 1) fetch_chunk(geo, c + 2, Slot1{});
                     else fetch_chunk(geo, c + 2, Slot0{});
                 }
+                if (c == (NCH > 1 ? 1 : 0)) fetch_residual(0, NPASS);
                 if (c == NCH - 1) {
-                    // conv2's weights (this wave's 32 output channels) come from L2 while the last chunk and the
-                    // t1 epilogue run.  They are not kept across tiles: the registers hold the next tile's input
-                    // during P3.  Requested only now so that no input chunk is queued behind them.
-                    const uint4 *wp = (const uint4 *)p.w2 + p.w2_off + (size_t)nh * 64;      // wave-uniform
-                    asm volatile("" : "+s"(wp));      // opaque per iteration: keeps the loads inside the tile loop
+                    // the first stages of conv2's weights come from L2 while the last chunk and the t1 epilogue run;
+                    // requested only now so that no input chunk is queued behind them
 #pragma unroll
-                    for (int ks = 0; ks < 36; ++ks) w2r[ks] = (wp + ks * 128)[(uint32_t)lane];
+                    for (int st = 0; st < (W2D < 12 ? W2D : 12); ++st) fetch_w2(st);
                 }
                 // fragments of k-step k4+1 are read from LDS while the MFMAs of k-step k4 run
                 uint4 af[2][2], bf[2][NBPW1];
@@ -337,55 +395,6 @@ void bottleneck16_kernel(BneckParams p) {
         }
         __syncthreads();
 
-        // ---- where this tile's results go and, for the fused form, where the residual x comes from.  Layout of
-        //      P3's memory accesses: instruction i of a pass (64 pixels = pixel blocks 2bp, 2bp+1) covers pixels
-        //      i*PPI + lane/CPP of the pass, 16-byte piece lane%CPP of the wave's channels.
-        const int out_w = FUSED ? p.W : p.ow;
-        __amdgpu_buffer_rsrc_t yrs;
-        uint32_t yorg;                   // byte offset of the sub-tile's output pixel (0, 0), first channel of the wave
-        int ox;                          // image column of sub-tile column 0 (on tiles: block column)
-        {
-            uint16_t *ybase = out;
-            int oy;
-            if (FUSED) {
-                oy = p.g_out.boffset_h + cur.by * p.g_out.bstride_h + geo.ty0;
-                ox = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + geo.tx0;
-                ybase += (long long)cur.n * p.H * p.W * C;
-            } else {
-                oy = geo.ty0;
-                ox = geo.tx0;
-                ybase += (long long)cur.b * p.oh * p.ow * C;
-            }
-            const uint32_t ybytes = (uint32_t)(FUSED ? p.H : p.oh) * out_w * C * 2u;
-            yrs = __builtin_amdgcn_make_buffer_rsrc((void *)ybase, 0, (int)ybytes, (int)kBufWord3B);
-            yorg = (uint32_t)((oy * out_w + ox) * C + wave * NBW * 32) * 2u;
-        }
-        // Rows below the image are outside the descriptors by themselves; columns outside and (C = 64) the channel
-        // blocks of waves without work get the out-of-range offset.
-        auto out_offset = [&](int bp, int i) __attribute__((always_inline)) {
-            int ln = lane;
-            asm volatile("" : "+v"(ln));     // opaque: recomputed at every use; kept, the 4 * NI offsets would be spilled
-            const int q = i * PPI + ln / CPP;                      // pixel of the pass
-            const int row = RPF * (2 * bp + (q >> 5)) + ((q & 31) >> LOGTS), col = q & (TS - 1);
-            const bool ok = wave * NBW < NB3 && (uint32_t)(ox + col) < (uint32_t)out_w;
-            return ok ? yorg + (uint32_t)((row * out_w + col) * C) * 2u + (ln % CPP) * 16 : kOutOfRangeB;
-        };
-        // residual x of the block (fused form), in that layout: the passes of the first half are requested before P2,
-        // whose matrix work hides the latency; the rest at the start of P3, ahead of the next tile's input so that
-        // they return first
-        constexpr int NPASS = NPB / 2;
-        constexpr int NPASS0 = (NPASS + 1) / 2;
-        uint4 rres[NPASS][NI];
-        auto fetch_residual = [&](int bp0, int bp1) __attribute__((always_inline)) {
-            if (!FUSED) return;
-#pragma unroll
-            for (int bp = bp0; bp < bp1; ++bp)
-#pragma unroll
-                for (int i = 0; i < NI; ++i) rres[bp][i] = bload16(geo.xrs, out_offset(bp, i));     // x and y have one shape
-            __builtin_amdgcn_sched_barrier(0);
-        };
-        fetch_residual(0, NPASS0);
-
         // ================= P2: t2 = ReLU(W2 * t1 + b2) -> xs =================
         {
             // wave (rh, nh): output rows rh*TS/2 .. + TS/2 (NP pixel blocks of RPF rows), mid channels nh*32 .. + 32.
@@ -405,9 +414,10 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
                 for (int mm = 0; mm < 3 * NP; ++mm) {
                     const int r = mm / NP, P = mm % NP;
-                    acc[P] = mfma32<DT>(w2r[(r * 3 + t) * 4 + kc], xf[st & 1][RPF * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
+                    acc[P] = mfma32<DT>(w2s[st % W2R][r], xf[st & 1][RPF * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
                     if (mm < NF && st + 1 < 12)
                         xf[(st + 1) & 1][mm] = *(const uint4 *)(L + (mm * kBT + tn) * kPS + kcn * 32);
+                    if (mm == 3 * NP - 1 && st + W2D < 12) fetch_w2(st + W2D);       // into the slot this stage just freed
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -429,7 +439,6 @@ void bottleneck16_kernel(BneckParams p) {
         const uint32_t nit = it + G;
         BItem nxt = cur;
         TileGeo ngeo = geo;
-        fetch_residual(NPASS0, NPASS);
         if (nit < items) {
             nxt = decode(nit);
             ngeo = geometry_of(nxt);
