@@ -42,8 +42,9 @@ def parse():
                          "per-node instrumentation inflates kernels replayed from a graph)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy: a known-size reference for scaling HBM byte counters")
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"],
-                    help="cfg2 (default) is the headline single 3x3 conv; cfg3/4/5 are the residual-unit workloads")
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "stages"],
+                    help="cfg2 (default) is the headline single 3x3 conv; cfg3/4/5 are the residual-unit workloads; "
+                         "stages = single 3x3 convs, stride 1 and 2, at the backbone's other stage shapes")
     return ap.parse_args()
 
 
@@ -224,6 +225,91 @@ def run_units(args):
     print(json.dumps(out))
 
 
+# ---------------------------------------------------------------------------------------------------
+# single sparse 3x3 convolutions at the other stage shapes of the backbone (Sec. 4), stride 1 and 2
+# ---------------------------------------------------------------------------------------------------
+def run_stages(args):
+    import numpy as np
+    import torch
+    import paper_1801_02108_amd as sb
+    from paper_1801_02108_amd import inputs as gen
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    shapes = [(800, 704, 64, 96, 2, 16), (400, 352, 96, 96, 1, 16), (400, 352, 96, 192, 2, 16),
+              (200, 176, 192, 192, 1, 16), (200, 176, 192, 256, 2, 16), (100, 88, 256, 384, 2, 8)]
+    F = torch.nn.functional
+    rows = []
+    for (H, W, Cin, Cout, s, bo) in shapes:
+        r = gen.rng_for(6, H + Cin + s)
+        g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, s, bo)
+        total = g_out.bcount_h * g_out.bcount_w
+        x = torch.randn((1, H, W, Cin), device=dev).to(torch.bfloat16)
+        y = torch.zeros((1, Ho, Wo, Cout), device=dev, dtype=torch.bfloat16)
+        wp = sb.pack_weights(torch.from_numpy(gen.conv_weights(r, 3, 3, Cin, Cout, "bf16")).to(torch.bfloat16).to(dev))
+        bias = torch.from_numpy(gen.bias_vector(r, Cout)).to(dev)
+        idx = torch.empty((total, 3), dtype=torch.int32, device=dev)
+        cnt = torch.empty((1,), dtype=torch.int32, device=dev)
+        ws = torch.empty((sb.workspace_bytes(1, g_out),), dtype=torch.uint8, device=dev)
+        fields = gen.road_band_fields(r, Ho, Wo, 3)
+
+        def count_active(m_np):
+            sb.reduce_mask(torch.from_numpy(m_np).to(dev), g_out, sb.POOL_AVG, 0.0, idx, cnt, ws)
+            return sb.read_count(cnt, total)
+
+        xt = x.permute(0, 3, 1, 2)
+        wt = torch.randn((Cout, Cin, 3, 3), device=dev).to(torch.bfloat16).contiguous(memory_format=torch.channels_last)
+        for _ in range(3):
+            F.conv2d(xt, wt, stride=s, padding=1)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(20):
+            F.conv2d(xt, wt, stride=s, padding=1)
+        e1.record()
+        torch.cuda.synchronize()
+        miopen_ms = e0.elapsed_time(e1) / 20
+        dense_ms = None
+        for target in (1.0, 0.3, 0.1):
+            if target >= 1.0:
+                m_np = np.ones((1, Ho, Wo), dtype=np.uint8)
+            else:
+                m_np = gen.calibrate(lambda sc: gen.road_band_mask(fields, sc), count_active, total, target, 0.0, 12.0, tol=0.03)[0]
+            m_d = torch.from_numpy(m_np).to(dev)
+            n = count_active(m_np)
+
+            def step():
+                sb.reduce_mask(m_d, g_out, sb.POOL_AVG, 0.0, idx, cnt, ws)
+                sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y, stride=s, relu=True)
+            for _ in range(3):
+                step()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(50):
+                step()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 50
+            e0.record()
+            for _ in range(50):
+                sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y, stride=s, relu=True)
+            e1.record()
+            torch.cuda.synchronize()
+            k_ms = e0.elapsed_time(e1) / 50
+            if target >= 1.0:
+                dense_ms = ms
+            rows.append({"H": H, "W": W, "Cin": Cin, "Cout": Cout, "stride": s, "block": bo, "target": target,
+                         "active_blocks": n, "total_blocks": total, "step_ms": round(ms, 5), "conv_kernel_ms": round(k_ms, 5),
+                         "conv_tflops": round(2.0 * n * bo * bo * 9 * Cin * Cout / k_ms / 1e9, 2),
+                         "speedup_vs_own_dense": round(dense_ms / ms, 3), "miopen_dense_ms": round(miopen_ms, 5)})
+    head = [r_ for r_ in rows if r_["H"] == 400 and r_["stride"] == 2 and r_["target"] == 0.3][0]
+    print(json.dumps({"metric": "sparse_conv_stage_shapes_ms", "value": head["step_ms"], "unit": "ms", "n_gpus": 1,
+                      "steps": 50, "warmup": 3, "ms_per_step": head["step_ms"], "higher_is_better": False, "scaling": "weak",
+                      "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "stages: single sparse 3x3 conv + ReLU, bf16, N=1, stride 1 and 2, road-band masks; "
+                                             "eager launches, step = reduce_mask + fused conv", "headline_row": head},
+                      "rows": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -243,6 +329,8 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.workload == "stages":
+        return run_stages(args)
     if args.workload != "cfg2":
         return run_units(args)
     torch.cuda.set_device(0)

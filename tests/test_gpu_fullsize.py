@@ -164,3 +164,48 @@ def test_stack_shape_batch_of_samples_sampled(bo):
         cy, cx = by * bo - gy_lo, bx * bo - gx_lo
         got = a[n_, by * bo:by * bo + bo, bx * bo:bx * bo + bo].to(torch.float64).cpu().numpy()
         assert_close(got, ref[0, cy:cy + bo, cx:cx + bo], 3e-2, "stack tile %d" % k)
+
+
+STAGE_CASES = [
+    # H, W, Cin, Cout, stride, bo: the other stage shapes of the detector backbone (Sec. 4), downsampling and not
+    (800, 704, 64, 96, 2, 16),
+    (400, 352, 96, 96, 1, 16),
+    (400, 352, 96, 192, 2, 16),
+    (200, 176, 192, 256, 2, 16),
+    (100, 88, 256, 384, 2, 8),
+]
+
+
+@pytest.mark.parametrize("H,W,Cin,Cout,s,bo", STAGE_CASES)
+def test_stage_shapes_sampled(H, W, Cin, Cout, s, bo):
+    """Single sparse 3x3 convolutions at the backbone's other stage shapes, stride 1 and 2 (for stride 2 the
+    input tile is (bo - 1) * 2 + 3 pixels wide and neighbouring tiles overlap by one pixel, Fig. 3), on a
+    road-band mask at about 30 % active blocks; sampled tiles against the oracle."""
+    step("stage shape %s" % ((H, W, Cin, Cout, s, bo),))
+    r = gen.rng_for(6, H + Cin + s)
+    N = 1
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, s, bo)
+    x = gen.activations(r, (N, H, W, Cin), "bf16")
+    w = gen.conv_weights(r, 3, 3, Cin, Cout, "bf16")
+    b = gen.bias_vector(r, Cout)
+    fields = gen.road_band_fields(r, Ho, Wo, 3)
+    og = ogeom(g_out)
+    total = N * g_out.bcount_h * g_out.bcount_w
+    mask, _, frac = gen.calibrate(lambda sc: gen.road_band_mask(fields, sc), lambda mm: len(orc.reduce_mask(mm, og)), total,
+                                  0.30, 0.0, 12.0, tol=0.03)
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_out, sb.POOL_AVG, 0.0)
+    idx = orc.reduce_mask(mask, og, orc.POOL_AVG, 0.0)
+    n = sb.read_count(d_cnt, d_idx.shape[0])
+    assert n == len(idx) and n > 0 and np.array_equal(d_idx[:n].cpu().numpy(), idx)
+    y0 = gen.activations(r, (N, Ho, Wo, Cout), "bf16")
+    y = to_dev(y0, "bf16")
+    sb.sparse_conv(to_dev(x, "bf16"), d_idx, d_cnt, g_in, g_out, sb.pack_weights(to_dev(w, "bf16")),
+                   torch.from_numpy(b).cuda(), y, stride=s, relu=True)
+    got = to_host(y)
+    bm = orc.block_mask(idx, og, N, Ho, Wo)
+    assert np.array_equal(got[~bm], y0[~bm])
+    rows = sample_tiles(idx, g_out, r, 6)
+    ref = np.maximum(orc.conv_valid(orc.gather(x, idx[rows], ogeom(g_in)), w, b, s), 0.0)
+    # blocks hanging over the image edge: the part outside is never stored (blocks_of pads it with zeros)
+    inside = blocks_of(np.ones((N, Ho, Wo, 1)), idx[rows], g_out) > 0
+    assert_close(blocks_of(got, idx[rows], g_out), np.where(inside, ref, 0.0), CONV_TOL["bf16"], "stage shape sampled tiles")
