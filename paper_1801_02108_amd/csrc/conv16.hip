@@ -19,7 +19,13 @@
 //     two tiles deep: while the matrix cores work on tile i, the same wave, between its MFMAs,
 //     writes tile i+1 (loaded during tile i-1) to the other LDS buffer and issues the loads of
 //     tile i+2 into the registers this frees.  The index triple of tile i+3 is requested at the
-//     same time.  No load waits on another load and none of this costs matrix-core time;
+//     same time.  No load waits on another load.  Per stage of 12 MFMAs this adds one LDS write, one
+//     buffer load and five VALU instructions (measured: a wave issues about two VALU instructions
+//     per MFMA for free, every further one delays the next MFMA by its own four cycles);
+//   * results leave through a wave-private LDS transpose, so that a store instruction writes 64-byte
+//     runs instead of 16-byte pieces, and as non-temporal stores;
+//   * a workgroup with a single tile (fewer active tiles than CUs) runs a copy of the tile code
+//     that starts its matrix work while the weights, requested in order of use, still stream in;
 //   * an LDS fragment is 32 pixels (two consecutive input rows x 16 columns) x 16 channels; the
 //     pixel stride is padded by 16 B, which makes the two rows of a fragment fall on disjoint
 //     bank groups.  A fragment starting on an even row is used for tap rows 0 and 2 of two
