@@ -5,28 +5,29 @@
 //
 // One kernel per unit; per TS x TS output sub-tile (TS = 16, or 8 for blocks that are no multiple of 16
 // and for problems with too few 16x16 sub-tiles to occupy the device) and workgroup (4 waves, one per
-// SIMD).  The
-// 1x1 weights W1, W3 and the biases stay in LDS for the life of the workgroup (MFMA operand order);
-// W2 (the 3x3, 72 KB) is re-read from L2 into registers once per tile while P1 runs:
-//   P1  t1 = ReLU(W1 x + b1) on the 18x18 input sub-tile.  x passes through LDS in 64-channel
+// SIMD).  The 1x1 weights W1, W3 and the biases stay in LDS for the life of the workgroup (MFMA operand
+// order); W2 (the 3x3, 72 KB) is re-read from L2 for every tile, through a ring of registers a few
+// stages ahead of P2's matrix work:
+//   P1  t1 = ReLU(W1 x + b1) on the (TS+2)^2 input sub-tile.  x passes through LDS in 64-channel
 //       chunks: eight lanes read one pixel's 128 contiguous bytes (8 full cache lines per wave
 //       instruction; loading the 32x32x16 B operand directly touches 32 lines for the same 1 KB and
 //       runs at the L1 tag rate), two chunks are in flight in registers, and the first two chunks of
 //       the NEXT tile are requested before P3 so that HBM stays busy during the matrix phases;
-//       t1 goes to LDS as bf16/f16.  Positions outside
-//       the image are forced to zero: the dense network pads the 3x3's input, i.e. t1, with
-//       zeros, and ReLU(b1) is not zero.
+//       t1 goes to LDS as bf16/f16.  Positions outside the image are forced to zero: the dense
+//       network pads the 3x3's input, i.e. t1, with zeros, and ReLU(b1) is not zero.  In the middle
+//       of P1 the residual (the block's own pixels of x) is requested into registers, while the
+//       same cache lines are passing through L2 for P1.
 //   P2  t2 = ReLU(W2 * t1 + b2), the 3x3 as nine shifted reads of the LDS copy of t1 (same scheme
 //       as the stand-alone 3x3 tile kernel); t2 goes to LDS.
-//   P3  t3 = W3 t2 + b3; fused form: y = x + t3 on the block's pixels (the residual x is re-read
-//       from global memory, where it was fetched moments ago for P1); on-tiles form: t3 is stored.
+//   P3  t3 = W3 t2 + b3; fused form: y = x + t3 on the block's pixels; on-tiles form: t3 is stored.
 //       A wave owns 64 (or 32) neighbouring output channels.  In the MFMA result layout a lane holds
 //       16 channels of one pixel, so loads and stores from it would be 16-byte pieces 2*C bytes
 //       apart, one memory request each.  t3 is therefore rounded to the storage type (as the tile
 //       stack of the unfused path would hold it) and transposed through a wave-private LDS area
 //       (the space of t1, dead by then): eight neighbouring lanes then hold the wave's 128 contiguous
 //       bytes of one pixel, the residual is read and the sum stored in that layout, whole cache lines
-//       per request.  Fused and unfused paths thereby give bit-identical results.
+//       per request, the stores non-temporal.  Fused and unfused paths thereby give bit-identical
+//       results.
 // Global memory is reached through buffer descriptors that cover one sample (or one tile): rows outside
 // the image fall outside the descriptor, columns outside get an out-of-range offset, and the hardware
 // returns zeros for such loads and drops such stores, so no memory operation needs a branch or predicate.
