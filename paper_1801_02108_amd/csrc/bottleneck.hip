@@ -410,7 +410,6 @@ void bottleneck16_kernel(BneckParams p) {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int st = 0; st < 12; ++st) {
-                const int t = st / 4, kc = st % 4;
                 const int tn = (st + 1) / 4, kcn = (st + 1) % 4;
 #pragma unroll
                 for (int mm = 0; mm < 3 * NP; ++mm) {
