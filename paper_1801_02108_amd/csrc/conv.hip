@@ -80,8 +80,12 @@ __global__ __launch_bounds__(256) void conv_direct(ConvParams p) {
 // ------------------------------------------------------------------------------------------
 // MFMA kernel
 // ------------------------------------------------------------------------------------------
-constexpr int kMB = 4;  // 16-pixel blocks per wave
+// 16-pixel blocks per wave is a template parameter of conv_mfma (MB): 4 (256 output pixels per workgroup) or, for
+// problems with too few work items to occupy the device, 1 (64 pixels: four times the work items, a quarter of
+// the staging and matrix work in each)
 constexpr int kNB = 4;  // 16-channel blocks per wave (64 output channels per workgroup)
+constexpr int kWD = 4;  // steps of weight fragments in flight ahead of the matrix work
+constexpr int kStage = 12;  // input vectors in flight per thread while a chunk is staged into LDS
 
 // Weight packing for conv_mfma.  Packed element (((ng*KS + ks)*4 + nb)*64 + lane)*8 + e holds
 // w[tap][c][o] with ks = tap*(CinP/32) + c/32, c = (ks % (CinP/32))*32 + (lane/16)*8 + e and
@@ -142,8 +146,9 @@ __global__ void copy_weights(const T *__restrict__ w, T *__restrict__ packed, si
         packed[idx] = w[idx];
 }
 
-template <int DT, bool FUSED>
+template <int DT, bool FUSED, int kMB>
 __global__ __launch_bounds__(256) void conv_mfma(ConvParams p) {
+    constexpr int PP = 64 * kMB;                // output pixels per pass
     extern __shared__ __align__(16) unsigned char lds[];
     const uint16_t *in = (const uint16_t *)p.in;
     uint16_t *out = (uint16_t *)p.out;
@@ -174,7 +179,7 @@ __global__ __launch_bounds__(256) void conv_mfma(ConvParams p) {
         }
 
         // output pixels of this pass and the input rows they need
-        const int p_lo = pass * 256, p_hi = min(p_lo + 256, M);
+        const int p_lo = pass * PP, p_hi = min(p_lo + PP, M);
         const int i_lo = (int)fdiv(p_lo, p.div_ow), i_hi = (int)fdiv(p_hi - 1, p.div_ow);
         const int r_lo = i_lo * p.sh;
         const int nrows = (i_hi - i_lo) * p.sh + p.kh;
@@ -204,12 +209,13 @@ __global__ __launch_bounds__(256) void conv_mfma(ConvParams p) {
             const FastDiv dcv = (chunk == p.nchunks - 1) ? p.div_cv_last : p.div_cv;
             __syncthreads();                            // previous chunk / item fully consumed
             const uint32_t nvec = (uint32_t)nrows * p.tw * cv;
-            // four independent global loads in flight per thread before the LDS stores
-            for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += 256 * 4) {
-                uint4 val[4];
-                uint32_t dst[4];
+            // kStage independent global loads in flight per thread before the LDS stores: a tile costs
+            // nvec / (256 * kStage) memory round trips
+            for (uint32_t v0 = threadIdx.x; v0 < nvec; v0 += 256 * kStage) {
+                uint4 val[kStage];
+                uint32_t dst[kStage];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < kStage; ++u) {
                     const uint32_t v = v0 + u * 256;
                     const uint32_t px = fdiv(v, dcv);
                     const int c8 = (int)(v - px * cv);
@@ -228,32 +234,33 @@ __global__ __launch_bounds__(256) void conv_mfma(ConvParams p) {
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < kStage; ++u)
                     if (v0 + u * 256 < nvec) *(uint4 *)(lds + dst[u]) = val[u];
             }
             __syncthreads();
 
-            // k loop over (tap row, tap column, 32-channel step); the weight fragments of the next
-            // step are fetched from L2 while the matrix cores work on the current one
+            // k loop over (tap row, tap column, 32-channel step).  The weight fragments come from L2 through a
+            // ring of kWD steps: the fragments of step i + kWD are requested when step i has consumed its slot, so a
+            // request has kWD steps of matrix work to land (one step is ~0.2 us, an L2 round trip several times
+            // that).  The body of the main loop is kWD steps of straight-line code, which keeps the wait counts
+            // exact; requests past the last step repeat it (harmless) instead of branching.
             const int steps = cc >> 5;
             const int nit = p.kh * p.kw * steps;
             const uint4 *wbase = (const uint4 *)p.w + ((size_t)ng * KS + (c0 >> 5)) * kNB * 64 + lane;
-            int r = 0, t = 0, st = 0;
-            uint4 wf[kNB];
+            int lt = 0, lst = 0;                       // request cursor: tap, channel step
+            uint4 ring[kWD][kNB];
+            auto request = [&](int slot) __attribute__((always_inline)) {
+                const uint4 *wp = wbase + ((size_t)(lt * c32_total + lst) * kNB) * 64;
 #pragma unroll
-            for (int nb = 0; nb < kNB; ++nb) wf[nb] = wbase[(size_t)nb * 64];
-            for (int it = 0; it < nit; ++it) {
-                int st2 = st + 1, t2 = t, r2 = r;
-                if (st2 == steps) { st2 = 0; if (++t2 == p.kw) { t2 = 0; ++r2; } }
-                uint4 wn[kNB];
-                if (it + 1 < nit) {
-                    const uint4 *wp = wbase + ((size_t)((r2 * p.kw + t2) * c32_total + st2) * kNB) * 64;
-#pragma unroll
-                    for (int nb = 0; nb < kNB; ++nb) wn[nb] = wp[(size_t)nb * 64];
-                } else {
-#pragma unroll
-                    for (int nb = 0; nb < kNB; ++nb) wn[nb] = wf[nb];
+                for (int nb = 0; nb < kNB; ++nb) ring[slot][nb] = wp[(size_t)nb * 64];
+                // advance, but never past the last step
+                const bool last = (lt == p.kh * p.kw - 1) && (lst == steps - 1);
+                if (!last) {
+                    if (++lst == steps) { lst = 0; ++lt; }
                 }
+            };
+            int r = 0, t = 0, st = 0;                  // use cursor: tap row, tap column, channel step
+            auto one_step = [&](int slot) __attribute__((always_inline)) {
                 const int off = (r * p.tw + t) * pix_stride + st * 64;
                 uint4 xf[kMB];
 #pragma unroll
@@ -261,11 +268,22 @@ __global__ __launch_bounds__(256) void conv_mfma(ConvParams p) {
 #pragma unroll
                 for (int mb = 0; mb < kMB; ++mb)
 #pragma unroll
-                    for (int nb = 0; nb < kNB; ++nb) acc[mb][nb] = mfma16x16x32<DT>(wf[nb], xf[mb], acc[mb][nb]);
+                    for (int nb = 0; nb < kNB; ++nb) acc[mb][nb] = mfma16x16x32<DT>(ring[slot][nb], xf[mb], acc[mb][nb]);
+                if (++st == steps) { st = 0; if (++t == p.kw) { t = 0; ++r; } }
+            };
 #pragma unroll
-                for (int nb = 0; nb < kNB; ++nb) wf[nb] = wn[nb];
-                r = r2; t = t2; st = st2;
+            for (int u = 0; u < kWD; ++u) request(u);
+            int it = 0;
+            for (; it + kWD <= nit; it += kWD) {
+#pragma unroll
+                for (int u = 0; u < kWD; ++u) {
+                    one_step(u);
+                    request(u);
+                }
             }
+#pragma unroll
+            for (int u = 0; u < kWD - 1; ++u)
+                if (it + u < nit) one_step(u);
         }
 
         // epilogue: lane holds channels ng*64 + h*32 + q*8 + [0,8), h = 0,1, of pixel (mb, l16)
@@ -367,10 +385,12 @@ static sbnet_status run_conv(const char *who, sbnet_dtype dt, ConvParams &p, hip
     }
 
     p.CinP = (p.Cin + 31) / 32 * 32;
-    p.mpasses = (int)((M + 255) / 256);
     p.ngroups = (p.Cout + 63) / 64;
-    // rows of input a pass of 256 consecutive output pixels can touch
-    int out_rows = (256 + p.ow - 1) / p.ow + ((256 % p.ow) ? 1 : 0);
+    // pixels per pass: 256, or 64 when even the caller's bound on the active blocks gives fewer work items than CUs
+    const int PP = ((long long)p.cap * ((M + 255) / 256) * p.ngroups < 256) ? 64 : 256;
+    p.mpasses = (int)((M + PP - 1) / PP);
+    // rows of input a pass of PP consecutive output pixels can touch
+    int out_rows = (PP + p.ow - 1) / p.ow + ((PP % p.ow) ? 1 : 0);
     if (out_rows > p.oh) out_rows = p.oh;
     int lds_rows = (out_rows - 1) * p.sh + p.kh;
     if (lds_rows > p.th) lds_rows = p.th;
@@ -390,15 +410,20 @@ static sbnet_status run_conv(const char *who, sbnet_dtype dt, ConvParams &p, hip
     if (items >= (1LL << 31)) return fail(SBNET_EUNSUPPORTED, "%s: too many work items", who);
     const int grid = (int)(items < 8192 ? items : 8192);
 
-#define SBNET_MFMA(DT)                                                                                         \
+#define SBNET_MFMA(DT, MB)                                                                                     \
     do {                                                                                                       \
         if (lds_bytes > 48 * 1024)                                                                             \
-            (void)hipFuncSetAttribute((const void *)conv_mfma<DT, FUSED>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                      (int)lds_bytes);                                                         \
-        hipLaunchKernelGGL((conv_mfma<DT, FUSED>), dim3(grid), dim3(256), (size_t)lds_bytes, s, p);            \
+            (void)hipFuncSetAttribute((const void *)conv_mfma<DT, FUSED, MB>,                                  \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);             \
+        hipLaunchKernelGGL((conv_mfma<DT, FUSED, MB>), dim3(grid), dim3(256), (size_t)lds_bytes, s, p);        \
     } while (0)
-    if (dt == SBNET_BF16) SBNET_MFMA(SBNET_BF16);
-    else SBNET_MFMA(SBNET_F16);
+    if (dt == SBNET_BF16) {
+        if (PP == 256) SBNET_MFMA(SBNET_BF16, 4);
+        else SBNET_MFMA(SBNET_BF16, 1);
+    } else {
+        if (PP == 256) SBNET_MFMA(SBNET_F16, 4);
+        else SBNET_MFMA(SBNET_F16, 1);
+    }
 #undef SBNET_MFMA
     return launch_status(who);
 }
