@@ -66,6 +66,10 @@ __device__ __forceinline__ f32x16 mfma32x32x16(uint4 a, uint4 b, f32x16 c) {
     }
 }
 
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t relu_pair(uint32_t w, uint32_t floor2) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2, w), __builtin_bit_cast(i16x2, floor2)));
+}
 __device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
     const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
     return make_uint4(v[0], v[1], v[2], v[3]);
@@ -240,6 +244,8 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
     // ReLU the floor is INT_MIN and the max is the identity.  One VALU op, no NaN canonicalisation.
     int floor_i = p.relu ? 0 : (int)0x80000000;
     asm volatile("" : "+s"(floor_i));                // opaque: otherwise the max is split into a max with 0 and a select
+    uint32_t floor16 = p.relu ? 0u : 0x80008000u;    // the same for two 16-bit values at once
+    asm volatile("" : "+s"(floor16));
 
     // ---- output plan: this lane stores pixel (rh*8 + 2P + prow, pcol) of the sub-tile, channels ch0 .. ch0+15
     const int out_w = FUSED ? p.Wo : p.ow;
@@ -336,30 +342,46 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
                         old[P][h] = buf_load16(orsrc, (col_ok && chan_ok[h]) ? origin + out_lane + P * out_pair + h * 16 : kOutOfRange);
             }
             unsigned char *os = ostage[wave];
-#pragma unroll
-            for (int P = 0; P < 4; ++P)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    float v[8];
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) v[k] = __int_as_float(max(__float_as_int(acc[P][h * 8 + k]), floor_i));
-                    if (ADD) {
-                        const uint4 o = old[P][h];
-                        v[0] += unpack_lo<DT>(o.x); v[1] += unpack_hi<DT>(o.x);
-                        v[2] += unpack_lo<DT>(o.y); v[3] += unpack_hi<DT>(o.y);
-                        v[4] += unpack_lo<DT>(o.z); v[5] += unpack_hi<DT>(o.z);
-                        v[6] += unpack_lo<DT>(o.w); v[7] += unpack_hi<DT>(o.w);
-                    }
-                    *(uint4 *)(os + ost_w + P * (2 * 16 * kOutPs) + h * 16) =
-                        make_uint4(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]), pack2<DT>(v[4], v[5]), pack2<DT>(v[6], v[7]));
-                }
-            __builtin_amdgcn_wave_barrier();     // LDS serves one wave's accesses in order: no wait, only no reordering
             const bool ok2 = chan_ok2 && (!FUSED || (uint32_t)(x0 + (lane >> 2)) < (uint32_t)p.Wo);
             const uint32_t off2 = ok2 ? origin + out_lane2 : kOutOfRange;
+            // Row pair P goes to LDS while the two rows of pair P - 1 come back in the store layout and leave: the
+            // LDS round trip of one pair hides behind the conversion of the next.  LDS serves one wave's accesses
+            // in order, so a read sees the writes before it without a wait.
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint4 v = *(const uint4 *)(os + ost_r + j * (16 * kOutPs));
-                buf_store16(orsrc, ok2 ? off2 + j * out_row : kOutOfRange, v);
+            for (int P = 0; P <= 4; ++P) {
+                if (P < 4) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        uint32_t w[4];
+                        if (ADD) {
+                            float v[8];
+#pragma unroll
+                            for (int k = 0; k < 8; ++k) v[k] = __int_as_float(max(__float_as_int(acc[P][h * 8 + k]), floor_i));
+                            const uint4 o = old[P][h];
+                            v[0] += unpack_lo<DT>(o.x); v[1] += unpack_hi<DT>(o.x);
+                            v[2] += unpack_lo<DT>(o.y); v[3] += unpack_hi<DT>(o.y);
+                            v[4] += unpack_lo<DT>(o.z); v[5] += unpack_hi<DT>(o.z);
+                            v[6] += unpack_lo<DT>(o.w); v[7] += unpack_hi<DT>(o.w);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) w[k] = pack2<DT>(v[2 * k], v[2 * k + 1]);
+                        } else {
+                            // ReLU after rounding, two channels per instruction: bf16 and f16 are sign-magnitude, so a
+                            // negative value is a negative 16-bit integer and max(., 0) is the ReLU (floor -32768: identity)
+#pragma unroll
+                            for (int k = 0; k < 4; ++k)
+                                w[k] = relu_pair(pack2<DT>(acc[P][h * 8 + 2 * k], acc[P][h * 8 + 2 * k + 1]), floor16);
+                        }
+                        *(uint4 *)(os + ost_w + P * (2 * 16 * kOutPs) + h * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+                    }
+                }
+                if (P >= 1) {
+                    __builtin_amdgcn_wave_barrier();     // no wait: only keeps the compiler from moving reads over writes
+#pragma unroll
+                    for (int j = 2 * (P - 1); j < 2 * P; ++j) {
+                        const uint4 v = *(const uint4 *)(os + ost_r + j * (16 * kOutPs));
+                        buf_store16(orsrc, ok2 ? off2 + j * out_row : kOutOfRange, v);
+                    }
+                }
             }
         }
 
