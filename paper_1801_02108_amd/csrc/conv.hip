@@ -371,6 +371,7 @@ static sbnet_status run_conv(const char *who, sbnet_dtype dt, ConvParams &p, hip
     if (use_mfma(dt, p.Cin, p.Cout)) p.w32_offset = packed_elems(dt, p.kh, p.kw, p.Cin, p.Cout) / 2 / 8;
     sbnet_status st16 = SBNET_OK;
     if (conv16_try(dt, FUSED, p, s, &st16, who)) return st16;
+    if (conv3_try(dt, FUSED, p, s, &st16, who)) return st16;
 
     if (!use_mfma(dt, p.Cin, p.Cout)) {
         p.div_cv = make_fastdiv(p.Cout);

@@ -38,8 +38,6 @@ namespace sbnet {
 
 constexpr int kT16 = 18;                 // input sub-tile side: 16 + 3 - 1
 constexpr int kT16Px = kT16 * kT16;
-constexpr uint32_t kBufWord3 = 0x00020000u;      // raw buffer descriptor, 32-bit data format
-constexpr uint32_t kOutOfRange = 0x80000000u;    // offset beyond any descriptor this kernel builds
 constexpr int kOutPs = 80;                       // LDS bytes per pixel of a wave's results: 32 channels + 16 B pad
 
 struct Sub16 {
@@ -53,34 +51,6 @@ struct Item16 {
     int si, sj;         // sub-tile inside the block
     int n, by, bx;      // fused form: sample and block coordinates
 };
-
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-
-template <int DT>
-__device__ __forceinline__ f32x16 mfma32x32x16(uint4 a, uint4 b, f32x16 c) {
-    if (DT == SBNET_BF16) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    } else {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-}
-
-typedef short i16x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t relu_pair(uint32_t w, uint32_t floor2) {
-    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2, w), __builtin_bit_cast(i16x2, floor2)));
-}
-__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
-    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
-    return make_uint4(v[0], v[1], v[2], v[3]);
-}
-__device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, uint32_t off, uint4 d) {
-    u32x4 v;
-    v[0] = d.x; v[1] = d.y; v[2] = d.z; v[3] = d.w;
-    // non-temporal: the results are not read again here and should not push input lines, which neighbouring
-    // tiles read again for their halos, out of L2
-    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 2);
-}
 
 // ADD (fused form only): the results are added to what the output holds.  A template parameter rather than a
 // branch on p.add: with two paths that issue different numbers of memory operations the compiler's wait counts

@@ -1,0 +1,595 @@
+// 3x3 tile convolution for any stride and tile size, bf16 / f16 with channel counts that are multiples of 8
+// (Sec. 3.2 of arXiv 1801.02108: the regular convolution that runs on every gathered block, here also for the
+// stride-2 geometry of Fig. 3 and the wider layers of the later backbone stages; in fused mode also the gather
+// before it and the scatter / scatter-add after it, Sec. 3.4).
+//
+// Design for gfx950: an implicit GEMM tiled through LDS, both operands read from LDS.
+//   * Measured on MI355X: with one wave per SIMD a stream of 32x32x16 MFMAs that takes BOTH operands from LDS
+//     (two 16-byte-per-lane reads per MFMA, conflict-free) still runs at 94 % of the rate of a register-only
+//     stream.  So nothing has to stay in registers across MFMAs and the matrix loop never waits on memory: a
+//     chunk of CC input channels of the input rows AND of the weights of the workgroup's 64 output channels sits
+//     in LDS, and the loop only reads LDS.
+//   * A work item is (active block, pass of PP output pixels, group of 64 output channels); a workgroup (4 waves,
+//     one per SIMD) walks its items and, inside an item, the chunks of CC input channels.  Chunks are
+//     double-buffered in LDS and pipelined two deep through registers: between the MFMAs of chunk i a thread
+//     writes its vectors of chunk i+1 (loaded during chunk i-1) to the other LDS buffer and, into the registers
+//     this frees, requests the same vectors of chunk i+2 (of a following item past the last chunk).  One or two
+//     vectors per MFMA step: issued all at once they would stall the wave at the memory pipeline (64 B per clock
+//     and CU) with the matrix cores idle behind them.
+//   * All global traffic goes through buffer descriptors: halo pixels outside the image, vectors past the end of
+//     the staged rows and channels past Cin read as zeros, stores outside the image or past Cout are dropped.  No
+//     branch surrounds a load, so the compiler's wait counts stay exact.
+//   * Columns are staged de-interleaved by stride phase (column x goes to plane x % sw, slot x / sw), which turns
+//     the stride-sw walk of a fragment read into consecutive LDS pixels: the same conflict-free pattern for every
+//     stride.  The LDS pixel stride is the chunk's channels + 16 B pad.
+//   * Results are transposed through a wave-private LDS area, 32 pixels x 32 channels at a time, so that a store
+//     instruction writes 64-byte runs instead of 16-byte pieces.
+//   * Workgroup tiles: 256 pixels x 64 channels (wave: 64 px x 64 ch, 4 accumulators), 128 x 64 for problems
+//     with too few items to fill the device (picked on the device from the active count: both are launched, one
+//     returns at once), and 64 x 64 for tiles of at most 64 output pixels.  Chunks of 32 channels where two
+//     buffers of that fit in LDS (stride 1), else of 16 (the 33x33 input tile of a strided 16x16 block).
+#include "conv_common.h"
+
+namespace sbnet {
+
+constexpr int kLds3 = 160 * 1024;
+constexpr int kDump3 = 4096;                 // one 16-byte slot per thread for staging vectors that have no place
+constexpr int kOst3Ps = 80;                  // result transpose: bytes per pixel (32 channels + 16 B pad)
+constexpr int kOst3 = 32 * kOst3Ps;          // ... per wave
+
+struct Plan3 {
+    int mpasses, ngroups;
+    FastDiv div_pt, div_ng, div_sw, div_nch;
+    int cpp;                 // LDS pixel slots per column phase: ceil(tw / sw)
+    uint32_t nvec_in;        // 16-byte vectors of one input chunk
+    int nchunks;
+    uint32_t buf_bytes;      // one LDS buffer: input chunk, then weight chunk
+    uint32_t w_off;          // offset of the weight chunk inside a buffer
+    uint32_t dump_off, ost_off, bias_off;    // after the two buffers
+    uint32_t w_bytes;        // bytes of the 32x32x16 operand copy of the weights
+    int ks16;                // 16-channel k-steps per output group: 9 * CinP / 16
+    uint32_t lo, hi;         // run only when lo <= active blocks <= hi
+};
+
+struct Item3 {
+    uint32_t b;
+    int pass, ng;
+    int n, by, bx;
+};
+
+struct Src3 {
+    const void *base;        // the sample (fused) or tile the rows come from
+    uint32_t origin;         // byte offset of staged pixel (0, 0); wraps below zero above / left of the image
+    int gx0;                 // image column of staged column 0
+    int ng;
+};
+
+struct Chunk3 {
+    const void *base;
+    uint32_t origin;         // ... of channel c0
+    int gx0;
+    int c0;
+    uint32_t wofs;           // byte offset of (group, tap 0, channel c0) in the packed weights
+};
+
+template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void conv3_kernel(ConvParams p, Plan3 q) {
+    static_assert(FUSED || !ADD, "adding into the output is part of the fused form");
+    constexpr int CV = CC / 8;                       // 16-byte vectors per pixel and chunk
+    constexpr int KST = CC / 16;                     // k-steps of 16 channels per tap
+    constexpr int NS = 9 * KST;                      // MFMA steps per chunk
+    constexpr int PS = CC * 2 + 16;                  // LDS bytes per input pixel
+    constexpr int WVEC = NS * 128;                   // vectors of a weight chunk: steps x 2 blocks of 32 channels x 64 lanes
+    constexpr int NVW = (WVEC + 255) / 256;
+    constexpr int NV = NVI + NVW;                    // staging vectors per thread and chunk
+    constexpr int PER = (NV + NS - 1) / NS;          // ... handled per MFMA step
+    constexpr int PP = WP * PBW * 32;                // output pixels per pass
+    constexpr int NM = CBW * PBW;                    // MFMAs per step
+    constexpr int D0 = NM >= 4 ? 2 : (NM == 2 ? 4 : 8);
+    constexpr int D = D0 < NS ? D0 : NS - 1;         // steps the fragment reads run ahead of the MFMAs
+    extern __shared__ __align__(16) unsigned char lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 5, m = lane & 31;          // k-group / channel half, pixel within a fragment
+    const int pw = wave % WP, cw = wave / WP;
+    const int M = p.oh * p.ow;
+
+    const int nact = max(min(*p.count, p.cap), 0);
+    if ((uint32_t)nact < q.lo || (uint32_t)nact > q.hi) return;
+    const uint32_t per_tile = (uint32_t)q.mpasses * q.ngroups;
+    const uint32_t items = (uint32_t)nact * per_tile;
+    const uint32_t G = gridDim.x;                    // multiple of 8
+    // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of items (the passes and
+    // channel groups of one block, and neighbouring blocks, share input lines in that XCD's L2)
+    const uint32_t first = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
+    if (first >= items) return;
+    const uint32_t last = items - 1u;
+
+    // A work item's index triple is requested three items ahead.  The address is the same in every lane, but the
+    // loads are issued as per-lane loads and left in vector registers (the opaque zero hides the uniformity): a
+    // value the compiler knows to be uniform is moved to a scalar register right after the load, which stalls
+    // the wave for a memory round trip on the spot.  It is made scalar (resolve) behind a point where younger
+    // loads have been waited for anyway.
+    int lane_zero = 0;
+    asm volatile("" : "+v"(lane_zero));
+    auto request = [&](uint32_t it) __attribute__((always_inline)) {
+        Item3 c;
+        c.b = fdiv(it, q.div_pt);
+        const uint32_t rest = it - c.b * per_tile;
+        c.pass = (int)fdiv(rest, q.div_ng);
+        c.ng = (int)rest - c.pass * q.ngroups;
+        c.n = c.by = c.bx = 0;
+        if (FUSED) {
+            const int32_t *t = p.indices + 3 * (size_t)c.b + lane_zero;
+            c.n = t[0];
+            c.by = t[1];
+            c.bx = t[2];
+        }
+        return c;
+    };
+    auto resolve = [&](const Item3 &c) __attribute__((always_inline)) {
+        Item3 r = c;
+        if (FUSED) {
+            r.n = __builtin_amdgcn_readfirstlane(c.n);
+            r.by = __builtin_amdgcn_readfirstlane(c.by);
+            r.bx = __builtin_amdgcn_readfirstlane(c.bx);
+        }
+        return r;
+    };
+    const int in_w = FUSED ? p.W : p.tw;                          // pixels per row of the addressed array
+    const uint32_t in_bytes = (uint32_t)(FUSED ? p.H : p.th) * in_w * p.Cin * 2u;   // one sample / one tile
+    auto source = [&](const Item3 &c) __attribute__((always_inline)) {
+        Src3 s;
+        const int r_lo = (int)fdiv((uint32_t)c.pass * PP, p.div_ow) * p.sh;          // first input row of the pass
+        const uint16_t *base = (const uint16_t *)p.in;
+        if (FUSED) {
+            const int y0 = p.g_in.boffset_h + c.by * p.g_in.bstride_h + r_lo;
+            const int x0 = p.g_in.boffset_w + c.bx * p.g_in.bstride_w;
+            base += (long long)c.n * p.H * p.W * p.Cin;
+            s.origin = (uint32_t)((y0 * in_w + x0) * p.Cin) * 2u;
+            s.gx0 = x0;
+        } else {
+            base += (long long)c.b * p.th * p.tw * p.Cin;
+            s.origin = (uint32_t)(r_lo * in_w * p.Cin) * 2u;
+            s.gx0 = 0;
+        }
+        s.base = base;
+        s.ng = c.ng;
+        return s;
+    };
+
+    // ---- staging plan, the same for every chunk.  Input vector u of this thread is 16 bytes (8 channels) of pixel
+    //      (tid + 256 u) / CV of the staged rows, row-major; a vector past the end gets a column no image has
+    //      (so it loads zeros) and the dump slot.  Weight vector u is vector tid + 256 u of the chunk's fragments.
+    //      LDS address of a vector = lbase + (buffer number) * lstep.
+    uint32_t gdelta[NVI], lbase[NV], lstep[NV], wsrc[NVW];
+    int colv[NVI];
+    const int c8 = tid % CV;
+    const int cin16 = p.CinP >> 4;
+#pragma unroll
+    for (int u = 0; u < NVI; ++u) {
+        const uint32_t v = (uint32_t)tid + 256u * u;
+        const uint32_t px = v / CV;
+        const uint32_t row = fdiv(px, p.div_tw), col = px - row * p.tw;
+        const uint32_t cq = fdiv(col, q.div_sw), cr = col - cq * p.sw;
+        const bool ok = v < q.nvec_in;
+        lbase[u] = ok ? ((row * p.sw + cr) * q.cpp + cq) * PS + c8 * 16 : q.dump_off + tid * 16;
+        lstep[u] = ok ? q.buf_bytes : 0u;
+        gdelta[u] = (uint32_t)((row * in_w + col) * p.Cin + c8 * 8) * 2u;
+        colv[u] = ok ? (int)col : 0x40000000;
+    }
+#pragma unroll
+    for (int u = 0; u < NVW; ++u) {
+        const uint32_t v = (uint32_t)tid + 256u * u;
+        const uint32_t tap = v / (KST * 128), rem = v % (KST * 128);
+        const bool ok = v < (uint32_t)WVEC;
+        lbase[NVI + u] = ok ? q.w_off + v * 16 : q.dump_off + tid * 16;
+        lstep[NVI + u] = ok ? q.buf_bytes : 0u;
+        wsrc[u] = ok ? (tap * cin16 * 128u + rem) * 16u : kOutOfRange;
+    }
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const uint4 *)p.w + p.w32_offset), 0, (int)q.w_bytes, (int)kBufWord3);
+
+    uint4 stage[NV];
+    // Rows outside the image fall outside the descriptor by themselves; columns outside would wrap into the
+    // neighbouring row and channels past Cin into the neighbouring pixel, so those get the out-of-range offset.
+    auto issue1 = [&](int u, const Chunk3 &ch, bool chan_ok) __attribute__((always_inline)) {
+        if (u < NVI) {
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)ch.base, 0, (int)in_bytes, (int)kBufWord3);
+            const bool ok = chan_ok && (uint32_t)(ch.gx0 + colv[u]) < (uint32_t)in_w;
+            stage[u] = buf_load16(rs, ok ? ch.origin + gdelta[u] : kOutOfRange);
+        } else {
+            stage[u] = buf_load16(wrs, wsrc[u - NVI] + ch.wofs);
+        }
+    };
+    auto write1 = [&](int u, uint32_t bufno) __attribute__((always_inline)) {
+        *(uint4 *)(lds + lbase[u] + bufno * lstep[u]) = stage[u];
+    };
+    auto chunk_of = [&](const Src3 &s, int c) __attribute__((always_inline)) {
+        Chunk3 ch;
+        ch.base = s.base;
+        ch.c0 = c * CC;
+        ch.origin = s.origin + (uint32_t)ch.c0 * 2u;
+        ch.gx0 = s.gx0;
+        ch.wofs = (uint32_t)(s.ng * q.ks16 + (ch.c0 >> 4)) * 2048u;
+        return ch;
+    };
+
+    // ---- the workgroup's chunks, numbered gi = 0, 1, ... over its items: chunk gi is chunk gi % nchunks of item
+    //      first + (gi / nchunks) * G (past the end: the last item again, staged but never used).  Three are
+    //      known at any time: the one the matrix cores work on, the one on its way to LDS and the one being
+    //      requested; the index triple of a fourth is in flight.
+    struct Work3 {
+        Item3 it;
+        Src3 s;
+        int c;
+    };
+    auto request_chunk = [&](uint32_t gi) __attribute__((always_inline)) {
+        Work3 w;
+        const uint32_t k = fdiv(gi, q.div_nch);
+        w.c = (int)(gi - k * q.nchunks);
+        w.it = request(min(first + k * G, last));
+        return w;
+    };
+    auto resolve_chunk = [&](const Work3 &r) __attribute__((always_inline)) {
+        Work3 w;
+        w.c = r.c;
+        w.it = resolve(r.it);
+        w.s = source(w.it);
+        return w;
+    };
+    Work3 cur = request_chunk(0), mid = request_chunk(1), ahead = request_chunk(2);
+    cur = resolve_chunk(cur);
+    mid = resolve_chunk(mid);
+    ahead = resolve_chunk(ahead);
+    const uint32_t nwork = ((last - first) / G + 1u) * (uint32_t)q.nchunks;     // chunks of this workgroup
+
+    {   // chunk 0 -> LDS buffer 0; chunk 1 stays in flight
+        const Chunk3 ch = chunk_of(cur.s, cur.c);
+        const bool chan_ok = ch.c0 + c8 * 8 < p.Cin;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) issue1(u, ch, chan_ok);
+    }
+    // bias of all groups -> LDS (zeros past Cout or without bias)
+    {
+        float *bl = (float *)(lds + q.bias_off);
+        for (int i = tid; i < q.ngroups * 64; i += 256) bl[i] = (p.bias && i < p.Cout) ? p.bias[i] : 0.f;
+    }
+    // tap offsets in the de-interleaved layout
+    uint32_t tapoff[9];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int t = 0; t < 3; ++t) tapoff[r * 3 + t] = (uint32_t)((r * p.sw + t % p.sw) * q.cpp + t / p.sw) * PS;
+    uint32_t floor16 = p.relu ? 0u : 0x80008000u;    // ReLU on a pair of rounded values: integer max with 0 (or with -32768: identity)
+    asm volatile("" : "+s"(floor16));
+    int floor_i = p.relu ? 0 : (int)0x80000000;
+    asm volatile("" : "+s"(floor_i));
+#pragma unroll
+    for (int u = 0; u < NV; ++u) write1(u, 0);
+    {
+        const Chunk3 ch = chunk_of(mid.s, mid.c);
+        const bool chan_ok = ch.c0 + c8 * 8 < p.Cin;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) issue1(u, ch, chan_ok);
+    }
+    __syncthreads();
+
+    uint32_t par = 0;                                // LDS buffer the matrix work reads
+    unsigned char *ost = lds + q.ost_off + wave * kOst3;
+    f32x16 acc[CBW][PBW];
+    uint32_t p_lo = 0;
+    uint32_t xbase[PBW];
+    for (uint32_t gi = 0; gi < nwork; ++gi) {
+        const Work3 rq = request_chunk(gi + 3);
+        const bool firstc = cur.c == 0, lastc = cur.c + 1 == q.nchunks;
+        {
+            const Chunk3 aheadc = chunk_of(ahead.s, ahead.c);
+            const bool chan_ok = aheadc.c0 + c8 * 8 < p.Cin;
+            const unsigned char *B = lds + par * q.buf_bytes;
+            if (firstc) {
+                // this lane's pixels: block pb of the wave is 32 consecutive output pixels of the pass
+                p_lo = (uint32_t)cur.it.pass * PP;
+                const uint32_t i_lo = fdiv(p_lo, p.div_ow);
+#pragma unroll
+                for (int pb = 0; pb < PBW; ++pb) {
+                    const uint32_t px = min(p_lo + (uint32_t)((pw * PBW + pb) * 32 + m), (uint32_t)M - 1u);
+                    const uint32_t i = fdiv(px, p.div_ow), j = px - i * p.ow;
+                    xbase[pb] = ((i - i_lo) * p.sh * p.sw * q.cpp + j) * PS + g * 16;
+                }
+                // accumulators start from the bias
+#pragma unroll
+                for (int cb = 0; cb < CBW; ++cb) {
+                    const float4 *bl = (const float4 *)(lds + q.bias_off) + (cur.it.ng * 64 + (cw * CBW + cb) * 32 + g * 16) / 4;
+#pragma unroll
+                    for (int k4 = 0; k4 < 4; ++k4) {
+                        const float4 bv = bl[k4];
+#pragma unroll
+                        for (int pb = 0; pb < PBW; ++pb) {
+                            acc[cb][pb][k4 * 4 + 0] = bv.x; acc[cb][pb][k4 * 4 + 1] = bv.y;
+                            acc[cb][pb][k4 * 4 + 2] = bv.z; acc[cb][pb][k4 * 4 + 3] = bv.w;
+                        }
+                    }
+                }
+            }
+
+            // ---- matrix work of the chunk: step s = (tap, 16-channel step); A = weights (32 channels x 16 k),
+            //      B = 32 pixels x 16 k; fragment reads run D steps ahead.  Between the MFMAs of a step: PER
+            //      staging vectors of the next chunk go to the other buffer and are requested again for the
+            //      chunk after it.
+            {
+                const unsigned char *WL = B + q.w_off + (cw * CBW) * 1024 + lane * 16;
+                uint4 xa[D + 1][CBW], xb[D + 1][PBW];
+                auto read = [&](int s) __attribute__((always_inline)) {
+                    const int slot = s % (D + 1);
+#pragma unroll
+                    for (int cb = 0; cb < CBW; ++cb) xa[slot][cb] = *(const uint4 *)(WL + (s * 2 + cb) * 1024);
+#pragma unroll
+                    for (int pb = 0; pb < PBW; ++pb)
+                        xb[slot][pb] = *(const uint4 *)(B + xbase[pb] + tapoff[s / KST] + (s % KST) * 32);
+                };
+#pragma unroll
+                for (int s = 0; s < D; ++s) read(s);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    if (s + D < NS) read(s + D);
+#pragma unroll
+                    for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                        for (int pb = 0; pb < PBW; ++pb) {
+                            acc[cb][pb] = mfma32x32x16<DT>(xa[s % (D + 1)][cb], xb[s % (D + 1)][pb], acc[cb][pb]);
+                            if (cb * PBW + pb < PER) {
+                                const int u = s * PER + cb * PBW + pb;
+                                if (u < NV) {
+                                    write1(u, par ^ 1u);
+                                    issue1(u, aheadc, chan_ok);
+                                }
+                            }
+                        }
+                    if (PER > NM) {
+#pragma unroll
+                        for (int e = NM; e < PER; ++e) {
+                            const int u = s * PER + e;
+                            if (u < NV) {
+                                write1(u, par ^ 1u);
+                                issue1(u, aheadc, chan_ok);
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+
+            // ---- epilogue after the last chunk: ReLU, optional add, NHWC stores.  A lane holds 16 consecutive
+            //      channels of one pixel per accumulator; 32 pixels x 32 channels at a time go through the wave's
+            //      LDS area and come back as 64 contiguous bytes per four lanes.  Pixels past the end of the tile,
+            //      columns outside the image and channels past Cout get the out-of-range offset; rows outside fall
+            //      outside the descriptor.
+            if (lastc) {
+                uint16_t *obase = (uint16_t *)p.out;
+                uint32_t obytes, origin;
+                int ox0 = 0, out_w;
+                if (FUSED) {
+                    const int oy0 = p.g_out.boffset_h + cur.it.by * p.g_out.bstride_h;
+                    ox0 = p.g_out.boffset_w + cur.it.bx * p.g_out.bstride_w;
+                    out_w = p.Wo;
+                    obase += (long long)cur.it.n * p.Ho * p.Wo * p.Cout;
+                    obytes = (uint32_t)p.Ho * p.Wo * p.Cout * 2u;
+                    origin = (uint32_t)((oy0 * p.Wo + ox0) * p.Cout) * 2u;
+                } else {
+                    out_w = p.ow;
+                    obase += (long long)cur.it.b * M * p.Cout;
+                    obytes = (uint32_t)M * p.Cout * 2u;
+                    origin = 0;
+                }
+                const __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc((void *)obase, 0, (int)obytes, (int)kBufWord3);
+                auto pixel_offset = [&](uint32_t px, bool &ok) __attribute__((always_inline)) {
+                    const uint32_t pc = min(px, (uint32_t)M - 1u);
+                    const uint32_t i = fdiv(pc, p.div_ow), j = pc - i * p.ow;
+                    ok = px < (uint32_t)M && (!FUSED || (uint32_t)(ox0 + (int)j) < (uint32_t)p.Wo);
+                    return origin + (uint32_t)((i * out_w + j) * p.Cout) * 2u;
+                };
+                const int chg = cur.it.ng * 64 + cw * CBW * 32;                    // first channel of the wave
+#pragma unroll
+                for (int pb = 0; pb < PBW; ++pb) {
+                    const uint32_t pblock = p_lo + (uint32_t)((pw * PBW + pb) * 32);
+                    uint4 old[CBW][2];
+                    if (ADD) {      // read in the MFMA layout, so that the sum is formed in fp32 and rounded once
+                        bool ok1;
+                        const uint32_t off1 = pixel_offset(pblock + m, ok1);
+#pragma unroll
+                        for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+                            for (int h = 0; h < 2; ++h) {
+                                const int ch = chg + cb * 32 + g * 16 + h * 8;
+                                old[cb][h] = buf_load16(ors, (ok1 && ch < p.Cout) ? off1 + (uint32_t)ch * 2u : kOutOfRange);
+                            }
+                    }
+                    bool ok2[2];
+                    uint32_t off2[2];
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) off2[j] = pixel_offset(pblock + j * 16 + (lane >> 2), ok2[j]);
+#pragma unroll
+                    for (int cb = 0; cb < CBW; ++cb) {
+#pragma unroll
+                        for (int h = 0; h < 2; ++h) {
+                            uint32_t w[4];
+                            if (ADD) {
+                                float v[8];
+#pragma unroll
+                                for (int k = 0; k < 8; ++k) v[k] = __int_as_float(max(__float_as_int(acc[cb][pb][h * 8 + k]), floor_i));
+                                const uint4 o = old[cb][h];
+                                v[0] += unpack_lo<DT>(o.x); v[1] += unpack_hi<DT>(o.x);
+                                v[2] += unpack_lo<DT>(o.y); v[3] += unpack_hi<DT>(o.y);
+                                v[4] += unpack_lo<DT>(o.z); v[5] += unpack_hi<DT>(o.z);
+                                v[6] += unpack_lo<DT>(o.w); v[7] += unpack_hi<DT>(o.w);
+#pragma unroll
+                                for (int k = 0; k < 4; ++k) w[k] = pack2<DT>(v[2 * k], v[2 * k + 1]);
+                            } else {
+#pragma unroll
+                                for (int k = 0; k < 4; ++k)
+                                    w[k] = relu_pair(pack2<DT>(acc[cb][pb][h * 8 + 2 * k], acc[cb][pb][h * 8 + 2 * k + 1]), floor16);
+                            }
+                            *(uint4 *)(ost + m * kOst3Ps + g * 32 + h * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+                        }
+                        __builtin_amdgcn_wave_barrier();     // LDS serves one wave's accesses in order: no wait needed
+                        const int ch = chg + cb * 32 + (lane & 3) * 8;
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const uint4 v = *(const uint4 *)(ost + (j * 16 + (lane >> 2)) * kOst3Ps + (lane & 3) * 16);
+                            buf_store16(ors, (ok2[j] && ch < p.Cout) ? off2[j] + (uint32_t)ch * 2u : kOutOfRange, v);
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                }
+            }
+        }
+        const Work3 nxt = resolve_chunk(rq);             // the loads waited for in this chunk are younger than its request
+        __syncthreads();
+        par ^= 1u;
+        cur = mid;
+        mid = ahead;
+        ahead = nxt;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+struct Shape3 {
+    int pp;          // output pixels per pass
+    int cc;          // input channels per chunk
+    bool ok;
+    Plan3 q;
+    size_t lds_bytes;
+};
+
+static Shape3 plan3(const ConvParams &p, int pp) {
+    Shape3 sh;
+    sh.pp = pp;
+    sh.ok = false;
+    Plan3 &q = sh.q;
+    const long long M = (long long)p.oh * p.ow;
+    const int CinP = (p.Cin + 31) / 32 * 32;
+    q.mpasses = (int)((M + pp - 1) / pp);
+    q.ngroups = (p.Cout + 63) / 64;
+    q.div_pt = make_fastdiv((uint32_t)q.mpasses * q.ngroups);
+    q.div_ng = make_fastdiv((uint32_t)q.ngroups);
+    q.div_sw = make_fastdiv((uint32_t)p.sw);
+    // input rows a pass of pp consecutive output pixels can touch
+    long long out_rows = (pp + p.ow - 1) / p.ow + ((pp % p.ow) ? 1 : 0);
+    if (out_rows > p.oh) out_rows = p.oh;
+    long long rows = (out_rows - 1) * p.sh + 3;
+    if (rows > p.th) rows = p.th;
+    q.cpp = (p.tw + p.sw - 1) / p.sw;
+    q.ks16 = 9 * (CinP / 16);
+    q.w_bytes = (uint32_t)((size_t)q.ngroups * q.ks16 * 2048);
+    q.lo = 0;
+    q.hi = 0xffffffffu;
+    const size_t bias_bytes = (size_t)q.ngroups * 64 * 4;
+    // chunks of 32 channels with up to 6 input vectors per thread, else of 16 with up to 9; two buffers must fit
+    for (int cc = 32; cc >= 16; cc -= 16) {
+        const long long nvec = rows * p.tw * (cc / 8);
+        if ((nvec + 255) / 256 > (cc == 32 ? 6 : 9)) continue;
+        const long long in_b = rows * p.sw * q.cpp * (cc * 2 + 16);
+        const long long buf = in_b + 9 * (cc / 16) * 2048;
+        const long long total = 2 * buf + kDump3 + 4 * kOst3 + (long long)bias_bytes;
+        if (total > kLds3) continue;
+        sh.cc = cc;
+        q.nvec_in = (uint32_t)nvec;
+        q.nchunks = CinP / cc;
+        q.div_nch = make_fastdiv((uint32_t)q.nchunks);
+        q.w_off = (uint32_t)in_b;
+        q.buf_bytes = (uint32_t)buf;
+        q.dump_off = 2u * q.buf_bytes;
+        q.ost_off = q.dump_off + kDump3;
+        q.bias_off = q.ost_off + 4 * kOst3;
+        sh.lds_bytes = (size_t)total;
+        sh.ok = true;
+        break;
+    }
+    return sh;
+}
+
+template <int DT, bool FUSED, bool ADD, int WP, int CBW, int PBW>
+static void launch3_cc(const ConvParams &p, const Shape3 &sh, int grid, hipStream_t s) {
+#define SBNET_L3(CC, NVI)                                                                                      \
+    do {                                                                                                       \
+        auto kern = conv3_kernel<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI>;                                       \
+        if (sh.lds_bytes > 48 * 1024)                                                                          \
+            (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,          \
+                                      (int)sh.lds_bytes);                                                      \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), sh.lds_bytes, s, p, sh.q);                             \
+    } while (0)
+    if (sh.cc == 32) SBNET_L3(32, 6);
+    else SBNET_L3(16, 9);
+#undef SBNET_L3
+}
+
+template <int DT, bool FUSED, bool ADD>
+static void launch3_shape(const ConvParams &p, const Shape3 &sh, int grid, hipStream_t s) {
+    if (sh.pp == 256) launch3_cc<DT, FUSED, ADD, 4, 2, 2>(p, sh, grid, s);
+    else if (sh.pp == 128) launch3_cc<DT, FUSED, ADD, 4, 2, 1>(p, sh, grid, s);
+    else launch3_cc<DT, FUSED, ADD, 2, 1, 1>(p, sh, grid, s);
+}
+
+static void launch3(sbnet_dtype dt, bool fused, const ConvParams &p, const Shape3 &sh, hipStream_t s) {
+    long long items = (long long)p.cap * sh.q.mpasses * sh.q.ngroups;
+    long long g = (items + 7) / 8 * 8;
+    if (g > 256) g = 256;                             // one persistent workgroup per CU
+    const int grid = (int)g;
+    if (dt == SBNET_BF16) {
+        if (fused && p.add) launch3_shape<SBNET_BF16, true, true>(p, sh, grid, s);
+        else if (fused) launch3_shape<SBNET_BF16, true, false>(p, sh, grid, s);
+        else launch3_shape<SBNET_BF16, false, false>(p, sh, grid, s);
+    } else {
+        if (fused && p.add) launch3_shape<SBNET_F16, true, true>(p, sh, grid, s);
+        else if (fused) launch3_shape<SBNET_F16, true, false>(p, sh, grid, s);
+        else launch3_shape<SBNET_F16, false, false>(p, sh, grid, s);
+    }
+}
+
+bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, sbnet_status *st, const char *who) {
+    if (dt != SBNET_BF16 && dt != SBNET_F16) return false;
+    if (p0.kh != 3 || p0.kw != 3) return false;
+    if (p0.Cin % 8 != 0 || p0.Cout % 8 != 0) return false;
+    // byte offsets inside one sample (fused) or one tile are kept in 32 bits and checked by the hardware
+    // against a buffer descriptor of that size
+    if ((fused ? (long long)p0.H * p0.W : (long long)p0.th * p0.tw) * p0.Cin >= (1LL << 30)) return false;
+    if ((fused ? (long long)p0.Ho * p0.Wo : (long long)p0.oh * p0.ow) * p0.Cout >= (1LL << 30)) return false;
+    ConvParams p = p0;
+    p.CinP = (p.Cin + 31) / 32 * 32;
+    const long long M = (long long)p.oh * p.ow;
+    if ((long long)((p.Cout + 63) / 64) * 9 * (p.CinP / 16) * 2048 >= (1LL << 31)) return false;
+
+    Shape3 big, small;
+    big.ok = small.ok = false;
+    if (M <= 64) {
+        big = plan3(p, 64);
+    } else {
+        if (M > 128) big = plan3(p, 256);
+        small = plan3(p, 128);
+    }
+    if (!big.ok && !small.ok) return false;
+    if ((long long)p.cap * (big.ok ? big.q.mpasses : small.q.mpasses) * ((p.Cout + 63) / 64) >= (1LL << 31)) return false;
+    if (big.ok && small.ok) {
+        // the larger tile once it alone gives every CU an item, the smaller one (twice the items) below that
+        const long long per_tile = (long long)big.q.mpasses * big.q.ngroups;
+        const long long thr = (256 + per_tile - 1) / per_tile;
+        if (thr <= 1) small.ok = false;
+        else if (p.cap < thr) big.ok = false;
+        else {
+            big.q.lo = (uint32_t)thr;
+            small.q.hi = (uint32_t)thr - 1u;
+        }
+    }
+    if (big.ok) launch3(dt, fused, p, big, s);
+    if (small.ok) launch3(dt, fused, p, small, s);
+    *st = launch_status(who);
+    return true;
+}
+
+}  // namespace sbnet

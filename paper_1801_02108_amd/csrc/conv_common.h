@@ -95,7 +95,43 @@ __device__ __forceinline__ float unpack_hi(uint32_t w) {
     return (float)v.h[1];
 }
 
+// ------------------------------------------------------------------------------------------
+// shared by the 32x32x16 MFMA kernels (conv16.hip, conv3.hip)
+// ------------------------------------------------------------------------------------------
+constexpr uint32_t kBufWord3 = 0x00020000u;      // raw buffer descriptor, 32-bit data format
+constexpr uint32_t kOutOfRange = 0x80000000u;    // offset beyond any descriptor these kernels build (all below 2 GiB)
+
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+
+template <int DT>
+__device__ __forceinline__ f32x16 mfma32x32x16(uint4 a, uint4 b, f32x16 c) {
+    if (DT == SBNET_BF16) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+}
+
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t relu_pair(uint32_t w, uint32_t floor2) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2, w), __builtin_bit_cast(i16x2, floor2)));
+}
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, uint32_t off, uint4 d) {
+    u32x4 v;
+    v[0] = d.x; v[1] = d.y; v[2] = d.z; v[3] = d.w;
+    // non-temporal: the results are not read again here and should not push input lines, which neighbouring
+    // tiles read again for their halos, out of L2
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)off, 0, 2);
+}
+
 // conv16.hip: returns true when it took the job (status in *st), false when the shape is not its own.
 bool conv16_try(sbnet_dtype dt, bool fused, const ConvParams &p, hipStream_t s, sbnet_status *st, const char *who);
+// conv3.hip: the same contract for the LDS-tiled 3x3 kernel (any stride, tile size and channel counts that are multiples of 8).
+bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p, hipStream_t s, sbnet_status *st, const char *who);
 
 }  // namespace sbnet
