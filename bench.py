@@ -280,21 +280,29 @@ def run_stages(args):
             def step():
                 sb.reduce_mask(m_d, g_out, sb.POOL_AVG, 0.0, idx, cnt, ws)
                 sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y, stride=s, relu=True)
-            for _ in range(3):
-                step()
-            torch.cuda.synchronize()
-            e0.record()
-            for _ in range(50):
-                step()
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / 50
-            e0.record()
-            for _ in range(50):
-                sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y, stride=s, relu=True)
-            e1.record()
-            torch.cuda.synchronize()
-            k_ms = e0.elapsed_time(e1) / 50
+            # device time per call: HIP events around replays of a graph of 20 back-to-back calls (eager launches of
+            # kernels this short would measure the host's launch rate)
+            def device_ms(fn, reps=20, replays=5):
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    fn()
+                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.synchronize()
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr):
+                    for _ in range(reps):
+                        fn()
+                gr.replay()
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(replays):
+                    gr.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / (reps * replays)
+            ms = device_ms(step)
+            k_ms = device_ms(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y, stride=s, relu=True))
             if target >= 1.0:
                 dense_ms = ms
             rows.append({"H": H, "W": W, "Cin": Cin, "Cout": Cout, "stride": s, "block": bo, "target": target,

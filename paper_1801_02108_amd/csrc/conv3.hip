@@ -25,10 +25,12 @@
 //   * Results are transposed through a wave-private LDS area, 32 pixels x 32 channels at a time, so that a store
 //     instruction writes 64-byte runs instead of 16-byte pieces.
 //   * Workgroup tiles: 256 pixels x 64 channels (wave: 64 px x 64 ch, 4 accumulators), 128 x 64 for problems
-//     with too few items to fill the device (picked on the device from the active count: both are launched, one
-//     returns at once), and 64 x 64 for tiles of at most 64 output pixels.  Chunks of 32 channels where two
+//     where that means fewer rounds of work on the device (picked on the device from the active count: both are
+//     launched, one returns at once), and 64 x 64 for tiles of at most 64 output pixels.  Chunks of 32 channels where two
 //     buffers of that fit in LDS (stride 1), else of 16 (the 33x33 input tile of a strided 16x16 block).
 #include "conv_common.h"
+
+#include <type_traits>
 
 namespace sbnet {
 
@@ -48,7 +50,9 @@ struct Plan3 {
     uint32_t dump_off, ost_off, bias_off;    // after the two buffers
     uint32_t w_bytes;        // bytes of the 32x32x16 operand copy of the weights
     int ks16;                // 16-channel k-steps per output group: 9 * CinP / 16
-    uint32_t lo, hi;         // run only when lo <= active blocks <= hi
+    // Two shapes of the workgroup tile may be launched for one call; the device-side count decides which one runs.
+    int role;                // 0: the only launch; 1: the larger tile of a pair; 2: the smaller one
+    uint32_t per_tile_big, per_tile_small;   // work items per active block of the two shapes
 };
 
 struct Item3 {
@@ -72,7 +76,7 @@ struct Chunk3 {
     uint32_t wofs;           // byte offset of (group, tap 0, channel c0) in the packed weights
 };
 
-template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
+template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI, int RS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void conv3_kernel(ConvParams p, Plan3 q) {
     static_assert(FUSED || !ADD, "adding into the output is part of the fused form");
@@ -97,7 +101,13 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     const int M = p.oh * p.ow;
 
     const int nact = max(min(*p.count, p.cap), 0);
-    if ((uint32_t)nact < q.lo || (uint32_t)nact > q.hi) return;
+    if (q.role != 0) {
+        // rounds of work on 256 CUs with either shape; an item of the smaller tile costs about 5/8 of a larger one
+        // (half the matrix work, the same weights to stage)
+        const uint32_t rb = ((uint32_t)nact * q.per_tile_big + 255u) >> 8, rs = ((uint32_t)nact * q.per_tile_small + 255u) >> 8;
+        const bool big = rb * 8u <= rs * 5u;
+        if (big != (q.role == 1)) return;
+    }
     const uint32_t per_tile = (uint32_t)q.mpasses * q.ngroups;
     const uint32_t items = (uint32_t)nact * per_tile;
     const uint32_t G = gridDim.x;                    // multiple of 8
@@ -192,20 +202,20 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         (void *)((const uint4 *)p.w + p.w32_offset), 0, (int)q.w_bytes, (int)kBufWord3);
 
-    uint4 stage[NV];
+    uint4 stage[RS][NV];
     // Rows outside the image fall outside the descriptor by themselves; columns outside would wrap into the
     // neighbouring row and channels past Cin into the neighbouring pixel, so those get the out-of-range offset.
-    auto issue1 = [&](int u, const Chunk3 &ch, bool chan_ok) __attribute__((always_inline)) {
+    auto issue1 = [&](int r, int u, const Chunk3 &ch, bool chan_ok) __attribute__((always_inline)) {
         if (u < NVI) {
             const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)ch.base, 0, (int)in_bytes, (int)kBufWord3);
             const bool ok = chan_ok && (uint32_t)(ch.gx0 + colv[u]) < (uint32_t)in_w;
-            stage[u] = buf_load16(rs, ok ? ch.origin + gdelta[u] : kOutOfRange);
+            stage[r][u] = buf_load16(rs, ok ? ch.origin + gdelta[u] : kOutOfRange);
         } else {
-            stage[u] = buf_load16(wrs, wsrc[u - NVI] + ch.wofs);
+            stage[r][u] = buf_load16(wrs, wsrc[u - NVI] + ch.wofs);
         }
     };
-    auto write1 = [&](int u, uint32_t bufno) __attribute__((always_inline)) {
-        *(uint4 *)(lds + lbase[u] + bufno * lstep[u]) = stage[u];
+    auto write1 = [&](int r, int u, uint32_t bufno) __attribute__((always_inline)) {
+        *(uint4 *)(lds + lbase[u] + bufno * lstep[u]) = stage[r][u];
     };
     auto chunk_of = [&](const Src3 &s, int c) __attribute__((always_inline)) {
         Chunk3 ch;
@@ -218,9 +228,11 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     };
 
     // ---- the workgroup's chunks, numbered gi = 0, 1, ... over its items: chunk gi is chunk gi % nchunks of item
-    //      first + (gi / nchunks) * G (past the end: the last item again, staged but never used).  Three are
-    //      known at any time: the one the matrix cores work on, the one on its way to LDS and the one being
-    //      requested; the index triple of a fourth is in flight.
+    //      first + (gi / nchunks) * G (past the end: the last item again, staged but never used).  RS + 2 are
+    //      known at any time: line[0] is the one the matrix cores work on, line[1] is on its way from registers to
+    //      LDS, line[RS + 1] is being requested; the index triple of one more is in flight.  RS = 1 where the
+    //      matrix work of a chunk covers a memory round trip, RS = 2 (two register sets, requests two chunks
+    //      further ahead) for the small workgroup tiles, whose chunks are shorter than that.
     struct Work3 {
         Item3 it;
         Src3 s;
@@ -240,17 +252,18 @@ void conv3_kernel(ConvParams p, Plan3 q) {
         w.s = source(w.it);
         return w;
     };
-    Work3 cur = request_chunk(0), mid = request_chunk(1), ahead = request_chunk(2);
-    cur = resolve_chunk(cur);
-    mid = resolve_chunk(mid);
-    ahead = resolve_chunk(ahead);
+    Work3 line[RS + 2];
+#pragma unroll
+    for (int k = 0; k < RS + 2; ++k) line[k] = request_chunk(k);
+#pragma unroll
+    for (int k = 0; k < RS + 2; ++k) line[k] = resolve_chunk(line[k]);
     const uint32_t nwork = ((last - first) / G + 1u) * (uint32_t)q.nchunks;     // chunks of this workgroup
 
-    {   // chunk 0 -> LDS buffer 0; chunk 1 stays in flight
-        const Chunk3 ch = chunk_of(cur.s, cur.c);
+    {   // chunk 0 -> LDS buffer 0; chunks 1 .. RS stay in flight
+        const Chunk3 ch = chunk_of(line[0].s, line[0].c);
         const bool chan_ok = ch.c0 + c8 * 8 < p.Cin;
 #pragma unroll
-        for (int u = 0; u < NV; ++u) issue1(u, ch, chan_ok);
+        for (int u = 0; u < NV; ++u) issue1(0, u, ch, chan_ok);
     }
     // bias of all groups -> LDS (zeros past Cout or without bias)
     {
@@ -268,12 +281,13 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     int floor_i = p.relu ? 0 : (int)0x80000000;
     asm volatile("" : "+s"(floor_i));
 #pragma unroll
-    for (int u = 0; u < NV; ++u) write1(u, 0);
-    {
-        const Chunk3 ch = chunk_of(mid.s, mid.c);
+    for (int u = 0; u < NV; ++u) write1(0, u, 0);
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        const Chunk3 ch = chunk_of(line[r + 1].s, line[r + 1].c);
         const bool chan_ok = ch.c0 + c8 * 8 < p.Cin;
 #pragma unroll
-        for (int u = 0; u < NV; ++u) issue1(u, ch, chan_ok);
+        for (int u = 0; u < NV; ++u) issue1(r, u, ch, chan_ok);
     }
     __syncthreads();
 
@@ -282,11 +296,14 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     f32x16 acc[CBW][PBW];
     uint32_t p_lo = 0;
     uint32_t xbase[PBW];
-    for (uint32_t gi = 0; gi < nwork; ++gi) {
-        const Work3 rq = request_chunk(gi + 3);
+    // one chunk: register set R holds chunk gi + 1 on entry and chunk gi + RS + 1 on exit
+    auto chunk_body = [&](auto r_tag, uint32_t gi) __attribute__((always_inline)) {
+        constexpr int R = decltype(r_tag)::value;
+        const Work3 rq = request_chunk(gi + RS + 2);
+        const Work3 cur = line[0];
         const bool firstc = cur.c == 0, lastc = cur.c + 1 == q.nchunks;
         {
-            const Chunk3 aheadc = chunk_of(ahead.s, ahead.c);
+            const Chunk3 aheadc = chunk_of(line[RS + 1].s, line[RS + 1].c);
             const bool chan_ok = aheadc.c0 + c8 * 8 < p.Cin;
             const unsigned char *B = lds + par * q.buf_bytes;
             if (firstc) {
@@ -344,8 +361,8 @@ void conv3_kernel(ConvParams p, Plan3 q) {
                             if (cb * PBW + pb < PER) {
                                 const int u = s * PER + cb * PBW + pb;
                                 if (u < NV) {
-                                    write1(u, par ^ 1u);
-                                    issue1(u, aheadc, chan_ok);
+                                    write1(R, u, par ^ 1u);
+                                    issue1(R, u, aheadc, chan_ok);
                                 }
                             }
                         }
@@ -354,8 +371,8 @@ void conv3_kernel(ConvParams p, Plan3 q) {
                         for (int e = NM; e < PER; ++e) {
                             const int u = s * PER + e;
                             if (u < NV) {
-                                write1(u, par ^ 1u);
-                                issue1(u, aheadc, chan_ok);
+                                write1(R, u, par ^ 1u);
+                                issue1(R, u, aheadc, chan_ok);
                             }
                         }
                     }
@@ -450,9 +467,13 @@ void conv3_kernel(ConvParams p, Plan3 q) {
         const Work3 nxt = resolve_chunk(rq);             // the loads waited for in this chunk are younger than its request
         __syncthreads();
         par ^= 1u;
-        cur = mid;
-        mid = ahead;
-        ahead = nxt;
+#pragma unroll
+        for (int k = 0; k < RS + 1; ++k) line[k] = line[k + 1];
+        line[RS + 1] = nxt;
+    };
+    for (uint32_t gi = 0; gi < nwork; gi += RS) {
+        chunk_body(std::integral_constant<int, 0>{}, gi);
+        if (RS > 1 && gi + 1 < nwork) chunk_body(std::integral_constant<int, RS - 1>{}, gi + 1);
     }
 }
 
@@ -487,8 +508,8 @@ static Shape3 plan3(const ConvParams &p, int pp) {
     q.cpp = (p.tw + p.sw - 1) / p.sw;
     q.ks16 = 9 * (CinP / 16);
     q.w_bytes = (uint32_t)((size_t)q.ngroups * q.ks16 * 2048);
-    q.lo = 0;
-    q.hi = 0xffffffffu;
+    q.role = 0;
+    q.per_tile_big = q.per_tile_small = 0;
     const size_t bias_bytes = (size_t)q.ngroups * 64 * 4;
     // chunks of 32 channels with up to 6 input vectors per thread, else of 16 with up to 9; two buffers must fit
     for (int cc = 32; cc >= 16; cc -= 16) {
@@ -518,7 +539,7 @@ template <int DT, bool FUSED, bool ADD, int WP, int CBW, int PBW>
 static void launch3_cc(const ConvParams &p, const Shape3 &sh, int grid, hipStream_t s) {
 #define SBNET_L3(CC, NVI)                                                                                      \
     do {                                                                                                       \
-        auto kern = conv3_kernel<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI>;                                       \
+        auto kern = conv3_kernel<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI, (WP * PBW >= 8 ? 1 : 2)>;                                       \
         if (sh.lds_bytes > 48 * 1024)                                                                          \
             (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,          \
                                       (int)sh.lds_bytes);                                                      \
@@ -574,17 +595,15 @@ bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, 
         small = plan3(p, 128);
     }
     if (!big.ok && !small.ok) return false;
-    if ((long long)p.cap * (big.ok ? big.q.mpasses : small.q.mpasses) * ((p.Cout + 63) / 64) >= (1LL << 31)) return false;
+    const int most_passes = small.ok ? small.q.mpasses : big.q.mpasses;          // the smaller tile has more of them
+    if ((long long)p.cap * most_passes * ((p.Cout + 63) / 64) >= (1LL << 31)) return false;
+    // with at most 256 items of the smaller tile whatever the count, the rule in the kernel never picks the larger one
+    if (big.ok && small.ok && (long long)p.cap * small.q.mpasses * small.q.ngroups <= 256) big.ok = false;
     if (big.ok && small.ok) {
-        // the larger tile once it alone gives every CU an item, the smaller one (twice the items) below that
-        const long long per_tile = (long long)big.q.mpasses * big.q.ngroups;
-        const long long thr = (256 + per_tile - 1) / per_tile;
-        if (thr <= 1) small.ok = false;
-        else if (p.cap < thr) big.ok = false;
-        else {
-            big.q.lo = (uint32_t)thr;
-            small.q.hi = (uint32_t)thr - 1u;
-        }
+        big.q.role = 1;
+        small.q.role = 2;
+        big.q.per_tile_big = small.q.per_tile_big = (uint32_t)big.q.mpasses * big.q.ngroups;
+        big.q.per_tile_small = small.q.per_tile_small = (uint32_t)small.q.mpasses * small.q.ngroups;
     }
     if (big.ok) launch3(dt, fused, p, big, s);
     if (small.ok) launch3(dt, fused, p, small, s);

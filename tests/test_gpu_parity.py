@@ -232,6 +232,13 @@ CONV_CASES = [
     (3, 18, 18, 32, 128, 3, 1, "bf16", True, True),     # register-stationary 3x3 kernel: two channel groups
     (2, 34, 18, 64, 24, 3, 1, "f16", False, True),      # ... two sub-tiles per tile, partial channel group
     (2, 18, 50, 32, 64, 3, 1, "bf16", True, False),     # ... three sub-tiles side by side
+    # LDS-tiled 3x3 kernel
+    (3, 26, 26, 40, 96, 3, 1, "bf16", True, True),      # three passes, last one short; padded channel chunk; Cout % 64 == 32
+    (2, 33, 33, 96, 64, 3, 2, "bf16", True, True),      # stride-2 tile of a 16x16 block: chunks of 16 channels
+    (4, 17, 17, 64, 32, 3, 2, "f16", False, True),      # stride-2 tile of an 8x8 block: 64-pixel workgroup tile
+    (2, 21, 19, 16, 8, 3, 1, "bf16", False, False),     # odd tile sides, one chunk per item
+    (3, 12, 12, 8, 72, 3, 3, "f16", True, True),        # stride 3: three column phases; last group of 8 channels
+    (2, 10, 70, 24, 16, 3, 1, "bf16", True, True),      # wide, flat tile: a pass covers part of a row
 ]
 
 
@@ -264,6 +271,11 @@ SPARSE_CASES = [
     (2, 35, 35, 8, 8, 3, 2, 4, "bf16"),        # strided convolution
     (1, 24, 24, 6, 5, 3, 1, 8, "f32"),
     (1, 32, 32, 64, 256, 1, 1, 16, "bf16"),
+    # LDS-tiled 3x3 kernel
+    (2, 70, 66, 96, 96, 3, 2, 16, "bf16"),     # downsampling unit, blocks hang over the edge, Cout % 64 == 32
+    (1, 96, 80, 192, 32, 3, 1, 16, "f16"),     # six channel chunks
+    (3, 40, 40, 32, 64, 3, 1, 8, "bf16"),      # 8x8 blocks, one chunk per item: the chunk pipeline runs over items
+    (1, 33, 49, 48, 40, 3, 2, 8, "bf16"),      # stride 2 with 8x8 blocks, ragged
 ]
 
 
@@ -302,12 +314,14 @@ def test_sparse_conv_fused_and_unfused(N, H, W, Cin, Cout, k, s, bo, dtype, add)
 
 
 @pytest.mark.parametrize("dens", [1.0, 0.35])
-def test_sparse_conv_more_tiles_than_workgroups(dens):
-    """Persistent kernel: 342 tiles on at most 256 workgroups, so the double-buffered tile loop
-    and its prefetch run several iterations per workgroup."""
-    step("sparse_conv persistent loop dens=%s" % dens)
+@pytest.mark.parametrize("Cin", [32, 40])
+def test_sparse_conv_more_tiles_than_workgroups(dens, Cin):
+    """Persistent kernels: 342 tiles on at most 256 workgroups, so the double-buffered tile loop and its prefetch
+    run several iterations per workgroup.  Cin = 32: register-stationary kernel; Cin = 40: LDS-tiled kernel, which
+    launches its 256-pixel and its 128-pixel variant and lets the device-side count pick (above / below 256 items)."""
+    step("sparse_conv persistent loop dens=%s Cin=%d" % (dens, Cin))
     r = gen.rng_for(5, 999)
-    N, H, W, Cin, Cout, bo = 1, 288, 304, 32, 64, 16
+    N, H, W, Cout, bo = 1, 288, 304, 64, 16
     g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, 1, bo)
     x = gen.activations(r, (N, H, W, Cin), "bf16")
     w = gen.conv_weights(r, 3, 3, Cin, Cout, "bf16")
