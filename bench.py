@@ -283,6 +283,16 @@ def run_stages(args):
             # device time per call: HIP events around replays of a graph of 20 back-to-back calls (eager launches of
             # kernels this short would measure the host's launch rate)
             def device_ms(fn, reps=20, replays=5):
+                if args.eager_kernel_timing:                       # under rocprofv3: no graphs
+                    for _ in range(3):
+                        fn()
+                    torch.cuda.synchronize()
+                    e0.record()
+                    for _ in range(50):
+                        fn()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    return e0.elapsed_time(e1) / 50
                 side = torch.cuda.Stream()
                 side.wait_stream(torch.cuda.current_stream())
                 with torch.cuda.stream(side):
@@ -314,7 +324,7 @@ def run_stages(args):
                       "steps": 50, "warmup": 3, "ms_per_step": head["step_ms"], "higher_is_better": False, "scaling": "weak",
                       "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
                       "config": {"workload": "stages: single sparse 3x3 conv + ReLU, bf16, N=1, stride 1 and 2, road-band masks; "
-                                             "eager launches, step = reduce_mask + fused conv", "headline_row": head},
+                                             "HIP graph replays, step = reduce_mask + fused conv", "headline_row": head},
                       "rows": rows}))
 
 

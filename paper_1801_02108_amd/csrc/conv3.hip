@@ -76,10 +76,14 @@ struct Chunk3 {
     uint32_t wofs;           // byte offset of (group, tap 0, channel c0) in the packed weights
 };
 
-template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI, int RS>
+template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void conv3_kernel(ConvParams p, Plan3 q) {
     static_assert(FUSED || !ADD, "adding into the output is part of the fused form");
+    // Register sets for chunks in flight.  Two (requests two chunks further ahead) were measured for the small
+    // workgroup tiles and gained nothing: the compiler's wait before a vector's LDS write allows only one set's
+    // worth of younger loads, and those tiles are bound by the issue of their staging instructions anyway.
+    constexpr int RS = 1;
     constexpr int CV = CC / 8;                       // 16-byte vectors per pixel and chunk
     constexpr int KST = CC / 16;                     // k-steps of 16 channels per tap
     constexpr int NS = 9 * KST;                      // MFMA steps per chunk
@@ -230,9 +234,7 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     // ---- the workgroup's chunks, numbered gi = 0, 1, ... over its items: chunk gi is chunk gi % nchunks of item
     //      first + (gi / nchunks) * G (past the end: the last item again, staged but never used).  RS + 2 are
     //      known at any time: line[0] is the one the matrix cores work on, line[1] is on its way from registers to
-    //      LDS, line[RS + 1] is being requested; the index triple of one more is in flight.  RS = 1 where the
-    //      matrix work of a chunk covers a memory round trip, RS = 2 (two register sets, requests two chunks
-    //      further ahead) for the small workgroup tiles, whose chunks are shorter than that.
+    //      LDS, line[RS + 1] is being requested; the index triple of one more is in flight.
     struct Work3 {
         Item3 it;
         Src3 s;
@@ -259,11 +261,14 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     for (int k = 0; k < RS + 2; ++k) line[k] = resolve_chunk(line[k]);
     const uint32_t nwork = ((last - first) / G + 1u) * (uint32_t)q.nchunks;     // chunks of this workgroup
 
-    {   // chunk 0 -> LDS buffer 0; chunks 1 .. RS stay in flight
-        const Chunk3 ch = chunk_of(line[0].s, line[0].c);
+    // chunk k lives in register set k % RS: chunks 0 .. RS-1 are requested at once, chunk 0 goes to LDS buffer 0 and
+    // chunk RS takes its registers
+#pragma unroll
+    for (int r = 0; r < RS; ++r) {
+        const Chunk3 ch = chunk_of(line[r].s, line[r].c);
         const bool chan_ok = ch.c0 + c8 * 8 < p.Cin;
 #pragma unroll
-        for (int u = 0; u < NV; ++u) issue1(0, u, ch, chan_ok);
+        for (int u = 0; u < NV; ++u) issue1(r, u, ch, chan_ok);
     }
     // bias of all groups -> LDS (zeros past Cout or without bias)
     {
@@ -282,12 +287,11 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     asm volatile("" : "+s"(floor_i));
 #pragma unroll
     for (int u = 0; u < NV; ++u) write1(0, u, 0);
-#pragma unroll
-    for (int r = 0; r < RS; ++r) {
-        const Chunk3 ch = chunk_of(line[r + 1].s, line[r + 1].c);
+    {
+        const Chunk3 ch = chunk_of(line[RS].s, line[RS].c);
         const bool chan_ok = ch.c0 + c8 * 8 < p.Cin;
 #pragma unroll
-        for (int u = 0; u < NV; ++u) issue1(r, u, ch, chan_ok);
+        for (int u = 0; u < NV; ++u) issue1(0, u, ch, chan_ok);
     }
     __syncthreads();
 
@@ -296,7 +300,7 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     f32x16 acc[CBW][PBW];
     uint32_t p_lo = 0;
     uint32_t xbase[PBW];
-    // one chunk: register set R holds chunk gi + 1 on entry and chunk gi + RS + 1 on exit
+    // one chunk: register set R = (gi + 1) % RS holds chunk gi + 1 on entry and chunk gi + RS + 1 on exit
     auto chunk_body = [&](auto r_tag, uint32_t gi) __attribute__((always_inline)) {
         constexpr int R = decltype(r_tag)::value;
         const Work3 rq = request_chunk(gi + RS + 2);
@@ -472,8 +476,8 @@ void conv3_kernel(ConvParams p, Plan3 q) {
         line[RS + 1] = nxt;
     };
     for (uint32_t gi = 0; gi < nwork; gi += RS) {
-        chunk_body(std::integral_constant<int, 0>{}, gi);
-        if (RS > 1 && gi + 1 < nwork) chunk_body(std::integral_constant<int, RS - 1>{}, gi + 1);
+        chunk_body(std::integral_constant<int, 1 % RS>{}, gi);
+        if (RS > 1 && gi + 1 < nwork) chunk_body(std::integral_constant<int, 0>{}, gi + 1);
     }
 }
 
@@ -483,6 +487,7 @@ void conv3_kernel(ConvParams p, Plan3 q) {
 struct Shape3 {
     int pp;          // output pixels per pass
     int cc;          // input channels per chunk
+    int nvi;         // input vectors per thread and chunk the kernel is built for
     bool ok;
     Plan3 q;
     size_t lds_bytes;
@@ -511,10 +516,13 @@ static Shape3 plan3(const ConvParams &p, int pp) {
     q.role = 0;
     q.per_tile_big = q.per_tile_small = 0;
     const size_t bias_bytes = (size_t)q.ngroups * 64 * 4;
-    // chunks of 32 channels with up to 6 input vectors per thread, else of 16 with up to 9; two buffers must fit
+    // chunks of 32 channels with up to 6 input vectors per thread, else of 16 with up to 9 (kernels are built for
+    // 3 / 6 and 5 / 9: every vector costs its staging instructions whether it carries data or not); two buffers must fit
     for (int cc = 32; cc >= 16; cc -= 16) {
         const long long nvec = rows * p.tw * (cc / 8);
-        if ((nvec + 255) / 256 > (cc == 32 ? 6 : 9)) continue;
+        const long long need = (nvec + 255) / 256;
+        if (need > (cc == 32 ? 6 : 9)) continue;
+        sh.nvi = cc == 32 ? (need <= 3 ? 3 : 6) : (need <= 5 ? 5 : 9);
         const long long in_b = rows * p.sw * q.cpp * (cc * 2 + 16);
         const long long buf = in_b + 9 * (cc / 16) * 2048;
         const long long total = 2 * buf + kDump3 + 4 * kOst3 + (long long)bias_bytes;
@@ -539,13 +547,15 @@ template <int DT, bool FUSED, bool ADD, int WP, int CBW, int PBW>
 static void launch3_cc(const ConvParams &p, const Shape3 &sh, int grid, hipStream_t s) {
 #define SBNET_L3(CC, NVI)                                                                                      \
     do {                                                                                                       \
-        auto kern = conv3_kernel<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI, (WP * PBW >= 8 ? 1 : 2)>;                                       \
+        auto kern = conv3_kernel<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI>;                                       \
         if (sh.lds_bytes > 48 * 1024)                                                                          \
             (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,          \
                                       (int)sh.lds_bytes);                                                      \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), sh.lds_bytes, s, p, sh.q);                             \
     } while (0)
-    if (sh.cc == 32) SBNET_L3(32, 6);
+    if (sh.cc == 32 && sh.nvi == 3) SBNET_L3(32, 3);
+    else if (sh.cc == 32) SBNET_L3(32, 6);
+    else if (sh.nvi == 5) SBNET_L3(16, 5);
     else SBNET_L3(16, 9);
 #undef SBNET_L3
 }
