@@ -3,11 +3,14 @@
 // gather of the input tile and the scatter (or scatter-add, Sec. 3.4) of the output block
 // happen inside the same kernel, so the tile stacks never reach HBM.
 //
-// Two kernels:
+// Two kernels here, two more behind conv16_try / conv3_try (conv16.hip: 3x3 stride 1 on tiles whose sides are
+// multiples of 16 with 32 or 64 input channels; conv3.hip: every other 3x3 case the matrix cores can take), which
+// are asked first:
 //   conv_direct  any shape, any of f32/bf16/f16: one thread per output element, fp32 FMA chain.
 //                Used for f32 (there is no fp32 MFMA worth using at these sizes) and for channel
 //                counts the MFMA path does not take.
-//   conv_mfma    bf16/f16 with Cin % 8 == 0 and Cout % 8 == 0: implicit GEMM on the matrix cores.
+//   conv_mfma    bf16/f16 with Cin % 8 == 0 and Cout % 8 == 0, kernel sizes other than 3x3 (and 3x3 tiles too
+//                large for the other kernels' LDS plans): implicit GEMM on the matrix cores.
 //                Per workgroup: up to 256 output pixels x 64 output channels, fp32 accumulators in
 //                registers.  The input rows those pixels need are staged in LDS in channel chunks
 //                (pixel stride padded by 16 B so the 16-byte operand reads of 16 neighbouring pixels

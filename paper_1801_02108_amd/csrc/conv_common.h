@@ -1,5 +1,6 @@
 // Types shared by the convolution kernels (conv.hip: generic direct + MFMA kernels;
-// conv16.hip: the register-stationary 3x3 kernel for 16-pixel-wide output tiles).
+// conv16.hip: the register-stationary 3x3 kernel for 16-pixel-wide output tiles;
+// conv3.hip: the LDS-tiled 3x3 kernel for any stride and tile).
 #pragma once
 #include "common.h"
 
