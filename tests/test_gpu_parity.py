@@ -261,6 +261,37 @@ def test_conv_on_tiles(B, th, tw, Cin, Cout, k, s, dtype, relu, bias):
     assert (got[B] == 5.0).all()
 
 
+def _random_3x3_shapes(n, seed):
+    """Seeded draws over what the 3x3 matrix-core kernels take: tile sides 3..40, strides 1..3, channels in multiples of 8."""
+    r = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        s = int(r.integers(1, 4))
+        th, tw = int(r.integers(3, 41)), int(r.integers(3, 41))
+        cin, cout = 8 * int(r.integers(1, 13)), 8 * int(r.integers(1, 13))
+        out.append((int(r.integers(1, 5)), th, tw, cin, cout, s, ("bf16", "f16")[int(r.integers(0, 2))],
+                    bool(r.integers(0, 2)), bool(r.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("B,th,tw,Cin,Cout,s,dtype,relu,bias", _random_3x3_shapes(40, 180102108))
+def test_conv_on_tiles_random_3x3_shapes(B, th, tw, Cin, Cout, s, dtype, relu, bias):
+    """Passes per tile, rows per pass, column phases, channel chunks and groups all vary with the shape."""
+    step("conv_on_tiles random %s" % ((B, th, tw, Cin, Cout, s, dtype, relu, bias),))
+    r = gen.rng_for(4, th * 1000 + tw * 10 + Cin + Cout + s)
+    t = gen.activations(r, (B + 1, th, tw, Cin), dtype)
+    w = gen.conv_weights(r, 3, 3, Cin, Cout, dtype)
+    b = gen.bias_vector(r, Cout, 0.5) if bias else None
+    cnt = torch.tensor([B], dtype=torch.int32).cuda()
+    oh, ow = (th - 3) // s + 1, (tw - 3) // s + 1
+    out = torch.full((B + 1, oh, ow, Cout), 5.0, dtype=TORCH_DT[dtype]).cuda()
+    sb.conv_on_tiles(to_dev(t, dtype), cnt, sb.pack_weights(to_dev(w, dtype)), None if b is None else torch.from_numpy(b).cuda(),
+                     stride=s, relu=relu, out=out)
+    got = to_host(out)
+    assert_close(got[:B], orc.conv_valid(t[:B], w, b, stride=s, relu=relu), CONV_TOL[dtype], "conv_on_tiles")
+    assert (got[B] == 5.0).all()
+
+
 # --------------------------------------------------------------------------- fused sparse conv
 SPARSE_CASES = [
     # N, H, W, Cin, Cout, k, s, bo, dtype
@@ -311,6 +342,39 @@ def test_sparse_conv_fused_and_unfused(N, H, W, Cin, Cout, k, s, bo, dtype, add)
         got = to_host(y)
         assert_close(got, ref, CONV_TOL[dtype], "unfused")
         assert np.array_equal(got[~bm], y0[~bm])
+
+
+def _random_fused_shapes(n, seed):
+    r = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        out.append((int(r.integers(1, 3)), int(r.integers(20, 71)), int(r.integers(20, 71)), 8 * int(r.integers(1, 9)),
+                    8 * int(r.integers(1, 9)), int(r.integers(1, 3)), (3, 4, 5, 8, 10, 16)[int(r.integers(0, 6))],
+                    ("bf16", "f16")[int(r.integers(0, 2))], bool(r.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("N,H,W,Cin,Cout,s,bo,dtype,add", _random_fused_shapes(16, 20180102))
+def test_sparse_conv_random_shapes(N, H, W, Cin, Cout, s, bo, dtype, add):
+    """Fused 3x3 on seeded random image sizes, block sizes and strides: blocks hang over every edge in some case."""
+    step("sparse_conv random %s" % ((N, H, W, Cin, Cout, s, bo, dtype, add),))
+    r = gen.rng_for(5, H * 1000 + W * 10 + Cin + bo + s)
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, s, bo)
+    x = gen.activations(r, (N, H, W, Cin), dtype)
+    w = gen.conv_weights(r, 3, 3, Cin, Cout, dtype)
+    b = gen.bias_vector(r, Cout, 0.5)
+    y0 = gen.activations(r, (N, Ho, Wo, Cout), dtype)
+    mask = (r.random((N, H, W)) < 0.004).astype(np.uint8)
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in)
+    idx = orc.reduce_mask(mask, ogeom(g_in))
+    assert np.array_equal(d_idx[:len(idx)].cpu().numpy(), idx)
+    y = to_dev(y0, dtype)
+    sb.sparse_conv(to_dev(x, dtype), d_idx, d_cnt, g_in, g_out, sb.pack_weights(to_dev(w, dtype)), torch.from_numpy(b).cuda(),
+                   y, stride=s, relu=True, add=add)
+    got = to_host(y)
+    assert_close(got, orc.sparse_conv_dense(x, idx, ogeom(g_out), w, b, y0, stride=s, relu=True, add=add), CONV_TOL[dtype], "fused")
+    bm = orc.block_mask(idx, ogeom(g_out), N, Ho, Wo)
+    assert np.array_equal(got[~bm], y0[~bm])
 
 
 @pytest.mark.parametrize("dens", [1.0, 0.35])
