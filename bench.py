@@ -534,6 +534,11 @@ def main():
             t_gather = tk(lambda: sb.sparse_gather(x, idx_small, cnt, g_in, tiles_buf[0]))
             t_tconv = tk(lambda: sb.conv_on_tiles(tiles_buf[0], cnt, wp, bias, out=tiles_buf[1]))
             t_scatter = tk(lambda: sb.sparse_scatter(tiles_buf[1], idx_small, cnt, g_out, y))
+            # the same copies with the transpose to channel-major tiles fused in (Sec. 3.4)
+            chw_in = torch.empty((n, C, BO + 2, BO + 2), dtype=torch.bfloat16, device=dev)
+            chw_out = torch.empty((n, K, BO, BO), dtype=torch.bfloat16, device=dev)
+            t_gather_chw = tk(lambda: sb.sparse_gather_chw(x, idx_small, cnt, g_in, chw_in))
+            t_scatter_chw = tk(lambda: sb.sparse_scatter_chw(chw_out, idx_small, cnt, g_out, y))
             tile_in_b = (BO + 2) ** 2 * C * 2
             tile_out_b = BO * BO * K * 2
             row = {"target": target, "active_blocks": n, "step_ms": round(t_step, 5), "fused_conv_ms": round(t_conv, 5),
@@ -541,6 +546,8 @@ def main():
                    "gather_ms": round(t_gather, 5), "gather_GBps": round(2 * tile_in_b * n / t_gather / 1e6, 1),
                    "conv_on_tiles_ms": round(t_tconv, 5), "conv_on_tiles_tflops": round(TILE_FLOPS * n / t_tconv / 1e9, 2),
                    "scatter_ms": round(t_scatter, 5), "scatter_GBps": round(2 * tile_out_b * n / t_scatter / 1e6, 1),
+                   "gather_chw_ms": round(t_gather_chw, 5), "gather_chw_GBps": round(2 * tile_in_b * n / t_gather_chw / 1e6, 1),
+                   "scatter_chw_ms": round(t_scatter_chw, 5), "scatter_chw_GBps": round(2 * tile_out_b * n / t_scatter_chw / 1e6, 1),
                    "unfused_sum_ms": round(t_gather + t_tconv + t_scatter, 5)}
             if target >= 1.0:
                 dense_ms = t_step

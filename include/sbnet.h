@@ -116,6 +116,25 @@ sbnet_status sbnet_sparse_scatter(const void *tiles, sbnet_dtype dtype, const in
                                   int N, int H, int W, int C, int add, void *stream);
 
 /*
+ * Gather and scatter with the transpose fused in (Sec. 3.4 "Fused transpose+gather and
+ * transpose+scatter kernels"): the feature map is NHWC as above, the tile stack channel-major,
+ * tiles_chw: [cap][C][g->bsize_h][g->bsize_w], for a consumer that wants that layout.
+ *   gather_chw:  tiles_chw[b][c][i][j] = x[n_b][y0_b + i][x0_b + j][c], zero outside the image;
+ *   scatter_chw: y[n_b][y0_b + i][x0_b + j][c] = (add ? y[...] : 0) + tiles_chw[b][c][i][j] inside
+ *                the image, nothing else in y touched; non-overlapping blocks as for
+ *                sbnet_sparse_scatter; the sum is formed in fp32 and rounded to nearest even.
+ * Bit-exact copies otherwise.  Same dtype on both sides (F32, BF16 or F16); C * element size
+ * must be a multiple of 16 bytes and a tile at most 1280 pixels, else SBNET_EUNSUPPORTED.
+ */
+sbnet_status sbnet_sparse_gather_chw(const void *x, sbnet_dtype dtype, int N, int H, int W, int C,
+                                     const int32_t *indices, const int32_t *count, int cap,
+                                     const sbnet_geom *g, void *tiles_chw, void *stream);
+sbnet_status sbnet_sparse_scatter_chw(const void *tiles_chw, sbnet_dtype dtype,
+                                      const int32_t *indices, const int32_t *count, int cap,
+                                      const sbnet_geom *g, void *y, int N, int H, int W, int C,
+                                      int add, void *stream);
+
+/*
  * Re-pack convolution weights once for the kernels below.  w_hwio: device, [kh][kw][Cin][Cout]
  * in `dtype` (the filter bank as a (kh*kw*Cin) x Cout matrix, Sec. 2).  With w_packed == NULL
  * only *bytes (host) is set to the size the packed copy needs.  The packed layout is private

@@ -120,6 +120,16 @@ def scatter(tiles, idx, g, y, add=False):
     return y
 
 
+def gather_chw(x, idx, g):
+    """Gather with the transpose of Sec. 3.4 ("Fused transpose+gather"): channel-major tiles [B, C, size_h, size_w]."""
+    return np.ascontiguousarray(np.transpose(gather(x, idx, g), (0, 3, 1, 2)))
+
+
+def scatter_chw(tiles_chw, idx, g, y, add=False):
+    """Scatter(-add) of channel-major tiles [B, C, size_h, size_w] (Sec. 3.4, "transpose+scatter")."""
+    return scatter(np.transpose(np.asarray(tiles_chw), (0, 2, 3, 1)), idx, g, y, add=add)
+
+
 def conv_valid(tiles, w, bias=None, stride=1, relu=False):
     """Unpadded cross-correlation on a tile stack; w is HWIO [kh,kw,Cin,Cout]."""
     tiles, pt = _d(tiles)

@@ -46,6 +46,8 @@ _SIGNATURES = {
     "sbnet_read_count": (_ci, [_vp, _ci, ctypes.POINTER(_ci), _vp]),
     "sbnet_sparse_gather": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp]),
     "sbnet_sparse_scatter": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _ci, _vp]),
+    "sbnet_sparse_gather_chw": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp]),
+    "sbnet_sparse_scatter_chw": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _ci, _vp]),
     "sbnet_pack_weights": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_conv_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp]),
     "sbnet_sparse_conv": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp,
@@ -165,6 +167,32 @@ def sparse_scatter(tiles, indices, count, g, y, add=False):
     assert tiles.shape == (cap, g.bsize_h, g.bsize_w, C), (tuple(tiles.shape), (cap, g.bsize_h, g.bsize_w, C))
     _check(lib().sbnet_sparse_scatter(_ptr(tiles), _dt(tiles), _ptr(indices), _ptr(count), cap, g, _ptr(y), N, H, W,
                                       C, int(bool(add)), _stream()))
+    return y
+
+
+def sparse_gather_chw(x, indices, count, g, tiles=None):
+    """Gather with the transpose fused in: x [N,H,W,C] -> channel-major tiles [cap,C,h,w]."""
+    _dev(x, "x"), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    N, H, W, C = x.shape
+    cap = indices.shape[0]
+    if tiles is None:
+        tiles = torch.empty((cap, C, g.bsize_h, g.bsize_w), dtype=x.dtype, device=x.device)
+    _dev(tiles, "tiles", x.dtype)
+    assert tiles.shape == (cap, C, g.bsize_h, g.bsize_w)
+    _check(lib().sbnet_sparse_gather_chw(_ptr(x), _dt(x), N, H, W, C, _ptr(indices), _ptr(count), cap, g, _ptr(tiles),
+                                         _stream()))
+    return tiles
+
+
+def sparse_scatter_chw(tiles, indices, count, g, y, add=False):
+    """Scatter (or scatter-add) of channel-major tiles [cap,C,h,w] into y [N,H,W,C] in place; returns y."""
+    _dev(tiles, "tiles"), _dev(y, "y", tiles.dtype)
+    _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    N, H, W, C = y.shape
+    cap = indices.shape[0]
+    assert tiles.shape == (cap, C, g.bsize_h, g.bsize_w)
+    _check(lib().sbnet_sparse_scatter_chw(_ptr(tiles), _dt(tiles), _ptr(indices), _ptr(count), cap, g, _ptr(y), N, H, W,
+                                          C, int(bool(add)), _stream()))
     return y
 
 

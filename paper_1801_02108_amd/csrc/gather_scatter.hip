@@ -9,7 +9,7 @@
 // Work decomposition: a tile is cut into S segments of consecutive vectors; workgroups stride
 // over (tile, segment) items and stop at the device-side active count, so the launch does not
 // depend on a host read-back of that count.
-#include "common.h"
+#include "tile_add.h"
 
 namespace sbnet {
 
@@ -28,29 +28,6 @@ struct CopyParams {
     FastDiv div_row;
     FastDiv div_segs;
 };
-
-template <int DT>
-__device__ __forceinline__ uint32_t add_word(uint32_t y, uint32_t t);
-template <>
-__device__ __forceinline__ uint32_t add_word<SBNET_F32>(uint32_t y, uint32_t t) {
-    return __float_as_uint(__uint_as_float(y) + __uint_as_float(t));
-}
-template <>
-__device__ __forceinline__ uint32_t add_word<SBNET_BF16>(uint32_t y, uint32_t t) {
-    const uint32_t lo = float_to_bf16_bits(bf16_bits_to_float(y & 0xffffu) + bf16_bits_to_float(t & 0xffffu));
-    const uint32_t hi = float_to_bf16_bits(bf16_bits_to_float(y >> 16) + bf16_bits_to_float(t >> 16));
-    return lo | (hi << 16);
-}
-__device__ __forceinline__ uint32_t f16_add_bits(uint32_t a, uint32_t b) {
-    union { _Float16 h; uint16_t u; } x, y, r;
-    x.u = (uint16_t)a; y.u = (uint16_t)b;
-    r.h = (_Float16)((float)x.h + (float)y.h);
-    return r.u;
-}
-template <>
-__device__ __forceinline__ uint32_t add_word<SBNET_F16>(uint32_t y, uint32_t t) {
-    return f16_add_bits(y & 0xffffu, t & 0xffffu) | (f16_add_bits(y >> 16, t >> 16) << 16);
-}
 
 template <int DT> __device__ __forceinline__ uint4 vadd(uint4 y, uint4 t) {
     return make_uint4(add_word<DT>(y.x, t.x), add_word<DT>(y.y, t.y), add_word<DT>(y.z, t.z), add_word<DT>(y.w, t.w));

@@ -215,6 +215,59 @@ def test_gather_scatter_round_trip_all_blocks():
     assert torch.equal(x, y)
 
 
+CHW_CASES = [
+    # H, W, C, k, s, bo, N, dtype: C * element size must fill 16-byte vectors
+    (48, 80, 64, 3, 1, 16, 2, "bf16"),     # one full slab of 64 channels
+    (33, 47, 256, 3, 1, 16, 1, "bf16"),    # four slabs, ragged blocks
+    (37, 29, 40, 3, 1, 4, 2, "f16"),       # a partial slab (5 vectors per pixel), tiny tiles
+    (64, 64, 16, 3, 1, 8, 1, "f32"),       # four-byte elements: slabs of 32 channels, partial
+    (40, 40, 72, 5, 1, 8, 1, "f32"),       # ... three slabs, halo 2
+    (35, 35, 8, 3, 2, 4, 2, "f16"),        # strided geometry, a single vector per pixel
+    (70, 70, 96, 3, 1, 32, 1, "bf16"),     # 34 x 34 tiles: the largest slab that fits in LDS
+]
+
+
+@pytest.mark.parametrize("H,W,C,k,s,bo,N,dtype", CHW_CASES)
+def test_transposing_gather_and_scatter_bit_exact(H, W, C, k, s, bo, N, dtype):
+    """Channel-major tile stack (Sec. 3.4, transpose fused into gather and scatter)."""
+    step("gather/scatter chw %s" % ((H, W, C, k, s, bo, N, dtype),))
+    r = gen.rng_for(2, H * 1000 + W + C + 7)
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, k, s, bo)
+    x = gen.activations(r, (N, H, W, C), dtype)
+    y0 = gen.activations(r, (N, Ho, Wo, C), dtype)
+    for dens in (0.0, 0.004, 1.0):
+        mask = (r.random((N, H, W)) < dens).astype(np.float32)
+        idx = orc.reduce_mask(mask, ogeom(g_in))
+        cap = len(idx) + 2
+        d_idx, d_cnt = dev_indices(idx, cap)
+        tiles = torch.full((cap, C, g_in.bsize_h, g_in.bsize_w), 9.0, dtype=TORCH_DT[dtype]).cuda()
+        sb.sparse_gather_chw(to_dev(x, dtype), d_idx, d_cnt, g_in, tiles)
+        got = to_host(tiles)
+        assert np.array_equal(got[:len(idx)], orc.gather_chw(x, idx, ogeom(g_in)))
+        assert (got[len(idx):] == 9.0).all()          # rows beyond the count are not written
+        t = gen.activations(r, (cap, C, bo, bo), dtype)
+        for add in (False, True):
+            y = to_dev(y0, dtype)
+            sb.sparse_scatter_chw(to_dev(t, dtype), d_idx, d_cnt, g_out, y, add=add)
+            want = round_like(orc.scatter_chw(t[:len(idx)], idx, ogeom(g_out), y0, add=add), dtype)
+            assert np.array_equal(to_host(y), want)
+
+
+def test_transposing_copies_refuse_what_they_do_not_take():
+    g_in, g_out, _, _ = sb.geometry(160, 160, 3, 1, 40)           # 42 x 42 tiles: a slab would not fit in LDS
+    x = torch.zeros((1, 160, 160, 64), dtype=torch.bfloat16).cuda()
+    idx, cnt = sb.reduce_mask(torch.ones((1, 160, 160), dtype=torch.uint8).cuda(), g_in)
+    with pytest.raises(sb.SbnetError) as e:
+        sb.sparse_gather_chw(x, idx, cnt, g_in)
+    assert e.value.code == sb.EUNSUPPORTED
+    g_in, _, _, _ = sb.geometry(16, 16, 3, 1, 8)
+    x = torch.zeros((1, 16, 16, 12), dtype=torch.bfloat16).cuda()  # 24 bytes per pixel
+    idx, cnt = sb.reduce_mask(torch.ones((1, 16, 16), dtype=torch.uint8).cuda(), g_in)
+    with pytest.raises(sb.SbnetError) as e:
+        sb.sparse_gather_chw(x, idx, cnt, g_in)
+    assert e.value.code == sb.EUNSUPPORTED
+
+
 # --------------------------------------------------------------------------- convolution on tiles
 CONV_CASES = [
     # B, th, tw, Cin, Cout, k, s, dtype, relu, bias

@@ -206,6 +206,34 @@ def test_gather_delta_input_lands_where_predicted():
     assert hits == want and len(want) == 4
 
 
+def test_transposing_gather_and_scatter_by_brute_force():
+    """Channel-major tiles (Sec. 3.4, fused transpose): every element written out from the definition, loop by loop,
+    and scatter as the inverse of gather on the blocks' own pixels."""
+    H, W, C, bo = 10, 7, 3, 4                                   # ragged: the last blocks hang over the edge
+    g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    x = rng0.standard_normal((2, H, W, C))
+    mask = np.zeros((2, H, W))
+    mask[0, 1, 1] = mask[1, 9, 6] = mask[1, 4, 3] = 1
+    idx = orc.reduce_mask(mask, g_in)
+    t = orc.gather_chw(x, idx, g_in)
+    assert t.shape == (len(idx), C, bo + 2, bo + 2)
+    for b, (n, by, bx) in enumerate(idx):
+        for c in range(C):
+            for i in range(bo + 2):
+                for j in range(bo + 2):
+                    yy, xx = by * bo - 1 + i, bx * bo - 1 + j
+                    want = x[n, yy, xx, c] if 0 <= yy < H and 0 <= xx < W else 0.0
+                    assert t[b, c, i, j] == want
+    # scatter the interiors back: active blocks' pixels reproduce x, the rest keeps y0; add doubles them
+    y0 = rng0.standard_normal((2, H, W, C))
+    inner = t[:, :, 1:-1, 1:-1]
+    y = orc.scatter_chw(inner, idx, g_out, y0)
+    bm = orc.block_mask(idx, g_out, 2, H, W)
+    assert np.array_equal(y[bm], x[bm]) and np.array_equal(y[~bm], y0[~bm])
+    ya = orc.scatter_chw(inner, idx, g_out, x, add=True)
+    assert np.array_equal(ya[bm], 2 * x[bm]) and np.array_equal(ya[~bm], x[~bm])
+
+
 def test_scatter_invariants():
     H, W, C, bo = 20, 12, 3, 4
     g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
