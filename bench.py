@@ -539,6 +539,10 @@ def main():
             chw_out = torch.empty((n, K, BO, BO), dtype=torch.bfloat16, device=dev)
             t_gather_chw = tk(lambda: sb.sparse_gather_chw(x, idx_small, cnt, g_in, chw_in))
             t_scatter_chw = tk(lambda: sb.sparse_scatter_chw(chw_out, idx_small, cnt, g_out, y))
+            # gradient of the gather: overlapping tile gradients summed onto dx (end of Sec. 3.3)
+            dxg = torch.zeros_like(x)
+            gb_ws = torch.empty((sb.lib().sbnet_gather_backward_workspace_bytes(1, g_in),), dtype=torch.uint8, device=dev)
+            t_gb = tk(lambda: sb.sparse_gather_backward(tiles_buf[0], idx_small, cnt, g_in, dxg, gb_ws))
             tile_in_b = (BO + 2) ** 2 * C * 2
             tile_out_b = BO * BO * K * 2
             row = {"target": target, "active_blocks": n, "step_ms": round(t_step, 5), "fused_conv_ms": round(t_conv, 5),
@@ -548,6 +552,8 @@ def main():
                    "scatter_ms": round(t_scatter, 5), "scatter_GBps": round(2 * tile_out_b * n / t_scatter / 1e6, 1),
                    "gather_chw_ms": round(t_gather_chw, 5), "gather_chw_GBps": round(2 * tile_in_b * n / t_gather_chw / 1e6, 1),
                    "scatter_chw_ms": round(t_scatter_chw, 5), "scatter_chw_GBps": round(2 * tile_out_b * n / t_scatter_chw / 1e6, 1),
+                   "gather_backward_ms": round(t_gb, 5),
+                   "gather_backward_GBps": round((tile_in_b + 2 * BO * BO * C * 2) * n / t_gb / 1e6, 1),
                    "unfused_sum_ms": round(t_gather + t_tconv + t_scatter, 5)}
             if target >= 1.0:
                 dense_ms = t_step

@@ -135,6 +135,27 @@ sbnet_status sbnet_sparse_scatter_chw(const void *tiles_chw, sbnet_dtype dtype,
                                       int add, void *stream);
 
 /*
+ * Gradient of the gather (end of Sec. 3.3, "End-to-end training of SBNet": the gradient of the
+ * overlapping gather is a scatter that adds the tile gradients, also where neighbouring tiles
+ * share their halo; the gradient of the scatter is sbnet_sparse_gather itself):
+ *   dx[n][y][x][c] += sum over active blocks b whose tile covers (y, x) of
+ *                     dtiles[b][y - y0_b][x - x0_b][c],      positions outside the image dropped.
+ * dtiles: [cap][g->bsize_h][g->bsize_w][C]; dx: [N][H][W][C], accumulated into (clear it first
+ * for a fresh gradient); same dtype (F32, BF16 or F16, C * element size a multiple of 4 bytes).
+ * The contributions of a pixel (at most (R+1)^2, R = ceil((bsize - bstride) / bstride) <= 3) are
+ * added in ascending (by, bx) order, then dx, in fp32, and rounded once: no atomics, the result
+ * does not depend on scheduling.  indices must hold distinct blocks of the g grid (as
+ * sbnet_reduce_mask writes them).  workspace: device, sbnet_gather_backward_workspace_bytes(N, g)
+ * bytes, 4-byte aligned, overwritten.
+ */
+size_t sbnet_gather_backward_workspace_bytes(int N, const sbnet_geom *g);
+sbnet_status sbnet_sparse_gather_backward(const void *dtiles, sbnet_dtype dtype,
+                                          const int32_t *indices, const int32_t *count, int cap,
+                                          const sbnet_geom *g, void *dx, int N, int H, int W,
+                                          int C, void *workspace, size_t workspace_bytes,
+                                          void *stream);
+
+/*
  * Re-pack convolution weights once for the kernels below.  w_hwio: device, [kh][kw][Cin][Cout]
  * in `dtype` (the filter bank as a (kh*kw*Cin) x Cout matrix, Sec. 2).  With w_packed == NULL
  * only *bytes (host) is set to the size the packed copy needs.  The packed layout is private

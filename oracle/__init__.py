@@ -120,6 +120,12 @@ def scatter(tiles, idx, g, y, add=False):
     return y
 
 
+def gather_backward(dtiles, idx, g, dx):
+    """Gradient of gather (end of Sec. 3.3): every tile gradient is added onto its window of a copy of dx, also
+    where windows of neighbouring tiles overlap; positions outside the image are dropped."""
+    return scatter(dtiles, idx, g, dx, add=True)
+
+
 def gather_chw(x, idx, g):
     """Gather with the transpose of Sec. 3.4 ("Fused transpose+gather"): channel-major tiles [B, C, size_h, size_w]."""
     return np.ascontiguousarray(np.transpose(gather(x, idx, g), (0, 3, 1, 2)))

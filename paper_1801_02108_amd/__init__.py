@@ -48,6 +48,8 @@ _SIGNATURES = {
     "sbnet_sparse_scatter": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _ci, _vp]),
     "sbnet_sparse_gather_chw": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp]),
     "sbnet_sparse_scatter_chw": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _ci, _vp]),
+    "sbnet_gather_backward_workspace_bytes": (_sz, [_ci, _gp]),
+    "sbnet_sparse_gather_backward": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _vp, _sz, _vp]),
     "sbnet_pack_weights": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_conv_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp]),
     "sbnet_sparse_conv": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp,
@@ -194,6 +196,22 @@ def sparse_scatter_chw(tiles, indices, count, g, y, add=False):
     _check(lib().sbnet_sparse_scatter_chw(_ptr(tiles), _dt(tiles), _ptr(indices), _ptr(count), cap, g, _ptr(y), N, H, W,
                                           C, int(bool(add)), _stream()))
     return y
+
+
+def sparse_gather_backward(dtiles, indices, count, g, dx, workspace=None):
+    """Gradient of sparse_gather: adds the tile gradients [cap,h,w,C] (overlapping halos included) into dx [N,H,W,C]."""
+    _dev(dtiles, "dtiles"), _dev(dx, "dx", dtiles.dtype)
+    _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    N, H, W, C = dx.shape
+    cap = indices.shape[0]
+    assert dtiles.shape == (cap, g.bsize_h, g.bsize_w, C)
+    need = lib().sbnet_gather_backward_workspace_bytes(N, g)
+    if workspace is None:
+        workspace = torch.empty((max(need, 4),), dtype=torch.uint8, device=dx.device)
+    _dev(workspace, "workspace", torch.uint8)
+    _check(lib().sbnet_sparse_gather_backward(_ptr(dtiles), _dt(dtiles), _ptr(indices), _ptr(count), cap, g, _ptr(dx),
+                                              N, H, W, C, _ptr(workspace), workspace.numel(), _stream()))
+    return dx
 
 
 class PackedWeights:

@@ -268,6 +268,51 @@ def test_transposing_copies_refuse_what_they_do_not_take():
     assert e.value.code == sb.EUNSUPPORTED
 
 
+GB_CASES = [
+    # H, W, C, k, s, bo, N, dtype
+    (48, 80, 64, 3, 1, 16, 2, "bf16"),     # one-pixel halo: up to four tiles per pixel
+    (37, 29, 6, 3, 1, 4, 2, "f16"),        # 4-byte vectors... 12 bytes per pixel, ragged blocks
+    (64, 64, 16, 3, 1, 8, 1, "f32"),
+    (40, 40, 12, 5, 1, 3, 1, "f32"),       # halo 2 on 3-pixel blocks: tiles reach over two following cells
+    (30, 26, 8, 7, 1, 2, 1, "bf16"),       # halo 3 on 2-pixel blocks: three following cells, 16 tiles per pixel
+    (35, 35, 8, 3, 2, 4, 2, "f16"),        # strided geometry: tile 9, stride 8
+    (24, 24, 32, 1, 1, 3, 1, "bf16"),      # 1x1: no overlap at all
+]
+
+
+@pytest.mark.parametrize("H,W,C,k,s,bo,N,dtype", GB_CASES)
+def test_gather_backward(H, W, C, k, s, bo, N, dtype):
+    """Gradient of the gather (end of Sec. 3.3): overlapping tile gradients summed per pixel, deterministic order."""
+    step("gather_backward %s" % ((H, W, C, k, s, bo, N, dtype),))
+    r = gen.rng_for(8, H * 1000 + W + C)
+    g_in, _, _, _ = sb.geometry(H, W, k, s, bo)
+    dx0 = gen.activations(r, (N, H, W, C), dtype)
+    for dens in (0.0, 0.01, 1.0):
+        mask = (r.random((N, H, W)) < dens).astype(np.float32)
+        idx = orc.reduce_mask(mask, ogeom(g_in))
+        cap = len(idx) + 2
+        d_idx, d_cnt = dev_indices(idx, cap)
+        t = gen.activations(r, (cap, g_in.bsize_h, g_in.bsize_w, C), dtype)
+        dx = to_dev(dx0, dtype)
+        sb.sparse_gather_backward(to_dev(t, dtype), d_idx, d_cnt, g_in, dx)
+        got = to_host(dx)
+        ref = orc.gather_backward(t[:len(idx)], idx, ogeom(g_in), dx0)
+        if dtype == "f32":
+            assert np.allclose(got, ref, rtol=2e-6, atol=2e-6)
+        else:
+            want = round_like(ref, dtype)
+            # the fp32 sum of up to 17 terms is not always exact: allow the neighbouring representable value, rarely
+            ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - (7 if dtype == "bf16" else 10))
+            assert (np.abs(got - want) <= ulp).all()
+            assert (got != want).mean() < 2e-3
+        untouched = ref == dx0
+        assert np.array_equal(got[untouched], dx0[untouched])
+        # two runs give the same bits: no atomics
+        dx2 = to_dev(dx0, dtype)
+        sb.sparse_gather_backward(to_dev(t, dtype), d_idx, d_cnt, g_in, dx2)
+        assert torch.equal(dx, dx2)
+
+
 # --------------------------------------------------------------------------- convolution on tiles
 CONV_CASES = [
     # B, th, tw, Cin, Cout, k, s, dtype, relu, bias

@@ -234,6 +234,32 @@ def test_transposing_gather_and_scatter_by_brute_force():
     assert np.array_equal(ya[bm], 2 * x[bm]) and np.array_equal(ya[~bm], x[~bm])
 
 
+@pytest.mark.parametrize("H,W,C,k,s,bo", [(12, 9, 2, 3, 1, 4), (17, 17, 1, 3, 2, 2), (9, 9, 3, 5, 1, 3), (10, 14, 2, 7, 1, 2)])
+def test_gather_backward_is_the_adjoint_of_gather(H, W, C, k, s, bo):
+    """<gather(x), t> == <x, gather_backward(t)> for any x, t: the defining property of a gradient of a linear
+    map; and with all-ones tile gradients dx counts the tiles covering each pixel (1 inside a block's own cells,
+    2 on shared edges, 4 on shared corners for a one-pixel halo)."""
+    g_in, _, _, _ = orc.geometry(H, W, k, s, bo)
+    mask = rng0.random((2, H, W)) < 0.08
+    mask[0, 0, 0] = mask[1, H - 1, W - 1] = True
+    idx = orc.reduce_mask(mask.astype(np.float64), g_in)
+    x = rng0.standard_normal((2, H, W, C))
+    t = rng0.standard_normal((len(idx), g_in.size_h, g_in.size_w, C))
+    lhs = float((orc.gather(x, idx, g_in) * t).sum())
+    rhs = float((x * orc.gather_backward(t, idx, g_in, np.zeros_like(x))).sum())
+    assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(lhs))
+    # accumulation: dx is added to, not overwritten
+    d0 = rng0.standard_normal(x.shape)
+    assert np.allclose(orc.gather_backward(t, idx, g_in, d0), d0 + orc.gather_backward(t, idx, g_in, np.zeros_like(x)), atol=1e-12)
+    # coverage counts by brute force
+    cover = np.zeros((2, H, W))
+    for n, by, bx in idx:
+        y0, x0 = g_in.off_h + by * g_in.stride_h, g_in.off_w + bx * g_in.stride_w
+        cover[n, max(y0, 0):max(min(y0 + g_in.size_h, H), 0), max(x0, 0):max(min(x0 + g_in.size_w, W), 0)] += 1
+    ones = orc.gather_backward(np.ones_like(t), idx, g_in, np.zeros_like(x))
+    assert np.array_equal(ones, np.repeat(cover[..., None], C, axis=3))
+
+
 def test_scatter_invariants():
     H, W, C, bo = 20, 12, 3, 4
     g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
