@@ -543,6 +543,9 @@ def main():
             dxg = torch.zeros_like(x)
             gb_ws = torch.empty((sb.lib().sbnet_gather_backward_workspace_bytes(1, g_in),), dtype=torch.uint8, device=dev)
             t_gb = tk(lambda: sb.sparse_gather_backward(tiles_buf[0], idx_small, cnt, g_in, dxg, gb_ws))
+            # batch-norm statistics over the active blocks of the output (Sec. 3.3)
+            bn_ws = torch.empty((sb.lib().sbnet_bn_stats_workspace_bytes(n, K),), dtype=torch.uint8, device=dev)
+            t_bn = tk(lambda: sb.sparse_bn_stats(y, idx_small, cnt, g_out, bn_ws))
             tile_in_b = (BO + 2) ** 2 * C * 2
             tile_out_b = BO * BO * K * 2
             row = {"target": target, "active_blocks": n, "step_ms": round(t_step, 5), "fused_conv_ms": round(t_conv, 5),
@@ -554,6 +557,7 @@ def main():
                    "scatter_chw_ms": round(t_scatter_chw, 5), "scatter_chw_GBps": round(2 * tile_out_b * n / t_scatter_chw / 1e6, 1),
                    "gather_backward_ms": round(t_gb, 5),
                    "gather_backward_GBps": round((tile_in_b + 2 * BO * BO * C * 2) * n / t_gb / 1e6, 1),
+                   "bn_stats_ms": round(t_bn, 5), "bn_stats_GBps": round(tile_out_b * n / t_bn / 1e6, 1),
                    "unfused_sum_ms": round(t_gather + t_tconv + t_scatter, 5)}
             if target >= 1.0:
                 dense_ms = t_step

@@ -156,6 +156,24 @@ sbnet_status sbnet_sparse_gather_backward(const void *dtiles, sbnet_dtype dtype,
                                           void *stream);
 
 /*
+ * Batch-norm statistics over the active blocks only (Sec. 3.3: normalising across the non-sparse
+ * elements keeps invalid data out of the statistics): for every channel c,
+ *   mean[c] = average, var[c] = biased variance of x[n][y][x][c]
+ * over the pixels of the blocks b < min(*count, cap) that lie inside the image (every pixel once:
+ * g must describe non-overlapping blocks, else SBNET_EINVAL).  With no such pixel both are 0.
+ * x: [N][H][W][C] in `dtype` (F32, BF16 or F16; C * element size a multiple of 16 bytes);
+ * mean, var: device float32 [C].  Sums are formed in fp32 in a fixed order (per block, relative to
+ * the block's first pixel; blocks merged in a fixed tree): no atomics, the result does not depend on
+ * scheduling.  workspace: device, sbnet_bn_stats_workspace_bytes(cap, C) bytes, 4-byte aligned,
+ * overwritten.
+ */
+size_t sbnet_bn_stats_workspace_bytes(int cap, int C);
+sbnet_status sbnet_sparse_bn_stats(const void *x, sbnet_dtype dtype, int N, int H, int W, int C,
+                                   const int32_t *indices, const int32_t *count, int cap,
+                                   const sbnet_geom *g, float *mean, float *var, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+/*
  * Re-pack convolution weights once for the kernels below.  w_hwio: device, [kh][kw][Cin][Cout]
  * in `dtype` (the filter bank as a (kh*kw*Cin) x Cout matrix, Sec. 2).  With w_packed == NULL
  * only *bytes (host) is set to the size the packed copy needs.  The packed layout is private

@@ -191,6 +191,18 @@ def block_mask(idx, g_out, N, H_out, W_out):
     return m
 
 
+def bn_stats(x, idx, g_out):
+    """Batch-norm statistics over the active blocks only (Sec. 3.3): per channel, mean and biased variance of x
+    [N,H,W,C] over the pixels that lie in a listed block; zeros when there is none."""
+    x = np.asarray(x, dtype=np.float64)
+    N, H, W, C = x.shape
+    vals = x[block_mask(idx, g_out, N, H, W)]                  # [pixels, C]
+    if vals.shape[0] == 0:
+        return np.zeros(C), np.zeros(C)
+    mean = vals.sum(axis=0) / vals.shape[0]
+    return mean, ((vals - mean) ** 2).sum(axis=0) / vals.shape[0]
+
+
 # ---------------------------------------------------------------------------------------
 # compositions
 # ---------------------------------------------------------------------------------------

@@ -50,6 +50,8 @@ _SIGNATURES = {
     "sbnet_sparse_scatter_chw": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _ci, _vp]),
     "sbnet_gather_backward_workspace_bytes": (_sz, [_ci, _gp]),
     "sbnet_sparse_gather_backward": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _vp, _sz, _vp]),
+    "sbnet_bn_stats_workspace_bytes": (_sz, [_ci, _ci]),
+    "sbnet_sparse_bn_stats": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp, _vp, _sz, _vp]),
     "sbnet_pack_weights": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_conv_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp]),
     "sbnet_sparse_conv": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp,
@@ -212,6 +214,22 @@ def sparse_gather_backward(dtiles, indices, count, g, dx, workspace=None):
     _check(lib().sbnet_sparse_gather_backward(_ptr(dtiles), _dt(dtiles), _ptr(indices), _ptr(count), cap, g, _ptr(dx),
                                               N, H, W, C, _ptr(workspace), workspace.numel(), _stream()))
     return dx
+
+
+def sparse_bn_stats(x, indices, count, g, workspace=None):
+    """Per-channel mean and biased variance of x [N,H,W,C] over the pixels of the active blocks; returns (mean, var)."""
+    _dev(x, "x"), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    N, H, W, C = x.shape
+    cap = indices.shape[0]
+    need = lib().sbnet_bn_stats_workspace_bytes(cap, C)
+    if workspace is None:
+        workspace = torch.empty((max(need, 4),), dtype=torch.uint8, device=x.device)
+    _dev(workspace, "workspace", torch.uint8)
+    mean = torch.empty((C,), dtype=torch.float32, device=x.device)
+    var = torch.empty((C,), dtype=torch.float32, device=x.device)
+    _check(lib().sbnet_sparse_bn_stats(_ptr(x), _dt(x), N, H, W, C, _ptr(indices), _ptr(count), cap, g, _ptr(mean),
+                                       _ptr(var), _ptr(workspace), workspace.numel(), _stream()))
+    return mean, var
 
 
 class PackedWeights:

@@ -313,6 +313,28 @@ def test_gather_backward(H, W, C, k, s, bo, N, dtype):
         assert torch.equal(dx, dx2)
 
 
+@pytest.mark.parametrize("H,W,C,bo,N,dtype", [(48, 80, 64, 16, 2, "bf16"), (37, 29, 40, 4, 2, "f16"), (64, 64, 16, 8, 1, "f32"),
+                                              (33, 47, 256, 16, 1, "bf16"), (70, 70, 96, 32, 1, "f32")])
+def test_sparse_bn_stats(H, W, C, bo, N, dtype):
+    """Batch-norm statistics over the active blocks only (Sec. 3.3); channels with a mean far from zero included."""
+    step("bn_stats %s" % ((H, W, C, bo, N, dtype),))
+    r = gen.rng_for(9, H * 1000 + W + C)
+    _, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    shift = np.where(np.arange(C) % 3 == 0, 20.0, 0.0)
+    x = gen.round_to((gen.activations(r, (N, H, W, C), "f32") + shift).astype(np.float32), dtype)
+    for dens in (0.0, 0.004, 1.0):
+        mask = (r.random((N, H, W)) < dens).astype(np.float32)
+        idx = orc.reduce_mask(mask, ogeom(g_out))
+        cap = len(idx) + 2
+        d_idx, d_cnt = dev_indices(idx, cap)
+        mean, var = sb.sparse_bn_stats(to_dev(x, dtype), d_idx, d_cnt, g_out)
+        rm, rv = orc.bn_stats(x, idx, ogeom(g_out))
+        assert np.allclose(mean.cpu().numpy(), rm, rtol=1e-5, atol=1e-5), np.abs(mean.cpu().numpy() - rm).max()
+        assert np.allclose(var.cpu().numpy(), rv, rtol=2e-4, atol=1e-6), np.abs(var.cpu().numpy() - rv).max()
+        mean2, var2 = sb.sparse_bn_stats(to_dev(x, dtype), d_idx, d_cnt, g_out)
+        assert torch.equal(mean, mean2) and torch.equal(var, var2)        # fixed summation order
+
+
 # --------------------------------------------------------------------------- convolution on tiles
 CONV_CASES = [
     # B, th, tw, Cin, Cout, k, s, dtype, relu, bias

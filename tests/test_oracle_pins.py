@@ -260,6 +260,37 @@ def test_gather_backward_is_the_adjoint_of_gather(H, W, C, k, s, bo):
     assert np.array_equal(ones, np.repeat(cover[..., None], C, axis=3))
 
 
+def test_bn_stats_over_active_blocks():
+    """Sparse batch-norm statistics (Sec. 3.3): all blocks active == the library's mean / variance over N, H, W;
+    affine maps of x move the statistics as they must; a pixel counts once and only if it is inside the image and
+    inside a listed block (brute force); the order of the list does not matter."""
+    H, W, C, bo = 10, 7, 3, 4                                   # blocks hang over the right and lower edges
+    _, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    x = rng0.standard_normal((2, H, W, C)) * np.array([1.0, 3.0, 0.1]) + np.array([0.0, 50.0, -2.0])
+    all_idx = orc.reduce_mask(np.ones((2, H, W)), g_out)
+    m, v = orc.bn_stats(x, all_idx, g_out)
+    assert np.allclose(m, x.mean(axis=(0, 1, 2)), rtol=1e-12) and np.allclose(v, x.var(axis=(0, 1, 2)), rtol=1e-12)
+    idx = all_idx[[1, 4, 5, 9]]
+    m, v = orc.bn_stats(x, idx, g_out)
+    rows = []
+    for n, by, bx in idx:
+        for i in range(bo):
+            for j in range(bo):
+                yy, xx = by * bo + i, bx * bo + j
+                if yy < H and xx < W:
+                    rows.append(x[n, yy, xx])
+    rows = np.array(rows)
+    assert np.allclose(m, rows.mean(axis=0), rtol=1e-12) and np.allclose(v, rows.var(axis=0), rtol=1e-12)
+    m2, v2 = orc.bn_stats(2.0 * x - 3.0, idx, g_out)
+    assert np.allclose(m2, 2.0 * m - 3.0, rtol=1e-12) and np.allclose(v2, 4.0 * v, rtol=1e-12)
+    m3, v3 = orc.bn_stats(x, idx[::-1], g_out)
+    assert np.allclose(m3, m, rtol=1e-13) and np.allclose(v3, v, rtol=1e-13)
+    mc, vc = orc.bn_stats(np.full_like(x, 7.0), idx, g_out)
+    assert np.array_equal(mc, np.full(C, 7.0)) and np.array_equal(vc, np.zeros(C))
+    m0, v0 = orc.bn_stats(x, np.zeros((0, 3), dtype=np.int32), g_out)
+    assert np.array_equal(m0, np.zeros(C)) and np.array_equal(v0, np.zeros(C))
+
+
 def test_scatter_invariants():
     H, W, C, bo = 20, 12, 3, 4
     g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
