@@ -161,10 +161,20 @@ def run_units(args):
             e1.record()
             torch.cuda.synchronize()
             k_ms = e0.elapsed_time(e1) / iters
+            # ... and in pre-activation form (ReLU(scale * x + shift) in front of conv1)
+            pre = (torch.ones(C, device=dev), torch.zeros(C, device=dev))
+            for _ in range(2):
+                sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1], pre=pre)
+            e0.record()
+            for _ in range(iters):
+                sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1], pre=pre)
+            e1.record()
+            torch.cuda.synchronize()
+            kp_ms = e0.elapsed_time(e1) / iters
             if target >= 1.0:
                 dense_ms = ms
             rows.append({"block": bo, "target": target, "active_blocks": n, "total_blocks": total,
-                         "step_ms": round(ms, 5), "unit_kernel_ms": round(k_ms, 5),
+                         "step_ms": round(ms, 5), "unit_kernel_ms": round(k_ms, 5), "preact_unit_kernel_ms": round(kp_ms, 5),
                          "unit_tflops": round(unit_flops(bo) * n / k_ms / 1e9, 2),
                          "unit_hbm_GBps_algorithmic": round(unit_bytes(bo) * n / k_ms / 1e6, 1),
                          "speedup_vs_own_dense": round(dense_ms / ms, 3), "ideal_speedup": round(total / max(n, 1), 2)})

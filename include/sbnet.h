@@ -261,6 +261,30 @@ sbnet_status sbnet_sparse_bottleneck(const void *x, sbnet_dtype dtype, int N, in
                                      const float *b2, const void *w3, const float *b3, void *y,
                                      void *stream);
 
+/*
+ * The same unit in pre-activation form: a per-channel affine map and ReLU (a batch norm folded to
+ * scale and shift, then ReLU) sit in front of the first convolution, the residual stays x:
+ *   y = x + W3 * ReLU(W2 (*) ReLU(W1 * ReLU(pre_scale . x + pre_shift) + b1) + b2) + b3
+ * on the active blocks (Sec. 3.3 names the unit's layers - three convolutions, batch
+ * normalisation, ReLU - without fixing their order; this is the order of pre-activation
+ * residual networks).  pre_scale, pre_shift: device float32 [C].  Everything else as for
+ * sbnet_bottleneck_on_tiles / sbnet_sparse_bottleneck, including the support matrix.
+ */
+sbnet_status sbnet_bottleneck_on_tiles_preact(const void *tiles_in, sbnet_dtype dtype, int H, int W,
+                                              int C, int Cm, const int32_t *indices,
+                                              const int32_t *count, int cap, const sbnet_geom *g_in,
+                                              const sbnet_geom *g_out, const float *pre_scale,
+                                              const float *pre_shift, const void *w1, const float *b1,
+                                              const void *w2, const float *b2, const void *w3,
+                                              const float *b3, void *tiles_out, void *stream);
+sbnet_status sbnet_sparse_bottleneck_preact(const void *x, sbnet_dtype dtype, int N, int H, int W,
+                                            int C, int Cm, const int32_t *indices,
+                                            const int32_t *count, int cap, const sbnet_geom *g_in,
+                                            const sbnet_geom *g_out, const float *pre_scale,
+                                            const float *pre_shift, const void *w1, const float *b1,
+                                            const void *w2, const float *b2, const void *w3,
+                                            const float *b3, void *y, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -222,28 +222,37 @@ def sparse_conv_dense(x, idx, g_out, w, bias, y, stride=1, relu=False, add=False
     return np.where(m, y + d if add else d, y)
 
 
-def bottleneck_on_tiles(tiles, idx, g_in, H, W, w1, b1, w2, b2, w3, b3):
+def _pre_activate(v, pre):
+    """ReLU(scale * v + shift) per channel (a batch norm and ReLU in front of the first convolution), or v."""
+    if pre is None:
+        return np.asarray(v, dtype=np.float64)
+    scale, shift = (np.asarray(a, dtype=np.float64) for a in pre)
+    return np.maximum(np.asarray(v, dtype=np.float64) * scale + shift, 0.0)
+
+
+def bottleneck_on_tiles(tiles, idx, g_in, H, W, w1, b1, w2, b2, w3, b3, pre=None):
     """Residual branch of a bottleneck unit on gathered tiles (Sec. 3.3, Fig. 4, BN folded
     into w, b): 1x1 + ReLU on the whole tile, zero outside the image, valid 3x3 + ReLU,
-    1x1.  Returns [B, bo, bo, Cout]."""
-    t1 = conv_valid(tiles, w1, b1, relu=True)
+    1x1.  Returns [B, bo, bo, Cout].  pre = (scale, shift): the pre-activation form, whose
+    first convolution reads ReLU(scale * x + shift) while the residual stays x."""
+    t1 = conv_valid(_pre_activate(tiles, pre), w1, b1, relu=True)
     t1 = zero_outside(t1, idx, g_in, H, W)
     t2 = conv_valid(t1, w2, b2, relu=True)
     return conv_valid(t2, w3, b3, relu=False)
 
 
-def sparse_bottleneck_tiled(x, idx, g_in, g_out, w1, b1, w2, b2, w3, b3):
+def sparse_bottleneck_tiled(x, idx, g_in, g_out, w1, b1, w2, b2, w3, b3, pre=None):
     """One sparse residual unit: one gather, three convolutions, one scatter-add onto x."""
     x = np.asarray(x, dtype=np.float64)
     tiles = gather(x, idx, g_in)
-    t3 = bottleneck_on_tiles(tiles, idx, g_in, x.shape[1], x.shape[2], w1, b1, w2, b2, w3, b3)
+    t3 = bottleneck_on_tiles(tiles, idx, g_in, x.shape[1], x.shape[2], w1, b1, w2, b2, w3, b3, pre=pre)
     return scatter(t3, idx, g_out, x, add=True)
 
 
-def sparse_bottleneck_dense(x, idx, g_out, w1, b1, w2, b2, w3, b3):
+def sparse_bottleneck_dense(x, idx, g_out, w1, b1, w2, b2, w3, b3, pre=None):
     """Dense residual unit, residual branch kept only on active blocks."""
     x = np.asarray(x, dtype=np.float64)
-    t1 = conv_dense(x, w1, b1, relu=True)
+    t1 = conv_dense(_pre_activate(x, pre), w1, b1, relu=True)
     t2 = conv_dense(t1, w2, b2, relu=True)
     t3 = conv_dense(t2, w3, b3, relu=False)
     m = block_mask(idx, g_out, *x.shape[:3])[..., None]

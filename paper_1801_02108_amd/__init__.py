@@ -61,6 +61,10 @@ _SIGNATURES = {
                                         _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "sbnet_sparse_bottleneck": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp,
                                       _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "sbnet_bottleneck_on_tiles_preact": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp,
+                                               _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "sbnet_sparse_bottleneck_preact": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp,
+                                             _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
 }
 
 
@@ -295,8 +299,16 @@ def _unit_args(weights):
     return (_ptr(w1.buf), _ptr(b1), _ptr(w2.buf), _ptr(b2), _ptr(w3.buf), _ptr(b3)), C, Cm
 
 
-def bottleneck_on_tiles(tiles, indices, count, g_in, g_out, H, W, weights, out=None):
-    """Residual branch (1x1+ReLU, 3x3+ReLU, 1x1) on gathered tiles [cap,h,w,C] -> t3 [cap,bo,bo,C]."""
+def _pre_args(pre, C):
+    scale, shift = pre
+    _dev(scale, "pre_scale", torch.float32), _dev(shift, "pre_shift", torch.float32)
+    assert scale.numel() == C and shift.numel() == C
+    return _ptr(scale), _ptr(shift)
+
+
+def bottleneck_on_tiles(tiles, indices, count, g_in, g_out, H, W, weights, out=None, pre=None):
+    """Residual branch (1x1+ReLU, 3x3+ReLU, 1x1) on gathered tiles [cap,h,w,C] -> t3 [cap,bo,bo,C];
+    pre = (scale, shift): pre-activation ReLU(scale * x + shift) in front of the first convolution."""
     _dev(tiles, "tiles"), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
     ptrs, C, Cm = _unit_args(weights)
     cap = indices.shape[0]
@@ -304,17 +316,27 @@ def bottleneck_on_tiles(tiles, indices, count, g_in, g_out, H, W, weights, out=N
     if out is None:
         out = torch.empty((cap, g_out.bsize_h, g_out.bsize_w, C), dtype=tiles.dtype, device=tiles.device)
     _dev(out, "out", tiles.dtype)
+    if pre is not None:
+        _check(lib().sbnet_bottleneck_on_tiles_preact(_ptr(tiles), _dt(tiles), H, W, C, Cm, _ptr(indices), _ptr(count),
+                                                      cap, g_in, g_out, *_pre_args(pre, C), *ptrs, _ptr(out), _stream()))
+        return out
     _check(lib().sbnet_bottleneck_on_tiles(_ptr(tiles), _dt(tiles), H, W, C, Cm, _ptr(indices), _ptr(count), cap,
                                            g_in, g_out, *ptrs, _ptr(out), _stream()))
     return out
 
 
-def sparse_bottleneck(x, indices, count, g_in, g_out, weights, y):
-    """Fused sparse residual unit: y[active] = x[active] + branch(x); y is a second buffer. Returns y."""
+def sparse_bottleneck(x, indices, count, g_in, g_out, weights, y, pre=None):
+    """Fused sparse residual unit: y[active] = x[active] + branch(x); y is a second buffer. Returns y.
+    pre = (scale, shift): pre-activation form."""
     _dev(x, "x"), _dev(y, "y", x.dtype), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
     ptrs, C, Cm = _unit_args(weights)
     N, H, W, Cx = x.shape
     assert Cx == C and y.shape == x.shape
+    if pre is not None:
+        _check(lib().sbnet_sparse_bottleneck_preact(_ptr(x), _dt(x), N, H, W, C, Cm, _ptr(indices), _ptr(count),
+                                                    indices.shape[0], g_in, g_out, *_pre_args(pre, C), *ptrs, _ptr(y),
+                                                    _stream()))
+        return y
     _check(lib().sbnet_sparse_bottleneck(_ptr(x), _dt(x), N, H, W, C, Cm, _ptr(indices), _ptr(count),
                                          indices.shape[0], g_in, g_out, *ptrs, _ptr(y), _stream()))
     return y

@@ -70,6 +70,7 @@ struct BneckParams {
     // complementary ranges and the count picks one.
     int per16;
     long long lo, hi;
+    const float *pre_scale, *pre_shift;   // pre-activation ReLU(scale * x + shift) in front of conv1, or both null
 };
 
 struct BItem {
@@ -94,7 +95,7 @@ __device__ __forceinline__ void bstore16(__amdgpu_buffer_rsrc_t r, uint32_t off,
 
 __device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v), 0); }
 
-template <int DT, int C, bool FUSED, int TS>
+template <int DT, int C, bool FUSED, int TS, bool PRE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void bottleneck16_kernel(BneckParams p) {
     static_assert(TS == 16 || TS == 8, "output sub-tile side");
@@ -124,6 +125,11 @@ void bottleneck16_kernel(BneckParams p) {
     __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];             // conv1 weights, 32x32x16 operand order
     __shared__ __align__(16) uint4 w3s[NB3 * 4 * 64];            // conv3 weights, [block of 32 outputs][k-step][lane]
     __shared__ __align__(16) float bias_s[2 * kCm + C];          // b1 | b2 | b3: accumulators start from these
+    float *pre_s = nullptr;                                      // pre-activation scale | shift
+    if constexpr (PRE) {
+        __shared__ __align__(16) float pre_store[2 * C];
+        pre_s = pre_store;
+    }
 
     const uint16_t *in = (const uint16_t *)p.in;
     uint16_t *out = (uint16_t *)p.out;
@@ -209,14 +215,38 @@ void bottleneck16_kernel(BneckParams p) {
         }
         __builtin_amdgcn_sched_barrier(0);                                // all loads issued here, in this order
     };
-    auto stash_chunk = [&](auto slot_tag) __attribute__((always_inline)) {
+    // With a pre-activation the chunk is transformed on its way to LDS: conv1 reads ReLU(scale * x + shift), the
+    // residual (requested separately) stays x.  A thread's vectors all hold the same eight channels of the chunk.
+    auto stash_chunk = [&](auto slot_tag, int chunk) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_tag)::value;
+        if constexpr (!PRE) {
 #pragma unroll
-        for (int k = 0; k < NVX; ++k) {
-            const int v = (int)threadIdx.x + k * 256;
-            // the tail beyond the last pixel goes to the 16 pad bytes of the last pixel: no branch
-            const int dst = v < kBTPx * 8 ? (v >> 3) * kPS + (v & 7) * 16 : (kBTPx - 1) * kPS + kCm * 2;
-            *(uint4 *)(xs + dst) = slot == 0 ? sx0[k] : sx1[k];
+            for (int k = 0; k < NVX; ++k) {
+                const int v = (int)threadIdx.x + k * 256;
+                // the tail beyond the last pixel goes to the 16 pad bytes of the last pixel: no branch
+                const int dst = v < kBTPx * 8 ? (v >> 3) * kPS + (v & 7) * 16 : (kBTPx - 1) * kPS + kCm * 2;
+                *(uint4 *)(xs + dst) = slot == 0 ? sx0[k] : sx1[k];
+            }
+        } else {
+            const int c0 = chunk * 64 + ((int)threadIdx.x & 7) * 8;
+            const float4 a0 = *(const float4 *)(pre_s + c0), a1 = *(const float4 *)(pre_s + c0 + 4);
+            const float4 h0 = *(const float4 *)(pre_s + C + c0), h1 = *(const float4 *)(pre_s + C + c0 + 4);
+            const float sc[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            const float sh[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+#pragma unroll
+            for (int k = 0; k < NVX; ++k) {
+                const int v = (int)threadIdx.x + k * 256;
+                const int dst = v < kBTPx * 8 ? (v >> 3) * kPS + (v & 7) * 16 : (kBTPx - 1) * kPS + kCm * 2;
+                const uint4 val = slot == 0 ? sx0[k] : sx1[k];
+                uint32_t w[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float lo = fmaf(sc[2 * i], unpack_lo<DT>(w[i]), sh[2 * i]);
+                    const float hi = fmaf(sc[2 * i + 1], unpack_hi<DT>(w[i]), sh[2 * i + 1]);
+                    w[i] = pack2<DT>(__int_as_float(relu_bits(lo)), __int_as_float(relu_bits(hi)));
+                }
+                *(uint4 *)(xs + dst) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
         }
     };
 
@@ -246,6 +276,8 @@ void bottleneck16_kernel(BneckParams p) {
         for (int k = 0; k < N3; ++k) w3s[threadIdx.x + k * 256] = t3v[k];
         for (int i = threadIdx.x; i < 2 * kCm + C; i += 256)
             bias_s[i] = i < kCm ? p.b1[i] : i < 2 * kCm ? p.b2[i - kCm] : p.b3[i - 2 * kCm];
+        if constexpr (PRE)
+            for (int i = threadIdx.x; i < 2 * C; i += 256) pre_s[i] = i < C ? p.pre_scale[i] : p.pre_shift[i - C];
     }
     // 16 consecutive biases from LDS as an accumulator-shaped vector
     auto load_bias16 = [&](int i0) __attribute__((always_inline)) {
@@ -335,8 +367,8 @@ void bottleneck16_kernel(BneckParams p) {
             for (int j = 0; j < NBPW1; ++j) boff[j] = min((wave + 4 * j) * 32 + m, kBTPx - 1) * kPS + g * 16;
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
-                if (c & 1) stash_chunk(Slot1{});
-                else stash_chunk(Slot0{});
+                if (c & 1) stash_chunk(Slot1{}, c);
+                else stash_chunk(Slot0{}, c);
                 __syncthreads();                                         // chunk c visible
                 if (c + 2 < NCH) {
                     if (c & 1) fetch_chunk(geo, c + 2, Slot1{});
@@ -524,15 +556,20 @@ static size_t w32_off(int taps, int Cin, int Cout) {     // 16-byte units, same 
     return taps * CinP * CoutP / 8;
 }
 
-template <int DT, bool FUSED, int TS>
-static sbnet_status launch_bneck(int C, const BneckParams &p, dim3 grid, hipStream_t s, const char *who) {
+template <int DT, bool FUSED, int TS, bool PRE>
+static sbnet_status launch_bneck_pre(int C, const BneckParams &p, dim3 grid, hipStream_t s, const char *who) {
     switch (C) {
-        case 64: hipLaunchKernelGGL((bottleneck16_kernel<DT, 64, FUSED, TS>), grid, dim3(256), 0, s, p); break;
-        case 128: hipLaunchKernelGGL((bottleneck16_kernel<DT, 128, FUSED, TS>), grid, dim3(256), 0, s, p); break;
-        case 256: hipLaunchKernelGGL((bottleneck16_kernel<DT, 256, FUSED, TS>), grid, dim3(256), 0, s, p); break;
+        case 64: hipLaunchKernelGGL((bottleneck16_kernel<DT, 64, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
+        case 128: hipLaunchKernelGGL((bottleneck16_kernel<DT, 128, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
+        case 256: hipLaunchKernelGGL((bottleneck16_kernel<DT, 256, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
         default: return fail(SBNET_EUNSUPPORTED, "%s: C must be 64, 128 or 256", who);
     }
     return launch_status(who);
+}
+template <int DT, bool FUSED, int TS>
+static sbnet_status launch_bneck(int C, const BneckParams &p, dim3 grid, hipStream_t s, const char *who) {
+    return p.pre_scale ? launch_bneck_pre<DT, FUSED, TS, true>(C, p, grid, s, who)
+                       : launch_bneck_pre<DT, FUSED, TS, false>(C, p, grid, s, who);
 }
 template <int DT, bool FUSED>
 static sbnet_status launch_bneck_ts(int ts, int C, const BneckParams &p, dim3 grid, hipStream_t s, const char *who) {
@@ -542,9 +579,12 @@ static sbnet_status launch_bneck_ts(int ts, int C, const BneckParams &p, dim3 gr
 static sbnet_status bneck_entry(const char *who, bool fused, const void *in, void *out, sbnet_dtype dt, int N, int H,
                                 int W, int C, int Cm, const int32_t *indices, const int32_t *count, int cap,
                                 const sbnet_geom *g_in, const sbnet_geom *g_out, const void *w1, const float *b1,
-                                const void *w2, const float *b2, const void *w3, const float *b3, void *stream) {
+                                const void *w2, const float *b2, const void *w3, const float *b3, void *stream,
+                                const float *pre_scale = nullptr, const float *pre_shift = nullptr) {
     if (!in || !out || !indices || !count || !w1 || !w2 || !w3 || !b1 || !b2 || !b3)
         return fail(SBNET_EINVAL, "%s: null pointer (biases are required)", who);
+    if ((pre_scale == nullptr) != (pre_shift == nullptr))
+        return fail(SBNET_EINVAL, "%s: pre-activation needs both scale and shift", who);
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || Cm <= 0 || cap < 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
     if (!geom_ok(g_in) || !geom_ok(g_out)) return fail(SBNET_EINVAL, "%s: bad geometry", who);
     if (g_in->bsize_h - 2 != g_out->bsize_h || g_in->bsize_w - 2 != g_out->bsize_w)
@@ -570,6 +610,7 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
     p.w1 = w1; p.w2 = w2; p.w3 = w3;
     p.w1_off = w32_off(1, C, Cm); p.w2_off = w32_off(9, Cm, Cm); p.w3_off = w32_off(1, Cm, C);
     p.b1 = b1; p.b2 = b2; p.b3 = b3;
+    p.pre_scale = pre_scale; p.pre_shift = pre_shift;
     p.indices = indices; p.count = count; p.cap = cap;
     p.th = g_in->bsize_h; p.tw = g_in->bsize_w; p.oh = g_out->bsize_h; p.ow = g_out->bsize_w;
     p.H = H; p.W = W;
@@ -622,4 +663,26 @@ extern "C" sbnet_status sbnet_sparse_bottleneck(const void *x, sbnet_dtype dtype
                                                 const float *b3, void *y, void *stream) {
     return bneck_entry("sbnet_sparse_bottleneck", true, x, y, dtype, N, H, W, C, Cm, indices, count, cap, g_in, g_out,
                        w1, b1, w2, b2, w3, b3, stream);
+}
+
+extern "C" sbnet_status sbnet_bottleneck_on_tiles_preact(const void *tiles_in, sbnet_dtype dtype, int H, int W, int C,
+                                                         int Cm, const int32_t *indices, const int32_t *count, int cap,
+                                                         const sbnet_geom *g_in, const sbnet_geom *g_out,
+                                                         const float *pre_scale, const float *pre_shift, const void *w1,
+                                                         const float *b1, const void *w2, const float *b2,
+                                                         const void *w3, const float *b3, void *tiles_out, void *stream) {
+    if (!pre_scale || !pre_shift) return fail(SBNET_EINVAL, "sbnet_bottleneck_on_tiles_preact: null pointer");
+    return bneck_entry("sbnet_bottleneck_on_tiles_preact", false, tiles_in, tiles_out, dtype, 1, H, W, C, Cm, indices,
+                       count, cap, g_in, g_out, w1, b1, w2, b2, w3, b3, stream, pre_scale, pre_shift);
+}
+
+extern "C" sbnet_status sbnet_sparse_bottleneck_preact(const void *x, sbnet_dtype dtype, int N, int H, int W, int C, int Cm,
+                                                       const int32_t *indices, const int32_t *count, int cap,
+                                                       const sbnet_geom *g_in, const sbnet_geom *g_out,
+                                                       const float *pre_scale, const float *pre_shift, const void *w1,
+                                                       const float *b1, const void *w2, const float *b2, const void *w3,
+                                                       const float *b3, void *y, void *stream) {
+    if (!pre_scale || !pre_shift) return fail(SBNET_EINVAL, "sbnet_sparse_bottleneck_preact: null pointer");
+    return bneck_entry("sbnet_sparse_bottleneck_preact", true, x, y, dtype, N, H, W, C, Cm, indices, count, cap, g_in,
+                       g_out, w1, b1, w2, b2, w3, b3, stream, pre_scale, pre_shift);
 }

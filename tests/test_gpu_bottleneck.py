@@ -90,6 +90,45 @@ def test_bottleneck_on_tiles_and_fused(N, H, W, C, bo, dtype):
             assert_close(got, orc.sparse_bottleneck_dense(x, idx, ogeom(g_out), *ws), CONV_TOL[dtype], "dense unit")
 
 
+@pytest.mark.parametrize("N,H,W,C,bo,dtype", [(2, 48, 48, 256, 16, "bf16"), (1, 40, 56, 128, 16, "f16"), (2, 40, 24, 256, 8, "bf16"),
+                                              (1, 37, 29, 64, 8, "f16")])
+def test_preactivation_unit(N, H, W, C, bo, dtype):
+    """Pre-activation form of the unit: ReLU(scale * x + shift) feeds conv1, the residual stays x."""
+    step("pre-activation bottleneck %s" % ((N, H, W, C, bo, dtype),))
+    r = gen.rng_for(3, H * 100 + C + bo + 5)
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    x = gen.activations(r, (N, H, W, C), dtype)
+    ws = gen.bottleneck_weights(r, C, 64, dtype)
+    scale = (1.0 + 0.3 * r.standard_normal(C)).astype(np.float32)
+    shift = (0.5 * r.standard_normal(C)).astype(np.float32)
+    pre = (scale.astype(np.float64), shift.astype(np.float64))
+    dpre = (torch.from_numpy(scale).cuda(), torch.from_numpy(shift).cuda())
+    dws = dev_weights(ws, dtype)
+    dx = to_dev(x, dtype)
+    for dens in (1.0, 0.3):
+        mask = block_aligned_mask(r, N, H, W, bo, dens)
+        d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_out)
+        idx = orc.reduce_mask(mask, ogeom(g_out))
+        ref = orc.sparse_bottleneck_tiled(x, idx, ogeom(g_in), ogeom(g_out), *ws, pre=pre)
+        tiles = sb.sparse_gather(dx, d_idx, d_cnt, g_in)
+        t3 = sb.bottleneck_on_tiles(tiles, d_idx, d_cnt, g_in, g_out, H, W, dws, pre=dpre)
+        y = dx.clone()
+        sb.sparse_scatter(t3, d_idx, d_cnt, g_out, y, add=True)
+        unfused = to_host(y)
+        assert_close(unfused, ref, CONV_TOL[dtype], "unfused pre-activation unit")
+        y0 = gen.activations(r, (N, H, W, C), dtype)
+        y = to_dev(y0, dtype)
+        sb.sparse_bottleneck(dx, d_idx, d_cnt, g_in, g_out, dws, y, pre=dpre)
+        got = to_host(y)
+        bm = orc.block_mask(idx, ogeom(g_out), N, H, W)
+        assert np.array_equal(got[~bm], y0[~bm])
+        assert_close(got[bm], ref[bm], CONV_TOL[dtype], "fused pre-activation unit")
+        assert np.array_equal(got[bm], unfused[bm])
+        # it is not the plain unit
+        plain = orc.sparse_bottleneck_tiled(x, idx, ogeom(g_in), ogeom(g_out), *ws)
+        assert np.abs(plain - ref).max() > 0.05
+
+
 def test_bottleneck_border_rule_matters_on_gpu_inputs():
     """With a large positive b1 the value ReLU(b1) would leak into the 3x3 at the image border if t1
     were not zeroed there; the GPU result must follow the dense unit (which pads t1 with zeros)."""

@@ -444,6 +444,34 @@ def test_bottleneck_all_ones_equals_dense_unit(H, W, bo):
                                rtol=1e-11, atol=1e-11)
 
 
+@pytest.mark.parametrize("H,W,bo", [(8, 8, 4), (10, 7, 3)])
+def test_preactivation_unit(H, W, bo):
+    """Pre-activation form: with every block active it equals the library's dense pre-activation unit (batch norm
+    folded to scale and shift, ReLU, then the three convolutions, residual = x itself); with scale 1, shift 0 and a
+    non-negative x it is the plain unit; on a partial mask the tiled and the dense statement agree, and the
+    border rule is unchanged although ReLU(shift) is not zero outside the image."""
+    r = np.random.default_rng(H * 10 + bo)
+    C, Cm = 4, 3
+    ws = _bneck_weights(r, C, Cm)
+    pre = (r.standard_normal(C), r.standard_normal(C) + 0.5)
+    x = r.standard_normal((2, H, W, C))
+    g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    idx = orc.reduce_mask(np.ones((2, H, W)), g_in)
+    xa = np.maximum(x * pre[0] + pre[1], 0.0)
+    want = x + (_torch_bottleneck(xa, *ws) - xa)                # the library unit's branch on the activated input
+    np.testing.assert_allclose(orc.sparse_bottleneck_tiled(x, idx, g_in, g_out, *ws, pre=pre), want, rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(orc.sparse_bottleneck_dense(x, idx, g_out, *ws, pre=pre), want, rtol=1e-11, atol=1e-11)
+    xp = np.abs(x)
+    np.testing.assert_allclose(orc.sparse_bottleneck_tiled(xp, idx, g_in, g_out, *ws, pre=(np.ones(C), np.zeros(C))),
+                               orc.sparse_bottleneck_tiled(xp, idx, g_in, g_out, *ws), rtol=1e-12, atol=1e-12)
+    part = idx[::3]
+    np.testing.assert_allclose(orc.sparse_bottleneck_tiled(x, part, g_in, g_out, *ws, pre=pre),
+                               orc.sparse_bottleneck_dense(x, part, g_out, *ws, pre=pre), rtol=1e-11, atol=1e-11)
+    # and it differs from the plain unit (the test would pass vacuously if pre were ignored)
+    assert np.abs(orc.sparse_bottleneck_tiled(x, idx, g_in, g_out, *ws, pre=pre) -
+                  orc.sparse_bottleneck_tiled(x, idx, g_in, g_out, *ws)).max() > 1e-3
+
+
 def test_bottleneck_partial_mask_and_special_cases():
     r = np.random.default_rng(5)
     H, W, C, Cm, bo = 12, 16, 4, 3, 4
