@@ -209,6 +209,36 @@ sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int N, int H, i
                                int add, void *stream);
 
 /*
+ * Data gradient of sbnet_conv_on_tiles (training support for the tile convolution of Sec. 3.2;
+ * the paper's own evaluation is inference only).  For y = valid convolution of x with W at stride
+ * (sh, sw), no bias and no activation, and a given dL/dy this writes
+ *   din[b][y][x][c] = sum over (r, t, o) with (y - r) % sh == 0, (x - t) % sw == 0 and the quotients
+ *                     inside the output tile of  W[r][t][c][o] * dout[b][(y - r)/sh][(x - t)/sw][o],
+ * rounded once to `dtype` (fp32 accumulation; BF16/F16 contractions on the matrix cores).  A ReLU
+ * in the forward call is the caller's to undo (mask dout by y > 0 first); the bias gradient is a
+ * plain sum of dout.
+ * dout_tiles: [cap][oh][ow][Cout] with oh = (th - kh)/sh + 1, ow likewise; din_tiles:
+ * [cap][th][tw][Cin], every element of the tiles b < min(*count, cap) written (input rows a strided
+ * window never reaches get 0).  w_packed_t: from sbnet_pack_weights_transposed, called with the
+ * forward convolution's w_hwio, kh, kw, Cin, Cout.  workspace: device, 16-byte aligned,
+ * sbnet_conv_backward_data_workspace_bytes(...) bytes (the output gradient spread by the stride and
+ * framed by kh-1 / kw-1 zeros: [cap][th+kh-1][tw+kw-1][Cout]); overwritten.  All pointers device
+ * and 16-byte aligned.  Feeding din_tiles to sbnet_sparse_gather_backward gives dL/dx of the whole
+ * sparse convolution; dout_tiles come from sbnet_sparse_gather of dL/dy with the output geometry.
+ */
+sbnet_status sbnet_pack_weights_transposed(const void *w_hwio, sbnet_dtype dtype, int kh, int kw,
+                                           int Cin, int Cout, void *w_packed, size_t *bytes,
+                                           void *stream);
+size_t sbnet_conv_backward_data_workspace_bytes(sbnet_dtype dtype, int cap, int th, int tw, int kh,
+                                                int kw, int Cout);
+sbnet_status sbnet_conv_on_tiles_backward_data(const void *dout_tiles, sbnet_dtype dtype,
+                                               const int32_t *count, int cap, int th, int tw,
+                                               int Cin, const void *w_packed_t, int kh, int kw,
+                                               int sh, int sw, int Cout, void *din_tiles,
+                                               void *workspace, size_t workspace_bytes,
+                                               void *stream);
+
+/*
  * Set every tile position that lies outside the H x W image to zero, in place.  Needed when a
  * residual unit is composed from single sbnet_conv_on_tiles calls: after the first convolution
  * the halo positions beyond the image border hold act(bias), but the next convolution's zero

@@ -154,6 +154,41 @@ def conv_valid(tiles, w, bias=None, stride=1, relu=False):
     return out
 
 
+def conv_valid_backward_data(dout, w, th, tw, stride=1):
+    """Gradient of conv_valid (no bias, no activation) with respect to its input tiles [B, th, tw, Cin]: the
+    forward sum out[b,i,j,o] = sum_{r,t,c} x[b, r + s i, t + s j, c] w[r,t,c,o] (Sec. 2, Sec. 3.2) hands
+    dout[b,i,j,o] w[r,t,c,o] back to each input element it read.  Training support, not part of the paper's
+    evaluated path."""
+    dout = np.asarray(dout, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    B, ho, wo, Cout = dout.shape
+    kh, kw, Cin, Cout2 = w.shape
+    assert Cout == Cout2
+    assert ho == conv_out_size(th, kh, stride) and wo == conv_out_size(tw, kw, stride)
+    din = np.zeros((B, th, tw, Cin), dtype=np.float64)
+    for r in range(kh):
+        for t in range(kw):
+            din[:, r:r + stride * (ho - 1) + 1:stride, t:t + stride * (wo - 1) + 1:stride, :] += dout @ w[r, t].T
+    return din
+
+
+def conv_valid_backward_weights(tiles, dout, kh, kw, stride=1):
+    """Gradient of conv_valid with respect to its weights, summed over the whole tile stack:
+    dw[r,t,c,o] = sum_{b,i,j} tiles[b, r + s i, t + s j, c] dout[b,i,j,o]."""
+    tiles = np.asarray(tiles, dtype=np.float64)
+    dout = np.asarray(dout, dtype=np.float64)
+    B, th, tw, Cin = tiles.shape
+    _, ho, wo, Cout = dout.shape
+    assert ho == conv_out_size(th, kh, stride) and wo == conv_out_size(tw, kw, stride)
+    dw = np.zeros((kh, kw, Cin, Cout), dtype=np.float64)
+    g2 = dout.reshape(-1, Cout)
+    for r in range(kh):
+        for t in range(kw):
+            xs = tiles[:, r:r + stride * (ho - 1) + 1:stride, t:t + stride * (wo - 1) + 1:stride, :]
+            dw[r, t] = xs.reshape(-1, Cin).T @ g2
+    return dw
+
+
 def conv_dense(x, w, bias=None, stride=1, relu=False):
     """Zero-padded (SAME, pad = (k-1)/2) cross-correlation of the whole feature map."""
     x, px = _d(x)

@@ -53,6 +53,10 @@ _SIGNATURES = {
     "sbnet_bn_stats_workspace_bytes": (_sz, [_ci, _ci]),
     "sbnet_sparse_bn_stats": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp, _vp, _sz, _vp]),
     "sbnet_pack_weights": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
+    "sbnet_pack_weights_transposed": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
+    "sbnet_conv_backward_data_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci, _ci]),
+    "sbnet_conv_on_tiles_backward_data": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _ci, _ci, _vp,
+                                                _vp, _sz, _vp]),
     "sbnet_conv_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp]),
     "sbnet_sparse_conv": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp,
                                 _ci, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _vp]),
@@ -268,6 +272,44 @@ def conv_on_tiles(tiles, count, w_packed, bias=None, stride=1, relu=False, out=N
         _dev(bias, "bias", torch.float32)
     _check(lib().sbnet_conv_on_tiles(_ptr(tiles), _dt(tiles), _ptr(count), cap, th, tw, Cin, _ptr(w_packed.buf),
                                      _ptr(bias), kh, kw, stride, stride, Cout, int(bool(relu)), _ptr(out), _stream()))
+    return out
+
+
+def pack_weights_transposed(w_hwio):
+    """Forward weights [kh,kw,Cin,Cout] -> packed buffer for conv_on_tiles_backward_data (taps mirrored, channel
+    roles exchanged); .shape keeps the forward convolution's (kh, kw, Cin, Cout)."""
+    _dev(w_hwio, "w_hwio")
+    kh, kw, Cin, Cout = w_hwio.shape
+    nbytes = _sz()
+    _check(lib().sbnet_pack_weights_transposed(None, _dt(w_hwio), kh, kw, Cin, Cout, None, nbytes, None))
+    buf = torch.empty((nbytes.value,), dtype=torch.uint8, device=w_hwio.device)
+    _check(lib().sbnet_pack_weights_transposed(_ptr(w_hwio), _dt(w_hwio), kh, kw, Cin, Cout, _ptr(buf), nbytes,
+                                               _stream()))
+    return PackedWeights(buf, (kh, kw, Cin, Cout), w_hwio.dtype)
+
+
+def conv_backward_data_workspace_bytes(dtype, cap, th, tw, kh, kw, Cout):
+    return int(lib().sbnet_conv_backward_data_workspace_bytes(_DTYPES[dtype], cap, th, tw, kh, kw, Cout))
+
+
+def conv_on_tiles_backward_data(dout_tiles, count, w_packed_t, th, tw, stride=1, out=None, workspace=None):
+    """dL/d(tiles_in) [cap,th,tw,Cin] of conv_on_tiles (no bias, no activation) from dL/d(tiles_out)
+    [cap,oh,ow,Cout]; w_packed_t from pack_weights_transposed of the forward weights."""
+    _dev(dout_tiles, "dout_tiles"), _dev(count, "count", torch.int32)
+    kh, kw, Cin, Cout = w_packed_t.shape
+    cap, oh, ow, C = dout_tiles.shape
+    assert C == Cout and w_packed_t.dtype == dout_tiles.dtype
+    assert oh == (th - kh) // stride + 1 and ow == (tw - kw) // stride + 1
+    if out is None:
+        out = torch.empty((cap, th, tw, Cin), dtype=dout_tiles.dtype, device=dout_tiles.device)
+    _dev(out, "out", dout_tiles.dtype)
+    need = conv_backward_data_workspace_bytes(dout_tiles.dtype, cap, th, tw, kh, kw, Cout)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dout_tiles.device)
+    _dev(workspace, "workspace", torch.uint8)
+    _check(lib().sbnet_conv_on_tiles_backward_data(_ptr(dout_tiles), _dt(dout_tiles), _ptr(count), cap, th, tw, Cin,
+                                                   _ptr(w_packed_t.buf), kh, kw, stride, stride, Cout, _ptr(out),
+                                                   _ptr(workspace), workspace.numel(), _stream()))
     return out
 
 

@@ -90,6 +90,14 @@ constexpr int kNB = 4;  // 16-channel blocks per wave (64 output channels per wo
 constexpr int kWD = 4;  // steps of weight fragments in flight ahead of the matrix work
 constexpr int kStage = 12;  // input vectors in flight per thread while a chunk is staged into LDS
 
+// Where the weight of (tap, input channel c, output channel o) of the convolution being packed for lies in the
+// caller's array.  Plain: that array is this convolution's own [taps][Cin][Cout].  Transposed: the array is the
+// [taps][Cout][Cin] filter bank of the forward convolution whose data gradient this convolution computes; the
+// gradient correlates with the taps mirrored and the two channel roles exchanged.
+__device__ __forceinline__ size_t weight_index(int tap, int c, int o, int taps, int Cin, int Cout, int transposed) {
+    return transposed ? ((size_t)(taps - 1 - tap) * Cout + o) * Cin + c : ((size_t)tap * Cin + c) * Cout + o;
+}
+
 // Weight packing for conv_mfma.  Packed element (((ng*KS + ks)*4 + nb)*64 + lane)*8 + e holds
 // w[tap][c][o] with ks = tap*(CinP/32) + c/32, c = (ks % (CinP/32))*32 + (lane/16)*8 + e and
 // o = ng*64 + (nb/2)*32 + ((lane%16)/4)*8 + (nb%2)*4 + (lane%16)%4, zero where c >= Cin or
@@ -98,7 +106,7 @@ constexpr int kStage = 12;  // input vectors in flight per thread while a chunk 
 // consecutive channels per half h.
 template <typename T>
 __global__ void pack_mfma_weights(const T *__restrict__ w, T *__restrict__ packed, int taps, int Cin, int Cout,
-                                  int CinP, int ngroups) {
+                                  int CinP, int ngroups, int transposed) {
     const int KS = taps * (CinP / 32);
     const size_t total = (size_t)ngroups * KS * kNB * 64 * 8;
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
@@ -112,7 +120,7 @@ __global__ void pack_mfma_weights(const T *__restrict__ w, T *__restrict__ packe
         const int rho = lane & 15;
         const int o = ng * 64 + (nb >> 1) * 32 + (rho >> 2) * 8 + (nb & 1) * 4 + (rho & 3);
         T v = 0;
-        if (c < Cin && o < Cout) v = w[((size_t)tap * Cin + c) * Cout + o];
+        if (c < Cin && o < Cout) v = w[weight_index(tap, c, o, taps, Cin, Cout, transposed)];
         packed[idx] = v;
     }
 }
@@ -124,7 +132,7 @@ __global__ void pack_mfma_weights(const T *__restrict__ w, T *__restrict__ packe
 // then hold 16 consecutive output channels.
 template <typename T>
 __global__ void pack_mfma32_weights(const T *__restrict__ w, T *__restrict__ packed, int taps, int Cin, int Cout,
-                                    int CinP, int ngroups) {
+                                    int CinP, int ngroups, int transposed) {
     const int KS = taps * (CinP / 16);
     const size_t total = (size_t)ngroups * KS * 2 * 64 * 8;
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
@@ -138,15 +146,18 @@ __global__ void pack_mfma32_weights(const T *__restrict__ w, T *__restrict__ pac
         const int rho = lane & 31;
         const int o = ng * 64 + nb * 32 + ((rho >> 2) & 1) * 16 + (rho >> 3) * 4 + (rho & 3);
         T v = 0;
-        if (c < Cin && o < Cout) v = w[((size_t)tap * Cin + c) * Cout + o];
+        if (c < Cin && o < Cout) v = w[weight_index(tap, c, o, taps, Cin, Cout, transposed)];
         packed[idx] = v;
     }
 }
 
 template <typename T>
-__global__ void copy_weights(const T *__restrict__ w, T *__restrict__ packed, size_t total) {
-    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x)
-        packed[idx] = w[idx];
+__global__ void copy_weights(const T *__restrict__ w, T *__restrict__ packed, size_t total, int taps, int Cin, int Cout,
+                             int transposed) {
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+        const int o = (int)(idx % Cout), c = (int)((idx / Cout) % Cin), tap = (int)(idx / ((size_t)Cout * Cin));
+        packed[idx] = w[weight_index(tap, c, o, taps, Cin, Cout, transposed)];
+    }
 }
 
 template <int DT, bool FUSED, int kMB>
@@ -436,33 +447,44 @@ static sbnet_status run_conv(const char *who, sbnet_dtype dt, ConvParams &p, hip
 
 using namespace sbnet;
 
-extern "C" sbnet_status sbnet_pack_weights(const void *w_hwio, sbnet_dtype dtype, int kh, int kw, int Cin, int Cout,
-                                           void *w_packed, size_t *bytes, void *stream) {
-    if (!is_float_dtype(dtype)) return fail(SBNET_EUNSUPPORTED, "sbnet_pack_weights: dtype must be f32, bf16 or f16");
-    if (kh <= 0 || kw <= 0 || Cin <= 0 || Cout <= 0) return fail(SBNET_EINVAL, "sbnet_pack_weights: bad sizes");
+// Cin, Cout: of the convolution the packed weights serve (for the transposed form: the forward convolution's Cout, Cin)
+static sbnet_status pack_entry(const char *who, const void *w_hwio, sbnet_dtype dtype, int kh, int kw, int Cin, int Cout,
+                               void *w_packed, size_t *bytes, int transposed, void *stream) {
+    if (!is_float_dtype(dtype)) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be f32, bf16 or f16", who);
+    if (kh <= 0 || kw <= 0 || Cin <= 0 || Cout <= 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
     const size_t elems = packed_elems(dtype, kh, kw, Cin, Cout);
     if (bytes) *bytes = elems * elem_bytes(dtype);
     if (!w_packed) {
-        if (!bytes) return fail(SBNET_EINVAL, "sbnet_pack_weights: nothing to do");
+        if (!bytes) return fail(SBNET_EINVAL, "%s: nothing to do", who);
         return SBNET_OK;
     }
-    if (!w_hwio) return fail(SBNET_EINVAL, "sbnet_pack_weights: null weights");
+    if (!w_hwio) return fail(SBNET_EINVAL, "%s: null weights", who);
     hipStream_t s = (hipStream_t)stream;
     const int grid = (int)((elems + 255) / 256 < 4096 ? (elems + 255) / 256 : 4096);
     if (use_mfma(dtype, Cin, Cout)) {
         const int CinP = (Cin + 31) / 32 * 32, ngroups = (Cout + 63) / 64;
         hipLaunchKernelGGL(pack_mfma_weights<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)w_hwio,
-                           (uint16_t *)w_packed, kh * kw, Cin, Cout, CinP, ngroups);
+                           (uint16_t *)w_packed, kh * kw, Cin, Cout, CinP, ngroups, transposed);
         hipLaunchKernelGGL(pack_mfma32_weights<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)w_hwio,
-                           (uint16_t *)w_packed + elems / 2, kh * kw, Cin, Cout, CinP, ngroups);
+                           (uint16_t *)w_packed + elems / 2, kh * kw, Cin, Cout, CinP, ngroups, transposed);
     } else if (dtype == SBNET_F32) {
         hipLaunchKernelGGL(copy_weights<uint32_t>, dim3(grid), dim3(256), 0, s, (const uint32_t *)w_hwio,
-                           (uint32_t *)w_packed, elems);
+                           (uint32_t *)w_packed, elems, kh * kw, Cin, Cout, transposed);
     } else {
         hipLaunchKernelGGL(copy_weights<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t *)w_hwio,
-                           (uint16_t *)w_packed, elems);
+                           (uint16_t *)w_packed, elems, kh * kw, Cin, Cout, transposed);
     }
-    return launch_status("sbnet_pack_weights");
+    return launch_status(who);
+}
+
+extern "C" sbnet_status sbnet_pack_weights(const void *w_hwio, sbnet_dtype dtype, int kh, int kw, int Cin, int Cout,
+                                           void *w_packed, size_t *bytes, void *stream) {
+    return pack_entry("sbnet_pack_weights", w_hwio, dtype, kh, kw, Cin, Cout, w_packed, bytes, 0, stream);
+}
+
+extern "C" sbnet_status sbnet_pack_weights_transposed(const void *w_hwio, sbnet_dtype dtype, int kh, int kw, int Cin,
+                                                      int Cout, void *w_packed, size_t *bytes, void *stream) {
+    return pack_entry("sbnet_pack_weights_transposed", w_hwio, dtype, kh, kw, Cout, Cin, w_packed, bytes, 1, stream);
 }
 
 extern "C" sbnet_status sbnet_conv_on_tiles(const void *tiles_in, sbnet_dtype dtype, const int32_t *count, int cap,
@@ -481,6 +503,86 @@ extern "C" sbnet_status sbnet_conv_on_tiles(const void *tiles_in, sbnet_dtype dt
     p.th = th; p.tw = tw; p.Cin = Cin; p.Cout = Cout;
     p.kh = kh; p.kw = kw; p.sh = sh; p.sw = sw; p.relu = relu ? 1 : 0;
     return run_conv<false>(who, dtype, p, (hipStream_t)stream);
+}
+
+// ---- data gradient of the tile convolution ----------------------------------------------------------------------
+// The gradient of a strided valid convolution with respect to its input is itself a stride-1 valid convolution: of
+// the output gradient spread out by the stride (zeros between its pixels) and framed by kh-1 / kw-1 zeros, with the
+// taps mirrored and the channel roles exchanged.  spread_tiles builds that framed stack; the convolution kernels of
+// this file then do the arithmetic with weights packed by sbnet_pack_weights_transposed.
+template <typename V>
+__global__ void spread_tiles(const V *__restrict__ dout, V *__restrict__ framed, const int32_t *__restrict__ count,
+                             int cap, int oh, int ow, int ph, int pw, int cv, int kh, int kw, int sh, int sw,
+                             FastDiv div_cv, FastDiv div_pw) {
+    int n = *count;
+    if (n > cap) n = cap;
+    const uint32_t per_tile = (uint32_t)ph * pw * cv;
+    for (int b = blockIdx.y; b < n; b += gridDim.y) {
+        for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < per_tile; i += gridDim.x * blockDim.x) {
+            const uint32_t px = fdiv(i, div_cv), c = i - px * cv;
+            const uint32_t y = fdiv(px, div_pw), x = px - y * pw;
+            const int u = (int)y - (kh - 1), v = (int)x - (kw - 1);
+            V val = {};
+            if (u >= 0 && v >= 0 && u % sh == 0 && v % sw == 0 && u / sh < oh && v / sw < ow)
+                val = dout[(((size_t)b * oh + u / sh) * ow + v / sw) * cv + c];
+            framed[(size_t)b * per_tile + i] = val;
+        }
+    }
+}
+
+static size_t framed_elems(int cap, int th, int tw, int kh, int kw, int Cout) {
+    return (size_t)cap * (size_t)(th + kh - 1) * (size_t)(tw + kw - 1) * (size_t)Cout;
+}
+
+extern "C" size_t sbnet_conv_backward_data_workspace_bytes(sbnet_dtype dtype, int cap, int th, int tw, int kh, int kw,
+                                                           int Cout) {
+    if (!is_float_dtype(dtype) || cap < 0 || th <= 0 || tw <= 0 || kh <= 0 || kw <= 0 || Cout <= 0) return 0;
+    return (framed_elems(cap, th, tw, kh, kw, Cout) * elem_bytes(dtype) + 255) / 256 * 256;
+}
+
+extern "C" sbnet_status sbnet_conv_on_tiles_backward_data(const void *dout_tiles, sbnet_dtype dtype,
+                                                          const int32_t *count, int cap, int th, int tw, int Cin,
+                                                          const void *w_packed_t, int kh, int kw, int sh, int sw,
+                                                          int Cout, void *din_tiles, void *workspace,
+                                                          size_t workspace_bytes, void *stream) {
+    const char *who = "sbnet_conv_on_tiles_backward_data";
+    if (!dout_tiles || !count || !w_packed_t || !din_tiles || !workspace)
+        return fail(SBNET_EINVAL, "%s: null pointer", who);
+    sbnet_status st = check_conv_shape(who, dtype, cap, th, tw, Cin, kh, kw, sh, sw, Cout);
+    if (st != SBNET_OK) return st;
+    if (((uintptr_t)dout_tiles | (uintptr_t)din_tiles | (uintptr_t)w_packed_t | (uintptr_t)workspace) & 15)
+        return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    if (workspace_bytes < sbnet_conv_backward_data_workspace_bytes(dtype, cap, th, tw, kh, kw, Cout))
+        return fail(SBNET_EINVAL, "%s: workspace too small", who);
+    if (cap == 0) return SBNET_OK;
+    const int oh = (th - kh) / sh + 1, ow = (tw - kw) / sw + 1;
+    const int ph = th + kh - 1, pw = tw + kw - 1;
+    const size_t row_bytes = (size_t)Cout * elem_bytes(dtype);
+    if ((long long)ph * pw * (long long)row_bytes >= (1LL << 31))
+        return fail(SBNET_EUNSUPPORTED, "%s: tile too large", who);
+    hipStream_t s = (hipStream_t)stream;
+    const int vb = row_bytes % 16 == 0 ? 16 : row_bytes % 8 == 0 ? 8 : row_bytes % 4 == 0 ? 4 : 2;
+    const int cv = (int)(row_bytes / vb);
+    const long long per_tile = (long long)ph * pw * cv;
+    dim3 grid((unsigned)((per_tile + 255) / 256 > 64 ? 64 : (per_tile + 255) / 256),
+              (unsigned)(cap > 4096 ? 4096 : cap));
+#define SBNET_SPREAD(V)                                                                                          \
+    hipLaunchKernelGGL((spread_tiles<V>), grid, dim3(256), 0, s, (const V *)dout_tiles, (V *)workspace, count,  \
+                       cap, oh, ow, ph, pw, cv, kh, kw, sh, sw, make_fastdiv(cv), make_fastdiv(pw))
+    if (vb == 16) SBNET_SPREAD(uint4);
+    else if (vb == 8) SBNET_SPREAD(uint2);
+    else if (vb == 4) SBNET_SPREAD(uint32_t);
+    else SBNET_SPREAD(uint16_t);
+#undef SBNET_SPREAD
+    st = launch_status(who);
+    if (st != SBNET_OK) return st;
+    // the gradient as a stride-1 convolution of the framed stack: Cout channels in, Cin channels out
+    ConvParams p = {};
+    p.in = workspace; p.out = din_tiles; p.w = w_packed_t; p.bias = nullptr;
+    p.count = count; p.cap = cap;
+    p.th = ph; p.tw = pw; p.Cin = Cout; p.Cout = Cin;
+    p.kh = kh; p.kw = kw; p.sh = 1; p.sw = 1; p.relu = 0;
+    return run_conv<false>(who, dtype, p, s);
 }
 
 extern "C" sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int N, int H, int W, int Cin,

@@ -1,0 +1,85 @@
+"""GPU parity of the tile convolution's gradients against the fp64 oracle (training support for the
+convolution of Sec. 3.2): element by element on seeded inputs, for every kernel the forward dispatch can
+pick for the gradient's own shape (1x1 and 3x3 matrix-core kernels, the LDS-tiled one, the direct fp32 one)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_1801_02108_amd as sb
+from paper_1801_02108_amd import inputs as gen
+from util import CONV_TOL, TORCH_DT, assert_close, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def step(msg):
+    print("[case] " + msg, flush=True)
+
+
+DGRAD_CASES = [
+    # B, th, tw, Cin, Cout, k, s, dtype
+    (5, 18, 18, 64, 64, 3, 1, "bf16"),       # the headline layer's tiles
+    (3, 18, 18, 64, 64, 3, 1, "f16"),
+    (4, 33, 33, 64, 96, 3, 2, "bf16"),       # downsampling layer: the output gradient is spread by the stride
+    (2, 18, 18, 96, 192, 3, 1, "bf16"),
+    (3, 10, 10, 32, 40, 3, 1, "bf16"),
+    (2, 17, 17, 256, 384, 3, 2, "bf16"),
+    (3, 16, 16, 64, 256, 1, 1, "bf16"),      # 1x1: no frame, no mirror
+    (2, 12, 20, 24, 16, 3, 1, "f32"),        # direct fp32 kernel
+    (2, 12, 13, 8, 8, 3, 2, "f32"),          # the last input column is not reached by any window
+    (2, 14, 12, 16, 8, 3, 2, "bf16"),        # the last input row is not reached by any window
+    (2, 11, 9, 6, 5, 3, 1, "bf16"),          # channel counts the matrix-core kernels do not take
+    (1, 9, 9, 3, 7, 5, 1, "f16"),
+    (2, 9, 11, 16, 16, 3, 3, "bf16"),        # stride 3
+]
+
+
+@pytest.mark.parametrize("B,th,tw,Cin,Cout,k,s,dtype", DGRAD_CASES)
+def test_conv_on_tiles_backward_data(B, th, tw, Cin, Cout, k, s, dtype):
+    step("conv_on_tiles_backward_data %s" % ((B, th, tw, Cin, Cout, k, s, dtype),))
+    r = gen.rng_for(21, th * 1000 + tw * 10 + Cin + Cout + s)
+    oh, ow = (th - k) // s + 1, (tw - k) // s + 1
+    g = gen.activations(r, (B + 1, oh, ow, Cout), dtype)
+    w = gen.conv_weights(r, k, k, Cin, Cout, dtype, unit_variance=(dtype == "f32"))
+    cnt = torch.tensor([B], dtype=torch.int32).cuda()
+    wt = sb.pack_weights_transposed(to_dev(w, dtype))
+    out = torch.full((B + 1, th, tw, Cin), 5.0, dtype=TORCH_DT[dtype]).cuda()
+    sb.conv_on_tiles_backward_data(to_dev(g, dtype), cnt, wt, th, tw, stride=s, out=out)
+    got = to_host(out)
+    ref = orc.conv_valid_backward_data(g[:B], w, th, tw, stride=s)
+    assert_close(got[:B], ref, CONV_TOL[dtype], "conv_on_tiles_backward_data")
+    assert (got[B] == 5.0).all()                        # tiles beyond the count are not touched
+    # input rows and columns that no window reaches get an exact zero
+    rh, rw = (oh - 1) * s + k, (ow - 1) * s + k
+    assert (got[:B, rh:] == 0).all() and (got[:B, :, rw:] == 0).all()
+
+
+def test_sparse_conv_input_gradient_end_to_end():
+    """dL/dx of the whole sparse convolution from library calls only: gather of dL/dy with the output geometry,
+    data gradient on tiles, gather_backward into the image; against the oracle's composition of the same steps."""
+    N, H, W, Cin, Cout, bo, dtype = 2, 70, 66, 64, 96, 16, "bf16"
+    for s in (1, 2):
+        step("sparse conv input gradient stride %d" % s)
+        r = gen.rng_for(22, s)
+        g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, s, bo)
+        mask = (r.random((N, H, W)) < 0.002).astype(np.float64)
+        og_in, og_out = orc.Geom(*g_in.astuple()), orc.Geom(*g_out.astuple())
+        idx_np = orc.reduce_mask(mask, og_in)
+        n, total = len(idx_np), N * g_in.bcount_h * g_in.bcount_w
+        assert 0 < n < total
+        buf = np.zeros((n + 2, 3), dtype=np.int32)
+        buf[:n] = idx_np
+        idx, cnt = torch.from_numpy(buf).cuda(), torch.tensor([n], dtype=torch.int32).cuda()
+        dy = gen.activations(r, (N, Ho, Wo, Cout), dtype)
+        w = gen.conv_weights(r, 3, 3, Cin, Cout, dtype)
+        dy_tiles = sb.sparse_gather(to_dev(dy, dtype), idx, cnt, g_out)
+        din_tiles = sb.conv_on_tiles_backward_data(dy_tiles, cnt, sb.pack_weights_transposed(to_dev(w, dtype)),
+                                                   g_in.bsize_h, g_in.bsize_w, stride=s)
+        dx = torch.zeros((N, H, W, Cin), dtype=TORCH_DT[dtype]).cuda()
+        sb.sparse_gather_backward(din_tiles, idx, cnt, g_in, dx)
+        ref_tiles = orc.conv_valid_backward_data(orc.gather(dy, idx_np, og_out), w, g_in.bsize_h, g_in.bsize_w, stride=s)
+        # the library rounds the tile gradient to bf16 before the overlap sum; so does the reference
+        ref_tiles_r = torch.from_numpy(ref_tiles).to(TORCH_DT[dtype]).to(torch.float64).numpy()
+        ref = orc.gather_backward(ref_tiles_r, idx_np, og_in, np.zeros((N, H, W, Cin)))
+        assert_close(to_host(dx), ref, CONV_TOL[dtype], "sparse conv dL/dx")

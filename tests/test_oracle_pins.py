@@ -260,6 +260,64 @@ def test_gather_backward_is_the_adjoint_of_gather(H, W, C, k, s, bo):
     assert np.array_equal(ones, np.repeat(cover[..., None], C, axis=3))
 
 
+@pytest.mark.parametrize("th,tw,Cin,Cout,k,s", [(5, 4, 2, 3, 3, 1), (7, 6, 2, 2, 3, 2), (6, 7, 1, 2, 3, 2), (4, 4, 3, 2, 1, 1),
+                                                (5, 5, 2, 1, 1, 2), (6, 5, 1, 2, 5, 1)])
+def test_conv_gradients_element_by_element(th, tw, Cin, Cout, k, s):
+    """The convolution is linear in its input and in its weights, so its two gradients are fixed by the forward
+    map alone: d out[q] / d x[p] and d out[q] / d w[p] are read off conv_valid (the C routine, separate code)
+    applied to unit inputs, and every element of both gradients is rebuilt from them.  A mirrored tap, exchanged
+    channel roles, a stride applied on the wrong side or a row a strided window never reaches (the (6, 7) and
+    (7, 6) tiles at stride 2) each change some element."""
+    B = 2
+    ho, wo = orc.conv_out_size(th, k, s), orc.conv_out_size(tw, k, s)
+    w = rng0.standard_normal((k, k, Cin, Cout))
+    x = rng0.standard_normal((B, th, tw, Cin))
+    g = rng0.standard_normal((B, ho, wo, Cout))
+    # data gradient: din[p] = sum_q g[q] * d out[q] / d x[p]
+    din = orc.conv_valid_backward_data(g, w, th, tw, stride=s)
+    assert din.shape == x.shape
+    want = np.zeros_like(x)
+    for p in np.ndindex(1, th, tw, Cin):                          # tiles do not interact: unit inputs in tile 0
+        e = np.zeros((1, th, tw, Cin))
+        e[p] = 1.0
+        col = orc.conv_valid(e, w, stride=s)[0]
+        for b in range(B):
+            want[(b,) + p[1:]] = float((col * g[b]).sum())
+    assert np.allclose(din, want, rtol=0, atol=1e-12)
+    # weight gradient: dw[p] = sum_q g[q] * d out[q] / d w[p]
+    dw = orc.conv_valid_backward_weights(x, g, k, k, stride=s)
+    want = np.zeros_like(w)
+    for p in np.ndindex(*w.shape):
+        e = np.zeros_like(w)
+        e[p] = 1.0
+        want[p] = float((orc.conv_valid(x, e, stride=s) * g).sum())
+    assert np.allclose(dw, want, rtol=0, atol=1e-12)
+
+
+def test_conv_gradients_special_cases():
+    """1x1 at stride 1 is a matrix product per pixel, so the gradients are the textbook ones of y = x W; and the
+    sparse convolution's input gradient, gather_backward of the tile gradient, satisfies the adjoint identity
+    against the tiled forward path."""
+    x = rng0.standard_normal((3, 4, 5, 6))
+    w = rng0.standard_normal((1, 1, 6, 7))
+    g = rng0.standard_normal((3, 4, 5, 7))
+    assert np.allclose(orc.conv_valid_backward_data(g, w, 4, 5), g @ w[0, 0].T, atol=1e-12)
+    assert np.allclose(orc.conv_valid_backward_weights(x, g, 1, 1)[0, 0], x.reshape(-1, 6).T @ g.reshape(-1, 7), atol=1e-12)
+    H, W, Cin, Cout, bo = 13, 11, 2, 3, 4
+    for s in (1, 2):
+        g_in, g_out, Ho, Wo = orc.geometry(H, W, 3, s, bo)
+        mask = rng0.random((1, H, W)) < 0.1
+        idx = orc.reduce_mask(mask.astype(np.float64), g_in)
+        x = rng0.standard_normal((1, H, W, Cin))
+        w = rng0.standard_normal((3, 3, Cin, Cout))
+        gy_tiles = rng0.standard_normal((len(idx), g_out.size_h, g_out.size_w, Cout))
+        fwd = orc.conv_valid(orc.gather(x, idx, g_in), w, stride=s)
+        dx = orc.gather_backward(orc.conv_valid_backward_data(gy_tiles, w, g_in.size_h, g_in.size_w, stride=s), idx, g_in,
+                                 np.zeros_like(x))
+        lhs, rhs = float((fwd * gy_tiles).sum()), float((x * dx).sum())
+        assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(lhs))
+
+
 def test_bn_stats_over_active_blocks():
     """Sparse batch-norm statistics (Sec. 3.3): all blocks active == the library's mean / variance over N, H, W;
     affine maps of x move the statistics as they must; a pixel counts once and only if it is inside the image and
