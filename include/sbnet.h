@@ -239,6 +239,29 @@ sbnet_status sbnet_conv_on_tiles_backward_data(const void *dout_tiles, sbnet_dty
                                                void *stream);
 
 /*
+ * Weight gradient of sbnet_conv_on_tiles (training support, as above): with the forward input
+ * tiles x and dL/dy on tiles,
+ *   dw[r][t][c][o] = sum over b < min(*count, cap) and output pixels (i, j) of
+ *                    x[b][r + sh*i][t + sw*j][c] * dout[b][i][j][o],
+ * written (not added) to dw: device float32 [kh][kw][Cin][Cout]; all zeros when no tile is
+ * active.  tiles_in: [cap][th][tw][Cin], dout_tiles: [cap][oh][ow][Cout] in `dtype` (F32, BF16 or
+ * F16), 16-byte aligned.  Products of BF16/F16 inputs are exact and summed in fp32; the tiles are
+ * split over workgroups whose partial sums are added in a fixed order (no atomics: the same
+ * inputs give the same bits).  3x3 kernels at stride 1 or 2 with channel counts that are multiples
+ * of 8 and output tiles up to 32 columns run on the matrix cores, everything else in a plain
+ * kernel.  workspace: device, 16-byte aligned,
+ * sbnet_conv_backward_weights_workspace_bytes(...) bytes (the partial sums); overwritten.
+ */
+size_t sbnet_conv_backward_weights_workspace_bytes(sbnet_dtype dtype, int cap, int th, int tw,
+                                                   int Cin, int kh, int kw, int sh, int sw,
+                                                   int Cout);
+sbnet_status sbnet_conv_on_tiles_backward_weights(const void *tiles_in, const void *dout_tiles,
+                                                  sbnet_dtype dtype, const int32_t *count, int cap,
+                                                  int th, int tw, int Cin, int kh, int kw, int sh,
+                                                  int sw, int Cout, float *dw, void *workspace,
+                                                  size_t workspace_bytes, void *stream);
+
+/*
  * Set every tile position that lies outside the H x W image to zero, in place.  Needed when a
  * residual unit is composed from single sbnet_conv_on_tiles calls: after the first convolution
  * the halo positions beyond the image border hold act(bias), but the next convolution's zero

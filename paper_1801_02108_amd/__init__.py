@@ -57,6 +57,9 @@ _SIGNATURES = {
     "sbnet_conv_backward_data_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci, _ci]),
     "sbnet_conv_on_tiles_backward_data": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _ci, _ci, _vp,
                                                 _vp, _sz, _vp]),
+    "sbnet_conv_backward_weights_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci]),
+    "sbnet_conv_on_tiles_backward_weights": (_ci, [_vp, _vp, _ci, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _vp,
+                                                   _vp, _sz, _vp]),
     "sbnet_conv_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp]),
     "sbnet_sparse_conv": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp,
                                 _ci, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _vp]),
@@ -310,6 +313,31 @@ def conv_on_tiles_backward_data(dout_tiles, count, w_packed_t, th, tw, stride=1,
     _check(lib().sbnet_conv_on_tiles_backward_data(_ptr(dout_tiles), _dt(dout_tiles), _ptr(count), cap, th, tw, Cin,
                                                    _ptr(w_packed_t.buf), kh, kw, stride, stride, Cout, _ptr(out),
                                                    _ptr(workspace), workspace.numel(), _stream()))
+    return out
+
+
+def conv_backward_weights_workspace_bytes(dtype, cap, th, tw, Cin, k, stride, Cout):
+    return int(lib().sbnet_conv_backward_weights_workspace_bytes(_DTYPES[dtype], cap, th, tw, Cin, k, k, stride, stride, Cout))
+
+
+def conv_on_tiles_backward_weights(tiles, dout_tiles, count, k, stride=1, out=None, workspace=None):
+    """dL/dw [k,k,Cin,Cout] (float32) of conv_on_tiles from its input tiles [cap,th,tw,Cin] and dL/d(tiles_out)
+    [cap,oh,ow,Cout], summed over the active tiles."""
+    _dev(tiles, "tiles"), _dev(dout_tiles, "dout_tiles", tiles.dtype), _dev(count, "count", torch.int32)
+    cap, th, tw, Cin = tiles.shape
+    cap2, oh, ow, Cout = dout_tiles.shape
+    assert cap2 == cap and oh == (th - k) // stride + 1 and ow == (tw - k) // stride + 1
+    if out is None:
+        out = torch.empty((k, k, Cin, Cout), dtype=torch.float32, device=tiles.device)
+    _dev(out, "out", torch.float32)
+    assert out.shape == (k, k, Cin, Cout)
+    need = conv_backward_weights_workspace_bytes(tiles.dtype, cap, th, tw, Cin, k, stride, Cout)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=tiles.device)
+    _dev(workspace, "workspace", torch.uint8)
+    _check(lib().sbnet_conv_on_tiles_backward_weights(_ptr(tiles), _ptr(dout_tiles), _dt(tiles), _ptr(count), cap, th, tw,
+                                                      Cin, k, k, stride, stride, Cout, _ptr(out), _ptr(workspace),
+                                                      workspace.numel(), _stream()))
     return out
 
 

@@ -55,6 +55,53 @@ def test_conv_on_tiles_backward_data(B, th, tw, Cin, Cout, k, s, dtype):
     assert (got[:B, rh:] == 0).all() and (got[:B, :, rw:] == 0).all()
 
 
+WGRAD_CASES = [
+    # B, th, tw, Cin, Cout, k, s, dtype
+    (5, 18, 18, 64, 64, 3, 1, "bf16"),       # the headline layer's tiles: one tile per split
+    (300, 18, 18, 64, 64, 3, 1, "bf16"),     # more tiles than splits: several tiles per workgroup, ragged
+    (7, 18, 18, 64, 64, 3, 1, "f16"),
+    (20, 33, 33, 64, 96, 3, 2, "bf16"),      # downsampling layer; the second block of output channels is half empty
+    (9, 34, 34, 32, 64, 3, 2, "bf16"),       # even tile at stride 2: the last row and column are never read
+    (6, 18, 18, 96, 192, 3, 1, "bf16"),      # several channel blocks
+    (11, 10, 10, 40, 24, 3, 1, "bf16"),      # 8x8 blocks: half-filled matrix rows, ragged channel counts
+    (4, 12, 15, 8, 16, 3, 1, "f16"),         # ragged tile: 10 x 13 outputs
+    (3, 34, 34, 16, 16, 3, 1, "bf16"),       # 32 x 32 outputs: two segments per row
+    (3, 37, 41, 16, 8, 3, 2, "bf16"),        # stride 2 with two segments per row (18 x 20 outputs)
+    (2, 21, 16, 8, 8, 3, 1, "bf16"),         # 19 output rows: the last stage is partly empty
+    (3, 12, 20, 24, 16, 3, 1, "f32"),        # plain kernel
+    (3, 11, 9, 6, 5, 3, 1, "bf16"),
+    (4, 16, 16, 64, 32, 1, 1, "bf16"),
+    (2, 9, 9, 3, 7, 5, 2, "f16"),
+    (2, 13, 11, 16, 16, 3, 3, "bf16"),
+]
+
+
+@pytest.mark.parametrize("B,th,tw,Cin,Cout,k,s,dtype", WGRAD_CASES)
+def test_conv_on_tiles_backward_weights(B, th, tw, Cin, Cout, k, s, dtype):
+    step("conv_on_tiles_backward_weights %s" % ((B, th, tw, Cin, Cout, k, s, dtype),))
+    r = gen.rng_for(23, th * 1000 + tw * 10 + Cin + Cout + s)
+    oh, ow = (th - k) // s + 1, (tw - k) // s + 1
+    x = gen.activations(r, (B + 2, th, tw, Cin), dtype)
+    g = gen.activations(r, (B + 2, oh, ow, Cout), dtype)
+    xd, gd = to_dev(x, dtype), to_dev(g, dtype)
+    ref = orc.conv_valid_backward_weights(x[:B], g[:B], k, k, stride=s)
+    # fp32 accumulation of exact products over B * oh * ow terms in a tree of partial sums
+    tol = 1e-4 if dtype == "f32" else 2e-5
+    for n in (B, 1, 0):
+        cnt = torch.tensor([n], dtype=torch.int32).cuda()
+        dw = torch.full((k, k, Cin, Cout), 7.0, dtype=torch.float32).cuda()
+        sb.conv_on_tiles_backward_weights(xd, gd, cnt, k, stride=s, out=dw)
+        want = ref if n == B else orc.conv_valid_backward_weights(x[:n], g[:n], k, k, stride=s)
+        if n == 0:
+            assert (dw == 0).all()
+        else:
+            assert_close(to_host(dw), want, tol, "conv_on_tiles_backward_weights n=%d" % n)
+        if n == B:
+            dw2 = torch.empty_like(dw)
+            sb.conv_on_tiles_backward_weights(xd, gd, cnt, k, stride=s, out=dw2)
+            assert torch.equal(dw, dw2)                  # fixed summation order: the same bits again
+
+
 def test_sparse_conv_input_gradient_end_to_end():
     """dL/dx of the whole sparse convolution from library calls only: gather of dL/dy with the output geometry,
     data gradient on tiles, gather_backward into the image; against the oracle's composition of the same steps."""
