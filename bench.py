@@ -256,6 +256,7 @@ def run_stages(args):
         x = torch.randn((1, H, W, Cin), device=dev).to(torch.bfloat16)
         y = torch.zeros((1, Ho, Wo, Cout), device=dev, dtype=torch.bfloat16)
         wp = sb.pack_weights(torch.from_numpy(gen.conv_weights(r, 3, 3, Cin, Cout, "bf16")).to(torch.bfloat16).to(dev))
+        wp_t = sb.pack_weights_transposed(torch.from_numpy(gen.conv_weights(r, 3, 3, Cin, Cout, "bf16")).to(torch.bfloat16).to(dev))
         bias = torch.from_numpy(gen.bias_vector(r, Cout)).to(dev)
         idx = torch.empty((total, 3), dtype=torch.int32, device=dev)
         cnt = torch.empty((1,), dtype=torch.int32, device=dev)
@@ -323,9 +324,25 @@ def run_stages(args):
                 return e0.elapsed_time(e1) / (reps * replays)
             ms = device_ms(step)
             k_ms = device_ms(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y, stride=s, relu=True))
+            # the two gradients of the same convolution on its tile stacks (unfused: tiles in, tiles out)
+            th = g_in.bsize_h
+            xt_tiles = torch.randn((max(n, 1), th, th, Cin), device=dev).to(torch.bfloat16)
+            gt_tiles = torch.randn((max(n, 1), bo, bo, Cout), device=dev).to(torch.bfloat16)
+            din_tiles = torch.empty_like(xt_tiles)
+            dw = torch.empty((3, 3, Cin, Cout), dtype=torch.float32, device=dev)
+            ws_d = torch.empty((max(sb.conv_backward_data_workspace_bytes(torch.bfloat16, max(n, 1), th, th, 3, 3, Cout), 16),),
+                               dtype=torch.uint8, device=dev)
+            ws_w = torch.empty((max(sb.conv_backward_weights_workspace_bytes(torch.bfloat16, max(n, 1), th, th, Cin, 3, s, Cout), 16),),
+                               dtype=torch.uint8, device=dev)
+            dgrad_ms = device_ms(lambda: sb.conv_on_tiles_backward_data(gt_tiles, cnt, wp_t, th, th, stride=s, out=din_tiles,
+                                                                        workspace=ws_d))
+            wgrad_ms = device_ms(lambda: sb.conv_on_tiles_backward_weights(xt_tiles, gt_tiles, cnt, 3, stride=s, out=dw,
+                                                                           workspace=ws_w))
             if target >= 1.0:
                 dense_ms = ms
             rows.append({"H": H, "W": W, "Cin": Cin, "Cout": Cout, "stride": s, "block": bo, "target": target,
+                         "backward_data_ms": round(dgrad_ms, 5), "backward_weights_ms": round(wgrad_ms, 5),
+                         "backward_weights_tflops": round(2.0 * n * bo * bo * 9 * Cin * Cout / wgrad_ms / 1e9, 2),
                          "active_blocks": n, "total_blocks": total, "step_ms": round(ms, 5), "conv_kernel_ms": round(k_ms, 5),
                          "conv_tflops": round(2.0 * n * bo * bo * 9 * Cin * Cout / k_ms / 1e9, 2),
                          "speedup_vs_own_dense": round(dense_ms / ms, 3), "miopen_dense_ms": round(miopen_ms, 5)})
@@ -531,6 +548,7 @@ def main():
     if not args.no_extras:
         sweep = []
         dense_ms = None
+        wp_t = sb.pack_weights_transposed(torch.from_numpy(w_np).to(torch.bfloat16).to(dev))
         for target in (0.05, 0.10, 0.20, 0.40, 1.0):
             m_np, fr = mask_for(target)
             m_d = torch.from_numpy(m_np).to(dev)
@@ -556,6 +574,19 @@ def main():
             # batch-norm statistics over the active blocks of the output (Sec. 3.3)
             bn_ws = torch.empty((sb.lib().sbnet_bn_stats_workspace_bytes(n, K),), dtype=torch.uint8, device=dev)
             t_bn = tk(lambda: sb.sparse_bn_stats(y, idx_small, cnt, g_out, bn_ws))
+            # gradients of the tile convolution: with respect to its input tiles and to its weights
+            dgrad_ws = torch.empty((max(sb.conv_backward_data_workspace_bytes(torch.bfloat16, n, BO + 2, BO + 2, 3, 3, K), 16),),
+                                   dtype=torch.uint8, device=dev)
+            wgrad_ws = torch.empty((max(sb.conv_backward_weights_workspace_bytes(torch.bfloat16, n, BO + 2, BO + 2, C, 3, 1, K), 16),),
+                                   dtype=torch.uint8, device=dev)
+            din_buf = torch.empty_like(tiles_buf[0])
+            dw_buf = torch.empty((3, 3, C, K), dtype=torch.float32, device=dev)
+            t_dgrad = tk(lambda: sb.conv_on_tiles_backward_data(tiles_buf[1], cnt, wp_t, BO + 2, BO + 2, out=din_buf,
+                                                                workspace=dgrad_ws))
+            t_wgrad = tk(lambda: sb.conv_on_tiles_backward_weights(tiles_buf[0], tiles_buf[1], cnt, 3, out=dw_buf,
+                                                                   workspace=wgrad_ws))
+            # the data gradient contracts over the (BO+2)^2 input pixels of the framed tile
+            dgrad_flops = 2 * 9 * C * K * (BO + 2) ** 2
             tile_in_b = (BO + 2) ** 2 * C * 2
             tile_out_b = BO * BO * K * 2
             row = {"target": target, "active_blocks": n, "step_ms": round(t_step, 5), "fused_conv_ms": round(t_conv, 5),
@@ -568,6 +599,10 @@ def main():
                    "gather_backward_ms": round(t_gb, 5),
                    "gather_backward_GBps": round((tile_in_b + 2 * BO * BO * C * 2) * n / t_gb / 1e6, 1),
                    "bn_stats_ms": round(t_bn, 5), "bn_stats_GBps": round(tile_out_b * n / t_bn / 1e6, 1),
+                   "conv_backward_data_ms": round(t_dgrad, 5),
+                   "conv_backward_data_tflops": round(dgrad_flops * n / t_dgrad / 1e9, 2),
+                   "conv_backward_weights_ms": round(t_wgrad, 5),
+                   "conv_backward_weights_tflops": round(TILE_FLOPS * n / t_wgrad / 1e9, 2),
                    "unfused_sum_ms": round(t_gather + t_tconv + t_scatter, 5)}
             if target >= 1.0:
                 dense_ms = t_step

@@ -13,12 +13,14 @@
 //     pixels are consecutive; a tap's window starts 0 or 1 elements (stride 2) or 0, 1, 2 elements (stride 1) into a
 //     16-byte vector and is cut from two neighbouring vectors with one byte-align per word;
 //   * the channel planes are an odd number of 16-byte vectors apart and the vector index inside a plane is XOR-ed with
-//     a function of the channel group: the 16-bit transposing writes of a wave (8 channel groups x 8 pixels) and the
-//     16-byte operand reads (32 consecutive channels) both spread over all banks;
+//     channel / 8: the 8-byte transposing writes of a wave (8 channel groups x 8 items of four pixels) and the
+//     16-byte operand reads (consecutive channels) both spread over all banks; the spare vector at the end of each
+//     plane takes the writes of staging slots that hold nothing, so that the writes need no branch;
 //   * columns beyond the output row and rows beyond the tile hold zeros, in both operands, so that a partial row or
 //     stage adds nothing.
-// Stages alternate between two LDS buffers: the loads of the next stage are issued before the matrix work of the
-// current one and written to the other buffer after it.
+// Stages alternate between two LDS buffers: the loads of the next stage are issued at the top of a stage, and in its
+// second half their data, transposed in registers four pixels at a time, is written to the other buffer between the
+// matrix instructions.
 //
 // wgrad_direct: every other shape and fp32; one thread per weight, plain loops.
 #include <hip/hip_runtime.h>
@@ -31,7 +33,7 @@ namespace {
 struct WgradParams {
     const void *x;            // [cap][th][tw][Cin]
     const void *g;            // [cap][oh][ow][Cout]
-    float *part;              // [nsplit][taps][CinP][CoutP]
+    float *part;              // [nsplit][taps][CinP][CoutP], split_stride() floats from one split to the next
     const int32_t *count;
     int cap, th, tw, oh, ow, Cin, Cout, kh, kw, sh, sw;
     int nsplit, ncb, nob, CinP, CoutP;
@@ -50,10 +52,28 @@ struct WgradShape {
     static constexpr int CSG = GPL + 1;
     static constexpr int XBYTES = 64 * CSX * 16;
     static constexpr int STAGE = 64 * (CSX + CSG) * 16;
-    static constexpr int TWMAX = 16 * NSEG * S + 2;
-    static constexpr int NVX = (RX * TWMAX * 8 + 255) / 256;
-    static constexpr int NVG = (R * 16 * NSEG * 8 + 255) / 256;
+    // staging items: four pixels of one phase row (or of one row of dout) times 8 channels
+    static constexpr int QX = (16 * NSEG + 2 + 3) / 4;    // items per phase row of x (at most 16 NSEG + 2 pixels)
+    static constexpr int QG = 4 * NSEG;                   // items per row of dout
+    static constexpr int NIX = (RX * S * QX * 8 + 255) / 256;
+    static constexpr int NIG = (R * QG * 8 + 255) / 256;
 };
+
+// Floats between the partial results of consecutive splits: the size of one result plus 256 bytes.  All workgroups
+// write their results at the same time and at the same offsets inside them; with the bare size (a multiple of 16 KiB
+// for 64 x 64 blocks) between them those writes would all fall on a few memory channels.
+__host__ __device__ __forceinline__ size_t split_stride(int taps, int CinP, int CoutP) { return (size_t)taps * CinP * CoutP + 64; }
+
+// Splits actually used for n active tiles, of the nsplit the launch provides.  Every split costs a partial result
+// (written once, read once by the sum) and every tile of a split costs matrix time, so the best number grows with the
+// square root of n: 8 sqrt(n) suits the two costs measured on 64 x 64 channel blocks.  Both kernels call this with
+// the same arguments.
+__device__ __forceinline__ int splits_used(int n, int nsplit) {
+    int ns = (int)sqrtf(64.f * (float)n);
+    if (ns > n) ns = n;
+    if (ns > nsplit) ns = nsplit;
+    return ns < 1 ? 1 : ns;
+}
 
 __device__ __forceinline__ uint4 lds_read16(const char *p) { return *(const uint4 *)p; }
 
@@ -65,22 +85,15 @@ __device__ __forceinline__ uint4 window1(uint4 v0, uint4 v1) {
 // elements 2..9
 __device__ __forceinline__ uint4 window2(uint4 v0, uint4 v1) { return make_uint4(v0.y, v0.z, v0.w, v1.x); }
 
-// the 8 elements of a staged vector go to 8 consecutive channel planes (plane_bytes apart)
-template <int PLANE_BYTES>
-__device__ __forceinline__ void lds_write_transposed(char *p, uint4 d) {
-    const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        *(uint16_t *)(p + (2 * k) * PLANE_BYTES) = (uint16_t)(w[k] & 0xffffu);
-        *(uint16_t *)(p + (2 * k + 1) * PLANE_BYTES) = (uint16_t)(w[k] >> 16);
-    }
-}
+// two 16-bit halves, one from each word: (lo, lo) or (hi, hi)
+__device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pair_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
 template <int DT, int S, int NSEG>
 __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
     typedef WgradShape<S, NSEG> Sh;
     constexpr int R = Sh::R, RX = Sh::RX, CPV = Sh::CPV, CSX = Sh::CSX, CSG = Sh::CSG, GV = Sh::GV;
-    constexpr int NVX = Sh::NVX, NVG = Sh::NVG;
+    constexpr int NIX = Sh::NIX, NIG = Sh::NIG, NI = NIX + NIG, QX = Sh::QX, QG = Sh::QG;
     extern __shared__ __align__(16) char lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -88,65 +101,76 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
     const int cb = cbob / p.nob, ob = cbob - cb * p.nob;
     int n = *p.count;
     if (n > p.cap) n = p.cap;
-    if (sigma >= n) return;                                        // the sum below reads no partial result of this split
-    const int ntiles = (n - sigma + p.nsplit - 1) / p.nsplit;
+    const int ns = splits_used(n, p.nsplit);
+    if (n <= 0 || sigma >= ns) return;                             // the sum reads no partial result of this split
+    const int ntiles = (n - sigma + ns - 1) / ns;
     const int H = (p.oh + R - 1) / R;
     const int nstages = ntiles * H;
 
-    // ---- what this thread stages: NVX vectors of x and NVG of dout per stage, fixed for the whole kernel ----------
-    uint32_t relx[NVX], ldsx[NVX], relg[NVG], ldsg[NVG];
+    // ---- what this thread stages, fixed for the whole kernel: items of four pixels (consecutive in a phase row of x,
+    // or in a row of dout) by 8 channels = four 16-byte loads, transposed in registers into 8 writes of four pixels.
+    // rel: byte offset of the first pixel inside the stage's first row (kOutOfRange: no item); cnt: pixels that exist.
+    uint32_t rel[NI], at[NI], cnt[NI];
     const int cv = tid & 7;                                        // 8-channel group inside the workgroup's 64
-    const uint32_t swz = 2u * (cv & 3);
 #pragma unroll
-    for (int u = 0; u < NVX; ++u) {
-        const int px = (u * 256 + tid) >> 3;
-        const int ry = px / p.tw, x = px - ry * p.tw;
-        const int xs = x / S, ph = x - xs * S;
-        const bool ok = ry < RX && cb * 64 + cv * 8 < p.Cin && xs < CPV * 8;
-        relx[u] = ok ? (uint32_t)(((ry * p.tw + x) * p.Cin + cb * 64 + cv * 8) * 2) : kOutOfRange;
-        const uint32_t v = (uint32_t)((ry * S + ph) * CPV + (xs >> 3)) ^ swz;
-        ldsx[u] = (uint32_t)(cv * 8 * CSX * 16) + v * 16 + (xs & 7) * 2;
+    for (int u = 0; u < NIX; ++u) {
+        const int it = (u * 256 + tid) >> 3;
+        const int q = it % QX, rp = it / QX, ph = rp % S, ry = rp / S;
+        const int x = 4 * q * S + ph;                              // column of the item's first pixel
+        const bool ok = ry < RX && cb * 64 + cv * 8 < p.Cin && x < p.tw;
+        rel[u] = ok ? (uint32_t)(((ry * p.tw + x) * p.Cin + cb * 64 + cv * 8) * 2) : kOutOfRange;
+        cnt[u] = ok ? (uint32_t)((p.tw - x + S - 1) / S) : 0u;
+        const uint32_t v = (uint32_t)((ry * S + ph) * CPV + (q >> 1)) ^ (uint32_t)cv;
+        at[u] = (uint32_t)(cv * 8 * CSX * 16) + (ok ? v * 16 + (q & 1) * 8 : (uint32_t)Sh::XPL * 16);
     }
 #pragma unroll
-    for (int u = 0; u < NVG; ++u) {
-        const int px = (u * 256 + tid) >> 3;
-        const int gy = px / p.ow, x = px - gy * p.ow;
-        const bool ok = gy < R && ob * 64 + cv * 8 < p.Cout;
-        relg[u] = ok ? (uint32_t)(((gy * p.ow + x) * p.Cout + ob * 64 + cv * 8) * 2) : kOutOfRange;
-        const uint32_t v = (uint32_t)(gy * GV + (x >> 3)) ^ swz;
-        ldsg[u] = (uint32_t)(Sh::XBYTES + cv * 8 * CSG * 16) + v * 16 + (x & 7) * 2;
+    for (int u = 0; u < NIG; ++u) {
+        const int it = (u * 256 + tid) >> 3;
+        const int q = it % QG, gy = it / QG, x = 4 * q;
+        const bool ok = gy < R && ob * 64 + cv * 8 < p.Cout && x < p.ow;
+        rel[NIX + u] = ok ? (uint32_t)(((gy * p.ow + x) * p.Cout + ob * 64 + cv * 8) * 2) : kOutOfRange;
+        cnt[NIX + u] = ok ? (uint32_t)(p.ow - x) : 0u;
+        const uint32_t v = (uint32_t)(gy * GV + (q >> 1)) ^ (uint32_t)cv;
+        at[NIX + u] = (uint32_t)(Sh::XBYTES + cv * 8 * CSG * 16) + (ok ? v * 16 + (q & 1) * 8 : (uint32_t)Sh::GPL * 16);
     }
     const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.x), 0, (int)((uint32_t)p.cap * p.x_tile_bytes), kBufWord3);
     const __amdgpu_buffer_rsrc_t gr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.g), 0, (int)((uint32_t)p.cap * p.g_tile_bytes), kBufWord3);
     const uint32_t x_stage_step = (uint32_t)(R * S * p.tw * p.Cin * 2), g_stage_step = (uint32_t)(R * p.ow * p.Cout * 2);
+    const uint32_t x_px_step = (uint32_t)(S * p.Cin * 2), g_px_step = (uint32_t)(p.Cout * 2);
 
-    uint4 xv[NVX], gv[NVG];
+    uint4 staged[NI][4];
     auto issue = [&](int b, int h) {
-        const uint32_t x0 = (uint32_t)h * x_stage_step, g0 = (uint32_t)h * g_stage_step;
 #pragma unroll
-        for (int u = 0; u < NVX; ++u) {
-            const uint32_t o = x0 + relx[u];                       // rows beyond the tile: zeros
-            xv[u] = buf_load16(xr, o < p.x_tile_bytes ? (uint32_t)b * p.x_tile_bytes + o : kOutOfRange);
-        }
+        for (int u = 0; u < NI; ++u) {
+            const bool isx = u < NIX;
+            const uint32_t tile = isx ? p.x_tile_bytes : p.g_tile_bytes;
+            const uint32_t o = (uint32_t)h * (isx ? x_stage_step : g_stage_step) + rel[u];
+            const uint32_t base = o < tile ? (uint32_t)b * tile + o : kOutOfRange;   // rows beyond the tile: zeros
 #pragma unroll
-        for (int u = 0; u < NVG; ++u) {
-            const uint32_t o = g0 + relg[u];
-            gv[u] = buf_load16(gr, o < p.g_tile_bytes ? (uint32_t)b * p.g_tile_bytes + o : kOutOfRange);
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t off = (base != kOutOfRange && (uint32_t)j < cnt[u]) ? base + j * (isx ? x_px_step : g_px_step) : kOutOfRange;
+                staged[u][j] = buf_load16(isx ? xr : gr, off);
+            }
         }
     };
-    auto write = [&](int bufno) {
-        char *base = lds + bufno * Sh::STAGE;
+    // channel k of item u: its four pixels as one 8-byte write into channel plane k of the item's 8
+    auto write_elem = [&](int w, char *base) {
+        const int u = w >> 3, k = w & 7;
+        uint32_t word[4];
 #pragma unroll
-        for (int u = 0; u < NVX; ++u)
-            if (relx[u] != kOutOfRange) lds_write_transposed<CSX * 16>(base + ldsx[u], xv[u]);
-#pragma unroll
-        for (int u = 0; u < NVG; ++u)
-            if (relg[u] != kOutOfRange) lds_write_transposed<CSG * 16>(base + ldsg[u], gv[u]);
+        for (int j = 0; j < 4; ++j) {
+            const uint4 d = staged[u][j];
+            word[j] = (k >> 1) == 0 ? d.x : (k >> 1) == 1 ? d.y : (k >> 1) == 2 ? d.z : d.w;
+        }
+        uint2 v;
+        v.x = (k & 1) ? pair_hi(word[0], word[1]) : pair_lo(word[0], word[1]);
+        v.y = (k & 1) ? pair_hi(word[2], word[3]) : pair_lo(word[2], word[3]);
+        *(uint2 *)(base + at[u] + k * ((u < NIX ? CSX : CSG) * 16)) = v;
     };
 
     // ---- matrix operands of this wave ------------------------------------------------------------------------------
     const int cl = (wave >> 1) * 32 + (lane & 31), ol = (wave & 1) * 32 + (lane & 31), m = lane >> 5;
-    const uint32_t swa = 2u * ((cl >> 3) & 3), swb = 2u * ((ol >> 3) & 3);
+    const uint32_t swa = (uint32_t)(cl >> 3), swb = (uint32_t)(ol >> 3);
     const char *xplane = lds + cl * CSX * 16, *gplane = lds + Sh::XBYTES + ol * CSG * 16;
     f32x16 acc[9];
 #pragma unroll
@@ -154,64 +178,106 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[k][e] = 0.f;
 
-    auto compute = [&](int bufno) {
+    // one step = 16 output pixels of one row (segment q of row i; q is the outer index so that consecutive steps share
+    // input rows): the operand of dout and, per kernel row, the vectors the three taps are cut from.  A step reads
+    // only the input rows the step before did not have.
+    constexpr int T = R * NSEG, XV = S == 1 ? 2 : 3;
+    struct Ops { uint4 b, x[3][XV]; };
+    auto load_row = [&](Ops &o, const char *xb, int i, int q, int r) {
+        const uint32_t v = (uint32_t)((i * S + r) * S * CPV + 2 * q + m);          // phase 0 of the row
+        o.x[r][0] = lds_read16(xb + (v ^ swa) * 16);
+        o.x[r][1] = lds_read16(xb + ((v + 1) ^ swa) * 16);
+        if (S == 2) o.x[r][XV - 1] = lds_read16(xb + ((v + CPV) ^ swa) * 16);      // phase 1
+    };
+    auto load_ops = [&](Ops &o, const Ops &prev, int bufno, int t) {
         const char *xb = xplane + bufno * Sh::STAGE, *gb = gplane + bufno * Sh::STAGE;
+        const int q = t / R, i = t - q * R;
+        o.b = lds_read16(gb + (((uint32_t)(i * GV + 2 * q + m)) ^ swb) * 16);
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
+        for (int r = 0; r < 3; ++r) {
+            if (i > 0 && r + S < 3) {
 #pragma unroll
-            for (int q = 0; q < NSEG; ++q) {
-                const uint4 bvec = lds_read16(gb + (((uint32_t)(i * GV + 2 * q + m)) ^ swb) * 16);
-#pragma unroll
-                for (int r = 0; r < 3; ++r) {
-                    const int row = i * S + r;
-                    uint4 a0, a1, a2;
-                    if (S == 1) {
-                        const uint32_t v = (uint32_t)(row * CPV + 2 * q + m);
-                        const uint4 v0 = lds_read16(xb + (v ^ swa) * 16), v1 = lds_read16(xb + ((v + 1) ^ swa) * 16);
-                        a0 = v0;
-                        a1 = window1(v0, v1);
-                        a2 = window2(v0, v1);
-                    } else {
-                        const uint32_t e = (uint32_t)((row * 2) * CPV + 2 * q + m), o = e + CPV;
-                        const uint4 v0 = lds_read16(xb + (e ^ swa) * 16), v1 = lds_read16(xb + ((e + 1) ^ swa) * 16);
-                        a0 = v0;
-                        a1 = lds_read16(xb + (o ^ swa) * 16);
-                        a2 = window1(v0, v1);
-                    }
-                    acc[r * 3 + 0] = mfma32x32x16<DT>(a0, bvec, acc[r * 3 + 0]);
-                    acc[r * 3 + 1] = mfma32x32x16<DT>(a1, bvec, acc[r * 3 + 1]);
-                    acc[r * 3 + 2] = mfma32x32x16<DT>(a2, bvec, acc[r * 3 + 2]);
-                }
+                for (int k = 0; k < XV; ++k) o.x[r][k] = prev.x[r + S][k];
+            } else {
+                load_row(o, xb, i, q, r);
             }
+        }
+    };
+    auto mfma1 = [&](const Ops &o, int j) {                       // tap j = 3 r + t of this step
+        const int r = j / 3, t = j - 3 * r;
+        uint4 a;
+        if (S == 1) a = t == 0 ? o.x[r][0] : t == 1 ? window1(o.x[r][0], o.x[r][1]) : window2(o.x[r][0], o.x[r][1]);
+        else a = t == 0 ? o.x[r][0] : t == 1 ? o.x[r][XV - 1] : window1(o.x[r][0], o.x[r][1]);
+        acc[j] = mfma32x32x16<DT>(a, o.b, acc[j]);
+    };
+
+    // stages in order: (tile sigma, rows 0..R-1), (tile sigma, rows R..), ..., (tile sigma + ns, rows 0..), ...
+    int b = sigma, h = 0, issued = 0;
+    auto next_stage = [&]() {                                      // beyond the last stage: the last one again
+        if (issued + 1 < nstages) {
+            ++issued;
+            if (++h == H) { h = 0; b += ns; }
         }
     };
 
     // ---- zero both buffers once: the padding is never written again ------------------------------------------------
-    for (int i = tid; i < 2 * Sh::STAGE / 16; i += 256) ((uint4 *)lds)[i] = make_uint4(0, 0, 0, 0);
-    int b = sigma, h = 0;
     issue(b, h);
+    for (int i = tid; i < 2 * Sh::STAGE / 16; i += 256) ((uint4 *)lds)[i] = make_uint4(0, 0, 0, 0);
     __syncthreads();
-    write(0);
+#pragma unroll
+    for (int w = 0; w < NI * 8; ++w) write_elem(w, lds);
     __syncthreads();
     for (int st = 0; st < nstages; ++st) {
-        // the stage after this one (the last one once more at the end: written to the idle buffer, never read)
-        if (st + 1 < nstages) {
-            if (++h == H) { h = 0; b += p.nsplit; }
-        }
+        // loads of the next stage at the top; matrix work on buffer st % 2, the operands of a step read one step ahead;
+        // in the second half of the stage the loaded items go to the other buffer, between the matrix instructions
+        next_stage();
         issue(b, h);
-        compute(st & 1);
-        write((st + 1) & 1);
+        const int cur = st & 1;
+        char *other = lds + (cur ^ 1) * Sh::STAGE;
+        Ops o0, o1;
+        load_ops(o0, o0, cur, 0);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            Ops &now = (t & 1) ? o1 : o0, &nxt = (t & 1) ? o0 : o1;
+            if (t + 1 < T) load_ops(nxt, now, cur, t + 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 9; ++j) {
+                mfma1(now, j);
+                constexpr int W = NI * 8, SLOTS = T * 9, FIRST = SLOTS / 2, LATE = SLOTS - FIRST;
+                const int slot = t * 9 + j - FIRST;
+                if (slot >= 0) {
+#pragma unroll
+                    for (int w = (slot * W + LATE - 1) / LATE; w < ((slot + 1) * W + LATE - 1) / LATE; ++w) write_elem(w, other);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
         __syncthreads();
     }
 
-    // ---- partial result: row (input channel) 8 (e / 4) + 4 (lane / 32) + e % 4, column (output channel) lane % 32 ----
-    float *out = p.part + (size_t)sigma * 9 * p.CinP * p.CoutP;
-    const int c0 = cb * 64 + (wave >> 1) * 32 + 4 * m, o = ob * 64 + (wave & 1) * 32 + (lane & 31);
+    // ---- partial result.  A lane holds column (output channel) lane % 32 and rows (input channels)
+    // 8 (e / 4) + 4 (lane / 32) + e % 4 of its wave's 32 x 32 block; written like that, every store instruction would
+    // carry 4 bytes per lane.  Each block goes through a wave-private LDS tile (the stage buffers are free now: the loop
+    // ends with a barrier) and leaves as 16-byte stores along the output channels.
+    float *out = p.part + (size_t)sigma * split_stride(9, p.CinP, p.CoutP);
+    constexpr int TS = 36;                                         // floats per tile row: 16-byte aligned rows, shifted banks
+    float *tiles = (float *)lds + wave * (2 * 32 * TS);
+    const int cblk = cb * 64 + (wave >> 1) * 32, oblk = ob * 64 + (wave & 1) * 32;
 #pragma unroll
-    for (int k = 0; k < 9; ++k)
+    for (int k = 0; k < 9; ++k) {
+        float *t = tiles + (k & 1) * (32 * TS);
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            out[((size_t)k * p.CinP + c0 + 8 * (e >> 2) + (e & 3)) * p.CoutP + o] = acc[k][e];
+        for (int e = 0; e < 16; ++e) t[(8 * (e >> 2) + 4 * m + (e & 3)) * TS + (lane & 31)] = acc[k][e];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int row = pass * 8 + (lane >> 3), col = 4 * (lane & 7);
+            const float4 v = *(const float4 *)(t + row * TS + col);
+            *(float4 *)(out + ((size_t)k * p.CinP + cblk + row) * p.CoutP + oblk + col) = v;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 template <int DT>
@@ -229,12 +295,12 @@ __global__ __launch_bounds__(256) void wgrad_direct(WgradParams p) {
     if (e >= total) return;
     int n = *p.count;
     if (n > p.cap) n = p.cap;
-    const int sigma = blockIdx.y;
-    if (sigma >= n) return;
+    const int sigma = blockIdx.y, ns = splits_used(n, p.nsplit);
+    if (n <= 0 || sigma >= ns) return;
     const int o = e % p.Cout, c = (e / p.Cout) % p.Cin, tap = e / (p.Cout * p.Cin);
     const int r = tap / p.kw, t = tap - r * p.kw;
     float acc = 0.f;
-    for (int b = sigma; b < n; b += p.nsplit) {
+    for (int b = sigma; b < n; b += ns) {
         for (int i = 0; i < p.oh; ++i) {
             const size_t xrow = ((size_t)b * p.th + r + (size_t)p.sh * i) * p.tw + t;
             const size_t grow = ((size_t)b * p.oh + i) * p.ow;
@@ -242,31 +308,42 @@ __global__ __launch_bounds__(256) void wgrad_direct(WgradParams p) {
                 acc = fmaf(load_elem<DT>(p.x, (xrow + (size_t)p.sw * j) * p.Cin + c), load_elem<DT>(p.g, (grow + j) * p.Cout + o), acc);
         }
     }
-    p.part[(size_t)sigma * total + e] = acc;
+    p.part[(size_t)sigma * split_stride(p.kh * p.kw, p.CinP, p.CoutP) + e] = acc;
 }
 
-// dw[tap][c][o] = partial results of the splits that had a tile, added in ascending order of the split
+// dw[tap][c][o] = partial results of the splits that had a tile, added in a fixed order: the four waves of a workgroup
+// each add every fourth split in ascending order (many independent loads in flight, where one chain of dependent
+// loads would be bound by latency), then the four sums are added in ascending order of the wave.
 __global__ __launch_bounds__(256) void wgrad_sum(const float *__restrict__ part, const int32_t *__restrict__ count, int cap,
                                                  int nsplit, int taps, int Cin, int Cout, int CinP, int CoutP,
                                                  float *__restrict__ dw) {
+    __shared__ float slice[4][64];
     const int total = taps * Cin * Cout;
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= total) return;
+    const int lane = threadIdx.x & 63, k = threadIdx.x >> 6;
+    const int e = blockIdx.x * 64 + lane;
     int n = *count;
     if (n > cap) n = cap;
-    if (n > nsplit) n = nsplit;
-    const int o = e % Cout, c = (e / Cout) % Cin, tap = e / (Cout * Cin);
-    const size_t at = ((size_t)tap * CinP + c) * CoutP + o, step = (size_t)taps * CinP * CoutP;
+    n = n > 0 ? splits_used(n, nsplit) : 0;
     float acc = 0.f;
-    int s = 0;
-    for (; s + 4 <= n; s += 4) {
-        const float a0 = part[at + (size_t)s * step], a1 = part[at + (size_t)(s + 1) * step];
-        const float a2 = part[at + (size_t)(s + 2) * step], a3 = part[at + (size_t)(s + 3) * step];
-        acc = ((acc + a0) + a1) + a2;
-        acc += a3;
+    if (e < total) {
+        const int o = e % Cout, c = (e / Cout) % Cin, tap = e / (Cout * Cin);
+        const size_t at = ((size_t)tap * CinP + c) * CoutP + o, step = split_stride(taps, CinP, CoutP);
+        // batches of 8 loads in flight (splits beyond the last read as the first one and count as zero)
+        for (int s = k; s < n; s += 32) {
+            float a[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int sj = s + 4 * j;
+                const float v = part[at + (size_t)(sj < n ? sj : 0) * step];
+                a[j] = sj < n ? v : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc += a[j];
+        }
     }
-    for (; s < n; ++s) acc += part[at + (size_t)s * step];
-    dw[e] = acc;
+    slice[k][lane] = acc;
+    __syncthreads();
+    if (k == 0 && e < total) dw[e] = ((slice[0][lane] + slice[1][lane]) + slice[2][lane]) + slice[3][lane];
 }
 
 struct WgradPlan {
@@ -304,7 +381,7 @@ bool plan_wgrad(sbnet_dtype dt, int cap, int th, int tw, int Cin, int kh, int kw
         q->nsplit = (int)ns;
     }
     if (q->nsplit > cap) q->nsplit = cap < 1 ? 1 : cap;
-    q->part_bytes = (size_t)q->nsplit * taps * q->CinP * q->CoutP * sizeof(float);
+    q->part_bytes = (size_t)q->nsplit * split_stride(taps, q->CinP, q->CoutP) * sizeof(float);
     return true;
 }
 
@@ -372,7 +449,7 @@ extern "C" sbnet_status sbnet_conv_on_tiles_backward_weights(const void *tiles_i
         sbnet_status st = launch_status(who);
         if (st != SBNET_OK) return st;
     }
-    hipLaunchKernelGGL(wgrad_sum, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const float *)workspace, count, cap,
+    hipLaunchKernelGGL(wgrad_sum, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, s, (const float *)workspace, count, cap,
                        q.nsplit, taps, Cin, Cout, q.CinP, q.CoutP, dw);
     return launch_status(who);
 }
