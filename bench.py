@@ -42,9 +42,10 @@ def parse():
                          "per-node instrumentation inflates kernels replayed from a graph)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy: a known-size reference for scaling HBM byte counters")
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "stages"],
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "stages", "backward"],
                     help="cfg2 (default) is the headline single 3x3 conv; cfg3/4/5 are the residual-unit workloads; "
-                         "stages = single 3x3 convs, stride 1 and 2, at the backbone's other stage shapes")
+                         "stages = single 3x3 convs, stride 1 and 2, at the backbone's other stage shapes; "
+                         "backward = the gradients of cfg2's convolution on its tile stacks")
     return ap.parse_args()
 
 
@@ -355,6 +356,64 @@ def run_stages(args):
                       "rows": rows}))
 
 
+def run_backward(args):
+    """Gradients of cfg2's tile convolution (18x18x64 tiles -> 16x16x64, bf16) at 5 ... 100 % of its 2200 blocks:
+    data gradient (frame + forward kernel), weight gradient (matrix-core kernel + sum of the partial results) and,
+    beside them, the forward call on the same tiles."""
+    import torch
+    import paper_1801_02108_amd as sb
+    from paper_1801_02108_amd import inputs as gen
+    from paper_1801_02108_amd.autotune import device_ms
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    C = K = 64
+    BO, TH, TOTAL = 16, 18, 2200
+    r = gen.rng_for(2, 77)
+    w = torch.from_numpy(gen.conv_weights(r, 3, 3, C, K, "bf16")).to(torch.bfloat16).to(dev)
+    wp, wp_t = sb.pack_weights(w), sb.pack_weights_transposed(w)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def eager_ms(fn, reps=50):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    tk = eager_ms if args.eager_kernel_timing else device_ms
+    rows = []
+    for frac in (0.05, 0.10, 0.20, 0.40, 1.0):
+        n = max(1, int(round(frac * TOTAL)))
+        x = torch.from_numpy(gen.activations(r, (n, TH, TH, C), "bf16")).to(torch.bfloat16).to(dev)
+        g = torch.from_numpy(gen.activations(r, (n, BO, BO, K), "bf16")).to(torch.bfloat16).to(dev)
+        cnt = torch.tensor([n], dtype=torch.int32, device=dev)
+        y = torch.empty_like(g)
+        din = torch.empty_like(x)
+        dw = torch.empty((3, 3, C, K), dtype=torch.float32, device=dev)
+        ws_d = torch.empty((sb.conv_backward_data_workspace_bytes(torch.bfloat16, n, TH, TH, 3, 3, K),), dtype=torch.uint8, device=dev)
+        ws_w = torch.empty((sb.conv_backward_weights_workspace_bytes(torch.bfloat16, n, TH, TH, C, 3, 1, K),), dtype=torch.uint8, device=dev)
+        t_f = tk(lambda: sb.conv_on_tiles(x, cnt, wp, None, out=y))
+        t_d = tk(lambda: sb.conv_on_tiles_backward_data(g, cnt, wp_t, TH, TH, out=din, workspace=ws_d))
+        t_w = tk(lambda: sb.conv_on_tiles_backward_weights(x, g, cnt, 3, out=dw, workspace=ws_w))
+        flops = 2.0 * n * BO * BO * 9 * C * K
+        rows.append({"active_blocks": n, "forward_ms": round(t_f, 5), "forward_tflops": round(flops / t_f / 1e9, 2),
+                     "backward_data_ms": round(t_d, 5),
+                     "backward_data_tflops": round(flops * (TH * TH) / (BO * BO) / t_d / 1e9, 2),
+                     "backward_weights_ms": round(t_w, 5), "backward_weights_tflops": round(flops / t_w / 1e9, 2)})
+    head = rows[1]
+    print(json.dumps({"metric": "conv_on_tiles_backward_ms_at_10pct_active_blocks",
+                      "value": round(head["backward_data_ms"] + head["backward_weights_ms"], 5), "unit": "ms", "n_gpus": 1,
+                      "steps": 50, "warmup": 3, "ms_per_step": round(head["backward_data_ms"] + head["backward_weights_ms"], 5),
+                      "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "backward: data and weight gradients of cfg2's 3x3 tile convolution "
+                                             "(18x18x64 -> 16x16x64 tiles, bf16), value = both at 220 tiles",
+                                 "timing": "eager launches" if args.eager_kernel_timing else "HIP graph replays"},
+                      "rows": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -374,6 +433,8 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.workload == "backward":
+        return run_backward(args)
     if args.workload == "stages":
         return run_stages(args)
     if args.workload != "cfg2":
