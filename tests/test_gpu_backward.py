@@ -130,3 +130,35 @@ def test_sparse_conv_input_gradient_end_to_end():
         ref_tiles_r = torch.from_numpy(ref_tiles).to(TORCH_DT[dtype]).to(torch.float64).numpy()
         ref = orc.gather_backward(ref_tiles_r, idx_np, og_in, np.zeros((N, H, W, Cin)))
         assert_close(to_host(dx), ref, CONV_TOL[dtype], "sparse conv dL/dx")
+
+
+@pytest.mark.parametrize("n,th,Cin,Cout,s", [(2200, 18, 64, 64, 1), (220, 18, 64, 64, 1), (550, 33, 64, 96, 2)])
+def test_gradients_at_full_size_sampled(n, th, Cin, Cout, s):
+    """The tile counts and shapes bench.py times (all 2200 blocks and 10 % of them for the headline layer, the dense
+    downsampling layer), in its launch configuration.  The oracle computes what it can one by one: the data gradient
+    of a seeded sample of tiles (the first and the last among them), and a seeded sample of weights, each of which is
+    a sum over every pixel of every tile."""
+    step("gradients at full size %s" % ((n, th, Cin, Cout, s),))
+    dtype = "bf16"
+    r = gen.rng_for(24, n + th + Cout)
+    oh = (th - 3) // s + 1
+    x = gen.activations(r, (n, th, th, Cin), dtype)
+    g = gen.activations(r, (n, oh, oh, Cout), dtype)
+    w = gen.conv_weights(r, 3, 3, Cin, Cout, dtype)
+    xd, gd = to_dev(x, dtype), to_dev(g, dtype)
+    cnt = torch.tensor([n], dtype=torch.int32).cuda()
+    din = sb.conv_on_tiles_backward_data(gd, cnt, sb.pack_weights_transposed(to_dev(w, dtype)), th, th, stride=s)
+    dw = sb.conv_on_tiles_backward_weights(xd, gd, cnt, 3, stride=s)
+    pick = np.unique(np.concatenate([[0, n - 1], r.choice(n, 10, replace=False)]))
+    ref = orc.conv_valid_backward_data(g[pick], w, th, th, stride=s)
+    assert_close(to_host(din[torch.from_numpy(pick).cuda()]), ref, CONV_TOL[dtype], "data gradient, sampled tiles")
+    got = to_host(dw)
+    samples = [(int(r.integers(0, 3)), int(r.integers(0, 3)), int(r.integers(0, Cin)), int(r.integers(0, Cout))) for _ in range(48)]
+    samples += [(0, 0, 0, 0), (2, 2, Cin - 1, Cout - 1), (1, 2, Cin - 1, 0), (2, 0, 0, Cout - 1)]
+    want = np.array([float((x[:, kr:kr + s * (oh - 1) + 1:s, kt:kt + s * (oh - 1) + 1:s, c] * g[:, :, :, o]).sum())
+                     for kr, kt, c, o in samples])
+    have = np.array([got[kr, kt, c, o] for kr, kt, c, o in samples])
+    # every weight's gradient is a sum of n * oh * oh products of independent unit-scale factors: scale sqrt(terms)
+    scale = np.sqrt(n * oh * oh)
+    assert np.abs(have - want).max() <= 2e-5 * scale + 2e-5 * np.abs(want).max()
+    assert np.isfinite(got).all() and 0.3 < np.sqrt((got ** 2).mean()) / scale < 3.0
