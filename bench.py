@@ -648,6 +648,15 @@ def main():
                                                                    workspace=wgrad_ws))
             # the data gradient contracts over the (BO+2)^2 input pixels of the framed tile
             dgrad_flops = 2 * 9 * C * K * (BO + 2) ** 2
+            # normalisation over the active blocks of the output, forward (in place) and training-mode backward
+            bn_mean, bn_var = sb.sparse_bn_stats(y, idx_small, cnt, g_out, bn_ws)
+            bn_gamma = torch.ones((K,), dtype=torch.float32, device=dev)
+            bn_beta = torch.zeros((K,), dtype=torch.float32, device=dev)
+            y_bn, dy_bn, dx_bn = torch.empty_like(y), torch.ones_like(y), torch.empty_like(y)
+            bnb_ws = torch.empty((sb.lib().sbnet_bn_backward_workspace_bytes(n, K),), dtype=torch.uint8, device=dev)
+            t_bna = tk(lambda: sb.sparse_bn_apply(y, idx_small, cnt, g_out, bn_mean, bn_var, bn_gamma, bn_beta, relu=True, y=y_bn))
+            t_bnb = tk(lambda: sb.sparse_bn_backward(y, dy_bn, idx_small, cnt, g_out, bn_mean, bn_var, bn_gamma, bn_beta,
+                                                     relu=True, dx=dx_bn, workspace=bnb_ws))
             tile_in_b = (BO + 2) ** 2 * C * 2
             tile_out_b = BO * BO * K * 2
             row = {"target": target, "active_blocks": n, "step_ms": round(t_step, 5), "fused_conv_ms": round(t_conv, 5),
@@ -660,6 +669,8 @@ def main():
                    "gather_backward_ms": round(t_gb, 5),
                    "gather_backward_GBps": round((tile_in_b + 2 * BO * BO * C * 2) * n / t_gb / 1e6, 1),
                    "bn_stats_ms": round(t_bn, 5), "bn_stats_GBps": round(tile_out_b * n / t_bn / 1e6, 1),
+                   "bn_apply_ms": round(t_bna, 5), "bn_apply_GBps": round(2 * tile_out_b * n / t_bna / 1e6, 1),
+                   "bn_backward_ms": round(t_bnb, 5), "bn_backward_GBps": round(5 * tile_out_b * n / t_bnb / 1e6, 1),
                    "conv_backward_data_ms": round(t_dgrad, 5),
                    "conv_backward_data_tflops": round(dgrad_flops * n / t_dgrad / 1e9, 2),
                    "conv_backward_weights_ms": round(t_wgrad, 5),

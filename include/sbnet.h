@@ -174,6 +174,40 @@ sbnet_status sbnet_sparse_bn_stats(const void *x, sbnet_dtype dtype, int N, int 
                                    size_t workspace_bytes, void *stream);
 
 /*
+ * Batch normalisation over the active blocks (Sec. 3.3), forward: for the pixels of the blocks
+ * b < min(*count, cap) that lie inside the image,
+ *   y = act(gamma[c] * (x - mean[c]) / sqrt(var[c] + eps) + beta[c]),   act = ReLU if relu != 0;
+ * every other pixel of y is left as it is.  x, y: [N][H][W][C] in `dtype` (C * element size a
+ * multiple of 16 bytes), 16-byte aligned, y may be x; mean, var (e.g. from sbnet_sparse_bn_stats),
+ * gamma, beta: device float32 [C], gamma / beta may be NULL (1 / 0).  g: non-overlapping blocks.
+ * fp32 arithmetic, one rounding to `dtype`.
+ */
+sbnet_status sbnet_sparse_bn_apply(const void *x, sbnet_dtype dtype, int N, int H, int W, int C,
+                                   const int32_t *indices, const int32_t *count, int cap,
+                                   const sbnet_geom *g, const float *mean, const float *var,
+                                   const float *gamma, const float *beta, float eps, int relu,
+                                   void *y, void *stream);
+
+/*
+ * Backward of the call above in training mode, i.e. when mean and var are the statistics of the
+ * same active pixels of x (count n).  With xhat = (x - mean) / sqrt(var + eps) and
+ * g = dy (relu == 0) or dy where gamma * xhat + beta > 0 and 0 elsewhere (relu != 0):
+ *   dbeta[c] = sum g,  dgamma[c] = sum g * xhat   over the active pixels,
+ *   dx = gamma / sqrt(var + eps) * (g - dbeta / n - xhat * dgamma / n)   on the active pixels;
+ * other pixels of dx are left as they are; dx may be dy.  dgamma, dbeta: device float32 [C],
+ * written also when gamma / beta are NULL.  Sums in fp32 in a fixed order (per block, then a fixed
+ * tree over the blocks): no atomics.  workspace: device, 4-byte aligned,
+ * sbnet_bn_backward_workspace_bytes(cap, C) bytes, overwritten.
+ */
+size_t sbnet_bn_backward_workspace_bytes(int cap, int C);
+sbnet_status sbnet_sparse_bn_backward(const void *x, const void *dy, sbnet_dtype dtype, int N, int H,
+                                      int W, int C, const int32_t *indices, const int32_t *count,
+                                      int cap, const sbnet_geom *g, const float *mean,
+                                      const float *var, const float *gamma, const float *beta,
+                                      float eps, int relu, void *dx, float *dgamma, float *dbeta,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Re-pack convolution weights once for the kernels below.  w_hwio: device, [kh][kw][Cin][Cout]
  * in `dtype` (the filter bank as a (kh*kw*Cin) x Cout matrix, Sec. 2).  With w_packed == NULL
  * only *bytes (host) is set to the size the packed copy needs.  The packed layout is private

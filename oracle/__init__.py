@@ -238,6 +238,47 @@ def bn_stats(x, idx, g_out):
     return mean, ((vals - mean) ** 2).sum(axis=0) / vals.shape[0]
 
 
+def bn_apply(x, idx, g_out, mean, var, gamma, beta, eps, y, relu=False):
+    """Normalisation over the active blocks (Sec. 3.3): act(gamma (x - mean) / sqrt(var + eps) + beta) on the pixels
+    of the listed blocks, a copy of y elsewhere."""
+    x = np.asarray(x, dtype=np.float64)
+    out = np.array(y, dtype=np.float64)
+    m = block_mask(idx, g_out, *x.shape[:3])
+    z = np.asarray(gamma, dtype=np.float64) * (x[m] - mean) / np.sqrt(np.asarray(var, dtype=np.float64) + eps) + beta
+    out[m] = np.maximum(z, 0.0) if relu else z
+    return out
+
+
+def bn_backward(x, dy, idx, g_out, gamma, beta, eps, dx, relu=False):
+    """Gradients of L through out = bn_apply(x, ...) when mean and var are bn_stats of the same active pixels
+    (training mode): returns (dx, dgamma, dbeta); dx is a copy of the argument outside the active blocks.  Written
+    as the chain rule through the three steps mean -> variance -> normalised value, not as the collapsed formula."""
+    x = np.asarray(x, dtype=np.float64)
+    dy = np.asarray(dy, dtype=np.float64)
+    gamma = np.asarray(gamma, dtype=np.float64)
+    out = np.array(dx, dtype=np.float64)
+    m = block_mask(idx, g_out, *x.shape[:3])
+    xa, ga = x[m], dy[m]                                       # [n, C]
+    n = xa.shape[0]
+    C = x.shape[-1]
+    if n == 0:
+        return out, np.zeros(C), np.zeros(C)
+    mean = xa.sum(axis=0) / n
+    xc = xa - mean
+    var = (xc ** 2).sum(axis=0) / n
+    rstd = 1.0 / np.sqrt(var + eps)
+    xhat = xc * rstd
+    if relu:
+        ga = np.where(gamma * xhat + beta > 0.0, ga, 0.0)
+    dbeta = ga.sum(axis=0)
+    dgamma = (ga * xhat).sum(axis=0)
+    dxhat = ga * gamma
+    dvar = (dxhat * xc).sum(axis=0) * (-0.5) * rstd ** 3
+    dmean = -(dxhat * rstd).sum(axis=0) + dvar * (-2.0 * xc.sum(axis=0) / n)
+    out[m] = dxhat * rstd + dvar * 2.0 * xc / n + dmean / n
+    return out, dgamma, dbeta
+
+
 # ---------------------------------------------------------------------------------------
 # compositions
 # ---------------------------------------------------------------------------------------

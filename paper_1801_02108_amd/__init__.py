@@ -52,6 +52,11 @@ _SIGNATURES = {
     "sbnet_sparse_gather_backward": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _vp, _sz, _vp]),
     "sbnet_bn_stats_workspace_bytes": (_sz, [_ci, _ci]),
     "sbnet_sparse_bn_stats": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp, _vp, _sz, _vp]),
+    "sbnet_sparse_bn_apply": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp, _vp, _vp, ctypes.c_float,
+                                    _ci, _vp, _vp]),
+    "sbnet_bn_backward_workspace_bytes": (_sz, [_ci, _ci]),
+    "sbnet_sparse_bn_backward": (_ci, [_vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp, _vp, _vp,
+                                       ctypes.c_float, _ci, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sbnet_pack_weights": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_pack_weights_transposed": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_conv_backward_data_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci, _ci]),
@@ -241,6 +246,52 @@ def sparse_bn_stats(x, indices, count, g, workspace=None):
     _check(lib().sbnet_sparse_bn_stats(_ptr(x), _dt(x), N, H, W, C, _ptr(indices), _ptr(count), cap, g, _ptr(mean),
                                        _ptr(var), _ptr(workspace), workspace.numel(), _stream()))
     return mean, var
+
+
+def _vec(t, name, C):
+    if t is not None:
+        _dev(t, name, torch.float32)
+        assert t.shape == (C,)
+    return _ptr(t)
+
+
+def sparse_bn_apply(x, indices, count, g, mean, var, gamma=None, beta=None, eps=1e-5, relu=False, y=None):
+    """y = act(gamma (x - mean) / sqrt(var + eps) + beta) on the pixels of the active blocks, y untouched elsewhere
+    (y defaults to x: in place); returns y."""
+    _dev(x, "x"), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    N, H, W, C = x.shape
+    if y is None:
+        y = x
+    _dev(y, "y", x.dtype)
+    assert y.shape == x.shape
+    _check(lib().sbnet_sparse_bn_apply(_ptr(x), _dt(x), N, H, W, C, _ptr(indices), _ptr(count), indices.shape[0], g,
+                                       _vec(mean, "mean", C), _vec(var, "var", C), _vec(gamma, "gamma", C),
+                                       _vec(beta, "beta", C), float(eps), int(bool(relu)), _ptr(y), _stream()))
+    return y
+
+
+def sparse_bn_backward(x, dy, indices, count, g, mean, var, gamma=None, beta=None, eps=1e-5, relu=False, dx=None,
+                       workspace=None):
+    """Gradients through sparse_bn_apply in training mode (mean, var = sparse_bn_stats of x over the same blocks);
+    returns (dx, dgamma, dbeta); dx defaults to a new zero tensor and is written on the active blocks only."""
+    _dev(x, "x"), _dev(dy, "dy", x.dtype), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    N, H, W, C = x.shape
+    cap = indices.shape[0]
+    if dx is None:
+        dx = torch.zeros_like(x)
+    _dev(dx, "dx", x.dtype)
+    assert dy.shape == x.shape and dx.shape == x.shape
+    need = lib().sbnet_bn_backward_workspace_bytes(cap, C)
+    if workspace is None:
+        workspace = torch.empty((max(need, 4),), dtype=torch.uint8, device=x.device)
+    _dev(workspace, "workspace", torch.uint8)
+    dgamma = torch.empty((C,), dtype=torch.float32, device=x.device)
+    dbeta = torch.empty((C,), dtype=torch.float32, device=x.device)
+    _check(lib().sbnet_sparse_bn_backward(_ptr(x), _ptr(dy), _dt(x), N, H, W, C, _ptr(indices), _ptr(count), cap, g,
+                                          _vec(mean, "mean", C), _vec(var, "var", C), _vec(gamma, "gamma", C),
+                                          _vec(beta, "beta", C), float(eps), int(bool(relu)), _ptr(dx), _ptr(dgamma),
+                                          _ptr(dbeta), _ptr(workspace), workspace.numel(), _stream()))
+    return dx, dgamma, dbeta
 
 
 class PackedWeights:

@@ -12,52 +12,9 @@
 //   bn_combine   one workgroup per channel merges the blocks' triples with the pairwise update of Chan, Golub and
 //                LeVeque (mean += delta * n_b / n; M2 += M2_b + delta^2 * n_a * n_b / n): every thread a strided
 //                subset in list order, then a fixed tree over the threads.
-#include "common.h"
+#include "bn_common.h"
 
 namespace sbnet {
-
-constexpr int kBnThreads = 256;
-
-struct BnParams {
-    sbnet_geom g;
-    int H, W, C, cap;
-    int slabs, cs;               // slabs per pixel, channels per full slab (128 bytes)
-    uint32_t pix_vecs;           // 16-byte vectors per pixel
-    int hw;                      // pixels per block
-    FastDiv div_slabs, div_w;
-};
-
-template <int DT> struct BnElem;
-template <> struct BnElem<SBNET_F32> {
-    static constexpr int EPV = 4;
-    static __device__ __forceinline__ void unpack(const uint4 &v, float *f) {
-        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
-    }
-};
-template <> struct BnElem<SBNET_BF16> {
-    static constexpr int EPV = 8;
-    static __device__ __forceinline__ void unpack(const uint4 &v, float *f) {
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            f[2 * i] = bf16_bits_to_float(w[i] & 0xffffu);
-            f[2 * i + 1] = bf16_bits_to_float(w[i] >> 16);
-        }
-    }
-};
-template <> struct BnElem<SBNET_F16> {
-    static constexpr int EPV = 8;
-    static __device__ __forceinline__ void unpack(const uint4 &v, float *f) {
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            union { _Float16 h[2]; uint32_t u; } x;
-            x.u = w[i];
-            f[2 * i] = (float)x.h[0];
-            f[2 * i + 1] = (float)x.h[1];
-        }
-    }
-};
 
 // workspace layout: float part[cap][C][2] (mean, M2), then float cnt[cap]
 template <int DT>
@@ -197,28 +154,12 @@ extern "C" sbnet_status sbnet_sparse_bn_stats(const void *x, sbnet_dtype dtype, 
                                               size_t workspace_bytes, void *stream) {
     const char *who = "sbnet_sparse_bn_stats";
     if (!x || !indices || !count || !mean || !var) return fail(SBNET_EINVAL, "%s: null pointer", who);
-    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || cap < 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
-    if (!geom_ok(g)) return fail(SBNET_EINVAL, "%s: bad geometry", who);
-    if (!is_float_dtype(dtype)) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be f32, bf16 or f16", who);
-    if (g->bstride_h < g->bsize_h || g->bstride_w < g->bsize_w)
-        return fail(SBNET_EINVAL, "%s: blocks must not overlap (every pixel counts once)", who);
+    BnParams p;
+    sbnet_status st = bn_fill_params(who, dtype, N, H, W, C, cap, g, &p);
+    if (st != SBNET_OK) return st;
     if ((uintptr_t)x & 15) return fail(SBNET_EINVAL, "%s: x must be 16-byte aligned", who);
-    const int es = elem_bytes(dtype);
-    if ((long long)C * es % 16) return fail(SBNET_EUNSUPPORTED, "%s: a pixel's channels must fill 16-byte vectors", who);
     if (cap > 0 && (!workspace || ((uintptr_t)workspace & 3) || workspace_bytes < sbnet_bn_stats_workspace_bytes(cap, C)))
         return fail(SBNET_EINVAL, "%s: workspace missing, misaligned or too small", who);
-    if ((long long)g->bsize_h * g->bsize_w >= (1LL << 24))
-        return fail(SBNET_EUNSUPPORTED, "%s: block too large (pixel counts are kept in fp32)", who);
-    BnParams p;
-    p.g = *g;
-    p.H = H; p.W = W; p.C = C; p.cap = cap;
-    p.cs = 128 / es;
-    p.slabs = (C + p.cs - 1) / p.cs;
-    p.pix_vecs = (uint32_t)(C * es / 16);
-    p.hw = g->bsize_h * g->bsize_w;
-    if ((long long)cap * p.slabs >= (1LL << 31)) return fail(SBNET_EUNSUPPORTED, "%s: too many work items", who);
-    p.div_slabs = make_fastdiv((uint32_t)p.slabs);
-    p.div_w = make_fastdiv((uint32_t)g->bsize_w);
     hipStream_t s = (hipStream_t)stream;
     float *part = (float *)workspace;
     float *cnt = part ? part + (size_t)cap * C * 2 : nullptr;

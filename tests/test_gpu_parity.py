@@ -335,6 +335,62 @@ def test_sparse_bn_stats(H, W, C, bo, N, dtype):
         assert torch.equal(mean, mean2) and torch.equal(var, var2)        # fixed summation order
 
 
+@pytest.mark.parametrize("H,W,C,bo,N,dtype", [(48, 80, 64, 16, 2, "bf16"), (37, 29, 40, 4, 2, "f16"), (64, 64, 16, 8, 1, "f32"),
+                                              (33, 47, 256, 16, 1, "bf16")])
+@pytest.mark.parametrize("relu", [False, True])
+def test_sparse_bn_apply_and_backward(H, W, C, bo, N, dtype, relu):
+    """Normalisation over the active blocks (Sec. 3.3), forward and training-mode backward, with the statistics the
+    library itself computed; pixels outside the active blocks keep their bits."""
+    step("bn apply/backward %s" % ((H, W, C, bo, N, dtype, relu),))
+    r = gen.rng_for(10, H * 1000 + W + C + int(relu))
+    _, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    eps = 1e-3
+    x = gen.round_to((gen.activations(r, (N, H, W, C), "f32") * 1.5 + 0.25).astype(np.float32), dtype)
+    dy = gen.activations(r, (N, H, W, C), dtype)
+    gamma = (r.standard_normal(C) * 0.3 + 1.0).astype(np.float32)
+    beta = (r.standard_normal(C) * 0.3).astype(np.float32)
+    y0 = gen.activations(r, (N, H, W, C), dtype)
+    tol = {"f32": 2e-5, "bf16": 8e-3, "f16": 1e-3}[dtype]       # one rounding of the result to the storage type
+    for dens in (0.0, 0.004, 1.0):
+        mask = (r.random((N, H, W)) < dens).astype(np.float32)
+        idx = orc.reduce_mask(mask, ogeom(g_out))
+        d_idx, d_cnt = dev_indices(idx, len(idx) + 2)
+        xd, dyd = to_dev(x, dtype), to_dev(dy, dtype)
+        mean, var = sb.sparse_bn_stats(xd, d_idx, d_cnt, g_out)
+        gd, bd = torch.from_numpy(gamma).cuda(), torch.from_numpy(beta).cuda()
+        y = sb.sparse_bn_apply(xd, d_idx, d_cnt, g_out, mean, var, gd, bd, eps=eps, relu=relu, y=to_dev(y0, dtype))
+        om, ov = orc.bn_stats(x, idx, ogeom(g_out))
+        ref = orc.bn_apply(x, idx, ogeom(g_out), om, ov, gamma, beta, eps, y0, relu=relu)
+        inside = orc.block_mask(idx, ogeom(g_out), N, H, W)
+        got = to_host(y)
+        assert np.array_equal(got[~inside], y0[~inside])
+        if inside.any():
+            assert_close(got[inside], ref[inside], tol, "bn_apply")
+        # in place gives the same bits
+        x2 = to_dev(x, dtype)
+        sb.sparse_bn_apply(x2, d_idx, d_cnt, g_out, mean, var, gd, bd, eps=eps, relu=relu)
+        assert torch.equal(x2[torch.from_numpy(inside).cuda()], y[torch.from_numpy(inside).cuda()])
+        # backward
+        d0 = gen.activations(r, (N, H, W, C), dtype)
+        dx, dgam, dbet = sb.sparse_bn_backward(xd, dyd, d_idx, d_cnt, g_out, mean, var, gd, bd, eps=eps, relu=relu,
+                                               dx=to_dev(d0, dtype))
+        rdx, rdg, rdb = orc.bn_backward(x, dy, idx, ogeom(g_out), gamma, beta, eps, d0, relu=relu)
+        gotdx = to_host(dx)
+        assert np.array_equal(gotdx[~inside], d0[~inside])
+        npx = int(inside.sum())
+        if npx:
+            # sums of npx terms of unit scale in fp32, partial sums per block then a tree
+            stol = 3e-5 * np.sqrt(npx) + 1e-4
+            assert np.abs(dgam.cpu().numpy() - rdg).max() <= stol * max(1.0, np.abs(rdg).max() / np.sqrt(npx)), np.abs(dgam.cpu().numpy() - rdg).max()
+            assert np.abs(dbet.cpu().numpy() - rdb).max() <= stol * max(1.0, np.abs(rdb).max() / np.sqrt(npx))
+            assert_close(gotdx[inside], rdx[inside], tol * 2, "bn_backward dx")
+        else:
+            assert (dgam == 0).all() and (dbet == 0).all()
+        dx2, dgam2, dbet2 = sb.sparse_bn_backward(xd, dyd, d_idx, d_cnt, g_out, mean, var, gd, bd, eps=eps, relu=relu,
+                                                  dx=to_dev(d0, dtype))
+        assert torch.equal(dx, dx2) and torch.equal(dgam, dgam2) and torch.equal(dbet, dbet2)
+
+
 # --------------------------------------------------------------------------- convolution on tiles
 CONV_CASES = [
     # B, th, tw, Cin, Cout, k, s, dtype, relu, bias

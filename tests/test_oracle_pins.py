@@ -260,6 +260,60 @@ def test_gather_backward_is_the_adjoint_of_gather(H, W, C, k, s, bo):
     assert np.array_equal(ones, np.repeat(cover[..., None], C, axis=3))
 
 
+def test_bn_apply_and_backward():
+    """All blocks active and no activation: the library's batch_norm in training mode and its autograd gradients
+    (fp64).  Some blocks active, with and without ReLU: the forward value by brute force over pixels; the three
+    gradients by central differences of L = sum(coef * bn_apply(x with statistics of the active pixels)), which
+    knows nothing of the backward formulas; pixels outside the active blocks keep the caller's values."""
+    import torch
+    N, H, W, C, bo, eps = 2, 9, 7, 3, 4, 1e-3
+    _, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    x = rng0.standard_normal((N, H, W, C)) * 2.0 + 0.5
+    dy = rng0.standard_normal((N, H, W, C))
+    gamma, beta = rng0.standard_normal(C) + 1.5, rng0.standard_normal(C) * 0.3
+    full = np.array([(n, by, bx) for n in range(N) for by in range(g_out.count_h) for bx in range(g_out.count_w)], dtype=np.int32)
+    mean, var = orc.bn_stats(x, full, g_out)
+    xt = torch.tensor(x.transpose(0, 3, 1, 2), dtype=torch.float64, requires_grad=True)
+    gt, bt = torch.tensor(gamma, requires_grad=True), torch.tensor(beta, requires_grad=True)
+    out_t = torch.nn.functional.batch_norm(xt, None, None, gt, bt, training=True, eps=eps)
+    out_t.backward(torch.tensor(dy.transpose(0, 3, 1, 2)))
+    out = orc.bn_apply(x, full, g_out, mean, var, gamma, beta, eps, np.zeros_like(x))
+    assert np.allclose(out, out_t.detach().numpy().transpose(0, 2, 3, 1), atol=1e-12)
+    dx, dgam, dbet = orc.bn_backward(x, dy, full, g_out, gamma, beta, eps, np.zeros_like(x))
+    assert np.allclose(dx, xt.grad.numpy().transpose(0, 2, 3, 1), atol=1e-11)
+    assert np.allclose(dgam, gt.grad.numpy(), atol=1e-11) and np.allclose(dbet, bt.grad.numpy(), atol=1e-11)
+
+    idx = full[[0, 3, 4, len(full) - 1]]                        # the last block hangs over both image edges
+    inside = orc.block_mask(idx, g_out, N, H, W)
+    y0 = rng0.standard_normal(x.shape)
+    for relu in (False, True):
+        mean, var = orc.bn_stats(x, idx, g_out)
+        out = orc.bn_apply(x, idx, g_out, mean, var, gamma, beta, eps, y0, relu=relu)
+        for n, yy, xx in [(0, 0, 0), (0, 3, 6), (1, 8, 6), (1, 4, 3), (0, 5, 1)]:
+            z = gamma * (x[n, yy, xx] - mean) / np.sqrt(var + eps) + beta
+            want = (np.maximum(z, 0) if relu else z) if inside[n, yy, xx] else y0[n, yy, xx]
+            assert np.allclose(out[n, yy, xx], want, atol=1e-12)
+
+        def loss(xv, gv, bv):
+            mu, vv = orc.bn_stats(xv, idx, g_out)
+            return float((dy * orc.bn_apply(xv, idx, g_out, mu, vv, gv, bv, eps, np.zeros_like(xv), relu=relu)).sum())
+        d0 = rng0.standard_normal(x.shape)
+        dx, dgam, dbet = orc.bn_backward(x, dy, idx, g_out, gamma, beta, eps, d0, relu=relu)
+        assert np.array_equal(dx[~inside], d0[~inside])
+        h = 1e-6
+        for n, yy, xx, c in [(0, 0, 0, 0), (0, 5, 5, 1), (1, 8, 6, 2), (0, 3, 3, 1), (0, 8, 2, 0)]:
+            assert inside[n, yy, xx]
+            e = np.zeros_like(x)
+            e[n, yy, xx, c] = h
+            fd = (loss(x + e, gamma, beta) - loss(x - e, gamma, beta)) / (2 * h)
+            assert abs(dx[n, yy, xx, c] - fd) < 1e-6 * max(1.0, abs(fd))
+        for c in range(C):
+            e = np.zeros(C)
+            e[c] = h
+            assert abs(dgam[c] - (loss(x, gamma + e, beta) - loss(x, gamma - e, beta)) / (2 * h)) < 1e-6 * max(1.0, abs(dgam[c]))
+            assert abs(dbet[c] - (loss(x, gamma, beta + e) - loss(x, gamma, beta - e)) / (2 * h)) < 1e-6 * max(1.0, abs(dbet[c]))
+
+
 @pytest.mark.parametrize("th,tw,Cin,Cout,k,s", [(5, 4, 2, 3, 3, 1), (7, 6, 2, 2, 3, 2), (6, 7, 1, 2, 3, 2), (4, 4, 3, 2, 1, 1),
                                                 (5, 5, 2, 1, 1, 2), (6, 5, 1, 2, 5, 1)])
 def test_conv_gradients_element_by_element(th, tw, Cin, Cout, k, s):
