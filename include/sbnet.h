@@ -255,8 +255,9 @@ sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int N, int H, i
  * [cap][th][tw][Cin], every element of the tiles b < min(*count, cap) written (input rows a strided
  * window never reaches get 0).  w_packed_t: from sbnet_pack_weights_transposed, called with the
  * forward convolution's w_hwio, kh, kw, Cin, Cout.  workspace: device, 16-byte aligned,
- * sbnet_conv_backward_data_workspace_bytes(...) bytes (the output gradient spread by the stride and
- * framed by kh-1 / kw-1 zeros: [cap][th+kh-1][tw+kw-1][Cout]); overwritten.  All pointers device
+ * sbnet_conv_backward_data_workspace_bytes(...) bytes (at strides above 1 the output gradient spread
+ * by the stride and framed by kh-1 / kw-1 zeros, [cap][th+kh-1][tw+kw-1][Cout]; at stride 1 only
+ * one index triple per tile); overwritten.  All pointers device
  * and 16-byte aligned.  Feeding din_tiles to sbnet_sparse_gather_backward gives dL/dx of the whole
  * sparse convolution; dout_tiles come from sbnet_sparse_gather of dL/dy with the output geometry.
  */

@@ -508,8 +508,10 @@ extern "C" sbnet_status sbnet_conv_on_tiles(const void *tiles_in, sbnet_dtype dt
 // ---- data gradient of the tile convolution ----------------------------------------------------------------------
 // The gradient of a strided valid convolution with respect to its input is itself a stride-1 valid convolution: of
 // the output gradient spread out by the stride (zeros between its pixels) and framed by kh-1 / kw-1 zeros, with the
-// taps mirrored and the channel roles exchanged.  spread_tiles builds that framed stack; the convolution kernels of
-// this file then do the arithmetic with weights packed by sbnet_pack_weights_transposed.
+// taps mirrored and the channel roles exchanged.  At stride 1 the fused kernels read that frame for free (a tile of
+// the output gradient is addressed as a small image, whose surroundings read as zeros); at larger strides
+// spread_tiles builds the framed stack.  The convolution kernels of this file then do the arithmetic with weights
+// packed by sbnet_pack_weights_transposed.
 template <typename V>
 __global__ void spread_tiles(const V *__restrict__ dout, V *__restrict__ framed, const int32_t *__restrict__ count,
                              int cap, int oh, int ow, int ph, int pw, int cv, int kh, int kw, int sh, int sw,
@@ -530,6 +532,16 @@ __global__ void spread_tiles(const V *__restrict__ dout, V *__restrict__ framed,
     }
 }
 
+// index triple (b, 0, 0) for tile b: every tile as a sample of its own with a single block
+__global__ void tile_indices(int32_t *__restrict__ idx, int cap) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < cap) {
+        idx[3 * b] = b;
+        idx[3 * b + 1] = 0;
+        idx[3 * b + 2] = 0;
+    }
+}
+
 static size_t framed_elems(int cap, int th, int tw, int kh, int kw, int Cout) {
     return (size_t)cap * (size_t)(th + kh - 1) * (size_t)(tw + kw - 1) * (size_t)Cout;
 }
@@ -537,7 +549,9 @@ static size_t framed_elems(int cap, int th, int tw, int kh, int kw, int Cout) {
 extern "C" size_t sbnet_conv_backward_data_workspace_bytes(sbnet_dtype dtype, int cap, int th, int tw, int kh, int kw,
                                                            int Cout) {
     if (!is_float_dtype(dtype) || cap < 0 || th <= 0 || tw <= 0 || kh <= 0 || kw <= 0 || Cout <= 0) return 0;
-    return (framed_elems(cap, th, tw, kh, kw, Cout) * elem_bytes(dtype) + 255) / 256 * 256;
+    size_t bytes = framed_elems(cap, th, tw, kh, kw, Cout) * elem_bytes(dtype);
+    if (bytes < (size_t)cap * 12) bytes = (size_t)cap * 12;        // or one index triple per tile (stride 1)
+    return (bytes + 255) / 256 * 256;
 }
 
 extern "C" sbnet_status sbnet_conv_on_tiles_backward_data(const void *dout_tiles, sbnet_dtype dtype,
@@ -561,6 +575,26 @@ extern "C" sbnet_status sbnet_conv_on_tiles_backward_data(const void *dout_tiles
     if ((long long)ph * pw * (long long)row_bytes >= (1LL << 31))
         return fail(SBNET_EUNSUPPORTED, "%s: tile too large", who);
     hipStream_t s = (hipStream_t)stream;
+    if (sh == 1 && sw == 1) {
+        // No stride, nothing to spread: the frame of zeros is what the fused kernels read around an image anyway.
+        // Every tile of dout is taken as a sample of its own (oh x ow), gathered with a window that starts kh-1 / kw-1
+        // outside it, and the result "scattered" into a th x tw image that is the tile of din.
+        int32_t *idx = (int32_t *)workspace;
+        hipLaunchKernelGGL(tile_indices, dim3((cap + 255) / 256), dim3(256), 0, s, idx, cap);
+        st = launch_status(who);
+        if (st != SBNET_OK) return st;
+        ConvParams p = {};
+        p.in = dout_tiles; p.out = din_tiles; p.w = w_packed_t; p.bias = nullptr;
+        p.indices = idx; p.count = count; p.cap = cap;
+        p.th = ph; p.tw = pw; p.Cin = Cout; p.Cout = Cin;
+        p.kh = kh; p.kw = kw; p.sh = 1; p.sw = 1; p.relu = 0; p.add = 0;
+        p.g_in.bsize_h = ph; p.g_in.bsize_w = pw; p.g_in.bstride_h = ph; p.g_in.bstride_w = pw;
+        p.g_in.boffset_h = -(kh - 1); p.g_in.boffset_w = -(kw - 1); p.g_in.bcount_h = p.g_in.bcount_w = 1;
+        p.g_out.bsize_h = th; p.g_out.bsize_w = tw; p.g_out.bstride_h = th; p.g_out.bstride_w = tw;
+        p.g_out.boffset_h = p.g_out.boffset_w = 0; p.g_out.bcount_h = p.g_out.bcount_w = 1;
+        p.H = oh; p.W = ow; p.Ho = th; p.Wo = tw;
+        return run_conv<true>(who, dtype, p, s);
+    }
     const int vb = row_bytes % 16 == 0 ? 16 : row_bytes % 8 == 0 ? 8 : row_bytes % 4 == 0 ? 4 : 2;
     const int cv = (int)(row_bytes / vb);
     const long long per_tile = (long long)ph * pw * cv;
