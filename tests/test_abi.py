@@ -64,3 +64,44 @@ def test_null_pointers_are_rejected_before_any_launch():
     assert lib.sbnet_sparse_gather(None, sb.BF16, 1, 16, 16, 8, None, None, 4, g_in, None, None) == sb.EINVAL
     assert lib.sbnet_sparse_scatter(None, sb.BF16, None, None, 4, g_out, None, 1, 16, 16, 8, 0, None) == sb.EINVAL
     assert lib.sbnet_conv_on_tiles(None, sb.BF16, None, 4, 6, 6, 8, None, None, 3, 3, 1, 1, 8, 0, None, None) == sb.EINVAL
+
+
+def test_gradient_and_normalisation_calls_check_their_arguments_on_the_host():
+    """Size queries and the argument checks of the training-side entry points, none of which reaches a launch."""
+    lib = sb.lib()
+    _, g_out, _, _ = sb.geometry(16, 16, 3, 1, 4)
+    g_in = sb.geometry(16, 16, 3, 1, 4)[0]
+    # data gradient: the framed copy at stride 2, never less than one index triple per tile
+    assert lib.sbnet_conv_backward_data_workspace_bytes(sb.BF16, 10, 33, 33, 3, 3, 96) >= 10 * 35 * 35 * 96 * 2
+    assert lib.sbnet_conv_backward_data_workspace_bytes(sb.F16, 7, 1, 1, 1, 1, 1) >= 7 * 12
+    assert lib.sbnet_conv_backward_data_workspace_bytes(sb.U8, 7, 6, 6, 3, 3, 8) == 0
+    nbytes = ctypes.c_size_t()
+    assert lib.sbnet_pack_weights_transposed(None, sb.BF16, 3, 3, 64, 96, None, nbytes, None) == sb.OK
+    fwd = ctypes.c_size_t()
+    assert lib.sbnet_pack_weights(None, sb.BF16, 3, 3, 96, 64, None, fwd, None) == sb.OK
+    assert nbytes.value == fwd.value                    # packed for a convolution with the channel roles exchanged
+    assert lib.sbnet_conv_on_tiles_backward_data(None, sb.BF16, None, 4, 6, 6, 8, None, 3, 3, 1, 1, 8, None, None, 0,
+                                                 None) == sb.EINVAL
+    assert b"null" in lib.sbnet_last_error()
+    # weight gradient: one partial result per split, a split for at most every tile
+    one = lib.sbnet_conv_backward_weights_workspace_bytes(sb.BF16, 1, 18, 18, 64, 3, 3, 1, 1, 64)
+    many = lib.sbnet_conv_backward_weights_workspace_bytes(sb.BF16, 5000, 18, 18, 64, 3, 3, 1, 1, 64)
+    assert one >= 9 * 64 * 64 * 4 and one < 2 * 9 * 64 * 64 * 4 and many >= 256 * 9 * 64 * 64 * 4
+    assert lib.sbnet_conv_backward_weights_workspace_bytes(sb.BF16, 4, 2, 2, 8, 3, 3, 1, 1, 8) == 0     # tile < kernel
+    assert lib.sbnet_conv_on_tiles_backward_weights(None, None, sb.BF16, None, 4, 6, 6, 8, 3, 3, 1, 1, 8, None, None, 0,
+                                                    None) == sb.EINVAL
+    # normalisation
+    assert lib.sbnet_bn_backward_workspace_bytes(10, 64) == (10 * 64 * 2 + 10 + 1) * 4
+    assert lib.sbnet_bn_backward_workspace_bytes(0, 64) == 4
+    assert lib.sbnet_sparse_bn_apply(None, sb.BF16, 1, 16, 16, 8, None, None, 4, g_out, None, None, None, None, 1e-5, 0,
+                                     None, None) == sb.EINVAL
+    assert lib.sbnet_sparse_bn_backward(None, None, sb.BF16, 1, 16, 16, 8, None, None, 4, g_out, None, None, None, None,
+                                        1e-5, 0, None, None, None, None, 0, None) == sb.EINVAL
+    # overlapping blocks (an input-tile geometry) would count pixels twice: refused with valid pointers too
+    buf = (ctypes.c_char * 4096)()
+    ptr = ctypes.cast(ctypes.byref(buf, 16 - ctypes.addressof(buf) % 16), ctypes.c_void_p)
+    assert lib.sbnet_sparse_bn_apply(ptr, sb.BF16, 1, 16, 16, 8, ptr, ptr, 4, g_in, ptr, ptr, None, None, 1e-5, 0, ptr,
+                                     None) == sb.EINVAL
+    assert b"overlap" in lib.sbnet_last_error()
+    assert lib.sbnet_sparse_bn_apply(ptr, sb.BF16, 1, 16, 16, 8, ptr, ptr, 4, g_out, ptr, ptr, None, None, -1.0, 0, ptr,
+                                     None) == sb.EINVAL
