@@ -102,9 +102,10 @@ def test_conv_on_tiles_backward_weights(B, th, tw, Cin, Cout, k, s, dtype):
             assert torch.equal(dw, dw2)                  # fixed summation order: the same bits again
 
 
-def test_sparse_conv_input_gradient_end_to_end():
-    """dL/dx of the whole sparse convolution from library calls only: gather of dL/dy with the output geometry,
-    data gradient on tiles, gather_backward into the image; against the oracle's composition of the same steps."""
+def test_sparse_conv_gradients_end_to_end():
+    """dL/dx and dL/dw of the whole sparse convolution from library calls only: gather of dL/dy with the output
+    geometry, data gradient on tiles, gather_backward into the image; gather of x, weight gradient on the two tile
+    stacks; against the oracle's composition of the same steps."""
     N, H, W, Cin, Cout, bo, dtype = 2, 70, 66, 64, 96, 16, "bf16"
     for s in (1, 2):
         step("sparse conv input gradient stride %d" % s)
@@ -130,6 +131,12 @@ def test_sparse_conv_input_gradient_end_to_end():
         ref_tiles_r = torch.from_numpy(ref_tiles).to(TORCH_DT[dtype]).to(torch.float64).numpy()
         ref = orc.gather_backward(ref_tiles_r, idx_np, og_in, np.zeros((N, H, W, Cin)))
         assert_close(to_host(dx), ref, CONV_TOL[dtype], "sparse conv dL/dx")
+        # dL/dw of the same layer: the forward input gathered with the input geometry against the gathered dL/dy
+        x = gen.activations(r, (N, H, W, Cin), dtype)
+        x_tiles = sb.sparse_gather(to_dev(x, dtype), idx, cnt, g_in)
+        dw = sb.conv_on_tiles_backward_weights(x_tiles, dy_tiles, cnt, 3, stride=s)
+        ref_dw = orc.conv_valid_backward_weights(orc.gather(x, idx_np, og_in), orc.gather(dy, idx_np, og_out), 3, 3, stride=s)
+        assert_close(to_host(dw), ref_dw, 2e-5, "sparse conv dL/dw")
 
 
 @pytest.mark.parametrize("n,th,Cin,Cout,s", [(2200, 18, 64, 64, 1), (220, 18, 64, 64, 1), (550, 33, 64, 96, 2)])
