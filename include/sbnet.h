@@ -282,9 +282,9 @@ sbnet_status sbnet_conv_on_tiles_backward_data(const void *dout_tiles, sbnet_dty
  * active.  tiles_in: [cap][th][tw][Cin], dout_tiles: [cap][oh][ow][Cout] in `dtype` (F32, BF16 or
  * F16), 16-byte aligned.  Products of BF16/F16 inputs are exact and summed in fp32; the tiles are
  * split over workgroups whose partial sums are added in a fixed order (no atomics: the same
- * inputs give the same bits).  3x3 kernels at stride 1 or 2 with channel counts that are multiples
- * of 8 and output tiles up to 32 columns run on the matrix cores, everything else in a plain
- * kernel.  workspace: device, 16-byte aligned,
+ * inputs give the same bits).  3x3 and 1x1 kernels at stride 1 or 2 with channel counts that are
+ * multiples of 8 (output tiles up to 32 columns; any tile for 1x1 at stride 1) run on the matrix
+ * cores, everything else in a plain kernel (correct, slow).  workspace: device, 16-byte aligned,
  * sbnet_conv_backward_weights_workspace_bytes(...) bytes (the partial sums); overwritten.
  */
 size_t sbnet_conv_backward_weights_workspace_bytes(sbnet_dtype dtype, int cap, int th, int tw,

@@ -5,8 +5,8 @@
 // workgroups, each of which keeps a partial dw in registers for all its tiles and writes it once; a second kernel adds
 // the partial results in a fixed order (no atomics: the result does not depend on scheduling).
 //
-// wgrad_mfma (3x3, stride 1 or 2, BF16/F16, channel counts multiples of 8): a workgroup owns 64 input by 64 output
-// channels, one 32x32 block per wave with nine fp32 accumulators (one per tap).  Tiles pass through LDS a few output
+// wgrad_mfma (3x3 or 1x1, stride 1 or 2, BF16/F16, channel counts multiples of 8): a workgroup owns 64 input by 64
+// output channels, one 32x32 block per wave with one fp32 accumulator per tap (nine, or one).  Tiles pass through LDS a few output
 // rows at a time (a "stage"), stored channel-major so that a lane's matrix operand (8 consecutive pixels of one
 // channel) is one aligned 16-byte read:
 //   * x rows are split by column phase (column % stride), so that the pixels a tap reads for consecutive output
@@ -40,10 +40,10 @@ struct WgradParams {
     uint32_t x_tile_bytes, g_tile_bytes;
 };
 
-template <int S, int NSEG>
+template <int KH, int S, int NSEG>
 struct WgradShape {
     static constexpr int R = 8 / (S * NSEG);              // output rows per stage
-    static constexpr int RX = (R - 1) * S + 3;            // input rows per stage
+    static constexpr int RX = (R - 1) * S + KH;           // input rows per stage
     static constexpr int CPV = 2 * NSEG + 1;              // 16-byte vectors per phase row of x (one spare for the window)
     static constexpr int XPL = (RX * S * CPV + 7) / 8 * 8;
     static constexpr int CSX = XPL + 1;                   // vectors between channel planes of x (odd)
@@ -89,9 +89,10 @@ __device__ __forceinline__ uint4 window2(uint4 v0, uint4 v1) { return make_uint4
 __device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
 __device__ __forceinline__ uint32_t pair_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
-template <int DT, int S, int NSEG>
+template <int DT, int KH, int S, int NSEG>
 __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
-    typedef WgradShape<S, NSEG> Sh;
+    typedef WgradShape<KH, S, NSEG> Sh;
+    constexpr int TAPS = KH * KH;
     constexpr int R = Sh::R, RX = Sh::RX, CPV = Sh::CPV, CSX = Sh::CSX, CSG = Sh::CSG, GV = Sh::GV;
     constexpr int NIX = Sh::NIX, NIG = Sh::NIG, NI = NIX + NIG, QX = Sh::QX, QG = Sh::QG;
     extern __shared__ __align__(16) char lds[];
@@ -145,10 +146,12 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
             const bool isx = u < NIX;
             const uint32_t tile = isx ? p.x_tile_bytes : p.g_tile_bytes;
             const uint32_t o = (uint32_t)h * (isx ? x_stage_step : g_stage_step) + rel[u];
-            const uint32_t base = o < tile ? (uint32_t)b * tile + o : kOutOfRange;   // rows beyond the tile: zeros
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint32_t off = (base != kOutOfRange && (uint32_t)j < cnt[u]) ? base + j * (isx ? x_px_step : g_px_step) : kOutOfRange;
+                // pixels beyond the row's end or beyond the tile (rows past its last one, or the rest of a last row
+                // that the tile does not fill): zeros; a slot that holds nothing has cnt = 0
+                const uint32_t oj = o + j * (isx ? x_px_step : g_px_step);
+                const uint32_t off = (oj < tile && (uint32_t)j < cnt[u]) ? (uint32_t)b * tile + oj : kOutOfRange;
                 staged[u][j] = buf_load16(isx ? xr : gr, off);
             }
         }
@@ -172,9 +175,9 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
     const int cl = (wave >> 1) * 32 + (lane & 31), ol = (wave & 1) * 32 + (lane & 31), m = lane >> 5;
     const uint32_t swa = (uint32_t)(cl >> 3), swb = (uint32_t)(ol >> 3);
     const char *xplane = lds + cl * CSX * 16, *gplane = lds + Sh::XBYTES + ol * CSG * 16;
-    f32x16 acc[9];
+    f32x16 acc[TAPS];
 #pragma unroll
-    for (int k = 0; k < 9; ++k)
+    for (int k = 0; k < TAPS; ++k)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[k][e] = 0.f;
 
@@ -182,7 +185,7 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
     // input rows): the operand of dout and, per kernel row, the vectors the three taps are cut from.  A step reads
     // only the input rows the step before did not have.
     constexpr int T = R * NSEG, XV = S == 1 ? 2 : 3;
-    struct Ops { uint4 b, x[3][XV]; };
+    struct Ops { uint4 b, x[KH][XV]; };
     auto load_row = [&](Ops &o, const char *xb, int i, int q, int r) {
         const uint32_t v = (uint32_t)((i * S + r) * S * CPV + 2 * q + m);          // phase 0 of the row
         o.x[r][0] = lds_read16(xb + (v ^ swa) * 16);
@@ -194,8 +197,8 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
         const int q = t / R, i = t - q * R;
         o.b = lds_read16(gb + (((uint32_t)(i * GV + 2 * q + m)) ^ swb) * 16);
 #pragma unroll
-        for (int r = 0; r < 3; ++r) {
-            if (i > 0 && r + S < 3) {
+        for (int r = 0; r < KH; ++r) {
+            if (i > 0 && r + S < KH) {
 #pragma unroll
                 for (int k = 0; k < XV; ++k) o.x[r][k] = prev.x[r + S][k];
             } else {
@@ -204,7 +207,7 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
         }
     };
     auto mfma1 = [&](const Ops &o, int j) {                       // tap j = 3 r + t of this step
-        const int r = j / 3, t = j - 3 * r;
+        const int r = j / KH, t = j - KH * r;
         uint4 a;
         if (S == 1) a = t == 0 ? o.x[r][0] : t == 1 ? window1(o.x[r][0], o.x[r][1]) : window2(o.x[r][0], o.x[r][1]);
         else a = t == 0 ? o.x[r][0] : t == 1 ? o.x[r][XV - 1] : window1(o.x[r][0], o.x[r][1]);
@@ -242,10 +245,10 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
             if (t + 1 < T) load_ops(nxt, now, cur, t + 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < 9; ++j) {
+            for (int j = 0; j < TAPS; ++j) {
                 mfma1(now, j);
-                constexpr int W = NI * 8, SLOTS = T * 9, FIRST = SLOTS / 2, LATE = SLOTS - FIRST;
-                const int slot = t * 9 + j - FIRST;
+                constexpr int W = NI * 8, SLOTS = T * TAPS, FIRST = SLOTS / 2, LATE = SLOTS - FIRST;
+                const int slot = t * TAPS + j - FIRST;
                 if (slot >= 0) {
 #pragma unroll
                     for (int w = (slot * W + LATE - 1) / LATE; w < ((slot + 1) * W + LATE - 1) / LATE; ++w) write_elem(w, other);
@@ -260,12 +263,12 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
     // 8 (e / 4) + 4 (lane / 32) + e % 4 of its wave's 32 x 32 block; written like that, every store instruction would
     // carry 4 bytes per lane.  Each block goes through a wave-private LDS tile (the stage buffers are free now: the loop
     // ends with a barrier) and leaves as 16-byte stores along the output channels.
-    float *out = p.part + (size_t)sigma * split_stride(9, p.CinP, p.CoutP);
+    float *out = p.part + (size_t)sigma * split_stride(TAPS, p.CinP, p.CoutP);
     constexpr int TS = 36;                                         // floats per tile row: 16-byte aligned rows, shifted banks
     float *tiles = (float *)lds + wave * (2 * 32 * TS);
     const int cblk = cb * 64 + (wave >> 1) * 32, oblk = ob * 64 + (wave & 1) * 32;
 #pragma unroll
-    for (int k = 0; k < 9; ++k) {
+    for (int k = 0; k < TAPS; ++k) {
         float *t = tiles + (k & 1) * (32 * TS);
 #pragma unroll
         for (int e = 0; e < 16; ++e) t[(8 * (e >> 2) + 4 * m + (e & 3)) * TS + (lane & 31)] = acc[k][e];
@@ -348,19 +351,22 @@ __global__ __launch_bounds__(256) void wgrad_sum(const float *__restrict__ part,
 
 struct WgradPlan {
     bool mfma;
-    int s, nseg, nsplit, ncb, nob, CinP, CoutP;
+    int kh, s, nseg, nsplit, ncb, nob, CinP, CoutP;
+    bool flat;               // 1x1 at stride 1: the tile as one run of pixels
     size_t part_bytes;
 };
 
 bool plan_wgrad(sbnet_dtype dt, int cap, int th, int tw, int Cin, int kh, int kw, int sh, int sw, int Cout, WgradPlan *q) {
     const int oh = (th - kh) / sh + 1, ow = (tw - kw) / sw + 1;
     const int taps = kh * kw;
-    q->mfma = (dt == SBNET_BF16 || dt == SBNET_F16) && kh == 3 && kw == 3 && sh == sw && (sh == 1 || sh == 2) && Cin % 8 == 0 &&
-              Cout % 8 == 0 && ow <= 32 && tw <= 32 * sw + 2 &&
+    q->flat = kh == 1 && kw == 1 && sh == 1 && sw == 1;
+    q->mfma = (dt == SBNET_BF16 || dt == SBNET_F16) && (kh == 3 || kh == 1) && kw == kh && sh == sw && (sh == 1 || sh == 2) && Cin % 8 == 0 &&
+              Cout % 8 == 0 && (q->flat || (ow <= 32 && tw <= 32 * sw + 2)) &&
               (long long)cap * th * tw * Cin * 2 < (1LL << 31) && (long long)cap * oh * ow * Cout * 2 < (1LL << 31);
+    q->kh = kh;
     if (q->mfma) {
         q->s = sh;
-        q->nseg = ow <= 16 && tw <= 16 * sw + 2 ? 1 : 2;
+        q->nseg = q->flat || (ow <= 16 && tw <= 16 * sw + 2) ? 1 : 2;
         q->ncb = (Cin + 63) / 64;
         q->nob = (Cout + 63) / 64;
         q->CinP = q->ncb * 64;
@@ -385,20 +391,27 @@ bool plan_wgrad(sbnet_dtype dt, int cap, int th, int tw, int Cin, int kh, int kw
     return true;
 }
 
-template <int DT, int S, int NSEG>
+template <int DT, int KH, int S, int NSEG>
 void launch_mfma(const WgradParams &p, hipStream_t s) {
-    constexpr int bytes = 2 * WgradShape<S, NSEG>::STAGE;
+    constexpr int bytes = 2 * WgradShape<KH, S, NSEG>::STAGE;
     static_assert(bytes <= 160 * 1024, "two stages must fit in LDS");
-    (void)hipFuncSetAttribute((const void *)wgrad_mfma<DT, S, NSEG>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    hipLaunchKernelGGL((wgrad_mfma<DT, S, NSEG>), dim3(p.nsplit * p.ncb * p.nob), dim3(256), bytes, s, p);
+    (void)hipFuncSetAttribute((const void *)wgrad_mfma<DT, KH, S, NSEG>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    hipLaunchKernelGGL((wgrad_mfma<DT, KH, S, NSEG>), dim3(p.nsplit * p.ncb * p.nob), dim3(256), bytes, s, p);
 }
 
 template <int DT>
 void launch_mfma_dt(const WgradPlan &q, const WgradParams &p, hipStream_t s) {
-    if (q.s == 1 && q.nseg == 1) launch_mfma<DT, 1, 1>(p, s);
-    else if (q.s == 1) launch_mfma<DT, 1, 2>(p, s);
-    else if (q.nseg == 1) launch_mfma<DT, 2, 1>(p, s);
-    else launch_mfma<DT, 2, 2>(p, s);
+    if (q.kh == 3) {
+        if (q.s == 1 && q.nseg == 1) launch_mfma<DT, 3, 1, 1>(p, s);
+        else if (q.s == 1) launch_mfma<DT, 3, 1, 2>(p, s);
+        else if (q.nseg == 1) launch_mfma<DT, 3, 2, 1>(p, s);
+        else launch_mfma<DT, 3, 2, 2>(p, s);
+    } else {
+        if (q.s == 1 && q.nseg == 1) launch_mfma<DT, 1, 1, 1>(p, s);
+        else if (q.s == 1) launch_mfma<DT, 1, 1, 2>(p, s);
+        else if (q.nseg == 1) launch_mfma<DT, 1, 2, 1>(p, s);
+        else launch_mfma<DT, 1, 2, 2>(p, s);
+    }
 }
 
 }  // namespace
@@ -436,6 +449,12 @@ extern "C" sbnet_status sbnet_conv_on_tiles_backward_weights(const void *tiles_i
     p.nsplit = q.nsplit; p.ncb = q.ncb; p.nob = q.nob; p.CinP = q.CinP; p.CoutP = q.CoutP;
     p.x_tile_bytes = (uint32_t)((size_t)th * tw * Cin * 2);
     p.g_tile_bytes = (uint32_t)((size_t)p.oh * p.ow * Cout * 2);
+    if (q.mfma && q.flat) {
+        // 1x1 at stride 1 pairs pixel with pixel, whatever the tile's shape: the matrix kernel sees rows of 16 pixels
+        // (the tile sizes in bytes stay the true ones, so the pixels past the end of the last row read as zeros)
+        p.th = p.oh = (th * tw + 15) / 16;
+        p.tw = p.ow = 16;
+    }
     if (cap > 0) {
         if (q.mfma) {
             if (dtype == SBNET_BF16) launch_mfma_dt<SBNET_BF16>(q, p, s);

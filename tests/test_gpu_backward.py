@@ -70,7 +70,13 @@ WGRAD_CASES = [
     (2, 21, 16, 8, 8, 3, 1, "bf16"),         # 19 output rows: the last stage is partly empty
     (3, 12, 20, 24, 16, 3, 1, "f32"),        # plain kernel
     (3, 11, 9, 6, 5, 3, 1, "bf16"),
-    (4, 16, 16, 64, 32, 1, 1, "bf16"),
+    (4, 16, 16, 64, 32, 1, 1, "bf16"),       # 1x1: one accumulator per wave
+    (40, 18, 18, 256, 64, 1, 1, "bf16"),     # first convolution of the residual unit on its input tile (two segments)
+    (5, 16, 16, 64, 256, 1, 1, "f16"),       # its last convolution
+    (3, 17, 17, 32, 48, 1, 2, "bf16"),       # 1x1 at stride 2: 9 x 9 outputs, odd phase never read
+    (4, 10, 10, 40, 24, 1, 1, "bf16"),
+    (6, 17, 17, 64, 64, 1, 1, "bf16"),       # 289 pixels: one pixel in the last row of 16
+    (9, 7, 5, 8, 16, 1, 1, "f16"),           # 35 pixels: not a whole item of four at the end
     (2, 9, 9, 3, 7, 5, 2, "f16"),
     (2, 13, 11, 16, 16, 3, 3, "bf16"),
 ]
