@@ -331,7 +331,7 @@ def run_stages(args):
             gt_tiles = torch.randn((max(n, 1), bo, bo, Cout), device=dev).to(torch.bfloat16)
             din_tiles = torch.empty_like(xt_tiles)
             dw = torch.empty((3, 3, Cin, Cout), dtype=torch.float32, device=dev)
-            ws_d = torch.empty((max(sb.conv_backward_data_workspace_bytes(torch.bfloat16, max(n, 1), th, th, 3, 3, Cout), 16),),
+            ws_d = torch.empty((max(sb.conv_backward_data_workspace_bytes(torch.bfloat16, max(n, 1), th, th, 3, 3, s, Cout), 16),),
                                dtype=torch.uint8, device=dev)
             ws_w = torch.empty((max(sb.conv_backward_weights_workspace_bytes(torch.bfloat16, max(n, 1), th, th, Cin, 3, s, Cout), 16),),
                                dtype=torch.uint8, device=dev)
@@ -393,7 +393,7 @@ def run_backward(args):
         y = torch.empty_like(g)
         din = torch.empty_like(x)
         dw = torch.empty((3, 3, C, K), dtype=torch.float32, device=dev)
-        ws_d = torch.empty((sb.conv_backward_data_workspace_bytes(torch.bfloat16, n, TH, TH, 3, 3, K),), dtype=torch.uint8, device=dev)
+        ws_d = torch.empty((sb.conv_backward_data_workspace_bytes(torch.bfloat16, n, TH, TH, 3, 3, 1, K),), dtype=torch.uint8, device=dev)
         ws_w = torch.empty((sb.conv_backward_weights_workspace_bytes(torch.bfloat16, n, TH, TH, C, 3, 1, K),), dtype=torch.uint8, device=dev)
         t_f = tk(lambda: sb.conv_on_tiles(x, cnt, wp, None, out=y))
         t_d = tk(lambda: sb.conv_on_tiles_backward_data(g, cnt, wp_t, TH, TH, out=din, workspace=ws_d))
@@ -403,6 +403,48 @@ def run_backward(args):
                      "backward_data_ms": round(t_d, 5),
                      "backward_data_tflops": round(flops * (TH * TH) / (BO * BO) / t_d / 1e9, 2),
                      "backward_weights_ms": round(t_w, 5), "backward_weights_tflops": round(flops / t_w / 1e9, 2)})
+    # the residual unit 256 -> 64 -> 64 -> 256 composed from single calls, activations kept: forward (three
+    # convolutions) and backward (three weight, three bias and three data gradients, two ReLU masks) on tile stacks
+    unit_rows = []
+    Cu, Cm = 256, 64
+    w1, b1, w2, b2, w3, b3 = gen.bottleneck_weights(r, Cu, Cm, "bf16")
+    tod = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(dev)
+    p1, p2, p3 = sb.pack_weights(tod(w1)), sb.pack_weights(tod(w2)), sb.pack_weights(tod(w3))
+    q1, q2, q3 = sb.pack_weights_transposed(tod(w1)), sb.pack_weights_transposed(tod(w2)), sb.pack_weights_transposed(tod(w3))
+    fb1, fb2, fb3 = (torch.from_numpy(b).to(dev) for b in (b1, b2, b3))
+    for n in (330, 2200):
+        xt = torch.from_numpy(gen.activations(r, (n, TH, TH, Cu), "bf16")).to(torch.bfloat16).to(dev)
+        d3 = torch.from_numpy(gen.activations(r, (n, BO, BO, Cu), "bf16")).to(torch.bfloat16).to(dev)
+        cnt = torch.tensor([n], dtype=torch.int32, device=dev)
+        t1 = torch.empty((n, TH, TH, Cm), dtype=torch.bfloat16, device=dev)
+        t2 = torch.empty((n, BO, BO, Cm), dtype=torch.bfloat16, device=dev)
+        t3 = torch.empty((n, BO, BO, Cu), dtype=torch.bfloat16, device=dev)
+        d2, d1, dxt = torch.empty_like(t2), torch.empty_like(t1), torch.empty_like(xt)
+        dw1 = torch.empty((1, 1, Cu, Cm), dtype=torch.float32, device=dev)
+        dw2 = torch.empty((3, 3, Cm, Cm), dtype=torch.float32, device=dev)
+        dw3 = torch.empty((1, 1, Cm, Cu), dtype=torch.float32, device=dev)
+        ws = torch.empty((64 << 20,), dtype=torch.uint8, device=dev)       # covers every workspace below
+
+        def fwd():
+            sb.conv_on_tiles(xt, cnt, p1, fb1, relu=True, out=t1)
+            sb.conv_on_tiles(t1, cnt, p2, fb2, relu=True, out=t2)
+            sb.conv_on_tiles(t2, cnt, p3, fb3, out=t3)
+
+        def bwd():
+            sb.conv_on_tiles_backward_weights(t2, d3, cnt, 1, out=dw3, workspace=ws)
+            sb.bias_backward_on_tiles(d3, cnt, workspace=ws)
+            sb.conv_on_tiles_backward_data(d3, cnt, q3, BO, BO, out=d2, workspace=ws)
+            sb.relu_backward_on_tiles(t2, d2, cnt, out=d2)
+            sb.conv_on_tiles_backward_weights(t1, d2, cnt, 3, out=dw2, workspace=ws)
+            sb.bias_backward_on_tiles(d2, cnt, workspace=ws)
+            sb.conv_on_tiles_backward_data(d2, cnt, q2, TH, TH, out=d1, workspace=ws)
+            sb.relu_backward_on_tiles(t1, d1, cnt, out=d1)
+            sb.conv_on_tiles_backward_weights(xt, d1, cnt, 1, out=dw1, workspace=ws)
+            sb.bias_backward_on_tiles(d1, cnt, workspace=ws)
+            sb.conv_on_tiles_backward_data(d1, cnt, q1, TH, TH, out=dxt, workspace=ws)
+        fwd()
+        unit_rows.append({"active_blocks": n, "unit_forward_composed_ms": round(tk(fwd), 5),
+                          "unit_backward_composed_ms": round(tk(bwd), 5)})
     head = rows[1]
     print(json.dumps({"metric": "conv_on_tiles_backward_ms_at_10pct_active_blocks",
                       "value": round(head["backward_data_ms"] + head["backward_weights_ms"], 5), "unit": "ms", "n_gpus": 1,
@@ -411,7 +453,7 @@ def run_backward(args):
                       "config": {"workload": "backward: data and weight gradients of cfg2's 3x3 tile convolution "
                                              "(18x18x64 -> 16x16x64 tiles, bf16), value = both at 220 tiles",
                                  "timing": "eager launches" if args.eager_kernel_timing else "HIP graph replays"},
-                      "rows": rows}))
+                      "rows": rows, "residual_unit_rows": unit_rows}))
 
 
 def main():
@@ -636,7 +678,7 @@ def main():
             bn_ws = torch.empty((sb.lib().sbnet_bn_stats_workspace_bytes(n, K),), dtype=torch.uint8, device=dev)
             t_bn = tk(lambda: sb.sparse_bn_stats(y, idx_small, cnt, g_out, bn_ws))
             # gradients of the tile convolution: with respect to its input tiles and to its weights
-            dgrad_ws = torch.empty((max(sb.conv_backward_data_workspace_bytes(torch.bfloat16, n, BO + 2, BO + 2, 3, 3, K), 16),),
+            dgrad_ws = torch.empty((max(sb.conv_backward_data_workspace_bytes(torch.bfloat16, n, BO + 2, BO + 2, 3, 3, 1, K), 16),),
                                    dtype=torch.uint8, device=dev)
             wgrad_ws = torch.empty((max(sb.conv_backward_weights_workspace_bytes(torch.bfloat16, n, BO + 2, BO + 2, C, 3, 1, K), 16),),
                                    dtype=torch.uint8, device=dev)

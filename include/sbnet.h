@@ -265,7 +265,7 @@ sbnet_status sbnet_pack_weights_transposed(const void *w_hwio, sbnet_dtype dtype
                                            int Cin, int Cout, void *w_packed, size_t *bytes,
                                            void *stream);
 size_t sbnet_conv_backward_data_workspace_bytes(sbnet_dtype dtype, int cap, int th, int tw, int kh,
-                                                int kw, int Cout);
+                                                int kw, int sh, int sw, int Cout);
 sbnet_status sbnet_conv_on_tiles_backward_data(const void *dout_tiles, sbnet_dtype dtype,
                                                const int32_t *count, int cap, int th, int tw,
                                                int Cin, const void *w_packed_t, int kh, int kw,
@@ -295,6 +295,27 @@ sbnet_status sbnet_conv_on_tiles_backward_weights(const void *tiles_in, const vo
                                                   int th, int tw, int Cin, int kh, int kw, int sh,
                                                   int sw, int Cout, float *dw, void *workspace,
                                                   size_t workspace_bytes, void *stream);
+
+/*
+ * The two element-wise pieces a backward pass through a chain of tile convolutions needs besides
+ * the convolutions' own gradients (the residual unit of Sec. 3.3 composed from single calls).
+ *
+ * sbnet_relu_backward_on_tiles: dout = dy where the forward activation y is > 0, else 0, on the tiles
+ * b < min(*count, cap) of stacks with tile_elems elements per tile (a whole number of 4-byte words);
+ * later tiles are not touched; dout may be dy.  Device pointers, 16-byte aligned.
+ *
+ * sbnet_bias_backward_on_tiles: db[c] = sum over those tiles and their `pixels` pixels of dy[b][pixel][c]
+ * (the gradient of the bias a convolution adds), device float32 [C], zeros when no tile is active.
+ * fp32 sums in a fixed order, no atomics.  C * element size a multiple of 4 bytes and at most 1 KiB.
+ * workspace: device, 4-byte aligned, sbnet_bias_backward_workspace_bytes(cap, C) bytes, overwritten.
+ */
+sbnet_status sbnet_relu_backward_on_tiles(const void *y_tiles, const void *dy_tiles, sbnet_dtype dtype,
+                                          const int32_t *count, int cap, size_t tile_elems,
+                                          void *dout_tiles, void *stream);
+size_t sbnet_bias_backward_workspace_bytes(int cap, int C);
+sbnet_status sbnet_bias_backward_on_tiles(const void *dy_tiles, sbnet_dtype dtype, const int32_t *count,
+                                          int cap, int pixels, int C, float *db, void *workspace,
+                                          size_t workspace_bytes, void *stream);
 
 /*
  * Set every tile position that lies outside the H x W image to zero, in place.  Needed when a

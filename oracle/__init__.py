@@ -317,6 +317,42 @@ def bottleneck_on_tiles(tiles, idx, g_in, H, W, w1, b1, w2, b2, w3, b3, pre=None
     return conv_valid(t2, w3, b3, relu=False)
 
 
+def relu_backward(y, dy):
+    """Gradient through y = ReLU(z): dy where y > 0."""
+    return np.where(np.asarray(y, dtype=np.float64) > 0.0, np.asarray(dy, dtype=np.float64), 0.0)
+
+
+def bias_backward(dy):
+    """Gradient of a bias added to every pixel of every tile: the sum of dy over tiles and pixels."""
+    return np.asarray(dy, dtype=np.float64).sum(axis=(0, 1, 2))
+
+
+def bottleneck_backward_on_tiles(tiles, idx, g_in, H, W, w1, b1, w2, b2, w3, b3, dt3, saved=None):
+    """Gradients of L through t3 = bottleneck_on_tiles(tiles, ...) (Sec. 3.3, the unit's residual branch), given
+    dt3 = dL/dt3: the chain rule through the three convolutions in reverse, each ReLU passing the gradient where
+    its output is positive.  The zeroing of t1 outside the image needs no step of its own: t1 is zero there, so
+    its ReLU mask already blocks the gradient.  saved = (t1, t2): activations kept from a forward pass, used in
+    place of recomputed ones (a forward pass that rounds them to a storage type decides the ReLU masks on the
+    rounded values).  Returns (dtiles, dw1, db1, dw2, db2, dw3, db3)."""
+    tiles = np.asarray(tiles, dtype=np.float64)
+    if saved is None:
+        t1 = zero_outside(conv_valid(tiles, w1, b1, relu=True), idx, g_in, H, W)
+        t2 = conv_valid(t1, w2, b2, relu=True)
+    else:
+        t1, t2 = (np.asarray(t, dtype=np.float64) for t in saved)
+    dt3 = np.asarray(dt3, dtype=np.float64)
+    dw3 = conv_valid_backward_weights(t2, dt3, 1, 1)
+    db3 = bias_backward(dt3)
+    dt2 = relu_backward(t2, conv_valid_backward_data(dt3, w3, t2.shape[1], t2.shape[2]))
+    dw2 = conv_valid_backward_weights(t1, dt2, 3, 3)
+    db2 = bias_backward(dt2)
+    dt1 = relu_backward(t1, conv_valid_backward_data(dt2, w2, t1.shape[1], t1.shape[2]))
+    dw1 = conv_valid_backward_weights(tiles, dt1, 1, 1)
+    db1 = bias_backward(dt1)
+    dtiles = conv_valid_backward_data(dt1, w1, tiles.shape[1], tiles.shape[2])
+    return dtiles, dw1, db1, dw2, db2, dw3, db3
+
+
 def sparse_bottleneck_tiled(x, idx, g_in, g_out, w1, b1, w2, b2, w3, b3, pre=None):
     """One sparse residual unit: one gather, three convolutions, one scatter-add onto x."""
     x = np.asarray(x, dtype=np.float64)

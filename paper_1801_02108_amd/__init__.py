@@ -57,9 +57,12 @@ _SIGNATURES = {
     "sbnet_bn_backward_workspace_bytes": (_sz, [_ci, _ci]),
     "sbnet_sparse_bn_backward": (_ci, [_vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp, _vp, _vp,
                                        ctypes.c_float, _ci, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "sbnet_relu_backward_on_tiles": (_ci, [_vp, _vp, _ci, _vp, _ci, _sz, _vp, _vp]),
+    "sbnet_bias_backward_workspace_bytes": (_sz, [_ci, _ci]),
+    "sbnet_bias_backward_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _vp, _vp, _sz, _vp]),
     "sbnet_pack_weights": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_pack_weights_transposed": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
-    "sbnet_conv_backward_data_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci, _ci]),
+    "sbnet_conv_backward_data_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci]),
     "sbnet_conv_on_tiles_backward_data": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _ci, _ci, _vp,
                                                 _vp, _sz, _vp]),
     "sbnet_conv_backward_weights_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci]),
@@ -294,6 +297,33 @@ def sparse_bn_backward(x, dy, indices, count, g, mean, var, gamma=None, beta=Non
     return dx, dgamma, dbeta
 
 
+def relu_backward_on_tiles(y_tiles, dy_tiles, count, out=None):
+    """dy where the forward activation y is positive, else 0, on the active tiles of two stacks of one shape."""
+    _dev(y_tiles, "y_tiles"), _dev(dy_tiles, "dy_tiles", y_tiles.dtype), _dev(count, "count", torch.int32)
+    assert y_tiles.shape == dy_tiles.shape
+    if out is None:
+        out = torch.empty_like(dy_tiles)
+    _dev(out, "out", y_tiles.dtype)
+    cap = y_tiles.shape[0]
+    _check(lib().sbnet_relu_backward_on_tiles(_ptr(y_tiles), _ptr(dy_tiles), _dt(y_tiles), _ptr(count), cap,
+                                              y_tiles[0].numel() if cap else 1, _ptr(out), _stream()))
+    return out
+
+
+def bias_backward_on_tiles(dy_tiles, count, workspace=None):
+    """Sum of dy [cap,h,w,C] over the active tiles and their pixels: float32 [C]."""
+    _dev(dy_tiles, "dy_tiles"), _dev(count, "count", torch.int32)
+    cap, h, w, C = dy_tiles.shape
+    need = lib().sbnet_bias_backward_workspace_bytes(cap, C)
+    if workspace is None:
+        workspace = torch.empty((max(need, 4),), dtype=torch.uint8, device=dy_tiles.device)
+    _dev(workspace, "workspace", torch.uint8)
+    db = torch.empty((C,), dtype=torch.float32, device=dy_tiles.device)
+    _check(lib().sbnet_bias_backward_on_tiles(_ptr(dy_tiles), _dt(dy_tiles), _ptr(count), cap, h * w, C, _ptr(db),
+                                              _ptr(workspace), workspace.numel(), _stream()))
+    return db
+
+
 class PackedWeights:
     """Device buffer in the library's private weight layout plus the shape it was packed for."""
 
@@ -342,8 +372,8 @@ def pack_weights_transposed(w_hwio):
     return PackedWeights(buf, (kh, kw, Cin, Cout), w_hwio.dtype)
 
 
-def conv_backward_data_workspace_bytes(dtype, cap, th, tw, kh, kw, Cout):
-    return int(lib().sbnet_conv_backward_data_workspace_bytes(_DTYPES[dtype], cap, th, tw, kh, kw, Cout))
+def conv_backward_data_workspace_bytes(dtype, cap, th, tw, kh, kw, stride, Cout):
+    return int(lib().sbnet_conv_backward_data_workspace_bytes(_DTYPES[dtype], cap, th, tw, kh, kw, stride, stride, Cout))
 
 
 def conv_on_tiles_backward_data(dout_tiles, count, w_packed_t, th, tw, stride=1, out=None, workspace=None):
@@ -357,7 +387,7 @@ def conv_on_tiles_backward_data(dout_tiles, count, w_packed_t, th, tw, stride=1,
     if out is None:
         out = torch.empty((cap, th, tw, Cin), dtype=dout_tiles.dtype, device=dout_tiles.device)
     _dev(out, "out", dout_tiles.dtype)
-    need = conv_backward_data_workspace_bytes(dout_tiles.dtype, cap, th, tw, kh, kw, Cout)
+    need = conv_backward_data_workspace_bytes(dout_tiles.dtype, cap, th, tw, kh, kw, stride, Cout)
     if workspace is None:
         workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dout_tiles.device)
     _dev(workspace, "workspace", torch.uint8)

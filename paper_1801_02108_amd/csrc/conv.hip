@@ -547,10 +547,11 @@ static size_t framed_elems(int cap, int th, int tw, int kh, int kw, int Cout) {
 }
 
 extern "C" size_t sbnet_conv_backward_data_workspace_bytes(sbnet_dtype dtype, int cap, int th, int tw, int kh, int kw,
-                                                           int Cout) {
-    if (!is_float_dtype(dtype) || cap < 0 || th <= 0 || tw <= 0 || kh <= 0 || kw <= 0 || Cout <= 0) return 0;
-    size_t bytes = framed_elems(cap, th, tw, kh, kw, Cout) * elem_bytes(dtype);
-    if (bytes < (size_t)cap * 12) bytes = (size_t)cap * 12;        // or one index triple per tile (stride 1)
+                                                           int sh, int sw, int Cout) {
+    if (!is_float_dtype(dtype) || cap < 0 || th <= 0 || tw <= 0 || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || Cout <= 0)
+        return 0;
+    // stride 1: one index triple per tile; otherwise the framed copy of the output gradient
+    const size_t bytes = (sh == 1 && sw == 1) ? (size_t)cap * 12 : framed_elems(cap, th, tw, kh, kw, Cout) * elem_bytes(dtype);
     return (bytes + 255) / 256 * 256;
 }
 
@@ -566,7 +567,7 @@ extern "C" sbnet_status sbnet_conv_on_tiles_backward_data(const void *dout_tiles
     if (st != SBNET_OK) return st;
     if (((uintptr_t)dout_tiles | (uintptr_t)din_tiles | (uintptr_t)w_packed_t | (uintptr_t)workspace) & 15)
         return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
-    if (workspace_bytes < sbnet_conv_backward_data_workspace_bytes(dtype, cap, th, tw, kh, kw, Cout))
+    if (workspace_bytes < sbnet_conv_backward_data_workspace_bytes(dtype, cap, th, tw, kh, kw, sh, sw, Cout))
         return fail(SBNET_EINVAL, "%s: workspace too small", who);
     if (cap == 0) return SBNET_OK;
     const int oh = (th - kh) / sh + 1, ow = (tw - kw) / sw + 1;

@@ -1,0 +1,186 @@
+// The two small pieces that the backward pass of a chain of tile convolutions needs besides the convolutions' own
+// gradients (training support for the residual unit of Sec. 3.3 of arXiv 1801.02108, composed from single calls):
+//
+//   tile_relu_backward   dout = dy where the forward activation y is positive, else 0, on the tiles
+//                        b < min(*count, cap); tiles beyond the count are not touched.
+//   tile_bias_partial +  db[c] = sum over those tiles and their pixels of dy[b][pixel][c]: one workgroup per tile
+//   tile_bias_sum        sums its pixels per channel in fp32 (threads strided over pixels, LDS tree), one workgroup
+//                        per channel block then adds the tiles' sums in list order per thread and a fixed tree: no
+//                        atomics, the same bits every run.
+#include "common.h"
+
+namespace sbnet {
+namespace {
+
+template <int DT>
+__device__ __forceinline__ float elem_to_float(uint32_t bits16or32) {
+    if (DT == SBNET_F32) return __uint_as_float(bits16or32);
+    if (DT == SBNET_BF16) return bf16_bits_to_float(bits16or32 & 0xffffu);
+    union { _Float16 h[2]; uint32_t u; } v;
+    v.u = bits16or32;
+    return (float)v.h[0];
+}
+
+// words of 4 bytes: one f32 element or two 16-bit elements
+template <int DT>
+__device__ __forceinline__ uint32_t relu_mask_word(uint32_t y, uint32_t dy) {
+    if (DT == SBNET_F32) return elem_to_float<DT>(y) > 0.f ? dy : 0u;
+    const uint32_t lo = elem_to_float<DT>(y & 0xffffu) > 0.f ? 0xffffu : 0u;
+    const uint32_t hi = elem_to_float<DT>(y >> 16) > 0.f ? 0xffff0000u : 0u;
+    return dy & (lo | hi);
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void tile_relu_backward(const uint32_t *__restrict__ y, const uint32_t *dy, uint32_t *dout,
+                                                          const int32_t *__restrict__ count, int cap, size_t words_per_tile) {
+    int n = *count;
+    if (n > cap) n = cap;
+    const size_t total = (size_t)(n > 0 ? n : 0) * words_per_tile;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    // four words per thread and step where the stack allows 16-byte accesses, single words for the tail
+    const size_t vec_end = total & ~(size_t)3;
+    for (; i < vec_end; i += stride * 4) {
+        const uint4 a = *(const uint4 *)(y + i), g = *(const uint4 *)(dy + i);
+        *(uint4 *)(dout + i) = make_uint4(relu_mask_word<DT>(a.x, g.x), relu_mask_word<DT>(a.y, g.y),
+                                          relu_mask_word<DT>(a.z, g.z), relu_mask_word<DT>(a.w, g.w));
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(total - vec_end))
+        dout[vec_end + threadIdx.x] = relu_mask_word<DT>(y[vec_end + threadIdx.x], dy[vec_end + threadIdx.x]);
+}
+
+// part[b][c] = sum over the pixels of tile b.  Thread t owns word t % cw of a pixel (cw = 4-byte words per pixel: one
+// f32 channel or two 16-bit ones; cw <= 256) and pixels t / cw, t / cw + 256 / cw, ...
+template <int DT>
+__global__ __launch_bounds__(256) void tile_bias_partial(const uint32_t *__restrict__ dy, const int32_t *__restrict__ count,
+                                                         int cap, int pixels, int C, int cw, float *__restrict__ part) {
+    constexpr int EPW = DT == SBNET_F32 ? 1 : 2;
+    __shared__ float red[256][2];
+    int n = *count;
+    if (n > cap) n = cap;
+    const int groups = 256 / cw;                                  // pixel groups that fit the workgroup
+    const int w = threadIdx.x % cw, pg = threadIdx.x / cw;
+    for (int b = blockIdx.x; b < n; b += gridDim.x) {
+        float s0 = 0.f, s1 = 0.f;
+        if (pg < groups) {
+            const uint32_t *src = dy + ((size_t)b * pixels) * cw + w;
+            for (int px = pg; px < pixels; px += groups) {
+                const uint32_t v = src[(size_t)px * cw];
+                if (DT == SBNET_F32) {
+                    s0 += __uint_as_float(v);
+                } else {
+                    s0 += elem_to_float<DT>(v & 0xffffu);
+                    s1 += elem_to_float<DT>(v >> 16);
+                }
+            }
+        }
+        red[threadIdx.x][0] = s0;
+        red[threadIdx.x][1] = s1;
+        __syncthreads();
+        if (threadIdx.x < (unsigned)cw) {                         // groups in ascending order
+            float a0 = 0.f, a1 = 0.f;
+            for (int k = 0; k < groups; ++k) {
+                a0 += red[k * cw + threadIdx.x][0];
+                a1 += red[k * cw + threadIdx.x][1];
+            }
+            const int c = threadIdx.x * EPW;
+            if (c < C) part[(size_t)b * C + c] = a0;
+            if (EPW == 2 && c + 1 < C) part[(size_t)b * C + c + 1] = a1;
+        }
+        __syncthreads();
+    }
+}
+
+// db[c] = sum over tiles of part[b][c]: 64 channels per workgroup, the four waves take every fourth tile in ascending
+// order, then the four sums are added in ascending order of the wave
+__global__ __launch_bounds__(256) void tile_bias_sum(const float *__restrict__ part, const int32_t *__restrict__ count, int cap,
+                                                     int C, float *__restrict__ db) {
+    __shared__ float slice[4][64];
+    const int lane = threadIdx.x & 63, k = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;
+    int n = *count;
+    if (n > cap) n = cap;
+    float acc = 0.f;
+    if (c < C) {
+        for (int b = k; b < n; b += 32) {
+            float a[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int bj = b + 4 * j;
+                const float v = part[(size_t)(bj < n ? bj : 0) * C + c];
+                a[j] = bj < n ? v : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc += a[j];
+        }
+    }
+    slice[k][lane] = acc;
+    __syncthreads();
+    if (k == 0 && c < C) db[c] = ((slice[0][lane] + slice[1][lane]) + slice[2][lane]) + slice[3][lane];
+}
+
+}  // namespace
+}  // namespace sbnet
+
+using namespace sbnet;
+
+extern "C" sbnet_status sbnet_relu_backward_on_tiles(const void *y_tiles, const void *dy_tiles, sbnet_dtype dtype,
+                                                     const int32_t *count, int cap, size_t tile_elems, void *dout_tiles,
+                                                     void *stream) {
+    const char *who = "sbnet_relu_backward_on_tiles";
+    if (!y_tiles || !dy_tiles || !dout_tiles || !count) return fail(SBNET_EINVAL, "%s: null pointer", who);
+    if (!is_float_dtype(dtype)) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be f32, bf16 or f16", who);
+    if (cap < 0 || tile_elems == 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
+    if (((uintptr_t)y_tiles | (uintptr_t)dy_tiles | (uintptr_t)dout_tiles) & 15)
+        return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    const size_t tile_bytes = tile_elems * elem_bytes(dtype);
+    if (tile_bytes % 4) return fail(SBNET_EUNSUPPORTED, "%s: a tile must be a whole number of 4-byte words", who);
+    if (cap == 0) return SBNET_OK;
+    const size_t words = tile_bytes / 4;
+    const size_t total = (size_t)cap * words;
+    const size_t want = (total / 4 + 255) / 256;
+    const int grid = (int)(want < 1 ? 1 : want > 2048 ? 2048 : want);
+    hipStream_t s = (hipStream_t)stream;
+#define SBNET_RB(DT) hipLaunchKernelGGL(tile_relu_backward<DT>, dim3(grid), dim3(256), 0, s, (const uint32_t *)y_tiles, \
+                                        (const uint32_t *)dy_tiles, (uint32_t *)dout_tiles, count, cap, words)
+    if (dtype == SBNET_F32) SBNET_RB(SBNET_F32);
+    else if (dtype == SBNET_BF16) SBNET_RB(SBNET_BF16);
+    else SBNET_RB(SBNET_F16);
+#undef SBNET_RB
+    return launch_status(who);
+}
+
+extern "C" size_t sbnet_bias_backward_workspace_bytes(int cap, int C) {
+    if (cap < 0 || C <= 0) return 0;
+    return ((size_t)(cap > 0 ? cap : 1) * C) * sizeof(float);
+}
+
+extern "C" sbnet_status sbnet_bias_backward_on_tiles(const void *dy_tiles, sbnet_dtype dtype, const int32_t *count, int cap,
+                                                     int pixels, int C, float *db, void *workspace, size_t workspace_bytes,
+                                                     void *stream) {
+    const char *who = "sbnet_bias_backward_on_tiles";
+    if (!dy_tiles || !count || !db || !workspace) return fail(SBNET_EINVAL, "%s: null pointer", who);
+    if (!is_float_dtype(dtype)) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be f32, bf16 or f16", who);
+    if (cap < 0 || pixels <= 0 || C <= 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
+    const int es = elem_bytes(dtype);
+    if ((long long)C * es % 4) return fail(SBNET_EUNSUPPORTED, "%s: a pixel's channels must fill 4-byte words", who);
+    const int cw = C * es / 4;
+    if (cw > 256) return fail(SBNET_EUNSUPPORTED, "%s: more than 256 words of channels per pixel", who);
+    if (((uintptr_t)dy_tiles & 3) || ((uintptr_t)workspace & 3)) return fail(SBNET_EINVAL, "%s: pointers must be 4-byte aligned", who);
+    if (workspace_bytes < sbnet_bias_backward_workspace_bytes(cap, C)) return fail(SBNET_EINVAL, "%s: workspace too small", who);
+    hipStream_t s = (hipStream_t)stream;
+    float *part = (float *)workspace;
+    if (cap > 0) {
+        const int grid = cap < 4096 ? cap : 4096;
+#define SBNET_BP(DT) hipLaunchKernelGGL(tile_bias_partial<DT>, dim3(grid), dim3(256), 0, s, (const uint32_t *)dy_tiles, count, \
+                                        cap, pixels, C, cw, part)
+        if (dtype == SBNET_F32) SBNET_BP(SBNET_F32);
+        else if (dtype == SBNET_BF16) SBNET_BP(SBNET_BF16);
+        else SBNET_BP(SBNET_F16);
+#undef SBNET_BP
+        sbnet_status st = launch_status(who);
+        if (st != SBNET_OK) return st;
+    }
+    hipLaunchKernelGGL(tile_bias_sum, dim3((C + 63) / 64), dim3(256), 0, s, part, count, cap, C, db);
+    return launch_status(who);
+}

@@ -71,10 +71,10 @@ def test_gradient_and_normalisation_calls_check_their_arguments_on_the_host():
     lib = sb.lib()
     _, g_out, _, _ = sb.geometry(16, 16, 3, 1, 4)
     g_in = sb.geometry(16, 16, 3, 1, 4)[0]
-    # data gradient: the framed copy at stride 2, never less than one index triple per tile
-    assert lib.sbnet_conv_backward_data_workspace_bytes(sb.BF16, 10, 33, 33, 3, 3, 96) >= 10 * 35 * 35 * 96 * 2
-    assert lib.sbnet_conv_backward_data_workspace_bytes(sb.F16, 7, 1, 1, 1, 1, 1) >= 7 * 12
-    assert lib.sbnet_conv_backward_data_workspace_bytes(sb.U8, 7, 6, 6, 3, 3, 8) == 0
+    # data gradient: the framed copy at stride 2, one index triple per tile at stride 1
+    assert lib.sbnet_conv_backward_data_workspace_bytes(sb.BF16, 10, 33, 33, 3, 3, 2, 2, 96) >= 10 * 35 * 35 * 96 * 2
+    assert 2200 * 12 <= lib.sbnet_conv_backward_data_workspace_bytes(sb.BF16, 2200, 18, 18, 3, 3, 1, 1, 64) < 2200 * 12 + 256
+    assert lib.sbnet_conv_backward_data_workspace_bytes(sb.U8, 7, 6, 6, 3, 3, 1, 1, 8) == 0
     nbytes = ctypes.c_size_t()
     assert lib.sbnet_pack_weights_transposed(None, sb.BF16, 3, 3, 64, 96, None, nbytes, None) == sb.OK
     fwd = ctypes.c_size_t()

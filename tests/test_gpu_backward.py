@@ -175,3 +175,86 @@ def test_gradients_at_full_size_sampled(n, th, Cin, Cout, s):
     scale = np.sqrt(n * oh * oh)
     assert np.abs(have - want).max() <= 2e-5 * scale + 2e-5 * np.abs(want).max()
     assert np.isfinite(got).all() and 0.3 < np.sqrt((got ** 2).mean()) / scale < 3.0
+
+
+RELU_BIAS_CASES = [(7, 18, 18, 64, "bf16"), (3, 5, 7, 6, "f32"), (4, 3, 3, 10, "f16"), (2, 1, 3, 2, "bf16"), (5, 16, 16, 256, "bf16")]
+
+
+@pytest.mark.parametrize("B,h,w,C,dtype", RELU_BIAS_CASES)
+def test_relu_and_bias_backward_on_tiles(B, h, w, C, dtype):
+    step("relu / bias backward %s" % ((B, h, w, C, dtype),))
+    r = gen.rng_for(25, B * 100 + h * w + C)
+    y = gen.activations(r, (B + 1, h, w, C), dtype)
+    y[r.random(y.shape) < 0.3] = 0.0
+    y = np.abs(y) * (r.random(y.shape) < 0.7)                       # a ReLU output: zeros and positive values
+    y = gen.round_to(y.astype(np.float32), dtype)
+    dy = gen.activations(r, (B + 1, h, w, C), dtype)
+    cnt = torch.tensor([B], dtype=torch.int32).cuda()
+    out = torch.full((B + 1, h, w, C), 3.0, dtype=TORCH_DT[dtype]).cuda()
+    sb.relu_backward_on_tiles(to_dev(y, dtype), to_dev(dy, dtype), cnt, out=out)
+    got = to_host(out)
+    assert np.array_equal(got[:B], orc.relu_backward(y[:B], dy[:B])) and (got[B] == 3.0).all()
+    inplace = to_dev(dy, dtype)
+    sb.relu_backward_on_tiles(to_dev(y, dtype), inplace, cnt, out=inplace)
+    assert torch.equal(inplace[:B], out[:B])
+    db = sb.bias_backward_on_tiles(to_dev(dy, dtype), cnt)
+    ref = orc.bias_backward(dy[:B])
+    assert np.abs(db.cpu().numpy() - ref).max() <= 1e-5 * np.sqrt(B * h * w) + 1e-6
+    db2 = sb.bias_backward_on_tiles(to_dev(dy, dtype), cnt)
+    assert torch.equal(db, db2)
+    assert (sb.bias_backward_on_tiles(to_dev(dy, dtype), torch.tensor([0], dtype=torch.int32).cuda()) == 0).all()
+
+
+@pytest.mark.parametrize("C,dens", [(64, 0.02), (256, 0.004)])
+def test_residual_unit_backward_composed_from_single_calls(C, dens):
+    """The residual branch of a unit (Sec. 3.3) forward with its activations kept, then every gradient from library
+    calls alone: weight, bias and data gradients of the three convolutions, the two ReLU masks, and the gather's
+    gradient into the image.  The oracle's chain rule runs on the same kept activations (the ReLU masks are
+    decisions, taken on the stored bf16 values by both sides)."""
+    step("residual unit backward C=%d" % C)
+    dtype, Cm, bo, N, H, W = "bf16", 64, 16, 1, 70, 66
+    r = gen.rng_for(26, C)
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    og_in = orc.Geom(*g_in.astuple())
+    mask = (r.random((N, H, W)) < dens).astype(np.float64)
+    mask[0, 0, 0] = mask[0, H - 1, W - 1] = 1.0                      # corner tiles: t1 is zeroed outside the image
+    idx_np = orc.reduce_mask(mask, og_in)
+    n = len(idx_np)
+    buf = np.zeros((n + 1, 3), dtype=np.int32)
+    buf[:n] = idx_np
+    idx, cnt = torch.from_numpy(buf).cuda(), torch.tensor([n], dtype=torch.int32).cuda()
+    x = gen.activations(r, (N, H, W, C), dtype)
+    w1, b1, w2, b2, w3, b3 = gen.bottleneck_weights(r, C, Cm, dtype)
+    dt3 = gen.activations(r, (n + 1, bo, bo, C), dtype)
+    dev = lambda a: to_dev(a, dtype)
+    fb = lambda b: torch.from_numpy(b).cuda()
+    # forward, activations kept
+    tiles = sb.sparse_gather(dev(x), idx, cnt, g_in)
+    t1 = sb.conv_on_tiles(tiles, cnt, sb.pack_weights(dev(w1)), fb(b1), relu=True)
+    sb.zero_outside(t1, idx, cnt, g_in, H, W)
+    t2 = sb.conv_on_tiles(t1, cnt, sb.pack_weights(dev(w2)), fb(b2), relu=True)
+    # backward
+    d3 = dev(dt3)
+    th = g_in.bsize_h
+    dw3 = sb.conv_on_tiles_backward_weights(t2, d3, cnt, 1)
+    db3 = sb.bias_backward_on_tiles(d3, cnt)
+    d2 = sb.relu_backward_on_tiles(t2, sb.conv_on_tiles_backward_data(d3, cnt, sb.pack_weights_transposed(dev(w3)), bo, bo), cnt)
+    dw2 = sb.conv_on_tiles_backward_weights(t1, d2, cnt, 3)
+    db2 = sb.bias_backward_on_tiles(d2, cnt)
+    d1 = sb.relu_backward_on_tiles(t1, sb.conv_on_tiles_backward_data(d2, cnt, sb.pack_weights_transposed(dev(w2)), th, th), cnt)
+    dw1 = sb.conv_on_tiles_backward_weights(tiles, d1, cnt, 1)
+    db1 = sb.bias_backward_on_tiles(d1, cnt)
+    dtiles = sb.conv_on_tiles_backward_data(d1, cnt, sb.pack_weights_transposed(dev(w1)), th, th)
+    dx = torch.zeros((N, H, W, C), dtype=TORCH_DT[dtype]).cuda()
+    sb.sparse_gather_backward(dtiles, idx, cnt, g_in, dx)
+    # oracle on the kept activations
+    ref = orc.bottleneck_backward_on_tiles(orc.gather(x, idx_np, og_in), idx_np, og_in, H, W, w1, b1, w2, b2, w3, b3, dt3[:n],
+                                           saved=(to_host(t1)[:n], to_host(t2)[:n]))
+    tol = 3e-2                                                       # a chain of up to three bf16 roundings of the gradient
+    assert_close(to_host(dtiles)[:n], ref[0], tol, "d tiles")
+    for name, got, want in (("dw1", dw1, ref[1]), ("dw2", dw2, ref[3]), ("dw3", dw3, ref[5])):
+        assert_close(to_host(got), want, tol, name)
+    for name, got, want in (("db1", db1, ref[2]), ("db2", db2, ref[4]), ("db3", db3, ref[6])):
+        assert_close(to_host(got), want, tol, name)
+    ref_tiles_r = torch.from_numpy(ref[0]).to(TORCH_DT[dtype]).to(torch.float64).numpy()
+    assert_close(to_host(dx), orc.gather_backward(ref_tiles_r, idx_np, og_in, np.zeros((N, H, W, C))), tol, "dx")

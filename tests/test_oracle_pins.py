@@ -260,6 +260,46 @@ def test_gather_backward_is_the_adjoint_of_gather(H, W, C, k, s, bo):
     assert np.array_equal(ones, np.repeat(cover[..., None], C, axis=3))
 
 
+def test_bottleneck_backward_by_finite_differences():
+    """Every gradient of the residual branch against central differences of L = sum(coef * bottleneck_on_tiles(...)),
+    the forward oracle, which shares nothing with the backward composition but the two convolution gradients
+    pinned above; a tile at the image corner is among the tiles, so the zeroing of t1 outside the image is on the
+    path.  Inputs are kept away from the ReLU kinks by construction of the check (a difference across a kink would
+    not match, and none does at this step size)."""
+    H, W, C, Cm, bo = 9, 8, 3, 2, 4
+    g_in, g_out, _, _ = orc.geometry(H, W, 3, 1, bo)
+    idx = np.array([(0, 0, 0), (0, 1, 1), (0, 2, 1)], dtype=np.int32)
+    x = rng0.standard_normal((1, H, W, C))
+    tiles = orc.gather(x, idx, g_in)
+    w1, b1 = rng0.standard_normal((1, 1, C, Cm)), rng0.standard_normal(Cm) * 0.5 + 0.3
+    w2, b2 = rng0.standard_normal((3, 3, Cm, Cm)) * 0.5, rng0.standard_normal(Cm) * 0.5
+    w3, b3 = rng0.standard_normal((1, 1, Cm, C)), rng0.standard_normal(C)
+    coef = rng0.standard_normal((len(idx), bo, bo, C))
+
+    def loss(t=tiles, a1=w1, c1=b1, a2=w2, c2=b2, a3=w3, c3=b3):
+        return float((coef * orc.bottleneck_on_tiles(t, idx, g_in, H, W, a1, c1, a2, c2, a3, c3)).sum())
+    grads = orc.bottleneck_backward_on_tiles(tiles, idx, g_in, H, W, w1, b1, w2, b2, w3, b3, coef)
+    names = ["t", "a1", "c1", "a2", "c2", "a3", "c3"]
+    args = [tiles, w1, b1, w2, b2, w3, b3]
+    h = 1e-6
+    checked = 0
+    for name, arg, grad in zip(names, args, grads):
+        assert grad.shape == arg.shape
+        flat = list(np.ndindex(*arg.shape))
+        for k in rng0.choice(len(flat), min(len(flat), 12), replace=False):
+            e = np.zeros_like(arg)
+            e[flat[k]] = h
+            fd = (loss(**{name: arg + e}) - loss(**{name: arg - e})) / (2 * h)
+            assert abs(grad[flat[k]] - fd) < 1e-6 * max(1.0, abs(fd)), (name, flat[k], grad[flat[k]], fd)
+            checked += 1
+    assert checked > 40
+    # the corner tile's t1 is zeroed outside the image: the input gradient vanishes there
+    dt = grads[0]
+    assert np.all(dt[0, 0, :, :] == 0) and np.all(dt[0, :, 0, :] == 0) and np.any(dt[0, 1:, 1:, :] != 0)
+    assert np.allclose(orc.relu_backward([-1.0, 0.0, 2.0], [5.0, 6.0, 7.0]), [0.0, 0.0, 7.0])
+    assert np.allclose(orc.bias_backward(np.ones((2, 3, 4, 5))), 24.0)
+
+
 def test_bn_apply_and_backward():
     """All blocks active and no activation: the library's batch_norm in training mode and its autograd gradients
     (fp64).  Some blocks active, with and without ReLU: the forward value by brute force over pixels; the three
