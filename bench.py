@@ -652,6 +652,7 @@ def main():
         sweep = []
         dense_ms = None
         wp_t = sb.pack_weights_transposed(torch.from_numpy(w_np).to(torch.bfloat16).to(dev))
+        wp_f8 = sb.pack_weights_f8(sb.quantize_f8(torch.from_numpy(w_np).to(torch.bfloat16).to(dev), 64.0))
         for target in (0.05, 0.10, 0.20, 0.40, 1.0):
             m_np, fr = mask_for(target)
             m_d = torch.from_numpy(m_np).to(dev)
@@ -665,6 +666,10 @@ def main():
             t_gather = tk(lambda: sb.sparse_gather(x, idx_small, cnt, g_in, tiles_buf[0]))
             t_tconv = tk(lambda: sb.conv_on_tiles(tiles_buf[0], cnt, wp, bias, out=tiles_buf[1]))
             t_scatter = tk(lambda: sb.sparse_scatter(tiles_buf[1], idx_small, cnt, g_out, y))
+            # the same tile convolution with FP8 (E4M3) tiles and weights, BF16 results
+            tiles_f8 = sb.quantize_f8(tiles_buf[0], 16.0)
+            t_quant = tk(lambda: sb.quantize_f8(tiles_buf[0], 16.0, out=tiles_f8))
+            t_f8 = tk(lambda: sb.conv_on_tiles_f8(tiles_f8, cnt, wp_f8, bias, out_scale=1.0 / (16.0 * 64.0), out=tiles_buf[1]))
             # the same copies with the transpose to channel-major tiles fused in (Sec. 3.4)
             chw_in = torch.empty((n, C, BO + 2, BO + 2), dtype=torch.bfloat16, device=dev)
             chw_out = torch.empty((n, K, BO, BO), dtype=torch.bfloat16, device=dev)
@@ -705,6 +710,8 @@ def main():
                    "fused_conv_tflops": round(TILE_FLOPS * n / t_conv / 1e9, 2),
                    "gather_ms": round(t_gather, 5), "gather_GBps": round(2 * tile_in_b * n / t_gather / 1e6, 1),
                    "conv_on_tiles_ms": round(t_tconv, 5), "conv_on_tiles_tflops": round(TILE_FLOPS * n / t_tconv / 1e9, 2),
+                   "quantize_f8_ms": round(t_quant, 5), "conv_on_tiles_f8_ms": round(t_f8, 5),
+                   "conv_on_tiles_f8_tflops": round(TILE_FLOPS * n / t_f8 / 1e9, 2),
                    "scatter_ms": round(t_scatter, 5), "scatter_GBps": round(2 * tile_out_b * n / t_scatter / 1e6, 1),
                    "gather_chw_ms": round(t_gather_chw, 5), "gather_chw_GBps": round(2 * tile_in_b * n / t_gather_chw / 1e6, 1),
                    "scatter_chw_ms": round(t_scatter_chw, 5), "scatter_chw_GBps": round(2 * tile_out_b * n / t_scatter_chw / 1e6, 1),

@@ -318,6 +318,33 @@ sbnet_status sbnet_bias_backward_on_tiles(const void *dy_tiles, sbnet_dtype dtyp
                                           size_t workspace_bytes, void *stream);
 
 /*
+ * FP8 variant of the tile convolution (the paper fixes no precision for the convolution between
+ * gather and scatter, Sec. 3.2).  Storage is FP8 E4M3 in the OCP "e4m3fn" encoding (sign, 4 exponent
+ * bits with bias 7, 3 mantissa bits; no infinities; 0x7f / 0xff are NaN; largest finite value 448).
+ *
+ * sbnet_quantize_f8: out[i] = e4m3(clamp(x[i] * scale, -448, 448)), round to nearest even (the product
+ * in fp32), for `elems` elements of any F32 / BF16 / F16 device buffer; out: device bytes.
+ *
+ * sbnet_pack_weights_f8: w_hwio_f8 [kh][kw][Cin][Cout] bytes -> the private operand order; size query
+ * as sbnet_pack_weights.
+ *
+ * sbnet_conv_on_tiles_f8: tiles_out[b] = act(out_scale * (valid convolution of tiles_in[b] with w) +
+ * bias) for b < min(*count, cap): products of the decoded FP8 values are exact, summed in fp32 on the
+ * matrix cores; out_scale (finite) undoes the scales inputs and weights were quantised with; the
+ * result is rounded once to BF16.  tiles_in: [cap][th][tw][Cin] bytes; tiles_out:
+ * [cap][oh][ow][Cout] BF16; bias: float32 [Cout] or NULL.  Cin % 16 == 0, Cout % 8 == 0, else
+ * SBNET_EUNSUPPORTED.  Device pointers, 16-byte aligned.
+ */
+sbnet_status sbnet_quantize_f8(const void *x, sbnet_dtype dtype, size_t elems, float scale, void *out,
+                               void *stream);
+sbnet_status sbnet_pack_weights_f8(const void *w_hwio_f8, int kh, int kw, int Cin, int Cout,
+                                   void *w_packed, size_t *bytes, void *stream);
+sbnet_status sbnet_conv_on_tiles_f8(const void *tiles_in_f8, const int32_t *count, int cap, int th,
+                                    int tw, int Cin, const void *w_packed_f8, const float *bias,
+                                    int kh, int kw, int sh, int sw, int Cout, int relu,
+                                    float out_scale, void *tiles_out_bf16, void *stream);
+
+/*
  * Set every tile position that lies outside the H x W image to zero, in place.  Needed when a
  * residual unit is composed from single sbnet_conv_on_tiles calls: after the first convolution
  * the halo positions beyond the image border hold act(bias), but the next convolution's zero

@@ -280,6 +280,46 @@ def bn_backward(x, dy, idx, g_out, gamma, beta, eps, dx, relu=False):
 
 
 # ---------------------------------------------------------------------------------------
+# FP8 E4M3 (OCP "e4m3fn": bias 7, no infinities, NaN = S.1111.111, largest finite 448)
+# ---------------------------------------------------------------------------------------
+def e4m3_decode(codes):
+    """Values of FP8 E4M3 codes (uint8 array): (-1)^s 2^(e-7) (1 + m/8) for e > 0, (-1)^s 2^-6 (m/8) for e = 0."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    s, e, m = c >> 7, (c >> 3) & 15, c & 7
+    mag = np.where(e > 0, np.ldexp(1.0 + m / 8.0, e - 7), np.ldexp(m / 8.0, -6))
+    mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    return np.where(s == 1, -mag, mag)
+
+
+def e4m3_encode(x):
+    """Nearest FP8 E4M3 code of each element (ties to the even mantissa), magnitudes above 448 clamped to 448: a
+    search over the 127 non-negative finite values, which are what e4m3_decode says they are."""
+    x = np.asarray(x, dtype=np.float64)
+    grid = e4m3_decode(np.arange(127, dtype=np.uint8))           # codes 0x00..0x7e: ascending magnitudes
+    a = np.minimum(np.abs(x), 448.0)
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 0, 126)
+    lo = np.clip(hi - 1, 0, 126)
+    dlo, dhi = a - grid[lo], grid[hi] - a
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    code = np.where(np.isnan(x), np.uint8(0x7f), code)
+    return (code | np.where(np.signbit(x) & ~np.isnan(x), 0x80, 0).astype(np.uint8)).astype(np.uint8)
+
+
+def quantize_f8(x, scale):
+    """Codes of x * scale, the product rounded to fp32 first (the precision the product is formed in)."""
+    prod = (np.asarray(x, dtype=np.float32) * np.float32(scale)).astype(np.float32)
+    return e4m3_encode(prod.astype(np.float64))
+
+
+def conv_valid_f8(tile_codes, w_codes, bias=None, stride=1, relu=False, out_scale=1.0):
+    """The FP8 variant of the tile convolution: act(out_scale * conv_valid(decoded tiles, decoded weights) + bias)."""
+    acc = conv_valid(e4m3_decode(tile_codes), e4m3_decode(w_codes), None, stride=stride, relu=False)
+    z = acc * float(np.float32(out_scale)) + (0.0 if bias is None else np.asarray(bias, dtype=np.float64))
+    return np.maximum(z, 0.0) if relu else z
+
+
+# ---------------------------------------------------------------------------------------
 # compositions
 # ---------------------------------------------------------------------------------------
 def sparse_conv_tiled(x, idx, g_in, g_out, w, bias, y, stride=1, relu=False, add=False):

@@ -60,6 +60,10 @@ _SIGNATURES = {
     "sbnet_relu_backward_on_tiles": (_ci, [_vp, _vp, _ci, _vp, _ci, _sz, _vp, _vp]),
     "sbnet_bias_backward_workspace_bytes": (_sz, [_ci, _ci]),
     "sbnet_bias_backward_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _vp, _vp, _sz, _vp]),
+    "sbnet_quantize_f8": (_ci, [_vp, _ci, _sz, ctypes.c_float, _vp, _vp]),
+    "sbnet_pack_weights_f8": (_ci, [_vp, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
+    "sbnet_conv_on_tiles_f8": (_ci, [_vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci,
+                                     ctypes.c_float, _vp, _vp]),
     "sbnet_pack_weights": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_pack_weights_transposed": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_conv_backward_data_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci]),
@@ -322,6 +326,45 @@ def bias_backward_on_tiles(dy_tiles, count, workspace=None):
     _check(lib().sbnet_bias_backward_on_tiles(_ptr(dy_tiles), _dt(dy_tiles), _ptr(count), cap, h * w, C, _ptr(db),
                                               _ptr(workspace), workspace.numel(), _stream()))
     return db
+
+
+def quantize_f8(x, scale=1.0, out=None):
+    """x (f32 / bf16 / f16 device tensor) -> uint8 tensor of FP8 E4M3 (e4m3fn) codes of clamp(x * scale, +-448)."""
+    _dev(x, "x")
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    _dev(out, "out", torch.uint8)
+    assert out.shape == x.shape
+    _check(lib().sbnet_quantize_f8(_ptr(x), _dt(x), x.numel(), float(scale), _ptr(out), _stream()))
+    return out
+
+
+def pack_weights_f8(w_f8):
+    """FP8 codes [kh,kw,Cin,Cout] (uint8 device tensor) -> packed buffer for conv_on_tiles_f8."""
+    _dev(w_f8, "w_f8", torch.uint8)
+    kh, kw, Cin, Cout = w_f8.shape
+    nbytes = _sz()
+    _check(lib().sbnet_pack_weights_f8(None, kh, kw, Cin, Cout, None, nbytes, None))
+    buf = torch.empty((nbytes.value,), dtype=torch.uint8, device=w_f8.device)
+    _check(lib().sbnet_pack_weights_f8(_ptr(w_f8), kh, kw, Cin, Cout, _ptr(buf), nbytes, _stream()))
+    return PackedWeights(buf, (kh, kw, Cin, Cout), torch.uint8)
+
+
+def conv_on_tiles_f8(tiles_f8, count, w_packed, bias=None, stride=1, relu=False, out_scale=1.0, out=None):
+    """Valid convolution of FP8 tiles [cap,th,tw,Cin] (uint8 codes) with FP8 weights -> bf16 [cap,th',tw',Cout]."""
+    _dev(tiles_f8, "tiles_f8", torch.uint8), _dev(count, "count", torch.int32)
+    kh, kw, Cin, Cout = w_packed.shape
+    cap, th, tw, C = tiles_f8.shape
+    assert C == Cin and w_packed.dtype == torch.uint8
+    oh, ow = (th - kh) // stride + 1, (tw - kw) // stride + 1
+    if out is None:
+        out = torch.empty((cap, oh, ow, Cout), dtype=torch.bfloat16, device=tiles_f8.device)
+    _dev(out, "out", torch.bfloat16)
+    if bias is not None:
+        _dev(bias, "bias", torch.float32)
+    _check(lib().sbnet_conv_on_tiles_f8(_ptr(tiles_f8), _ptr(count), cap, th, tw, Cin, _ptr(w_packed.buf), _ptr(bias), kh,
+                                        kw, stride, stride, Cout, int(bool(relu)), float(out_scale), _ptr(out), _stream()))
+    return out
 
 
 class PackedWeights:

@@ -105,3 +105,20 @@ def test_gradient_and_normalisation_calls_check_their_arguments_on_the_host():
     assert b"overlap" in lib.sbnet_last_error()
     assert lib.sbnet_sparse_bn_apply(ptr, sb.BF16, 1, 16, 16, 8, ptr, ptr, 4, g_out, ptr, ptr, None, None, -1.0, 0, ptr,
                                      None) == sb.EINVAL
+
+
+def test_f8_entry_points_check_their_arguments_on_the_host():
+    lib = sb.lib()
+    nbytes = ctypes.c_size_t()
+    assert lib.sbnet_pack_weights_f8(None, 3, 3, 64, 64, None, nbytes, None) == sb.OK and nbytes.value == 9 * 64 * 64
+    assert lib.sbnet_pack_weights_f8(None, 3, 3, 48, 40, None, nbytes, None) == sb.OK and nbytes.value == 9 * 64 * 64
+    buf = (ctypes.c_char * 4096)()
+    ptr = ctypes.cast(ctypes.byref(buf, 16 - ctypes.addressof(buf) % 16), ctypes.c_void_p)
+    assert lib.sbnet_quantize_f8(None, sb.BF16, 16, 1.0, None, None) == sb.EINVAL
+    assert lib.sbnet_quantize_f8(ptr, sb.BF16, 16, 0.0, ptr, None) == sb.EINVAL and b"scale" in lib.sbnet_last_error()
+    assert lib.sbnet_quantize_f8(ptr, sb.U8, 16, 1.0, ptr, None) == sb.EUNSUPPORTED
+    assert lib.sbnet_quantize_f8(ptr, sb.BF16, 0, 1.0, ptr, None) == sb.OK          # nothing to do, nothing launched
+    assert lib.sbnet_conv_on_tiles_f8(ptr, ptr, 4, 6, 6, 24, ptr, None, 3, 3, 1, 1, 8, 0, 1.0, ptr, None) == sb.EUNSUPPORTED
+    assert b"multiple of 16" in lib.sbnet_last_error()
+    assert lib.sbnet_conv_on_tiles_f8(None, None, 4, 6, 6, 16, None, None, 3, 3, 1, 1, 8, 0, 1.0, None, None) == sb.EINVAL
+    assert lib.sbnet_conv_on_tiles_f8(ptr, ptr, 4, 6, 6, 16, ptr, None, 3, 3, 1, 1, 8, 0, float("inf"), ptr, None) == sb.EINVAL

@@ -300,6 +300,34 @@ def test_bottleneck_backward_by_finite_differences():
     assert np.allclose(orc.bias_backward(np.ones((2, 3, 4, 5))), 24.0)
 
 
+def test_e4m3_against_the_format_and_the_library():
+    """Decode: the values the OCP format fixes (1.0 = 0x38, 448 = 0x7e, 2^-9 = 0x01, 2^-6 = 0x08, 0x7f NaN) and all
+    256 codes against torch's float8_e4m3fn.  Encode: every code decodes and encodes back to itself; exact midpoints
+    go to the even mantissa; above 448 saturates; random values against torch's conversion (which saturates the same
+    way for finite inputs within range)."""
+    import torch
+    assert orc.e4m3_decode([0x38, 0x7e, 0x01, 0x08, 0xb8, 0x00])[:5].tolist() == [1.0, 448.0, 2.0 ** -9, 2.0 ** -6, -1.0]
+    assert np.isnan(orc.e4m3_decode([0x7f, 0xff])).all()
+    codes = np.arange(256, dtype=np.uint8)
+    lib_vals = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    ours = orc.e4m3_decode(codes)
+    assert np.array_equal(np.isnan(ours), np.isnan(lib_vals)) and np.array_equal(ours[~np.isnan(ours)], lib_vals[~np.isnan(ours)])
+    finite = codes[~np.isnan(ours)]
+    back = orc.e4m3_encode(ours[~np.isnan(ours)])
+    assert np.array_equal(back & 0x7f, finite & 0x7f)            # the sign of zero aside
+    assert orc.e4m3_encode([1.0625, 1.1875, 17.0, 500.0, -1e9, 2.0 ** -10, 3 * 2.0 ** -10]).tolist() == \
+        [0x38, 0x3a, 0x58, 0x7e, 0xfe, 0x00, 0x02]               # ties to even; 17 -> 16; saturation; subnormal ties
+    x = (rng0.standard_normal(20000) * np.exp(rng0.uniform(-8, 5, 20000))).astype(np.float32)
+    x = x[np.abs(x) <= 448.0]
+    lib_codes = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    ours = orc.e4m3_encode(x.astype(np.float64))
+    assert np.array_equal(ours, lib_codes), int((ours != lib_codes).sum())
+    # the convolution on codes is the fp64 convolution of their values
+    t = rng0.integers(0, 0x7f, (2, 4, 5, 3)).astype(np.uint8)
+    w = rng0.integers(0, 0x7f, (3, 3, 3, 2)).astype(np.uint8)
+    assert np.allclose(orc.conv_valid_f8(t, w, out_scale=0.5), 0.5 * orc.conv_valid(orc.e4m3_decode(t), orc.e4m3_decode(w)))
+
+
 def test_bn_apply_and_backward():
     """All blocks active and no activation: the library's batch_norm in training mode and its autograd gradients
     (fp64).  Some blocks active, with and without ReLU: the forward value by brute force over pixels; the three
