@@ -209,3 +209,59 @@ def test_stage_shapes_sampled(H, W, Cin, Cout, s, bo):
     # blocks hanging over the image edge: the part outside is never stored (blocks_of pads it with zeros)
     inside = blocks_of(np.ones((N, Ho, Wo, 1)), idx[rows], g_out) > 0
     assert_close(blocks_of(got, idx[rows], g_out), np.where(inside, ref, 0.0), CONV_TOL["bf16"], "stage shape sampled tiles")
+
+
+def test_training_side_calls_at_the_headline_size():
+    """The tile counts bench.py times for the headline layer (800 x 704 x 64, 16 x 16 blocks, all 2200 blocks): the
+    FP8 tile convolution on a seeded sample of tiles, ReLU mask and bias gradient whole, and the normalisation over
+    active blocks forward and backward on a road-band mask at 30 % (the oracle works on the gathered active pixels,
+    which takes seconds)."""
+    step("training-side calls, headline size")
+    r = gen.rng_for(2, 91)
+    n, th, bo, C = 2200, 18, 16, 64
+    cnt = torch.tensor([n], dtype=torch.int32).cuda()
+    t_codes = orc.quantize_f8(gen.activations(r, (n, th, th, C), "bf16"), 16.0)
+    w_codes = orc.quantize_f8(gen.conv_weights(r, 3, 3, C, C, "bf16"), 64.0)
+    out = sb.conv_on_tiles_f8(torch.from_numpy(t_codes).cuda(), cnt, sb.pack_weights_f8(torch.from_numpy(w_codes).cuda()),
+                              relu=True, out_scale=1.0 / 1024.0)
+    pick = np.unique(np.concatenate([[0, n - 1], r.choice(n, 10, replace=False)]))
+    assert_close(to_host(out[torch.from_numpy(pick).cuda()]), orc.conv_valid_f8(t_codes[pick], w_codes, relu=True, out_scale=1.0 / 1024.0),
+                 8e-3, "conv_on_tiles_f8, sampled tiles")
+    y = to_host(out)
+    dy = gen.activations(r, (n, bo, bo, C), "bf16")
+    dyd = to_dev(dy, "bf16")
+    assert np.array_equal(to_host(sb.relu_backward_on_tiles(out, dyd, cnt)), orc.relu_backward(y, dy))
+    db = sb.bias_backward_on_tiles(dyd, cnt).cpu().numpy()
+    assert np.abs(db - orc.bias_backward(dy)).max() <= 2e-5 * np.sqrt(n * bo * bo)
+
+    N, H, W = 1, 800, 704
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    mask, frac = road_mask(r, H, W, g_out, N, 0.30)
+    idx_np = orc.reduce_mask(mask, ogeom(g_out))
+    nb = len(idx_np)
+    assert 500 < nb < 800
+    idx = torch.from_numpy(np.ascontiguousarray(idx_np)).cuda()
+    cntb = torch.tensor([nb], dtype=torch.int32).cuda()
+    x = gen.round_to((gen.activations(r, (N, H, W, C), "f32") * 1.5 + 0.25).astype(np.float32), "bf16")
+    g = gen.activations(r, (N, H, W, C), "bf16")
+    gamma = (r.standard_normal(C) * 0.3 + 1.0).astype(np.float32)
+    beta = (r.standard_normal(C) * 0.3).astype(np.float32)
+    xd, gd = to_dev(x, "bf16"), to_dev(g, "bf16")
+    mean, var = sb.sparse_bn_stats(xd, idx, cntb, g_out)
+    gm, bt = torch.from_numpy(gamma).cuda(), torch.from_numpy(beta).cuda()
+    yb = sb.sparse_bn_apply(xd, idx, cntb, g_out, mean, var, gm, bt, eps=1e-3, relu=True, y=torch.zeros_like(xd))
+    dx, dgam, dbet = sb.sparse_bn_backward(xd, gd, idx, cntb, g_out, mean, var, gm, bt, eps=1e-3, relu=True)
+    inside = orc.block_mask(idx_np, ogeom(g_out), N, H, W)
+    om, ov = orc.bn_stats(x, idx_np, ogeom(g_out))
+    assert np.allclose(mean.cpu().numpy(), om, rtol=1e-5, atol=1e-5) and np.allclose(var.cpu().numpy(), ov, rtol=2e-4, atol=1e-6)
+    ref_y = orc.bn_apply(x, idx_np, ogeom(g_out), om, ov, gamma, beta, 1e-3, np.zeros_like(x), relu=True)
+    got_y = to_host(yb)
+    assert not got_y[~inside].any()
+    assert_close(got_y[inside], ref_y[inside], 8e-3, "bn_apply")
+    rdx, rdg, rdb = orc.bn_backward(x, g, idx_np, ogeom(g_out), gamma, beta, 1e-3, np.zeros_like(x), relu=True)
+    npx = int(inside.sum())
+    assert np.abs(dgam.cpu().numpy() - rdg).max() <= 3e-5 * np.sqrt(npx) + 1e-4 * np.abs(rdg).max()
+    assert np.abs(dbet.cpu().numpy() - rdb).max() <= 3e-5 * np.sqrt(npx) + 1e-4 * np.abs(rdb).max()
+    got_dx = to_host(dx)
+    assert not got_dx[~inside].any()
+    assert_close(got_dx[inside], rdx[inside], 1.6e-2, "bn_backward dx")
