@@ -41,6 +41,18 @@ __global__ void gb_map_fill(int32_t *map, const int32_t *__restrict__ indices, c
     }
 }
 
+// both steps in one workgroup (one launch less) when the map and the list are small enough for it
+__global__ __launch_bounds__(1024) void gb_map_build(int32_t *map, int nmap, const int32_t *__restrict__ indices,
+                                                     const int32_t *__restrict__ count, int cap, int N, int bh, int bw) {
+    for (int i = threadIdx.x; i < nmap; i += blockDim.x) map[i] = -1;
+    __syncthreads();
+    const int nact = min(*count, cap);
+    for (int b = threadIdx.x; b < nact; b += blockDim.x) {
+        const int n = indices[3 * b], by = indices[3 * b + 1], bx = indices[3 * b + 2];
+        if (n >= 0 && n < N && by >= 0 && by < bh && bx >= 0 && bx < bw) map[(n * bh + by) * bw + bx] = b;
+    }
+}
+
 // fp32 sum of storage words, element-wise
 template <int DT> struct Acc;
 template <> struct Acc<SBNET_F32> {
@@ -245,9 +257,13 @@ extern "C" sbnet_status sbnet_sparse_gather_backward(const void *dtiles, sbnet_d
     hipStream_t s = (hipStream_t)stream;
     int32_t *map = (int32_t *)workspace;
     const int nmap = N * g->bcount_h * g->bcount_w;
-    hipLaunchKernelGGL(gb_map_clear, dim3((nmap + 255) / 256 > 1024 ? 1024 : (nmap + 255) / 256), dim3(256), 0, s, map, nmap);
-    hipLaunchKernelGGL(gb_map_fill, dim3((cap + 255) / 256 > 1024 ? 1024 : (cap + 255) / 256), dim3(256), 0, s, map, indices,
-                       count, cap, N, g->bcount_h, g->bcount_w);
+    if (nmap <= 32768 && cap <= 32768) {
+        hipLaunchKernelGGL(gb_map_build, dim3(1), dim3(1024), 0, s, map, nmap, indices, count, cap, N, g->bcount_h, g->bcount_w);
+    } else {
+        hipLaunchKernelGGL(gb_map_clear, dim3((nmap + 255) / 256 > 1024 ? 1024 : (nmap + 255) / 256), dim3(256), 0, s, map, nmap);
+        hipLaunchKernelGGL(gb_map_fill, dim3((cap + 255) / 256 > 1024 ? 1024 : (cap + 255) / 256), dim3(256), 0, s, map, indices,
+                           count, cap, N, g->bcount_h, g->bcount_w);
+    }
     if (dtype == SBNET_F32) return dispatch_gb<SBNET_F32>(vec, dx, dtiles, map, p, s);
     if (dtype == SBNET_BF16) return dispatch_gb<SBNET_BF16>(vec, dx, dtiles, map, p, s);
     return dispatch_gb<SBNET_F16>(vec, dx, dtiles, map, p, s);
