@@ -134,24 +134,27 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
         const uint32_t v = (uint32_t)(gy * GV + (q >> 1)) ^ (uint32_t)cv;
         at[NIX + u] = (uint32_t)(Sh::XBYTES + cv * 8 * CSG * 16) + (ok ? v * 16 + (q & 1) * 8 : (uint32_t)Sh::GPL * 16);
     }
-    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.x), 0, (int)((uint32_t)p.cap * p.x_tile_bytes), kBufWord3);
-    const __amdgpu_buffer_rsrc_t gr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p.g), 0, (int)((uint32_t)p.cap * p.g_tile_bytes), kBufWord3);
     const uint32_t x_stage_step = (uint32_t)(R * S * p.tw * p.Cin * 2), g_stage_step = (uint32_t)(R * p.ow * p.Cout * 2);
     const uint32_t x_px_step = (uint32_t)(S * p.Cin * 2), g_px_step = (uint32_t)(p.Cout * 2);
 
     uint4 staged[NI][4];
     auto issue = [&](int b, int h) {
+        // one buffer descriptor per tile: offsets stay below the tile size whatever the size of the stack, and an
+        // offset beyond the tile (a row past its last one) reads zeros by itself
+        const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((const char *)p.x + (size_t)b * p.x_tile_bytes), 0, (int)p.x_tile_bytes, kBufWord3);
+        const __amdgpu_buffer_rsrc_t gr = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)((const char *)p.g + (size_t)b * p.g_tile_bytes), 0, (int)p.g_tile_bytes, kBufWord3);
 #pragma unroll
         for (int u = 0; u < NI; ++u) {
             const bool isx = u < NIX;
-            const uint32_t tile = isx ? p.x_tile_bytes : p.g_tile_bytes;
             const uint32_t o = (uint32_t)h * (isx ? x_stage_step : g_stage_step) + rel[u];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                // pixels beyond the row's end or beyond the tile (rows past its last one, or the rest of a last row
-                // that the tile does not fill): zeros; a slot that holds nothing has cnt = 0
+                // pixels beyond the row's end (a slot that holds nothing has cnt = 0): zeros; so are, by the
+                // descriptor, pixels beyond the tile (rows past its last one, the rest of a last row it does not fill)
                 const uint32_t oj = o + j * (isx ? x_px_step : g_px_step);
-                const uint32_t off = (oj < tile && (uint32_t)j < cnt[u]) ? (uint32_t)b * tile + oj : kOutOfRange;
+                const uint32_t off = (uint32_t)j < cnt[u] ? oj : kOutOfRange;
                 staged[u][j] = buf_load16(isx ? xr : gr, off);
             }
         }
@@ -362,7 +365,7 @@ bool plan_wgrad(sbnet_dtype dt, int cap, int th, int tw, int Cin, int kh, int kw
     q->flat = kh == 1 && kw == 1 && sh == 1 && sw == 1;
     q->mfma = (dt == SBNET_BF16 || dt == SBNET_F16) && (kh == 3 || kh == 1) && kw == kh && sh == sw && (sh == 1 || sh == 2) && Cin % 8 == 0 &&
               Cout % 8 == 0 && (q->flat || (ow <= 32 && tw <= 32 * sw + 2)) &&
-              (long long)cap * th * tw * Cin * 2 < (1LL << 31) && (long long)cap * oh * ow * Cout * 2 < (1LL << 31);
+              (long long)th * tw * Cin * 2 < (1LL << 30) && (long long)oh * ow * Cout * 2 < (1LL << 30);
     q->kh = kh;
     if (q->mfma) {
         q->s = sh;

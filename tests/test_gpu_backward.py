@@ -258,3 +258,33 @@ def test_residual_unit_backward_composed_from_single_calls(C, dens):
         assert_close(to_host(got), want, tol, name)
     ref_tiles_r = torch.from_numpy(ref[0]).to(TORCH_DT[dtype]).to(torch.float64).numpy()
     assert_close(to_host(dx), orc.gather_backward(ref_tiles_r, idx_np, og_in, np.zeros((N, H, W, C))), tol, "dx")
+
+
+def test_weight_gradient_of_a_stack_beyond_two_gib():
+    """13 500 tiles of 18 x 18 x 256 (the residual unit's first convolution at the batched configurations' scale) are
+    2.24 GB: byte offsets into the stack do not fit 31 bits, and the kernel addresses every tile through a descriptor
+    of its own.  Inputs come from a seeded device generator (a host copy serves the oracle's samples: single weights,
+    each a sum over every pixel of every tile)."""
+    step("weight gradient, stack beyond 2 GiB")
+    n, th, C, K = 13500, 18, 256, 64
+    gen_t = torch.Generator(device="cuda")
+    gen_t.manual_seed(gen.BASE_SEED + 27)
+    x = torch.randn((n, th, th, C), generator=gen_t, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    g = torch.randn((n, th, th, K), generator=gen_t, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    assert x.numel() * 2 > 2 ** 31
+    cnt = torch.tensor([n], dtype=torch.int32).cuda()
+    dw = sb.conv_on_tiles_backward_weights(x, g, cnt, 1)
+    xc, gc = x.cpu(), g.cpu()
+    got = dw.cpu().numpy()
+    r = gen.rng_for(27)
+    samples = [(int(r.integers(0, C)), int(r.integers(0, K))) for _ in range(10)] + [(0, 0), (C - 1, K - 1), (C - 1, 0), (0, K - 1)]
+    scale = np.sqrt(n * th * th)
+    for c, o in samples:
+        want = float((xc[..., c].to(torch.float64) * gc[..., o].to(torch.float64)).sum())
+        assert abs(got[0, 0, c, o] - want) <= 2e-5 * scale + 2e-5 * abs(want), (c, o, got[0, 0, c, o], want)
+    # the last tile reaches the sums: with it left out, the sampled weights differ
+    cnt2 = torch.tensor([n - 1], dtype=torch.int32).cuda()
+    dw2 = sb.conv_on_tiles_backward_weights(x, g, cnt2, 1).cpu().numpy()
+    c, o = samples[0]
+    last = float((xc[n - 1, ..., c].to(torch.float64) * gc[n - 1, ..., o].to(torch.float64)).sum())
+    assert abs((got[0, 0, c, o] - dw2[0, 0, c, o]) - last) <= 4e-5 * scale
