@@ -512,6 +512,8 @@ extern "C" sbnet_status sbnet_conv_on_tiles(const void *tiles_in, sbnet_dtype dt
 // the output gradient is addressed as a small image, whose surroundings read as zeros); at larger strides
 // spread_tiles builds the framed stack.  The convolution kernels of this file then do the arithmetic with weights
 // packed by sbnet_pack_weights_transposed.
+namespace sbnet {
+
 template <typename V>
 __global__ void spread_tiles(const V *__restrict__ dout, V *__restrict__ framed, const int32_t *__restrict__ count,
                              int cap, int oh, int ow, int ph, int pw, int cv, int kh, int kw, int sh, int sw,
@@ -541,6 +543,8 @@ __global__ void tile_indices(int32_t *__restrict__ idx, int cap) {
         idx[3 * b + 2] = 0;
     }
 }
+
+}  // namespace sbnet
 
 static size_t framed_elems(int cap, int th, int tw, int kh, int kw, int Cout) {
     return (size_t)cap * (size_t)(th + kh - 1) * (size_t)(tw + kw - 1) * (size_t)Cout;
