@@ -50,9 +50,6 @@ struct Plan3 {
     uint32_t dump_off, ost_off, bias_off;    // after the two buffers
     uint32_t w_bytes;        // bytes of the 32x32x16 operand copy of the weights
     int ks16;                // 16-channel k-steps per output group: 9 * CinP / 16
-    // Two shapes of the workgroup tile may be launched for one call; the device-side count decides which one runs.
-    int role;                // 0: the only launch; 1: the larger tile of a pair; 2: the smaller one
-    uint32_t per_tile_big, per_tile_small;   // work items per active block of the two shapes
 };
 
 struct Item3 {
@@ -77,8 +74,7 @@ struct Chunk3 {
 };
 
 template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void conv3_kernel(ConvParams p, Plan3 q) {
+__device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) {
     static_assert(FUSED || !ADD, "adding into the output is part of the fused form");
     // Register sets for chunks in flight.  Two (requests two chunks further ahead) were measured for the small
     // workgroup tiles and gained nothing: the compiler's wait before a vector's LDS write allows only one set's
@@ -105,13 +101,6 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     const int M = p.oh * p.ow;
 
     const int nact = max(min(*p.count, p.cap), 0);
-    if (q.role != 0) {
-        // rounds of work on 256 CUs with either shape; an item of the smaller tile costs about 5/8 of a larger one
-        // (half the matrix work, the same weights to stage)
-        const uint32_t rb = ((uint32_t)nact * q.per_tile_big + 255u) >> 8, rs = ((uint32_t)nact * q.per_tile_small + 255u) >> 8;
-        const bool big = rb * 8u <= rs * 5u;
-        if (big != (q.role == 1)) return;
-    }
     const uint32_t per_tile = (uint32_t)q.mpasses * q.ngroups;
     const uint32_t items = (uint32_t)nact * per_tile;
     const uint32_t G = gridDim.x;                    // multiple of 8
@@ -481,6 +470,25 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     }
 }
 
+template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void conv3_kernel(ConvParams p, Plan3 q) {
+    conv3_body<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI>(p, q);
+}
+
+// The 256-pixel and the 128-pixel tile shape in one launch: the device-side count picks one (rounds of work on 256
+// CUs with either shape; an item of the smaller tile costs about 5/8 of a larger one: half the matrix work, the same
+// weights to stage).  Two separate launches, of which one returns, cost a launch more.
+template <int DT, bool FUSED, bool ADD, int CCB, int NVIB, int CCS, int NVIS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void conv3_pair_kernel(ConvParams p, Plan3 qb, Plan3 qs) {
+    const int nact = max(min(*p.count, p.cap), 0);
+    const uint32_t per_big = (uint32_t)qb.mpasses * qb.ngroups, per_small = (uint32_t)qs.mpasses * qs.ngroups;
+    const uint32_t rb = ((uint32_t)nact * per_big + 255u) >> 8, rs = ((uint32_t)nact * per_small + 255u) >> 8;
+    if (rb * 8u <= rs * 5u) conv3_body<DT, FUSED, ADD, CCB, 4, 2, 2, NVIB>(p, qb);
+    else conv3_body<DT, FUSED, ADD, CCS, 4, 2, 1, NVIS>(p, qs);
+}
+
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
@@ -513,8 +521,6 @@ static Shape3 plan3(const ConvParams &p, int pp) {
     q.cpp = (p.tw + p.sw - 1) / p.sw;
     q.ks16 = 9 * (CinP / 16);
     q.w_bytes = (uint32_t)((size_t)q.ngroups * q.ks16 * 2048);
-    q.role = 0;
-    q.per_tile_big = q.per_tile_small = 0;
     const size_t bias_bytes = (size_t)q.ngroups * 64 * 4;
     // chunks of 32 channels with up to 6 input vectors per thread, else of 16 with up to 9 (kernels are built for
     // 3 / 6 and 5 / 9: every vector costs its staging instructions whether it carries data or not); two buffers must fit
@@ -583,6 +589,48 @@ static void launch3(sbnet_dtype dt, bool fused, const ConvParams &p, const Shape
     }
 }
 
+template <int DT, bool FUSED, bool ADD, int CCB, int NVIB>
+static void launch3_pair_small(const ConvParams &p, const Shape3 &big, const Shape3 &small, int grid, size_t lds, hipStream_t s) {
+#define SBNET_L3P(CCS, NVIS)                                                                                   \
+    do {                                                                                                       \
+        auto kern = conv3_pair_kernel<DT, FUSED, ADD, CCB, NVIB, CCS, NVIS>;                                   \
+        if (lds > 48 * 1024)                                                                                   \
+            (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, p, big.q, small.q);                            \
+    } while (0)
+    if (small.cc == 32 && small.nvi == 3) SBNET_L3P(32, 3);
+    else if (small.cc == 32) SBNET_L3P(32, 6);
+    else if (small.nvi == 5) SBNET_L3P(16, 5);
+    else SBNET_L3P(16, 9);
+#undef SBNET_L3P
+}
+
+template <int DT, bool FUSED, bool ADD>
+static void launch3_pair_big(const ConvParams &p, const Shape3 &big, const Shape3 &small, int grid, size_t lds, hipStream_t s) {
+    if (big.cc == 32 && big.nvi == 3) launch3_pair_small<DT, FUSED, ADD, 32, 3>(p, big, small, grid, lds, s);
+    else if (big.cc == 32) launch3_pair_small<DT, FUSED, ADD, 32, 6>(p, big, small, grid, lds, s);
+    else if (big.nvi == 5) launch3_pair_small<DT, FUSED, ADD, 16, 5>(p, big, small, grid, lds, s);
+    else launch3_pair_small<DT, FUSED, ADD, 16, 9>(p, big, small, grid, lds, s);
+}
+
+// both tile shapes in one launch
+static void launch3_pair(sbnet_dtype dt, bool fused, const ConvParams &p, const Shape3 &big, const Shape3 &small, hipStream_t s) {
+    const long long items = (long long)p.cap * small.q.mpasses * small.q.ngroups;     // the smaller tile has more items
+    long long g = (items + 7) / 8 * 8;
+    if (g > 256) g = 256;                             // one persistent workgroup per CU
+    const int grid = (int)g;
+    const size_t lds = big.lds_bytes > small.lds_bytes ? big.lds_bytes : small.lds_bytes;
+    if (dt == SBNET_BF16) {
+        if (fused && p.add) launch3_pair_big<SBNET_BF16, true, true>(p, big, small, grid, lds, s);
+        else if (fused) launch3_pair_big<SBNET_BF16, true, false>(p, big, small, grid, lds, s);
+        else launch3_pair_big<SBNET_BF16, false, false>(p, big, small, grid, lds, s);
+    } else {
+        if (fused && p.add) launch3_pair_big<SBNET_F16, true, true>(p, big, small, grid, lds, s);
+        else if (fused) launch3_pair_big<SBNET_F16, true, false>(p, big, small, grid, lds, s);
+        else launch3_pair_big<SBNET_F16, false, false>(p, big, small, grid, lds, s);
+    }
+}
+
 bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, sbnet_status *st, const char *who) {
     if (dt != SBNET_BF16 && dt != SBNET_F16) return false;
     if (p0.kh != 3 || p0.kw != 3) return false;
@@ -609,14 +657,9 @@ bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, 
     if ((long long)p.cap * most_passes * ((p.Cout + 63) / 64) >= (1LL << 31)) return false;
     // with at most 256 items of the smaller tile whatever the count, the rule in the kernel never picks the larger one
     if (big.ok && small.ok && (long long)p.cap * small.q.mpasses * small.q.ngroups <= 256) big.ok = false;
-    if (big.ok && small.ok) {
-        big.q.role = 1;
-        small.q.role = 2;
-        big.q.per_tile_big = small.q.per_tile_big = (uint32_t)big.q.mpasses * big.q.ngroups;
-        big.q.per_tile_small = small.q.per_tile_small = (uint32_t)small.q.mpasses * small.q.ngroups;
-    }
-    if (big.ok) launch3(dt, fused, p, big, s);
-    if (small.ok) launch3(dt, fused, p, small, s);
+    if (big.ok && small.ok) launch3_pair(dt, fused, p, big, small, s);     // the device-side count picks the shape
+    else if (big.ok) launch3(dt, fused, p, big, s);
+    else launch3(dt, fused, p, small, s);
     *st = launch_status(who);
     return true;
 }
