@@ -25,8 +25,8 @@
 //   * Results are transposed through a wave-private LDS area, 32 pixels x 32 channels at a time, so that a store
 //     instruction writes 64-byte runs instead of 16-byte pieces.
 //   * Workgroup tiles: 256 pixels x 64 channels (wave: 64 px x 64 ch, 4 accumulators), 128 x 64 for problems
-//     where that means fewer rounds of work on the device (picked on the device from the active count: both are
-//     launched, one returns at once), and 64 x 64 for tiles of at most 64 output pixels.  Chunks of 32 channels where two
+//     where that means fewer rounds of work on the device (picked on the device from the active count: one launch
+//     holds both shapes), and 64 x 64 for tiles of at most 64 output pixels.  Chunks of 32 channels where two
 //     buffers of that fit in LDS (stride 1), else of 16 (the 33x33 input tile of a strided 16x16 block).
 #include "conv_common.h"
 
