@@ -430,18 +430,11 @@ def run_backward(args):
             sb.conv_on_tiles(t1, cnt, p2, fb2, relu=True, out=t2)
             sb.conv_on_tiles(t2, cnt, p3, fb3, out=t3)
 
+        ws_b = torch.empty((sb.lib().sbnet_bottleneck_backward_workspace_bytes(sb.BF16, n, TH, TH, Cu, Cm),), dtype=torch.uint8,
+                           device=dev)
+
         def bwd():
-            sb.conv_on_tiles_backward_weights(t2, d3, cnt, 1, out=dw3, workspace=ws)
-            sb.bias_backward_on_tiles(d3, cnt, workspace=ws)
-            sb.conv_on_tiles_backward_data(d3, cnt, q3, BO, BO, out=d2, workspace=ws)
-            sb.relu_backward_on_tiles(t2, d2, cnt, out=d2)
-            sb.conv_on_tiles_backward_weights(t1, d2, cnt, 3, out=dw2, workspace=ws)
-            sb.bias_backward_on_tiles(d2, cnt, workspace=ws)
-            sb.conv_on_tiles_backward_data(d2, cnt, q2, TH, TH, out=d1, workspace=ws)
-            sb.relu_backward_on_tiles(t1, d1, cnt, out=d1)
-            sb.conv_on_tiles_backward_weights(xt, d1, cnt, 1, out=dw1, workspace=ws)
-            sb.bias_backward_on_tiles(d1, cnt, workspace=ws)
-            sb.conv_on_tiles_backward_data(d1, cnt, q1, TH, TH, out=dxt, workspace=ws)
+            sb.bottleneck_backward_on_tiles(xt, t1, t2, d3, cnt, (q1, q2, q3), workspace=ws_b)
         fwd()
         unit_rows.append({"active_blocks": n, "unit_forward_composed_ms": round(tk(fwd), 5),
                           "unit_backward_composed_ms": round(tk(bwd), 5)})

@@ -345,6 +345,30 @@ sbnet_status sbnet_conv_on_tiles_f8(const void *tiles_in_f8, const int32_t *coun
                                     float out_scale, void *tiles_out_bf16, void *stream);
 
 /*
+ * Backward pass of the residual branch of a bottleneck unit on tiles (Sec. 3.3; the forward branch is
+ * sbnet_bottleneck_on_tiles), composed from the calls above; nothing but they runs.  The caller keeps
+ * the forward activations t1 = ReLU(W1 x + b1) with the positions outside the image set to zero
+ * ([cap][th][tw][Cm]) and t2 = ReLU(W2 * t1 + b2) ([cap][th-2][tw-2][Cm]) - a training forward pass
+ * runs the three convolutions as single calls, the fused kernel does not keep them - and passes
+ * dt3 = dL/dt3 ([cap][th-2][tw-2][C]).  Written: dtiles_in = dL/dx on the input tiles ([cap][th][tw][C],
+ * `dtype`), and in float32 dw1 [1][1][C][Cm], db1 [Cm], dw2 [3][3][Cm][Cm], db2 [Cm], dw3 [1][1][Cm][C],
+ * db3 [C], each summed over the tiles b < min(*count, cap).  w1_t, w2_t, w3_t: the three forward weight
+ * arrays packed by sbnet_pack_weights_transposed.  workspace: device, 256-byte aligned,
+ * sbnet_bottleneck_backward_workspace_bytes(...) bytes, overwritten (it holds dL/dt2, dL/dt1 and the
+ * scratch of the single calls).  The unit's identity path adds dL/dy to dL/dx outside this call.
+ */
+size_t sbnet_bottleneck_backward_workspace_bytes(sbnet_dtype dtype, int cap, int th, int tw, int C,
+                                                 int Cm);
+sbnet_status sbnet_bottleneck_backward_on_tiles(const void *tiles_in, const void *t1, const void *t2,
+                                                const void *dt3, sbnet_dtype dtype,
+                                                const int32_t *count, int cap, int th, int tw, int C,
+                                                int Cm, const void *w1_t, const void *w2_t,
+                                                const void *w3_t, void *dtiles_in, float *dw1,
+                                                float *db1, float *dw2, float *db2, float *dw3,
+                                                float *db3, void *workspace, size_t workspace_bytes,
+                                                void *stream);
+
+/*
  * Set every tile position that lies outside the H x W image to zero, in place.  Needed when a
  * residual unit is composed from single sbnet_conv_on_tiles calls: after the first convolution
  * the halo positions beyond the image border hold act(bias), but the next convolution's zero

@@ -64,6 +64,9 @@ _SIGNATURES = {
     "sbnet_pack_weights_f8": (_ci, [_vp, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_conv_on_tiles_f8": (_ci, [_vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci,
                                      ctypes.c_float, _vp, _vp]),
+    "sbnet_bottleneck_backward_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci]),
+    "sbnet_bottleneck_backward_on_tiles": (_ci, [_vp, _vp, _vp, _vp, _ci, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _vp,
+                                                 _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sbnet_pack_weights": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_pack_weights_transposed": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_conv_backward_data_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci]),
@@ -365,6 +368,32 @@ def conv_on_tiles_f8(tiles_f8, count, w_packed, bias=None, stride=1, relu=False,
     _check(lib().sbnet_conv_on_tiles_f8(_ptr(tiles_f8), _ptr(count), cap, th, tw, Cin, _ptr(w_packed.buf), _ptr(bias), kh,
                                         kw, stride, stride, Cout, int(bool(relu)), float(out_scale), _ptr(out), _stream()))
     return out
+
+
+def bottleneck_backward_on_tiles(tiles, t1, t2, dt3, count, weights_t, workspace=None):
+    """Backward of the residual branch on tiles from kept activations: returns (dtiles, dw1, db1, dw2, db2, dw3, db3).
+    weights_t = (w1_t, w2_t, w3_t) from pack_weights_transposed of the three forward weight arrays."""
+    for name, t in (("tiles", tiles), ("t1", t1), ("t2", t2), ("dt3", dt3)):
+        _dev(t, name, tiles.dtype)
+    _dev(count, "count", torch.int32)
+    cap, th, tw, C = tiles.shape
+    Cm = t1.shape[3]
+    assert t1.shape == (cap, th, tw, Cm) and t2.shape == (cap, th - 2, tw - 2, Cm) and dt3.shape == (cap, th - 2, tw - 2, C)
+    w1_t, w2_t, w3_t = weights_t
+    assert w1_t.shape == (1, 1, C, Cm) and w2_t.shape == (3, 3, Cm, Cm) and w3_t.shape == (1, 1, Cm, C)
+    need = lib().sbnet_bottleneck_backward_workspace_bytes(_dt(tiles), cap, th, tw, C, Cm)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=tiles.device)
+    _dev(workspace, "workspace", torch.uint8)
+    dev = tiles.device
+    dtiles = torch.empty_like(tiles)
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
+    dw1, db1, dw2, db2, dw3, db3 = f32(1, 1, C, Cm), f32(Cm), f32(3, 3, Cm, Cm), f32(Cm), f32(1, 1, Cm, C), f32(C)
+    _check(lib().sbnet_bottleneck_backward_on_tiles(_ptr(tiles), _ptr(t1), _ptr(t2), _ptr(dt3), _dt(tiles), _ptr(count), cap,
+                                                    th, tw, C, Cm, _ptr(w1_t.buf), _ptr(w2_t.buf), _ptr(w3_t.buf),
+                                                    _ptr(dtiles), _ptr(dw1), _ptr(db1), _ptr(dw2), _ptr(db2), _ptr(dw3),
+                                                    _ptr(db3), _ptr(workspace), workspace.numel(), _stream()))
+    return dtiles, dw1, db1, dw2, db2, dw3, db3
 
 
 class PackedWeights:

@@ -122,3 +122,16 @@ def test_f8_entry_points_check_their_arguments_on_the_host():
     assert b"multiple of 16" in lib.sbnet_last_error()
     assert lib.sbnet_conv_on_tiles_f8(None, None, 4, 6, 6, 16, None, None, 3, 3, 1, 1, 8, 0, 1.0, None, None) == sb.EINVAL
     assert lib.sbnet_conv_on_tiles_f8(ptr, ptr, 4, 6, 6, 16, ptr, None, 3, 3, 1, 1, 8, 0, float("inf"), ptr, None) == sb.EINVAL
+
+
+def test_bottleneck_backward_checks_its_arguments_on_the_host():
+    lib = sb.lib()
+    need = lib.sbnet_bottleneck_backward_workspace_bytes(sb.BF16, 100, 18, 18, 256, 64)
+    # dL/dt2 and dL/dt1 of 100 tiles plus the largest scratch of the single calls (the 3x3 weight gradient's partial sums)
+    assert need >= 100 * (16 * 16 + 18 * 18) * 64 * 2 + 100 * 9 * 64 * 64 * 4 // 2
+    assert lib.sbnet_bottleneck_backward_workspace_bytes(sb.U8, 100, 18, 18, 256, 64) == 0
+    assert lib.sbnet_bottleneck_backward_workspace_bytes(sb.BF16, 100, 2, 18, 256, 64) == 0
+    n = None
+    assert lib.sbnet_bottleneck_backward_on_tiles(n, n, n, n, sb.BF16, n, 4, 18, 18, 256, 64, n, n, n, n, n, n, n, n, n, n, n, 0,
+                                                  n) == sb.EINVAL
+    assert b"null" in lib.sbnet_last_error()

@@ -258,6 +258,12 @@ def test_residual_unit_backward_composed_from_single_calls(C, dens):
         assert_close(to_host(got), want, tol, name)
     ref_tiles_r = torch.from_numpy(ref[0]).to(TORCH_DT[dtype]).to(torch.float64).numpy()
     assert_close(to_host(dx), orc.gather_backward(ref_tiles_r, idx_np, og_in, np.zeros((N, H, W, C))), tol, "dx")
+    # the one-call form runs the same sequence: the same bits
+    one = sb.bottleneck_backward_on_tiles(tiles, t1, t2, d3, cnt, (sb.pack_weights_transposed(dev(w1)),
+                                                                    sb.pack_weights_transposed(dev(w2)),
+                                                                    sb.pack_weights_transposed(dev(w3))))
+    for got, want in zip(one, (dtiles, dw1, db1, dw2, db2, dw3, db3)):
+        assert torch.equal(got[:n] if got.dim() == 4 and got.shape[0] == n + 1 else got, want[:n] if want.dim() == 4 and want.shape[0] == n + 1 else want)
 
 
 def test_weight_gradient_of_a_stack_beyond_two_gib():
