@@ -306,7 +306,8 @@ sbnet_status sbnet_conv_on_tiles_backward_weights(const void *tiles_in, const vo
  *
  * sbnet_bias_backward_on_tiles: db[c] = sum over those tiles and their `pixels` pixels of dy[b][pixel][c]
  * (the gradient of the bias a convolution adds), device float32 [C], zeros when no tile is active.
- * fp32 sums in a fixed order, no atomics.  C * element size a multiple of 4 bytes and at most 1 KiB.
+ * fp32 sums in a fixed order, no atomics.  C * element size a multiple of 4 bytes and at most 1 KiB
+ * (4 KiB where it is a multiple of 16 bytes and dy_tiles is 16-byte aligned).
  * workspace: device, 4-byte aligned, sbnet_bias_backward_workspace_bytes(cap, C) bytes, overwritten.
  */
 sbnet_status sbnet_relu_backward_on_tiles(const void *y_tiles, const void *dy_tiles, sbnet_dtype dtype,

@@ -3,10 +3,10 @@
 //
 //   tile_relu_backward   dout = dy where the forward activation y is positive, else 0, on the tiles
 //                        b < min(*count, cap); tiles beyond the count are not touched.
-//   tile_bias_partial +  db[c] = sum over those tiles and their pixels of dy[b][pixel][c]: one workgroup per tile
-//   tile_bias_sum        sums its pixels per channel in fp32 (threads strided over pixels, LDS tree), one workgroup
-//                        per channel block then adds the tiles' sums in list order per thread and a fixed tree: no
-//                        atomics, the same bits every run.
+//   tile_bias_partial +  db[c] = sum over those tiles and their pixels of dy[b][pixel][c]: workgroup w of G (at most 256)
+//   tile_bias_sum        sums tiles w, w + G, ... per channel in fp32 (threads strided over pixels, one LDS reduction
+//                        at the end), then one workgroup per 64 channels adds the G sums in a fixed order: no
+//                        atomics, the same bits every run for a given cap.
 #include "common.h"
 
 namespace sbnet {
@@ -49,57 +49,97 @@ __global__ __launch_bounds__(256) void tile_relu_backward(const uint32_t *__rest
         dout[vec_end + threadIdx.x] = relu_mask_word<DT>(y[vec_end + threadIdx.x], dy[vec_end + threadIdx.x]);
 }
 
-// part[b][c] = sum over the pixels of tile b.  Thread t owns word t % cw of a pixel (cw = 4-byte words per pixel: one
-// f32 channel or two 16-bit ones; cw <= 256) and pixels t / cw, t / cw + 256 / cw, ...
-template <int DT>
+// part[w][c] = sum over the pixels of the tiles w, w + G, ... of workgroup w (G = gridDim.x).  VW = 4: a thread owns
+// 16 bytes (4 words) of a pixel's channels and every (256 / vectors per pixel)-th pixel, four loads in flight; VW = 1:
+// one word, for channel counts that do not fill 16-byte vectors.  cw = 4-byte words per pixel (one f32 channel or two
+// 16-bit ones), cw / VW <= 256.  Every thread adds its pixels tile after tile in ascending order; the pixel groups
+// are then added in ascending order through LDS.
+template <int DT, int VW>
 __global__ __launch_bounds__(256) void tile_bias_partial(const uint32_t *__restrict__ dy, const int32_t *__restrict__ count,
                                                          int cap, int pixels, int C, int cw, float *__restrict__ part) {
     constexpr int EPW = DT == SBNET_F32 ? 1 : 2;
-    __shared__ float red[256][2];
+    constexpr int NE = VW * EPW;                                  // channels per thread
+    __shared__ float red[256][NE + 1];
     int n = *count;
     if (n > cap) n = cap;
-    const int groups = 256 / cw;                                  // pixel groups that fit the workgroup
-    const int w = threadIdx.x % cw, pg = threadIdx.x / cw;
-    for (int b = blockIdx.x; b < n; b += gridDim.x) {
-        float s0 = 0.f, s1 = 0.f;
-        if (pg < groups) {
-            const uint32_t *src = dy + ((size_t)b * pixels) * cw + w;
-            for (int px = pg; px < pixels; px += groups) {
-                const uint32_t v = src[(size_t)px * cw];
-                if (DT == SBNET_F32) {
-                    s0 += __uint_as_float(v);
-                } else {
-                    s0 += elem_to_float<DT>(v & 0xffffu);
-                    s1 += elem_to_float<DT>(v >> 16);
+    if ((int)blockIdx.x >= n) return;                             // the sum reads no result of this workgroup
+    const int cvn = cw / VW;                                      // threads per pixel
+    const int groups = 256 / cvn;                                 // pixel groups that fit the workgroup
+    const int w = threadIdx.x % cvn, pg = threadIdx.x / cvn;
+    float acc[NE];
+#pragma unroll
+    for (int e = 0; e < NE; ++e) acc[e] = 0.f;
+    auto add = [&](const uint32_t *v) {
+#pragma unroll
+        for (int k = 0; k < VW; ++k) {
+            if (DT == SBNET_F32) {
+                acc[k] += __uint_as_float(v[k]);
+            } else {
+                acc[2 * k] += elem_to_float<DT>(v[k] & 0xffffu);
+                acc[2 * k + 1] += elem_to_float<DT>(v[k] >> 16);
+            }
+        }
+    };
+    if (pg < groups) {
+        for (int b = blockIdx.x; b < n; b += gridDim.x) {
+            const uint32_t *src = dy + ((size_t)b * pixels) * cw + (size_t)w * VW;
+            int px = pg;
+            for (; px + 3 * groups < pixels; px += 4 * groups) {
+                uint32_t v[4][VW];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t *q = src + (size_t)(px + u * groups) * cw;
+                    if (VW == 4) {
+                        const uint4 t = *(const uint4 *)q;
+                        v[u][0] = t.x; v[u][VW > 1 ? 1 : 0] = t.y; v[u][VW > 2 ? 2 : 0] = t.z; v[u][VW > 3 ? 3 : 0] = t.w;
+                    } else {
+                        v[u][0] = q[0];
+                    }
                 }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) add(v[u]);
+            }
+            for (; px < pixels; px += groups) {
+                uint32_t v[VW];
+                const uint32_t *q = src + (size_t)px * cw;
+                if (VW == 4) {
+                    const uint4 t = *(const uint4 *)q;
+                    v[0] = t.x; v[VW > 1 ? 1 : 0] = t.y; v[VW > 2 ? 2 : 0] = t.z; v[VW > 3 ? 3 : 0] = t.w;
+                } else {
+                    v[0] = q[0];
+                }
+                add(v);
             }
         }
-        red[threadIdx.x][0] = s0;
-        red[threadIdx.x][1] = s1;
-        __syncthreads();
-        if (threadIdx.x < (unsigned)cw) {                         // groups in ascending order
-            float a0 = 0.f, a1 = 0.f;
-            for (int k = 0; k < groups; ++k) {
-                a0 += red[k * cw + threadIdx.x][0];
-                a1 += red[k * cw + threadIdx.x][1];
-            }
-            const int c = threadIdx.x * EPW;
-            if (c < C) part[(size_t)b * C + c] = a0;
-            if (EPW == 2 && c + 1 < C) part[(size_t)b * C + c + 1] = a1;
+    }
+#pragma unroll
+    for (int e = 0; e < NE; ++e) red[threadIdx.x][e] = acc[e];
+    __syncthreads();
+    if (threadIdx.x < (unsigned)cvn) {                            // groups in ascending order
+        float a[NE];
+#pragma unroll
+        for (int e = 0; e < NE; ++e) a[e] = 0.f;
+        for (int k = 0; k < groups; ++k)
+#pragma unroll
+            for (int e = 0; e < NE; ++e) a[e] += red[k * cvn + threadIdx.x][e];
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int c = threadIdx.x * NE + e;
+            if (c < C) part[(size_t)blockIdx.x * C + c] = a[e];
         }
-        __syncthreads();
     }
 }
 
-// db[c] = sum over tiles of part[b][c]: 64 channels per workgroup, the four waves take every fourth tile in ascending
-// order, then the four sums are added in ascending order of the wave
+// db[c] = sum over the workgroups' results part[w][c], w < min(n, G): 64 channels per workgroup, the four waves take
+// every fourth result in ascending order, then the four sums are added in ascending order of the wave
 __global__ __launch_bounds__(256) void tile_bias_sum(const float *__restrict__ part, const int32_t *__restrict__ count, int cap,
-                                                     int C, float *__restrict__ db) {
+                                                     int G, int C, float *__restrict__ db) {
     __shared__ float slice[4][64];
     const int lane = threadIdx.x & 63, k = threadIdx.x >> 6;
     const int c = blockIdx.x * 64 + lane;
     int n = *count;
     if (n > cap) n = cap;
+    if (n > G) n = G;
     float acc = 0.f;
     if (c < C) {
         for (int b = k; b < n; b += 32) {
@@ -165,15 +205,21 @@ extern "C" sbnet_status sbnet_bias_backward_on_tiles(const void *dy_tiles, sbnet
     const int es = elem_bytes(dtype);
     if ((long long)C * es % 4) return fail(SBNET_EUNSUPPORTED, "%s: a pixel's channels must fill 4-byte words", who);
     const int cw = C * es / 4;
-    if (cw > 256) return fail(SBNET_EUNSUPPORTED, "%s: more than 256 words of channels per pixel", who);
+    const bool vec = cw % 4 == 0 && ((uintptr_t)dy_tiles & 15) == 0;   // 16-byte loads
+    if ((vec ? cw / 4 : cw) > 256) return fail(SBNET_EUNSUPPORTED, "%s: too many channels per pixel", who);
     if (((uintptr_t)dy_tiles & 3) || ((uintptr_t)workspace & 3)) return fail(SBNET_EINVAL, "%s: pointers must be 4-byte aligned", who);
     if (workspace_bytes < sbnet_bias_backward_workspace_bytes(cap, C)) return fail(SBNET_EINVAL, "%s: workspace too small", who);
     hipStream_t s = (hipStream_t)stream;
     float *part = (float *)workspace;
     if (cap > 0) {
-        const int grid = cap < 4096 ? cap : 4096;
-#define SBNET_BP(DT) hipLaunchKernelGGL(tile_bias_partial<DT>, dim3(grid), dim3(256), 0, s, (const uint32_t *)dy_tiles, count, \
-                                        cap, pixels, C, cw, part)
+        const int grid = cap < 256 ? cap : 256;
+#define SBNET_BP(DT)                                                                                                  \
+    do {                                                                                                             \
+        if (vec) hipLaunchKernelGGL((tile_bias_partial<DT, 4>), dim3(grid), dim3(256), 0, s, (const uint32_t *)dy_tiles, \
+                                    count, cap, pixels, C, cw, part);                                               \
+        else hipLaunchKernelGGL((tile_bias_partial<DT, 1>), dim3(grid), dim3(256), 0, s, (const uint32_t *)dy_tiles,    \
+                                count, cap, pixels, C, cw, part);                                                   \
+    } while (0)
         if (dtype == SBNET_F32) SBNET_BP(SBNET_F32);
         else if (dtype == SBNET_BF16) SBNET_BP(SBNET_BF16);
         else SBNET_BP(SBNET_F16);
@@ -181,6 +227,6 @@ extern "C" sbnet_status sbnet_bias_backward_on_tiles(const void *dy_tiles, sbnet
         sbnet_status st = launch_status(who);
         if (st != SBNET_OK) return st;
     }
-    hipLaunchKernelGGL(tile_bias_sum, dim3((C + 63) / 64), dim3(256), 0, s, part, count, cap, C, db);
+    hipLaunchKernelGGL(tile_bias_sum, dim3((C + 63) / 64), dim3(256), 0, s, part, count, cap, cap < 256 ? cap : 256, C, db);
     return launch_status(who);
 }
