@@ -358,6 +358,20 @@ sbnet_status sbnet_conv_on_tiles_f8(const void *tiles_in_f8, const int32_t *coun
  * sbnet_bottleneck_backward_workspace_bytes(...) bytes, overwritten (it holds dL/dt2, dL/dt1 and the
  * scratch of the single calls).  The unit's identity path adds dL/dy to dL/dx outside this call.
  */
+/*
+ * The forward pass that keeps what the call below needs: the residual branch of sbnet_bottleneck_on_tiles
+ * as its three convolutions in single calls, writing t1 (with the positions outside the H x W image set
+ * to zero, [cap][th][tw][Cm]), t2 ([cap][th-2][tw-2][Cm]) and t3 ([cap][th-2][tw-2][C]).  Weights from
+ * sbnet_pack_weights, biases float32 or NULL; any element type and channel counts the tile convolution
+ * takes.  th, tw = g_in->bsize.  The results equal the fused kernel's up to its rounding of t1 and t2.
+ */
+sbnet_status sbnet_bottleneck_forward_keep_on_tiles(const void *tiles_in, sbnet_dtype dtype, int H, int W,
+                                                    int C, int Cm, const int32_t *indices,
+                                                    const int32_t *count, int cap,
+                                                    const sbnet_geom *g_in, const void *w1,
+                                                    const float *b1, const void *w2, const float *b2,
+                                                    const void *w3, const float *b3, void *t1, void *t2,
+                                                    void *t3, void *stream);
 size_t sbnet_bottleneck_backward_workspace_bytes(sbnet_dtype dtype, int cap, int th, int tw, int C,
                                                  int Cm);
 sbnet_status sbnet_bottleneck_backward_on_tiles(const void *tiles_in, const void *t1, const void *t2,

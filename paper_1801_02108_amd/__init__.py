@@ -64,6 +64,8 @@ _SIGNATURES = {
     "sbnet_pack_weights_f8": (_ci, [_vp, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_conv_on_tiles_f8": (_ci, [_vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci,
                                      ctypes.c_float, _vp, _vp]),
+    "sbnet_bottleneck_forward_keep_on_tiles": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp, _vp, _vp,
+                                                     _vp, _vp, _vp, _vp, _vp, _vp]),
     "sbnet_bottleneck_backward_workspace_bytes": (_sz, [_ci, _ci, _ci, _ci, _ci, _ci]),
     "sbnet_bottleneck_backward_on_tiles": (_ci, [_vp, _vp, _vp, _vp, _ci, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _vp,
                                                  _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -368,6 +370,22 @@ def conv_on_tiles_f8(tiles_f8, count, w_packed, bias=None, stride=1, relu=False,
     _check(lib().sbnet_conv_on_tiles_f8(_ptr(tiles_f8), _ptr(count), cap, th, tw, Cin, _ptr(w_packed.buf), _ptr(bias), kh,
                                         kw, stride, stride, Cout, int(bool(relu)), float(out_scale), _ptr(out), _stream()))
     return out
+
+
+def bottleneck_forward_keep_on_tiles(tiles, indices, count, g_in, H, W, weights):
+    """Residual branch on tiles with its activations kept for the backward pass: returns (t1, t2, t3).
+    weights = (w1, b1, w2, b2, w3, b3) as sparse_bottleneck takes them."""
+    _dev(tiles, "tiles"), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    w1, b1, w2, b2, w3, b3 = weights
+    cap, th, tw, C = tiles.shape
+    Cm = w1.shape[3]
+    assert (th, tw) == (g_in.bsize_h, g_in.bsize_w) and cap == indices.shape[0]
+    new = lambda h, w, c: torch.empty((cap, h, w, c), dtype=tiles.dtype, device=tiles.device)
+    t1, t2, t3 = new(th, tw, Cm), new(th - 2, tw - 2, Cm), new(th - 2, tw - 2, C)
+    _check(lib().sbnet_bottleneck_forward_keep_on_tiles(_ptr(tiles), _dt(tiles), H, W, C, Cm, _ptr(indices), _ptr(count), cap,
+                                                        g_in, _ptr(w1.buf), _ptr(b1), _ptr(w2.buf), _ptr(b2), _ptr(w3.buf),
+                                                        _ptr(b3), _ptr(t1), _ptr(t2), _ptr(t3), _stream()))
+    return t1, t2, t3
 
 
 def bottleneck_backward_on_tiles(tiles, t1, t2, dt3, count, weights_t, workspace=None):

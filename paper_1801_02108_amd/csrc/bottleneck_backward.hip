@@ -1,4 +1,4 @@
-// Backward pass of the residual branch of a sparse bottleneck unit on tiles (Sec. 3.3 of arXiv 1801.02108; training
+// Training forward and backward of the residual branch of a sparse bottleneck unit on tiles (Sec. 3.3 of arXiv 1801.02108; training
 // is the subject of the section's last paragraph), as a composition of the library's own calls: no kernel lives here.
 // With the forward pass  t1 = zero_outside(ReLU(W1 x + b1)),  t2 = ReLU(W2 * t1 + b2),  t3 = W3 t2 + b3  kept by the
 // caller (the fused forward kernel does not keep t1 and t2; a training forward runs the three convolutions as
@@ -9,6 +9,8 @@
 //   dW1 = x^T dt1,  db1 = sum dt1,  dx = dt1 W1^T
 // Every step is one of sbnet_conv_on_tiles_backward_weights / _backward_data, sbnet_bias_backward_on_tiles and
 // sbnet_relu_backward_on_tiles; the workspace holds dt2, dt1 and the largest scratch any of them asks for.
+// The matching forward pass that keeps t1 and t2 is the same three convolutions as single calls plus the zeroing of
+// t1 outside the image.
 #include "common.h"
 
 using namespace sbnet;
@@ -89,4 +91,24 @@ extern "C" sbnet_status sbnet_bottleneck_backward_on_tiles(const void *tiles_in,
     SBNET_STEP(sbnet_conv_on_tiles_backward_data(dt1, dtype, count, cap, th, tw, C, w1_t, 1, 1, 1, 1, Cm, dtiles_in, scratch, sb, stream));
 #undef SBNET_STEP
     return SBNET_OK;
+}
+
+
+extern "C" sbnet_status sbnet_bottleneck_forward_keep_on_tiles(const void *tiles_in, sbnet_dtype dtype, int H, int W, int C, int Cm,
+                                                               const int32_t *indices, const int32_t *count, int cap,
+                                                               const sbnet_geom *g_in, const void *w1, const float *b1,
+                                                               const void *w2, const float *b2, const void *w3,
+                                                               const float *b3, void *t1, void *t2, void *t3, void *stream) {
+    const char *who = "sbnet_bottleneck_forward_keep_on_tiles";
+    if (!tiles_in || !indices || !count || !g_in || !w1 || !w2 || !w3 || !t1 || !t2 || !t3)
+        return fail(SBNET_EINVAL, "%s: null pointer", who);
+    if (!geom_ok(g_in) || g_in->bsize_h < 3 || g_in->bsize_w < 3) return fail(SBNET_EINVAL, "%s: bad geometry", who);
+    const int th = g_in->bsize_h, tw = g_in->bsize_w;
+    sbnet_status st = sbnet_conv_on_tiles(tiles_in, dtype, count, cap, th, tw, C, w1, b1, 1, 1, 1, 1, Cm, 1, t1, stream);
+    if (st != SBNET_OK) return st;
+    st = sbnet_zero_outside(t1, dtype, H, W, Cm, indices, count, cap, g_in, stream);
+    if (st != SBNET_OK) return st;
+    st = sbnet_conv_on_tiles(t1, dtype, count, cap, th, tw, Cm, w2, b2, 3, 3, 1, 1, Cm, 1, t2, stream);
+    if (st != SBNET_OK) return st;
+    return sbnet_conv_on_tiles(t2, dtype, count, cap, th - 2, tw - 2, Cm, w3, b3, 1, 1, 1, 1, C, 0, t3, stream);
 }

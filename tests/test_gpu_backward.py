@@ -258,6 +258,12 @@ def test_residual_unit_backward_composed_from_single_calls(C, dens):
         assert_close(to_host(got), want, tol, name)
     ref_tiles_r = torch.from_numpy(ref[0]).to(TORCH_DT[dtype]).to(torch.float64).numpy()
     assert_close(to_host(dx), orc.gather_backward(ref_tiles_r, idx_np, og_in, np.zeros((N, H, W, C))), tol, "dx")
+    # the forward pass that keeps its activations, as one call: the same t1 and t2, and t3 against the oracle's branch
+    k1, k2, k3 = sb.bottleneck_forward_keep_on_tiles(tiles, idx, cnt, g_in, H, W, (sb.pack_weights(dev(w1)), fb(b1), sb.pack_weights(dev(w2)),
+                                                                                     fb(b2), sb.pack_weights(dev(w3)), fb(b3)))
+    assert torch.equal(k1[:n], t1[:n]) and torch.equal(k2[:n], t2[:n])
+    assert_close(to_host(k3)[:n], orc.bottleneck_on_tiles(orc.gather(x, idx_np, og_in), idx_np, og_in, H, W, w1, b1, w2, b2, w3, b3),
+                 tol, "t3 of the keeping forward pass")
     # the one-call form runs the same sequence: the same bits
     one = sb.bottleneck_backward_on_tiles(tiles, t1, t2, d3, cnt, (sb.pack_weights_transposed(dev(w1)),
                                                                     sb.pack_weights_transposed(dev(w2)),
