@@ -1,4 +1,5 @@
-// 3x3 tile convolution for any stride and tile size, bf16 / f16 with channel counts that are multiples of 8
+// 3x3 tile convolution for any stride and tile size, bf16 / f16 with channel counts that are multiples of 8, and
+// the pointwise (1x1) convolution with input channels in multiples of 64 through the same pipeline
 // (Sec. 3.2 of arXiv 1801.02108: the regular convolution that runs on every gathered block, here also for the
 // stride-2 geometry of Fig. 3 and the wider layers of the later backbone stages; in fused mode also the gather
 // before it and the scatter / scatter-add after it, Sec. 3.4).
@@ -73,7 +74,9 @@ struct Chunk3 {
     uint32_t wofs;           // byte offset of (group, tap 0, channel c0) in the packed weights
 };
 
-template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
+// KH = 3: the 3x3 kernel this file is named for; KH = 1: pointwise convolutions through the same pipeline (one tap,
+// chunks of 64 channels so that a chunk still holds several MFMA steps).
+template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI, int KH = 3>
 __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) {
     static_assert(FUSED || !ADD, "adding into the output is part of the fused form");
     // Register sets for chunks in flight.  Two (requests two chunks further ahead) were measured for the small
@@ -82,7 +85,8 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
     constexpr int RS = 1;
     constexpr int CV = CC / 8;                       // 16-byte vectors per pixel and chunk
     constexpr int KST = CC / 16;                     // k-steps of 16 channels per tap
-    constexpr int NS = 9 * KST;                      // MFMA steps per chunk
+    constexpr int TAPS = KH * KH;
+    constexpr int NS = TAPS * KST;                   // MFMA steps per chunk
     constexpr int PS = CC * 2 + 16;                  // LDS bytes per input pixel
     constexpr int WVEC = NS * 128;                   // vectors of a weight chunk: steps x 2 blocks of 32 channels x 64 lanes
     constexpr int NVW = (WVEC + 255) / 256;
@@ -265,11 +269,11 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
         for (int i = tid; i < q.ngroups * 64; i += 256) bl[i] = (p.bias && i < p.Cout) ? p.bias[i] : 0.f;
     }
     // tap offsets in the de-interleaved layout
-    uint32_t tapoff[9];
+    uint32_t tapoff[TAPS];
 #pragma unroll
-    for (int r = 0; r < 3; ++r)
+    for (int r = 0; r < KH; ++r)
 #pragma unroll
-        for (int t = 0; t < 3; ++t) tapoff[r * 3 + t] = (uint32_t)((r * p.sw + t % p.sw) * q.cpp + t / p.sw) * PS;
+        for (int t = 0; t < KH; ++t) tapoff[r * KH + t] = (uint32_t)((r * p.sw + t % p.sw) * q.cpp + t / p.sw) * PS;
     uint32_t floor16 = p.relu ? 0u : 0x80008000u;    // ReLU on a pair of rounded values: integer max with 0 (or with -32768: identity)
     asm volatile("" : "+s"(floor16));
     int floor_i = p.relu ? 0 : (int)0x80000000;
@@ -470,10 +474,10 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
     }
 }
 
-template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
+template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI, int KH = 3>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void conv3_kernel(ConvParams p, Plan3 q) {
-    conv3_body<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI>(p, q);
+    conv3_body<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI, KH>(p, q);
 }
 
 // The 256-pixel and the 128-pixel tile shape in one launch: the device-side count picks one (rounds of work on 256
@@ -516,21 +520,25 @@ static Shape3 plan3(const ConvParams &p, int pp) {
     // input rows a pass of pp consecutive output pixels can touch
     long long out_rows = (pp + p.ow - 1) / p.ow + ((pp % p.ow) ? 1 : 0);
     if (out_rows > p.oh) out_rows = p.oh;
-    long long rows = (out_rows - 1) * p.sh + 3;
+    long long rows = (out_rows - 1) * p.sh + p.kh;
     if (rows > p.th) rows = p.th;
     q.cpp = (p.tw + p.sw - 1) / p.sw;
-    q.ks16 = 9 * (CinP / 16);
+    const int taps = p.kh * p.kw;
+    q.ks16 = taps * (CinP / 16);
     q.w_bytes = (uint32_t)((size_t)q.ngroups * q.ks16 * 2048);
     const size_t bias_bytes = (size_t)q.ngroups * 64 * 4;
     // chunks of 32 channels with up to 6 input vectors per thread, else of 16 with up to 9 (kernels are built for
     // 3 / 6 and 5 / 9: every vector costs its staging instructions whether it carries data or not); two buffers must fit
-    for (int cc = 32; cc >= 16; cc -= 16) {
+    // a pointwise kernel has one tap: chunks of 64 channels (up to 9 vectors per thread; kernels built for 5 / 9) keep
+    // four MFMA steps in a chunk
+    for (int cc = (taps == 1 ? 64 : 32); cc >= (taps == 1 ? 64 : 16); cc -= 16) {
+        if (CinP % cc) continue;
         const long long nvec = rows * p.tw * (cc / 8);
         const long long need = (nvec + 255) / 256;
         if (need > (cc == 32 ? 6 : 9)) continue;
         sh.nvi = cc == 32 ? (need <= 3 ? 3 : 6) : (need <= 5 ? 5 : 9);
         const long long in_b = rows * p.sw * q.cpp * (cc * 2 + 16);
-        const long long buf = in_b + 9 * (cc / 16) * 2048;
+        const long long buf = in_b + (long long)taps * (cc / 16) * 2048;
         const long long total = 2 * buf + kDump3 + 4 * kOst3 + (long long)bias_bytes;
         if (total > kLds3) continue;
         sh.cc = cc;
@@ -559,7 +567,19 @@ static void launch3_cc(const ConvParams &p, const Shape3 &sh, int grid, hipStrea
                                       (int)sh.lds_bytes);                                                      \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), sh.lds_bytes, s, p, sh.q);                             \
     } while (0)
-    if (sh.cc == 32 && sh.nvi == 3) SBNET_L3(32, 3);
+    if (sh.cc == 64) {                                // pointwise
+#define SBNET_L1(NVI)                                                                                          \
+    do {                                                                                                       \
+        auto kern = conv3_kernel<DT, FUSED, ADD, 64, WP, CBW, PBW, NVI, 1>;                                    \
+        if (sh.lds_bytes > 48 * 1024)                                                                          \
+            (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,          \
+                                      (int)sh.lds_bytes);                                                      \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), sh.lds_bytes, s, p, sh.q);                             \
+    } while (0)
+        if (sh.nvi == 5) SBNET_L1(5);
+        else SBNET_L1(9);
+#undef SBNET_L1
+    } else if (sh.cc == 32 && sh.nvi == 3) SBNET_L3(32, 3);
     else if (sh.cc == 32) SBNET_L3(32, 6);
     else if (sh.nvi == 5) SBNET_L3(16, 5);
     else SBNET_L3(16, 9);
@@ -633,7 +653,7 @@ static void launch3_pair(sbnet_dtype dt, bool fused, const ConvParams &p, const 
 
 bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, sbnet_status *st, const char *who) {
     if (dt != SBNET_BF16 && dt != SBNET_F16) return false;
-    if (p0.kh != 3 || p0.kw != 3) return false;
+    if (p0.kh != p0.kw || (p0.kh != 3 && p0.kh != 1)) return false;
     if (p0.Cin % 8 != 0 || p0.Cout % 8 != 0) return false;
     // byte offsets inside one sample (fused) or one tile are kept in 32 bits and checked by the hardware
     // against a buffer descriptor of that size
@@ -642,12 +662,14 @@ bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, 
     ConvParams p = p0;
     p.CinP = (p.Cin + 31) / 32 * 32;
     const long long M = (long long)p.oh * p.ow;
-    if ((long long)((p.Cout + 63) / 64) * 9 * (p.CinP / 16) * 2048 >= (1LL << 31)) return false;
+    if ((long long)((p.Cout + 63) / 64) * p.kh * p.kw * (p.CinP / 16) * 2048 >= (1LL << 31)) return false;
 
     Shape3 big, small;
     big.ok = small.ok = false;
     if (M <= 64) {
         big = plan3(p, 64);
+    } else if (p.kh == 1) {
+        big = plan3(p, M > 128 ? 256 : 128);          // pointwise: one shape, chosen on the host
     } else {
         if (M > 128) big = plan3(p, 256);
         small = plan3(p, 128);
