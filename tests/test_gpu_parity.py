@@ -468,6 +468,35 @@ def test_conv_on_tiles_random_3x3_shapes(B, th, tw, Cin, Cout, s, dtype, relu, b
     assert (got[B] == 5.0).all()
 
 
+def _random_pointwise_shapes(n, seed):
+    """Seeded draws over what the pipelined pointwise path takes: input channels in multiples of 64, any tile and stride 1..2."""
+    r = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        out.append((int(r.integers(1, 5)), int(r.integers(1, 36)), int(r.integers(1, 36)), 64 * int(r.integers(1, 6)),
+                    8 * int(r.integers(1, 41)), int(r.integers(1, 3)), ("bf16", "f16")[int(r.integers(0, 2))],
+                    bool(r.integers(0, 2)), bool(r.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("B,th,tw,Cin,Cout,s,dtype,relu,bias", _random_pointwise_shapes(24, 1801021081))
+def test_conv_on_tiles_random_pointwise_shapes(B, th, tw, Cin, Cout, s, dtype, relu, bias):
+    """1x1 convolutions on tiles from one pixel to several passes, one to five 64-channel chunks, up to five channel groups."""
+    step("conv_on_tiles pointwise %s" % ((B, th, tw, Cin, Cout, s, dtype, relu, bias),))
+    r = gen.rng_for(4, th * 1000 + tw * 10 + Cin + Cout + s)
+    t = gen.activations(r, (B + 1, th, tw, Cin), dtype)
+    w = gen.conv_weights(r, 1, 1, Cin, Cout, dtype)
+    b = gen.bias_vector(r, Cout, 0.5) if bias else None
+    cnt = torch.tensor([B], dtype=torch.int32).cuda()
+    oh, ow = (th - 1) // s + 1, (tw - 1) // s + 1
+    out = torch.full((B + 1, oh, ow, Cout), 5.0, dtype=TORCH_DT[dtype]).cuda()
+    sb.conv_on_tiles(to_dev(t, dtype), cnt, sb.pack_weights(to_dev(w, dtype)), None if b is None else torch.from_numpy(b).cuda(),
+                     stride=s, relu=relu, out=out)
+    got = to_host(out)
+    assert_close(got[:B], orc.conv_valid(t[:B], w, b, stride=s, relu=relu), CONV_TOL[dtype], "conv_on_tiles")
+    assert (got[B] == 5.0).all()
+
+
 # --------------------------------------------------------------------------- fused sparse conv
 SPARSE_CASES = [
     # N, H, W, Cin, Cout, k, s, bo, dtype
@@ -478,6 +507,8 @@ SPARSE_CASES = [
     (2, 35, 35, 8, 8, 3, 2, 4, "bf16"),        # strided convolution
     (1, 24, 24, 6, 5, 3, 1, 8, "f32"),
     (1, 32, 32, 64, 256, 1, 1, 16, "bf16"),
+    (2, 45, 39, 128, 72, 1, 1, 8, "f16"),      # pointwise, fused, blocks hang over the edge, two chunks
+    (1, 50, 50, 64, 64, 1, 2, 8, "bf16"),      # pointwise stride 2: the shortcut of a downsampling unit
     # LDS-tiled 3x3 kernel
     (2, 70, 66, 96, 96, 3, 2, 16, "bf16"),     # downsampling unit, blocks hang over the edge, Cout % 64 == 32
     (1, 96, 80, 192, 32, 3, 1, 16, "f16"),     # six channel chunks
