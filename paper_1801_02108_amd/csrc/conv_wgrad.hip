@@ -44,7 +44,8 @@ template <int KH, int S, int NSEG>
 struct WgradShape {
     static constexpr int R = 8 / (S * NSEG);              // output rows per stage
     static constexpr int RX = (R - 1) * S + KH;           // input rows per stage
-    static constexpr int CPV = 2 * NSEG + 1;              // 16-byte vectors per phase row of x (one spare for the window)
+    // 16-byte vectors per phase row of x: 3x3 keeps one spare for the window of the taps; 1x1 reads 16 NSEG pixels only
+    static constexpr int CPV = KH == 1 ? 2 * NSEG : 2 * NSEG + 1;
     static constexpr int XPL = (RX * S * CPV + 7) / 8 * 8;
     static constexpr int CSX = XPL + 1;                   // vectors between channel planes of x (odd)
     static constexpr int GV = 2 * NSEG;                   // vectors per row of dout
@@ -53,7 +54,7 @@ struct WgradShape {
     static constexpr int XBYTES = 64 * CSX * 16;
     static constexpr int STAGE = 64 * (CSX + CSG) * 16;
     // staging items: four pixels of one phase row (or of one row of dout) times 8 channels
-    static constexpr int QX = (16 * NSEG + 2 + 3) / 4;    // items per phase row of x (at most 16 NSEG + 2 pixels)
+    static constexpr int QX = KH == 1 ? 4 * NSEG : (16 * NSEG + 2 + 3) / 4;    // items per phase row of x (at most 16 NSEG + KH - 1 pixels)
     static constexpr int QG = 4 * NSEG;                   // items per row of dout
     static constexpr int NIX = (RX * S * QX * 8 + 255) / 256;
     static constexpr int NIG = (R * QG * 8 + 255) / 256;
@@ -192,6 +193,7 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
     auto load_row = [&](Ops &o, const char *xb, int i, int q, int r) {
         const uint32_t v = (uint32_t)((i * S + r) * S * CPV + 2 * q + m);          // phase 0 of the row
         o.x[r][0] = lds_read16(xb + (v ^ swa) * 16);
+        if (KH == 1) return;                                                       // the one tap is vector 0
         o.x[r][1] = lds_read16(xb + ((v + 1) ^ swa) * 16);
         if (S == 2) o.x[r][XV - 1] = lds_read16(xb + ((v + CPV) ^ swa) * 16);      // phase 1
     };
@@ -374,7 +376,9 @@ bool plan_wgrad(sbnet_dtype dt, int cap, int th, int tw, int Cin, int kh, int kw
         q->nob = (Cout + 63) / 64;
         q->CinP = q->ncb * 64;
         q->CoutP = q->nob * 64;
-        int ns = 256 / (q->ncb * q->nob);
+        // one workgroup per CU for 3x3 (its two stages take 100 KB of LDS); two for 1x1 (70 KB), whose stages hold
+        // little matrix work and wait on memory: the second workgroup's loads fill that wait
+        int ns = (kh == 1 ? 512 : 256) / (q->ncb * q->nob);
         ns = ns / 8 * 8;                                   // splits of one channel block share an XCD's L2 with the others
         if (ns < 8) ns = 8;
         q->nsplit = ns;
