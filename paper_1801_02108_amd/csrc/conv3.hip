@@ -480,6 +480,14 @@ void conv3_kernel(ConvParams p, Plan3 q) {
     conv3_body<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI, KH>(p, q);
 }
 
+// Pointwise convolutions wait on memory, not on the matrix cores: their kernel is built for two workgroups per CU
+// (at most 256 registers, and the host picks a tile shape whose LDS plan fits twice).
+template <int DT, bool FUSED, bool ADD, int WP, int CBW, int PBW, int NVI>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void conv3_pointwise_kernel(ConvParams p, Plan3 q) {
+    conv3_body<DT, FUSED, ADD, 64, WP, CBW, PBW, NVI, 1>(p, q);
+}
+
 // The 256-pixel and the 128-pixel tile shape in one launch: the device-side count picks one (rounds of work on 256
 // CUs with either shape; an item of the smaller tile costs about 5/8 of a larger one: half the matrix work, the same
 // weights to stage).  Two separate launches, of which one returns, cost a launch more.
@@ -570,7 +578,7 @@ static void launch3_cc(const ConvParams &p, const Shape3 &sh, int grid, hipStrea
     if (sh.cc == 64) {                                // pointwise
 #define SBNET_L1(NVI)                                                                                          \
     do {                                                                                                       \
-        auto kern = conv3_kernel<DT, FUSED, ADD, 64, WP, CBW, PBW, NVI, 1>;                                    \
+        auto kern = conv3_pointwise_kernel<DT, FUSED, ADD, WP, CBW, PBW, NVI>;                                 \
         if (sh.lds_bytes > 48 * 1024)                                                                          \
             (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,          \
                                       (int)sh.lds_bytes);                                                      \
@@ -596,7 +604,8 @@ static void launch3_shape(const ConvParams &p, const Shape3 &sh, int grid, hipSt
 static void launch3(sbnet_dtype dt, bool fused, const ConvParams &p, const Shape3 &sh, hipStream_t s) {
     long long items = (long long)p.cap * sh.q.mpasses * sh.q.ngroups;
     long long g = (items + 7) / 8 * 8;
-    if (g > 256) g = 256;                             // one persistent workgroup per CU
+    const long long most = sh.cc == 64 && 2 * sh.lds_bytes <= (size_t)kLds3 ? 512 : 256;   // persistent workgroups: one per CU, two for pointwise
+    if (g > most) g = most;
     const int grid = (int)g;
     if (dt == SBNET_BF16) {
         if (fused && p.add) launch3_shape<SBNET_BF16, true, true>(p, sh, grid, s);
@@ -669,7 +678,12 @@ bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, 
     if (M <= 64) {
         big = plan3(p, 64);
     } else if (p.kh == 1) {
-        big = plan3(p, M > 128 ? 256 : 128);          // pointwise: one shape, chosen on the host
+        // pointwise: one shape, chosen on the host; a smaller tile if that lets two workgroups share a CU
+        big = plan3(p, M > 128 ? 256 : 128);
+        if (!big.ok || 2 * big.lds_bytes > (size_t)kLds3) {
+            Shape3 alt = plan3(p, 128);
+            if (alt.ok && (!big.ok || 2 * alt.lds_bytes <= (size_t)kLds3)) big = alt;
+        }
     } else {
         if (M > 128) big = plan3(p, 256);
         small = plan3(p, 128);

@@ -73,6 +73,7 @@ WGRAD_CASES = [
     (4, 16, 16, 64, 32, 1, 1, "bf16"),       # 1x1: one accumulator per wave
     (40, 18, 18, 256, 64, 1, 1, "bf16"),     # first convolution of the residual unit on its input tile (two segments)
     (5, 16, 16, 64, 256, 1, 1, "f16"),       # its last convolution
+    (300, 16, 16, 64, 64, 1, 1, "bf16"),     # 1x1 with more tiles than splits: two or three tiles per workgroup
     (3, 17, 17, 32, 48, 1, 2, "bf16"),       # 1x1 at stride 2: 9 x 9 outputs, odd phase never read
     (4, 10, 10, 40, 24, 1, 1, "bf16"),
     (6, 17, 17, 64, 64, 1, 1, "bf16"),       # 289 pixels: one pixel in the last row of 16
