@@ -309,6 +309,12 @@ sbnet_status sbnet_conv_on_tiles_backward_weights(const void *tiles_in, const vo
  * fp32 sums in a fixed order, no atomics.  C * element size a multiple of 4 bytes and at most 1 KiB
  * (4 KiB where it is a multiple of 16 bytes and dy_tiles is 16-byte aligned).
  * workspace: device, 4-byte aligned, sbnet_bias_backward_workspace_bytes(cap, C) bytes, overwritten.
+ *
+ * sbnet_relu_bias_backward_on_tiles: both in one pass over the gradient that enters a convolution
+ * through its ReLU: dout = dy where y > 0, else 0, and db[c] = the sum of dout over the active tiles
+ * and their pixels; same results, bit for bit, as the two calls above in that order.  Tiles of
+ * `pixels` pixels with C channels; dout may be dy; limits and workspace as for
+ * sbnet_bias_backward_on_tiles (16-byte accesses need all three stacks 16-byte aligned).
  */
 sbnet_status sbnet_relu_backward_on_tiles(const void *y_tiles, const void *dy_tiles, sbnet_dtype dtype,
                                           const int32_t *count, int cap, size_t tile_elems,
@@ -317,6 +323,11 @@ size_t sbnet_bias_backward_workspace_bytes(int cap, int C);
 sbnet_status sbnet_bias_backward_on_tiles(const void *dy_tiles, sbnet_dtype dtype, const int32_t *count,
                                           int cap, int pixels, int C, float *db, void *workspace,
                                           size_t workspace_bytes, void *stream);
+sbnet_status sbnet_relu_bias_backward_on_tiles(const void *y_tiles, const void *dy_tiles,
+                                               sbnet_dtype dtype, const int32_t *count, int cap,
+                                               int pixels, int C, void *dout_tiles, float *db,
+                                               void *workspace, size_t workspace_bytes,
+                                               void *stream);
 
 /*
  * FP8 variant of the tile convolution (the paper fixes no precision for the convolution between

@@ -60,6 +60,7 @@ _SIGNATURES = {
     "sbnet_relu_backward_on_tiles": (_ci, [_vp, _vp, _ci, _vp, _ci, _sz, _vp, _vp]),
     "sbnet_bias_backward_workspace_bytes": (_sz, [_ci, _ci]),
     "sbnet_bias_backward_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _vp, _vp, _sz, _vp]),
+    "sbnet_relu_bias_backward_on_tiles": (_ci, [_vp, _vp, _ci, _vp, _ci, _ci, _ci, _vp, _vp, _vp, _sz, _vp]),
     "sbnet_quantize_f8": (_ci, [_vp, _ci, _sz, ctypes.c_float, _vp, _vp]),
     "sbnet_pack_weights_f8": (_ci, [_vp, _ci, _ci, _ci, _ci, _vp, ctypes.POINTER(_sz), _vp]),
     "sbnet_conv_on_tiles_f8": (_ci, [_vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci,
@@ -331,6 +332,25 @@ def bias_backward_on_tiles(dy_tiles, count, workspace=None):
     _check(lib().sbnet_bias_backward_on_tiles(_ptr(dy_tiles), _dt(dy_tiles), _ptr(count), cap, h * w, C, _ptr(db),
                                               _ptr(workspace), workspace.numel(), _stream()))
     return db
+
+
+def relu_bias_backward_on_tiles(y_tiles, dy_tiles, count, out=None, workspace=None):
+    """(dout, db): dy [cap,h,w,C] masked by y > 0 on the active tiles, and its per-channel sum (float32 [C]), in one pass."""
+    _dev(y_tiles, "y_tiles"), _dev(dy_tiles, "dy_tiles", y_tiles.dtype), _dev(count, "count", torch.int32)
+    assert y_tiles.shape == dy_tiles.shape
+    cap, h, w, C = dy_tiles.shape
+    if out is None:
+        out = torch.empty_like(dy_tiles)
+    _dev(out, "out", dy_tiles.dtype)
+    assert out.shape == dy_tiles.shape
+    need = lib().sbnet_bias_backward_workspace_bytes(cap, C)
+    if workspace is None:
+        workspace = torch.empty((max(need, 4),), dtype=torch.uint8, device=dy_tiles.device)
+    _dev(workspace, "workspace", torch.uint8)
+    db = torch.empty((C,), dtype=torch.float32, device=dy_tiles.device)
+    _check(lib().sbnet_relu_bias_backward_on_tiles(_ptr(y_tiles), _ptr(dy_tiles), _dt(dy_tiles), _ptr(count), cap, h * w, C,
+                                                   _ptr(out), _ptr(db), _ptr(workspace), workspace.numel(), _stream()))
+    return out, db
 
 
 def quantize_f8(x, scale=1.0, out=None):

@@ -8,7 +8,8 @@
 //                                                                              mask also blocks the gradient there)
 //   dW1 = x^T dt1,  db1 = sum dt1,  dx = dt1 W1^T
 // Every step is one of sbnet_conv_on_tiles_backward_weights / _backward_data, sbnet_bias_backward_on_tiles and
-// sbnet_relu_backward_on_tiles; the workspace holds dt2, dt1 and the largest scratch any of them asks for.
+// sbnet_relu_bias_backward_on_tiles (the ReLU mask and the bias sum of the masked gradient in one pass); the workspace
+// holds dt2, dt1 and the largest scratch any of them asks for.
 // The matching forward pass that keeps t1 and t2 is the same three convolutions as single calls plus the zeroing of
 // t1 outside the image.
 #include "common.h"
@@ -79,15 +80,13 @@ extern "C" sbnet_status sbnet_bottleneck_backward_on_tiles(const void *tiles_in,
     SBNET_STEP(sbnet_conv_on_tiles_backward_weights(t2, dt3, dtype, count, cap, oh, ow, Cm, 1, 1, 1, 1, C, dw3, scratch, sb, stream));
     SBNET_STEP(sbnet_bias_backward_on_tiles(dt3, dtype, count, cap, oh * ow, C, db3, scratch, sb, stream));
     SBNET_STEP(sbnet_conv_on_tiles_backward_data(dt3, dtype, count, cap, oh, ow, Cm, w3_t, 1, 1, 1, 1, C, dt2, scratch, sb, stream));
-    SBNET_STEP(sbnet_relu_backward_on_tiles(t2, dt2, dtype, count, cap, (size_t)oh * ow * Cm, dt2, stream));
+    SBNET_STEP(sbnet_relu_bias_backward_on_tiles(t2, dt2, dtype, count, cap, oh * ow, Cm, dt2, db2, scratch, sb, stream));
     // second convolution (3x3 valid, Cm -> Cm)
     SBNET_STEP(sbnet_conv_on_tiles_backward_weights(t1, dt2, dtype, count, cap, th, tw, Cm, 3, 3, 1, 1, Cm, dw2, scratch, sb, stream));
-    SBNET_STEP(sbnet_bias_backward_on_tiles(dt2, dtype, count, cap, oh * ow, Cm, db2, scratch, sb, stream));
     SBNET_STEP(sbnet_conv_on_tiles_backward_data(dt2, dtype, count, cap, th, tw, Cm, w2_t, 3, 3, 1, 1, Cm, dt1, scratch, sb, stream));
-    SBNET_STEP(sbnet_relu_backward_on_tiles(t1, dt1, dtype, count, cap, (size_t)th * tw * Cm, dt1, stream));
+    SBNET_STEP(sbnet_relu_bias_backward_on_tiles(t1, dt1, dtype, count, cap, th * tw, Cm, dt1, db1, scratch, sb, stream));
     // first convolution (1x1, C -> Cm)
     SBNET_STEP(sbnet_conv_on_tiles_backward_weights(tiles_in, dt1, dtype, count, cap, th, tw, C, 1, 1, 1, 1, Cm, dw1, scratch, sb, stream));
-    SBNET_STEP(sbnet_bias_backward_on_tiles(dt1, dtype, count, cap, th * tw, Cm, db1, scratch, sb, stream));
     SBNET_STEP(sbnet_conv_on_tiles_backward_data(dt1, dtype, count, cap, th, tw, C, w1_t, 1, 1, 1, 1, Cm, dtiles_in, scratch, sb, stream));
 #undef SBNET_STEP
     return SBNET_OK;

@@ -319,13 +319,15 @@ __global__ __launch_bounds__(256) void wgrad_direct(WgradParams p) {
     p.part[(size_t)sigma * split_stride(p.kh * p.kw, p.CinP, p.CoutP) + e] = acc;
 }
 
-// dw[tap][c][o] = partial results of the splits that had a tile, added in a fixed order: the four waves of a workgroup
-// each add every fourth split in ascending order (many independent loads in flight, where one chain of dependent
-// loads would be bound by latency), then the four sums are added in ascending order of the wave.
-__global__ __launch_bounds__(256) void wgrad_sum(const float *__restrict__ part, const int32_t *__restrict__ count, int cap,
-                                                 int nsplit, int taps, int Cin, int Cout, int CinP, int CoutP,
-                                                 float *__restrict__ dw) {
-    __shared__ float slice[4][64];
+// dw[tap][c][o] = partial results of the splits that had a tile, added in a fixed order: the NW waves of a workgroup
+// each add every NW-th split in ascending order (many independent loads in flight, where one chain of dependent
+// loads would be bound by latency), then the NW sums are added in ascending order of the wave.  NW = 16 where the
+// weights fill at most 256 workgroups (1x1 kernels: the launch is short and the splits are many), else 4.
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void wgrad_sum(const float *__restrict__ part, const int32_t *__restrict__ count, int cap,
+                                                  int nsplit, int taps, int Cin, int Cout, int CinP, int CoutP,
+                                                  float *__restrict__ dw) {
+    __shared__ float slice[NW][64];
     const int total = taps * Cin * Cout;
     const int lane = threadIdx.x & 63, k = threadIdx.x >> 6;
     const int e = blockIdx.x * 64 + lane;
@@ -337,11 +339,11 @@ __global__ __launch_bounds__(256) void wgrad_sum(const float *__restrict__ part,
         const int o = e % Cout, c = (e / Cout) % Cin, tap = e / (Cout * Cin);
         const size_t at = ((size_t)tap * CinP + c) * CoutP + o, step = split_stride(taps, CinP, CoutP);
         // batches of 8 loads in flight (splits beyond the last read as the first one and count as zero)
-        for (int s = k; s < n; s += 32) {
+        for (int s = k; s < n; s += 8 * NW) {
             float a[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int sj = s + 4 * j;
+                const int sj = s + NW * j;
                 const float v = part[at + (size_t)(sj < n ? sj : 0) * step];
                 a[j] = sj < n ? v : 0.f;
             }
@@ -351,7 +353,12 @@ __global__ __launch_bounds__(256) void wgrad_sum(const float *__restrict__ part,
     }
     slice[k][lane] = acc;
     __syncthreads();
-    if (k == 0 && e < total) dw[e] = ((slice[0][lane] + slice[1][lane]) + slice[2][lane]) + slice[3][lane];
+    if (k == 0 && e < total) {
+        float t = slice[0][lane];
+#pragma unroll
+        for (int i = 1; i < NW; ++i) t += slice[i][lane];
+        dw[e] = t;
+    }
 }
 
 struct WgradPlan {
@@ -475,8 +482,13 @@ extern "C" sbnet_status sbnet_conv_on_tiles_backward_weights(const void *tiles_i
         sbnet_status st = launch_status(who);
         if (st != SBNET_OK) return st;
     }
-    hipLaunchKernelGGL(wgrad_sum, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, s, (const float *)workspace, count, cap,
-                       q.nsplit, taps, Cin, Cout, q.CinP, q.CoutP, dw);
+    const unsigned sum_grid = (unsigned)((total + 63) / 64);
+    if (sum_grid <= 256)
+        hipLaunchKernelGGL(wgrad_sum<16>, dim3(sum_grid), dim3(1024), 0, s, (const float *)workspace, count, cap, q.nsplit, taps,
+                           Cin, Cout, q.CinP, q.CoutP, dw);
+    else
+        hipLaunchKernelGGL(wgrad_sum<4>, dim3(sum_grid), dim3(256), 0, s, (const float *)workspace, count, cap, q.nsplit, taps,
+                           Cin, Cout, q.CinP, q.CoutP, dw);
     return launch_status(who);
 }
 

@@ -90,6 +90,15 @@ def test_gradient_and_normalisation_calls_check_their_arguments_on_the_host():
     assert lib.sbnet_conv_backward_weights_workspace_bytes(sb.BF16, 4, 2, 2, 8, 3, 3, 1, 1, 8) == 0     # tile < kernel
     assert lib.sbnet_conv_on_tiles_backward_weights(None, None, sb.BF16, None, 4, 6, 6, 8, 3, 3, 1, 1, 8, None, None, 0,
                                                     None) == sb.EINVAL
+    # ReLU mask and bias sum in one pass: refused without the activation or the place for the masked gradient,
+    # and for pixels whose channels do not fill 4-byte words
+    buf0 = (ctypes.c_char * 4096)()
+    p0 = ctypes.cast(ctypes.byref(buf0, 16 - ctypes.addressof(buf0) % 16), ctypes.c_void_p)
+    assert lib.sbnet_relu_bias_backward_on_tiles(None, p0, sb.BF16, p0, 4, 9, 8, p0, p0, p0, 4096, None) == sb.EINVAL
+    assert lib.sbnet_relu_bias_backward_on_tiles(p0, p0, sb.BF16, p0, 4, 9, 8, None, p0, p0, 4096, None) == sb.EINVAL
+    assert lib.sbnet_relu_bias_backward_on_tiles(p0, p0, sb.BF16, p0, 4, 9, 3, p0, p0, p0, 4096, None) == sb.EUNSUPPORTED
+    assert lib.sbnet_relu_bias_backward_on_tiles(p0, p0, sb.BF16, p0, 4, 9, 8, p0, p0, p0, 8, None) == sb.EINVAL
+    assert b"workspace" in lib.sbnet_last_error()
     # normalisation
     assert lib.sbnet_bn_backward_workspace_bytes(10, 64) == (10 * 64 * 2 + 10 + 1) * 4
     assert lib.sbnet_bn_backward_workspace_bytes(0, 64) == 4

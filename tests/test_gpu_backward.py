@@ -204,6 +204,19 @@ def test_relu_and_bias_backward_on_tiles(B, h, w, C, dtype):
     db2 = sb.bias_backward_on_tiles(to_dev(dy, dtype), cnt)
     assert torch.equal(db, db2)
     assert (sb.bias_backward_on_tiles(to_dev(dy, dtype), torch.tensor([0], dtype=torch.int32).cuda()) == 0).all()
+    # both in one pass: the masked gradient bit for bit, its sum against the oracle and, bit for bit, against the sum
+    # the separate call makes of the masked stack
+    out2 = torch.full((B + 1, h, w, C), 3.0, dtype=TORCH_DT[dtype]).cuda()
+    _, dbm = sb.relu_bias_backward_on_tiles(to_dev(y, dtype), to_dev(dy, dtype), cnt, out=out2)
+    assert torch.equal(out2, out)
+    refm = orc.bias_backward(orc.relu_backward(y[:B], dy[:B]))
+    assert np.abs(dbm.cpu().numpy() - refm).max() <= 1e-5 * np.sqrt(B * h * w) + 1e-6
+    assert torch.equal(dbm, sb.bias_backward_on_tiles(out, cnt))
+    inplace = to_dev(dy, dtype)
+    _, dbi = sb.relu_bias_backward_on_tiles(to_dev(y, dtype), inplace, cnt, out=inplace)
+    assert torch.equal(inplace[:B], out[:B]) and torch.equal(inplace[B], to_dev(dy, dtype)[B]) and torch.equal(dbi, dbm)
+    _, db0 = sb.relu_bias_backward_on_tiles(to_dev(y, dtype), to_dev(dy, dtype), torch.tensor([0], dtype=torch.int32).cuda(), out=out2)
+    assert (db0 == 0).all() and torch.equal(out2, out)             # no active tile: nothing written, zero sums
 
 
 @pytest.mark.parametrize("C,dens", [(64, 0.02), (256, 0.004)])
