@@ -580,6 +580,16 @@ extern "C" sbnet_status sbnet_conv_on_tiles_backward_data(const void *dout_tiles
     if ((long long)ph * pw * (long long)row_bytes >= (1LL << 31))
         return fail(SBNET_EUNSUPPORTED, "%s: tile too large", who);
     hipStream_t s = (hipStream_t)stream;
+    if (sh == 1 && sw == 1 && kh == 1 && kw == 1) {
+        // A pointwise convolution has no frame either: its data gradient is the pointwise convolution of the tiles of
+        // dout with the exchanged weights, tile for tile.
+        ConvParams p = {};
+        p.in = dout_tiles; p.out = din_tiles; p.w = w_packed_t; p.bias = nullptr;
+        p.count = count; p.cap = cap;
+        p.th = th; p.tw = tw; p.Cin = Cout; p.Cout = Cin;
+        p.kh = 1; p.kw = 1; p.sh = 1; p.sw = 1; p.relu = 0;
+        return run_conv<false>(who, dtype, p, s);
+    }
     if (sh == 1 && sw == 1) {
         // No stride, nothing to spread: the frame of zeros is what the fused kernels read around an image anyway.
         // Every tile of dout is taken as a sample of its own (oh x ow), gathered with a window that starts kh-1 / kw-1
