@@ -453,7 +453,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); the path shards by blocks or samples "
-                 "without collectives, see DESIGN.md")
+                 "without collectives, each GPU running this same single-GPU path on its share")
     import numpy as np
     import torch
     import paper_1801_02108_amd as sb
