@@ -314,3 +314,35 @@ def test_weight_gradient_of_a_stack_beyond_two_gib():
     c, o = samples[0]
     last = float((xc[n - 1, ..., c].to(torch.float64) * gc[n - 1, ..., o].to(torch.float64)).sum())
     assert abs((got[0, 0, c, o] - dw2[0, 0, c, o]) - last) <= 4e-5 * scale
+
+
+def test_pointwise_forward_and_data_gradient_of_a_stack_beyond_two_gib():
+    """The same 2.24 GB stack through the pointwise kernel, once as the input of the residual unit's first convolution
+    (256 -> 64) and once as the result of that convolution's data gradient (64 -> 256): every tile is addressed from a
+    64-bit base through a descriptor of its own.  Sampled pixels, the last tile's among them, against fp64 dot products."""
+    step("pointwise forward / data gradient, stack beyond 2 GiB")
+    n, th, C, K = 13500, 18, 256, 64
+    gen_t = torch.Generator(device="cuda")
+    gen_t.manual_seed(gen.BASE_SEED + 29)
+    x = torch.randn((n, th, th, C), generator=gen_t, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    assert x.numel() * 2 > 2 ** 31
+    r = gen.rng_for(29)
+    w = gen.conv_weights(r, 1, 1, C, K, "bf16")
+    wd = to_dev(w, "bf16")
+    cnt = torch.tensor([n], dtype=torch.int32).cuda()
+    y = sb.conv_on_tiles(x, cnt, sb.pack_weights(wd), None, relu=False)
+    pts = [(int(r.integers(0, n)), int(r.integers(0, th)), int(r.integers(0, th))) for _ in range(40)]
+    pts += [(n - 1, th - 1, th - 1), (n - 1, 0, 0), (0, 0, 0), (n // 2, th - 1, 0)]
+    w64 = w[0, 0].astype(np.float64)
+    for b, i, j in pts:
+        want = x[b, i, j].to(torch.float64).cpu().numpy() @ w64
+        got = y[b, i, j].to(torch.float64).cpu().numpy()
+        assert_close(got, want, CONV_TOL["bf16"], "pointwise forward at %s" % ((b, i, j),))
+    # data gradient: dL/dx = dL/dy W^T, a stack of the size of x
+    del x
+    dx = sb.conv_on_tiles_backward_data(y, cnt, sb.pack_weights_transposed(wd), th, th)
+    assert dx.numel() * 2 > 2 ** 31
+    for b, i, j in pts:
+        want = w64 @ y[b, i, j].to(torch.float64).cpu().numpy()
+        got = dx[b, i, j].to(torch.float64).cpu().numpy()
+        assert_close(got, want, CONV_TOL["bf16"], "pointwise data gradient at %s" % ((b, i, j),))
