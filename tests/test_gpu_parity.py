@@ -479,7 +479,16 @@ def _random_pointwise_shapes(n, seed):
     return out
 
 
-@pytest.mark.parametrize("B,th,tw,Cin,Cout,s,dtype,relu,bias", _random_pointwise_shapes(24, 1801021081))
+POINTWISE_PADDED_CASES = [
+    # input channels that do not fill the last 64-channel chunk (40, 48, 104, 120 -> padded to 64 / 128)
+    (3, 18, 18, 48, 192, 1, "bf16", True, True),
+    (2, 11, 13, 40, 24, 1, "f16", False, True),
+    (4, 9, 9, 104, 64, 1, "bf16", True, False),
+    (2, 17, 17, 120, 40, 2, "bf16", False, True),
+]
+
+
+@pytest.mark.parametrize("B,th,tw,Cin,Cout,s,dtype,relu,bias", POINTWISE_PADDED_CASES + _random_pointwise_shapes(24, 1801021081))
 def test_conv_on_tiles_random_pointwise_shapes(B, th, tw, Cin, Cout, s, dtype, relu, bias):
     """1x1 convolutions on tiles from one pixel to several passes, one to five 64-channel chunks, up to five channel groups."""
     step("conv_on_tiles pointwise %s" % ((B, th, tw, Cin, Cout, s, dtype, relu, bias),))
