@@ -75,7 +75,7 @@ struct Chunk3 {
 };
 
 // KH = 3: the 3x3 kernel this file is named for; KH = 1: pointwise convolutions through the same pipeline (one tap,
-// chunks of 64 channels so that a chunk still holds several MFMA steps).
+// chunks of 64 channels so that a chunk still holds several MFMA steps; of 32 for channel counts that need it).
 template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI, int KH = 3>
 __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) {
     static_assert(FUSED || !ADD, "adding into the output is part of the fused form");
@@ -482,10 +482,10 @@ void conv3_kernel(ConvParams p, Plan3 q) {
 
 // Pointwise convolutions wait on memory, not on the matrix cores: their kernel is built for two workgroups per CU
 // (at most 256 registers, and the host picks a tile shape whose LDS plan fits twice).
-template <int DT, bool FUSED, bool ADD, int WP, int CBW, int PBW, int NVI>
+template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void conv3_pointwise_kernel(ConvParams p, Plan3 q) {
-    conv3_body<DT, FUSED, ADD, 64, WP, CBW, PBW, NVI, 1>(p, q);
+    conv3_body<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI, 1>(p, q);
 }
 
 // The 256-pixel and the 128-pixel tile shape in one launch: the device-side count picks one (rounds of work on 256
@@ -538,8 +538,8 @@ static Shape3 plan3(const ConvParams &p, int pp) {
     // chunks of 32 channels with up to 6 input vectors per thread, else of 16 with up to 9 (kernels are built for
     // 3 / 6 and 5 / 9: every vector costs its staging instructions whether it carries data or not); two buffers must fit
     // a pointwise kernel has one tap: chunks of 64 channels (up to 9 vectors per thread; kernels built for 5 / 9) keep
-    // four MFMA steps in a chunk
-    for (int cc = (taps == 1 ? 64 : 32); cc >= (taps == 1 ? 64 : 16); cc -= 16) {
+    // four MFMA steps in a chunk; channel counts that are no multiple of 64 take chunks of 32
+    for (int cc = (taps == 1 ? 64 : 32); cc >= (taps == 1 ? 32 : 16); cc -= (taps == 1 ? 32 : 16)) {
         if (CinP % cc) continue;
         const long long nvec = rows * p.tw * (cc / 8);
         const long long need = (nvec + 255) / 256;
@@ -575,17 +575,19 @@ static void launch3_cc(const ConvParams &p, const Shape3 &sh, int grid, hipStrea
                                       (int)sh.lds_bytes);                                                      \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), sh.lds_bytes, s, p, sh.q);                             \
     } while (0)
-    if (sh.cc == 64) {                                // pointwise
-#define SBNET_L1(NVI)                                                                                          \
+    if (p.kh == 1) {                                  // pointwise
+#define SBNET_L1(CC, NVI)                                                                                      \
     do {                                                                                                       \
-        auto kern = conv3_pointwise_kernel<DT, FUSED, ADD, WP, CBW, PBW, NVI>;                                 \
+        auto kern = conv3_pointwise_kernel<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI>;                             \
         if (sh.lds_bytes > 48 * 1024)                                                                          \
             (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,          \
                                       (int)sh.lds_bytes);                                                      \
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), sh.lds_bytes, s, p, sh.q);                             \
     } while (0)
-        if (sh.nvi == 5) SBNET_L1(5);
-        else SBNET_L1(9);
+        if (sh.cc == 64 && sh.nvi == 5) SBNET_L1(64, 5);
+        else if (sh.cc == 64) SBNET_L1(64, 9);
+        else if (sh.nvi == 3) SBNET_L1(32, 3);
+        else SBNET_L1(32, 6);
 #undef SBNET_L1
     } else if (sh.cc == 32 && sh.nvi == 3) SBNET_L3(32, 3);
     else if (sh.cc == 32) SBNET_L3(32, 6);
@@ -604,7 +606,7 @@ static void launch3_shape(const ConvParams &p, const Shape3 &sh, int grid, hipSt
 static void launch3(sbnet_dtype dt, bool fused, const ConvParams &p, const Shape3 &sh, hipStream_t s) {
     long long items = (long long)p.cap * sh.q.mpasses * sh.q.ngroups;
     long long g = (items + 7) / 8 * 8;
-    const long long most = sh.cc == 64 && 2 * sh.lds_bytes <= (size_t)kLds3 ? 512 : 256;   // persistent workgroups: one per CU, two for pointwise
+    const long long most = p.kh == 1 && 2 * sh.lds_bytes <= (size_t)kLds3 ? 512 : 256;   // persistent workgroups: one per CU, two for pointwise
     if (g > most) g = most;
     const int grid = (int)g;
     if (dt == SBNET_BF16) {

@@ -485,6 +485,13 @@ POINTWISE_PADDED_CASES = [
     (2, 11, 13, 40, 24, 1, "f16", False, True),
     (4, 9, 9, 104, 64, 1, "bf16", True, False),
     (2, 17, 17, 120, 40, 2, "bf16", False, True),
+    # channel counts that are multiples of 32 only: chunks of 32 channels
+    (3, 18, 18, 96, 24, 1, "bf16", True, True),
+    (2, 16, 16, 24, 96, 1, "bf16", False, True),
+    (2, 18, 18, 96, 96, 1, "f16", True, False),
+    (2, 13, 11, 160, 48, 2, "bf16", False, True),
+    (1, 34, 34, 32, 64, 1, "bf16", True, True),         # 1156 pixels: five passes of 256
+    (5, 5, 7, 224, 8, 1, "f16", False, False),          # seven chunks, 35 pixels
 ]
 
 
@@ -518,6 +525,7 @@ SPARSE_CASES = [
     (1, 32, 32, 64, 256, 1, 1, 16, "bf16"),
     (2, 45, 39, 128, 72, 1, 1, 8, "f16"),      # pointwise, fused, blocks hang over the edge, two chunks
     (1, 50, 50, 64, 64, 1, 2, 8, "bf16"),      # pointwise stride 2: the shortcut of a downsampling unit
+    (1, 40, 36, 96, 24, 1, 1, 8, "bf16"),      # pointwise with 32-channel chunks, fused, ragged blocks
     # LDS-tiled 3x3 kernel
     (2, 70, 66, 96, 96, 3, 2, 16, "bf16"),     # downsampling unit, blocks hang over the edge, Cout % 64 == 32
     (1, 96, 80, 192, 32, 3, 1, 16, "f16"),     # six channel chunks
