@@ -26,6 +26,8 @@ DGRAD_CASES = [
     (3, 10, 10, 32, 40, 3, 1, "bf16"),
     (2, 17, 17, 256, 384, 3, 2, "bf16"),
     (3, 16, 16, 64, 256, 1, 1, "bf16"),      # 1x1: no frame, no mirror
+    (3, 18, 18, 96, 24, 1, 1, "bf16"),       # 1x1 with channel counts of the 96-channel stage
+    (2, 9, 9, 24, 40, 1, 2, "f16"),          # 1x1 at stride 2: the gradient is spread, every other pixel stays zero
     (2, 12, 20, 24, 16, 3, 1, "f32"),        # direct fp32 kernel
     (2, 12, 13, 8, 8, 3, 2, "f32"),          # the last input column is not reached by any window
     (2, 14, 12, 16, 8, 3, 2, "bf16"),        # the last input row is not reached by any window
