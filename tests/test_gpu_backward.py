@@ -221,14 +221,14 @@ def test_relu_and_bias_backward_on_tiles(B, h, w, C, dtype):
     assert (db0 == 0).all() and torch.equal(out2, out)             # no active tile: nothing written, zero sums
 
 
-@pytest.mark.parametrize("C,dens", [(64, 0.02), (256, 0.004)])
-def test_residual_unit_backward_composed_from_single_calls(C, dens):
+@pytest.mark.parametrize("C,Cm,dens", [(64, 64, 0.02), (256, 64, 0.004), (96, 24, 0.01)])
+def test_residual_unit_backward_composed_from_single_calls(C, Cm, dens):
     """The residual branch of a unit (Sec. 3.3) forward with its activations kept, then every gradient from library
     calls alone: weight, bias and data gradients of the three convolutions, the two ReLU masks, and the gather's
     gradient into the image.  The oracle's chain rule runs on the same kept activations (the ReLU masks are
     decisions, taken on the stored bf16 values by both sides)."""
-    step("residual unit backward C=%d" % C)
-    dtype, Cm, bo, N, H, W = "bf16", 64, 16, 1, 70, 66
+    step("residual unit backward C=%d Cm=%d" % (C, Cm))
+    dtype, bo, N, H, W = "bf16", 16, 1, 70, 66
     r = gen.rng_for(26, C)
     g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
     og_in = orc.Geom(*g_in.astuple())
