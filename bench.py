@@ -339,9 +339,18 @@ def run_stages(args):
                                                                         workspace=ws_d))
             wgrad_ms = device_ms(lambda: sb.conv_on_tiles_backward_weights(xt_tiles, gt_tiles, cnt, 3, stride=s, out=dw,
                                                                            workspace=ws_w))
+            # the 1x1 layers of a residual unit of the stage's width on the same tiles: Cin -> Cin / 4 on the input
+            # tile, Cout / 4 -> Cout on the output block
+            pw_ms = []
+            for (pc, pk, side) in ((Cin, Cin // 4, th), (Cout // 4, Cout, bo)):
+                pw_x = torch.randn((max(n, 1), side, side, pc), device=dev).to(torch.bfloat16)
+                pw_y = torch.empty((max(n, 1), side, side, pk), device=dev, dtype=torch.bfloat16)
+                pw_w = sb.pack_weights(torch.from_numpy(gen.conv_weights(r, 1, 1, pc, pk, "bf16")).to(torch.bfloat16).to(dev))
+                pw_ms.append(device_ms(lambda: sb.conv_on_tiles(pw_x, cnt, pw_w, None, relu=True, out=pw_y)))
             if target >= 1.0:
                 dense_ms = ms
             rows.append({"H": H, "W": W, "Cin": Cin, "Cout": Cout, "stride": s, "block": bo, "target": target,
+                         "pointwise_reduce_ms": round(pw_ms[0], 5), "pointwise_expand_ms": round(pw_ms[1], 5),
                          "backward_data_ms": round(dgrad_ms, 5), "backward_weights_ms": round(wgrad_ms, 5),
                          "backward_weights_tflops": round(2.0 * n * bo * bo * 9 * Cin * Cout / wgrad_ms / 1e9, 2),
                          "active_blocks": n, "total_blocks": total, "step_ms": round(ms, 5), "conv_kernel_ms": round(k_ms, 5),
