@@ -69,8 +69,8 @@ __host__ __device__ __forceinline__ size_t split_stride(int taps, int CinP, int 
 // (written once, read once by the sum) and every tile of a split costs matrix time, so the best number grows with the
 // square root of n: 8 sqrt(n) suits the two costs measured on 64 x 64 channel blocks.  Both kernels call this with
 // the same arguments.
-__device__ __forceinline__ int splits_used(int n, int nsplit) {
-    int ns = (int)sqrtf(64.f * (float)n);
+__device__ __forceinline__ int splits_used(int n, int nsplit, int taps) {
+    int ns = (int)sqrtf((taps == 1 ? 256.f : 64.f) * (float)n);   // a 1x1 partial result is a ninth of a 3x3 one: 16 sqrt(n)
     if (ns > n) ns = n;
     if (ns > nsplit) ns = nsplit;
     return ns < 1 ? 1 : ns;
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
     const int cb = cbob / p.nob, ob = cbob - cb * p.nob;
     int n = *p.count;
     if (n > p.cap) n = p.cap;
-    const int ns = splits_used(n, p.nsplit);
+    const int ns = splits_used(n, p.nsplit, p.kh * p.kw);
     if (n <= 0 || sigma >= ns) return;                             // the sum reads no partial result of this split
     const int ntiles = (n - sigma + ns - 1) / ns;
     const int H = (p.oh + R - 1) / R;
@@ -303,7 +303,7 @@ __global__ __launch_bounds__(256) void wgrad_direct(WgradParams p) {
     if (e >= total) return;
     int n = *p.count;
     if (n > p.cap) n = p.cap;
-    const int sigma = blockIdx.y, ns = splits_used(n, p.nsplit);
+    const int sigma = blockIdx.y, ns = splits_used(n, p.nsplit, p.kh * p.kw);
     if (n <= 0 || sigma >= ns) return;
     const int o = e % p.Cout, c = (e / p.Cout) % p.Cin, tap = e / (p.Cout * p.Cin);
     const int r = tap / p.kw, t = tap - r * p.kw;
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(64 * NW) void wgrad_sum(const float *__restrict__ p
     const int e = blockIdx.x * 64 + lane;
     int n = *count;
     if (n > cap) n = cap;
-    n = n > 0 ? splits_used(n, nsplit) : 0;
+    n = n > 0 ? splits_used(n, nsplit, taps) : 0;
     float acc = 0.f;
     if (e < total) {
         const int o = e % Cout, c = (e / Cout) % Cin, tap = e / (Cout * Cin);
