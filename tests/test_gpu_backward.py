@@ -348,3 +348,36 @@ def test_pointwise_forward_and_data_gradient_of_a_stack_beyond_two_gib():
         want = w64 @ y[b, i, j].to(torch.float64).cpu().numpy()
         got = dx[b, i, j].to(torch.float64).cpu().numpy()
         assert_close(got, want, CONV_TOL["bf16"], "pointwise data gradient at %s" % ((b, i, j),))
+
+
+def _random_gradient_shapes(n, seed):
+    """Seeded draws over what the matrix-core gradient kernels take: 1x1 and 3x3, stride 1 or 2, channels in multiples of 8."""
+    r = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        k = (1, 3)[int(r.integers(0, 2))]
+        s = int(r.integers(1, 3))
+        th, tw = int(r.integers(k, 36)), int(r.integers(k, 36))
+        out.append((int(r.integers(1, 7)), th, tw, 8 * int(r.integers(1, 25)), 8 * int(r.integers(1, 25)), k, s,
+                    ("bf16", "f16")[int(r.integers(0, 2))]))
+    return out
+
+
+@pytest.mark.parametrize("B,th,tw,Cin,Cout,k,s,dtype", _random_gradient_shapes(24, 18010210))
+def test_gradients_on_random_shapes(B, th, tw, Cin, Cout, k, s, dtype):
+    """Both gradients on seeded random tiles: rows per stage, segments, stride phases, channel blocks and the choice
+    between the pointwise, the 3x3 and the plain kernels all vary with the shape."""
+    step("gradients random %s" % ((B, th, tw, Cin, Cout, k, s, dtype),))
+    r = gen.rng_for(31, th * 1000 + tw * 10 + Cin + Cout + s + k)
+    oh, ow = (th - k) // s + 1, (tw - k) // s + 1
+    x = gen.activations(r, (B + 1, th, tw, Cin), dtype)
+    g = gen.activations(r, (B + 1, oh, ow, Cout), dtype)
+    w = gen.conv_weights(r, k, k, Cin, Cout, dtype)
+    cnt = torch.tensor([B], dtype=torch.int32).cuda()
+    dw = sb.conv_on_tiles_backward_weights(to_dev(x, dtype), to_dev(g, dtype), cnt, k, stride=s)
+    assert_close(to_host(dw), orc.conv_valid_backward_weights(x[:B], g[:B], k, k, stride=s), 2e-5, "weights")
+    dx = torch.full((B + 1, th, tw, Cin), 5.0, dtype=TORCH_DT[dtype]).cuda()
+    sb.conv_on_tiles_backward_data(to_dev(g, dtype), cnt, sb.pack_weights_transposed(to_dev(w, dtype)), th, tw, stride=s, out=dx)
+    got = to_host(dx)
+    assert_close(got[:B], orc.conv_valid_backward_data(g[:B], w, th, tw, stride=s), CONV_TOL[dtype], "data")
+    assert (got[B] == 5.0).all()
