@@ -89,6 +89,24 @@ sbnet_status sbnet_reduce_mask(const void *mask, sbnet_dtype mask_dtype, int N, 
                                size_t workspace_bytes, void *stream);
 
 /*
+ * sbnet_reduce_mask for callers that cannot allocate or hand over device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and kernels as sbnet_reduce_mask, minus the workspace: the row counts and block flags go to a
+ * buffer of SBNET_REDUCE_MASK_STATIC_MAX_BYTES that is part of the library's device image (every
+ * GPU the library runs on holds its own copy until the process ends).  The call allocates and
+ * frees nothing.  Problems whose sbnet_workspace_bytes(N, g) exceeds the buffer are rejected
+ * with SBNET_EUNSUPPORTED before anything is enqueued (1 MiB holds e.g. 8 samples of 800 x 704
+ * with 8 x 8 blocks fourteen times over).  Nothing in the buffer has to start at zero: every byte
+ * the kernels read is written earlier in the same call.  All calls on one GPU share the one
+ * buffer, so two calls whose kernels may overlap (different streams, no dependency) race;
+ * calls on one stream, or ordered by events, are safe.
+ */
+#define SBNET_REDUCE_MASK_STATIC_MAX_BYTES ((size_t)1 << 20)
+sbnet_status sbnet_reduce_mask_static(const void *mask, sbnet_dtype mask_dtype, int N, int H, int W,
+                                      const sbnet_geom *g, sbnet_pool pool, float threshold,
+                                      int32_t *indices, int32_t *count, int cap, void *stream);
+
+/*
  * Synchronising helper: copies *count to the host after waiting for `stream`.  Returns
  * SBNET_ECAP (and still stores the true count) when it exceeds cap.
  */

@@ -43,6 +43,7 @@ _SIGNATURES = {
     "sbnet_geometry": (_ci, [_ci] * 8 + [_gp, _gp, ctypes.POINTER(_ci), ctypes.POINTER(_ci)]),
     "sbnet_workspace_bytes": (_sz, [_ci, _gp]),
     "sbnet_reduce_mask": (_ci, [_vp, _ci, _ci, _ci, _ci, _gp, _ci, ctypes.c_float, _vp, _vp, _ci, _vp, _sz, _vp]),
+    "sbnet_reduce_mask_static": (_ci, [_vp, _ci, _ci, _ci, _ci, _gp, _ci, ctypes.c_float, _vp, _vp, _ci, _vp]),
     "sbnet_read_count": (_ci, [_vp, _ci, ctypes.POINTER(_ci), _vp]),
     "sbnet_sparse_gather": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp, _vp]),
     "sbnet_sparse_scatter": (_ci, [_vp, _ci, _vp, _vp, _ci, _gp, _vp, _ci, _ci, _ci, _ci, _ci, _vp]),
@@ -168,6 +169,16 @@ def reduce_mask(mask, g, pool=POOL_AVG, threshold=0.0, indices=None, count=None,
     _check(lib().sbnet_reduce_mask(_ptr(mask), _dt(mask), N, H, W, g, pool, float(threshold), _ptr(indices),
                                    _ptr(count), cap, _ptr(workspace), workspace.numel() * workspace.element_size(),
                                    _stream()))
+    return indices, count
+
+
+def reduce_mask_static(mask, g, indices, count, pool=POOL_AVG, threshold=0.0):
+    """reduce_mask without a workspace argument (the library's built-in scratch): the caller passes every
+    buffer, nothing is allocated on the way.  Returns (indices, count) as passed."""
+    _dev(mask, "mask"), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    N, H, W = mask.shape
+    _check(lib().sbnet_reduce_mask_static(_ptr(mask), _dt(mask), N, H, W, g, pool, float(threshold), _ptr(indices),
+                                          _ptr(count), indices.shape[0], _stream()))
     return indices, count
 
 

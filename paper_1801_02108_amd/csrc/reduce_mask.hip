@@ -13,6 +13,8 @@
 //           ballot + popcount compaction of the row's flags into the index list.
 #include "common.h"
 
+#include <mutex>
+
 namespace sbnet {
 
 constexpr int kRmThreads = 256;
@@ -180,10 +182,12 @@ extern "C" size_t sbnet_workspace_bytes(int N, const sbnet_geom *g) {
     return rowcount_bytes((int)rows) + ((rows * g->bcount_w + 15) & ~(size_t)15);
 }
 
-extern "C" sbnet_status sbnet_reduce_mask(const void *mask, sbnet_dtype mdt, int N, int H, int W,
-                                          const sbnet_geom *g, sbnet_pool pool, float threshold,
-                                          int32_t *indices, int32_t *count, int cap, void *workspace,
-                                          size_t ws_bytes, void *stream) {
+// Argument checks and the two launches shared by both entry points; `workspace` is device memory of at
+// least sbnet_workspace_bytes(N, g), every byte the kernels read from it is written by pass 1 first.
+static sbnet_status reduce_mask_launch(const void *mask, sbnet_dtype mdt, int N, int H, int W,
+                                       const sbnet_geom *g, sbnet_pool pool, float threshold,
+                                       int32_t *indices, int32_t *count, int cap, void *workspace,
+                                       size_t ws_bytes, void *stream) {
     if (!mask || !indices || !count || !workspace) return fail(SBNET_EINVAL, "sbnet_reduce_mask: null pointer");
     if (N <= 0 || H <= 0 || W <= 0 || cap < 0) return fail(SBNET_EINVAL, "sbnet_reduce_mask: bad sizes");
     if (!geom_ok(g)) return fail(SBNET_EINVAL, "sbnet_reduce_mask: bad geometry");
@@ -233,4 +237,56 @@ extern "C" sbnet_status sbnet_reduce_mask(const void *mask, sbnet_dtype mdt, int
     hipLaunchKernelGGL(rm_compact, dim3(rows), dim3(kRmThreads), 0, s, rowcount, flags, rows, g->bcount_h,
                        g->bcount_w, indices, count, cap);
     return launch_status("sbnet_reduce_mask(compact)");
+}
+
+extern "C" sbnet_status sbnet_reduce_mask(const void *mask, sbnet_dtype mdt, int N, int H, int W,
+                                          const sbnet_geom *g, sbnet_pool pool, float threshold,
+                                          int32_t *indices, int32_t *count, int cap, void *workspace,
+                                          size_t ws_bytes, void *stream) {
+    return reduce_mask_launch(mask, mdt, N, H, W, g, pool, threshold, indices, count, cap, workspace, ws_bytes,
+                              stream);
+}
+
+// ---- the same call for callers that cannot hand over (or allocate) a workspace -------------------
+// The row counts and flags live in a file-scope device array.  On the host the array's name is only a
+// handle: its device address is looked up once per device with hipGetSymbolAddress and kept; kernels
+// and every other host-side use take that address.
+constexpr size_t kStaticScratchBytes = SBNET_REDUCE_MASK_STATIC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void *scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, 0 = not looked up
+
+static sbnet_status static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(SBNET_EHIP, "sbnet_reduce_mask_static: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SBNET_EUNSUPPORTED, "sbnet_reduce_mask_static: device %d", dev);
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(SBNET_EHIP, "sbnet_reduce_mask_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return SBNET_OK;
+}
+
+extern "C" sbnet_status sbnet_reduce_mask_static(const void *mask, sbnet_dtype mdt, int N, int H, int W,
+                                                 const sbnet_geom *g, sbnet_pool pool, float threshold,
+                                                 int32_t *indices, int32_t *count, int cap, void *stream) {
+    if (N <= 0 || !geom_ok(g)) return fail(SBNET_EINVAL, "sbnet_reduce_mask_static: bad sizes or geometry");
+    const unsigned long long need = (unsigned long long)sbnet_workspace_bytes(N, g);
+    if (need > kStaticScratchBytes)
+        return fail(SBNET_EUNSUPPORTED, "sbnet_reduce_mask_static: %llu bytes of scratch needed for %d x %d x %d blocks, "
+                    "the built-in buffer holds %llu; use sbnet_reduce_mask with a workspace",
+                    need, N, g->bcount_h, g->bcount_w, (unsigned long long)kStaticScratchBytes);
+    void *ws = nullptr;
+    sbnet_status st = static_scratch(&ws);
+    if (st != SBNET_OK) return st;
+    return reduce_mask_launch(mask, mdt, N, H, W, g, pool, threshold, indices, count, cap, ws, kStaticScratchBytes,
+                              stream);
 }
