@@ -291,8 +291,8 @@ def test_residual_unit_backward_composed_from_single_calls(C, Cm, dens):
 def test_weight_gradient_of_a_stack_beyond_two_gib():
     """13 500 tiles of 18 x 18 x 256 (the residual unit's first convolution at the batched configurations' scale) are
     2.24 GB: byte offsets into the stack do not fit 31 bits, and the kernel addresses every tile through a descriptor
-    of its own.  Inputs come from a seeded device generator (a host copy serves the oracle's samples: single weights,
-    each a sum over every pixel of every tile)."""
+    of its own.  Inputs come from a seeded device generator (a host copy serves the oracle: sampled single weights, each a sum
+    over every pixel of every tile, and the last tiles' whole contribution)."""
     step("weight gradient, stack beyond 2 GiB")
     n, th, C, K = 13500, 18, 256, 64
     gen_t = torch.Generator(device="cuda")
@@ -307,21 +307,25 @@ def test_weight_gradient_of_a_stack_beyond_two_gib():
     r = gen.rng_for(27)
     samples = [(int(r.integers(0, C)), int(r.integers(0, K))) for _ in range(10)] + [(0, 0), (C - 1, K - 1), (C - 1, 0), (0, K - 1)]
     scale = np.sqrt(n * th * th)
+    # one weight of a 1x1 kernel depends on one input and one output channel only: the oracle's weight gradient on
+    # those two channel planes of the WHOLE stack is that weight
+    def plane(t, c):
+        return t[..., c:c + 1].to(torch.float64).numpy()
     for c, o in samples:
-        want = float((xc[..., c].to(torch.float64) * gc[..., o].to(torch.float64)).sum())
+        want = float(orc.conv_valid_backward_weights(plane(xc, c), plane(gc, o), 1, 1)[0, 0, 0, 0])
         assert abs(got[0, 0, c, o] - want) <= 2e-5 * scale + 2e-5 * abs(want), (c, o, got[0, 0, c, o], want)
-    # the last tile reaches the sums: with it left out, the sampled weights differ
-    cnt2 = torch.tensor([n - 1], dtype=torch.int32).cuda()
+    # the last tiles reach the sums: with three left out, every weight moves by the oracle's gradient of those three
+    cnt2 = torch.tensor([n - 3], dtype=torch.int32).cuda()
     dw2 = sb.conv_on_tiles_backward_weights(x, g, cnt2, 1).cpu().numpy()
-    c, o = samples[0]
-    last = float((xc[n - 1, ..., c].to(torch.float64) * gc[n - 1, ..., o].to(torch.float64)).sum())
-    assert abs((got[0, 0, c, o] - dw2[0, 0, c, o]) - last) <= 4e-5 * scale
+    tail = orc.conv_valid_backward_weights(xc[n - 3:].to(torch.float64).numpy(), gc[n - 3:].to(torch.float64).numpy(), 1, 1)
+    assert np.abs(tail).max() > 10.0
+    assert np.abs((got - dw2) - tail).max() <= 4e-5 * scale
 
 
 def test_pointwise_forward_and_data_gradient_of_a_stack_beyond_two_gib():
     """The same 2.24 GB stack through the pointwise kernel, once as the input of the residual unit's first convolution
     (256 -> 64) and once as the result of that convolution's data gradient (64 -> 256): every tile is addressed from a
-    64-bit base through a descriptor of its own.  Sampled pixels, the last tile's among them, against fp64 dot products."""
+    64-bit base through a descriptor of its own.  Sampled tiles, the first and the last among them, against the oracle."""
     step("pointwise forward / data gradient, stack beyond 2 GiB")
     n, th, C, K = 13500, 18, 256, 64
     gen_t = torch.Generator(device="cuda")
@@ -333,21 +337,16 @@ def test_pointwise_forward_and_data_gradient_of_a_stack_beyond_two_gib():
     wd = to_dev(w, "bf16")
     cnt = torch.tensor([n], dtype=torch.int32).cuda()
     y = sb.conv_on_tiles(x, cnt, sb.pack_weights(wd), None, relu=False)
-    pts = [(int(r.integers(0, n)), int(r.integers(0, th)), int(r.integers(0, th))) for _ in range(40)]
-    pts += [(n - 1, th - 1, th - 1), (n - 1, 0, 0), (0, 0, 0), (n // 2, th - 1, 0)]
-    w64 = w[0, 0].astype(np.float64)
-    for b, i, j in pts:
-        want = x[b, i, j].to(torch.float64).cpu().numpy() @ w64
-        got = y[b, i, j].to(torch.float64).cpu().numpy()
-        assert_close(got, want, CONV_TOL["bf16"], "pointwise forward at %s" % ((b, i, j),))
+    # whole sampled tiles, the first and the last of the stack among them, against the oracle's tile convolution
+    pick = np.unique(np.concatenate([[0, n - 1, n // 2, 6472, 6473], r.integers(0, n, 8)]))   # 6473 * 165888 B > 2^30
+    sel = torch.from_numpy(pick).cuda()
+    assert_close(to_host(y[sel]), orc.conv_valid(to_host(x[sel]), w), CONV_TOL["bf16"], "pointwise forward, sampled tiles")
     # data gradient: dL/dx = dL/dy W^T, a stack of the size of x
     del x
     dx = sb.conv_on_tiles_backward_data(y, cnt, sb.pack_weights_transposed(wd), th, th)
     assert dx.numel() * 2 > 2 ** 31
-    for b, i, j in pts:
-        want = w64 @ y[b, i, j].to(torch.float64).cpu().numpy()
-        got = dx[b, i, j].to(torch.float64).cpu().numpy()
-        assert_close(got, want, CONV_TOL["bf16"], "pointwise data gradient at %s" % ((b, i, j),))
+    assert_close(to_host(dx[sel]), orc.conv_valid_backward_data(to_host(y[sel]), w, th, th), CONV_TOL["bf16"],
+                 "pointwise data gradient, sampled tiles")
 
 
 def _random_gradient_shapes(n, seed):

@@ -166,6 +166,168 @@ def test_stack_shape_batch_of_samples_sampled(bo):
         assert_close(got, ref[0, cy:cy + bo, cx:cx + bo], 3e-2, "stack tile %d" % k)
 
 
+def _window_reference(x0_dev, idx, n_, by, bx, bo, H, W, units):
+    """Oracle result of a stack of residual units on the 3 x 3 block window around block (n_, by, bx), treated as an
+    image of its own; returns the window result and the centre block's offset inside it."""
+    gy_lo, gx_lo = max(by - 1, 0) * bo, max(bx - 1, 0) * bo
+    gy_hi, gx_hi = min((by + 2) * bo, H), min((bx + 2) * bo, W)
+    win = x0_dev[n_, gy_lo:gy_hi, gx_lo:gx_hi].to(torch.float64).cpu().numpy()[None]
+    wg_in, wg_out, _, _ = orc.geometry(win.shape[1], win.shape[2], 3, 1, bo)
+    sel = idx[(idx[:, 0] == n_) & (idx[:, 1] * bo >= gy_lo) & (idx[:, 1] * bo < gy_hi) &
+              (idx[:, 2] * bo >= gx_lo) & (idx[:, 2] * bo < gx_hi)].copy()
+    sel[:, 0] = 0
+    sel[:, 1] -= gy_lo // bo
+    sel[:, 2] -= gx_lo // bo
+    ref = win
+    for ws in units:
+        ref = orc.sparse_bottleneck_tiled(ref, sel, wg_in, wg_out, *ws)
+    return ref, by * bo - gy_lo, bx * bo - gx_lo
+
+
+def test_config5_as_stated_sampled():
+    """Config 5 at its stated size: N = 8 samples of 800 x 704 x 256, a per-sample low-resolution mask at 15 % active
+    blocks, EIGHT residual units with distinct weights sharing one index list and alternating two buffers, 16 x 16
+    blocks.  Eight stacked units reach 8 pixels; the oracle runs all eight on the 3 x 3 block window around each
+    sampled block, whose artificial border is 16 pixels from the centre block, so the centre block is exact.
+    Tolerance: each unit rounds the running sum once more to bf16 (2^-9) and the next unit's branch reads the rounded
+    values; 3e-2 holds for 2-3 units, eight get 5e-2 (random-walk growth sqrt(8/3) of the per-unit share)."""
+    step("config 5 as stated: N=8, 8 units")
+    r = gen.rng_for(5, 88)
+    N, H, W, C, bo, n_units = 8, 800, 704, 256, 16, 8
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    dev = torch.device("cuda:0")
+    tg = torch.Generator(device=dev)
+    tg.manual_seed(gen.BASE_SEED + 588)
+    a = torch.empty((N, H, W, C), device=dev, dtype=torch.bfloat16)
+    for n_ in range(N):      # sample by sample: the fp32 draw of the whole batch would be 4.6 GB
+        a[n_] = torch.randn((H, W, C), generator=tg, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    b = a.clone()
+    x0 = a.clone()
+    logits = gen.smooth_noise(r, N, H // 8, W // 8, 2.0)
+    og = ogeom(g_in)
+    total = N * g_in.bcount_h * g_in.bcount_w
+    assert total == 17600
+    mask, thr, frac = gen.calibrate(lambda t: gen.lowres_mask(logits, t), lambda mm: len(orc.reduce_mask(mm, og)), total,
+                                    0.15, -4.0, 4.0, increasing=False)
+    assert abs(frac - 0.15) < 0.01
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).to(dev), g_in)
+    idx = orc.reduce_mask(mask, og)
+    n = sb.read_count(d_cnt, d_idx.shape[0])
+    assert n == len(idx) and np.array_equal(d_idx[:n].cpu().numpy(), idx)
+    assert len(set(idx[:, 0].tolist())) == N                     # every sample has active blocks of its own
+    units = [gen.bottleneck_weights(r, C, 64, "bf16") for _ in range(n_units)]
+    for ws in units:
+        dws = (sb.pack_weights(to_dev(ws[0], "bf16")), torch.from_numpy(ws[1]).to(dev), sb.pack_weights(to_dev(ws[2], "bf16")),
+               torch.from_numpy(ws[3]).to(dev), sb.pack_weights(to_dev(ws[4], "bf16")), torch.from_numpy(ws[5]).to(dev))
+        sb.sparse_bottleneck(a, d_idx, d_cnt, g_in, g_out, dws, b)
+        a, b = b, a
+    torch.cuda.synchronize()
+    bm = torch.from_numpy(orc.block_mask(idx, ogeom(g_out), N, H, W)).to(dev)
+    for n_ in range(N):                                          # inactive pixels never change, sample by sample
+        assert torch.equal(a[n_][~bm[n_]], x0[n_][~bm[n_]])
+    # sampled blocks: the first and the last of the list, one at an image corner or edge if active, a few random ones
+    edge = np.flatnonzero((idx[:, 1] == 0) | (idx[:, 2] == 0) | (idx[:, 1] == g_in.bcount_h - 1) | (idx[:, 2] == g_in.bcount_w - 1))
+    rows = [0, len(idx) - 1] + [int(v) for v in r.choice(len(idx), 4, replace=False)]
+    if len(edge):
+        rows += [int(v) for v in r.choice(edge, min(2, len(edge)), replace=False)]
+    worst = 0.0
+    for k in sorted(set(rows)):
+        n_, by, bx = (int(v) for v in idx[k])
+        ref, cy, cx = _window_reference(x0, idx, n_, by, bx, bo, H, W, units)
+        got = a[n_, by * bo:by * bo + bo, bx * bo:bx * bo + bo].to(torch.float64).cpu().numpy()
+        worst = max(worst, assert_close(got, ref[0, cy:cy + bo, cx:cx + bo], 5e-2, "config 5 tile %d" % k))
+    print("config 5 sampled: worst max|err|/max|ref| = %.3g" % worst, flush=True)
+
+
+def test_config4_block_32_batch_of_four_sampled():
+    """Config 4's largest block size at its stated batch: N = 4 samples of 800 x 704 x 256, 32 x 32 blocks (2200
+    blocks, 34 x 34 input tiles), blob mask at about 10 % active blocks, one residual unit; sampled tiles, every
+    active image-border tile's candidates among them, against the oracle tile by tile."""
+    step("config 4, bo=32, N=4")
+    r = gen.rng_for(4, 32)
+    N, H, W, C, bo = 4, 800, 704, 256, 32
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    assert N * g_in.bcount_h * g_in.bcount_w == 2200 and g_in.bsize_h == 34
+    dev = torch.device("cuda:0")
+    tg = torch.Generator(device=dev)
+    tg.manual_seed(gen.BASE_SEED + 432)
+    dx = torch.randn((N, H, W, C), generator=tg, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    field = gen.smooth_noise(r, N, H, W, 24.0)
+    og = ogeom(g_in)
+    mask, thr, frac = gen.calibrate(lambda t: gen.blob_mask(field, t), lambda mm: len(orc.reduce_mask(mm, og)),
+                                    N * g_in.bcount_h * g_in.bcount_w, 0.10, -4.0, 4.0, increasing=False)
+    assert abs(frac - 0.10) < 0.01
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).to(dev), g_in)
+    idx = orc.reduce_mask(mask, og)
+    n = sb.read_count(d_cnt, d_idx.shape[0])
+    assert n == len(idx) and np.array_equal(d_idx[:n].cpu().numpy(), idx)
+    ws = gen.bottleneck_weights(r, C, 64, "bf16")
+    dws = (sb.pack_weights(to_dev(ws[0], "bf16")), torch.from_numpy(ws[1]).to(dev), sb.pack_weights(to_dev(ws[2], "bf16")),
+           torch.from_numpy(ws[3]).to(dev), sb.pack_weights(to_dev(ws[4], "bf16")), torch.from_numpy(ws[5]).to(dev))
+    y = dx.clone()
+    sb.sparse_bottleneck(dx, d_idx, d_cnt, g_in, g_out, dws, y)
+    torch.cuda.synchronize()
+    bm = torch.from_numpy(orc.block_mask(idx, ogeom(g_out), N, H, W)).to(dev)
+    assert torch.equal(y[~bm], dx[~bm])
+    rows = np.unique(np.concatenate([sample_tiles(idx, g_in, r, 5)[:12], [0, len(idx) - 1]]))
+    host = {}
+    for k in rows:
+        n_, by, bx = (int(v) for v in idx[k])
+        # the oracle gathers from the whole sample, so that zero padding at the image border is its own
+        if n_ not in host:
+            host = {n_: dx[n_].to(torch.float64).cpu().numpy()[None]}
+        xs = host[n_]
+        one = np.array([[0, by, bx]], dtype=np.int32)
+        t3 = orc.bottleneck_on_tiles(orc.gather(xs, one, og), one, og, H, W, *ws)
+        ref = xs[0, by * bo:(by + 1) * bo, bx * bo:(bx + 1) * bo] + t3[0]
+        got = y[n_, by * bo:(by + 1) * bo, bx * bo:(bx + 1) * bo].to(torch.float64).cpu().numpy()
+        assert_close(got, ref, CONV_TOL["bf16"], "config 4 bo=32 tile %d" % k)
+
+
+def test_gather_scatter_of_stacks_beyond_two_gib():
+    """Tile stacks whose byte offsets do not fit 31 bits: all 17 600 blocks of N = 8 samples of 800 x 704 x 256 bf16.
+    The 18 x 18 input tiles are 2.92 GB: sampled tiles, the first and the last among them, bit-exact against the
+    oracle's gather.  The 16 x 16 blocks are 2.31 GB: scattered into a cleared tensor they must give back the input
+    bit for bit (every pixel belongs to exactly one block), and scatter-add onto the input must equal x + x."""
+    step("gather / scatter, stacks beyond 2 GiB")
+    r = gen.rng_for(5, 2)
+    N, H, W, C, bo = 8, 800, 704, 256, 16
+    g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+    dev = torch.device("cuda:0")
+    tg = torch.Generator(device=dev)
+    tg.manual_seed(gen.BASE_SEED + 502)
+    x = torch.empty((N, H, W, C), device=dev, dtype=torch.bfloat16)
+    for n_ in range(N):
+        x[n_] = torch.randn((H, W, C), generator=tg, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    og_in, og_out = ogeom(g_in), ogeom(g_out)
+    ones = np.ones((N, H, W), np.uint8)
+    d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(ones).to(dev), g_out, sb.POOL_MAX, 0.0)
+    idx = orc.reduce_mask(ones, og_out, orc.POOL_MAX, 0.0)
+    n = sb.read_count(d_cnt, d_idx.shape[0])
+    assert n == 17600 == len(idx) and np.array_equal(d_idx.cpu().numpy(), idx)
+    tiles = sb.sparse_gather(x, d_idx, d_cnt, g_in)
+    assert tiles.numel() * 2 > 2 ** 31
+    pick = np.unique(np.concatenate([[0, n - 1, n // 2, 43, 44, 2199, 2200], r.choice(n, 12, replace=False)]))
+    host = {}
+    for k in pick:
+        n_ = int(idx[k, 0])
+        one = idx[k:k + 1].copy()
+        one[0, 0] = 0
+        if n_ not in host:
+            host = {n_: x[n_].to(torch.float64).cpu().numpy()[None]}
+        ref = orc.gather(host[n_], one, og_in)
+        assert np.array_equal(tiles[int(k)].to(torch.float64).cpu().numpy(), ref[0]), "gathered tile %d" % k
+    del tiles
+    blocks = sb.sparse_gather(x, d_idx, d_cnt, g_out)
+    assert blocks.numel() * 2 > 2 ** 31
+    y = torch.zeros_like(x)
+    sb.sparse_scatter(blocks, d_idx, d_cnt, g_out, y)
+    assert torch.equal(y, x)
+    sb.sparse_scatter(blocks, d_idx, d_cnt, g_out, y, add=True)
+    two = (x.to(torch.float32) * 2).to(torch.bfloat16)      # doubling is exact in bf16
+    assert torch.equal(y, two)
+
+
 STAGE_CASES = [
     # H, W, Cin, Cout, stride, bo: the other stage shapes of the detector backbone (Sec. 4), downsampling and not
     (800, 704, 64, 96, 2, 16),
