@@ -464,6 +464,10 @@ def main():
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); the path shards by blocks or samples "
                  "without collectives, each GPU running this same single-GPU path on its share")
     import numpy as np
+    if not args.no_cpu_baseline:                                  # compile / load the CPU oracle before any GPU call
+        import oracle as orc
+        orc.build()
+        orc._c()
     import torch
     import paper_1801_02108_amd as sb
     from paper_1801_02108_amd import inputs as gen
@@ -578,11 +582,27 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    INNER = 20      # steps captured per HIP graph: fixed, whatever --steps / --warmup say
+
     def time_step_graph(fn, steps, warmup):
-        """ms per step with `steps` steps replayed from graphs of `inner` steps each"""
-        inner = 10 if steps % 10 == 0 and warmup % 10 == 0 else 1
-        g = graph_of(fn, inner)
-        return time_steps(g.replay, steps // inner, max(warmup // inner, 1)) / inner, inner
+        """Device milliseconds per step: HIP events on the launch stream around whole replays of a graph of INNER
+        back-to-back steps.  At least 50 replays are timed (a step lasts ~10 us; fewer would time the clock), more
+        if `steps` asks for more; warm-up runs as whole replays too.  Returns (ms per step, steps timed, wall-clock
+        ms per step over the same region between two device synchronisations)."""
+        g = graph_of(fn, INNER)
+        replays = max(50, -(-steps // INNER))
+        for _ in range(max(2, -(-warmup // INNER))):
+            g.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(replays):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        return e0.elapsed_time(e1) / (replays * INNER), replays * INNER, wall / (replays * INNER)
 
     # ------------------------------------------------------------------ headline: 10 % active blocks
     mask_np, frac = mask_for(args.density)
@@ -590,12 +610,12 @@ def main():
     nact = count_active(mask_np)
     pix_density = float(mask_np.mean())
 
-    eager_ms = time_steps(lambda: step_fused(mask_d), args.steps, args.warmup)
-    graph_ok, inner = True, 1
+    eager_ms = time_steps(lambda: step_fused(mask_d), max(args.steps, 100), max(args.warmup, 10))
+    graph_ok, steps_timed, wall_ms = True, args.steps, None
     try:
         if args.eager_kernel_timing:
             raise RuntimeError("eager timing requested")
-        ms_per_step, inner = time_step_graph(lambda: step_fused(mask_d), args.steps, args.warmup)
+        ms_per_step, steps_timed, wall_ms = time_step_graph(lambda: step_fused(mask_d), args.steps, args.warmup)
         single_graph_ms = time_steps(graph_of(lambda: step_fused(mask_d), 1).replay, 100, 10)
     except Exception as e:                                         # pragma: no cover
         graph_ok = False
@@ -635,8 +655,10 @@ def main():
                                "road-band mask", "target_active_block_fraction": args.density,
                    "active_blocks": nact, "total_blocks": total_blocks, "active_block_fraction": round(frac, 4),
                    "mask_pixel_density": round(pix_density, 4), "step": "reduce_mask + fused gather/conv/scatter",
-                   "timing": ("%d steps per HIP graph replay, wall clock between device syncs" % inner) if graph_ok
-                   else "eager launches, wall clock between device syncs"},
+                   "timing": ("HIP events around %d steps replayed from HIP graphs of %d steps each (always at least "
+                              "50 replays, warm-up in whole replays)" % (steps_timed, INNER)) if graph_ok
+                   else "eager launches, wall clock between device syncs", "steps_timed": steps_timed},
+        "ms_per_step_wall_clock_same_region": None if wall_ms is None else round(wall_ms, 6),
         "ms_per_step_eager": round(eager_ms, 6),
         "ms_per_step_one_graph_per_step": round(single_graph_ms, 6),
         "kernel_ms": {"reduce_mask(2 kernels)": round(reduce_ms, 6), "sparse_conv(fused mfma)": round(conv_ms, 6)},
@@ -659,7 +681,7 @@ def main():
             m_np, fr = mask_for(target)
             m_d = torch.from_numpy(m_np).to(dev)
             n = count_active(m_np)
-            t_step = time_step_graph(lambda: step_fused(m_d), 100, 10)[0] if graph_ok else \
+            t_step = time_step_graph(lambda: step_fused(m_d), args.steps, args.warmup)[0] if graph_ok else \
                 time_steps(lambda: step_fused(m_d), 100, 10)
             t_conv = tk(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y))
             tiles_buf[0] = torch.empty((n, BO + 2, BO + 2, C), dtype=torch.bfloat16, device=dev)
@@ -735,6 +757,15 @@ def main():
             row["speedup_vs_own_dense"] = round(dense_ms / row["step_ms"], 3)
             row["ideal_speedup"] = round(total_blocks / max(row["active_blocks"], 1), 3)
         out["sweep"] = sweep
+        # both rooflines of the fused kernel at every density of the sweep (its arithmetic intensity, 254 FLOP/B, sits
+        # just under the ridge of 312, so the HBM fraction is the binding one; the matrix-core fraction is quoted
+        # against the published dense bf16 peak)
+        out["roofline_by_density"] = [
+            {"target": row["target"], "active_blocks": row["active_blocks"], "kernel_ms": row["fused_conv_ms"],
+             "hbm_GBps": round(TILE_BYTES * row["active_blocks"] / row["fused_conv_ms"] / 1e6, 1),
+             "hbm_frac": round(TILE_BYTES * row["active_blocks"] / row["fused_conv_ms"] / 1e6 / PEAK_HBM_GBS, 4),
+             "mfma_tflops": row["fused_conv_tflops"], "mfma_frac": round(row["fused_conv_tflops"] / PEAK_BF16_TFLOPS, 4)}
+            for row in sweep]
         out["own_dense_ms"] = round(dense_ms, 5)
         out["speedup_vs_own_dense"] = round(dense_ms / ms_per_step, 3)
         # MIOpen dense convolution through torch (channels-last bf16), an external baseline only
@@ -753,8 +784,10 @@ def main():
 
     # ------------------------------------------------------------------ CPU oracle on the same workload
     if not args.no_cpu_baseline:
-        import oracle as orc
         og_in, og_out = orc.Geom(*g_in.astuple()), orc.Geom(*g_out.astuple())
+        wg_in, wg_out, _, _ = orc.geometry(8, 8, 3, 1, 4)           # one tiny warm call: the timer starts on loaded code
+        orc.sparse_conv_tiled(np.zeros((1, 8, 8, 2)), orc.reduce_mask(np.ones((1, 8, 8)), wg_in), wg_in, wg_out,
+                              np.zeros((3, 3, 2, 2)), np.zeros(2), np.zeros((1, 8, 8, 2)))
         x64 = x_np.astype(np.float64)
         w64 = w_np.astype(np.float64)
         b64 = b_np.astype(np.float64)

@@ -44,9 +44,13 @@ _lib = None
 
 
 def _c():
+    """The loaded C library.  It is never compiled from here: build() runs once per process, before the process
+    touches a GPU (tests: a session hook; benchmark and smoke check: their first statement)."""
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        if not os.path.exists(_LIB):
+            raise ImportError("%s not found: call oracle.build() first" % _LIB)
+        _lib = ctypes.CDLL(_LIB)
         _lib.orc_reduce_mask.restype = ctypes.c_int
     return _lib
 

@@ -3,14 +3,22 @@
 // arXiv 1801.02108).
 //
 // The paper appends indices with a global atomic counter, which gives an arbitrary order.
-// Here the list is produced in lexicographic (n, by, bx) order without atomics:
-//   pass 1  one workgroup per block row: coalesced column pooling of the window rows into LDS
-//           (four columns per thread and all rows of a window in flight, so the window costs one
-//           memory latency),
-//           then one thread per block pools its window columns, thresholds, stores a flag byte
-//           and the row's number of active blocks;
-//   pass 2  one workgroup per block row: exclusive prefix over the row counts, then wavefront
+// Here the list is produced in lexicographic (n, by, bx) order without atomics, in two launches.
+// Grids of at most 65 536 blocks (every configuration of the paper's detector is far below):
+//   pass 1  rm_pool_blocks: one wavefront per block.  All loads of a window are issued at once (aligned
+//           4-byte words where the mask allows), the lanes' partial pools are combined with cross-lane
+//           moves, one lane thresholds and stores the block's flag byte.  No LDS, no barrier, no
+//           branch around a load: the kernel is one memory round trip long;
+//   pass 2  rm_compact_flags: one workgroup per 256 consecutive blocks counts the flags in front of
+//           its run (16 flags per load) and compacts its own 256 by ballot + popcount.
+// Larger grids (a count over all earlier flags per workgroup would grow quadratically):
+//   pass 1  rm_pool_rows: one workgroup per block row, coalesced column pooling of the window rows
+//           into LDS, then one thread per block pools its window columns, thresholds, stores a flag
+//           byte and the row's number of active blocks;
+//   pass 2  rm_compact: one workgroup per block row: exclusive prefix over the row counts, then
 //           ballot + popcount compaction of the row's flags into the index list.
+// The flag bytes of pass 1 are also what the fused consumers take (conv16.hip): they do the compaction
+// of pass 2 in their own prologue, which saves a launch where a launch is a third of the step.
 #include "common.h"
 
 #include <mutex>
@@ -170,6 +178,212 @@ __global__ __launch_bounds__(kRmThreads) void rm_compact(const int32_t *__restri
     if (row == rows - 1 && threadIdx.x == 0) *count = base;
 }
 
+// ---- grids of at most kFlagPathMaxBlocks blocks ---------------------------------------------------------------
+
+// Sum (or max) of a non-negative int over the 64 lanes, result in lane 63: four shifts inside the rows of 16
+// lanes, then the row totals are passed on to the next row and to the upper half (cross-lane moves in the
+// VALU's data path: no LDS round trips).  Lanes without a source read 0, the identity of both operations here.
+template <int POOL>
+__device__ __forceinline__ int wave_pool_nonneg(int v) {
+#define SBNET_RM_STEP(CTRL, ROWS)                                                                     \
+    {                                                                                                 \
+        const int o = __builtin_amdgcn_update_dpp(0, v, CTRL, ROWS, 0xf, false);                      \
+        v = POOL == SBNET_POOL_AVG ? v + o : (o > v ? o : v);                                          \
+    }
+    SBNET_RM_STEP(0x111, 0xf)   // row_shr:1
+    SBNET_RM_STEP(0x112, 0xf)   // row_shr:2
+    SBNET_RM_STEP(0x114, 0xf)   // row_shr:4
+    SBNET_RM_STEP(0x118, 0xf)   // row_shr:8      lane 15 of every row: the row's pool
+    SBNET_RM_STEP(0x142, 0xa)   // row_bcast:15   rows 1 and 3 take in the row before them
+    SBNET_RM_STEP(0x143, 0xc)   // row_bcast:31   rows 2 and 3 take in lane 31: lane 63 holds everything
+#undef SBNET_RM_STEP
+    return v;
+}
+
+template <typename Acc, int POOL>
+__device__ __forceinline__ Acc wave_pool_any(Acc v) {
+    for (int o = 32; o > 0; o >>= 1) {
+        const Acc u = __shfl_xor(v, o, 64);
+        v = POOL == SBNET_POOL_AVG ? v + u : (u > v ? u : v);
+    }
+    return v;
+}
+
+constexpr int kFlagPathMaxBlocks = 65536;
+constexpr int kPoolUnroll = 4;       // loads a lane keeps in flight per batch
+
+struct BlockDivs {
+    FastDiv per_sample, per_row;     // blocks per sample, blocks per block row
+};
+
+// WORDS: T is uint8_t, W % 4 == 0 and the mask is 4-byte aligned: a lane loads aligned words that cover the
+// window's columns and leaves out the bytes beside it.  Otherwise one element per load.
+template <typename T, typename Acc, int POOL, bool WORDS>
+__global__ __launch_bounds__(kRmThreads) void rm_pool_blocks(const T *__restrict__ mask, int H, int W, sbnet_geom g,
+                                                              BlockDivs dv, int total, double threshold,
+                                                              uint8_t *__restrict__ flags) {
+    const int lane = threadIdx.x & 63;
+    const int blk = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRmThreads / 64) + (threadIdx.x >> 6)));
+    if (blk >= total) return;                                 // uniform over the wavefront
+    const int n = (int)fdiv((uint32_t)blk, dv.per_sample);
+    const int rem = blk - n * g.bcount_h * g.bcount_w;
+    const int by = (int)fdiv((uint32_t)rem, dv.per_row), bx = rem - by * g.bcount_w;
+    const int y0 = g.boffset_h + by * g.bstride_h, x0 = g.boffset_w + bx * g.bstride_w;
+    const int ylo = max(y0, 0), yhi = min(y0 + g.bsize_h, H);
+    const int xlo = max(x0, 0), xhi = min(x0 + g.bsize_w, W);
+    const bool clipped = y0 < 0 || x0 < 0 || y0 + g.bsize_h > H || x0 + g.bsize_w > W;
+    const Acc neutral = POOL == SBNET_POOL_AVG ? (Acc)0 : lowest_of<Acc>();
+    Acc a = neutral;
+    if (yhi > ylo && xhi > xlo) {                             // uniform: the window meets the image
+        const int per_row = WORDS ? ((xhi + 3) >> 2) - (xlo >> 2) : xhi - xlo;     // loads per window row
+        const int first = WORDS ? (xlo >> 2) : xlo;
+        const int count = per_row * (yhi - ylo);
+        const size_t row_units = WORDS ? (size_t)(W >> 2) : (size_t)W;
+        const size_t base = ((size_t)n * H + ylo) * row_units + first;
+        for (int i0 = 0; i0 < count; i0 += 64 * kPoolUnroll) {
+            uint32_t wv[kPoolUnroll];
+            T ev[kPoolUnroll];
+            int col[kPoolUnroll];
+#pragma unroll
+            for (int u = 0; u < kPoolUnroll; ++u) {            // every load is issued (index clamped), none waits
+                const int i = min(i0 + u * 64 + lane, count - 1);
+                const int r = i / per_row, c = i - r * per_row;
+                col[u] = first + c;
+                if (WORDS) wv[u] = reinterpret_cast<const uint32_t *>(mask)[base + (size_t)r * row_units + c];
+                else ev[u] = mask[base + (size_t)r * row_units + c];
+            }
+#pragma unroll
+            for (int u = 0; u < kPoolUnroll; ++u) {
+                const bool live = i0 + u * 64 + lane < count;
+                if (WORDS) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int x = col[u] * 4 + k;
+                        const Acc v = (live && x >= xlo && x < xhi) ? (Acc)((wv[u] >> (8 * k)) & 0xffu) : neutral;
+                        a = POOL == SBNET_POOL_AVG ? a + v : (v > a ? v : a);
+                    }
+                } else {
+                    const Acc v = live ? (Acc)ev[u] : neutral;
+                    a = POOL == SBNET_POOL_AVG ? a + v : (v > a ? v : a);
+                }
+            }
+        }
+    }
+    if (sizeof(Acc) == 4) {       // integer pools of a u8 mask: never negative, identity 0
+        a = (Acc)wave_pool_nonneg<POOL>((int)(POOL == SBNET_POOL_AVG ? a : (a < (Acc)0 ? (Acc)0 : a)));
+    } else {
+        a = wave_pool_any<Acc, POOL>(a);
+    }
+    if (lane == 63) {
+        if (POOL == SBNET_POOL_MAX && clipped) a = a < (Acc)0 ? (Acc)0 : a;      // outside counts as 0
+        const double area = (double)g.bsize_h * (double)g.bsize_w;
+        const double pooled = POOL == SBNET_POOL_AVG ? (double)a / area : (double)a;
+        flags[blk] = pooled > threshold ? (uint8_t)1 : (uint8_t)0;
+    }
+}
+
+// The common case, tuned for latency: u8 mask, W % 4 == 0, 4-byte aligned.  A lane owns one aligned word of
+// one window row per batch: LP = 2^lp_shift lanes side by side cover a row's words, 64 / LP rows per batch.
+// Bytes beside the window are cleared with one AND; the sum of a word's bytes is one instruction.  The
+// threshold is an integer cutoff worked out on the host (smallest pool value that counts as active), so
+// the decision needs no division here and is the same decision bit for bit.
+template <int POOL>
+__global__ __launch_bounds__(kRmThreads) void rm_pool_blocks_u8w(const uint32_t *__restrict__ mask, int H, int W4,
+                                                                  sbnet_geom g, BlockDivs dv, int total, int lp_shift,
+                                                                  int cutoff, uint8_t *__restrict__ flags) {
+    const int lane = threadIdx.x & 63;
+    const int blk = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRmThreads / 64) + (threadIdx.x >> 6)));
+    if (blk >= total) return;                                 // uniform over the wavefront
+    const int n = (int)fdiv((uint32_t)blk, dv.per_sample);
+    const int rem = blk - n * g.bcount_h * g.bcount_w;
+    const int by = (int)fdiv((uint32_t)rem, dv.per_row), bx = rem - by * g.bcount_w;
+    const int y0 = g.boffset_h + by * g.bstride_h, x0 = g.boffset_w + bx * g.bstride_w;
+    const int ylo = max(y0, 0), yhi = min(y0 + g.bsize_h, H);
+    const int xlo = max(x0, 0), xhi = min(x0 + g.bsize_w, W4 * 4);
+    int a = 0;
+    if (yhi > ylo && xhi > xlo) {                             // uniform: the window meets the image
+        const int w_lo = xlo >> 2, w_hi = (xhi - 1) >> 2;     // first and last word of a window row
+        const int lp = 1 << lp_shift;
+        const int c = lane & (lp - 1), r = lane >> lp_shift, rows_per = 64 >> lp_shift;
+        const uint32_t *base = mask + ((size_t)n * H) * W4;
+        for (int c0 = w_lo; c0 <= w_hi; c0 += lp) {
+            const int wc = c0 + c;
+            // bytes of word wc inside [xlo, xhi)
+            uint32_t keep = 0xffffffffu;
+            if (wc == w_lo) keep &= 0xffffffffu << (8 * (xlo & 3));
+            if (wc == w_hi) keep &= 0xffffffffu >> (8 * (3 - ((xhi - 1) & 3)));
+            if (wc > w_hi) keep = 0u;
+            const int wcl = min(wc, w_hi);
+            for (int r0 = ylo; r0 < yhi; r0 += rows_per * kPoolUnroll) {
+                uint32_t q[kPoolUnroll];
+#pragma unroll
+                for (int u = 0; u < kPoolUnroll; ++u)            // clamped: every load is issued, none waits
+                    q[u] = base[(size_t)min(r0 + u * rows_per + r, yhi - 1) * W4 + wcl];
+#pragma unroll
+                for (int u = 0; u < kPoolUnroll; ++u) {
+                    const uint32_t w = (r0 + u * rows_per + r < yhi) ? (q[u] & keep) : 0u;
+                    if (POOL == SBNET_POOL_AVG) {
+                        a = (int)__builtin_amdgcn_sad_u8(w, 0u, (uint32_t)a);
+                    } else {
+                        const uint32_t m01 = max(w & 0xffu, (w >> 8) & 0xffu), m23 = max((w >> 16) & 0xffu, w >> 24);
+                        a = max(a, (int)max(m01, m23));
+                    }
+                }
+            }
+        }
+    }
+    a = wave_pool_nonneg<POOL>(a);
+    if (lane == 63) flags[blk] = a >= cutoff ? (uint8_t)1 : (uint8_t)0;
+}
+
+// number of non-zero bytes among the first `valid` (0..16) bytes of q
+__device__ __forceinline__ int count_flags16(uint4 q, int valid) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    int c = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t t = w[k];
+        const int keep = min(max(valid - 4 * k, 0), 4);                  // bytes of this word that count
+        t = keep >= 4 ? t : (keep <= 0 ? 0u : (t & ((1u << (8 * keep)) - 1u)));
+        t |= t >> 4; t |= t >> 2; t |= t >> 1;                            // bit 0 of every byte: byte != 0
+        c += __popc(t & 0x01010101u);
+    }
+    return c;
+}
+
+// flags: one byte per block in lexicographic order, padded to a multiple of 16 bytes (the padding is never counted)
+__global__ __launch_bounds__(kRmThreads) void rm_compact_flags(const uint8_t *__restrict__ flags, int total, sbnet_geom g,
+                                                                BlockDivs dv, int32_t *__restrict__ indices,
+                                                                int32_t *__restrict__ count, int cap) {
+    __shared__ int red[4];
+    __shared__ int wave_cnt[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int start = blockIdx.x * kRmThreads;                // first block of this workgroup's run (multiple of 16)
+    const int blk = start + (int)threadIdx.x;
+    const bool on = blk < total && flags[blk] != 0;           // travels together with the loads of the count
+    int part = 0;
+    for (int v = threadIdx.x; v * 16 < start; v += kRmThreads)
+        part += count_flags16(reinterpret_cast<const uint4 *>(flags)[v], 16);
+    const int base = block_sum(part, red);                    // active blocks in front of the run
+    const unsigned long long ballot = __ballot(on);
+    if (lane == 0) wave_cnt[wave] = __popcll(ballot);
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+    if (on) {
+        const int pos = base + before + __popcll(ballot & ((1ull << lane) - 1ull));
+        if (pos < cap) {
+            const int n = (int)fdiv((uint32_t)blk, dv.per_sample);
+            const int rem = blk - n * g.bcount_h * g.bcount_w;
+            const int by = (int)fdiv((uint32_t)rem, dv.per_row);
+            indices[3 * (size_t)pos + 0] = n;
+            indices[3 * (size_t)pos + 1] = by;
+            indices[3 * (size_t)pos + 2] = rem - by * g.bcount_w;
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *count = base + wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+}
+
 }  // namespace sbnet
 
 using namespace sbnet;
@@ -182,6 +396,84 @@ extern "C" size_t sbnet_workspace_bytes(int N, const sbnet_geom *g) {
     return rowcount_bytes((int)rows) + ((rows * g->bcount_w + 15) & ~(size_t)15);
 }
 
+namespace sbnet {
+
+static sbnet_status check_mask_args(const char *who, const void *mask, sbnet_dtype mdt, int N, int H, int W,
+                                    const sbnet_geom *g, sbnet_pool pool) {
+    if (!mask) return fail(SBNET_EINVAL, "%s: null pointer", who);
+    if (N <= 0 || H <= 0 || W <= 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
+    if (!geom_ok(g)) return fail(SBNET_EINVAL, "%s: bad geometry", who);
+    if (pool != SBNET_POOL_MAX && pool != SBNET_POOL_AVG) return fail(SBNET_EINVAL, "%s: bad pool", who);
+    if (mdt != SBNET_U8 && mdt != SBNET_F32) return fail(SBNET_EUNSUPPORTED, "%s: mask must be u8 or f32", who);
+    if ((long long)N * g->bcount_h * g->bcount_w > 0x7fffffffLL || (long long)N * g->bcount_h > 0x7fffffffLL)
+        return fail(SBNET_EUNSUPPORTED, "%s: more than 2^31 blocks", who);
+    return SBNET_OK;
+}
+
+bool mask_flag_path(int N, const sbnet_geom *g) {
+    return (long long)N * g->bcount_h * g->bcount_w <= kFlagPathMaxBlocks;
+}
+
+BlockDivs block_divs(const sbnet_geom *g) {
+    BlockDivs dv;
+    dv.per_sample = make_fastdiv((uint32_t)g->bcount_h * (uint32_t)g->bcount_w);
+    dv.per_row = make_fastdiv((uint32_t)g->bcount_w);
+    return dv;
+}
+
+// Pass 1 of the small-grid path: flags[blk] = 1 where block blk (lexicographic) is active, else 0, for all
+// N * bcount_h * bcount_w blocks; flags must hold that many bytes rounded up to 16.
+sbnet_status mask_to_flags(const char *who, const void *mask, sbnet_dtype mdt, int N, int H, int W,
+                           const sbnet_geom *g, sbnet_pool pool, float threshold, uint8_t *flags, hipStream_t s) {
+    sbnet_status st = check_mask_args(who, mask, mdt, N, H, W, g, pool);
+    if (st != SBNET_OK) return st;
+    if (!flags) return fail(SBNET_EINVAL, "%s: null pointer", who);
+    if (!mask_flag_path(N, g)) return fail(SBNET_EUNSUPPORTED, "%s: more than %d blocks", who, kFlagPathMaxBlocks);
+    const int total = N * g->bcount_h * g->bcount_w;
+    const BlockDivs dv = block_divs(g);
+    const double thr = (double)threshold;
+    const dim3 grid((unsigned)((total + kRmThreads / 64 - 1) / (kRmThreads / 64)));
+    const bool words = mdt == SBNET_U8 && (W % 4 == 0) && (((uintptr_t)mask) % 4 == 0);
+    if (words) {
+        // Smallest integer pool value v that counts as active: the decision everywhere is
+        // (avg ? (double)v / area : (double)v) > (double)threshold, monotone in v, so it is a cutoff on v.
+        const double area = (double)g->bsize_h * (double)g->bsize_w;
+        const long long vmax = pool == SBNET_POOL_AVG ? 255LL * g->bsize_h * g->bsize_w : 255LL;
+        auto active = [&](long long v) { return (pool == SBNET_POOL_AVG ? (double)v / area : (double)v) > thr; };
+        long long lo = 0, hi = vmax + 1;                      // active(hi) taken as true: hi = "never"
+        if (active(0)) hi = 0;
+        while (hi - lo > 1) {                                 // invariant: !active(lo), hi active or vmax + 1
+            const long long mid = lo + (hi - lo) / 2;
+            if (active(mid)) hi = mid; else lo = mid;
+        }
+        if (hi <= 0x7fffffffLL) {
+            int words_per_row = (g->bsize_w + 6) / 4, lp_shift = 0;           // most words a window row can touch
+            while ((1 << lp_shift) < words_per_row && lp_shift < 6) ++lp_shift;
+            if (pool == SBNET_POOL_MAX)
+                hipLaunchKernelGGL((rm_pool_blocks_u8w<SBNET_POOL_MAX>), grid, dim3(kRmThreads), 0, s, (const uint32_t *)mask, H,
+                                   W / 4, *g, dv, total, lp_shift, (int)hi, flags);
+            else
+                hipLaunchKernelGGL((rm_pool_blocks_u8w<SBNET_POOL_AVG>), grid, dim3(kRmThreads), 0, s, (const uint32_t *)mask, H,
+                                   W / 4, *g, dv, total, lp_shift, (int)hi, flags);
+            return launch_status(who);
+        }
+    }
+#define SBNET_RM_BLOCKS(T, ACC, P, WORDS)                                                               \
+    hipLaunchKernelGGL((rm_pool_blocks<T, ACC, P, WORDS>), grid, dim3(kRmThreads), 0, s, (const T *)mask, H, W, *g, \
+                       dv, total, thr, flags)
+    if (mdt == SBNET_U8) {
+        if (pool == SBNET_POOL_MAX) { if (words) SBNET_RM_BLOCKS(uint8_t, int, SBNET_POOL_MAX, true); else SBNET_RM_BLOCKS(uint8_t, int, SBNET_POOL_MAX, false); }
+        else { if (words) SBNET_RM_BLOCKS(uint8_t, int, SBNET_POOL_AVG, true); else SBNET_RM_BLOCKS(uint8_t, int, SBNET_POOL_AVG, false); }
+    } else {
+        if (pool == SBNET_POOL_MAX) SBNET_RM_BLOCKS(float, double, SBNET_POOL_MAX, false);
+        else SBNET_RM_BLOCKS(float, double, SBNET_POOL_AVG, false);
+    }
+#undef SBNET_RM_BLOCKS
+    return launch_status(who);
+}
+
+}  // namespace sbnet
+
 // Argument checks and the two launches shared by both entry points; `workspace` is device memory of at
 // least sbnet_workspace_bytes(N, g), every byte the kernels read from it is written by pass 1 first.
 static sbnet_status reduce_mask_launch(const void *mask, sbnet_dtype mdt, int N, int H, int W,
@@ -189,23 +481,27 @@ static sbnet_status reduce_mask_launch(const void *mask, sbnet_dtype mdt, int N,
                                        int32_t *indices, int32_t *count, int cap, void *workspace,
                                        size_t ws_bytes, void *stream) {
     if (!mask || !indices || !count || !workspace) return fail(SBNET_EINVAL, "sbnet_reduce_mask: null pointer");
-    if (N <= 0 || H <= 0 || W <= 0 || cap < 0) return fail(SBNET_EINVAL, "sbnet_reduce_mask: bad sizes");
-    if (!geom_ok(g)) return fail(SBNET_EINVAL, "sbnet_reduce_mask: bad geometry");
-    if (pool != SBNET_POOL_MAX && pool != SBNET_POOL_AVG) return fail(SBNET_EINVAL, "sbnet_reduce_mask: bad pool");
-    if (mdt != SBNET_U8 && mdt != SBNET_F32)
-        return fail(SBNET_EUNSUPPORTED, "sbnet_reduce_mask: mask must be u8 or f32");
+    if (cap < 0) return fail(SBNET_EINVAL, "sbnet_reduce_mask: bad sizes");
+    sbnet_status st = check_mask_args("sbnet_reduce_mask", mask, mdt, N, H, W, g, pool);
+    if (st != SBNET_OK) return st;
     if (ws_bytes < sbnet_workspace_bytes(N, g)) return fail(SBNET_EINVAL, "sbnet_reduce_mask: workspace too small");
-    const long long rows_ll = (long long)N * g->bcount_h;
-    if (rows_ll * g->bcount_w > 0x7fffffffLL || rows_ll > 0x7fffffffLL)
-        return fail(SBNET_EUNSUPPORTED, "sbnet_reduce_mask: more than 2^31 blocks");
-    const int rows = (int)rows_ll;
+    hipStream_t s = (hipStream_t)stream;
+    if (mask_flag_path(N, g)) {
+        uint8_t *flags = (uint8_t *)workspace;
+        st = mask_to_flags("sbnet_reduce_mask(pool)", mask, mdt, N, H, W, g, pool, threshold, flags, s);
+        if (st != SBNET_OK) return st;
+        const int total = N * g->bcount_h * g->bcount_w;
+        hipLaunchKernelGGL(rm_compact_flags, dim3((unsigned)((total + kRmThreads - 1) / kRmThreads)), dim3(kRmThreads), 0, s,
+                           flags, total, *g, block_divs(g), indices, count, cap);
+        return launch_status("sbnet_reduce_mask(compact)");
+    }
+    const int rows = N * g->bcount_h;
     const size_t acc_bytes = mdt == SBNET_U8 ? 4 : 8;
     const size_t lds = (size_t)W * acc_bytes;
     if (lds > 128 * 1024) return fail(SBNET_EUNSUPPORTED, "sbnet_reduce_mask: W too large for the column buffer");
 
     int32_t *rowcount = (int32_t *)workspace;
     uint8_t *flags = (uint8_t *)workspace + rowcount_bytes(rows);
-    hipStream_t s = (hipStream_t)stream;
     const double thr = (double)threshold;
 
     const bool vec4 = (W % 4 == 0) && (((uintptr_t)mask) % 16 == 0);
@@ -232,7 +528,7 @@ static sbnet_status reduce_mask_launch(const void *mask, sbnet_dtype mdt, int N,
     }
 #undef SBNET_RM_LAUNCH
 #undef SBNET_RM_LAUNCH1
-    sbnet_status st = launch_status("sbnet_reduce_mask(pool)");
+    st = launch_status("sbnet_reduce_mask(pool)");
     if (st != SBNET_OK) return st;
     hipLaunchKernelGGL(rm_compact, dim3(rows), dim3(kRmThreads), 0, s, rowcount, flags, rows, g->bcount_h,
                        g->bcount_w, indices, count, cap);

@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # compile (if needed) and load the CPU oracle once, before anything in this process initialises a GPU
+    import oracle
+    oracle.build()
+    oracle._c()
 
 
 def _have_gpu():
