@@ -518,7 +518,15 @@ def main():
         m, _, frac = gen.calibrate(lambda s: gen.road_band_mask(fields, s), count_active, total_blocks, target, 0.0, 12.0)
         return m, frac
 
+    flags = torch.empty((sb.lib().sbnet_block_flags_bytes(1, g_in),), dtype=torch.uint8, device=dev)
+
     def step_fused(mask_d):
+        """the whole path, mask -> y (and the index list, for later consumers): two launches"""
+        sb.block_flags(mask_d, g_in, sb.POOL_AVG, 0.0, flags)
+        sb.sparse_conv_from_flags(flags, x, g_in, g_out, wp, bias, y, idx, cnt)
+
+    def step_three_launches(mask_d):
+        """the same through the four-call interface's first and fused last call: reduce_mask (2 launches) + sparse_conv"""
         sb.reduce_mask(mask_d, g_in, sb.POOL_AVG, 0.0, idx, cnt, ws)
         sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y)
 
@@ -624,8 +632,12 @@ def main():
 
     # per-kernel device time: graphs of 20 back-to-back launches of one entry point, HIP events
     tk = time_kernel if (graph_ok and not args.eager_kernel_timing) else (lambda fn: time_events(fn, 200))
-    conv_ms = tk(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y))
+    sb.block_flags(mask_d, g_in, sb.POOL_AVG, 0.0, flags)
+    conv_ms = tk(lambda: sb.sparse_conv_from_flags(flags, x, g_in, g_out, wp, bias, y, idx, cnt))
+    flags_ms = tk(lambda: sb.block_flags(mask_d, g_in, sb.POOL_AVG, 0.0, flags))
+    conv_idx_ms = tk(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y))
     reduce_ms = tk(lambda: sb.reduce_mask(mask_d, g_in, sb.POOL_AVG, 0.0, idx, cnt, ws))
+    three_ms = time_step_graph(lambda: step_three_launches(mask_d), args.steps, args.warmup)[0] if graph_ok else None
     count_active(mask_np)                                          # leave idx/cnt consistent
 
     flops = TILE_FLOPS * nact
@@ -654,17 +666,23 @@ def main():
         "config": {"workload": "cfg2: sparse 3x3 conv bf16 NHWC, N=1 H=800 W=704 C=64->64, block 16x16 + halo 1, "
                                "road-band mask", "target_active_block_fraction": args.density,
                    "active_blocks": nact, "total_blocks": total_blocks, "active_block_fraction": round(frac, 4),
-                   "mask_pixel_density": round(pix_density, 4), "step": "reduce_mask + fused gather/conv/scatter",
+                   "mask_pixel_density": round(pix_density, 4),
+                   "step": "block_flags (mask -> one flag per block) + sparse_conv_from_flags (compaction in the prologue, "
+                           "gather / MFMA conv / scatter; also writes the index list and count)",
                    "timing": ("HIP events around %d steps replayed from HIP graphs of %d steps each (always at least "
                               "50 replays, warm-up in whole replays)" % (steps_timed, INNER)) if graph_ok
                    else "eager launches, wall clock between device syncs", "steps_timed": steps_timed},
         "ms_per_step_wall_clock_same_region": None if wall_ms is None else round(wall_ms, 6),
         "ms_per_step_eager": round(eager_ms, 6),
         "ms_per_step_one_graph_per_step": round(single_graph_ms, 6),
-        "kernel_ms": {"reduce_mask(2 kernels)": round(reduce_ms, 6), "sparse_conv(fused mfma)": round(conv_ms, 6)},
+        "kernel_ms": {"block_flags(rm_pool_blocks)": round(flags_ms, 6),
+                      "sparse_conv_from_flags(conv16_kernel, flag-fed)": round(conv_ms, 6)},
+        "three_launch_path": {"ms_per_step": None if three_ms is None else round(three_ms, 6),
+                              "reduce_mask(2 kernels)_ms": round(reduce_ms, 6),
+                              "sparse_conv(conv16_kernel, index-fed)_ms": round(conv_idx_ms, 6)},
         "effective_tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 3),
         # AI of the fused kernel = 18 874 368 FLOP / 74 240 B = 254 FLOP/B, below the ridge 2500 / 8 = 312: HBM-bound
-        "roofline": {"bound": "hbm", "kernel": "conv16_kernel<bf16,64,fused>",
+        "roofline": {"bound": "hbm", "kernel": "conv16_kernel<bf16,64,fused,flag-fed>",
                      "achieved": round(TILE_BYTES * nact / (conv_ms * 1e-3) / 1e9, 2), "peak": PEAK_HBM_GBS,
                      "unit": "GB/s", "frac": round(TILE_BYTES * nact / (conv_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 5),
                      "traffic": traffic, "algorithmic_bytes_per_launch": TILE_BYTES * nact,
@@ -683,7 +701,8 @@ def main():
             n = count_active(m_np)
             t_step = time_step_graph(lambda: step_fused(m_d), args.steps, args.warmup)[0] if graph_ok else \
                 time_steps(lambda: step_fused(m_d), 100, 10)
-            t_conv = tk(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y))
+            sb.block_flags(m_d, g_in, sb.POOL_AVG, 0.0, flags)
+            t_conv = tk(lambda: sb.sparse_conv_from_flags(flags, x, g_in, g_out, wp, bias, y, idx, cnt))
             tiles_buf[0] = torch.empty((n, BO + 2, BO + 2, C), dtype=torch.bfloat16, device=dev)
             tiles_buf[1] = torch.empty((n, BO, BO, K), dtype=torch.bfloat16, device=dev)
             idx_small = idx[:n]

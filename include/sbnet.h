@@ -261,6 +261,55 @@ sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int N, int H, i
                                int add, void *stream);
 
 /*
+ * The pooling half of reduce_mask on its own (Sec. 3.1; Sec. 3.4 "fused downsample and indexing" stops
+ * one step earlier): flags[blk] = 1 where block blk = (n * bcount_h + by) * bcount_w + bx is active
+ * (same pooling and threshold rule as sbnet_reduce_mask), else 0, for every block of the grid.
+ * flags: device, sbnet_block_flags_bytes(N, g) bytes (one per block, rounded up to 16; the bytes behind
+ * the last block are written as 0), 16-byte aligned.
+ * Grids of more than 65 536 blocks return SBNET_EUNSUPPORTED (use sbnet_reduce_mask).
+ */
+size_t sbnet_block_flags_bytes(int N, const sbnet_geom *g);
+sbnet_status sbnet_block_flags(const void *mask, sbnet_dtype mask_dtype, int N, int H, int W,
+                               const sbnet_geom *g, sbnet_pool pool, float threshold, uint8_t *flags,
+                               size_t flags_bytes, void *stream);
+
+/*
+ * sbnet_sparse_conv fed by the block flags instead of the index list (Fig. 1 with the second half of
+ * Sec. 3.1 moved into the consumer): the same y as sbnet_sparse_conv on the list those flags compact to,
+ * and that list and its count are written to indices / count for later calls.  Where the convolution
+ * kernel can take flags (3x3, stride 1, 16 x 16 output blocks, 32 or 64 input channels, bf16 / f16) every
+ * workgroup compacts them in its prologue while its weights arrive, which saves reduce_mask's second
+ * launch; every other shape compacts the flags in a launch of its own and runs sbnet_sparse_conv.
+ * The block grid of g_in and g_out is the one the flags were made for; at most 65 536 blocks.  flags is
+ * what sbnet_block_flags writes: every byte 0 or 1, sbnet_block_flags_bytes(N, g_in) of them, zero behind
+ * the last block.
+ */
+sbnet_status sbnet_sparse_conv_from_flags(const uint8_t *flags, const void *x, sbnet_dtype dtype, int N,
+                                          int H, int W, int Cin, int32_t *indices, int32_t *count, int cap,
+                                          const sbnet_geom *g_in, const sbnet_geom *g_out,
+                                          const void *w_packed, const float *bias, int kh, int kw, int sh,
+                                          int sw, int Cout, int relu, void *y, int H_out, int W_out, int add,
+                                          void *stream);
+
+/*
+ * Mask in, convolved active blocks out, in one call (Fig. 1 end to end): sbnet_block_flags into the
+ * workspace followed by sbnet_sparse_conv_from_flags; grids beyond 65 536 blocks run sbnet_reduce_mask and
+ * sbnet_sparse_conv.  Same results as those calls, in y and in indices / count.
+ * mask: [N][mask_H][mask_W] (u8 or f32), pooled over the windows of g_mask, whose block grid must be that
+ * of g_in and g_out (for a stride-1 convolution the mask has the input's extent and g_mask is g_in or the
+ * output-block geometry).  workspace: at least sbnet_workspace_bytes(N, g_mask), 16-byte aligned, contents
+ * don't-care.  All other arguments as in the calls it stands for.
+ */
+sbnet_status sbnet_sparse_conv_from_mask(const void *mask, sbnet_dtype mask_dtype, int mask_H, int mask_W,
+                                         const sbnet_geom *g_mask, sbnet_pool pool, float threshold,
+                                         const void *x, sbnet_dtype dtype, int N, int H, int W, int Cin,
+                                         int32_t *indices, int32_t *count, int cap,
+                                         const sbnet_geom *g_in, const sbnet_geom *g_out,
+                                         const void *w_packed, const float *bias, int kh, int kw, int sh,
+                                         int sw, int Cout, int relu, void *y, int H_out, int W_out, int add,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Data gradient of sbnet_conv_on_tiles (training support for the tile convolution of Sec. 3.2;
  * the paper's own evaluation is inference only).  For y = valid convolution of x with W at stride
  * (sh, sw), no bias and no activation, and a given dL/dy this writes

@@ -82,6 +82,12 @@ _SIGNATURES = {
     "sbnet_conv_on_tiles": (_ci, [_vp, _ci, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp]),
     "sbnet_sparse_conv": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp,
                                 _ci, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _vp]),
+    "sbnet_block_flags_bytes": (_sz, [_ci, _gp]),
+    "sbnet_block_flags": (_ci, [_vp, _ci, _ci, _ci, _ci, _gp, _ci, ctypes.c_float, _vp, _sz, _vp]),
+    "sbnet_sparse_conv_from_flags": (_ci, [_vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp,
+                                           _ci, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _vp]),
+    "sbnet_sparse_conv_from_mask": (_ci, [_vp, _ci, _ci, _ci, _gp, _ci, ctypes.c_float, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci,
+                                          _gp, _gp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _vp, _sz, _vp]),
     "sbnet_zero_outside": (_ci, [_vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp]),
     "sbnet_bottleneck_on_tiles": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp,
                                         _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -557,6 +563,58 @@ def sparse_conv(x, indices, count, g_in, g_out, w_packed, bias, y, stride=1, rel
     _check(lib().sbnet_sparse_conv(_ptr(x), _dt(x), N, H, W, Cin, _ptr(indices), _ptr(count), indices.shape[0],
                                    g_in, g_out, _ptr(w_packed.buf), _ptr(bias), kh, kw, stride, stride, Cout,
                                    int(bool(relu)), _ptr(y), Ho, Wo, int(bool(add)), _stream()))
+    return y
+
+
+def block_flags(mask, g, pool=POOL_AVG, threshold=0.0, flags=None):
+    """mask [N,H,W] u8/f32 -> one flag byte per block (lexicographic), padded to a multiple of 16 bytes."""
+    _dev(mask, "mask")
+    N, H, W = mask.shape
+    need = lib().sbnet_block_flags_bytes(N, g)
+    if flags is None:
+        flags = torch.empty((need,), dtype=torch.uint8, device=mask.device)
+    _dev(flags, "flags", torch.uint8)
+    _check(lib().sbnet_block_flags(_ptr(mask), _dt(mask), N, H, W, g, pool, float(threshold), _ptr(flags), flags.numel(),
+                                   _stream()))
+    return flags
+
+
+def sparse_conv_from_flags(flags, x, g_in, g_out, w_packed, bias, y, indices, count, stride=1, relu=False, add=False):
+    """Fused sparse conv fed by block flags; fills y in place and writes the index list and count.  Returns y."""
+    _dev(flags, "flags", torch.uint8), _dev(x, "x"), _dev(y, "y", x.dtype)
+    _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    kh, kw, Cin, Cout = w_packed.shape
+    N, H, W, C = x.shape
+    assert C == Cin and w_packed.dtype == x.dtype
+    Ny, Ho, Wo, Cy = y.shape
+    assert Ny == N and Cy == Cout and flags.numel() >= lib().sbnet_block_flags_bytes(N, g_in)
+    if bias is not None:
+        _dev(bias, "bias", torch.float32)
+    _check(lib().sbnet_sparse_conv_from_flags(_ptr(flags), _ptr(x), _dt(x), N, H, W, Cin, _ptr(indices), _ptr(count),
+                                              indices.shape[0], g_in, g_out, _ptr(w_packed.buf), _ptr(bias), kh, kw, stride,
+                                              stride, Cout, int(bool(relu)), _ptr(y), Ho, Wo, int(bool(add)), _stream()))
+    return y
+
+
+def sparse_conv_from_mask(mask, g_mask, x, g_in, g_out, w_packed, bias, y, indices, count, workspace, pool=POOL_AVG,
+                          threshold=0.0, stride=1, relu=False, add=False):
+    """reduce_mask + fused sparse conv in one call (two launches where the convolution kernel takes block flags);
+    fills y in place and leaves the index list and the count in indices / count.  Returns y."""
+    _dev(mask, "mask"), _dev(x, "x"), _dev(y, "y", x.dtype), _dev(workspace, "workspace")
+    _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    kh, kw, Cin, Cout = w_packed.shape
+    N, H, W, C = x.shape
+    Nm, mH, mW = mask.shape
+    assert C == Cin and w_packed.dtype == x.dtype and Nm == N
+    Ny, Ho, Wo, Cy = y.shape
+    assert Ny == N and Cy == Cout
+    if bias is not None:
+        _dev(bias, "bias", torch.float32)
+    _check(lib().sbnet_sparse_conv_from_mask(_ptr(mask), _dt(mask), mH, mW, g_mask, pool, float(threshold), _ptr(x), _dt(x),
+                                             N, H, W, Cin, _ptr(indices), _ptr(count), indices.shape[0], g_in, g_out,
+                                             _ptr(w_packed.buf), _ptr(bias), kh, kw, stride, stride, Cout, int(bool(relu)),
+                                             _ptr(y), Ho, Wo, int(bool(add)), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream()))
     return y
 
 

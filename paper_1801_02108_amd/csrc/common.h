@@ -31,6 +31,16 @@ inline bool geom_ok(const sbnet_geom *g) {
            g->bcount_h > 0 && g->bcount_w > 0;
 }
 
+// reduce_mask.hip, pass 1 of the small-grid path, also used by the fused consumers: one flag byte per block in
+// lexicographic (n, by, bx) order.  `flags` must hold N * bcount_h * bcount_w bytes rounded up to 16.
+bool mask_flag_path(int N, const sbnet_geom *g);
+sbnet_status mask_to_flags(const char *who, const void *mask, sbnet_dtype mdt, int N, int H, int W, const sbnet_geom *g,
+                           sbnet_pool pool, float threshold, uint8_t *flags, hipStream_t s);
+
+// pass 2 of the same path: flags -> index list and count
+sbnet_status flags_to_indices(const char *who, const uint8_t *flags, int N, const sbnet_geom *g, int32_t *indices,
+                              int32_t *count, int cap, hipStream_t s);
+
 inline sbnet_status launch_status(const char *what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(SBNET_EHIP, "%s: %s", what, hipGetErrorString(e));
@@ -55,6 +65,34 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv f) {
     // round-up method: q = (t + ((n - t) >> 1)) >> (s - 1), t = mulhi(n, m); valid for all n < 2^32
     uint32_t t = __umulhi(n, f.m);
     return f.s == 0 ? n : (t + ((n - t) >> 1)) >> (f.s - 1);
+}
+
+// Inclusive prefix sum of a non-negative int over the 64 lanes (lane 63: the total): four shifts inside the
+// rows of 16 lanes, then the row totals are passed on to the next row and to the upper half.  Cross-lane
+// moves in the VALU's data path, no LDS round trips; lanes without a source read 0.
+__device__ __forceinline__ int wave_inclusive_sum(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// 16-bit mask of the non-zero bytes among the first `valid` (0..16) bytes of q (bit i = byte i)
+__device__ __forceinline__ uint32_t nonzero_bytes16(uint4 q, int valid) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+    uint32_t bits = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t t = w[k];
+        t |= t >> 4; t |= t >> 2; t |= t >> 1;
+        t &= 0x01010101u;                                        // bit 0 of every byte: byte != 0
+        t = (t | (t >> 7) | (t >> 14) | (t >> 21)) & 0xfu;       // gathered into four neighbouring bits
+        bits |= t << (4 * k);
+    }
+    return valid >= 16 ? bits : (valid <= 0 ? 0u : bits & ((1u << valid) - 1u));
 }
 
 // bf16 <-> fp32 on the device (round to nearest even; NaN kept quiet)

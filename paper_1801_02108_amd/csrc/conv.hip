@@ -661,3 +661,82 @@ extern "C" sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int 
     p.H = H; p.W = W; p.Ho = H_out; p.Wo = W_out;
     return run_conv<true>(who, dtype, p, (hipStream_t)stream);
 }
+
+// Block flags in, convolved active blocks out: the fused convolution with reduce_mask's compaction folded into its
+// prologue where the kernel can take flags (3x3 stride 1, 16 x 16 output blocks, 32 or 64 input channels, bf16 / f16);
+// other shapes compact the flags in a launch of their own and run sbnet_sparse_conv.  Either way indices / count hold
+// the list afterwards.
+extern "C" sbnet_status sbnet_sparse_conv_from_flags(const uint8_t *flags, const void *x, sbnet_dtype dtype, int N, int H,
+                                                     int W, int Cin, int32_t *indices, int32_t *count, int cap,
+                                                     const sbnet_geom *g_in, const sbnet_geom *g_out, const void *w_packed,
+                                                     const float *bias, int kh, int kw, int sh, int sw, int Cout, int relu,
+                                                     void *y, int H_out, int W_out, int add, void *stream) {
+    const char *who = "sbnet_sparse_conv_from_flags";
+    if (!flags || !x || !indices || !count || !w_packed || !y) return fail(SBNET_EINVAL, "%s: null pointer", who);
+    if (N <= 0 || H <= 0 || W <= 0 || H_out <= 0 || W_out <= 0 || cap < 0) return fail(SBNET_EINVAL, "%s: bad sizes", who);
+    if (!geom_ok(g_in) || !geom_ok(g_out)) return fail(SBNET_EINVAL, "%s: bad geometry", who);
+    if (g_out->bcount_h != g_in->bcount_h || g_out->bcount_w != g_in->bcount_w)
+        return fail(SBNET_EINVAL, "%s: g_in and g_out must describe one block grid", who);
+    if (!mask_flag_path(N, g_in)) return fail(SBNET_EUNSUPPORTED, "%s: more blocks than the flag form takes", who);
+    if (((uintptr_t)flags) & 15) return fail(SBNET_EINVAL, "%s: flags must be 16-byte aligned", who);
+    hipStream_t s = (hipStream_t)stream;
+    bool fold = cap > 0 && x != y && !(((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_packed) & 15) &&
+                check_conv_shape(who, dtype, cap, g_in->bsize_h, g_in->bsize_w, Cin, kh, kw, sh, sw, Cout) == SBNET_OK &&
+                (g_in->bsize_h - kh) / sh + 1 == g_out->bsize_h && (g_in->bsize_w - kw) / sw + 1 == g_out->bsize_w &&
+                g_out->bstride_h >= g_out->bsize_h && g_out->bstride_w >= g_out->bsize_w && use_mfma(dtype, Cin, Cout);
+    ConvParams p = {};
+    if (fold) {
+        p.in = x; p.out = y; p.w = w_packed; p.bias = bias;
+        p.cap = cap;
+        p.th = g_in->bsize_h; p.tw = g_in->bsize_w; p.Cin = Cin; p.Cout = Cout;
+        p.kh = kh; p.kw = kw; p.sh = sh; p.sw = sw; p.relu = relu ? 1 : 0; p.add = add ? 1 : 0;
+        p.g_in = *g_in; p.g_out = *g_out;
+        p.H = H; p.W = W; p.Ho = H_out; p.Wo = W_out;
+        p.oh = g_out->bsize_h; p.ow = g_out->bsize_w;
+        p.w32_offset = packed_elems(dtype, kh, kw, Cin, Cout) / 2 / 8;
+        p.flags = flags;
+        p.total_blocks = N * g_in->bcount_h * g_in->bcount_w;
+        p.indices_out = indices; p.count_out = count;
+        fold = conv16_accepts(dtype, true, p);
+    }
+    if (!fold) {
+        sbnet_status st = flags_to_indices(who, flags, N, g_in, indices, count, cap, s);
+        if (st != SBNET_OK) return st;
+        return sbnet_sparse_conv(x, dtype, N, H, W, Cin, indices, count, cap, g_in, g_out, w_packed, bias, kh, kw, sh, sw, Cout,
+                                 relu, y, H_out, W_out, add, stream);
+    }
+    sbnet_status st = SBNET_OK;
+    if (!conv16_try(dtype, true, p, s, &st, who)) return fail(SBNET_EHIP, "%s: internal dispatch error", who);
+    return st;
+}
+
+// Mask in, convolved active blocks out, in one call: sbnet_block_flags + sbnet_sparse_conv_from_flags where the grid is
+// small enough for flags, sbnet_reduce_mask + sbnet_sparse_conv beyond.
+extern "C" sbnet_status sbnet_sparse_conv_from_mask(const void *mask, sbnet_dtype mask_dtype, int mask_H, int mask_W,
+                                                    const sbnet_geom *g_mask, sbnet_pool pool, float threshold,
+                                                    const void *x, sbnet_dtype dtype, int N, int H, int W, int Cin,
+                                                    int32_t *indices, int32_t *count, int cap, const sbnet_geom *g_in,
+                                                    const sbnet_geom *g_out, const void *w_packed, const float *bias,
+                                                    int kh, int kw, int sh, int sw, int Cout, int relu, void *y, int H_out,
+                                                    int W_out, int add, void *workspace, size_t workspace_bytes,
+                                                    void *stream) {
+    const char *who = "sbnet_sparse_conv_from_mask";
+    if (!mask || !workspace || !indices || !count) return fail(SBNET_EINVAL, "%s: null pointer", who);
+    if (N <= 0 || !geom_ok(g_mask) || !geom_ok(g_in)) return fail(SBNET_EINVAL, "%s: bad sizes or geometry", who);
+    if (g_mask->bcount_h != g_in->bcount_h || g_mask->bcount_w != g_in->bcount_w)
+        return fail(SBNET_EINVAL, "%s: the geometries must describe one block grid", who);
+    if (workspace_bytes < sbnet_workspace_bytes(N, g_mask)) return fail(SBNET_EINVAL, "%s: workspace too small", who);
+    sbnet_status st;
+    if (mask_flag_path(N, g_mask)) {
+        st = sbnet_block_flags(mask, mask_dtype, N, mask_H, mask_W, g_mask, pool, threshold, (uint8_t *)workspace,
+                               workspace_bytes, stream);
+        if (st != SBNET_OK) return st;
+        return sbnet_sparse_conv_from_flags((const uint8_t *)workspace, x, dtype, N, H, W, Cin, indices, count, cap, g_in, g_out,
+                                            w_packed, bias, kh, kw, sh, sw, Cout, relu, y, H_out, W_out, add, stream);
+    }
+    st = sbnet_reduce_mask(mask, mask_dtype, N, mask_H, mask_W, g_mask, pool, threshold, indices, count, cap, workspace,
+                           workspace_bytes, stream);
+    if (st != SBNET_OK) return st;
+    return sbnet_sparse_conv(x, dtype, N, H, W, Cin, indices, count, cap, g_in, g_out, w_packed, bias, kh, kw, sh, sw, Cout, relu,
+                             y, H_out, W_out, add, stream);
+}

@@ -56,10 +56,18 @@ struct Item16 {
 // branch on p.add: with two paths that issue different numbers of memory operations the compiler's wait counts
 // after the join are those of the shorter path, and the first LDS write of the next tile then waits for this
 // tile's stores to be acknowledged.
-template <int DT, int CIN, bool FUSED, bool ADD>
+// FLAGS (fused form, 16 x 16 blocks only): the active blocks come as one flag byte per block instead of an index
+// list.  Every wave counts the flags in its prologue (16 per lane and load, prefix sums across the lanes) and
+// notes the blocks of its workgroup's items in LDS; the workgroups also write the index triples of their items
+// and the count, so that the call leaves behind what reduce_mask would have.  This replaces reduce_mask's second launch, and the count
+// and index loads of the plain form, by work that overlaps the arrival of the weights.
+constexpr int kMineMax = 256;            // items per workgroup in the flag-fed form: 65 536 blocks / 256 workgroups
+
+template <int DT, int CIN, bool FUSED, bool ADD, bool FLAGS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void conv16_kernel(ConvParams p, Sub16 sp) {
     static_assert(FUSED || !ADD, "adding into the output is part of the fused form");
+    static_assert(FUSED || !FLAGS, "flags replace the index list of the fused form");
     constexpr int KC = CIN / 16;                     // 16-channel k-steps per tap
     constexpr int CV = CIN / 8;                      // 16-byte vectors per pixel
     constexpr int PS = (CIN + 8) * 2;                // LDS bytes per pixel
@@ -72,6 +80,7 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
     static_assert(NV <= NST, "one staging vector per pipeline stage");
     __shared__ __align__(16) unsigned char lds[2][LPX * PS];
     __shared__ __align__(16) unsigned char ostage[4][8 * 16 * kOutPs];       // per wave: 8 rows x 16 pixels of results
+    __shared__ uint32_t mine_all[4][FLAGS ? kMineMax : 1];      // FLAGS: block number of this workgroup's k-th item, one copy per wave
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -79,6 +88,7 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
     const int prow = m >> 4, pcol = m & 15;
     const int rh = wave >> 1, nh = wave & 1;
     const int ng = blockIdx.y;
+    uint32_t *mine = mine_all[wave];
     const uint32_t per_block = (uint32_t)sp.sub_h * sp.sub_w;
     const uint32_t G = gridDim.x;                    // multiple of 8
     // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of items
@@ -97,7 +107,14 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
         c.si = (int)fdiv(sidx, sp.div_subw);
         c.sj = (int)sidx - c.si * sp.sub_w;
         c.n = c.by = c.bx = 0;
-        if (FUSED) {
+        if (FLAGS) {
+            const uint32_t k = fdiv(it - first, p.div_grid);         // this workgroup's k-th item
+            const uint32_t blk = mine[k + lane_zero];
+            c.n = (int)fdiv(blk, p.div_bps);
+            const uint32_t rem = blk - (uint32_t)c.n * (uint32_t)(p.g_in.bcount_h * p.g_in.bcount_w);
+            c.by = (int)fdiv(rem, p.div_bw);
+            c.bx = (int)rem - c.by * p.g_in.bcount_w;
+        } else if (FUSED) {
             const int32_t *t = p.indices + 3 * (size_t)c.b + lane_zero;
             c.n = t[0];
             c.by = t[1];
@@ -115,17 +132,62 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
         return r;
     };
 
-    // The count and the first index triple are independent loads (the index is clamped into the
-    // buffer), so their latencies overlap instead of chaining.  Items past the end repeat the last
-    // one: its loads are harmless and nothing is stored for it (the loop has ended by then).
-    const int nact_raw = *p.count;
-    Item16 cur = request(min(first, (uint32_t)p.cap * per_block - 1u));
-    const uint32_t items = (uint32_t)max(min(nact_raw, p.cap), 0) * per_block;
-    if (first >= items) return;
-    const uint32_t last = items - 1u;
-    Item16 nx1 = request(min(first + G, last));
-    Item16 nx2 = request(min(first + 2 * G, last));
-    cur = resolve(cur);
+    // ---- Prologue.  Order of the requests (loads return in the order they were issued, and a workgroup's four
+    //      waves share one address unit that takes 16 cycles per 16-byte load instruction, so a wave's 36 weight
+    //      loads alone keep it busy for ~2300 cycles):
+    //        1. the few bytes the block list hangs on (count and first index triple, or the flags),
+    //        2. the bias and the weights of the first stages,
+    //        3. (after the list is known) the first tile,
+    //        4. the weights of the next few stages; the rest follows once the tile is in LDS (a workgroup with a
+    //           single tile requests them between its first MFMAs): they stream in faster than the matrix work
+    //           consumes them, and a wave that is busy issuing loads cannot move its tile to LDS.
+    //      Everything that does not depend on the block list is computed while those first bytes are on their way.
+    int nact_raw = 0;
+    constexpr int kEarly = 4;                         // flag vectors per lane requested up front: 4096 blocks
+    uint4 fl[kEarly];                                 // indexed by constants only: stays in registers
+    Item16 cur;
+    if (FLAGS) {
+        // no branch around a load (the wave would wait for it on the spot): the vector number is clamped into the
+        // flag buffer and what lies behind the last block is dropped when the flags are counted
+        const int last_vec = (p.total_blocks - 1) >> 4;
+#pragma unroll
+        for (int r = 0; r < kEarly; ++r) fl[r] = reinterpret_cast<const uint4 *>(p.flags)[min(lane * kEarly + r, last_vec)];
+    } else {
+        // The count and the first index triple are independent loads (the index is clamped into the
+        // buffer), so their latencies overlap instead of chaining.  Items past the end repeat the last
+        // one: its loads are harmless and nothing is stored for it (the loop has ended by then).
+        nact_raw = *p.count;
+        cur = request(min(first, (uint32_t)p.cap * per_block - 1u));
+    }
+    const int ch0 = ng * 64 + nh * 32 + g * 16;      // first of this lane's 16 output channels
+    f32x16 biasv;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) biasv[k] = 0.f;
+    if (p.bias) {                                    // Cout % 8 == 0: eight at a time
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            if (ch0 + h * 8 < p.Cout) {
+                const float4 b0 = *(const float4 *)(p.bias + ch0 + h * 8), b1 = *(const float4 *)(p.bias + ch0 + h * 8 + 4);
+                biasv[h * 8 + 0] = b0.x; biasv[h * 8 + 1] = b0.y; biasv[h * 8 + 2] = b0.z; biasv[h * 8 + 3] = b0.w;
+                biasv[h * 8 + 4] = b1.x; biasv[h * 8 + 5] = b1.y; biasv[h * 8 + 6] = b1.z; biasv[h * 8 + 7] = b1.w;
+            }
+    }
+    // weights of this wave: every k-step of its 32 output channels
+    uint4 wreg[KS];
+    const uint4 *wsrc = (const uint4 *)p.w + p.w32_offset + ((size_t)ng * KS * 2 + nh) * 64 + lane;
+    auto wload1 = [&](int st, int r) __attribute__((always_inline)) {       // k-step of tap row r that stage st multiplies with
+        const int ks = (r * 3 + st / KC) * KC + st % KC;
+        wreg[ks] = wsrc[(size_t)ks * 128];
+    };
+    auto wload = [&](int st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 3; ++r) wload1(st, r);
+    };
+    constexpr int kWFirst = 1;                        // stages whose weights go ahead of the first tile,
+    constexpr int kWPro = NST < 3 ? NST : 3;          // ... and stages whose weights are requested before its matrix work starts
+#pragma unroll
+    for (int st = 0; st < kWFirst; ++st) wload(st);
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- staging plan, the same for every tile: vector k of this thread is 16 bytes of pixel px0 + k*PXK
     //      of the 18x18 sub-tile (LDS has slots for the few pixel numbers past the end).
@@ -177,39 +239,93 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
     auto stash1 = [&](int buf, int k) __attribute__((always_inline)) {
         *(uint4 *)(&lds[buf][stash_off + k * PXK * PS]) = stage[k];
     };
+    __builtin_amdgcn_sched_barrier(0);
+
+    uint32_t kk = 0;                                 // FLAGS: number of this workgroup's items
+    if (FLAGS) {
+        // Compaction of the flag bytes (each 0 or 1, the padding behind the last block 0).  Every wave does all of it
+        // for itself, 4096 blocks per round: a lane takes 64 consecutive flags, a prefix sum over the lanes and the
+        // rounds gives the list positions of its active blocks.  Only the positions of this workgroup's own items
+        // (first, first + G, ...) are resolved to a block, by the one lane whose run contains them, into a table the
+        // wave keeps for itself: no barrier and no exchange between waves, and a round without an item of this
+        // workgroup costs some forty instructions.  per_block is 1 in this form: list position = item number.
+        int running = 0;
+        uint32_t pk = first;                         // list position of the next own item
+        static_assert(kEarly == 4, "the scan takes four flag vectors per lane and round");
+        auto count16 = [](uint4 v) __attribute__((always_inline)) { return __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w); };
+        // (the four vectors travel as values, not as an array: an array indexed at run time would live in scratch memory)
+        auto scan_round = [&](uint4 q0, uint4 q1, uint4 q2, uint4 q3, int b0) __attribute__((always_inline)) {
+            const int c0 = b0 < p.total_blocks ? count16(q0) : 0, c1 = b0 + 16 < p.total_blocks ? count16(q1) : 0;
+            const int c2 = b0 + 32 < p.total_blocks ? count16(q2) : 0, c3 = b0 + 48 < p.total_blocks ? count16(q3) : 0;
+            const int c = c0 + c1 + c2 + c3;
+            const int incl = wave_inclusive_sum(c);
+            const int excl = running + incl - c;
+            const int end = running + __builtin_amdgcn_readlane(incl, 63);
+            while ((int)pk < end && (int)pk < p.cap) {                   // uniform over the wave
+                if ((int)pk >= excl && (int)pk < excl + c) {             // one lane: find its (pk - excl)-th flag
+                    int skip = (int)pk - excl, r = 0;
+                    uint4 v = q0;
+                    if (skip >= c0) { skip -= c0; v = q1; r = 1;
+                        if (skip >= c1) { skip -= c1; v = q2; r = 2;
+                            if (skip >= c2) { skip -= c2; v = q3; r = 3; } } }
+                    // the 0/1 bytes of a word gathered into four neighbouring bits by one multiplication
+                    uint32_t bits = ((v.x * 0x01020408u) >> 24) | (((v.y * 0x01020408u) >> 24) << 4) |
+                                    (((v.z * 0x01020408u) >> 24) << 8) | (((v.w * 0x01020408u) >> 24) << 12);
+                    for (; skip > 0; --skip) bits &= bits - 1;
+                    mine[kk] = (uint32_t)(b0 + r * 16 + __ffs(bits) - 1);        // kk < kMineMax: checked on the host
+                }
+                pk += G;
+                ++kk;
+            }
+            running = end;
+        };
+        scan_round(fl[0], fl[1], fl[2], fl[3], lane * kEarly * 16);
+        for (int c0 = kEarly * 1024; c0 < p.total_blocks; c0 += kEarly * 1024) {
+            const int b0 = c0 + lane * kEarly * 16;
+            const int last_vec = (p.total_blocks - 1) >> 4;
+            const uint4 *fv = reinterpret_cast<const uint4 *>(p.flags);
+            const uint4 q0 = fv[min((b0 >> 4) + 0, last_vec)], q1 = fv[min((b0 >> 4) + 1, last_vec)];
+            const uint4 q2 = fv[min((b0 >> 4) + 2, last_vec)], q3 = fv[min((b0 >> 4) + 3, last_vec)];
+            scan_round(q0, q1, q2, q3, b0);
+        }
+        nact_raw = running;
+    }
+    const uint32_t items = (uint32_t)max(min(nact_raw, p.cap), 0) * per_block;
+    if (first >= items) {
+        // no item: all that is left is the count, should this be the workgroup that reports it
+        if (FLAGS && blockIdx.x == 0 && ng == 0 && threadIdx.x == 0) *p.count_out = nact_raw;
+        return;
+    }
+    const uint32_t last = items - 1u;
+    if (FLAGS) cur = request(first);
+    Item16 nx1 = request(min(first + G, last));
+    Item16 nx2 = request(min(first + 2 * G, last));
+    cur = resolve(cur);
 
     Src src = source(cur);
 #pragma unroll
-    for (int k = 0; k < NV; ++k) fetch1(src, k);     // first: the longest latency of the prologue
+    for (int k = 0; k < NV; ++k) fetch1(src, k);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int st = kWFirst; st < kWPro; ++st) wload(st);
     __builtin_amdgcn_sched_barrier(0);
 
-    const int ch0 = ng * 64 + nh * 32 + g * 16;      // first of this lane's 16 output channels
-    f32x16 biasv;           // requested before the weights: the first MFMA needs it, and loads return in order
-#pragma unroll
-    for (int k = 0; k < 16; ++k) biasv[k] = 0.f;
-    if (p.bias) {                                    // Cout % 8 == 0: eight at a time
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-            if (ch0 + h * 8 < p.Cout) {
-                const float4 b0 = *(const float4 *)(p.bias + ch0 + h * 8), b1 = *(const float4 *)(p.bias + ch0 + h * 8 + 4);
-                biasv[h * 8 + 0] = b0.x; biasv[h * 8 + 1] = b0.y; biasv[h * 8 + 2] = b0.z; biasv[h * 8 + 3] = b0.w;
-                biasv[h * 8 + 4] = b1.x; biasv[h * 8 + 5] = b1.y; biasv[h * 8 + 6] = b1.z; biasv[h * 8 + 7] = b1.w;
-            }
+    if (FLAGS && ng == 0 && wave == 0) {
+        // what reduce_mask would have left behind: every workgroup writes the index triples of its own items
+        // (together they are the whole list up to cap), one lane the count
+        for (uint32_t k = lane; k < kk; k += 64) {
+            const uint32_t blk = mine[k];
+            const int n = (int)fdiv(blk, p.div_bps);
+            const uint32_t rem = blk - (uint32_t)n * (uint32_t)(p.g_in.bcount_h * p.g_in.bcount_w);
+            const int by = (int)fdiv(rem, p.div_bw);
+            int32_t *t = p.indices_out + 3 * ((size_t)first + (size_t)k * G);
+            t[0] = n;
+            t[1] = by;
+            t[2] = (int)rem - by * p.g_in.bcount_w;
+        }
+        if (blockIdx.x == 0 && lane == 0) *p.count_out = nact_raw;
     }
-    // ---- weights of this wave: every k-step of its 32 output channels, requested in the order the stages of a tile
-    //      use them: the first tile's matrix work starts when the first of them have landed and runs while the
-    //      rest stream in
-    uint4 wreg[KS];
-    {
-        const uint4 *wp = (const uint4 *)p.w + p.w32_offset + ((size_t)ng * KS * 2 + nh) * 64 + lane;
-#pragma unroll
-        for (int st = 0; st < NST; ++st)
-#pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                const int ks = (r * 3 + st / KC) * KC + st % KC;
-                wreg[ks] = wp[(size_t)ks * 128];
-            }
-    }
+
     // ReLU as an integer max on the float bits (negative floats are negative integers); without
     // ReLU the floor is INT_MIN and the max is the identity.  One VALU op, no NaN canonicalisation.
     int floor_i = p.relu ? 0 : (int)0x80000000;
@@ -276,6 +392,8 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
                 if (!SINGLE) {
                     if (mm == 9 && st < NV) stash1(buf ^ 1, st);
                     if (mm == 10 && st < NV) fetch1(src, st);
+                } else if (mm >= 8 && mm <= 10 && st + kWPro < NST) {
+                    wload1(st + kWPro, mm - 8);      // the weights of the later stages arrive while the first ones are used
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -368,6 +486,8 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
         tile(first, std::true_type{});
         return;
     }
+#pragma unroll
+    for (int st = kWPro; st < NST; ++st) wload(st);
     src = source(nx1);
 #pragma unroll
     for (int k = 0; k < NV; ++k) fetch1(src, k);     // tile 1 rides through tile 0's matrix work
@@ -380,12 +500,15 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
 
 template <int DT, int CIN>
 static void launch16(bool fused, const ConvParams &p, const Sub16 &sp, dim3 grid, hipStream_t s) {
-    if (fused && p.add) hipLaunchKernelGGL((conv16_kernel<DT, CIN, true, true>), grid, dim3(256), 0, s, p, sp);
-    else if (fused) hipLaunchKernelGGL((conv16_kernel<DT, CIN, true, false>), grid, dim3(256), 0, s, p, sp);
-    else hipLaunchKernelGGL((conv16_kernel<DT, CIN, false, false>), grid, dim3(256), 0, s, p, sp);
+    if (fused && p.flags && p.add) hipLaunchKernelGGL((conv16_kernel<DT, CIN, true, true, true>), grid, dim3(256), 0, s, p, sp);
+    else if (fused && p.flags) hipLaunchKernelGGL((conv16_kernel<DT, CIN, true, false, true>), grid, dim3(256), 0, s, p, sp);
+    else if (fused && p.add) hipLaunchKernelGGL((conv16_kernel<DT, CIN, true, true, false>), grid, dim3(256), 0, s, p, sp);
+    else if (fused) hipLaunchKernelGGL((conv16_kernel<DT, CIN, true, false, false>), grid, dim3(256), 0, s, p, sp);
+    else hipLaunchKernelGGL((conv16_kernel<DT, CIN, false, false, false>), grid, dim3(256), 0, s, p, sp);
 }
 
-bool conv16_try(sbnet_dtype dt, bool fused, const ConvParams &p, hipStream_t s, sbnet_status *st, const char *who) {
+// Shape checks and launch shape; false when the shape (or, with p.flags set, the flag-fed form) is not this kernel's.
+static bool conv16_plan(sbnet_dtype dt, bool fused, const ConvParams &p, Sub16 *spo, dim3 *grido) {
     if (dt != SBNET_BF16 && dt != SBNET_F16) return false;
     if (p.kh != 3 || p.kw != 3 || p.sh != 1 || p.sw != 1) return false;
     if (p.Cin != 32 && p.Cin != 64) return false;
@@ -403,13 +526,39 @@ bool conv16_try(sbnet_dtype dt, bool fused, const ConvParams &p, hipStream_t s, 
     if ((fused ? (long long)p.Ho * p.Wo : (long long)p.oh * p.ow) * p.Cout >= (1LL << 30)) return false;
     long long g = (items + 7) / 8 * 8;
     if (g > 256) g = 256;                             // one persistent workgroup per CU
-    dim3 grid((unsigned)g, (unsigned)((p.Cout + 63) / 64));
+    if (p.flags) {
+        // flag-fed form: list position = item number, a workgroup's items fit its table, block numbers fit the scan
+        if (!fused || sp.sub_h != 1 || sp.sub_w != 1 || p.total_blocks > 65536 || p.total_blocks <= 0) return false;
+        if (g == 0 || (items + g - 1) / g > kMineMax) return false;
+        if (!p.indices_out || !p.count_out) return false;
+    }
+    *spo = sp;
+    *grido = dim3((unsigned)g, (unsigned)((p.Cout + 63) / 64));
+    return true;
+}
+
+bool conv16_accepts(sbnet_dtype dt, bool fused, const ConvParams &p) {
+    Sub16 sp;
+    dim3 grid;
+    return p.cap > 0 && conv16_plan(dt, fused, p, &sp, &grid);
+}
+
+bool conv16_try(sbnet_dtype dt, bool fused, const ConvParams &p, hipStream_t s, sbnet_status *st, const char *who) {
+    Sub16 sp;
+    dim3 grid;
+    if (!conv16_plan(dt, fused, p, &sp, &grid)) return false;
+    ConvParams pf = p;
+    if (p.flags) {
+        pf.div_grid = make_fastdiv(grid.x);
+        pf.div_bps = make_fastdiv((uint32_t)p.g_in.bcount_h * (uint32_t)p.g_in.bcount_w);
+        pf.div_bw = make_fastdiv((uint32_t)p.g_in.bcount_w);
+    }
     if (dt == SBNET_BF16) {
-        if (p.Cin == 64) launch16<SBNET_BF16, 64>(fused, p, sp, grid, s);
-        else launch16<SBNET_BF16, 32>(fused, p, sp, grid, s);
+        if (p.Cin == 64) launch16<SBNET_BF16, 64>(fused, pf, sp, grid, s);
+        else launch16<SBNET_BF16, 32>(fused, pf, sp, grid, s);
     } else {
-        if (p.Cin == 64) launch16<SBNET_F16, 64>(fused, p, sp, grid, s);
-        else launch16<SBNET_F16, 32>(fused, p, sp, grid, s);
+        if (p.Cin == 64) launch16<SBNET_F16, 64>(fused, pf, sp, grid, s);
+        else launch16<SBNET_F16, 32>(fused, pf, sp, grid, s);
     }
     *st = launch_status(who);
     return true;

@@ -41,6 +41,13 @@ struct ConvParams {
     int relu, add;
     sbnet_geom g_in, g_out;  // fused form only
     int H, W, Ho, Wo;        // fused form only
+    // fused form fed by block flags instead of an index list (conv16.hip): the kernel compacts the flags of all
+    // total_blocks blocks itself and also writes the list and the count it derives for later consumers
+    const uint8_t *flags;    // [total_blocks] padded to 16 bytes, or null
+    int total_blocks;
+    int32_t *indices_out;    // [cap][3]
+    int32_t *count_out;      // [1]
+    FastDiv div_bps, div_bw, div_grid;       // blocks per sample, blocks per block row, workgroups along x
     // MFMA path work decomposition
     int CinP;                // Cin rounded up to 32
     int CC;                  // channels per LDS chunk (multiple of 32)
@@ -131,7 +138,10 @@ __device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, uint32_t o
 }
 
 // conv16.hip: returns true when it took the job (status in *st), false when the shape is not its own.
+// With p.flags set it only takes shapes its flag-fed variant serves (16 x 16 output blocks, at most 65 536 blocks).
 bool conv16_try(sbnet_dtype dt, bool fused, const ConvParams &p, hipStream_t s, sbnet_status *st, const char *who);
+// the same decision without a launch (p.oh, p.ow set)
+bool conv16_accepts(sbnet_dtype dt, bool fused, const ConvParams &p);
 // conv3.hip: the same contract for the LDS-tiled 3x3 kernel (any stride, tile size and channel counts that are multiples of 8).
 bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p, hipStream_t s, sbnet_status *st, const char *who);
 

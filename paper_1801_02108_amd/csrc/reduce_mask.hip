@@ -224,7 +224,10 @@ __global__ __launch_bounds__(kRmThreads) void rm_pool_blocks(const T *__restrict
                                                               uint8_t *__restrict__ flags) {
     const int lane = threadIdx.x & 63;
     const int blk = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRmThreads / 64) + (threadIdx.x >> 6)));
-    if (blk >= total) return;                                 // uniform over the wavefront
+    if (blk >= total) {                                       // uniform over the wavefront
+        if (blk < ((total + 15) & ~15) && lane == 0) flags[blk] = 0;     // the padding up to a multiple of 16 reads as inactive
+        return;
+    }
     const int n = (int)fdiv((uint32_t)blk, dv.per_sample);
     const int rem = blk - n * g.bcount_h * g.bcount_w;
     const int by = (int)fdiv((uint32_t)rem, dv.per_row), bx = rem - by * g.bcount_w;
@@ -293,7 +296,10 @@ __global__ __launch_bounds__(kRmThreads) void rm_pool_blocks_u8w(const uint32_t 
                                                                   int cutoff, uint8_t *__restrict__ flags) {
     const int lane = threadIdx.x & 63;
     const int blk = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kRmThreads / 64) + (threadIdx.x >> 6)));
-    if (blk >= total) return;                                 // uniform over the wavefront
+    if (blk >= total) {                                       // uniform over the wavefront
+        if (blk < ((total + 15) & ~15) && lane == 0) flags[blk] = 0;     // the padding up to a multiple of 16 reads as inactive
+        return;
+    }
     const int n = (int)fdiv((uint32_t)blk, dv.per_sample);
     const int rem = blk - n * g.bcount_h * g.bcount_w;
     const int by = (int)fdiv((uint32_t)rem, dv.per_row), bx = rem - by * g.bcount_w;
@@ -336,21 +342,6 @@ __global__ __launch_bounds__(kRmThreads) void rm_pool_blocks_u8w(const uint32_t 
     if (lane == 63) flags[blk] = a >= cutoff ? (uint8_t)1 : (uint8_t)0;
 }
 
-// number of non-zero bytes among the first `valid` (0..16) bytes of q
-__device__ __forceinline__ int count_flags16(uint4 q, int valid) {
-    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-    int c = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        uint32_t t = w[k];
-        const int keep = min(max(valid - 4 * k, 0), 4);                  // bytes of this word that count
-        t = keep >= 4 ? t : (keep <= 0 ? 0u : (t & ((1u << (8 * keep)) - 1u)));
-        t |= t >> 4; t |= t >> 2; t |= t >> 1;                            // bit 0 of every byte: byte != 0
-        c += __popc(t & 0x01010101u);
-    }
-    return c;
-}
-
 // flags: one byte per block in lexicographic order, padded to a multiple of 16 bytes (the padding is never counted)
 __global__ __launch_bounds__(kRmThreads) void rm_compact_flags(const uint8_t *__restrict__ flags, int total, sbnet_geom g,
                                                                 BlockDivs dv, int32_t *__restrict__ indices,
@@ -363,7 +354,7 @@ __global__ __launch_bounds__(kRmThreads) void rm_compact_flags(const uint8_t *__
     const bool on = blk < total && flags[blk] != 0;           // travels together with the loads of the count
     int part = 0;
     for (int v = threadIdx.x; v * 16 < start; v += kRmThreads)
-        part += count_flags16(reinterpret_cast<const uint4 *>(flags)[v], 16);
+        part += __popc(nonzero_bytes16(reinterpret_cast<const uint4 *>(flags)[v], 16));
     const int base = block_sum(part, red);                    // active blocks in front of the run
     const unsigned long long ballot = __ballot(on);
     if (lane == 0) wave_cnt[wave] = __popcll(ballot);
@@ -432,7 +423,7 @@ sbnet_status mask_to_flags(const char *who, const void *mask, sbnet_dtype mdt, i
     const int total = N * g->bcount_h * g->bcount_w;
     const BlockDivs dv = block_divs(g);
     const double thr = (double)threshold;
-    const dim3 grid((unsigned)((total + kRmThreads / 64 - 1) / (kRmThreads / 64)));
+    const dim3 grid((unsigned)((((total + 15) & ~15) + kRmThreads / 64 - 1) / (kRmThreads / 64)));   // one wave per flag byte, padding included
     const bool words = mdt == SBNET_U8 && (W % 4 == 0) && (((uintptr_t)mask) % 4 == 0);
     if (words) {
         // Smallest integer pool value v that counts as active: the decision everywhere is
@@ -472,7 +463,28 @@ sbnet_status mask_to_flags(const char *who, const void *mask, sbnet_dtype mdt, i
     return launch_status(who);
 }
 
+sbnet_status flags_to_indices(const char *who, const uint8_t *flags, int N, const sbnet_geom *g, int32_t *indices,
+                              int32_t *count, int cap, hipStream_t s) {
+    const int total = N * g->bcount_h * g->bcount_w;
+    hipLaunchKernelGGL(rm_compact_flags, dim3((unsigned)((total + kRmThreads - 1) / kRmThreads)), dim3(kRmThreads), 0, s,
+                       flags, total, *g, block_divs(g), indices, count, cap);
+    return launch_status(who);
+}
+
 }  // namespace sbnet
+
+extern "C" size_t sbnet_block_flags_bytes(int N, const sbnet_geom *g) {
+    if (N <= 0 || !geom_ok(g)) return 0;
+    return ((size_t)N * g->bcount_h * g->bcount_w + 15) & ~(size_t)15;
+}
+
+extern "C" sbnet_status sbnet_block_flags(const void *mask, sbnet_dtype mdt, int N, int H, int W, const sbnet_geom *g,
+                                          sbnet_pool pool, float threshold, uint8_t *flags, size_t flags_bytes,
+                                          void *stream) {
+    if (N > 0 && geom_ok(g) && flags_bytes < sbnet_block_flags_bytes(N, g))
+        return fail(SBNET_EINVAL, "sbnet_block_flags: flag buffer too small");
+    return mask_to_flags("sbnet_block_flags", mask, mdt, N, H, W, g, pool, threshold, flags, (hipStream_t)stream);
+}
 
 // Argument checks and the two launches shared by both entry points; `workspace` is device memory of at
 // least sbnet_workspace_bytes(N, g), every byte the kernels read from it is written by pass 1 first.
@@ -490,10 +502,7 @@ static sbnet_status reduce_mask_launch(const void *mask, sbnet_dtype mdt, int N,
         uint8_t *flags = (uint8_t *)workspace;
         st = mask_to_flags("sbnet_reduce_mask(pool)", mask, mdt, N, H, W, g, pool, threshold, flags, s);
         if (st != SBNET_OK) return st;
-        const int total = N * g->bcount_h * g->bcount_w;
-        hipLaunchKernelGGL(rm_compact_flags, dim3((unsigned)((total + kRmThreads - 1) / kRmThreads)), dim3(kRmThreads), 0, s,
-                           flags, total, *g, block_divs(g), indices, count, cap);
-        return launch_status("sbnet_reduce_mask(compact)");
+        return flags_to_indices("sbnet_reduce_mask(compact)", flags, N, g, indices, count, cap, s);
     }
     const int rows = N * g->bcount_h;
     const size_t acc_bytes = mdt == SBNET_U8 ? 4 : 8;

@@ -566,6 +566,96 @@ def test_sparse_conv_fused_and_unfused(N, H, W, Cin, Cout, k, s, bo, dtype, add)
         got = to_host(y)
         assert_close(got, ref, CONV_TOL[dtype], "unfused")
         assert np.array_equal(got[~bm], y0[~bm])
+        # mask in, result out in one call: the same bits as reduce_mask + the fused kernel, and the same list left behind
+        y_fused = to_dev(y0, dtype)
+        sb.sparse_conv(to_dev(x, dtype), d_idx, d_cnt, g_in, g_out, wp, d_b, y_fused, stride=s, relu=True, add=add)
+        y = to_dev(y0, dtype)
+        m_idx = torch.full_like(d_idx, -3)
+        m_cnt = torch.full_like(d_cnt, -3)
+        ws = torch.full((sb.workspace_bytes(N, g_in),), 0x5b, dtype=torch.uint8).cuda()
+        sb.sparse_conv_from_mask(torch.from_numpy(mask).cuda(), g_in, to_dev(x, dtype), g_in, g_out, wp, d_b, y, m_idx, m_cnt, ws,
+                                 stride=s, relu=True, add=add)
+        assert torch.equal(y, y_fused)
+        n = sb.read_count(m_cnt, m_idx.shape[0])
+        assert n == len(idx) and np.array_equal(m_idx[:n].cpu().numpy(), idx) and bool((m_idx[n:] == -3).all())
+
+
+FROM_MASK_CASES = [
+    # N, H, W, Cin, Cout, bo, dtype, add, density, cap (None = all blocks): shapes the flag-fed kernel takes, and around them
+    (1, 800, 704, 64, 64, 16, "bf16", False, 0.0008, None),   # the headline layer: 2200 flags, one round of the scan
+    (4, 400, 352, 64, 64, 16, "bf16", True, 0.002, None),     # 2200 blocks over four samples
+    (5, 800, 704, 32, 64, 16, "f16", False, 0.0005, None),    # 11 000 flags: three rounds of 4096, 32 input channels
+    (1, 250, 170, 64, 128, 16, "bf16", False, 0.004, None),   # ragged edges, two groups of output channels
+    (1, 800, 704, 64, 64, 16, "bf16", False, 1.0, None),      # every block active: 8-9 items per workgroup
+    (2, 160, 160, 64, 64, 16, "bf16", True, 0.01, 7),         # fewer list rows than active blocks
+    (1, 64, 48, 64, 64, 16, "bf16", False, 0.0, None),        # empty mask
+    (1, 4112, 4112, 64, 8, 16, "bf16", False, 0.00002, None), # 66 049 blocks: beyond the flag path, the two calls in sequence
+]
+
+
+@pytest.mark.parametrize("N,H,W,Cin,Cout,bo,dtype,add,dens,cap", FROM_MASK_CASES)
+def test_sparse_conv_from_mask(N, H, W, Cin, Cout, bo, dtype, add, dens, cap):
+    """sbnet_sparse_conv_from_mask against the oracle: index list and count bit-exact, the convolved blocks within the
+    convolution's tolerance on sampled tiles (whole tensor for the small cases), inactive pixels untouched."""
+    step("sparse_conv_from_mask %s" % ((N, H, W, Cin, Cout, bo, dtype, add, dens, cap),))
+    r = gen.rng_for(5, 7000 + H + W + Cin + N)
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, 1, bo)
+    og_in, og_out = ogeom(g_in), ogeom(g_out)
+    total = N * g_in.bcount_h * g_in.bcount_w
+    mask = (r.random((N, H, W)) < dens).astype(np.uint8)
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    tg = torch.Generator(device="cuda")
+    tg.manual_seed(gen.BASE_SEED + 7000 + H)
+    xd = torch.randn((N, H, W, Cin), generator=tg, device="cuda", dtype=torch.float32).to(tdt)
+    yd = torch.randn((N, Ho, Wo, Cout), generator=tg, device="cuda", dtype=torch.float32).to(tdt)
+    y_before = yd.clone()
+    w = gen.conv_weights(r, 3, 3, Cin, Cout, dtype)
+    b = gen.bias_vector(r, Cout, 0.5)
+    rows = total if cap is None else cap
+    d_idx = torch.full((rows, 3), -3, dtype=torch.int32).cuda()
+    d_cnt = torch.full((1,), -3, dtype=torch.int32).cuda()
+    ws = torch.full((sb.workspace_bytes(N, g_in),), 0xa7, dtype=torch.uint8).cuda()
+    sb.sparse_conv_from_mask(torch.from_numpy(mask).cuda(), g_in, xd, g_in, g_out, sb.pack_weights(to_dev(w, dtype)),
+                             torch.from_numpy(b).cuda(), yd, d_idx, d_cnt, ws, relu=True, add=add)
+    idx = orc.reduce_mask(mask, og_in)
+    assert int(d_cnt.item()) == len(idx)
+    if total <= 65536:
+        # the two halves as calls of their own: flags = membership in the oracle's list; the same y, list and count
+        flags = sb.block_flags(torch.from_numpy(mask).cuda(), g_in)
+        want = np.zeros(total, np.uint8)
+        want[(idx[:, 0] * g_in.bcount_h + idx[:, 1]) * g_in.bcount_w + idx[:, 2]] = 1
+        assert np.array_equal(flags[:total].cpu().numpy(), want)
+        y2, i2, c2 = y_before.clone(), torch.full_like(d_idx, -3), torch.full_like(d_cnt, -3)
+        sb.sparse_conv_from_flags(flags, xd, g_in, g_out, sb.pack_weights(to_dev(w, dtype)), torch.from_numpy(b).cuda(), y2, i2, c2,
+                                  relu=True, add=add)
+        assert torch.equal(y2, yd) and torch.equal(i2, d_idx) and torch.equal(c2, d_cnt)
+    used = min(len(idx), rows)
+    got_idx = d_idx.cpu().numpy()
+    assert np.array_equal(got_idx[:used], idx[:used]) and (got_idx[used:] == -3).all()
+    idx = idx[:used]
+    bm = torch.from_numpy(orc.block_mask(idx, og_out, N, Ho, Wo)).cuda()
+    assert torch.equal(yd[~bm], y_before[~bm])
+    if used == 0:
+        return
+    pick = np.unique(np.concatenate([[0, used - 1], r.integers(0, used, 10)]))
+    for k in pick:
+        n_, by, bx = (int(v) for v in idx[k])
+        one = np.array([[0, by, bx]], dtype=np.int32)
+        if H * W <= 800 * 704:
+            tile = orc.gather(xd[n_].to(torch.float64).cpu().numpy()[None], one, og_in)
+        else:
+            # very large image: the oracle gets the 3 x 3 block window around the block as an image of its own (the
+            # window ends a whole block beyond the tile, or at the image's edge, where its zero padding is the image's)
+            y_lo, x_lo = max(by * bo - bo, 0), max(bx * bo - bo, 0)
+            xs = xd[n_, y_lo:min(by * bo + 2 * bo, H), x_lo:min(bx * bo + 2 * bo, W)].to(torch.float64).cpu().numpy()[None]
+            wg_in, _, _, _ = orc.geometry(xs.shape[1], xs.shape[2], 3, 1, bo)
+            tile = orc.gather(xs, np.array([[0, (by * bo - y_lo) // bo, (bx * bo - x_lo) // bo]], dtype=np.int32), wg_in)
+        hh, ww = min(bo, Ho - by * bo), min(bo, Wo - bx * bo)
+        ref = np.maximum(orc.conv_valid(tile, w, b), 0.0)[0, :hh, :ww]
+        if add:
+            ref = ref + y_before[n_, by * bo:by * bo + hh, bx * bo:bx * bo + ww].to(torch.float64).cpu().numpy()
+        blk = yd[n_, by * bo:by * bo + hh, bx * bo:bx * bo + ww].to(torch.float64).cpu().numpy()
+        assert_close(blk, ref, CONV_TOL[dtype], "from mask, tile %d" % k)
 
 
 def _random_fused_shapes(n, seed):
