@@ -413,3 +413,48 @@ def sparse_bottleneck_dense(x, idx, g_out, w1, b1, w2, b2, w3, b3, pre=None):
     t3 = conv_dense(t2, w3, b3, relu=False)
     m = block_mask(idx, g_out, *x.shape[:3])[..., None]
     return x + np.where(m, t3, 0.0)
+
+
+# ---------------------------------------------------------------------------------------
+# residual units of any width, with a strided 3x3 and a projected shortcut (the backbone's
+# downsampling units, Sec. 4 "Architecture"; geometry of the strided tile: Sec. 3.1, Fig. 3)
+# ---------------------------------------------------------------------------------------
+def unit_on_tiles(tiles, idx, g_in, H, W, w1, b1, w2, b2, w3, b3, stride=1, shortcut=None):
+    """What a residual unit adds up on the output block of every gathered tile: the branch
+    1x1 + ReLU (whole tile, zero outside the image) -> valid 3x3 with `stride` + ReLU -> 1x1, plus the shortcut:
+    shortcut = (ws, bs): the 1x1 convolution with the same stride, i.e. of the tile pixels (i*stride + 1,
+    j*stride + 1) that lie under the output pixels (the tile starts one pixel outside the block);
+    shortcut = None: those pixels themselves (identity; needs equal channel counts).
+    Returns [B, bo_h, bo_w, Cout]."""
+    tiles = np.asarray(tiles, dtype=np.float64)
+    t1 = zero_outside(conv_valid(tiles, w1, b1, relu=True), idx, g_in, H, W)
+    t2 = conv_valid(t1, w2, b2, stride=stride, relu=True)
+    t3 = conv_valid(t2, w3, b3, relu=False)
+    oh, ow = t3.shape[1], t3.shape[2]
+    centre = tiles[:, 1:1 + (oh - 1) * stride + 1:stride, 1:1 + (ow - 1) * stride + 1:stride, :]
+    if shortcut is None:
+        return centre + t3
+    ws, bs = shortcut
+    return conv_valid(centre, ws, bs, relu=False) + t3
+
+
+def sparse_unit_tiled(x, idx, g_in, g_out, w1, b1, w2, b2, w3, b3, y, stride=1, shortcut=None):
+    """One sparse residual unit, step by step: one gather, the unit on the tiles, one scatter (plain: the
+    shortcut is part of what is scattered) into y, whose other pixels stay."""
+    x = np.asarray(x, dtype=np.float64)
+    tiles = gather(x, idx, g_in)
+    out = unit_on_tiles(tiles, idx, g_in, x.shape[1], x.shape[2], w1, b1, w2, b2, w3, b3, stride=stride, shortcut=shortcut)
+    return scatter(out, idx, g_out, y, add=False)
+
+
+def sparse_unit_dense(x, idx, g_out, w1, b1, w2, b2, w3, b3, y, stride=1, shortcut=None):
+    """What it must equal: the dense unit (zero-padded 3x3 with `stride`, shortcut a 1x1 convolution with the same
+    stride or the identity) on the pixels of the active output blocks, y elsewhere."""
+    x = np.asarray(x, dtype=np.float64)
+    t1 = conv_dense(x, w1, b1, relu=True)
+    t2 = conv_dense(t1, w2, b2, stride=stride, relu=True)
+    t3 = conv_dense(t2, w3, b3, relu=False)
+    sc = x[:, ::stride, ::stride, :] if shortcut is None else conv_dense(x, shortcut[0], shortcut[1], stride=stride)
+    d = sc + t3
+    m = block_mask(idx, g_out, *d.shape[:3])[..., None]
+    return np.where(m, d, np.asarray(y, dtype=np.float64))

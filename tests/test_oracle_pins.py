@@ -686,6 +686,59 @@ def test_bottleneck_partial_mask_and_special_cases():
     np.testing.assert_allclose(y2, d2, atol=1e-10)
 
 
+def _torch_unit(x, w1, b1, w2, b2, w3, b3, stride, shortcut):
+    t1 = _torch_conv(x, w1, b1, 1, 0, relu=True)
+    t2 = _torch_conv(t1, w2, b2, stride, 1, relu=True)
+    sc = x[:, ::stride, ::stride, :] if shortcut is None else _torch_conv(x, shortcut[0], shortcut[1], stride, 0)
+    return sc + _torch_conv(t2, w3, b3, 1, 0)
+
+
+@pytest.mark.parametrize("H,W,bo,stride,C,Cm,Co", [(9, 9, 2, 2, 4, 3, 6), (12, 10, 3, 2, 3, 2, 5), (11, 8, 4, 2, 5, 3, 5),
+                                                  (8, 8, 4, 1, 4, 3, 6), (10, 7, 3, 1, 4, 3, 4)])
+def test_general_unit_strided_and_projected(H, W, bo, stride, C, Cm, Co):
+    """Residual units with a strided 3x3 and a projected (1x1, same stride) shortcut, and stride-1 units whose
+    shortcut is a projection: with every block active the tiled statement equals the library's dense unit
+    (torch, fp64); on a partial mask tiled and dense agree, active pixels equal torch's, the others keep y; with the
+    last convolution zero the unit is the shortcut alone; at stride 1 with the identity it is the unit pinned above."""
+    r = np.random.default_rng(H * 100 + W * 10 + stride)
+    w1, b1 = r.standard_normal((1, 1, C, Cm)), r.standard_normal(Cm)
+    w2, b2 = r.standard_normal((3, 3, Cm, Cm)), r.standard_normal(Cm)
+    w3, b3 = r.standard_normal((1, 1, Cm, Co)), r.standard_normal(Co)
+    sc = (r.standard_normal((1, 1, C, Co)), r.standard_normal(Co))
+    ws = (w1, b1, w2, b2, w3, b3)
+    x = r.standard_normal((2, H, W, C))
+    g_in, g_out, Ho, Wo = orc.geometry(H, W, 3, stride, bo)
+    y0 = r.standard_normal((2, Ho, Wo, Co))
+    ref = _torch_unit(x, *ws, stride, sc)
+    assert ref.shape == y0.shape
+    every = orc.reduce_mask(np.ones((2, Ho, Wo)), g_out)
+    np.testing.assert_allclose(orc.sparse_unit_tiled(x, every, g_in, g_out, *ws, y0, stride=stride, shortcut=sc), ref,
+                               rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(orc.sparse_unit_dense(x, every, g_out, *ws, y0, stride=stride, shortcut=sc), ref,
+                               rtol=1e-11, atol=1e-11)
+    part = every[1::3]
+    bm = orc.block_mask(part, g_out, 2, Ho, Wo)
+    assert 0 < bm.mean() < 1
+    yt = orc.sparse_unit_tiled(x, part, g_in, g_out, *ws, y0, stride=stride, shortcut=sc)
+    np.testing.assert_allclose(yt[bm], ref[bm], rtol=1e-11, atol=1e-11)
+    assert np.array_equal(yt[~bm], y0[~bm])
+    np.testing.assert_allclose(yt, orc.sparse_unit_dense(x, part, g_out, *ws, y0, stride=stride, shortcut=sc), atol=1e-11)
+    # last convolution zero: what is left is the shortcut, a 1x1 convolution with the unit's stride
+    only = orc.sparse_unit_tiled(x, every, g_in, g_out, w1, b1, w2, b2, 0 * w3, 0 * b3, y0, stride=stride, shortcut=sc)
+    np.testing.assert_allclose(only, _torch_conv(x, sc[0], sc[1], stride, 0), rtol=1e-11, atol=1e-11)
+    if stride == 1 and C == Co:
+        # identity shortcut: the unit of Sec. 3.3 as pinned above (scatter-add onto x)
+        same = orc.sparse_unit_tiled(x, part, g_in, g_out, *ws, x, stride=1, shortcut=None)
+        np.testing.assert_allclose(same, orc.sparse_bottleneck_tiled(x, part, g_in, g_out, *ws), rtol=1e-12, atol=1e-12)
+    if stride == 2:
+        # the strided tile of Fig. 3: input side (bo - 1) * 2 + 3, neighbouring tiles share one pixel
+        assert g_in.size_h == 2 * bo + 1 and g_in.stride_h == 2 * bo
+        # identity shortcut at stride 2 (a subsampling shortcut) needs equal channel counts: take the projection away
+        if C == Co:
+            sub = orc.sparse_unit_tiled(x, every, g_in, g_out, *ws, y0, stride=2, shortcut=None)
+            np.testing.assert_allclose(sub, _torch_unit(x, *ws, 2, None), rtol=1e-11, atol=1e-11)
+
+
 def test_bottleneck_border_needs_zeroed_t1():
     # without zeroing t1 outside the image, relu(b1) leaks into the 3x3 at the border and the
     # all-ones result no longer equals the dense unit: shows the border rule is load-bearing
