@@ -483,9 +483,10 @@ sbnet_status sbnet_zero_outside(void *tiles, sbnet_dtype dtype, int H, int W, in
  * for the border rule.  w1, w2, w3 come from sbnet_pack_weights (shapes [1][1][C][Cm],
  * [3][3][Cm][Cm], [1][1][Cm][C]); b1, b2, b3 are device float32 and required.  t1 and t2 are
  * rounded to `dtype` between the layers; sums are fp32.
- * Supported: bf16 / f16, Cm = 64, C in {64, 128, 256}, block sides multiples of 8, input tile =
- * block + one-pixel halo, one tile below 2^30 elements; anything else returns SBNET_EUNSUPPORTED
- * (compose the unit from sbnet_conv_on_tiles instead).
+ * Supported: bf16 / f16, C in {64, 96, 128, 192, 256}, Cm a multiple of 8 up to 64 (the unit widths of
+ * the detector backbone of Sec. 4 up to its third stage: 96/24, 192/48, 256/64), block sides multiples
+ * of 8, input tile = block + one-pixel halo, one tile below 2^30 elements; anything else returns
+ * SBNET_EUNSUPPORTED (sbnet_sparse_unit takes every width, strides and projected shortcuts).
  */
 sbnet_status sbnet_bottleneck_on_tiles(const void *tiles_in, sbnet_dtype dtype, int H, int W, int C,
                                        int Cm, const int32_t *indices, const int32_t *count, int cap,

@@ -1,6 +1,8 @@
 // Sparse residual (bottleneck) unit on tiles (Sec. 3.3, Fig. 4 of arXiv 1801.02108): the three
-// convolutions of a ResNet bottleneck (1x1 C->64 + ReLU, 3x3 64->64 + ReLU, 1x1 64->C; batch norm
-// folded into weights and bias) share one gather and one scatter-add (Sec. 3.4).  The receptive
+// convolutions of a ResNet bottleneck (1x1 C->Cm + ReLU, 3x3 Cm->Cm + ReLU, 1x1 Cm->C; batch norm
+// folded into weights and bias) share one gather and one scatter-add (Sec. 3.4).  C is 64, 96, 128, 192 or
+// 256 (the widths of the detector backbone's stages, Sec. 4, up to its third), Cm any multiple of 8 up to
+// 64 (a narrower unit runs as width 64 on zero-padded weights).  The receptive
 // field of the whole unit is that of its single 3x3, so the input tile is block + 1-pixel halo.
 //
 // One kernel per unit; per TS x TS output sub-tile (TS = 16, or 8 for blocks that are no multiple of 16
@@ -71,6 +73,10 @@ struct BneckParams {
     int per16;
     long long lo, hi;
     const float *pre_scale, *pre_shift;   // pre-activation ReLU(scale * x + shift) in front of conv1, or both null
+    // Bottleneck widths below 64 run as width 64: the packed weights carry zeros for the channels that do not
+    // exist (t1 and t2 are exactly zero there), the biases are read as zero beyond Cm, and the packed copies of
+    // W2 and W3 hold km = (Cm rounded up to 32) / 16 k-steps per tap instead of 4.
+    int Cm, km;
 };
 
 struct BItem {
@@ -109,7 +115,7 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int W2D = TS == 16 ? 7 : 12;     // stages of conv2 weights requested ahead
     constexpr int W2R = W2D < 12 ? W2D : 12;   // ... and ring slots holding them
     constexpr int K1 = C / 16;                 // k-steps of conv1
-    constexpr int NCH = C / 64;                // 64-channel chunks of the input tile
+    constexpr int NCH = (C + 63) / 64;         // 64-channel chunks of the input tile (the last may be half empty)
     constexpr int NB3 = C / 32;                // 32-channel output blocks of conv3
     constexpr int NBW = (NB3 + 3) / 4;         // ... per wave
     constexpr int NBLK1 = (kBTPx + 31) / 32;   // 11 pixel blocks in P1
@@ -208,7 +214,7 @@ void bottleneck16_kernel(BneckParams p) {
             const uint32_t off = t.xorg + (uint32_t)(row * row_stride + col * C + c8 * 8 + chunk * 64) * 2u;
             // rows outside the image are outside the descriptor; columns outside would wrap into the neighbouring
             // row, so they (and the unused tail of the last vector) get the out-of-range offset: zeros either way
-            const bool ok = v < kBTPx * 8 && (uint32_t)(t.gx0 + col) < (uint32_t)in_w;
+            const bool ok = v < kBTPx * 8 && (uint32_t)(t.gx0 + col) < (uint32_t)in_w && (C % 64 == 0 || c8 * 8 + chunk * 64 < C);
             const uint4 val = bload16(t.xrs, ok ? off : kOutOfRangeB);
             if (slot == 0) sx0[k] = val;
             else sx1[k] = val;
@@ -268,14 +274,15 @@ void bottleneck16_kernel(BneckParams p) {
         for (int k = 0; k < N3; ++k) {
             const int i = threadIdx.x + k * 256;
             const int ln = i & 63, ks = (i >> 6) & 3, nbg = i >> 8;
-            t3v[k] = w3g[(((size_t)(nbg >> 1) * 4 + ks) * 2 + (nbg & 1)) * 64 + ln];
+            // (k-steps the packed copy does not hold multiply zeros of t2: any finite fragment will do)
+            t3v[k] = w3g[(((size_t)(nbg >> 1) * p.km + min(ks, p.km - 1)) * 2 + (nbg & 1)) * 64 + ln];
         }
 #pragma unroll
         for (int k = 0; k < N1; ++k) w1s[threadIdx.x + k * 256] = t1v[k];
 #pragma unroll
         for (int k = 0; k < N3; ++k) w3s[threadIdx.x + k * 256] = t3v[k];
         for (int i = threadIdx.x; i < 2 * kCm + C; i += 256)
-            bias_s[i] = i < kCm ? p.b1[i] : i < 2 * kCm ? p.b2[i - kCm] : p.b3[i - 2 * kCm];
+            bias_s[i] = i < kCm ? (i < p.Cm ? p.b1[i] : 0.f) : i < 2 * kCm ? (i - kCm < p.Cm ? p.b2[i - kCm] : 0.f) : p.b3[i - 2 * kCm];
         if constexpr (PRE)
             for (int i = threadIdx.x; i < 2 * C; i += 256) pre_s[i] = i < C ? p.pre_scale[i] : p.pre_shift[i - C];
     }
@@ -301,7 +308,8 @@ void bottleneck16_kernel(BneckParams p) {
         asm volatile("" : "+s"(w2p));      // opaque per iteration: keeps the loads inside the tile loop
         auto fetch_w2 = [&](int st) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < 3; ++r) w2s[st % W2R][r] = (w2p + ((r * 3 + st / 4) * 4 + st % 4) * 128)[(uint32_t)lane];
+            for (int r = 0; r < 3; ++r)     // (as for W3: a k-step beyond km multiplies zeros of t1)
+                w2s[st % W2R][r] = (w2p + ((r * 3 + st / 4) * p.km + min(st % 4, p.km - 1)) * 128)[(uint32_t)lane];
         };
 
         // ---- where this tile's results go and, for the fused form, where the residual x comes from.  Layout of
@@ -389,8 +397,8 @@ void bottleneck16_kernel(BneckParams p) {
                 for (int j = 0; j < NBPW1; ++j) bf[0][j] = *(const uint4 *)(xs + boff[j]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int k4 = 0; k4 < 4; ++k4) {
-                    if (k4 + 1 < 4) {
+                for (int k4 = 0; k4 < 4 && c * 4 + k4 < K1; ++k4) {       // the last chunk of C = 96 holds two k-steps
+                    if (k4 + 1 < 4 && c * 4 + k4 + 1 < K1) {
                         af[(k4 + 1) & 1][0] = w1s[((c * 4 + k4 + 1) * 2 + 0) * 64 + lane];
                         af[(k4 + 1) & 1][1] = w1s[((c * 4 + k4 + 1) * 2 + 1) * 64 + lane];
 #pragma unroll
@@ -560,9 +568,11 @@ template <int DT, bool FUSED, int TS, bool PRE>
 static sbnet_status launch_bneck_pre(int C, const BneckParams &p, dim3 grid, hipStream_t s, const char *who) {
     switch (C) {
         case 64: hipLaunchKernelGGL((bottleneck16_kernel<DT, 64, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
+        case 96: hipLaunchKernelGGL((bottleneck16_kernel<DT, 96, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
         case 128: hipLaunchKernelGGL((bottleneck16_kernel<DT, 128, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
+        case 192: hipLaunchKernelGGL((bottleneck16_kernel<DT, 192, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
         case 256: hipLaunchKernelGGL((bottleneck16_kernel<DT, 256, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
-        default: return fail(SBNET_EUNSUPPORTED, "%s: C must be 64, 128 or 256", who);
+        default: return fail(SBNET_EUNSUPPORTED, "%s: C must be 64, 96, 128, 192 or 256", who);
     }
     return launch_status(who);
 }
@@ -595,7 +605,7 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
     if (((uintptr_t)in | (uintptr_t)out | (uintptr_t)w1 | (uintptr_t)w2 | (uintptr_t)w3) & 15)
         return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
     if (dt != SBNET_BF16 && dt != SBNET_F16) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be bf16 or f16", who);
-    if (Cm != kCm) return fail(SBNET_EUNSUPPORTED, "%s: bottleneck width must be 64", who);
+    if (Cm > kCm || Cm % 8) return fail(SBNET_EUNSUPPORTED, "%s: bottleneck width must be a multiple of 8, at most 64", who);
     if (g_out->bsize_h % 8 || g_out->bsize_w % 8)
         return fail(SBNET_EUNSUPPORTED, "%s: block sides must be multiples of 8", who);
     if (!packed_is_mfma(dt, C, Cm)) return fail(SBNET_EUNSUPPORTED, "%s: channel counts must be multiples of 8", who);
@@ -611,6 +621,7 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
     p.w1_off = w32_off(1, C, Cm); p.w2_off = w32_off(9, Cm, Cm); p.w3_off = w32_off(1, Cm, C);
     p.b1 = b1; p.b2 = b2; p.b3 = b3;
     p.pre_scale = pre_scale; p.pre_shift = pre_shift;
+    p.Cm = Cm; p.km = (Cm + 31) / 32 * 2;
     p.indices = indices; p.count = count; p.cap = cap;
     p.th = g_in->bsize_h; p.tw = g_in->bsize_w; p.oh = g_out->bsize_h; p.ow = g_out->bsize_w;
     p.H = H; p.W = W;

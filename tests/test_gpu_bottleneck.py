@@ -50,11 +50,32 @@ UNIT_CASES = [
 
 @pytest.mark.parametrize("N,H,W,C,bo,dtype", UNIT_CASES)
 def test_bottleneck_on_tiles_and_fused(N, H, W, C, bo, dtype):
-    step("bottleneck %s" % ((N, H, W, C, bo, dtype),))
-    r = gen.rng_for(3, H * 100 + C + bo)
+    _unit_case(N, H, W, C, 64, bo, dtype)
+
+
+UNIT_WIDTH_CASES = [
+    # N, H, W, C, Cm, bo, dtype: the unit widths of the detector backbone's stages (Sec. 4) and bottleneck widths around them
+    (1, 48, 64, 96, 24, 16, "bf16"),      # second stage: 96 / 24; C = 96 fills one and a half 64-channel chunks
+    (2, 40, 40, 192, 48, 16, "bf16"),     # third stage: 192 / 48, three chunks
+    (1, 40, 24, 96, 24, 8, "f16"),        # 8 x 8 blocks
+    (1, 64, 48, 128, 32, 16, "bf16"),     # bottleneck width exactly 32: two k-steps per tap in W2 / W3
+    (1, 48, 48, 256, 56, 16, "bf16"),     # a width between 32 and 64
+    (1, 37, 45, 192, 8, 8, "bf16"),       # the narrowest, ragged image edges
+    (3, 160, 192, 96, 24, 16, "bf16"),    # 360 blocks: both sub-tile variants
+]
+
+
+@pytest.mark.parametrize("N,H,W,C,Cm,bo,dtype", UNIT_WIDTH_CASES)
+def test_unit_widths_of_the_backbone(N, H, W, C, Cm, bo, dtype):
+    _unit_case(N, H, W, C, Cm, bo, dtype)
+
+
+def _unit_case(N, H, W, C, Cm, bo, dtype):
+    step("bottleneck %s" % ((N, H, W, C, Cm, bo, dtype),))
+    r = gen.rng_for(3, H * 100 + C + bo + (0 if Cm == 64 else Cm))
     g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
     x = gen.activations(r, (N, H, W, C), dtype)
-    ws = gen.bottleneck_weights(r, C, 64, dtype)
+    ws = gen.bottleneck_weights(r, C, Cm, dtype)
     dws = dev_weights(ws, dtype)
     dx = to_dev(x, dtype)
     for dens in (1.0, 0.3, 0.0):
