@@ -462,6 +462,31 @@ sbnet_status sbnet_bottleneck_backward_on_tiles(const void *tiles_in, const void
                                                 void *stream);
 
 /*
+ * Sparse residual unit of any width, stride and shortcut (Sec. 3.3; the downsampling units of the backbone
+ * of Sec. 4; strided tile geometry of Sec. 3.1 / Fig. 3).  On the active output blocks
+ *     y = shortcut(x) + W3 ReLU(W2 *_s t1 + b2) + b3,   t1 = ReLU(W1 x + b1), zero outside the image,
+ * W1: 1x1 Cin -> Cm, W2: 3x3 with `stride` and padding 1, Cm -> Cm, W3: 1x1 Cm -> Cout (all from
+ * sbnet_pack_weights; biases device float32, required).  shortcut: w_shortcut / b_shortcut = a 1x1
+ * convolution Cin -> Cout with the same stride (packed the same way), or both NULL = the identity (needs
+ * stride 1 and Cin == Cout).  Pixels of y outside the active blocks are neither read nor written.
+ * x: [N][H][W][Cin]; y: [N][H_out][W_out][Cout]; g_in / g_out from sbnet_geometry(H, W, 3, 3, stride, stride, ...).
+ * y may be x only with the identity shortcut (the in-place scatter-add of Sec. 3.4).
+ * Stride 1 with the identity, Cin in {64, 96, 128, 192, 256}, Cm <= 64 and y != x run as the one-kernel unit
+ * (sbnet_sparse_bottleneck; workspace may then be NULL).  Every other shape runs as gather, the three
+ * convolutions on tile stacks, the shortcut and one scatter-add, on tile stacks in `workspace`
+ * (sbnet_sparse_unit_workspace_bytes, 256-byte aligned, contents don't-care): t1, t2 and t3 are rounded to
+ * `dtype` between the steps, the shortcut is rounded before the branch is added.
+ */
+size_t sbnet_sparse_unit_workspace_bytes(sbnet_dtype dtype, int cap, const sbnet_geom *g_in,
+                                         const sbnet_geom *g_out, int Cin, int Cm, int Cout);
+sbnet_status sbnet_sparse_unit(const void *x, sbnet_dtype dtype, int N, int H, int W, int Cin, int Cm,
+                               int Cout, int stride, const int32_t *indices, const int32_t *count, int cap,
+                               const sbnet_geom *g_in, const sbnet_geom *g_out, const void *w1,
+                               const float *b1, const void *w2, const float *b2, const void *w3,
+                               const float *b3, const void *w_shortcut, const float *b_shortcut, void *y,
+                               int H_out, int W_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Set every tile position that lies outside the H x W image to zero, in place.  Needed when a
  * residual unit is composed from single sbnet_conv_on_tiles calls: after the first convolution
  * the halo positions beyond the image border hold act(bias), but the next convolution's zero

@@ -88,6 +88,9 @@ _SIGNATURES = {
                                            _ci, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _vp]),
     "sbnet_sparse_conv_from_mask": (_ci, [_vp, _ci, _ci, _ci, _gp, _ci, ctypes.c_float, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci,
                                           _gp, _gp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _ci, _ci, _ci, _vp, _sz, _vp]),
+    "sbnet_sparse_unit_workspace_bytes": (_sz, [_ci, _ci, _gp, _gp, _ci, _ci, _ci]),
+    "sbnet_sparse_unit": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp, _vp, _vp, _vp, _vp, _vp,
+                                _vp, _vp, _vp, _vp, _ci, _ci, _vp, _sz, _vp]),
     "sbnet_zero_outside": (_ci, [_vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _vp]),
     "sbnet_bottleneck_on_tiles": (_ci, [_vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _gp, _gp,
                                         _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -679,3 +682,33 @@ def zero_outside(tiles, indices, count, g, H, W):
     assert (h, w) == (g.bsize_h, g.bsize_w) and cap == indices.shape[0]
     _check(lib().sbnet_zero_outside(_ptr(tiles), _dt(tiles), H, W, C, _ptr(indices), _ptr(count), cap, g, _stream()))
     return tiles
+
+
+def sparse_unit(x, indices, count, g_in, g_out, weights, y, stride=1, shortcut=None, workspace=None):
+    """Residual unit of any width: weights = (w1p, b1, w2p, b2, w3p, b3) packed, shortcut = (wsp, bs) packed 1x1 with the
+    unit's stride or None for the identity.  Writes the active blocks of y [N,H_out,W_out,Cout] in place; returns y."""
+    _dev(x, "x"), _dev(y, "y", x.dtype), _dev(indices, "indices", torch.int32), _dev(count, "count", torch.int32)
+    w1, b1, w2, b2, w3, b3 = weights
+    _, _, Cin, Cm = w1.shape
+    Cout = w3.shape[3]
+    assert w2.shape == (3, 3, Cm, Cm) and w3.shape[:3] == (1, 1, Cm)
+    for b, n in ((b1, Cm), (b2, Cm), (b3, Cout)):
+        _dev(b, "bias", torch.float32)
+        assert b.numel() == n
+    N, H, W, C = x.shape
+    Ny, Ho, Wo, Cy = y.shape
+    assert C == Cin and Cy == Cout and Ny == N
+    wsp, bs = (None, None) if shortcut is None else shortcut
+    if wsp is not None:
+        assert wsp.shape == (1, 1, Cin, Cout) and bs.numel() == Cout
+        _dev(bs, "shortcut bias", torch.float32)
+    cap = indices.shape[0]
+    need = lib().sbnet_sparse_unit_workspace_bytes(_dt(x), cap, g_in, g_out, Cin, Cm, Cout)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    _dev(workspace, "workspace")
+    _check(lib().sbnet_sparse_unit(_ptr(x), _dt(x), N, H, W, Cin, Cm, Cout, stride, _ptr(indices), _ptr(count), cap, g_in, g_out,
+                                   _ptr(w1.buf), _ptr(b1), _ptr(w2.buf), _ptr(b2), _ptr(w3.buf), _ptr(b3),
+                                   _ptr(wsp.buf) if wsp is not None else None, _ptr(bs), _ptr(y), Ho, Wo, _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()))
+    return y

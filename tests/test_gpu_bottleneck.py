@@ -1,6 +1,8 @@
 """GPU parity of the sparse residual (bottleneck) unit against the fp64 oracle: the branch on
 gathered tiles, the fused one-kernel unit, stacks with two alternating buffers, and the unit
 composed from single calls for block sizes the fused kernel does not take."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -235,3 +237,74 @@ def test_zero_outside_bit_exact():
     got = to_host(dt)
     assert np.array_equal(got[:len(idx)], orc.zero_outside(t[:len(idx)], idx, ogeom(g_in), H, W))
     assert np.array_equal(got[len(idx):], t[len(idx):])
+
+
+GENERAL_UNIT_CASES = [
+    # N, H, W, Cin, Cm, Cout, stride, bo, projection, dtype
+    (1, 66, 50, 64, 24, 96, 2, 16, True, "bf16"),      # the downsampling units of the backbone's four stages (Sec. 4) ...
+    (2, 49, 65, 96, 48, 192, 2, 8, True, "bf16"),      # ... odd extents: blocks hang over the edge of the halved map
+    (1, 64, 48, 192, 64, 256, 2, 16, True, "bf16"),
+    (1, 40, 40, 256, 96, 384, 2, 8, True, "f16"),
+    (1, 48, 40, 384, 96, 384, 1, 8, False, "bf16"),    # fourth stage, stride 1, identity: wider than the one-kernel unit takes
+    (2, 40, 56, 96, 24, 96, 1, 16, False, "bf16"),     # a shape the one-kernel unit takes: routed to it
+    (1, 32, 48, 64, 16, 128, 1, 16, True, "bf16"),     # stride 1 with a projection (a change of width without downsampling)
+    (1, 35, 29, 24, 8, 40, 2, 4, True, "bf16"),        # small channel counts, 4 x 4 blocks
+]
+
+
+@pytest.mark.parametrize("N,H,W,Cin,Cm,Cout,stride,bo,proj,dtype", GENERAL_UNIT_CASES)
+def test_sparse_unit_any_width_stride_and_shortcut(N, H, W, Cin, Cm, Cout, stride, bo, proj, dtype):
+    """sbnet_sparse_unit against the oracle's step-by-step unit: strided 3x3, projected shortcut, every stage width."""
+    step("sparse_unit %s" % ((N, H, W, Cin, Cm, Cout, stride, bo, proj, dtype),))
+    r = gen.rng_for(3, 9000 + H + Cin + Cout + stride)
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, stride, bo)
+    og_in, og_out = ogeom(g_in), ogeom(g_out)
+    x = gen.activations(r, (N, H, W, Cin), dtype)
+    w1, b1 = gen.conv_weights(r, 1, 1, Cin, Cm, dtype), gen.bias_vector(r, Cm)
+    w2, b2 = gen.conv_weights(r, 3, 3, Cm, Cm, dtype), gen.bias_vector(r, Cm)
+    w3, b3 = gen.conv_weights(r, 1, 1, Cm, Cout, dtype, scale=0.5), gen.bias_vector(r, Cout)
+    sc = (gen.conv_weights(r, 1, 1, Cin, Cout, dtype), gen.bias_vector(r, Cout)) if proj else None
+    fb = lambda b: torch.from_numpy(b).cuda()
+    dws = (sb.pack_weights(to_dev(w1, dtype)), fb(b1), sb.pack_weights(to_dev(w2, dtype)), fb(b2), sb.pack_weights(to_dev(w3, dtype)), fb(b3))
+    dsc = (sb.pack_weights(to_dev(sc[0], dtype)), fb(sc[1])) if proj else None
+    dx = to_dev(x, dtype)
+    for dens in (1.0, 0.3, 0.0):
+        mask = (r.random((N, Ho, Wo)) < dens * (0.02 if dens < 1.0 else 1.0)).astype(np.uint8) if dens > 0 else np.zeros((N, Ho, Wo), np.uint8)
+        d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_out)
+        idx = orc.reduce_mask(mask, og_out)
+        assert sb.read_count(d_cnt, d_idx.shape[0]) == len(idx)
+        y0 = gen.activations(r, (N, Ho, Wo, Cout), dtype)
+        y = to_dev(y0, dtype)
+        sb.sparse_unit(dx, d_idx, d_cnt, g_in, g_out, dws, y, stride=stride, shortcut=dsc)
+        got = to_host(y)
+        ref = orc.sparse_unit_tiled(x, idx, og_in, og_out, w1, b1, w2, b2, w3, b3, y0, stride=stride, shortcut=sc)
+        bm = orc.block_mask(idx, og_out, N, Ho, Wo)
+        assert np.array_equal(got[~bm], y0[~bm])
+        assert_close(got[bm], ref[bm], CONV_TOL[dtype], "sparse_unit")
+        if dens == 1.0:
+            assert_close(got, orc.sparse_unit_dense(x, idx, og_out, w1, b1, w2, b2, w3, b3, y0, stride=stride, shortcut=sc),
+                         CONV_TOL[dtype], "dense unit")
+        if not proj and dens == 0.3:
+            # the identity shortcut in place (the scatter-add of Sec. 3.4): y is x
+            z = dx.clone()
+            sb.sparse_unit(z, d_idx, d_cnt, g_in, g_out, dws, z, stride=1, shortcut=None)
+            ref_in = orc.sparse_unit_tiled(x, idx, og_in, og_out, w1, b1, w2, b2, w3, b3, x, stride=1, shortcut=None)
+            got_in = to_host(z)
+            assert np.array_equal(got_in[~bm], x[~bm])
+            assert_close(got_in[bm], ref_in[bm], CONV_TOL[dtype], "sparse_unit in place")
+
+
+def test_sparse_unit_rejects_what_it_cannot_mean():
+    g_in, g_out, Ho, Wo = sb.geometry(32, 32, 3, 2, 8)
+    lib = sb.lib()
+    d = torch.zeros(64, dtype=torch.int32).cuda()
+    p = ctypes.c_void_p(d.data_ptr())
+    # identity shortcut at stride 2
+    rc = lib.sbnet_sparse_unit(p, sb.BF16, 1, 32, 32, 64, 16, 64, 2, p, p, 4, g_in, g_out, p, p, p, p, p, p, None, None, p, Ho, Wo,
+                               None, 0, None)
+    assert rc == sb.EINVAL and b"identity" in lib.sbnet_last_error()
+    # geometry of another stride
+    g1_in, g1_out, _, _ = sb.geometry(32, 32, 3, 1, 8)
+    rc = lib.sbnet_sparse_unit(p, sb.BF16, 1, 32, 32, 64, 16, 96, 2, p, p, 4, g1_in, g1_out, p, p, p, p, p, p, p, p, p, Ho, Wo,
+                               None, 0, None)
+    assert rc == sb.EINVAL and b"geometries" in lib.sbnet_last_error()
