@@ -347,9 +347,42 @@ def run_stages(args):
                 pw_y = torch.empty((max(n, 1), side, side, pk), device=dev, dtype=torch.bfloat16)
                 pw_w = sb.pack_weights(torch.from_numpy(gen.conv_weights(r, 1, 1, pc, pk, "bf16")).to(torch.bfloat16).to(dev))
                 pw_ms.append(device_ms(lambda: sb.conv_on_tiles(pw_x, cnt, pw_w, None, relu=True, out=pw_y)))
+            # residual units of the stage (Sec. 4): the downsampling unit Cin -> Cout with a strided 3x3 and a projected
+            # shortcut at stride 2 (sequence of calls on tile stacks), and the stage's stride-1 unit Cout / (Cout / 4)
+            # with the identity shortcut on the same block grid (one kernel up to 256 / 64)
+            Cm = Cout // 4
+
+            def unit_weights(ci, cm, co, with_proj):
+                ww = (gen.conv_weights(r, 1, 1, ci, cm, "bf16"), gen.bias_vector(r, cm), gen.conv_weights(r, 3, 3, cm, cm, "bf16"),
+                      gen.bias_vector(r, cm), gen.conv_weights(r, 1, 1, cm, co, "bf16", scale=0.5), gen.bias_vector(r, co))
+                dw_ = tuple(sb.pack_weights(torch.from_numpy(a).to(torch.bfloat16).to(dev)) if a.ndim == 4 else torch.from_numpy(a).to(dev)
+                            for a in ww)
+                pr = None
+                if with_proj:
+                    pr = (sb.pack_weights(torch.from_numpy(gen.conv_weights(r, 1, 1, ci, co, "bf16")).to(torch.bfloat16).to(dev)),
+                          torch.from_numpy(gen.bias_vector(r, co)).to(dev))
+                return dw_, pr
+            unit_row = {}
+            if s == 2:
+                dwu, pru = unit_weights(Cin, Cm, Cout, True)
+                wsu = torch.empty((max(sb.lib().sbnet_sparse_unit_workspace_bytes(sb.BF16, total, g_in, g_out, Cin, Cm, Cout), 256),),
+                                  dtype=torch.uint8, device=dev)
+                u_ms = device_ms(lambda: sb.sparse_unit(x, idx, cnt, g_in, g_out, dwu, y, stride=2, shortcut=pru, workspace=wsu))
+                u_bytes = n * (g_in.bsize_h * g_in.bsize_w * Cin + bo * bo * Cout) * 2
+                unit_row.update({"down_unit_ms": round(u_ms, 5), "down_unit_algorithmic_GBps": round(u_bytes / u_ms / 1e6, 1)})
+            g1_in, g1_out, _, _ = sb.geometry(Ho, Wo, 3, 1, bo)
+            dw1, _ = unit_weights(Cout, Cm, Cout, False)
+            x1 = torch.randn((1, Ho, Wo, Cout), device=dev).to(torch.bfloat16)
+            y1 = x1.clone()
+            ws1 = torch.empty((max(sb.lib().sbnet_sparse_unit_workspace_bytes(sb.BF16, total, g1_in, g1_out, Cout, Cm, Cout), 256),),
+                              dtype=torch.uint8, device=dev)
+            u1_ms = device_ms(lambda: sb.sparse_unit(x1, idx, cnt, g1_in, g1_out, dw1, y1, stride=1, shortcut=None, workspace=ws1))
+            u1_bytes = n * ((bo + 2) ** 2 + bo * bo) * Cout * 2
+            unit_row.update({"unit_ms": round(u1_ms, 5), "unit_algorithmic_GBps": round(u1_bytes / u1_ms / 1e6, 1),
+                             "unit_width": "%d/%d" % (Cout, Cm), "unit_path": "one kernel" if Cout <= 256 else "sequence of calls"})
             if target >= 1.0:
                 dense_ms = ms
-            rows.append({"H": H, "W": W, "Cin": Cin, "Cout": Cout, "stride": s, "block": bo, "target": target,
+            rows.append({"H": H, "W": W, "Cin": Cin, "Cout": Cout, "stride": s, "block": bo, "target": target, **unit_row,
                          "pointwise_reduce_ms": round(pw_ms[0], 5), "pointwise_expand_ms": round(pw_ms[1], 5),
                          "backward_data_ms": round(dgrad_ms, 5), "backward_weights_ms": round(wgrad_ms, 5),
                          "backward_weights_tflops": round(2.0 * n * bo * bo * 9 * Cin * Cout / wgrad_ms / 1e9, 2),
