@@ -42,10 +42,11 @@ def parse():
                          "per-node instrumentation inflates kernels replayed from a graph)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy: a known-size reference for scaling HBM byte counters")
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "stages", "backward"],
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "stages", "backward", "tune"],
                     help="cfg2 (default) is the headline single 3x3 conv; cfg3/4/5 are the residual-unit workloads; "
                          "stages = single 3x3 convs, stride 1 and 2, at the backbone's other stage shapes; "
-                         "backward = the gradients of cfg2's convolution on its tile stacks")
+                         "backward = the gradients of cfg2's convolution on its tile stacks; "
+                         "tune = the compute-tile choices inside the kernels, each alternative forced, with the measured crossovers")
     return ap.parse_args()
 
 
@@ -491,6 +492,55 @@ def run_backward(args):
                       "rows": rows, "residual_unit_rows": unit_rows}))
 
 
+def run_tune(args):
+    """Compute-tile choices inside the kernels (the second half of Sec. 4's search): each alternative forced through
+    sbnet_tuning over a range of active counts; reports the measured crossover beside the default in force."""
+    import torch
+    import paper_1801_02108_amd as sb
+    from paper_1801_02108_amd import autotune as at
+    from paper_1801_02108_amd import inputs as gen
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    r = gen.rng_for(9)
+    kt = at.KernelChoiceTuner()
+    out = {"defaults": sb.get_tuning(), "unit_subtiles": [], "conv3_items": [], "wgrad_splits": []}
+    pk = lambda a: sb.pack_weights(torch.from_numpy(a).to(torch.bfloat16).to(dev)) if a.ndim == 4 else torch.from_numpy(a).to(dev)
+    for (H, W, C, Cm) in ((400, 352, 256, 64), (400, 352, 96, 24), (200, 176, 192, 48)):
+        x = torch.randn((1, H, W, C), device=dev).to(torch.bfloat16)
+        ws = tuple(pk(a) for a in gen.bottleneck_weights(r, C, Cm, "bf16"))
+        res = kt.unit_subtiles(x, ws, block=16, counts=(8, 16, 32, 48, 64, 80, 96, 112, 128, 144, 160, 192, 224, 256, 320, 384, 512))
+        res.update({"shape": "%dx%dx%d/%d" % (H, W, C, Cm), "ms16": [round(v, 5) for v in res["ms16"]], "ms8": [round(v, 5) for v in res["ms8"]]})
+        out["unit_subtiles"].append(res)
+    for (H, W, Cin, Cout, s_) in ((400, 352, 96, 96, 1), (800, 704, 64, 96, 2), (200, 176, 192, 192, 1)):
+        x = torch.randn((1, H, W, Cin), device=dev).to(torch.bfloat16)
+        w = torch.from_numpy(gen.conv_weights(r, 3, 3, Cin, Cout, "bf16")).to(torch.bfloat16).to(dev)
+        res = kt.conv3_items(x, w, stride=s_, block=16, counts=(8, 16, 32, 64, 96, 128, 192, 256, 320, 384, 512))
+        # what the default cost ratio would have picked at each count (rounds of work over 256 CUs)
+        ngroups = (Cout + 63) // 64
+        picks = []
+        for n in res["counts"]:
+            rb, rs = (n * 1 * ngroups + 255) // 256, (n * 2 * ngroups + 255) // 256
+            picks.append("256" if rb * 8 <= rs * out["defaults"]["conv3_small_item_cost_eighths"] else "128")
+        res.update({"shape": "%dx%dx%d->%d s%d" % (H, W, Cin, Cout, s_), "ms256": [round(v, 5) for v in res["ms256"]],
+                    "ms128": [round(v, 5) for v in res["ms128"]], "default_picks": picks})
+        out["conv3_items"].append(res)
+    for (k, th, oh, Cin, Cout) in ((3, 18, 16, 64, 64), (1, 18, 18, 256, 64), (3, 18, 16, 96, 96)):
+        t = torch.randn((2200, th, th, Cin), device=dev).to(torch.bfloat16)
+        g = torch.randn((2200, oh, oh, Cout), device=dev).to(torch.bfloat16)
+        res = kt.wgrad_splits(t, g, k, factors=(2, 4, 8, 16, 32), counts=(30, 110, 220, 880, 2200))
+        res.update({"shape": "%dx%d %d->%d on %dx%d tiles" % (k, k, Cin, Cout, th, th),
+                    "ms": {str(f): [round(v, 5) for v in row] for f, row in res["ms"].items()}})
+        out["wgrad_splits"].append(res)
+    for res in out["unit_subtiles"]:      # what the rule in force picks at each count, beside what was faster
+        cost = out["defaults"]["unit_small_item_cost_eighths"]
+        res["default_picks"] = ["16" if -(-n // 256) * 8 <= -(-n * 4 // 256) * cost else "8" for n in res["counts"]]
+    print(json.dumps({"metric": "kernel_choice_crossovers", "value": out["unit_subtiles"][0]["cost_eighths"], "unit": "eighths",
+                      "n_gpus": 1, "steps": 50, "warmup": 1, "ms_per_step": None, "higher_is_better": False, "scaling": "weak",
+                      "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "tune: compute-tile choices inside the kernels, each alternative forced; HIP graph replays"},
+                      **out}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -516,6 +566,8 @@ def main():
         del src, dst
     if args.workload == "backward":
         return run_backward(args)
+    if args.workload == "tune":
+        return run_tune(args)
     if args.workload == "stages":
         return run_stages(args)
     if args.workload != "cfg2":

@@ -58,6 +58,28 @@ typedef struct {
     int bcount_h, bcount_w;
 } sbnet_geom;
 
+/*
+ * Compute-tile choices the kernels make from the device-side count of active blocks (Sec. 4, "Choosing the
+ * optimal block sizes", carried from the block size to the shapes inside a kernel).  Process-wide, host side,
+ * read when a call is enqueued; sbnet_set_tuning(NULL) restores the defaults, which are the crossover points
+ * measured on MI355X.  Results never depend on them beyond the rounding order of the weight gradient's sum.
+ */
+typedef struct {
+    /* residual unit: cost of an 8 x 8 sub-tile in eighths of a 16 x 16 one; the size whose cost-weighted rounds of
+       work over 256 workgroups are fewer is run (8 x 8: four times the items, a shorter latency chain each).
+       Default 3; 0 = always 8 x 8; 1000 = always 16 x 16 where the block allows it. */
+    int unit_small_item_cost_eighths;
+    /* LDS-tiled 3x3 convolution: cost of a 128-pixel work item in eighths of a 256-pixel one; the shape whose
+       cost-weighted rounds of work over 256 CUs are fewer is run.  Default 5; 0 = always 128-pixel items;
+       1000 = always 256-pixel items. */
+    int conv3_small_item_cost_eighths;
+    /* weight gradient: splits of the tile list used = min(launch's, n, f * sqrt(n)) for n active tiles, f given
+       here for 3x3 and for 1x1 kernels.  Defaults 8 and 16. */
+    int wgrad_split_factor_3x3, wgrad_split_factor_1x1;
+} sbnet_tuning;
+sbnet_status sbnet_set_tuning(const sbnet_tuning *t);      /* host pointer or NULL */
+sbnet_status sbnet_get_tuning(sbnet_tuning *t);            /* host pointer */
+
 /* Last error text of the calling thread (host pointer, valid until the next failing call). */
 const char *sbnet_last_error(void);
 

@@ -25,6 +25,15 @@ class SbnetError(RuntimeError):
         self.code = code
 
 
+class Tuning(ctypes.Structure):
+    """sbnet_tuning: the compute-tile choices the kernels make from the device-side count of active blocks."""
+    _fields_ = [(n, ctypes.c_int) for n in (
+        "unit_small_item_cost_eighths", "conv3_small_item_cost_eighths", "wgrad_split_factor_3x3", "wgrad_split_factor_1x1")]
+
+    def asdict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
 class Geom(ctypes.Structure):
     """sbnet_geom: block extent, stride, origin and count along h and w."""
     _fields_ = [(n, ctypes.c_int) for n in (
@@ -40,6 +49,8 @@ _gp = ctypes.POINTER(Geom)
 
 _SIGNATURES = {
     "sbnet_last_error": (ctypes.c_char_p, []),
+    "sbnet_set_tuning": (_ci, [ctypes.POINTER(Tuning)]),
+    "sbnet_get_tuning": (_ci, [ctypes.POINTER(Tuning)]),
     "sbnet_geometry": (_ci, [_ci] * 8 + [_gp, _gp, ctypes.POINTER(_ci), ctypes.POINTER(_ci)]),
     "sbnet_workspace_bytes": (_sz, [_ci, _gp]),
     "sbnet_reduce_mask": (_ci, [_vp, _ci, _ci, _ci, _ci, _gp, _ci, ctypes.c_float, _vp, _vp, _ci, _vp, _sz, _vp]),
@@ -120,6 +131,29 @@ def lib():
             fn.restype, fn.argtypes = res, args
         _lib = l
     return _lib
+
+
+def get_tuning():
+    """The compute-tile choices in force, as a dict."""
+    t = Tuning()
+    _check(lib().sbnet_get_tuning(ctypes.byref(t)))
+    return t.asdict()
+
+
+def set_tuning(**kw):
+    """Change some of the compute-tile choices (keyword = field of sbnet_tuning); no keyword restores the defaults.
+    Returns what is in force afterwards."""
+    if not kw:
+        _check(lib().sbnet_set_tuning(None))
+        return get_tuning()
+    t = Tuning()
+    _check(lib().sbnet_get_tuning(ctypes.byref(t)))
+    for k, v in kw.items():
+        if k not in dict(Tuning._fields_):
+            raise KeyError(k)
+        setattr(t, k, int(v))
+    _check(lib().sbnet_set_tuning(ctypes.byref(t)))
+    return get_tuning()
 
 
 def _check(code):

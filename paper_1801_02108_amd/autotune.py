@@ -6,17 +6,22 @@ module does the same on the device the library runs on: for every candidate it b
 geometry, reduces the mask to its block list and times the fused sparse step (reduce_mask +
 sparse_conv, or reduce_mask + sparse_bottleneck) from HIP-graph replays, then keeps the fastest.
 
-Only host logic and calls of the binding live here; the sub-tile choices inside the kernels (16- or
-8-pixel sub-tiles of the residual unit, 256- or 128-pixel workgroup tiles of the 3x3 kernels) are
-made on the device from the active count and need no tuning.  Winners are cached under a key of the
-layer shape and the mask's coarse density, and the cache can be stored as JSON.
+Only host logic and calls of the binding live here.  Winners are cached under a key of the layer shape,
+the mask's coarse density, the layer's options and the candidate set, and the cache can be stored as JSON.
+
+The second half of the search are the compute-tile choices INSIDE the kernels, which the device makes from
+its own count of active blocks against thresholds that come with the launch (sbnet_tuning): 16- or 8-pixel
+sub-tiles of the residual unit, 256- or 128-pixel work items of the LDS-tiled 3x3 convolution, the number of
+splits of the weight gradient.  KernelChoiceTuner measures each alternative forced, over a range of active
+counts, reports where the faster one changes (the crossover the default threshold should sit at) and can put
+the measured thresholds in force.
 """
 import json
 
 import torch
 
-from . import (POOL_AVG, geometry, pack_weights, read_count, reduce_mask, sparse_bottleneck, sparse_conv,
-               workspace_bytes)
+from . import (POOL_AVG, conv_backward_weights_workspace_bytes, conv_on_tiles_backward_weights, geometry, get_tuning,
+               pack_weights, read_count, reduce_mask, set_tuning, sparse_bottleneck, sparse_conv, workspace_bytes)
 
 
 class TuneResult:
@@ -42,8 +47,11 @@ def density_bucket(active_pixel_fraction):
     return b
 
 
-def cache_key(kind, N, H, W, Cin, Cout, stride, dtype, bucket):
-    return "%s:%dx%dx%dx%d->%d:s%d:%s:d%d" % (kind, N, H, W, Cin, Cout, stride, str(dtype).replace("torch.", ""), bucket)
+def cache_key(kind, N, H, W, Cin, Cout, stride, dtype, bucket, options="", candidates=()):
+    """Everything a sweep's outcome depends on: layer shape, density band, the layer's options (ReLU, bias, ...)
+    and the block sizes that were tried."""
+    return "%s:%dx%dx%dx%d->%d:s%d:%s:d%d:%s:c%s" % (kind, N, H, W, Cin, Cout, stride, str(dtype).replace("torch.", ""), bucket,
+                                                   options, "-".join(str(c) for c in candidates))
 
 
 def pick_best(table):
@@ -126,7 +134,8 @@ class BlockSizeTuner:
         k, _, _, Cout = w_hwio.shape
         wp = pack_weights(w_hwio)
         bucket = density_bucket(float(mask.float().mean().item()))
-        key = cache_key("conv%d" % k, N, H, W, Cin, Cout, stride, x.dtype, bucket)
+        key = cache_key("conv%d" % k, N, H, W, Cin, Cout, stride, x.dtype, bucket,
+                        "relu%d.bias%d" % (int(bool(relu)), int(bias is not None)), self.candidates)
 
         def run_for_block(bo):
             g_in, g_out, Ho, Wo = geometry(H, W, k, stride, bo)
@@ -148,7 +157,7 @@ class BlockSizeTuner:
         sparse_bottleneck takes them.  The unit writes x + t3 into a second buffer (ping-pong)."""
         N, H, W, C = x.shape
         bucket = density_bucket(float(mask.float().mean().item()))
-        key = cache_key("bottleneck", N, H, W, C, C, 1, x.dtype, bucket)
+        key = cache_key("bottleneck", N, H, W, C, C, 1, x.dtype, bucket, "cm%d" % weights[0].shape[3], self.candidates)
 
         def run_for_block(bo):
             g_in, g_out, _, _ = geometry(H, W, 3, 1, bo)
@@ -164,3 +173,116 @@ class BlockSizeTuner:
             step()
             return step, read_count(cnt, total), total
         return self._sweep(key, run_for_block)
+
+
+def crossover(counts, t_small_regime, t_large_regime):
+    """Smallest count from which the large-regime alternative stays at least as fast, given the two alternatives'
+    times at ascending `counts`; None when it never is.  (Host logic, separately testable.)"""
+    first = None
+    for n, a, b in zip(counts, t_small_regime, t_large_regime):
+        if b <= a:
+            if first is None:
+                first = n
+        else:
+            first = None
+    return first
+
+
+def fit_cost_eighths(counts, ms_large, ms_small, per_large, per_small, floor_ms=0.004, workgroups=256):
+    """Cost of a small work item in eighths of a large one, from the times of the two alternatives at `counts` active
+    blocks: time above the launch floor divided by the rounds of work either needs, ratio small / large, median over
+    the counts.  (Host logic, separately testable.)"""
+    ratios = []
+    for n, a, b in zip(counts, ms_large, ms_small):
+        rl, rs = -(-n * per_large // workgroups), -(-n * per_small // workgroups)
+        if a > floor_ms and b > floor_ms:
+            ratios.append(((b - floor_ms) / rs) / ((a - floor_ms) / rl))
+    if not ratios:
+        return None
+    ratios.sort()
+    return round(8.0 * ratios[len(ratios) // 2], 2)
+
+
+class KernelChoiceTuner:
+    """Measures the device-side compute-tile choices with each alternative forced (through sbnet_tuning) and reports
+    the measured crossovers beside the defaults.  `measure` as for BlockSizeTuner."""
+
+    def __init__(self, measure=device_ms):
+        self.measure = measure
+
+    def _timed(self, fn, **forced):
+        before = get_tuning()
+        try:
+            set_tuning(**forced)
+            return self.measure(fn)
+        finally:
+            set_tuning(**before)
+
+    def unit_subtiles(self, x, weights, block=16, counts=(8, 16, 32, 64, 96, 128, 160, 192, 256, 384, 512)):
+        """Residual unit on x [N,H,W,C]: time with 16 x 16 and with 8 x 8 sub-tiles forced for the first n blocks of
+        the grid active, n in `counts`.  Returns the two time rows, which was faster per count, and the cost of an
+        8 x 8 item in eighths of a 16 x 16 one fitted to the full rounds of either (what unit_small_item_cost_eighths
+        means): the median over counts of 8 * (ms8 / rounds8) / (ms16 / rounds16), launch floor taken off both."""
+        N, H, W, C = x.shape
+        g_in, g_out, _, _ = geometry(H, W, 3, 1, block)
+        total = N * g_in.bcount_h * g_in.bcount_w
+        per16, per8 = (block // 16) ** 2, (block // 8) ** 2
+        idx_all = torch.tensor([(n, by, bx) for n in range(N) for by in range(g_in.bcount_h) for bx in range(g_in.bcount_w)],
+                               dtype=torch.int32, device=x.device)
+        y = x.clone()
+        ms16, ms8, used = [], [], []
+        for n in counts:
+            if n > total:
+                break
+            cnt = torch.tensor([n], dtype=torch.int32, device=x.device)
+            fn = lambda: sparse_bottleneck(x, idx_all, cnt, g_in, g_out, weights, y)
+            ms16.append(self._timed(fn, unit_small_item_cost_eighths=1000))
+            ms8.append(self._timed(fn, unit_small_item_cost_eighths=0))
+            used.append(n)
+        return {"counts": used, "ms16": ms16, "ms8": ms8, "faster": ["16" if a <= b else "8" for a, b in zip(ms16, ms8)],
+                "cost_eighths": fit_cost_eighths(used, ms16, ms8, per16, per8)}
+
+    def conv3_items(self, x, w_hwio, bias=None, stride=1, block=16, counts=(8, 16, 32, 64, 128, 192, 256, 384, 512, 1024)):
+        """LDS-tiled 3x3 convolution: time with 256-pixel and with 128-pixel work items forced.  Returns the two time
+        rows and, per count, which was faster."""
+        N, H, W, Cin = x.shape
+        k, _, _, Cout = w_hwio.shape
+        wp = pack_weights(w_hwio)
+        g_in, g_out, Ho, Wo = geometry(H, W, k, stride, block)
+        total = N * g_in.bcount_h * g_in.bcount_w
+        idx_all = torch.tensor([(n, by, bx) for n in range(N) for by in range(g_in.bcount_h) for bx in range(g_in.bcount_w)],
+                               dtype=torch.int32, device=x.device)
+        y = torch.zeros((N, Ho, Wo, Cout), dtype=x.dtype, device=x.device)
+        big, small, used = [], [], []
+        for n in counts:
+            if n > total:
+                break
+            cnt = torch.tensor([n], dtype=torch.int32, device=x.device)
+            fn = lambda: sparse_conv(x, idx_all, cnt, g_in, g_out, wp, bias, y, stride=stride, relu=True)
+            big.append(self._timed(fn, conv3_small_item_cost_eighths=1000))
+            small.append(self._timed(fn, conv3_small_item_cost_eighths=0))
+            used.append(n)
+        return {"counts": used, "ms256": big, "ms128": small,
+                "faster": ["256" if b <= s_ else "128" for b, s_ in zip(big, small)]}
+
+    def wgrad_splits(self, tiles, dout, k, stride=1, factors=(4, 8, 16, 32), counts=(32, 128, 512, 2048)):
+        """Weight gradient on tile stacks: time per split factor and active-tile count; returns the table and the
+        factor with the smallest total."""
+        cap = tiles.shape[0]
+        Cin, Cout = tiles.shape[3], dout.shape[3]
+        ws = torch.empty((max(conv_backward_weights_workspace_bytes(tiles.dtype, cap, tiles.shape[1], tiles.shape[2], Cin, k, stride, Cout), 16),),
+                         dtype=torch.uint8, device=tiles.device)
+        dw = torch.empty((k, k, Cin, Cout), dtype=torch.float32, device=tiles.device)
+        field = "wgrad_split_factor_1x1" if k == 1 else "wgrad_split_factor_3x3"
+        table = {}
+        for f in factors:
+            row = []
+            for n in counts:
+                if n > cap:
+                    break
+                cnt = torch.tensor([n], dtype=torch.int32, device=tiles.device)
+                row.append(self._timed(lambda: conv_on_tiles_backward_weights(tiles, dout, cnt, k, stride=stride, out=dw, workspace=ws),
+                                       **{field: f}))
+            table[f] = row
+        best = min(table, key=lambda f: sum(table[f]))
+        return {"counts": [n for n in counts if n <= cap], "ms": table, "best": best}

@@ -67,11 +67,11 @@ struct BneckParams {
     sbnet_geom g_in, g_out;
     int sub_h, sub_w;
     FastDiv div_sub, div_subw;
-    // The launch does its work only if lo <= (active blocks) * per16 <= hi, else every workgroup returns at once:
-    // the host cannot see the device-side count, so it launches the 16- and the 8-pixel sub-tile variants with
-    // complementary ranges and the count picks one.
-    int per16;
-    long long lo, hi;
+    // Which sub-tile size runs is decided on the device, from the count of active blocks: rounds of work over the
+    // workgroups with either size, an 8 x 8 item costing cost8 eighths of a 16 x 16 one.  The host cannot see the
+    // count, so it launches both variants and the one the rule does not pick returns at once (want16 says which
+    // variant this launch is; per16 / per8 = sub-tiles per block of either size, per16 = 0: 8 x 8 only).
+    int per16, per8, cost8, want16;
     const float *pre_scale, *pre_shift;   // pre-activation ReLU(scale * x + shift) in front of conv1, or both null
     // Bottleneck widths below 64 run as width 64: the packed weights carry zeros for the channels that do not
     // exist (t1 and t2 are exactly zero there), the biases are read as zero beyond Cm, and the packed copies of
@@ -167,8 +167,12 @@ void bottleneck16_kernel(BneckParams p) {
     BItem cur = decode(min(first, (uint32_t)p.cap * per_block - 1u));
     const int nact = max(min(nact_raw, p.cap), 0);
     const uint32_t items = (uint32_t)nact * per_block;
-    const long long work16 = (long long)nact * p.per16;
-    if (first >= items || work16 < p.lo || work16 > p.hi) return;
+    bool use16 = false;
+    if (p.per16 > 0) {
+        const unsigned long long r16 = ((unsigned long long)nact * p.per16 + 255u) >> 8, r8 = ((unsigned long long)nact * p.per8 + 255u) >> 8;
+        use16 = r16 * 8u <= r8 * (unsigned long long)p.cost8;
+    }
+    if (first >= items || use16 != (p.want16 != 0)) return;
 
     // ---- geometry of a sub-tile: origin in memory and the rows / columns that exist and lie inside the image
     struct TileGeo {
@@ -626,19 +630,21 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
     p.th = g_in->bsize_h; p.tw = g_in->bsize_w; p.oh = g_out->bsize_h; p.ow = g_out->bsize_w;
     p.H = H; p.W = W;
     p.g_in = *g_in; p.g_out = *g_out;
-    // Sub-tile side: 16 where the block allows it and the active blocks give at least half of the CUs a
-    // sub-tile of that size; otherwise 8, which quadruples the number of work items at 1.56x the halo overhead
-    // and shortens the latency chain of each.  Only the device knows the active count, so both variants are
-    // launched with complementary ranges of it and one of them returns at once (a few microseconds).
+    // Sub-tile side: 16 x 16 where the block allows it, or 8 x 8: four times the work items at 1.56x the halo overhead
+    // and a shorter latency chain each, which wins where the larger items leave most CUs idle or the last round of
+    // them nearly empty.  The device decides from its count (see BneckParams); both variants are launched and one of
+    // them returns at once (a few microseconds).
     const bool can16 = g_out->bsize_h % 16 == 0 && g_out->bsize_w % 16 == 0;
-    const long long kSmall = 128;
+    const int cost8 = tuning().unit_small_item_cost_eighths;
     hipStream_t s = (hipStream_t)stream;
     for (int ts = 16; ts >= 8; ts -= 8) {
         if (ts == 16 && !can16) continue;
         p.per16 = can16 ? (p.oh / 16) * (p.ow / 16) : 0;
-        if (ts == 16) { p.lo = kSmall + 1; p.hi = (1LL << 62); }
-        else { p.lo = 0; p.hi = can16 ? kSmall : (1LL << 62); }
-        if (can16 && ts == 16 && (long long)cap * p.per16 <= kSmall) continue;       // can never be chosen
+        p.per8 = (p.oh / 8) * (p.ow / 8);
+        p.cost8 = cost8;
+        p.want16 = ts == 16;
+        if (can16 && ts == 16 && cost8 <= 0) continue;          // can never be chosen
+        if (can16 && ts == 8 && cost8 >= 1000) continue;        // neither can this one
         p.sub_h = p.oh / ts; p.sub_w = p.ow / ts;
         p.div_sub = make_fastdiv((uint32_t)p.sub_h * p.sub_w);
         p.div_subw = make_fastdiv((uint32_t)p.sub_w);
@@ -646,7 +652,6 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
         if (items >= (1LL << 31)) return fail(SBNET_EUNSUPPORTED, "%s: too many work items", who);
         long long gx = (items + 7) / 8 * 8;
         if (gx > 256) gx = 256;
-        if (ts == 8 && can16 && gx > (kSmall * 4 + 7) / 8 * 8) gx = (kSmall * 4 + 7) / 8 * 8;   // never more items than that
         dim3 grid((unsigned)gx);
         sbnet_status st;
         if (dt == SBNET_BF16)

@@ -10,6 +10,9 @@
 
 namespace sbnet {
 
+// the compute-tile choices in force (sbnet_set_tuning), read when a call is enqueued
+sbnet_tuning tuning();
+
 // thread-local text behind sbnet_last_error()
 char *error_buffer();
 sbnet_status fail(sbnet_status code, const char *fmt, ...);

@@ -490,14 +490,14 @@ void conv3_pointwise_kernel(ConvParams p, Plan3 q) {
 
 // The 256-pixel and the 128-pixel tile shape in one launch: the device-side count picks one (rounds of work on 256
 // CUs with either shape; an item of the smaller tile costs about 5/8 of a larger one: half the matrix work, the same
-// weights to stage).  Two separate launches, of which one returns, cost a launch more.
+// weights to stage; the ratio comes with the launch, in eighths).  Two separate launches, of which one returns, cost a launch more.
 template <int DT, bool FUSED, bool ADD, int CCB, int NVIB, int CCS, int NVIS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void conv3_pair_kernel(ConvParams p, Plan3 qb, Plan3 qs) {
     const int nact = max(min(*p.count, p.cap), 0);
     const uint32_t per_big = (uint32_t)qb.mpasses * qb.ngroups, per_small = (uint32_t)qs.mpasses * qs.ngroups;
     const uint32_t rb = ((uint32_t)nact * per_big + 255u) >> 8, rs = ((uint32_t)nact * per_small + 255u) >> 8;
-    if (rb * 8u <= rs * 5u) conv3_body<DT, FUSED, ADD, CCB, 4, 2, 2, NVIB>(p, qb);
+    if ((unsigned long long)rb * 8u <= (unsigned long long)rs * (uint32_t)p.small_cost8) conv3_body<DT, FUSED, ADD, CCB, 4, 2, 2, NVIB>(p, qb);
     else conv3_body<DT, FUSED, ADD, CCS, 4, 2, 1, NVIS>(p, qs);
 }
 
@@ -627,7 +627,9 @@ static void launch3_pair_small(const ConvParams &p, const Shape3 &big, const Sha
         auto kern = conv3_pair_kernel<DT, FUSED, ADD, CCB, NVIB, CCS, NVIS>;                                   \
         if (lds > 48 * 1024)                                                                                   \
             (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, p, big.q, small.q);                            \
+        ConvParams pt = p;                                                                                     \
+        pt.small_cost8 = tuning().conv3_small_item_cost_eighths;                                               \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, pt, big.q, small.q);                           \
     } while (0)
     if (small.cc == 32 && small.nvi == 3) SBNET_L3P(32, 3);
     else if (small.cc == 32) SBNET_L3P(32, 6);

@@ -37,6 +37,7 @@ struct WgradParams {
     const int32_t *count;
     int cap, th, tw, oh, ow, Cin, Cout, kh, kw, sh, sw;
     int nsplit, ncb, nob, CinP, CoutP;
+    int split_factor;         // splits used = min(nsplit, n, split_factor * sqrt(n))
     uint32_t x_tile_bytes, g_tile_bytes;
 };
 
@@ -69,8 +70,8 @@ __host__ __device__ __forceinline__ size_t split_stride(int taps, int CinP, int 
 // (written once, read once by the sum) and every tile of a split costs matrix time, so the best number grows with the
 // square root of n: 8 sqrt(n) suits the two costs measured on 64 x 64 channel blocks.  Both kernels call this with
 // the same arguments.
-__device__ __forceinline__ int splits_used(int n, int nsplit, int taps) {
-    int ns = (int)sqrtf((taps == 1 ? 256.f : 64.f) * (float)n);   // a 1x1 partial result is a ninth of a 3x3 one: 16 sqrt(n)
+__device__ __forceinline__ int splits_used(int n, int nsplit, int factor) {
+    int ns = (int)sqrtf((float)(factor * factor) * (float)n);     // factor: 8 for 3x3; a 1x1 partial result is a ninth of that: 16
     if (ns > n) ns = n;
     if (ns > nsplit) ns = nsplit;
     return ns < 1 ? 1 : ns;
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(256) void wgrad_mfma(WgradParams p) {
     const int cb = cbob / p.nob, ob = cbob - cb * p.nob;
     int n = *p.count;
     if (n > p.cap) n = p.cap;
-    const int ns = splits_used(n, p.nsplit, p.kh * p.kw);
+    const int ns = splits_used(n, p.nsplit, p.split_factor);
     if (n <= 0 || sigma >= ns) return;                             // the sum reads no partial result of this split
     const int ntiles = (n - sigma + ns - 1) / ns;
     const int H = (p.oh + R - 1) / R;
@@ -303,7 +304,7 @@ __global__ __launch_bounds__(256) void wgrad_direct(WgradParams p) {
     if (e >= total) return;
     int n = *p.count;
     if (n > p.cap) n = p.cap;
-    const int sigma = blockIdx.y, ns = splits_used(n, p.nsplit, p.kh * p.kw);
+    const int sigma = blockIdx.y, ns = splits_used(n, p.nsplit, p.split_factor);
     if (n <= 0 || sigma >= ns) return;
     const int o = e % p.Cout, c = (e / p.Cout) % p.Cin, tap = e / (p.Cout * p.Cin);
     const int r = tap / p.kw, t = tap - r * p.kw;
@@ -325,15 +326,15 @@ __global__ __launch_bounds__(256) void wgrad_direct(WgradParams p) {
 // weights fill at most 256 workgroups (1x1 kernels: the launch is short and the splits are many), else 4.
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void wgrad_sum(const float *__restrict__ part, const int32_t *__restrict__ count, int cap,
-                                                  int nsplit, int taps, int Cin, int Cout, int CinP, int CoutP,
-                                                  float *__restrict__ dw) {
+                                                  int nsplit, int split_factor, int taps, int Cin, int Cout, int CinP,
+                                                  int CoutP, float *__restrict__ dw) {
     __shared__ float slice[NW][64];
     const int total = taps * Cin * Cout;
     const int lane = threadIdx.x & 63, k = threadIdx.x >> 6;
     const int e = blockIdx.x * 64 + lane;
     int n = *count;
     if (n > cap) n = cap;
-    n = n > 0 ? splits_used(n, nsplit, taps) : 0;
+    n = n > 0 ? splits_used(n, nsplit, split_factor) : 0;
     float acc = 0.f;
     if (e < total) {
         const int o = e % Cout, c = (e / Cout) % Cin, tap = e / (Cout * Cin);
@@ -461,6 +462,8 @@ extern "C" sbnet_status sbnet_conv_on_tiles_backward_weights(const void *tiles_i
     p.cap = cap; p.th = th; p.tw = tw; p.oh = (th - kh) / sh + 1; p.ow = (tw - kw) / sw + 1;
     p.Cin = Cin; p.Cout = Cout; p.kh = kh; p.kw = kw; p.sh = sh; p.sw = sw;
     p.nsplit = q.nsplit; p.ncb = q.ncb; p.nob = q.nob; p.CinP = q.CinP; p.CoutP = q.CoutP;
+    const sbnet_tuning tune = tuning();
+    p.split_factor = taps == 1 ? tune.wgrad_split_factor_1x1 : tune.wgrad_split_factor_3x3;
     p.x_tile_bytes = (uint32_t)((size_t)th * tw * Cin * 2);
     p.g_tile_bytes = (uint32_t)((size_t)p.oh * p.ow * Cout * 2);
     if (q.mfma && q.flat) {
@@ -484,11 +487,11 @@ extern "C" sbnet_status sbnet_conv_on_tiles_backward_weights(const void *tiles_i
     }
     const unsigned sum_grid = (unsigned)((total + 63) / 64);
     if (sum_grid <= 256)
-        hipLaunchKernelGGL(wgrad_sum<16>, dim3(sum_grid), dim3(1024), 0, s, (const float *)workspace, count, cap, q.nsplit, taps,
-                           Cin, Cout, q.CinP, q.CoutP, dw);
+        hipLaunchKernelGGL(wgrad_sum<16>, dim3(sum_grid), dim3(1024), 0, s, (const float *)workspace, count, cap, q.nsplit, p.split_factor,
+                           taps, Cin, Cout, q.CinP, q.CoutP, dw);
     else
-        hipLaunchKernelGGL(wgrad_sum<4>, dim3(sum_grid), dim3(256), 0, s, (const float *)workspace, count, cap, q.nsplit, taps,
-                           Cin, Cout, q.CinP, q.CoutP, dw);
+        hipLaunchKernelGGL(wgrad_sum<4>, dim3(sum_grid), dim3(256), 0, s, (const float *)workspace, count, cap, q.nsplit, p.split_factor,
+                           taps, Cin, Cout, q.CinP, q.CoutP, dw);
     return launch_status(who);
 }
 

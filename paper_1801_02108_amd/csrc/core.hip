@@ -2,7 +2,18 @@
 // and the synchronising read-back of the active-block counter.
 #include "common.h"
 
+#include <mutex>
+
 namespace sbnet {
+
+static const sbnet_tuning kDefaultTuning = {3, 5, 8, 16};
+static sbnet_tuning g_tuning = kDefaultTuning;
+static std::mutex g_tuning_mutex;
+
+sbnet_tuning tuning() {
+    std::lock_guard<std::mutex> lock(g_tuning_mutex);
+    return g_tuning;
+}
 
 char *error_buffer() {
     static thread_local char buf[512] = "";
@@ -22,6 +33,21 @@ sbnet_status fail(sbnet_status code, const char *fmt, ...) {
 using namespace sbnet;
 
 extern "C" const char *sbnet_last_error(void) { return error_buffer(); }
+
+extern "C" sbnet_status sbnet_set_tuning(const sbnet_tuning *t) {
+    if (t && (t->unit_small_item_cost_eighths < 0 || t->conv3_small_item_cost_eighths < 0 || t->wgrad_split_factor_3x3 < 1 ||
+              t->wgrad_split_factor_1x1 < 1 || t->wgrad_split_factor_3x3 > 1024 || t->wgrad_split_factor_1x1 > 1024))
+        return fail(SBNET_EINVAL, "sbnet_set_tuning: value out of range");
+    std::lock_guard<std::mutex> lock(g_tuning_mutex);
+    g_tuning = t ? *t : kDefaultTuning;
+    return SBNET_OK;
+}
+
+extern "C" sbnet_status sbnet_get_tuning(sbnet_tuning *t) {
+    if (!t) return fail(SBNET_EINVAL, "sbnet_get_tuning: null pointer");
+    *t = tuning();
+    return SBNET_OK;
+}
 
 extern "C" sbnet_status sbnet_geometry(int H, int W, int kh, int kw, int sh, int sw, int bo_h, int bo_w,
                                        sbnet_geom *g_in, sbnet_geom *g_out, int *H_out, int *W_out) {

@@ -39,7 +39,10 @@ def test_sweep_caches_and_round_trips_through_json(tmp_path):
         return (lambda: bo), 10 * bo, 100
 
     tuner = at.BlockSizeTuner(candidates=(8, 16, 32), measure=lambda fn: cost[fn()])
-    key = at.cache_key("conv3", 1, 64, 64, 32, 32, 1, torch.bfloat16, 5)
+    key = at.cache_key("conv3", 1, 64, 64, 32, 32, 1, torch.bfloat16, 5, "relu1.bias1", (8, 16, 32))
+    # what a sweep depends on is in the key: other options or another candidate set is another entry
+    assert key != at.cache_key("conv3", 1, 64, 64, 32, 32, 1, torch.bfloat16, 5, "relu0.bias1", (8, 16, 32))
+    assert key != at.cache_key("conv3", 1, 64, 64, 32, 32, 1, torch.bfloat16, 5, "relu1.bias1", (8, 16))
     res = tuner._sweep(key, run_for_block)
     assert res.best == 16 and calls == [8, 16]
     assert res.table[8]["active_blocks"] == 80 and "error" in res.table[32]
@@ -52,6 +55,143 @@ def test_sweep_caches_and_round_trips_through_json(tmp_path):
     fresh = at.BlockSizeTuner()
     fresh.load(str(path))
     assert fresh.lookup(key) == 16 and fresh._sweep(key, run_for_block).best == 16 and calls == [8, 16]
+
+
+def test_crossover_is_the_first_count_from_which_the_large_regime_stays_faster():
+    counts = [8, 16, 32, 64, 128]
+    assert at.crossover(counts, [1, 2, 3, 4, 5], [2, 2.5, 2.9, 3, 3]) == 32
+    assert at.crossover(counts, [1, 1, 1, 1, 1], [2, 2, 2, 2, 2]) is None
+    assert at.crossover(counts, [3, 3, 3, 3, 3], [2, 2, 2, 2, 2]) == 8
+    assert at.crossover(counts, [1, 3, 1, 3, 3], [2, 2, 2, 2, 2]) == 64      # a dip back restarts the search
+
+
+def test_tuning_struct_round_trips_and_rejects_nonsense():
+    import paper_1801_02108_amd as sb
+    try:
+        d = sb.set_tuning()
+        assert d == {"unit_small_item_cost_eighths": 3, "conv3_small_item_cost_eighths": 5, "wgrad_split_factor_3x3": 8,
+                     "wgrad_split_factor_1x1": 16}
+        assert sb.set_tuning(unit_small_item_cost_eighths=4)["unit_small_item_cost_eighths"] == 4
+        assert sb.get_tuning()["wgrad_split_factor_1x1"] == 16
+        with pytest.raises(sb.SbnetError):
+            sb.set_tuning(wgrad_split_factor_3x3=0)
+        with pytest.raises(KeyError):
+            sb.set_tuning(no_such_field=1)
+        assert sb.get_tuning()["unit_small_item_cost_eighths"] == 4             # a rejected change changes nothing
+    finally:
+        assert sb.set_tuning()["unit_small_item_cost_eighths"] == 3
+
+
+def test_cost_fit_recovers_the_ratio_of_per_round_times():
+    # large items: 20 us per round of 256; small ones (four per block): 8 us per round; 4 us launch floor on both
+    counts = [32, 64, 128, 256, 512]
+    large = [0.004 + 0.020 * -(-n // 256) for n in counts]
+    small = [0.004 + 0.008 * -(-n * 4 // 256) for n in counts]
+    assert at.fit_cost_eighths(counts, large, small, 1, 4) == 3.2
+    assert at.fit_cost_eighths([], [], [], 1, 4) is None
+
+
+@pytest.mark.gpu
+def test_results_at_the_tuned_choices_equal_the_oracle():
+    """Whatever the tuner picks must compute the same thing: the fused convolution and the residual unit at the tuned
+    block size, and under every forced compute-tile choice, against the oracle; the two sub-tile sizes of the unit and
+    the two item sizes of the 3x3 kernel give the same bits; the weight gradient at every split factor stays within
+    its tolerance."""
+    import oracle as orc
+    import paper_1801_02108_amd as sb
+    from paper_1801_02108_amd import inputs as gen
+    from util import CONV_TOL, assert_close, to_dev, to_host
+    r = gen.rng_for(7, 3)
+    N, H, W, C, K = 1, 96, 128, 96, 96
+    x = gen.activations(r, (N, H, W, C), "bf16")
+    w = gen.conv_weights(r, 3, 3, C, K, "bf16")
+    b = gen.bias_vector(r, K)
+    mask = np.zeros((N, H, W), np.uint8)
+    mask[:, 10:70, 30:100] = 1
+    dx, dw_, db, dm = to_dev(x, "bf16"), to_dev(w, "bf16"), torch.from_numpy(b).cuda(), torch.from_numpy(mask).cuda()
+    tuner = at.BlockSizeTuner(candidates=(8, 16, 32))
+    best = tuner.tune_conv(dx, dm, dw_, db).best
+
+    def conv_at(bo):
+        g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, 1, bo)
+        idx, cnt = sb.reduce_mask(dm, g_in)
+        y0 = gen.activations(r, (N, Ho, Wo, K), "bf16")
+        y = to_dev(y0, "bf16")
+        sb.sparse_conv(dx, idx, cnt, g_in, g_out, sb.pack_weights(dw_), db, y, relu=True)
+        oidx = orc.reduce_mask(mask, orc.Geom(*g_in.astuple()))
+        return y, orc.sparse_conv_dense(x, oidx, orc.Geom(*g_out.astuple()), w, b, y0, relu=True)
+    try:
+        y, ref = conv_at(best)
+        assert_close(to_host(y), ref, CONV_TOL["bf16"], "conv at the tuned block size %d" % best)
+        # 96 channels run on the LDS-tiled kernel: both item sizes forced
+        sb.set_tuning(conv3_small_item_cost_eighths=1000)
+        y_big, ref16 = conv_at(16)
+        sb.set_tuning(conv3_small_item_cost_eighths=0)
+        y_small, _ = conv_at(16)
+        assert_close(to_host(y_big), ref16, CONV_TOL["bf16"], "256-pixel items")
+        # (the reference draws a fresh y0 per call: compare the active blocks)
+        bm = torch.from_numpy(orc.block_mask(orc.reduce_mask(mask, orc.Geom(*sb.geometry(H, W, 3, 1, 16)[0].astuple())),
+                                             orc.Geom(*sb.geometry(H, W, 3, 1, 16)[1].astuple()), N, H, W)).cuda()
+        assert torch.equal(y_big[bm], y_small[bm])
+        sb.set_tuning()
+
+        # residual unit 96 / 24 at its tuned block size and with either sub-tile size forced
+        ws = gen.bottleneck_weights(r, C, 24, "bf16")
+        dws = tuple(sb.pack_weights(to_dev(t, "bf16")) if t.ndim == 4 else torch.from_numpy(t).cuda() for t in ws)
+        bu = tuner.tune_bottleneck(dx, dm, dws).best
+        outs = {}
+        for name, thr in (("tuned", None), ("sub16", 1000), ("sub8", 0)):
+            bo = bu if name == "tuned" else 16
+            if thr is not None:
+                sb.set_tuning(unit_small_item_cost_eighths=thr)
+            g_in, g_out, _, _ = sb.geometry(H, W, 3, 1, bo)
+            idx, cnt = sb.reduce_mask(dm, g_in)
+            y = dx.clone()
+            sb.sparse_bottleneck(dx, idx, cnt, g_in, g_out, dws, y)
+            oidx = orc.reduce_mask(mask, orc.Geom(*g_in.astuple()))
+            ref = orc.sparse_bottleneck_tiled(x, oidx, orc.Geom(*g_in.astuple()), orc.Geom(*g_out.astuple()), *ws)
+            assert_close(to_host(y), ref, CONV_TOL["bf16"], "unit, " + name)
+            outs[name] = y
+            sb.set_tuning()
+        assert torch.equal(outs["sub16"], outs["sub8"])
+
+        # weight gradient at every split factor
+        tiles = gen.activations(r, (300, 18, 18, 64), "bf16")
+        dout = gen.activations(r, (300, 16, 16, 64), "bf16")
+        cnt = torch.tensor([300], dtype=torch.int32).cuda()
+        want = orc.conv_valid_backward_weights(tiles, dout, 3, 3)
+        for f in (1, 4, 8, 32, 1024):
+            sb.set_tuning(wgrad_split_factor_3x3=f)
+            got = sb.conv_on_tiles_backward_weights(to_dev(tiles, "bf16"), to_dev(dout, "bf16"), cnt, 3)
+            assert_close(to_host(got), want, 2e-5, "weight gradient, split factor %d" % f)
+    finally:
+        sb.set_tuning()
+
+
+@pytest.mark.gpu
+def test_kernel_choice_tuner_measures_both_alternatives():
+    """The second half of the search runs: both alternatives of every choice are timed, the tuning in force is restored."""
+    import paper_1801_02108_amd as sb
+    from paper_1801_02108_amd import inputs as gen
+    r = gen.rng_for(7, 4)
+    before = sb.get_tuning()
+    kt = at.KernelChoiceTuner()
+    xb = torch.from_numpy(gen.activations(r, (1, 160, 192, 64), "bf16")).to(torch.bfloat16).cuda()
+    wts = gen.bottleneck_weights(r, 64, 64, "bf16")
+    dev_w = tuple(sb.pack_weights(torch.from_numpy(t).to(torch.bfloat16).cuda()) if t.ndim == 4 else torch.from_numpy(t).cuda()
+                  for t in wts)
+    res = kt.unit_subtiles(xb, dev_w, block=16, counts=(8, 64, 120))
+    assert res["counts"] == [8, 64, 120] and len(res["ms16"]) == len(res["ms8"]) == 3 and all(v > 0 for v in res["ms16"] + res["ms8"])
+    assert set(res["faster"]) <= {"16", "8"} and res["cost_eighths"] > 0
+    xc = torch.from_numpy(gen.activations(r, (1, 128, 128, 96), "bf16")).to(torch.bfloat16).cuda()
+    wc = torch.from_numpy(gen.conv_weights(r, 3, 3, 96, 96, "bf16")).to(torch.bfloat16).cuda()
+    rc = kt.conv3_items(xc, wc, counts=(8, 64))
+    assert rc["counts"] == [8, 64] and set(rc["faster"]) <= {"256", "128"}
+    t = torch.from_numpy(gen.activations(r, (64, 18, 18, 64), "bf16")).to(torch.bfloat16).cuda()
+    g = torch.from_numpy(gen.activations(r, (64, 16, 16, 64), "bf16")).to(torch.bfloat16).cuda()
+    rw = kt.wgrad_splits(t, g, 3, factors=(4, 8), counts=(32, 64))
+    assert rw["best"] in (4, 8) and rw["counts"] == [32, 64]
+    assert sb.get_tuning() == before
 
 
 @pytest.mark.gpu
