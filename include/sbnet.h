@@ -273,7 +273,7 @@ sbnet_status sbnet_conv_on_tiles(const void *tiles_in, sbnet_dtype dtype, const 
  * sbnet_sparse_gather with g_in, sbnet_conv_on_tiles, sbnet_sparse_scatter with g_out, except
  * that the convolution result is not rounded to `dtype` before the add; the intermediate tile
  * stacks never exist.  x: [N][H][W][Cin]; y: [N][H_out][W_out][Cout].
- * g_in/g_out as produced by sbnet_geometry for this convolution.  y must not alias x.
+ * g_in/g_out as produced by sbnet_geometry for this convolution.  y must not overlap x (not even in part).
  */
 sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int N, int H, int W, int Cin,
                                const int32_t *indices, const int32_t *count, int cap,

@@ -605,7 +605,8 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
         return fail(SBNET_EINVAL, "%s: input tile must be the output block plus a one-pixel halo", who);
     if (g_out->bstride_h < g_out->bsize_h || g_out->bstride_w < g_out->bsize_w)
         return fail(SBNET_EINVAL, "%s: output blocks must not overlap", who);
-    if (fused && in == out) return fail(SBNET_EINVAL, "%s: y must not alias x (use two buffers, see header)", who);
+    if (fused && ranges_overlap(in, (size_t)N * H * W * C * 2, out, (size_t)N * H * W * C * 2))
+        return fail(SBNET_EINVAL, "%s: y must not overlap x (use two buffers, see header)", who);
     if (((uintptr_t)in | (uintptr_t)out | (uintptr_t)w1 | (uintptr_t)w2 | (uintptr_t)w3) & 15)
         return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
     if (dt != SBNET_BF16 && dt != SBNET_F16) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be bf16 or f16", who);

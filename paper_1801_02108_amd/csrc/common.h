@@ -44,6 +44,12 @@ sbnet_status mask_to_flags(const char *who, const void *mask, sbnet_dtype mdt, i
 sbnet_status flags_to_indices(const char *who, const uint8_t *flags, int N, const sbnet_geom *g, int32_t *indices,
                               int32_t *count, int cap, hipStream_t s);
 
+// do the byte ranges [a, a + a_bytes) and [b, b + b_bytes) share a byte?
+inline bool ranges_overlap(const void *a, size_t a_bytes, const void *b, size_t b_bytes) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
 inline sbnet_status launch_status(const char *what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(SBNET_EHIP, "%s: %s", what, hipGetErrorString(e));

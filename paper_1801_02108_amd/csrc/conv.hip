@@ -649,7 +649,8 @@ extern "C" sbnet_status sbnet_sparse_conv(const void *x, sbnet_dtype dtype, int 
         return fail(SBNET_EINVAL, "%s: output block does not match the convolution of the input tile", who);
     if (g_out->bstride_h < g_out->bsize_h || g_out->bstride_w < g_out->bsize_w)
         return fail(SBNET_EINVAL, "%s: output blocks must not overlap", who);
-    if (x == y) return fail(SBNET_EINVAL, "%s: y must not alias x", who);
+    if (ranges_overlap(x, (size_t)N * H * W * Cin * elem_bytes(dtype), y, (size_t)N * H_out * W_out * Cout * elem_bytes(dtype)))
+        return fail(SBNET_EINVAL, "%s: y must not overlap x", who);
     if (((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_packed) & 15)
         return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
     ConvParams p = {};
@@ -680,7 +681,9 @@ extern "C" sbnet_status sbnet_sparse_conv_from_flags(const uint8_t *flags, const
     if (!mask_flag_path(N, g_in)) return fail(SBNET_EUNSUPPORTED, "%s: more blocks than the flag form takes", who);
     if (((uintptr_t)flags) & 15) return fail(SBNET_EINVAL, "%s: flags must be 16-byte aligned", who);
     hipStream_t s = (hipStream_t)stream;
-    bool fold = cap > 0 && x != y && !(((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_packed) & 15) &&
+    bool fold = cap > 0 && is_float_dtype(dtype) &&
+                !ranges_overlap(x, (size_t)N * H * W * Cin * elem_bytes(dtype), y, (size_t)N * H_out * W_out * Cout * elem_bytes(dtype)) &&
+                !(((uintptr_t)x | (uintptr_t)y | (uintptr_t)w_packed) & 15) &&
                 check_conv_shape(who, dtype, cap, g_in->bsize_h, g_in->bsize_w, Cin, kh, kw, sh, sw, Cout) == SBNET_OK &&
                 (g_in->bsize_h - kh) / sh + 1 == g_out->bsize_h && (g_in->bsize_w - kw) / sw + 1 == g_out->bsize_w &&
                 g_out->bstride_h >= g_out->bsize_h && g_out->bstride_w >= g_out->bsize_w && use_mfma(dtype, Cin, Cout);

@@ -66,6 +66,9 @@ extern "C" sbnet_status sbnet_sparse_unit(const void *x, sbnet_dtype dtype, int 
     if (!w_shortcut && (Cin != Cout || stride != 1))
         return fail(SBNET_EINVAL, "%s: the identity shortcut needs stride 1 and equal channel counts", who);
     if (w_shortcut && !b_shortcut) return fail(SBNET_EINVAL, "%s: a projected shortcut needs its bias", who);
+    if (is_float_dtype(dtype) && x != y &&
+        ranges_overlap(x, (size_t)N * H * W * Cin * elem_bytes(dtype), y, (size_t)N * H_out * W_out * Cout * elem_bytes(dtype)))
+        return fail(SBNET_EINVAL, "%s: y must be x itself (identity shortcut only) or not overlap it", who);
     if (w_shortcut && x == y) return fail(SBNET_EINVAL, "%s: y must not alias x with a projected shortcut", who);
     if (cap == 0) return SBNET_OK;
 

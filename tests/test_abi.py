@@ -144,3 +144,20 @@ def test_bottleneck_backward_checks_its_arguments_on_the_host():
     assert lib.sbnet_bottleneck_backward_on_tiles(n, n, n, n, sb.BF16, n, 4, 18, 18, 256, 64, n, n, n, n, n, n, n, n, n, n, n, 0,
                                                   n) == sb.EINVAL
     assert b"null" in lib.sbnet_last_error()
+
+
+def test_overlapping_input_and_output_are_rejected_not_only_equal_pointers():
+    """The fused calls read halo pixels of x that other workgroups may already have overwritten if y shared memory with
+    x: any overlap of the two byte ranges is an argument error, found on the host (fake, aligned addresses; no launch)."""
+    lib = sb.lib()
+    g_in, g_out, _, _ = sb.geometry(32, 32, 3, 1, 16)
+    base = 0x7f0000000000
+    nbytes = 1 * 32 * 32 * 64 * 2
+    P = ctypes.c_void_p
+    for dy in (0, 16, nbytes // 2, nbytes - 16):
+        rc = lib.sbnet_sparse_conv(P(base), sb.BF16, 1, 32, 32, 64, P(base), P(base), 4, g_in, g_out, P(base), None,
+                                   3, 3, 1, 1, 64, 0, P(base + dy), 32, 32, 0, None)
+        assert rc == sb.EINVAL and b"overlap" in lib.sbnet_last_error(), dy
+        rc = lib.sbnet_sparse_bottleneck(P(base), sb.BF16, 1, 32, 32, 64, 64, P(base), P(base), 4, g_in, g_out, P(base), P(base),
+                                         P(base), P(base), P(base), P(base), P(base + dy), None)
+        assert rc == sb.EINVAL and b"overlap" in lib.sbnet_last_error(), dy

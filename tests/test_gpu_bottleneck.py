@@ -10,7 +10,7 @@ import torch
 import oracle as orc
 import paper_1801_02108_amd as sb
 from paper_1801_02108_amd import inputs as gen
-from util import CONV_TOL, TORCH_DT, assert_close, to_dev, to_host
+from util import round_like, CONV_TOL, TORCH_DT, assert_close, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -109,6 +109,25 @@ def _unit_case(N, H, W, C, Cm, bo, dtype):
         assert_close(got[bm], ref[bm], CONV_TOL[dtype], "fused unit")
         # the fused kernel rounds t3 to the storage type before the add, as the tile stack of the unfused path does
         assert np.array_equal(got[bm], unfused[bm])
+        # A tighter, second check: the oracle with t1, t2 and t3 rounded to the storage type where the kernel rounds
+        # them.  What is left is fp32 summation order and the rare value that lands on the other side of a rounding
+        # boundary: every element within four units in the last place (bf16: 2^-8, f16: 2^-11) of the magnitude
+        # of its terms, where the stated tolerance allows 2e-2 of the tensor's RMS.
+        if len(idx):
+            rl = lambda a: round_like(a, dtype)
+            tiles_r = orc.gather(x, idx, ogeom(g_in))
+            t1_r = rl(orc.zero_outside(orc.conv_valid(tiles_r, ws[0], ws[1], relu=True), idx, ogeom(g_in), H, W))
+            t2_r = rl(orc.conv_valid(t1_r, ws[2], ws[3], relu=True))
+            t3_r = rl(orc.conv_valid(t2_r, ws[4], ws[5]))
+            y_r = rl(orc.scatter(t3_r, idx, ogeom(g_out), x, add=True))
+            # magnitude an element's error scales with: |x| plus the sum of |t2| |w3| over the last layer's terms (t3
+            # itself may be small by cancellation while a one-unit change of any t2 moves it by that unit's share)
+            t3_mag = orc.conv_valid(np.abs(t2_r), np.abs(ws[4]), np.abs(ws[5]))
+            mag = np.abs(x) + orc.scatter(t3_mag, idx, ogeom(g_out), np.zeros_like(x), add=False)
+            ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -11
+            worst = (np.abs(got - y_r) / (mag + 1e-30))[bm].max()
+            print("rounded-intermediates check: worst %.2f units in the last place" % (worst / ulp), flush=True)
+            assert worst <= 4 * ulp, "fused unit against the oracle with rounded intermediates: %.3g units in the last place" % (worst / ulp)
         if dens == 1.0:                                            # every block active: the dense unit
             assert_close(got, orc.sparse_bottleneck_dense(x, idx, ogeom(g_out), *ws), CONV_TOL[dtype], "dense unit")
 
