@@ -245,12 +245,13 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
     if (FLAGS) {
         // Compaction of the flag bytes (each 0 or 1, the padding behind the last block 0).  Every wave does all of it
         // for itself, 4096 blocks per round: a lane takes 64 consecutive flags, a prefix sum over the lanes and the
-        // rounds gives the list positions of its active blocks.  Only the positions of this workgroup's own items
-        // (first, first + G, ...) are resolved to a block, by the one lane whose run contains them, into a table the
-        // wave keeps for itself: no barrier and no exchange between waves, and a round without an item of this
-        // workgroup costs some forty instructions.  per_block is 1 in this form: list position = item number.
+        // rounds gives the list positions [excl, excl + c) of its active blocks.  This workgroup's items are the
+        // positions first, first + G, ...; G is at least 64, so a lane's run holds at most one of them, and every lane
+        // looks for its own in parallel: k = ceil((excl - first) / G), and if first + k G lies in the run, the block is
+        // the (first + k G - excl)-th set flag of the lane's 64, found by halving.  The table the blocks go to is the
+        // wave's own: no barrier and no exchange between waves, some sixty instructions per round whatever the number
+        // of items.  per_block is 1 in this form: list position = item number.
         int running = 0;
-        uint32_t pk = first;                         // list position of the next own item
         static_assert(kEarly == 4, "the scan takes four flag vectors per lane and round");
         auto count16 = [](uint4 v) __attribute__((always_inline)) { return __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w); };
         // (the four vectors travel as values, not as an array: an array indexed at run time would live in scratch memory)
@@ -260,24 +261,25 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
             const int c = c0 + c1 + c2 + c3;
             const int incl = wave_inclusive_sum(c);
             const int excl = running + incl - c;
-            const int end = running + __builtin_amdgcn_readlane(incl, 63);
-            while ((int)pk < end && (int)pk < p.cap) {                   // uniform over the wave
-                if ((int)pk >= excl && (int)pk < excl + c) {             // one lane: find its (pk - excl)-th flag
-                    int skip = (int)pk - excl, r = 0;
-                    uint4 v = q0;
-                    if (skip >= c0) { skip -= c0; v = q1; r = 1;
-                        if (skip >= c1) { skip -= c1; v = q2; r = 2;
-                            if (skip >= c2) { skip -= c2; v = q3; r = 3; } } }
-                    // the 0/1 bytes of a word gathered into four neighbouring bits by one multiplication
-                    uint32_t bits = ((v.x * 0x01020408u) >> 24) | (((v.y * 0x01020408u) >> 24) << 4) |
-                                    (((v.z * 0x01020408u) >> 24) << 8) | (((v.w * 0x01020408u) >> 24) << 12);
-                    for (; skip > 0; --skip) bits &= bits - 1;
-                    mine[kk] = (uint32_t)(b0 + r * 16 + __ffs(bits) - 1);        // kk < kMineMax: checked on the host
+            const uint32_t k = excl > (int)first ? fdiv((uint32_t)excl - first + G - 1u, p.div_grid) : 0u;
+            const int pos = (int)(first + k * G);                        // the first own position not in front of the run
+            if (pos < excl + c && pos < p.cap) {                         // (pos >= excl by construction)
+                int skip = pos - excl, at = 0;
+                uint4 v = q0;
+                if (skip >= c0) { skip -= c0; v = q1; at = 16;
+                    if (skip >= c1) { skip -= c1; v = q2; at = 32;
+                        if (skip >= c2) { skip -= c2; v = q3; at = 48; } } }
+                // the 0/1 bytes of a word gathered into four neighbouring bits by one multiplication
+                uint32_t bits = ((v.x * 0x01020408u) >> 24) | (((v.y * 0x01020408u) >> 24) << 4) |
+                                (((v.z * 0x01020408u) >> 24) << 8) | (((v.w * 0x01020408u) >> 24) << 12);
+#pragma unroll
+                for (int half = 8; half >= 1; half >>= 1) {              // the skip-th set bit, by halving
+                    const int below = __popc(bits & ((1u << half) - 1u));
+                    if (skip >= below) { skip -= below; bits >>= half; at += half; }
                 }
-                pk += G;
-                ++kk;
+                mine[k] = (uint32_t)(b0 + at);                           // k < kMineMax: checked on the host
             }
-            running = end;
+            running += __builtin_amdgcn_readlane(incl, 63);
         };
         scan_round(fl[0], fl[1], fl[2], fl[3], lane * kEarly * 16);
         for (int c0 = kEarly * 1024; c0 < p.total_blocks; c0 += kEarly * 1024) {
@@ -291,6 +293,7 @@ void conv16_kernel(ConvParams p, Sub16 sp) {
         nact_raw = running;
     }
     const uint32_t items = (uint32_t)max(min(nact_raw, p.cap), 0) * per_block;
+    if (FLAGS && first < items) kk = fdiv(items - 1u - first, p.div_grid) + 1u;
     if (first >= items) {
         // no item: all that is left is the count, should this be the workgroup that reports it
         if (FLAGS && blockIdx.x == 0 && ng == 0 && threadIdx.x == 0) *p.count_out = nact_raw;
@@ -529,7 +532,7 @@ static bool conv16_plan(sbnet_dtype dt, bool fused, const ConvParams &p, Sub16 *
     if (p.flags) {
         // flag-fed form: list position = item number, a workgroup's items fit its table, block numbers fit the scan
         if (!fused || sp.sub_h != 1 || sp.sub_w != 1 || p.total_blocks > 65536 || p.total_blocks <= 0) return false;
-        if (g == 0 || (items + g - 1) / g > kMineMax) return false;
+        if (g < 64 || (items + g - 1) / g > kMineMax) return false;      // a lane's 64 flags hold at most one of a workgroup's items
         if (!p.indices_out || !p.count_out) return false;
     }
     *spo = sp;
