@@ -72,6 +72,7 @@ def run_units(args):
     import torch
     import paper_1801_02108_amd as sb
     from paper_1801_02108_amd import inputs as gen
+    from paper_1801_02108_amd.autotune import device_ms
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
     cfg = args.workload
@@ -153,26 +154,26 @@ def run_units(args):
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / iters
-            # the unit kernel alone
+            # the unit kernel alone, and in pre-activation form (ReLU(scale * x + shift) in front of conv1): device time
+            # from graph replays (eager launches of a 10 us kernel would time the host), eager under the profiler
             u0 = units[0]
-            for _ in range(2):
-                sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1])
-            e0.record()
-            for _ in range(iters):
-                sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1])
-            e1.record()
-            torch.cuda.synchronize()
-            k_ms = e0.elapsed_time(e1) / iters
-            # ... and in pre-activation form (ReLU(scale * x + shift) in front of conv1)
             pre = (torch.ones(C, device=dev), torch.zeros(C, device=dev))
-            for _ in range(2):
-                sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1], pre=pre)
-            e0.record()
-            for _ in range(iters):
-                sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1], pre=pre)
-            e1.record()
-            torch.cuda.synchronize()
-            kp_ms = e0.elapsed_time(e1) / iters
+
+            def unit_ms(fn):
+                if not args.eager_kernel_timing:
+                    return device_ms(fn, reps=5 if n * n_units > 2000 else 10, replays=5)
+                for _ in range(2):
+                    fn()
+                e0.record()
+                for _ in range(iters):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / iters
+            k_ms = unit_ms(lambda: sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1]))
+            kp_ms = unit_ms(lambda: sb.sparse_bottleneck(bufs[0], idx, cnt, g_in, g_out, u0, bufs[1], pre=pre))
+            if n * n_units <= 2000 and thr_t is None and not args.eager_kernel_timing:
+                ms = device_ms(step)          # small problems: the step from graph replays too
             if target >= 1.0:
                 dense_ms = ms
             rows.append({"block": bo, "target": target, "active_blocks": n, "total_blocks": total,
