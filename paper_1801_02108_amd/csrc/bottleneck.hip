@@ -63,7 +63,11 @@ struct BneckParams {
     const int32_t *indices, *count;
     int cap;
     int th, tw, oh, ow;          // tile and output block extents
-    int H, W;                    // image extent (border zeroing; fused addressing)
+    int H, W;                    // input image extent (border zeroing; fused addressing)
+    int Ho, Wo;                  // output image extent (fused addressing; equal to H, W without a stride)
+    const void *ws;              // downsampling form: packed 1x1 shortcut weights C -> CO (32x32x16 operand copy at ws_off)
+    size_t ws_off;
+    const float *bs;             // ... and its bias
     sbnet_geom g_in, g_out;
     int sub_h, sub_w;
     FastDiv div_sub, div_subw;
@@ -101,12 +105,19 @@ __device__ __forceinline__ void bstore16(__amdgpu_buffer_rsrc_t r, uint32_t off,
 
 __device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v), 0); }
 
-template <int DT, int C, bool FUSED, int TS, bool PRE>
+// S, PROJ, CO: the downsampling form (Sec. 4: the units that open a stage): the 3x3 runs with stride S = 2 on the
+// (2 TS + 1)^2 input sub-tile of Fig. 3, the unit has CO output channels and its shortcut is the 1x1 convolution
+// with the same stride (PROJ), whose products P3 adds to the same accumulators as W3 t2: K is simply longer by C.
+// Its B operands are the input pixels under the output pixels, read from L2 in the MFMA layout (they passed
+// through this CU for P1 a moment ago).  8 x 8 sub-tiles only: t1 of a 33 x 33 sub-tile would not fit LDS.
+template <int DT, int C, bool FUSED, int TS, bool PRE, int S = 1, bool PROJ = false, int CO = C>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void bottleneck16_kernel(BneckParams p) {
     static_assert(TS == 16 || TS == 8, "output sub-tile side");
-    constexpr int kBT = TS + 2;                // input sub-tile side
-    constexpr int kBTPx = kBT * kBT;           // 324 or 100 pixels
+    static_assert(S == 1 || (S == 2 && TS == 8 && FUSED && PROJ && !PRE), "the strided form: 8 x 8 sub-tiles, fused, projected");
+    static_assert(PROJ || CO == C, "the identity shortcut keeps the channel count");
+    constexpr int kBT = TS * S + 3 - S;        // input sub-tile side: TS + 2, or 2 TS + 1 with the stride
+    constexpr int kBTPx = kBT * kBT;           // 324 or 100 pixels (289 with the stride)
     constexpr int LOGTS = TS == 16 ? 4 : 3;
     constexpr int RPF = 32 / TS;               // sub-tile rows covered by one 32-pixel MFMA block (2 or 4)
     constexpr int NPB = TS * TS / 32;          // 32-pixel blocks of the output sub-tile (8 or 2)
@@ -116,7 +127,7 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int W2R = W2D < 12 ? W2D : 12;   // ... and ring slots holding them
     constexpr int K1 = C / 16;                 // k-steps of conv1
     constexpr int NCH = (C + 63) / 64;         // 64-channel chunks of the input tile (the last may be half empty)
-    constexpr int NB3 = C / 32;                // 32-channel output blocks of conv3
+    constexpr int NB3 = CO / 32;               // 32-channel output blocks of conv3
     constexpr int NBW = (NB3 + 3) / 4;         // ... per wave
     constexpr int NBLK1 = (kBTPx + 31) / 32;   // 11 pixel blocks in P1
     constexpr int NBPW1 = (NBLK1 + 3) / 4;     // ... per wave
@@ -130,7 +141,7 @@ void bottleneck16_kernel(BneckParams p) {
     __shared__ __align__(16) unsigned char xs[kBTPx * kPS];      // one 64-channel chunk of x in P1, t2 afterwards
     __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];             // conv1 weights, 32x32x16 operand order
     __shared__ __align__(16) uint4 w3s[NB3 * 4 * 64];            // conv3 weights, [block of 32 outputs][k-step][lane]
-    __shared__ __align__(16) float bias_s[2 * kCm + C];          // b1 | b2 | b3: accumulators start from these
+    __shared__ __align__(16) float bias_s[2 * kCm + CO];         // b1 | b2 | b3 (+ bs): accumulators start from these
     float *pre_s = nullptr;                                      // pre-activation scale | shift
     if constexpr (PRE) {
         __shared__ __align__(16) float pre_store[2 * C];
@@ -186,16 +197,17 @@ void bottleneck16_kernel(BneckParams p) {
     const uint32_t in_bytes = (uint32_t)(FUSED ? p.H : p.th) * row_stride * 2u;
     auto geometry_of = [&](const BItem &c) __attribute__((always_inline)) {
         TileGeo t;
-        t.ty0 = c.si * TS;
+        t.ty0 = c.si * TS;                                                    // sub-tile origin inside the OUTPUT block
         t.tx0 = c.sj * TS;
-        const int gy0 = p.g_in.boffset_h + c.by * p.g_in.bstride_h + t.ty0;   // sub-tile origin in image coordinates
-        const int gx0 = p.g_in.boffset_w + c.bx * p.g_in.bstride_w + t.tx0;
+        const int iy0 = t.ty0 * S, ix0 = t.tx0 * S;                           // ... and inside the input tile
+        const int gy0 = p.g_in.boffset_h + c.by * p.g_in.bstride_h + iy0;     // sub-tile origin in image coordinates
+        const int gx0 = p.g_in.boffset_w + c.bx * p.g_in.bstride_w + ix0;
         t.rlo = max(0, -gy0);
-        t.rhi = min(min(kBT, p.th - t.ty0), p.H - gy0);
+        t.rhi = min(min(kBT, p.th - iy0), p.H - gy0);
         t.clo = max(0, -gx0);
-        t.chi = min(min(kBT, p.tw - t.tx0), p.W - gx0);
+        t.chi = min(min(kBT, p.tw - ix0), p.W - gx0);
         const uint16_t *base = FUSED ? in + (long long)c.n * p.H * row_stride : in + (long long)c.b * p.th * row_stride;
-        const int y0 = FUSED ? gy0 : t.ty0, x0 = FUSED ? gx0 : t.tx0;
+        const int y0 = FUSED ? gy0 : iy0, x0 = FUSED ? gx0 : ix0;
         t.xrs = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)in_bytes, (int)kBufWord3B);
         t.xorg = (uint32_t)(y0 * row_stride + x0 * C) * 2u;
         t.gx0 = x0;
@@ -285,8 +297,9 @@ void bottleneck16_kernel(BneckParams p) {
         for (int k = 0; k < N1; ++k) w1s[threadIdx.x + k * 256] = t1v[k];
 #pragma unroll
         for (int k = 0; k < N3; ++k) w3s[threadIdx.x + k * 256] = t3v[k];
-        for (int i = threadIdx.x; i < 2 * kCm + C; i += 256)
-            bias_s[i] = i < kCm ? (i < p.Cm ? p.b1[i] : 0.f) : i < 2 * kCm ? (i - kCm < p.Cm ? p.b2[i - kCm] : 0.f) : p.b3[i - 2 * kCm];
+        for (int i = threadIdx.x; i < 2 * kCm + CO; i += 256)
+            bias_s[i] = i < kCm ? (i < p.Cm ? p.b1[i] : 0.f) : i < 2 * kCm ? (i - kCm < p.Cm ? p.b2[i - kCm] : 0.f)
+                                : p.b3[i - 2 * kCm] + (PROJ ? p.bs[i - 2 * kCm] : 0.f);
         if constexpr (PRE)
             for (int i = threadIdx.x; i < 2 * C; i += 256) pre_s[i] = i < C ? p.pre_scale[i] : p.pre_shift[i - C];
     }
@@ -319,7 +332,7 @@ void bottleneck16_kernel(BneckParams p) {
         // ---- where this tile's results go and, for the fused form, where the residual x comes from.  Layout of
         //      P3's memory accesses: instruction i of a pass (64 pixels = pixel blocks 2bp, 2bp+1) covers pixels
         //      i*PPI + lane/CPP of the pass, 16-byte piece lane%CPP of the wave's channels.
-        const int out_w = FUSED ? p.W : p.ow;
+        const int out_w = FUSED ? p.Wo : p.ow;
         __amdgpu_buffer_rsrc_t yrs;
         uint32_t yorg;                   // byte offset of the sub-tile's output pixel (0, 0), first channel of the wave
         int ox;                          // image column of sub-tile column 0 (on tiles: block column)
@@ -329,15 +342,15 @@ void bottleneck16_kernel(BneckParams p) {
             if (FUSED) {
                 oy = p.g_out.boffset_h + cur.by * p.g_out.bstride_h + geo.ty0;
                 ox = p.g_out.boffset_w + cur.bx * p.g_out.bstride_w + geo.tx0;
-                ybase += (long long)cur.n * p.H * p.W * C;
+                ybase += (long long)cur.n * p.Ho * p.Wo * CO;
             } else {
                 oy = geo.ty0;
                 ox = geo.tx0;
-                ybase += (long long)cur.b * p.oh * p.ow * C;
+                ybase += (long long)cur.b * p.oh * p.ow * CO;
             }
-            const uint32_t ybytes = (uint32_t)(FUSED ? p.H : p.oh) * out_w * C * 2u;
+            const uint32_t ybytes = (uint32_t)(FUSED ? p.Ho : p.oh) * out_w * CO * 2u;
             yrs = __builtin_amdgcn_make_buffer_rsrc((void *)ybase, 0, (int)ybytes, (int)kBufWord3B);
-            yorg = (uint32_t)((oy * out_w + ox) * C + wave * NBW * 32) * 2u;
+            yorg = (uint32_t)((oy * out_w + ox) * CO + wave * NBW * 32) * 2u;
         }
         // Rows below the image are outside the descriptors by themselves; columns outside and (C = 64) the channel
         // blocks of waves without work get the out-of-range offset.
@@ -347,7 +360,7 @@ void bottleneck16_kernel(BneckParams p) {
             const int q = i * PPI + ln / CPP;                      // pixel of the pass
             const int row = RPF * (2 * bp + (q >> 5)) + ((q & 31) >> LOGTS), col = q & (TS - 1);
             const bool ok = wave * NBW < NB3 && (uint32_t)(ox + col) < (uint32_t)out_w;
-            return ok ? yorg + (uint32_t)((row * out_w + col) * C) * 2u + (ln % CPP) * 16 : kOutOfRangeB;
+            return ok ? yorg + (uint32_t)((row * out_w + col) * CO) * 2u + (ln % CPP) * 16 : kOutOfRangeB;
         };
         // residual x of the block (fused form), in that layout.  It is requested in the middle of P1, when half of the
         // tile's chunks have just come through L2 and the other half is about to: each of its cache lines then crosses
@@ -356,7 +369,7 @@ void bottleneck16_kernel(BneckParams p) {
         constexpr int NPASS = NPB / 2;
         uint4 rres[NPASS][NI];
         auto fetch_residual = [&](int bp0, int bp1) __attribute__((always_inline)) {
-            if (!FUSED) return;
+            if (!FUSED || PROJ) return;
 #pragma unroll
             for (int bp = bp0; bp < bp1; ++bp)
 #pragma unroll
@@ -447,8 +460,9 @@ void bottleneck16_kernel(BneckParams p) {
             // reads fragment RPF*P + r.
             f32x16b acc[NP];
             const f32x16b bias2 = load_bias16(kCm + cm0);
-            const unsigned char *L = t1s + ((rh * (TS / 2) + prow) * kBT + pcol) * kPS + g * 16;
+            const unsigned char *L = t1s + ((rh * (TS / 2) + prow) * S * kBT + pcol * S) * kPS + g * 16;
             uint4 xf[2][NF];
+            static_assert(S == 1 || NF == 3, "with a stride a pixel block's three tap rows are three fragments of their own");
 #pragma unroll
             for (int j = 0; j < NF; ++j) xf[0][j] = *(const uint4 *)(L + (j * kBT) * kPS);
             __builtin_amdgcn_sched_barrier(0);
@@ -523,6 +537,42 @@ void bottleneck16_kernel(BneckParams p) {
                     for (int u = 0; u < 2; ++u)
 #pragma unroll
                         for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(w3r[ks][j], tf[u][ks], acc[u][j]);
+                if constexpr (PROJ) {
+                    // the shortcut: + Ws x at the input pixels under the pass's 64 output pixels, K = C in steps of 16,
+                    // four k-steps of loads in flight (operands straight from L2, 16 bytes per lane)
+                    const uint4 *wsg = (const uint4 *)p.ws + p.ws_off;            // [ng][ks][nb][lane]
+                    uint32_t xoff[2];
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const int q = (2 * bp + u) * 32 + m;                          // output pixel of the sub-tile
+                        const int orow = q >> LOGTS, ocol = q & (TS - 1);
+                        xoff[u] = geo.xorg + (uint32_t)((orow * S + 1) * row_stride + (ocol * S + 1) * C + g * 8) * 2u;
+                    }
+                    constexpr int KB = 4;
+#pragma unroll
+                    for (int k0 = 0; k0 < K1; k0 += KB) {
+                        uint4 xb[KB][2], wa[KB][NBW];
+#pragma unroll
+                        for (int kk = 0; kk < KB; ++kk) {
+                            if (k0 + kk >= K1) continue;
+#pragma unroll
+                            for (int u = 0; u < 2; ++u) xb[kk][u] = bload16(geo.xrs, xoff[u] + (uint32_t)(k0 + kk) * 32u);
+#pragma unroll
+                            for (int j = 0; j < NBW; ++j) {
+                                const int nbg = min(wave * NBW + j, NB3 - 1);
+                                wa[kk][j] = wsg[(((size_t)(nbg >> 1) * K1 + (k0 + kk)) * 2 + (nbg & 1)) * 64 + lane];
+                            }
+                        }
+#pragma unroll
+                        for (int kk = 0; kk < KB; ++kk) {
+                            if (k0 + kk >= K1) continue;
+#pragma unroll
+                            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                                for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(wa[kk][j], xb[kk][u], acc[u][j]);
+                        }
+                    }
+                }
                 // MFMA layout -> LDS: lane (g, m) holds channels j*32 + g*16 .. + 16 of pixel u*32 + m
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
@@ -539,7 +589,7 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
                 for (int i = 0; i < NI; ++i) {
                     uint4 v = *(const uint4 *)(ost + (i * PPI + lane / CPP) * OPS + (lane % CPP) * 16);
-                    if (FUSED) {
+                    if (FUSED && !PROJ) {
                         const uint4 rv = rres[bp][i];
                         v.x = pack2<DT>(unpack_lo<DT>(v.x) + unpack_lo<DT>(rv.x), unpack_hi<DT>(v.x) + unpack_hi<DT>(rv.x));
                         v.y = pack2<DT>(unpack_lo<DT>(v.y) + unpack_lo<DT>(rv.y), unpack_hi<DT>(v.y) + unpack_hi<DT>(rv.y));
@@ -629,7 +679,7 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
     p.Cm = Cm; p.km = (Cm + 31) / 32 * 2;
     p.indices = indices; p.count = count; p.cap = cap;
     p.th = g_in->bsize_h; p.tw = g_in->bsize_w; p.oh = g_out->bsize_h; p.ow = g_out->bsize_w;
-    p.H = H; p.W = W;
+    p.H = H; p.W = W; p.Ho = H; p.Wo = W;
     p.g_in = *g_in; p.g_out = *g_out;
     // Sub-tile side: 16 x 16 where the block allows it, or 8 x 8: four times the work items at 1.56x the halo overhead
     // and a shorter latency chain each, which wins where the larger items leave most CUs idle or the last round of
@@ -663,6 +713,65 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
     }
     return SBNET_OK;
 }
+
+// The downsampling unit in one launch: stride 2, projected shortcut, 8 x 8 output sub-tiles.  Returns
+// SBNET_EUNSUPPORTED for shapes it does not serve (the caller then composes the unit from single calls).
+namespace sbnet {
+
+template <int DT>
+static sbnet_status launch_down(int C, int CO, const BneckParams &p, dim3 grid, hipStream_t s, const char *who) {
+#define SBNET_DOWN(CI, CC) \
+    if (C == CI && CO == CC) { hipLaunchKernelGGL((bottleneck16_kernel<DT, CI, true, 8, false, 2, true, CC>), grid, dim3(256), 0, s, p); return launch_status(who); }
+    SBNET_DOWN(64, 96)
+    SBNET_DOWN(96, 192)
+    SBNET_DOWN(192, 256)
+    SBNET_DOWN(64, 128)
+    SBNET_DOWN(128, 256)
+#undef SBNET_DOWN
+    return fail(SBNET_EUNSUPPORTED, "%s: no one-launch downsampling unit for %d -> %d channels", who, C, CO);
+}
+
+sbnet_status unit_down_try(const char *who, const void *x, sbnet_dtype dt, int N, int H, int W, int C, int Cm, int CO,
+                           const int32_t *indices, const int32_t *count, int cap, const sbnet_geom *g_in,
+                           const sbnet_geom *g_out, const void *w1, const float *b1, const void *w2, const float *b2,
+                           const void *w3, const float *b3, const void *ws, const float *bs, void *y, int Ho, int Wo,
+                           void *stream) {
+    // (the caller has checked pointers, sizes, that the geometries are those of a 3x3 with stride 2, and overlap)
+    if (dt != SBNET_BF16 && dt != SBNET_F16) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be bf16 or f16", who);
+    if (Cm > kCm || Cm % 8 || g_out->bsize_h % 8 || g_out->bsize_w % 8)
+        return fail(SBNET_EUNSUPPORTED, "%s: width a multiple of 8 up to 64 and block sides multiples of 8", who);
+    const bool pair = (C == 64 && CO == 96) || (C == 96 && CO == 192) || (C == 192 && CO == 256) || (C == 64 && CO == 128) ||
+                      (C == 128 && CO == 256);
+    if (!pair) return fail(SBNET_EUNSUPPORTED, "%s: no one-launch downsampling unit for %d -> %d channels", who, C, CO);
+    if (((uintptr_t)x | (uintptr_t)y | (uintptr_t)w1 | (uintptr_t)w2 | (uintptr_t)w3 | (uintptr_t)ws) & 15)
+        return fail(SBNET_EUNSUPPORTED, "%s: pointers not 16-byte aligned", who);
+    if ((long long)H * W * C >= (1LL << 30) || (long long)Ho * Wo * CO >= (1LL << 30))
+        return fail(SBNET_EUNSUPPORTED, "%s: a sample must stay below 2^30 elements", who);
+    const long long items = (long long)cap * (g_out->bsize_h / 8) * (g_out->bsize_w / 8);
+    if (items >= (1LL << 31)) return fail(SBNET_EUNSUPPORTED, "%s: too many work items", who);
+
+    BneckParams p = {};
+    p.in = x; p.out = y;
+    p.w1 = w1; p.w2 = w2; p.w3 = w3; p.ws = ws;
+    p.w1_off = w32_off(1, C, Cm); p.w2_off = w32_off(9, Cm, Cm); p.w3_off = w32_off(1, Cm, CO); p.ws_off = w32_off(1, C, CO);
+    p.b1 = b1; p.b2 = b2; p.b3 = b3; p.bs = bs;
+    p.Cm = Cm; p.km = (Cm + 31) / 32 * 2;
+    p.indices = indices; p.count = count; p.cap = cap;
+    p.th = g_in->bsize_h; p.tw = g_in->bsize_w; p.oh = g_out->bsize_h; p.ow = g_out->bsize_w;
+    p.H = H; p.W = W; p.Ho = Ho; p.Wo = Wo;
+    p.g_in = *g_in; p.g_out = *g_out;
+    p.per16 = 0; p.per8 = (p.oh / 8) * (p.ow / 8); p.cost8 = 8; p.want16 = 0;
+    p.sub_h = p.oh / 8; p.sub_w = p.ow / 8;
+    p.div_sub = make_fastdiv((uint32_t)p.sub_h * p.sub_w);
+    p.div_subw = make_fastdiv((uint32_t)p.sub_w);
+    long long gx = (items + 7) / 8 * 8;
+    if (gx > 256) gx = 256;
+    dim3 grid((unsigned)gx);
+    return dt == SBNET_BF16 ? launch_down<SBNET_BF16>(C, CO, p, grid, (hipStream_t)stream, who)
+                            : launch_down<SBNET_F16>(C, CO, p, grid, (hipStream_t)stream, who);
+}
+
+}  // namespace sbnet
 
 extern "C" sbnet_status sbnet_bottleneck_on_tiles(const void *tiles_in, sbnet_dtype dtype, int H, int W, int C, int Cm,
                                                   const int32_t *indices, const int32_t *count, int cap,

@@ -44,6 +44,14 @@ sbnet_status mask_to_flags(const char *who, const void *mask, sbnet_dtype mdt, i
 sbnet_status flags_to_indices(const char *who, const uint8_t *flags, int N, const sbnet_geom *g, int32_t *indices,
                               int32_t *count, int cap, hipStream_t s);
 
+// bottleneck.hip: the downsampling residual unit (stride 2, projected shortcut) in one launch, for the shapes it
+// serves; SBNET_EUNSUPPORTED otherwise.  Arguments as sbnet_sparse_unit, already validated by it.
+sbnet_status unit_down_try(const char *who, const void *x, sbnet_dtype dt, int N, int H, int W, int C, int Cm, int CO,
+                           const int32_t *indices, const int32_t *count, int cap, const sbnet_geom *g_in,
+                           const sbnet_geom *g_out, const void *w1, const float *b1, const void *w2, const float *b2,
+                           const void *w3, const float *b3, const void *ws, const float *bs, void *y, int Ho, int Wo,
+                           void *stream);
+
 // do the byte ranges [a, a + a_bytes) and [b, b + b_bytes) share a byte?
 inline bool ranges_overlap(const void *a, size_t a_bytes, const void *b, size_t b_bytes) {
     const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;

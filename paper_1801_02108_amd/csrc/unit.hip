@@ -5,14 +5,16 @@
 //     y = shortcut(x) + W3 ReLU(W2 *_s zero_outside(ReLU(W1 x + b1)) + b2) + b3,
 // shortcut = a 1x1 convolution with the unit's stride (ws, bs) or the identity; other pixels of y stay.
 //
-// Shapes the one-kernel unit serves (stride 1, identity shortcut, C in {64, 96, 128, 192, 256}, width up to 64)
-// go to it.  Everything else runs as a sequence of the library's own calls on tile stacks in the caller's workspace,
+// Shapes the one-kernel unit serves go to it: stride 1 with the identity shortcut, C in {64, 96, 128, 192, 256}, and
+// stride 2 with a projected shortcut, Cin -> Cout in {64->96, 96->192, 192->256, 64->128, 128->256}; width a multiple
+// of 8 up to 64, block sides multiples of 8, bf16 / f16.  Everything else runs as a sequence of the library's own calls on tile stacks in the caller's workspace,
 // no kernel lives here:
 //     gather (input tile) -> 1x1 + ReLU -> zero outside the image -> 3x3 with stride + ReLU -> 1x1
 //     shortcut:  projection: the fused 1x1 convolution with stride writes y's active blocks;
 //                identity:   the active blocks of x are copied to y (skipped when y is x);
 //     scatter-add of the branch onto y.
-// The sum therefore rounds the shortcut to the storage type before the branch is added (two roundings).
+// The sum therefore rounds the shortcut to the storage type before the branch is added (two roundings; the one-kernel
+// forms add in fp32 and round once).
 #include "common.h"
 
 using namespace sbnet;
@@ -76,6 +78,13 @@ extern "C" sbnet_status sbnet_sparse_unit(const void *x, sbnet_dtype dtype, int 
     if (!w_shortcut && x != y) {
         sbnet_status st = sbnet_sparse_bottleneck(x, dtype, N, H, W, Cin, Cm, indices, count, cap, g_in, g_out, w1, b1, w2, b2,
                                                   w3, b3, y, stream);
+        if (st != SBNET_EUNSUPPORTED) return st;
+    }
+
+    // ... and the one-kernel downsampling unit
+    if (w_shortcut && stride == 2) {
+        sbnet_status st = unit_down_try(who, x, dtype, N, H, W, Cin, Cm, Cout, indices, count, cap, g_in, g_out, w1, b1, w2, b2,
+                                        w3, b3, w_shortcut, b_shortcut, y, H_out, W_out, stream);
         if (st != SBNET_EUNSUPPORTED) return st;
     }
 

@@ -268,7 +268,12 @@ GENERAL_UNIT_CASES = [
     (2, 40, 56, 96, 24, 96, 1, 16, False, "bf16"),     # a shape the one-kernel unit takes: routed to it
     (1, 32, 48, 64, 16, 128, 1, 16, True, "bf16"),     # stride 1 with a projection (a change of width without downsampling)
     (1, 35, 29, 24, 8, 40, 2, 4, True, "bf16"),        # small channel counts, 4 x 4 blocks
+    (2, 258, 250, 64, 24, 96, 2, 8, True, "bf16"),     # more 8 x 8 items than workgroups: every workgroup loops over tiles
+    (1, 100, 90, 128, 64, 256, 2, 24, True, "f16"),    # 3 x 3 sub-tiles per block, blocks over the edge, f16
+    (1, 70, 70, 64, 32, 128, 2, 16, True, "f16"),
 ]
+# shapes the one-launch downsampling unit serves (it needs no workspace: called without one below)
+ONE_LAUNCH_DOWN = {(64, 96), (96, 192), (192, 256), (64, 128), (128, 256)}
 
 
 @pytest.mark.parametrize("N,H,W,Cin,Cm,Cout,stride,bo,proj,dtype", GENERAL_UNIT_CASES)
@@ -294,7 +299,9 @@ def test_sparse_unit_any_width_stride_and_shortcut(N, H, W, Cin, Cm, Cout, strid
         assert sb.read_count(d_cnt, d_idx.shape[0]) == len(idx)
         y0 = gen.activations(r, (N, Ho, Wo, Cout), dtype)
         y = to_dev(y0, dtype)
-        sb.sparse_unit(dx, d_idx, d_cnt, g_in, g_out, dws, y, stride=stride, shortcut=dsc)
+        one_launch = stride == 2 and proj and (Cin, Cout) in ONE_LAUNCH_DOWN and Cm <= 64 and bo % 8 == 0
+        none = torch.empty((0,), dtype=torch.uint8, device="cuda")
+        sb.sparse_unit(dx, d_idx, d_cnt, g_in, g_out, dws, y, stride=stride, shortcut=dsc, workspace=none if one_launch else None)
         got = to_host(y)
         ref = orc.sparse_unit_tiled(x, idx, og_in, og_out, w1, b1, w2, b2, w3, b3, y0, stride=stride, shortcut=sc)
         bm = orc.block_mask(idx, og_out, N, Ho, Wo)
