@@ -123,7 +123,7 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NPB = TS * TS / 32;          // 32-pixel blocks of the output sub-tile (8 or 2)
     constexpr int NP = NPB / 2;                // ... per wave in P2: waves split the rows in two halves (4 or 1)
     constexpr int NF = RPF * (NP - 1) + 3;     // LDS fragments per P2 stage (9 or 3)
-    constexpr int W2D = TS == 16 ? 7 : 12;     // stages of conv2 weights requested ahead
+    constexpr int W2D = TS == 16 ? (C > 128 ? 5 : 7) : 12;   // stages of conv2 weights requested ahead (registers permitting)
     constexpr int W2R = W2D < 12 ? W2D : 12;   // ... and ring slots holding them
     constexpr int K1 = C / 16;                 // k-steps of conv1
     constexpr int NCH = (C + 63) / 64;         // 64-channel chunks of the input tile (the last may be half empty)
@@ -132,6 +132,7 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NBLK1 = (kBTPx + 31) / 32;   // 11 pixel blocks in P1
     constexpr int NBPW1 = (NBLK1 + 3) / 4;     // ... per wave
     constexpr int NVX = (kBTPx * 8 + 255) / 256;   // 16-byte staging vectors per thread and chunk
+    static_assert(NVX <= 12, "one vector of the next tile's second chunk is requested per stage of P2");
     constexpr int OPS = NBW * 64 + 16;         // LDS bytes per pixel of a wave's P3 results (+16 B pad)
     constexpr int CPP = NBW * 4;               // 16-byte pieces per pixel of those
     constexpr int PPI = 64 / CPP;              // pixels per wave instruction in the store layout
@@ -218,23 +219,25 @@ void bottleneck16_kernel(BneckParams p) {
     //      Eight neighbouring lanes read one pixel's 128 contiguous bytes, so a wave instruction touches 8 full
     //      cache lines.  Offsets are recomputed per use: keeping them would cost 2 registers per vector.
     uint4 sx0[NVX], sx1[NVX];                                             // two chunks in flight (slot 0 / slot 1)
-    auto fetch_chunk = [&](const TileGeo &t, int chunk, auto slot_tag) __attribute__((always_inline)) {
+    // one vector of a chunk (live = false: a tile that does not exist, nothing is read)
+    auto fetch_vec = [&](const TileGeo &t, int chunk, auto slot_tag, int k, bool live) __attribute__((always_inline)) {
         constexpr int slot = decltype(slot_tag)::value;
         int tid = (int)threadIdx.x;
         asm volatile("" : "+v"(tid));     // opaque: otherwise the per-vector offsets are hoisted out of the tile loop and spilled
+        const int v = tid + k * 256;
+        const int px = v >> 3, c8 = v & 7;
+        const int row = px / kBT, col = px - row * kBT;
+        const uint32_t off = t.xorg + (uint32_t)(row * row_stride + col * C + c8 * 8 + chunk * 64) * 2u;
+        // rows outside the image are outside the descriptor; columns outside would wrap into the neighbouring
+        // row, so they (and the unused tail of the last vector) get the out-of-range offset: zeros either way
+        const bool ok = live && v < kBTPx * 8 && (uint32_t)(t.gx0 + col) < (uint32_t)in_w && (C % 64 == 0 || c8 * 8 + chunk * 64 < C);
+        const uint4 val = bload16(t.xrs, ok ? off : kOutOfRangeB);
+        if (slot == 0) sx0[k] = val;
+        else sx1[k] = val;
+    };
+    auto fetch_chunk = [&](const TileGeo &t, int chunk, auto slot_tag) __attribute__((always_inline)) {
 #pragma unroll
-        for (int k = 0; k < NVX; ++k) {
-            const int v = tid + k * 256;
-            const int px = v >> 3, c8 = v & 7;
-            const int row = px / kBT, col = px - row * kBT;
-            const uint32_t off = t.xorg + (uint32_t)(row * row_stride + col * C + c8 * 8 + chunk * 64) * 2u;
-            // rows outside the image are outside the descriptor; columns outside would wrap into the neighbouring
-            // row, so they (and the unused tail of the last vector) get the out-of-range offset: zeros either way
-            const bool ok = v < kBTPx * 8 && (uint32_t)(t.gx0 + col) < (uint32_t)in_w && (C % 64 == 0 || c8 * 8 + chunk * 64 < C);
-            const uint4 val = bload16(t.xrs, ok ? off : kOutOfRangeB);
-            if (slot == 0) sx0[k] = val;
-            else sx1[k] = val;
-        }
+        for (int k = 0; k < NVX; ++k) fetch_vec(t, chunk, slot_tag, k, true);
         __builtin_amdgcn_sched_barrier(0);                                // all loads issued here, in this order
     };
     // With a pre-activation the chunk is transformed on its way to LDS: conv1 reads ReLU(scale * x + shift), the
@@ -354,28 +357,68 @@ void bottleneck16_kernel(BneckParams p) {
         }
         // Rows below the image are outside the descriptors by themselves; columns outside and (C = 64) the channel
         // blocks of waves without work get the out-of-range offset.
+        // Pixel q = i * PPI + lane / CPP of the pass: its row is a constant of (bp, i) plus (8-pixel sub-tiles with
+        // 16 pixels per instruction) a lane part, its column one of at most two lane parts.  The lane parts are kept
+        // (one or two registers), the row constant is added per access from a scalar.
+        constexpr int NCOLV = (TS == 16 && PPI == 8) ? 2 : 1;
+        uint32_t lane_off[NCOLV];
+        const uint32_t out_row_bytes = (uint32_t)(out_w * CO) * 2u;
+        {
+            const int l = lane / CPP;
+            const int rowl = (TS == 8 && PPI == 16) ? (l >> 3) : 0;
+#pragma unroll
+            for (int v = 0; v < NCOLV; ++v) {
+                const int col = NCOLV == 2 ? v * 8 + l : (l & (TS - 1));
+                const bool ok = wave * NBW < NB3 && (uint32_t)(ox + col) < (uint32_t)out_w;
+                lane_off[v] = ok ? yorg + (uint32_t)((rowl * out_w + col) * CO) * 2u + (lane % CPP) * 16 : kOutOfRangeB;
+            }
+        }
         auto out_offset = [&](int bp, int i) __attribute__((always_inline)) {
-            int ln = lane;
-            asm volatile("" : "+v"(ln));     // opaque: recomputed at every use; kept, the 4 * NI offsets would be spilled
-            const int q = i * PPI + ln / CPP;                      // pixel of the pass
-            const int row = RPF * (2 * bp + (q >> 5)) + ((q & 31) >> LOGTS), col = q & (TS - 1);
-            const bool ok = wave * NBW < NB3 && (uint32_t)(ox + col) < (uint32_t)out_w;
-            return ok ? yorg + (uint32_t)((row * out_w + col) * CO) * 2u + (ln % CPP) * 16 : kOutOfRangeB;
+            const int rowc = RPF * (2 * bp + ((i * PPI) >> 5)) + (((i * PPI) & 31) >> LOGTS);
+            // (an out-of-range lane part stays out of range: the sum is below 2^32)
+            return lane_off[NCOLV == 2 ? (i & 1) : 0] + (uint32_t)rowc * out_row_bytes;
         };
         // residual x of the block (fused form), in that layout.  It is requested in the middle of P1, when half of the
         // tile's chunks have just come through L2 and the other half is about to: each of its cache lines then crosses
         // the memory fabric once.  (Requested after P1, half of the block had been evicted again: L2 holds about
         // 3 microseconds of this kernel's traffic, P1 alone takes 7.)
         constexpr int NPASS = NPB / 2;
-        uint4 rres[NPASS][NI];
+        uint4 rres[NPASS][NI];                   // pre-activation form: x in the store layout
+        uint4 rb[NPASS][2][NBW][2];              // otherwise: x as MFMA B operands (see below)
         auto fetch_residual = [&](int bp0, int bp1) __attribute__((always_inline)) {
-            if (!FUSED || PROJ) return;
+            if (!FUSED || PROJ || !PRE) return;
 #pragma unroll
             for (int bp = bp0; bp < bp1; ++bp)
 #pragma unroll
                 for (int i = 0; i < NI; ++i) rres[bp][i] = bload16(geo.xrs, out_offset(bp, i));     // x and y have one shape
             __builtin_amdgcn_sched_barrier(0);
         };
+        // Without a pre-activation the residual never leaves the chip: the wave's output channels are (part of) one
+        // 64-channel chunk of the input, which lies in LDS for a while during P1.  The wave copies the block's pixels
+        // of it to registers then, as B operands (lane (g, m): pixel m of a block of 32, eight channels), and P3 adds
+        // them to its accumulators with two more matrix steps per block against a 0/1 matrix: the sum x + t3 is formed
+        // in fp32 and rounded once, and the vector unit, which bounds P3, has nothing to do for it.
+        constexpr bool kResidualFromLds = FUSED && !PROJ && !PRE;
+        const int rchunk = min(wave * NBW * 32 / 64, NCH - 1);                 // wave-uniform
+        auto residual_from_lds = [&]() __attribute__((always_inline)) {
+            const int roff = (wave * NBW * 32 % 64 + g * 8) * 2;
+#pragma unroll
+            for (int bp = 0; bp < NPASS; ++bp)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int q = (2 * bp + u) * 32 + m;                       // output pixel of the sub-tile
+                    const unsigned char *src = xs + (((q >> LOGTS) + 1) * kBT + (q & (TS - 1)) + 1) * kPS + roff;
+#pragma unroll
+                    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+                        for (int k2 = 0; k2 < 2; ++k2) rb[bp][u][j][k2] = *(const uint4 *)(src + (j * 32 + k2 * 16) * 2);
+                }
+        };
+
+        const uint32_t nit = it + G;                                      // the workgroup's next tile, if any
+        const bool has_next = nit < items;
+        BItem nxt = cur;
+        TileGeo ngeo = geo;
 
         // ================= P1: t1 = ReLU(W1 x + b1), zero outside the image =================
         // x passes through LDS in 64-channel chunks: coalesced global loads -> registers -> xs -> MFMA B operands.
@@ -402,10 +445,18 @@ void bottleneck16_kernel(BneckParams p) {
                 if (c == (NCH > 1 ? 1 : 0)) fetch_residual(0, NPASS);
                 if (c == NCH - 1) {
                     // the first stages of conv2's weights come from L2 while the last chunk and the t1 epilogue run;
-                    // requested only now so that no input chunk is queued behind them
+                    // requested only now so that no input chunk of this tile is queued behind them
 #pragma unroll
                     for (int st = 0; st < (W2D < 12 ? W2D : 12); ++st) fetch_w2(st);
+                    // Both staging slots are free from here on.  The next tile's first two chunks are requested a vector
+                    // at a time between the steps of the phases that follow, which keep the vector and matrix units busy
+                    // and leave the memory pipeline idle: the end of P1 (chunk 0) and P2 (chunk 1).  (Requested in one
+                    // burst, the wave stands at the loads until the memory pipeline has taken them: it accepts about
+                    // 18 bytes per clock and CU.)
+                    nxt = decode(min(nit, (uint32_t)p.cap * per_block - 1u));
+                    ngeo = geometry_of(nxt);
                 }
+                if (kResidualFromLds && c == rchunk) residual_from_lds();
                 // fragments of k-step k4+1 are read from LDS while the MFMAs of k-step k4 run
                 uint4 af[2][2], bf[2][NBPW1];
                 af[0][0] = w1s[((c * 4) * 2 + 0) * 64 + lane];
@@ -434,6 +485,9 @@ void bottleneck16_kernel(BneckParams p) {
             }
 #pragma unroll
             for (int j = 0; j < NBPW1; ++j) {
+#pragma unroll
+                for (int k = j * NVX / NBPW1; k < (j + 1) * NVX / NBPW1; ++k) fetch_vec(ngeo, 0, Slot0{}, k, has_next);
+                __builtin_amdgcn_sched_barrier(0);
                 // lanes past the last pixel were fed pixel 323's operands: they write pixel 323's values again
                 const int pi = min((wave + 4 * j) * 32 + m, kBTPx - 1);
                 const int row = pi / kBT, col = pi - row * kBT;
@@ -473,6 +527,7 @@ void bottleneck16_kernel(BneckParams p) {
                 for (int mm = 0; mm < 3 * NP; ++mm) {
                     const int r = mm / NP, P = mm % NP;
                     acc[P] = mfma32<DT>(w2s[st % W2R][r], xf[st & 1][RPF * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
+                    if (NCH > 1 && mm == 0 && st < NVX) fetch_vec(ngeo, 1, Slot1{}, st, has_next);
                     if (mm < NF && st + 1 < 12)
                         xf[(st + 1) & 1][mm] = *(const uint4 *)(L + (mm * kBT + tn) * kPS + kcn * 32);
                     if (mm == 3 * NP - 1 && st + W2D < 12) fetch_w2(st + W2D);       // into the slot this stage just freed
@@ -493,17 +548,6 @@ void bottleneck16_kernel(BneckParams p) {
         }
         __syncthreads();
 
-        // ---- the next tile's first two input chunks are requested now and land during P3
-        const uint32_t nit = it + G;
-        BItem nxt = cur;
-        TileGeo ngeo = geo;
-        if (nit < items) {
-            nxt = decode(nit);
-            ngeo = geometry_of(nxt);
-            fetch_chunk(ngeo, 0, Slot0{});
-            if (NCH > 1) fetch_chunk(ngeo, 1, Slot1{});
-        }
-
         // ================= P3: t3 = W3 t2 + b3 (+ x), two pixel blocks (64 pixels) per pass =================
         {
             uint4 w3r[4][NBW];
@@ -514,6 +558,19 @@ void bottleneck16_kernel(BneckParams p) {
                 for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];
             }
             unsigned char *ost = t1s + wave * (64 * OPS);                 // t1 is dead: the wave's private staging area
+            // 0/1 matrix that routes channel k of the residual operand to the accumulator row holding that channel
+            // (rows are permuted as the packed weights are: row rho holds channel (rho/4 % 2) * 16 + rho/8 * 4 + rho % 4)
+            uint4 ida[2];
+            if constexpr (kResidualFromLds) {
+                const int ol = ((m >> 2) & 1) * 16 + (m >> 3) * 4 + (m & 3);
+                const uint32_t one = DT == SBNET_BF16 ? 0x3F80u : 0x3C00u;
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    const int t = ol - k2 * 16 - g * 8;                       // this lane's element that is 1, if in 0..7
+                    const uint32_t w = (t & 1) ? one << 16 : one;
+                    ida[k2] = make_uint4((t >> 1) == 0 ? w : 0u, (t >> 1) == 1 ? w : 0u, (t >> 1) == 2 ? w : 0u, (t >> 1) == 3 ? w : 0u);
+                }
+            }
 #pragma unroll
             for (int bp = 0; bp < NPASS; ++bp) {
                 uint4 tf[2][4];
@@ -537,6 +594,14 @@ void bottleneck16_kernel(BneckParams p) {
                     for (int u = 0; u < 2; ++u)
 #pragma unroll
                         for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(w3r[ks][j], tf[u][ks], acc[u][j]);
+                if constexpr (kResidualFromLds) {
+#pragma unroll
+                    for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+                        for (int u = 0; u < 2; ++u)
+#pragma unroll
+                            for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(ida[k2], rb[bp][u][j][k2], acc[u][j]);
+                }
                 if constexpr (PROJ) {
                     // the shortcut: + Ws x at the input pixels under the pass's 64 output pixels, K = C in steps of 16,
                     // four k-steps of loads in flight (operands straight from L2, 16 bytes per lane)
@@ -589,7 +654,7 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
                 for (int i = 0; i < NI; ++i) {
                     uint4 v = *(const uint4 *)(ost + (i * PPI + lane / CPP) * OPS + (lane % CPP) * 16);
-                    if (FUSED && !PROJ) {
+                    if (FUSED && !PROJ && PRE) {
                         const uint4 rv = rres[bp][i];
                         v.x = pack2<DT>(unpack_lo<DT>(v.x) + unpack_lo<DT>(rv.x), unpack_hi<DT>(v.x) + unpack_hi<DT>(rv.x));
                         v.y = pack2<DT>(unpack_lo<DT>(v.y) + unpack_lo<DT>(rv.y), unpack_hi<DT>(v.y) + unpack_hi<DT>(rv.y));
