@@ -91,6 +91,11 @@ struct BItem {
 constexpr uint32_t kBufWord3B = 0x00020000u;     // raw buffer descriptor, 32-bit data format
 constexpr uint32_t kOutOfRangeB = 0x80000000u;   // offset beyond any descriptor this kernel builds
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4b;
+typedef const u32x4b __attribute__((address_space(1))) *gvec_t;    // a pointer known to be to global memory
+__device__ __forceinline__ uint4 gload16(gvec_t q) {
+    const u32x4b v = *q;
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
 __device__ __forceinline__ uint4 bload16(__amdgpu_buffer_rsrc_t r, uint32_t off) {
     const u32x4b v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
     return make_uint4(v[0], v[1], v[2], v[3]);
@@ -104,6 +109,15 @@ __device__ __forceinline__ void bstore16(__amdgpu_buffer_rsrc_t r, uint32_t off,
 }
 
 __device__ __forceinline__ int relu_bits(float v) { return max(__float_as_int(v), 0); }
+
+// ReLU of two values and their rounding to the storage type, in that word's two halves.  Rounding keeps the sign, so
+// the ReLU is taken afterwards, on both halves at once: a negative bf16 / f16 (or -0) is a negative 16-bit integer.
+typedef short short2b __attribute__((ext_vector_type(2)));
+template <int DT>
+__device__ __forceinline__ uint32_t relu_pack2(float lo, float hi) {
+    const short2b v = __builtin_bit_cast(short2b, pack2<DT>(lo, hi)), zero = {0, 0};
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(v, zero));
+}
 
 // S, PROJ, CO: the downsampling form (Sec. 4: the units that open a stage): the 3x3 runs with stride S = 2 on the
 // (2 TS + 1)^2 input sub-tile of Fig. 3, the unit has CO output channels and its shortcut is the 1x1 convolution
@@ -329,7 +343,7 @@ void bottleneck16_kernel(BneckParams p) {
         auto fetch_w2 = [&](int st) __attribute__((always_inline)) {
 #pragma unroll
             for (int r = 0; r < 3; ++r)     // (as for W3: a k-step beyond km multiplies zeros of t1)
-                w2s[st % W2R][r] = (w2p + ((r * 3 + st / 4) * p.km + min(st % 4, p.km - 1)) * 128)[(uint32_t)lane];
+                w2s[st % W2R][r] = gload16((gvec_t)w2p + ((r * 3 + st / 4) * p.km + min(st % 4, p.km - 1)) * 128 + (uint32_t)lane);
         };
 
         // ---- where this tile's results go and, for the fused form, where the residual x comes from.  Layout of
@@ -492,11 +506,12 @@ void bottleneck16_kernel(BneckParams p) {
                 const int pi = min((wave + 4 * j) * 32 + m, kBTPx - 1);
                 const int row = pi / kBT, col = pi - row * kBT;
                 const bool inside = row >= geo.rlo && row < geo.rhi && col >= geo.clo && col < geo.chi;
+                const uint32_t keep = inside ? 0xffffffffu : 0u;         // (a mask, not a select: selects became branches here)
                 uint32_t w[16];
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    w[k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc[j][0][2 * k])), __int_as_float(relu_bits(acc[j][0][2 * k + 1]))) : 0u;
-                    w[8 + k] = inside ? pack2<DT>(__int_as_float(relu_bits(acc[j][1][2 * k])), __int_as_float(relu_bits(acc[j][1][2 * k + 1]))) : 0u;
+                    w[k] = relu_pack2<DT>(acc[j][0][2 * k], acc[j][0][2 * k + 1]) & keep;
+                    w[8 + k] = relu_pack2<DT>(acc[j][1][2 * k], acc[j][1][2 * k + 1]) & keep;
                 }
                 uint4 *d = (uint4 *)(t1s + pi * kPS + g * 32);
                 d[0] = make_uint4(w[0], w[1], w[2], w[3]);
@@ -540,7 +555,7 @@ void bottleneck16_kernel(BneckParams p) {
                 uint32_t w[8];
 #pragma unroll
                 for (int k = 0; k < 8; ++k)
-                    w[k] = pack2<DT>(__int_as_float(relu_bits(acc[P][2 * k])), __int_as_float(relu_bits(acc[P][2 * k + 1])));
+                    w[k] = relu_pack2<DT>(acc[P][2 * k], acc[P][2 * k + 1]);
                 uint4 *d = (uint4 *)(xs + po * kPS + cm0 * 2);
                 d[0] = make_uint4(w[0], w[1], w[2], w[3]);
                 d[1] = make_uint4(w[4], w[5], w[6], w[7]);
