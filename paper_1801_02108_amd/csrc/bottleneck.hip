@@ -137,7 +137,7 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NPB = TS * TS / 32;          // 32-pixel blocks of the output sub-tile (8 or 2)
     constexpr int NP = NPB / 2;                // ... per wave in P2: waves split the rows in two halves (4 or 1)
     constexpr int NF = RPF * (NP - 1) + 3;     // LDS fragments per P2 stage (9 or 3)
-    constexpr int W2D = TS == 16 ? (C > 128 ? 5 : 7) : 12;   // stages of conv2 weights requested ahead (registers permitting)
+    constexpr int W2D = TS == 16 ? (C > 192 ? 4 : C > 128 ? 5 : 7) : 12;   // stages of conv2 weights requested ahead (registers permitting)
     constexpr int W2R = W2D < 12 ? W2D : 12;   // ... and ring slots holding them
     constexpr int K1 = C / 16;                 // k-steps of conv1
     constexpr int NCH = (C + 63) / 64;         // 64-channel chunks of the input tile (the last may be half empty)
@@ -458,15 +458,10 @@ void bottleneck16_kernel(BneckParams p) {
                 }
                 if (c == (NCH > 1 ? 1 : 0)) fetch_residual(0, NPASS);
                 if (c == NCH - 1) {
-                    // the first stages of conv2's weights come from L2 while the last chunk and the t1 epilogue run;
-                    // requested only now so that no input chunk of this tile is queued behind them
-#pragma unroll
-                    for (int st = 0; st < (W2D < 12 ? W2D : 12); ++st) fetch_w2(st);
-                    // Both staging slots are free from here on.  The next tile's first two chunks are requested a vector
-                    // at a time between the steps of the phases that follow, which keep the vector and matrix units busy
-                    // and leave the memory pipeline idle: the end of P1 (chunk 0) and P2 (chunk 1).  (Requested in one
-                    // burst, the wave stands at the loads until the memory pipeline has taken them: it accepts about
-                    // 18 bytes per clock and CU.)
+                    // Both staging slots are free from here on.  The next tile's first two chunks are requested a few
+                    // vectors at a time between the steps of the phases that follow and leave the memory pipeline idle:
+                    // the end of P1 (chunk 0) and P2 (chunk 1, one vector per stage).  Measured: a load costs the wave
+                    // about 100 clocks there, 450 among the stores of P3, and 200 in one burst of 22.
                     nxt = decode(min(nit, (uint32_t)p.cap * per_block - 1u));
                     ngeo = geometry_of(nxt);
                 }
@@ -497,6 +492,10 @@ void bottleneck16_kernel(BneckParams p) {
                 }
                 if (c + 1 < NCH) __syncthreads();                        // everyone done with xs before the next chunk
             }
+            // the first stages of conv2's weights come from L2 while t1 is written (requested only now: no input chunk of
+            // this tile is queued behind them, and their registers are not held through the last chunk's matrix steps)
+#pragma unroll
+            for (int st = 0; st < (W2D < 12 ? W2D : 12); ++st) fetch_w2(st);
 #pragma unroll
             for (int j = 0; j < NBPW1; ++j) {
 #pragma unroll
@@ -573,6 +572,32 @@ void bottleneck16_kernel(BneckParams p) {
                 for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];
             }
             unsigned char *ost = t1s + wave * (64 * OPS);                 // t1 is dead: the wave's private staging area
+            // P3 is bound by LDS traffic, and accumulators that start from the bias read it from LDS in every pass (16
+            // of a pass's 40 LDS instructions; kept in registers it would take 32 of them).  The bias is added by the
+            // matrix unit instead: split into three bf16 / f16 pieces (b = p0 + p1 + p2 exactly for bf16: 3 x 8 bits
+            // cover fp32's 24; f16 drops what lies below its smallest number, under 1e-7), as columns 0..2 of an A
+            // operand whose B operand is all ones in those rows: one more matrix step per block and pass, no LDS.
+            uint4 biasA[NBW], onesB;
+            {
+                const int ol = ((m >> 2) & 1) * 16 + (m >> 3) * 4 + (m & 3);      // channel of A row m within its block
+                const uint32_t one = DT == SBNET_BF16 ? 0x3F80u : 0x3C00u;
+                onesB = g == 0 ? make_uint4(one | one << 16, one, 0u, 0u) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+                for (int j = 0; j < NBW; ++j) {
+                    const float b = bias_s[2 * kCm + min(wave * NBW + j, NB3 - 1) * 32 + ol];
+                    const uint32_t w0 = pack2<DT>(b, 0.f);
+                    const float r1 = b - unpack_lo<DT>(w0);
+                    const uint32_t w1 = pack2<DT>(r1, 0.f);
+                    const float r2 = r1 - unpack_lo<DT>(w1);
+                    const uint32_t w2 = pack2<DT>(r2, 0.f);
+                    biasA[j] = g == 0 ? make_uint4((w0 & 0xffffu) | w1 << 16, w2 & 0xffffu, 0u, 0u) : make_uint4(0u, 0u, 0u, 0u);
+                }
+            }
+            const f32x16b zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            // Blocks of 32 pixels per pass: two for waves with one block of channels (two independent chains of matrix
+            // steps), one for waves with two (half the accumulators and operands: registers are short in P3)
+            constexpr int UB = NBW >= 2 ? 1 : 2;
+            static_assert(NI % 2 == 0, "a pass's store instructions split between its two pixel blocks");
             // 0/1 matrix that routes channel k of the residual operand to the accumulator row holding that channel
             // (rows are permuted as the packed weights are: row rho holds channel (rho/4 % 2) * 16 + rho/8 * 4 + rho % 4)
             uint4 ida[2];
@@ -587,33 +612,31 @@ void bottleneck16_kernel(BneckParams p) {
                 }
             }
 #pragma unroll
-            for (int bp = 0; bp < NPASS; ++bp) {
+            for (int bp = 0; bp < NPASS; ++bp)
+#pragma unroll
+            for (int u0 = 0; u0 < 2; u0 += UB) {
                 uint4 tf[2][4];
 #pragma unroll
-                for (int u = 0; u < 2; ++u)
+                for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks)
                         tf[u][ks] = *(const uint4 *)(xs + ((2 * bp + u) * 32 + m) * kPS + ks * 32 + g * 16);
-                f32x16b acc[2][NBW];     // start from the bias (re-read from LDS per pass: holding it would cost 32 registers)
+                f32x16b acc[2][NBW];
 #pragma unroll
-                for (int u = 0; u < 2; ++u)
+                for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
-                    for (int j = 0; j < NBW; ++j) {
-                        int bi = 2 * kCm + min(wave * NBW + j, NB3 - 1) * 32 + g * 16;
-                        asm volatile("" : "+v"(bi));                      // opaque: one read per use, not one copy kept
-                        acc[u][j] = load_bias16(bi);
-                    }
+                    for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(biasA[j], onesB, zero16);
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-                    for (int u = 0; u < 2; ++u)
+                    for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
                         for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(w3r[ks][j], tf[u][ks], acc[u][j]);
                 if constexpr (kResidualFromLds) {
 #pragma unroll
                     for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-                        for (int u = 0; u < 2; ++u)
+                        for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
                             for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(ida[k2], rb[bp][u][j][k2], acc[u][j]);
                 }
@@ -623,7 +646,7 @@ void bottleneck16_kernel(BneckParams p) {
                     const uint4 *wsg = (const uint4 *)p.ws + p.ws_off;            // [ng][ks][nb][lane]
                     uint32_t xoff[2];
 #pragma unroll
-                    for (int u = 0; u < 2; ++u) {
+                    for (int u = u0; u < u0 + UB; ++u) {
                         const int q = (2 * bp + u) * 32 + m;                          // output pixel of the sub-tile
                         const int orow = q >> LOGTS, ocol = q & (TS - 1);
                         xoff[u] = geo.xorg + (uint32_t)((orow * S + 1) * row_stride + (ocol * S + 1) * C + g * 8) * 2u;
@@ -636,7 +659,7 @@ void bottleneck16_kernel(BneckParams p) {
                         for (int kk = 0; kk < KB; ++kk) {
                             if (k0 + kk >= K1) continue;
 #pragma unroll
-                            for (int u = 0; u < 2; ++u) xb[kk][u] = bload16(geo.xrs, xoff[u] + (uint32_t)(k0 + kk) * 32u);
+                            for (int u = u0; u < u0 + UB; ++u) xb[kk][u] = bload16(geo.xrs, xoff[u] + (uint32_t)(k0 + kk) * 32u);
 #pragma unroll
                             for (int j = 0; j < NBW; ++j) {
                                 const int nbg = min(wave * NBW + j, NB3 - 1);
@@ -647,7 +670,7 @@ void bottleneck16_kernel(BneckParams p) {
                         for (int kk = 0; kk < KB; ++kk) {
                             if (k0 + kk >= K1) continue;
 #pragma unroll
-                            for (int u = 0; u < 2; ++u)
+                            for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
                                 for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(wa[kk][j], xb[kk][u], acc[u][j]);
                         }
@@ -655,7 +678,7 @@ void bottleneck16_kernel(BneckParams p) {
                 }
                 // MFMA layout -> LDS: lane (g, m) holds channels j*32 + g*16 .. + 16 of pixel u*32 + m
 #pragma unroll
-                for (int u = 0; u < 2; ++u)
+                for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
                     for (int j = 0; j < NBW; ++j) {
                         uint32_t w[8];
@@ -667,7 +690,7 @@ void bottleneck16_kernel(BneckParams p) {
                     }
                 // LDS -> store layout (LDS serves one wave's accesses in order: no wait between the two), add, store
 #pragma unroll
-                for (int i = 0; i < NI; ++i) {
+                for (int i = u0 * (NI / 2); i < (u0 + UB) * (NI / 2); ++i) {
                     uint4 v = *(const uint4 *)(ost + (i * PPI + lane / CPP) * OPS + (lane % CPP) * 16);
                     if (FUSED && !PROJ && PRE) {
                         const uint4 rv = rres[bp][i];
