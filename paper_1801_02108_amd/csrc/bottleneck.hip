@@ -137,7 +137,7 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NPB = TS * TS / 32;          // 32-pixel blocks of the output sub-tile (8 or 2)
     constexpr int NP = NPB / 2;                // ... per wave in P2: waves split the rows in two halves (4 or 1)
     constexpr int NF = RPF * (NP - 1) + 3;     // LDS fragments per P2 stage (9 or 3)
-    constexpr int W2D = TS == 16 ? (C > 192 ? 4 : C > 128 ? 5 : 7) : 12;   // stages of conv2 weights requested ahead (registers permitting)
+    constexpr int W2D = TS == 16 ? (C > 128 ? 4 : 7) : 12;   // stages of conv2 weights requested ahead (registers permitting)
     constexpr int W2R = W2D < 12 ? W2D : 12;   // ... and ring slots holding them
     constexpr int K1 = C / 16;                 // k-steps of conv1
     constexpr int NCH = (C + 63) / 64;         // 64-channel chunks of the input tile (the last may be half empty)
@@ -233,25 +233,41 @@ void bottleneck16_kernel(BneckParams p) {
     //      Eight neighbouring lanes read one pixel's 128 contiguous bytes, so a wave instruction touches 8 full
     //      cache lines.  Offsets are recomputed per use: keeping them would cost 2 registers per vector.
     uint4 sx0[NVX], sx1[NVX];                                             // two chunks in flight (slot 0 / slot 1)
-    // one vector of a chunk (live = false: a tile that does not exist, nothing is read)
-    auto fetch_vec = [&](const TileGeo &t, int chunk, auto slot_tag, int k, bool live) __attribute__((always_inline)) {
-        constexpr int slot = decltype(slot_tag)::value;
+    // The vectors of a chunk are requested in order through an iterator that holds the pixel's column in the
+    // sub-tile and its byte offset: from vector k to k + 1 the pixel index grows by 32, i.e. by 32 / kBT rows and
+    // 32 % kBT columns with at most one carry (a division per vector cost twice the vector instructions).
+    struct VecIt { int col; uint32_t off; };
+    auto vec_begin = [&](const TileGeo &t, int chunk) __attribute__((always_inline)) {
         int tid = (int)threadIdx.x;
         asm volatile("" : "+v"(tid));     // opaque: otherwise the per-vector offsets are hoisted out of the tile loop and spilled
-        const int v = tid + k * 256;
-        const int px = v >> 3, c8 = v & 7;
-        const int row = px / kBT, col = px - row * kBT;
-        const uint32_t off = t.xorg + (uint32_t)(row * row_stride + col * C + c8 * 8 + chunk * 64) * 2u;
+        const int p0 = tid >> 3, c8 = tid & 7;
+        const int row = p0 / kBT;
+        VecIt it;
+        it.col = p0 - row * kBT;
+        it.off = t.xorg + (uint32_t)(row * row_stride + it.col * C + c8 * 8 + chunk * 64) * 2u;
+        return it;
+    };
+    // vector k of the chunk (k in order from 0; live = false: a tile that does not exist, nothing is read)
+    auto fetch_vec = [&](const TileGeo &t, int chunk, auto slot_tag, int k, bool live, VecIt &it) __attribute__((always_inline)) {
+        constexpr int slot = decltype(slot_tag)::value;
         // rows outside the image are outside the descriptor; columns outside would wrap into the neighbouring
         // row, so they (and the unused tail of the last vector) get the out-of-range offset: zeros either way
-        const bool ok = live && v < kBTPx * 8 && (uint32_t)(t.gx0 + col) < (uint32_t)in_w && (C % 64 == 0 || c8 * 8 + chunk * 64 < C);
-        const uint4 val = bload16(t.xrs, ok ? off : kOutOfRangeB);
+        bool ok = live && (uint32_t)(t.gx0 + it.col) < (uint32_t)in_w;
+        if (C % 64 != 0) ok = ok && ((int)(threadIdx.x & 7) * 8 + chunk * 64 < C);
+        if ((k + 1) * 256 > kBTPx * 8) ok = ok && (int)threadIdx.x < kBTPx * 8 - k * 256;
+        const uint4 val = bload16(t.xrs, ok ? it.off : kOutOfRangeB);
         if (slot == 0) sx0[k] = val;
         else sx1[k] = val;
+        constexpr int RA = 32 / kBT, CA = 32 % kBT;
+        const int col = it.col + CA;
+        const bool carry = col >= kBT;
+        it.col = carry ? col - kBT : col;
+        it.off += (uint32_t)(RA * row_stride + CA * C) * 2u + (carry ? (uint32_t)(row_stride - kBT * C) * 2u : 0u);
     };
     auto fetch_chunk = [&](const TileGeo &t, int chunk, auto slot_tag) __attribute__((always_inline)) {
+        VecIt it = vec_begin(t, chunk);
 #pragma unroll
-        for (int k = 0; k < NVX; ++k) fetch_vec(t, chunk, slot_tag, k, true);
+        for (int k = 0; k < NVX; ++k) fetch_vec(t, chunk, slot_tag, k, true, it);
         __builtin_amdgcn_sched_barrier(0);                                // all loads issued here, in this order
     };
     // With a pre-activation the chunk is transformed on its way to LDS: conv1 reads ReLU(scale * x + shift), the
@@ -496,10 +512,11 @@ void bottleneck16_kernel(BneckParams p) {
             // this tile is queued behind them, and their registers are not held through the last chunk's matrix steps)
 #pragma unroll
             for (int st = 0; st < (W2D < 12 ? W2D : 12); ++st) fetch_w2(st);
+            VecIt nit0 = vec_begin(ngeo, 0);
 #pragma unroll
             for (int j = 0; j < NBPW1; ++j) {
 #pragma unroll
-                for (int k = j * NVX / NBPW1; k < (j + 1) * NVX / NBPW1; ++k) fetch_vec(ngeo, 0, Slot0{}, k, has_next);
+                for (int k = j * NVX / NBPW1; k < (j + 1) * NVX / NBPW1; ++k) fetch_vec(ngeo, 0, Slot0{}, k, has_next, nit0);
                 __builtin_amdgcn_sched_barrier(0);
                 // lanes past the last pixel were fed pixel 323's operands: they write pixel 323's values again
                 const int pi = min((wave + 4 * j) * 32 + m, kBTPx - 1);
@@ -530,6 +547,7 @@ void bottleneck16_kernel(BneckParams p) {
             const f32x16b bias2 = load_bias16(kCm + cm0);
             const unsigned char *L = t1s + ((rh * (TS / 2) + prow) * S * kBT + pcol * S) * kPS + g * 16;
             uint4 xf[2][NF];
+            VecIt nit1 = vec_begin(ngeo, NCH > 1 ? 1 : 0);
             static_assert(S == 1 || NF == 3, "with a stride a pixel block's three tap rows are three fragments of their own");
 #pragma unroll
             for (int j = 0; j < NF; ++j) xf[0][j] = *(const uint4 *)(L + (j * kBT) * kPS);
@@ -541,7 +559,7 @@ void bottleneck16_kernel(BneckParams p) {
                 for (int mm = 0; mm < 3 * NP; ++mm) {
                     const int r = mm / NP, P = mm % NP;
                     acc[P] = mfma32<DT>(w2s[st % W2R][r], xf[st & 1][RPF * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
-                    if (NCH > 1 && mm == 0 && st < NVX) fetch_vec(ngeo, 1, Slot1{}, st, has_next);
+                    if (NCH > 1 && mm == 0 && st < NVX) fetch_vec(ngeo, 1, Slot1{}, st, has_next, nit1);
                     if (mm < NF && st + 1 < 12)
                         xf[(st + 1) & 1][mm] = *(const uint4 *)(L + (mm * kBT + tn) * kPS + kcn * 32);
                     if (mm == 3 * NP - 1 && st + W2D < 12) fetch_w2(st + W2D);       // into the slot this stage just freed
