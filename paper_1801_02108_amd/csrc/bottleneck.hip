@@ -13,23 +13,26 @@
 //   P1  t1 = ReLU(W1 x + b1) on the (TS+2)^2 input sub-tile.  x passes through LDS in 64-channel
 //       chunks: eight lanes read one pixel's 128 contiguous bytes (8 full cache lines per wave
 //       instruction; loading the 32x32x16 B operand directly touches 32 lines for the same 1 KB and
-//       runs at the L1 tag rate), two chunks are in flight in registers, and the first two chunks of
-//       the NEXT tile are requested before P3 so that HBM stays busy during the matrix phases;
+//       runs at the L1 tag rate), two chunks are in flight in registers;
 //       t1 goes to LDS as bf16/f16.  Positions outside the image are forced to zero: the dense
-//       network pads the 3x3's input, i.e. t1, with zeros, and ReLU(b1) is not zero.  In the middle
-//       of P1 the residual (the block's own pixels of x) is requested into registers, while the
-//       same cache lines are passing through L2 for P1.
+//       network pads the 3x3's input, i.e. t1, with zeros, and ReLU(b1) is not zero.  While the chunk
+//       that holds a wave's output channels lies in LDS, the wave copies the block's own pixels of it to
+//       registers as MFMA B operands: the residual never leaves the chip (the pre-activation form,
+//       whose LDS copy is the transformed x, requests x again in the middle of P1, while the same
+//       cache lines are passing through L2).  The next tile's first chunk is requested a few vectors
+//       at a time while t1 is written, its second one vector per stage of P2.
 //   P2  t2 = ReLU(W2 * t1 + b2), the 3x3 as nine shifted reads of the LDS copy of t1 (same scheme
 //       as the stand-alone 3x3 tile kernel); t2 goes to LDS.
 //   P3  t3 = W3 t2 + b3; fused form: y = x + t3 on the block's pixels; on-tiles form: t3 is stored.
-//       A wave owns 64 (or 32) neighbouring output channels.  In the MFMA result layout a lane holds
-//       16 channels of one pixel, so loads and stores from it would be 16-byte pieces 2*C bytes
-//       apart, one memory request each.  t3 is therefore rounded to the storage type (as the tile
-//       stack of the unfused path would hold it) and transposed through a wave-private LDS area
-//       (the space of t1, dead by then): eight neighbouring lanes then hold the wave's 128 contiguous
-//       bytes of one pixel, the residual is read and the sum stored in that layout, whole cache lines
-//       per request, the stores non-temporal.  Fused and unfused paths thereby give bit-identical
-//       results.
+//       A wave owns 64 (or 32) neighbouring output channels.  The bias enters by a matrix step (three
+//       bf16 / f16 pieces of each fp32 bias against a column of ones) and the residual by two more
+//       against a 0/1 matrix, so the sum is formed in fp32 and rounded once, and the phase, which is
+//       bound by its LDS traffic, reads neither from LDS.  In the MFMA result layout a lane holds
+//       16 channels of one pixel, so stores from it would be 16-byte pieces 2*C bytes apart, one
+//       memory request each.  The results are therefore rounded to the storage type and transposed
+//       through a wave-private LDS area (the space of t1, dead by then): eight neighbouring lanes
+//       then hold the wave's 128 contiguous bytes of one pixel and store whole cache lines per
+//       request, non-temporal.  (The pre-activation form adds its residual in that layout.)
 // Global memory is reached through buffer descriptors that cover one sample (or one tile): rows outside
 // the image fall outside the descriptor, columns outside get an out-of-range offset, and the hardware
 // returns zeros for such loads and drops such stores, so no memory operation needs a branch or predicate.
