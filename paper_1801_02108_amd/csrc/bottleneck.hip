@@ -158,7 +158,12 @@ void bottleneck16_kernel(BneckParams p) {
     __shared__ __align__(16) unsigned char t1s[T1B];             // t1; in P3 the four waves' result staging
     __shared__ __align__(16) unsigned char xs[kBTPx * kPS];      // one 64-channel chunk of x in P1, t2 afterwards
     __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];             // conv1 weights, 32x32x16 operand order
-    __shared__ __align__(16) uint4 w3s[NB3 * 4 * 64];            // conv3 weights, [block of 32 outputs][k-step][lane]
+    // 8-pixel sub-tiles serve the launches with few tiles per workgroup, where the time to the first matrix step
+    // counts: conv3's weights are then not staged in LDS by the prologue (32 KB of its loads) but read from L2 by
+    // each wave for each tile during P2, and conv2's weights are requested before P1 instead of at its end.
+    constexpr bool kW3FromL2 = TS == 8;
+    constexpr bool kW2Early = TS == 8 && S == 1;
+    __shared__ __align__(16) uint4 w3s[kW3FromL2 ? 1 : NB3 * 4 * 64];   // conv3 weights, [block of 32 outputs][k-step][lane]
     __shared__ __align__(16) float bias_s[2 * kCm + CO];         // b1 | b2 | b3 (+ bs): accumulators start from these
     float *pre_s = nullptr;                                      // pre-activation scale | shift
     if constexpr (PRE) {
@@ -308,18 +313,17 @@ void bottleneck16_kernel(BneckParams p) {
         }
     };
 
-    TileGeo geo = geometry_of(cur);
+    // ---- Prologue.  What does not depend on the block list is requested first and arrives while the list's entry
+    //      does: W1 (and W3) for LDS and the biases (all loads before all LDS stores); then the first two chunks of
+    //      the first tile are requested.
     using Slot0 = std::integral_constant<int, 0>;
     using Slot1 = std::integral_constant<int, 1>;
-    fetch_chunk(geo, 0, Slot0{});
-    if (NCH > 1) fetch_chunk(geo, 1, Slot1{});
-
-    // ---- W1, W3 and the biases go to LDS once per workgroup (all loads first, then all LDS stores)
+    const uint4 *w3g = (const uint4 *)p.w3 + p.w3_off;           // [ng][ks][nb][lane] -> [ng*2+nb][ks][lane]
     {
         const uint4 *w1g = (const uint4 *)p.w1 + p.w1_off;       // [ks][nb][lane], one group of 64 outputs
-        const uint4 *w3g = (const uint4 *)p.w3 + p.w3_off;       // [ng][ks][nb][lane] -> [ng*2+nb][ks][lane]
-        constexpr int N1 = K1 * 2 * 64 / 256, N3 = NB3 * 4 * 64 / 256;
-        uint4 t1v[N1], t3v[N3];
+        constexpr int N1 = K1 * 2 * 64 / 256, N3 = kW3FromL2 ? 0 : NB3 * 4 * 64 / 256, NBI = (2 * kCm + CO + 255) / 256;
+        uint4 t1v[N1], t3v[N3 > 0 ? N3 : 1];
+        float bv[NBI];
 #pragma unroll
         for (int k = 0; k < N1; ++k) t1v[k] = w1g[threadIdx.x + k * 256];
 #pragma unroll
@@ -329,16 +333,30 @@ void bottleneck16_kernel(BneckParams p) {
             // (k-steps the packed copy does not hold multiply zeros of t2: any finite fragment will do)
             t3v[k] = w3g[(((size_t)(nbg >> 1) * p.km + min(ks, p.km - 1)) * 2 + (nbg & 1)) * 64 + ln];
         }
+        // biases b1 | b2 | b3 (+ bs), zero beyond the unit's width: every lane loads from a clamped address (a load
+        // under a condition is waited for at once)
+#pragma unroll
+        for (int k = 0; k < NBI; ++k) {
+            const int i = threadIdx.x + k * 256;
+            const int i3 = min(max(i - 2 * kCm, 0), CO - 1);
+            const float *src = i < kCm ? p.b1 + min(i, p.Cm - 1) : i < 2 * kCm ? p.b2 + min(i - kCm, p.Cm - 1) : p.b3 + i3;
+            float v = *src;
+            if (PROJ) v += i >= 2 * kCm ? p.bs[i3] : 0.f;
+            bv[k] = (i < 2 * kCm && (i & (kCm - 1)) >= p.Cm) ? 0.f : v;
+        }
 #pragma unroll
         for (int k = 0; k < N1; ++k) w1s[threadIdx.x + k * 256] = t1v[k];
 #pragma unroll
         for (int k = 0; k < N3; ++k) w3s[threadIdx.x + k * 256] = t3v[k];
-        for (int i = threadIdx.x; i < 2 * kCm + CO; i += 256)
-            bias_s[i] = i < kCm ? (i < p.Cm ? p.b1[i] : 0.f) : i < 2 * kCm ? (i - kCm < p.Cm ? p.b2[i - kCm] : 0.f)
-                                : p.b3[i - 2 * kCm] + (PROJ ? p.bs[i - 2 * kCm] : 0.f);
+#pragma unroll
+        for (int k = 0; k < NBI; ++k)
+            if ((int)threadIdx.x + k * 256 < 2 * kCm + CO) bias_s[threadIdx.x + k * 256] = bv[k];
         if constexpr (PRE)
             for (int i = threadIdx.x; i < 2 * C; i += 256) pre_s[i] = i < C ? p.pre_scale[i] : p.pre_shift[i - C];
     }
+    TileGeo geo = geometry_of(cur);
+    fetch_chunk(geo, 0, Slot0{});
+    if (NCH > 1) fetch_chunk(geo, 1, Slot1{});
     // 16 consecutive biases from LDS as an accumulator-shaped vector
     auto load_bias16 = [&](int i0) __attribute__((always_inline)) {
         f32x16b v;
@@ -448,6 +466,11 @@ void bottleneck16_kernel(BneckParams p) {
                 }
         };
 
+        if (kW2Early) {
+#pragma unroll
+            for (int st = 0; st < 12; ++st) fetch_w2(st);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         const uint32_t nit = it + G;                                      // the workgroup's next tile, if any
         const bool has_next = nit < items;
         BItem nxt = cur;
@@ -513,8 +536,10 @@ void bottleneck16_kernel(BneckParams p) {
             }
             // the first stages of conv2's weights come from L2 while t1 is written (requested only now: no input chunk of
             // this tile is queued behind them, and their registers are not held through the last chunk's matrix steps)
+            if (!kW2Early) {
 #pragma unroll
-            for (int st = 0; st < (W2D < 12 ? W2D : 12); ++st) fetch_w2(st);
+                for (int st = 0; st < (W2D < 12 ? W2D : 12); ++st) fetch_w2(st);
+            }
             VecIt nit0 = vec_begin(ngeo, 0);
 #pragma unroll
             for (int j = 0; j < NBPW1; ++j) {
@@ -542,6 +567,16 @@ void bottleneck16_kernel(BneckParams p) {
         __syncthreads();
 
         // ================= P2: t2 = ReLU(W2 * t1 + b2) -> xs =================
+        uint4 w3r[4][NBW];                                               // conv3's weights of this wave's channels
+        if constexpr (kW3FromL2) {
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) {
+                const int nbg = min(wave * NBW + j, NB3 - 1);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    w3r[ks][j] = w3g[(((size_t)(nbg >> 1) * p.km + min(ks, p.km - 1)) * 2 + (nbg & 1)) * 64 + lane];
+            }
+        }
         {
             // wave (rh, nh): output rows rh*TS/2 .. + TS/2 (NP pixel blocks of RPF rows), mid channels nh*32 .. + 32.
             // Fragment j of a stage holds input rows rh*TS/2 + j .. + RPF at tap column t; pixel block P with tap row r
@@ -585,12 +620,13 @@ void bottleneck16_kernel(BneckParams p) {
 
         // ================= P3: t3 = W3 t2 + b3 (+ x), two pixel blocks (64 pixels) per pass =================
         {
-            uint4 w3r[4][NBW];
+            if constexpr (!kW3FromL2) {
 #pragma unroll
-            for (int j = 0; j < NBW; ++j) {
-                const int nbg = min(wave * NBW + j, NB3 - 1);             // this wave's neighbouring blocks of 32 channels
+                for (int j = 0; j < NBW; ++j) {
+                    const int nbg = min(wave * NBW + j, NB3 - 1);         // this wave's neighbouring blocks of 32 channels
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];
+                    for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];
+                }
             }
             unsigned char *ost = t1s + wave * (64 * OPS);                 // t1 is dead: the wave's private staging area
             // P3 is bound by LDS traffic, and accumulators that start from the bias read it from LDS in every pass (16
