@@ -140,7 +140,7 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NPB = TS * TS / 32;          // 32-pixel blocks of the output sub-tile (8 or 2)
     constexpr int NP = NPB / 2;                // ... per wave in P2: waves split the rows in two halves (4 or 1)
     constexpr int NF = RPF * (NP - 1) + 3;     // LDS fragments per P2 stage (9 or 3)
-    constexpr int W2D = TS == 16 ? (C > 128 ? 4 : 7) : 12;   // stages of conv2 weights requested ahead (registers permitting)
+    constexpr int W2D = TS == 16 ? (C > 128 ? 3 : 7) : 12;   // stages of conv2 weights requested ahead (registers permitting)
     constexpr int W2R = W2D < 12 ? W2D : 12;   // ... and ring slots holding them
     constexpr int K1 = C / 16;                 // k-steps of conv1
     constexpr int NCH = (C + 63) / 64;         // 64-channel chunks of the input tile (the last may be half empty)
@@ -159,10 +159,12 @@ void bottleneck16_kernel(BneckParams p) {
     __shared__ __align__(16) unsigned char xs[kBTPx * kPS];      // one 64-channel chunk of x in P1, t2 afterwards
     __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];             // conv1 weights, 32x32x16 operand order
     // 8-pixel sub-tiles serve the launches with few tiles per workgroup, where the time to the first matrix step
-    // counts: conv3's weights are then not staged in LDS by the prologue (32 KB of its loads) but read from L2 by
-    // each wave for each tile during P2, and conv2's weights are requested before P1 instead of at its end.
+    // counts, and their LDS is far from full: conv3's weights are not staged in LDS by the prologue (32 KB of its
+    // loads) but read from L2 by each wave for each tile during P2, and (stride 1) conv2's weights live in LDS for
+    // the life of the workgroup: 72 KB once instead of 144 KB through registers per tile (two waves share each half).
     constexpr bool kW3FromL2 = TS == 8;
-    constexpr bool kW2Early = TS == 8 && S == 1;
+    constexpr bool kW2InLds = TS == 8 && S == 1;
+    __shared__ __align__(16) uint4 w2l[kW2InLds ? 36 * 2 * 64 : 1];     // conv2 weights, [tap][k-step][half][lane]
     __shared__ __align__(16) uint4 w3s[kW3FromL2 ? 1 : NB3 * 4 * 64];   // conv3 weights, [block of 32 outputs][k-step][lane]
     __shared__ __align__(16) float bias_s[2 * kCm + CO];         // b1 | b2 | b3 (+ bs): accumulators start from these
     float *pre_s = nullptr;                                      // pre-activation scale | shift
@@ -319,19 +321,27 @@ void bottleneck16_kernel(BneckParams p) {
     using Slot0 = std::integral_constant<int, 0>;
     using Slot1 = std::integral_constant<int, 1>;
     const uint4 *w3g = (const uint4 *)p.w3 + p.w3_off;           // [ng][ks][nb][lane] -> [ng*2+nb][ks][lane]
+    TileGeo geo;
     {
         const uint4 *w1g = (const uint4 *)p.w1 + p.w1_off;       // [ks][nb][lane], one group of 64 outputs
         constexpr int N1 = K1 * 2 * 64 / 256, N3 = kW3FromL2 ? 0 : NB3 * 4 * 64 / 256, NBI = (2 * kCm + CO + 255) / 256;
-        uint4 t1v[N1], t3v[N3 > 0 ? N3 : 1];
+        constexpr int N2 = kW2InLds ? 36 * 2 * 64 / 256 : 0;
+        uint4 t1v[N1], t3v[N3 > 0 ? N3 : 1], t2v[N2 > 0 ? N2 : 1];
         float bv[NBI];
 #pragma unroll
-        for (int k = 0; k < N1; ++k) t1v[k] = w1g[threadIdx.x + k * 256];
+        for (int k = 0; k < N1; ++k) t1v[k] = gload16((gvec_t)w1g + (threadIdx.x + k * 256));     // (by value: a struct copy kept the array in memory)
 #pragma unroll
         for (int k = 0; k < N3; ++k) {
             const int i = threadIdx.x + k * 256;
             const int ln = i & 63, ks = (i >> 6) & 3, nbg = i >> 8;
             // (k-steps the packed copy does not hold multiply zeros of t2: any finite fragment will do)
-            t3v[k] = w3g[(((size_t)(nbg >> 1) * p.km + min(ks, p.km - 1)) * 2 + (nbg & 1)) * 64 + ln];
+            t3v[k] = gload16((gvec_t)w3g + ((((size_t)(nbg >> 1) * p.km + min(ks, p.km - 1)) * 2 + (nbg & 1)) * 64 + ln));
+        }
+#pragma unroll
+        for (int k = 0; k < N2; ++k) {
+            const int i = threadIdx.x + k * 256;
+            const int ln = i & 63, half = (i >> 6) & 1, kc = (i >> 7) & 3, tap = i >> 9;
+            t2v[k] = gload16((gvec_t)((const uint4 *)p.w2 + p.w2_off) + ((tap * p.km + min(kc, p.km - 1)) * 128 + half * 64 + ln));
         }
         // biases b1 | b2 | b3 (+ bs), zero beyond the unit's width: every lane loads from a clamped address (a load
         // under a condition is waited for at once)
@@ -344,19 +354,21 @@ void bottleneck16_kernel(BneckParams p) {
             if (PROJ) v += i >= 2 * kCm ? p.bs[i3] : 0.f;
             bv[k] = (i < 2 * kCm && (i & (kCm - 1)) >= p.Cm) ? 0.f : v;
         }
+        geo = geometry_of(cur);
+        fetch_chunk(geo, 0, Slot0{});
+        if (NCH > 1) fetch_chunk(geo, 1, Slot1{});
 #pragma unroll
         for (int k = 0; k < N1; ++k) w1s[threadIdx.x + k * 256] = t1v[k];
 #pragma unroll
         for (int k = 0; k < N3; ++k) w3s[threadIdx.x + k * 256] = t3v[k];
+#pragma unroll
+        for (int k = 0; k < N2; ++k) w2l[threadIdx.x + k * 256] = t2v[k];
 #pragma unroll
         for (int k = 0; k < NBI; ++k)
             if ((int)threadIdx.x + k * 256 < 2 * kCm + CO) bias_s[threadIdx.x + k * 256] = bv[k];
         if constexpr (PRE)
             for (int i = threadIdx.x; i < 2 * C; i += 256) pre_s[i] = i < C ? p.pre_scale[i] : p.pre_shift[i - C];
     }
-    TileGeo geo = geometry_of(cur);
-    fetch_chunk(geo, 0, Slot0{});
-    if (NCH > 1) fetch_chunk(geo, 1, Slot1{});
     // 16 consecutive biases from LDS as an accumulator-shaped vector
     auto load_bias16 = [&](int i0) __attribute__((always_inline)) {
         f32x16b v;
@@ -466,11 +478,6 @@ void bottleneck16_kernel(BneckParams p) {
                 }
         };
 
-        if (kW2Early) {
-#pragma unroll
-            for (int st = 0; st < 12; ++st) fetch_w2(st);
-            __builtin_amdgcn_sched_barrier(0);
-        }
         const uint32_t nit = it + G;                                      // the workgroup's next tile, if any
         const bool has_next = nit < items;
         BItem nxt = cur;
@@ -536,7 +543,7 @@ void bottleneck16_kernel(BneckParams p) {
             }
             // the first stages of conv2's weights come from L2 while t1 is written (requested only now: no input chunk of
             // this tile is queued behind them, and their registers are not held through the last chunk's matrix steps)
-            if (!kW2Early) {
+            if (!kW2InLds) {
 #pragma unroll
                 for (int st = 0; st < (W2D < 12 ? W2D : 12); ++st) fetch_w2(st);
             }
@@ -584,11 +591,17 @@ void bottleneck16_kernel(BneckParams p) {
             f32x16b acc[NP];
             const f32x16b bias2 = load_bias16(kCm + cm0);
             const unsigned char *L = t1s + ((rh * (TS / 2) + prow) * S * kBT + pcol * S) * kPS + g * 16;
-            uint4 xf[2][NF];
+            uint4 xf[2][NF], wl[2][3];
+            // (kW2InLds) fragment r of stage st: tap (r, st / 4), k-step st % 4, this wave's half of the mid channels
+            const uint4 *wlp = w2l + nh * 64 + lane;
             VecIt nit1 = vec_begin(ngeo, NCH > 1 ? 1 : 0);
             static_assert(S == 1 || NF == 3, "with a stride a pixel block's three tap rows are three fragments of their own");
 #pragma unroll
             for (int j = 0; j < NF; ++j) xf[0][j] = *(const uint4 *)(L + (j * kBT) * kPS);
+            if (kW2InLds) {
+#pragma unroll
+                for (int r = 0; r < 3; ++r) wl[0][r] = wlp[(r * 3 * 4) * 128];
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int st = 0; st < 12; ++st) {
@@ -596,11 +609,12 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
                 for (int mm = 0; mm < 3 * NP; ++mm) {
                     const int r = mm / NP, P = mm % NP;
-                    acc[P] = mfma32<DT>(w2s[st % W2R][r], xf[st & 1][RPF * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
+                    acc[P] = mfma32<DT>(kW2InLds ? wl[st & 1][r] : w2s[st % W2R][r], xf[st & 1][RPF * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
+                    if (kW2InLds && mm < 3 && st + 1 < 12) wl[(st + 1) & 1][mm] = wlp[((mm * 3 + tn) * 4 + kcn) * 128];
                     if (NCH > 1 && mm == 0 && st < NVX) fetch_vec(ngeo, 1, Slot1{}, st, has_next, nit1);
                     if (mm < NF && st + 1 < 12)
                         xf[(st + 1) & 1][mm] = *(const uint4 *)(L + (mm * kBT + tn) * kPS + kcn * 32);
-                    if (mm == 3 * NP - 1 && st + W2D < 12) fetch_w2(st + W2D);       // into the slot this stage just freed
+                    if (!kW2InLds && mm == 3 * NP - 1 && st + W2D < 12) fetch_w2(st + W2D);       // into the slot this stage just freed
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
