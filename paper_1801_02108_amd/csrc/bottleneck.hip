@@ -127,10 +127,18 @@ __device__ __forceinline__ uint32_t relu_pack2(float lo, float hi) {
 // with the same stride (PROJ), whose products P3 adds to the same accumulators as W3 t2: K is simply longer by C.
 // Its B operands are the input pixels under the output pixels, read from L2 in the MFMA layout (they passed
 // through this CU for P1 a moment ago).  8 x 8 sub-tiles only: t1 of a 33 x 33 sub-tile would not fit LDS.
-template <int DT, int C, bool FUSED, int TS, bool PRE, int S = 1, bool PROJ = false, int CO = C>
+// CM: the bottleneck width the kernel is built for, 64 or (the fourth stage of the backbone, Sec. 4: 384 / 96) 96:
+// three blocks of 32 mid channels instead of two; conv2's third block is a second pass of the waves that own the
+// first; 8 x 8 sub-tiles only.
+template <int DT, int C, bool FUSED, int TS, bool PRE, int S = 1, bool PROJ = false, int CO = C, int CM = kCm>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void bottleneck16_kernel(BneckParams p) {
     static_assert(TS == 16 || TS == 8, "output sub-tile side");
+    static_assert(CM == 64 || (CM == 96 && TS == 8 && FUSED && !PRE), "the wide form: 8 x 8 sub-tiles, fused, no pre-activation");
+    constexpr int NMB = CM / 32;               // blocks of 32 mid channels
+    constexpr int KT = CM / 16;                // k-steps over the mid channels (per tap of conv2; of conv3)
+    constexpr int NST = 3 * KT;                // stages of P2: tap column x k-step
+    constexpr int PS = (CM + 8) * 2;           // LDS bytes per pixel of t1 / t2 (16 B pad); kPS: of a 64-channel chunk of x
     static_assert(S == 1 || (S == 2 && TS == 8 && FUSED && PROJ && !PRE), "the strided form: 8 x 8 sub-tiles, fused, projected");
     static_assert(PROJ || CO == C, "the identity shortcut keeps the channel count");
     constexpr int kBT = TS * S + 3 - S;        // input sub-tile side: TS + 2, or 2 TS + 1 with the stride
@@ -140,8 +148,8 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NPB = TS * TS / 32;          // 32-pixel blocks of the output sub-tile (8 or 2)
     constexpr int NP = NPB / 2;                // ... per wave in P2: waves split the rows in two halves (4 or 1)
     constexpr int NF = RPF * (NP - 1) + 3;     // LDS fragments per P2 stage (9 or 3)
-    constexpr int W2D = TS == 16 ? (C > 128 ? 3 : 7) : 12;   // stages of conv2 weights requested ahead (registers permitting)
-    constexpr int W2R = W2D < 12 ? W2D : 12;   // ... and ring slots holding them
+    constexpr int W2D = TS == 16 ? (C > 128 ? 3 : 7) : CM == 64 ? 12 : S == 2 ? 3 : 9;   // stages of conv2 weights requested ahead (registers permitting)
+    constexpr int W2R = W2D < NST ? W2D : NST; // ... and ring slots holding them
     constexpr int K1 = C / 16;                 // k-steps of conv1
     constexpr int NCH = (C + 63) / 64;         // 64-channel chunks of the input tile (the last may be half empty)
     constexpr int NB3 = CO / 32;               // 32-channel output blocks of conv3
@@ -150,23 +158,26 @@ void bottleneck16_kernel(BneckParams p) {
     constexpr int NBPW1 = (NBLK1 + 3) / 4;     // ... per wave
     constexpr int NVX = (kBTPx * 8 + 255) / 256;   // 16-byte staging vectors per thread and chunk
     static_assert(NVX <= 12, "one vector of the next tile's second chunk is requested per stage of P2");
-    constexpr int OPS = NBW * 64 + 16;         // LDS bytes per pixel of a wave's P3 results (+16 B pad)
-    constexpr int CPP = NBW * 4;               // 16-byte pieces per pixel of those
+    constexpr int SB = NBW <= 2 ? NBW : 1;     // channel blocks that leave together through the staging area
+    constexpr int NSG = NBW / SB;              // ... groups of them per wave
+    constexpr int OPS = SB * 64 + 16;          // LDS bytes per pixel of a group's results (+16 B pad)
+    constexpr int CPP = SB * 4;                // 16-byte pieces per pixel of those
     constexpr int PPI = 64 / CPP;              // pixels per wave instruction in the store layout
     constexpr int NI = 64 / PPI;               // instructions per pass (64 pixels)
-    constexpr int T1B = kBTPx * kPS > 4 * 64 * OPS ? kBTPx * kPS : 4 * 64 * OPS;
+    constexpr int T1B = kBTPx * PS > 4 * 64 * OPS ? kBTPx * PS : 4 * 64 * OPS;
+    constexpr int XSB = kBTPx * kPS > TS * TS * PS ? kBTPx * kPS : TS * TS * PS;
     __shared__ __align__(16) unsigned char t1s[T1B];             // t1; in P3 the four waves' result staging
-    __shared__ __align__(16) unsigned char xs[kBTPx * kPS];      // one 64-channel chunk of x in P1, t2 afterwards
-    __shared__ __align__(16) uint4 w1s[K1 * 2 * 64];             // conv1 weights, 32x32x16 operand order
+    __shared__ __align__(16) unsigned char xs[XSB];              // one 64-channel chunk of x in P1, t2 afterwards
+    __shared__ __align__(16) uint4 w1s[K1 * NMB * 64];           // conv1 weights, 32x32x16 operand order: [k-step][mid block][lane]
     // 8-pixel sub-tiles serve the launches with few tiles per workgroup, where the time to the first matrix step
     // counts, and their LDS is far from full: conv3's weights are not staged in LDS by the prologue (32 KB of its
     // loads) but read from L2 by each wave for each tile during P2, and (stride 1) conv2's weights live in LDS for
     // the life of the workgroup: 72 KB once instead of 144 KB through registers per tile (two waves share each half).
     constexpr bool kW3FromL2 = TS == 8;
-    constexpr bool kW2InLds = TS == 8 && S == 1;
+    constexpr bool kW2InLds = TS == 8 && S == 1 && CM == 64;
     __shared__ __align__(16) uint4 w2l[kW2InLds ? 36 * 2 * 64 : 1];     // conv2 weights, [tap][k-step][half][lane]
     __shared__ __align__(16) uint4 w3s[kW3FromL2 ? 1 : NB3 * 4 * 64];   // conv3 weights, [block of 32 outputs][k-step][lane]
-    __shared__ __align__(16) float bias_s[2 * kCm + CO];         // b1 | b2 | b3 (+ bs): accumulators start from these
+    __shared__ __align__(16) float bias_s[2 * CM + CO];         // b1 | b2 | b3 (+ bs): accumulators start from these
     float *pre_s = nullptr;                                      // pre-activation scale | shift
     if constexpr (PRE) {
         __shared__ __align__(16) float pre_store[2 * C];
@@ -324,12 +335,17 @@ void bottleneck16_kernel(BneckParams p) {
     TileGeo geo;
     {
         const uint4 *w1g = (const uint4 *)p.w1 + p.w1_off;       // [ks][nb][lane], one group of 64 outputs
-        constexpr int N1 = K1 * 2 * 64 / 256, N3 = kW3FromL2 ? 0 : NB3 * 4 * 64 / 256, NBI = (2 * kCm + CO + 255) / 256;
+        static_assert(K1 * NMB * 64 % 256 == 0, "conv1's weights divide among the threads");
+        constexpr int N1 = K1 * NMB * 64 / 256, N3 = kW3FromL2 ? 0 : NB3 * 4 * 64 / 256, NBI = (2 * CM + CO + 255) / 256;
         constexpr int N2 = kW2InLds ? 36 * 2 * 64 / 256 : 0;
         uint4 t1v[N1], t3v[N3 > 0 ? N3 : 1], t2v[N2 > 0 ? N2 : 1];
         float bv[NBI];
 #pragma unroll
-        for (int k = 0; k < N1; ++k) t1v[k] = gload16((gvec_t)w1g + (threadIdx.x + k * 256));     // (by value: a struct copy kept the array in memory)
+        for (int k = 0; k < N1; ++k) {       // (by value: a struct copy kept the array in memory)
+            const int i = threadIdx.x + k * 256;
+            const int ln = i & 63, q = i >> 6, mb = q % NMB, ks = q / NMB;     // packed: [group of 64][k-step][block of 32][lane]
+            t1v[k] = gload16((gvec_t)w1g + ((((mb >> 1) * K1 + ks) * 2 + (mb & 1)) * 64 + ln));
+        }
 #pragma unroll
         for (int k = 0; k < N3; ++k) {
             const int i = threadIdx.x + k * 256;
@@ -348,11 +364,11 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
         for (int k = 0; k < NBI; ++k) {
             const int i = threadIdx.x + k * 256;
-            const int i3 = min(max(i - 2 * kCm, 0), CO - 1);
-            const float *src = i < kCm ? p.b1 + min(i, p.Cm - 1) : i < 2 * kCm ? p.b2 + min(i - kCm, p.Cm - 1) : p.b3 + i3;
+            const int i3 = min(max(i - 2 * CM, 0), CO - 1);
+            const float *src = i < CM ? p.b1 + min(i, p.Cm - 1) : i < 2 * CM ? p.b2 + min(i - CM, p.Cm - 1) : p.b3 + i3;
             float v = *src;
-            if (PROJ) v += i >= 2 * kCm ? p.bs[i3] : 0.f;
-            bv[k] = (i < 2 * kCm && (i & (kCm - 1)) >= p.Cm) ? 0.f : v;
+            if (PROJ) v += i >= 2 * CM ? p.bs[i3] : 0.f;
+            bv[k] = (i < 2 * CM && (i < CM ? i : i - CM) >= p.Cm) ? 0.f : v;
         }
         geo = geometry_of(cur);
         fetch_chunk(geo, 0, Slot0{});
@@ -365,7 +381,7 @@ void bottleneck16_kernel(BneckParams p) {
         for (int k = 0; k < N2; ++k) w2l[threadIdx.x + k * 256] = t2v[k];
 #pragma unroll
         for (int k = 0; k < NBI; ++k)
-            if ((int)threadIdx.x + k * 256 < 2 * kCm + CO) bias_s[threadIdx.x + k * 256] = bv[k];
+            if ((int)threadIdx.x + k * 256 < 2 * CM + CO) bias_s[threadIdx.x + k * 256] = bv[k];
         if constexpr (PRE)
             for (int i = threadIdx.x; i < 2 * C; i += 256) pre_s[i] = i < C ? p.pre_scale[i] : p.pre_shift[i - C];
     }
@@ -378,7 +394,6 @@ void bottleneck16_kernel(BneckParams p) {
         v[8] = q2.x; v[9] = q2.y; v[10] = q2.z; v[11] = q2.w; v[12] = q3.x; v[13] = q3.y; v[14] = q3.z; v[15] = q3.w;
         return v;
     };
-    const int cm0 = nh * 32 + g * 16;                // this lane's 16 mid channels in P2
     __syncthreads();                                 // weights and biases visible to every wave
 
     for (uint32_t it = first; it < items; it += G) {
@@ -387,12 +402,14 @@ void bottleneck16_kernel(BneckParams p) {
         // would cost 144 registers that the residual needs); 8-pixel sub-tiles: a stage is too short for that,
         // everything is requested before P2.
         uint4 w2s[W2R][3];
-        const uint4 *w2p = (const uint4 *)p.w2 + p.w2_off + (size_t)nh * 64;      // wave-uniform
+        const uint4 *w2p = (const uint4 *)p.w2 + p.w2_off;                        // wave-uniform
         asm volatile("" : "+s"(w2p));      // opaque per iteration: keeps the loads inside the tile loop
-        auto fetch_w2 = [&](int st) __attribute__((always_inline)) {
+        // stage st of mid block cb: packed [group of 64 outputs][tap][k-step][block of 32][lane]
+        auto fetch_w2 = [&](int st, int cb) __attribute__((always_inline)) {
+            const uint4 *wb = w2p + ((size_t)(cb >> 1) * 9 * p.km * 2 + (cb & 1)) * 64;
 #pragma unroll
             for (int r = 0; r < 3; ++r)     // (as for W3: a k-step beyond km multiplies zeros of t1)
-                w2s[st % W2R][r] = gload16((gvec_t)w2p + ((r * 3 + st / 4) * p.km + min(st % 4, p.km - 1)) * 128 + (uint32_t)lane);
+                w2s[st % W2R][r] = gload16((gvec_t)wb + ((r * 3 + st / KT) * p.km + min(st % KT, p.km - 1)) * 128 + (uint32_t)lane);
         };
 
         // ---- where this tile's results go and, for the fused form, where the residual x comes from.  Layout of
@@ -426,7 +443,8 @@ void bottleneck16_kernel(BneckParams p) {
         constexpr int NCOLV = (TS == 16 && PPI == 8) ? 2 : 1;
         uint32_t lane_off[NCOLV];
         const uint32_t out_row_bytes = (uint32_t)(out_w * CO) * 2u;
-        {
+        // (computed where first needed, P3, or P1 with a pre-activation: kept across P2 they were spilled)
+        auto set_lane_off = [&]() __attribute__((always_inline)) {
             const int l = lane / CPP;
             const int rowl = (TS == 8 && PPI == 16) ? (l >> 3) : 0;
 #pragma unroll
@@ -435,7 +453,8 @@ void bottleneck16_kernel(BneckParams p) {
                 const bool ok = wave * NBW < NB3 && (uint32_t)(ox + col) < (uint32_t)out_w;
                 lane_off[v] = ok ? yorg + (uint32_t)((rowl * out_w + col) * CO) * 2u + (lane % CPP) * 16 : kOutOfRangeB;
             }
-        }
+        };
+        if (PRE) set_lane_off();
         auto out_offset = [&](int bp, int i) __attribute__((always_inline)) {
             const int rowc = RPF * (2 * bp + ((i * PPI) >> 5)) + (((i * PPI) & 31) >> LOGTS);
             // (an out-of-range lane part stays out of range: the sum is below 2^32)
@@ -462,9 +481,9 @@ void bottleneck16_kernel(BneckParams p) {
         // them to its accumulators with two more matrix steps per block against a 0/1 matrix: the sum x + t3 is formed
         // in fp32 and rounded once, and the vector unit, which bounds P3, has nothing to do for it.
         constexpr bool kResidualFromLds = FUSED && !PROJ && !PRE;
-        const int rchunk = min(wave * NBW * 32 / 64, NCH - 1);                 // wave-uniform
-        auto residual_from_lds = [&]() __attribute__((always_inline)) {
-            const int roff = (wave * NBW * 32 % 64 + g * 8) * 2;
+        // (block j of the wave = block wave * NBW + j of the unit's channels: half of chunk (wave * NBW + j) / 2)
+        auto residual_from_lds = [&](int j) __attribute__((always_inline)) {
+            const int roff = (((wave * NBW + j) & 1) * 32 + g * 8) * 2;
 #pragma unroll
             for (int bp = 0; bp < NPASS; ++bp)
 #pragma unroll
@@ -472,9 +491,7 @@ void bottleneck16_kernel(BneckParams p) {
                     const int q = (2 * bp + u) * 32 + m;                       // output pixel of the sub-tile
                     const unsigned char *src = xs + (((q >> LOGTS) + 1) * kBT + (q & (TS - 1)) + 1) * kPS + roff;
 #pragma unroll
-                    for (int j = 0; j < NBW; ++j)
-#pragma unroll
-                        for (int k2 = 0; k2 < 2; ++k2) rb[bp][u][j][k2] = *(const uint4 *)(src + (j * 32 + k2 * 16) * 2);
+                    for (int k2 = 0; k2 < 2; ++k2) rb[bp][u][j][k2] = *(const uint4 *)(src + (k2 * 16) * 2);
                 }
         };
 
@@ -487,12 +504,11 @@ void bottleneck16_kernel(BneckParams p) {
         // x passes through LDS in 64-channel chunks: coalesced global loads -> registers -> xs -> MFMA B operands.
         // Wave w owns pixel blocks w, w+4, w+8 (32 pixels each, row-major over the 18x18 tile) and all 64 outputs.
         {
-            f32x16b acc[NBPW1][2];
+            f32x16b acc[NBPW1][NMB];
 #pragma unroll
-            for (int j = 0; j < NBPW1; ++j) {
-                acc[j][0] = load_bias16(g * 16);
-                acc[j][1] = load_bias16(32 + g * 16);
-            }
+            for (int j = 0; j < NBPW1; ++j)
+#pragma unroll
+                for (int mb = 0; mb < NMB; ++mb) acc[j][mb] = load_bias16(mb * 32 + g * 16);
             int boff[NBPW1];                                             // LDS byte offset of this lane's pixel
 #pragma unroll
             for (int j = 0; j < NBPW1; ++j) boff[j] = min((wave + 4 * j) * 32 + m, kBTPx - 1) * kPS + g * 16;
@@ -507,26 +523,31 @@ void bottleneck16_kernel(BneckParams p) {
                 }
                 if (c == (NCH > 1 ? 1 : 0)) fetch_residual(0, NPASS);
                 if (c == NCH - 1) {
-                    // Both staging slots are free from here on.  The next tile's first two chunks are requested a few
-                    // vectors at a time between the steps of the phases that follow and leave the memory pipeline idle:
-                    // the end of P1 (chunk 0) and P2 (chunk 1, one vector per stage).  Measured: a load costs the wave
-                    // about 100 clocks there, 450 among the stores of P3, and 200 in one burst of 22.
+                    // Both staging slots are free from here on.  The next tile's first two chunks are requested a vector
+                    // of each per stage of P2, which leaves the memory pipeline idle otherwise.  Measured: a load costs
+                    // the wave about 100 clocks there, 450 among the stores of P3, and 200 in one burst of 22 after P2;
+                    // while t1 is written (the end of P1) they cost the same as in P2 but their registers, on top of
+                    // the accumulators of P1, made the compiler spill, and a spill's reload waits for every load in flight.
                     nxt = decode(min(nit, (uint32_t)p.cap * per_block - 1u));
                     ngeo = geometry_of(nxt);
                 }
-                if (kResidualFromLds && c == rchunk) residual_from_lds();
+                if (kResidualFromLds) {
+#pragma unroll
+                    for (int j = 0; j < NBW; ++j)
+                        if (c == min((wave * NBW + j) >> 1, NCH - 1)) residual_from_lds(j);
+                }
                 // fragments of k-step k4+1 are read from LDS while the MFMAs of k-step k4 run
-                uint4 af[2][2], bf[2][NBPW1];
-                af[0][0] = w1s[((c * 4) * 2 + 0) * 64 + lane];
-                af[0][1] = w1s[((c * 4) * 2 + 1) * 64 + lane];
+                uint4 af[2][NMB], bf[2][NBPW1];
+#pragma unroll
+                for (int mb = 0; mb < NMB; ++mb) af[0][mb] = w1s[((c * 4) * NMB + mb) * 64 + lane];
 #pragma unroll
                 for (int j = 0; j < NBPW1; ++j) bf[0][j] = *(const uint4 *)(xs + boff[j]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int k4 = 0; k4 < 4 && c * 4 + k4 < K1; ++k4) {       // the last chunk of C = 96 holds two k-steps
                     if (k4 + 1 < 4 && c * 4 + k4 + 1 < K1) {
-                        af[(k4 + 1) & 1][0] = w1s[((c * 4 + k4 + 1) * 2 + 0) * 64 + lane];
-                        af[(k4 + 1) & 1][1] = w1s[((c * 4 + k4 + 1) * 2 + 1) * 64 + lane];
+#pragma unroll
+                        for (int mb = 0; mb < NMB; ++mb) af[(k4 + 1) & 1][mb] = w1s[((c * 4 + k4 + 1) * NMB + mb) * 64 + lane];
 #pragma unroll
                         for (int j = 0; j < NBPW1; ++j) bf[(k4 + 1) & 1][j] = *(const uint4 *)(xs + boff[j] + (k4 + 1) * 32);
                     }
@@ -534,8 +555,8 @@ void bottleneck16_kernel(BneckParams p) {
                     for (int j = 0; j < NBPW1; ++j) {
                         // (wave 3's third block does not exist: it recomputes pixel 323 and the result is dropped;
                         //  a branch here would cost a copy of every accumulator per step)
-                        acc[j][0] = mfma32<DT>(af[k4 & 1][0], bf[k4 & 1][j], acc[j][0]);
-                        acc[j][1] = mfma32<DT>(af[k4 & 1][1], bf[k4 & 1][j], acc[j][1]);
+#pragma unroll
+                        for (int mb = 0; mb < NMB; ++mb) acc[j][mb] = mfma32<DT>(af[k4 & 1][mb], bf[k4 & 1][j], acc[j][mb]);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -545,76 +566,88 @@ void bottleneck16_kernel(BneckParams p) {
             // this tile is queued behind them, and their registers are not held through the last chunk's matrix steps)
             if (!kW2InLds) {
 #pragma unroll
-                for (int st = 0; st < (W2D < 12 ? W2D : 12); ++st) fetch_w2(st);
+                for (int st = 0; st < W2R; ++st) fetch_w2(st, nh);
             }
-            VecIt nit0 = vec_begin(ngeo, 0);
 #pragma unroll
             for (int j = 0; j < NBPW1; ++j) {
-#pragma unroll
-                for (int k = j * NVX / NBPW1; k < (j + 1) * NVX / NBPW1; ++k) fetch_vec(ngeo, 0, Slot0{}, k, has_next, nit0);
-                __builtin_amdgcn_sched_barrier(0);
                 // lanes past the last pixel were fed pixel 323's operands: they write pixel 323's values again
                 const int pi = min((wave + 4 * j) * 32 + m, kBTPx - 1);
                 const int row = pi / kBT, col = pi - row * kBT;
                 const bool inside = row >= geo.rlo && row < geo.rhi && col >= geo.clo && col < geo.chi;
                 const uint32_t keep = inside ? 0xffffffffu : 0u;         // (a mask, not a select: selects became branches here)
-                uint32_t w[16];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    w[k] = relu_pack2<DT>(acc[j][0][2 * k], acc[j][0][2 * k + 1]) & keep;
-                    w[8 + k] = relu_pack2<DT>(acc[j][1][2 * k], acc[j][1][2 * k + 1]) & keep;
+                for (int mb = 0; mb < NMB; ++mb) {
+                    uint32_t w[8];
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) w[k] = relu_pack2<DT>(acc[j][mb][2 * k], acc[j][mb][2 * k + 1]) & keep;
+                    uint4 *d = (uint4 *)(t1s + pi * PS + mb * 64 + g * 32);     // channels mb * 32 + g * 16 .. + 16
+                    d[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                    d[1] = make_uint4(w[4], w[5], w[6], w[7]);
                 }
-                uint4 *d = (uint4 *)(t1s + pi * kPS + g * 32);
-                d[0] = make_uint4(w[0], w[1], w[2], w[3]);
-                d[1] = make_uint4(w[4], w[5], w[6], w[7]);
-                d[4] = make_uint4(w[8], w[9], w[10], w[11]);             // +64 B: channels 32..63
-                d[5] = make_uint4(w[12], w[13], w[14], w[15]);
             }
         }
         __syncthreads();
 
         // ================= P2: t2 = ReLU(W2 * t1 + b2) -> xs =================
-        uint4 w3r[4][NBW];                                               // conv3's weights of this wave's channels
+        uint4 w3r[KT][NBW];                                              // conv3's weights of this wave's channels
         if constexpr (kW3FromL2) {
 #pragma unroll
             for (int j = 0; j < NBW; ++j) {
                 const int nbg = min(wave * NBW + j, NB3 - 1);
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
+                for (int ks = 0; ks < KT; ++ks)
                     w3r[ks][j] = w3g[(((size_t)(nbg >> 1) * p.km + min(ks, p.km - 1)) * 2 + (nbg & 1)) * 64 + lane];
             }
         }
-        {
-            // wave (rh, nh): output rows rh*TS/2 .. + TS/2 (NP pixel blocks of RPF rows), mid channels nh*32 .. + 32.
-            // Fragment j of a stage holds input rows rh*TS/2 + j .. + RPF at tap column t; pixel block P with tap row r
-            // reads fragment RPF*P + r.
+        // wave (rh, nh): output rows rh*TS/2 .. + TS/2 (NP pixel blocks of RPF rows), mid channels nh*32 .. + 32; with
+        // three blocks of mid channels the waves nh = 0 then take the third in a second pass.
+        // Fragment j of a stage holds input rows rh*TS/2 + j .. + RPF at tap column t; pixel block P with tap row r
+        // reads fragment RPF*P + r.
+#pragma unroll
+        for (int pass = 0; pass < (NMB > 2 ? 2 : 1); ++pass) {
+            const int cb = pass == 0 ? nh : 2;                            // block of 32 mid channels, wave-uniform
+            if (pass == 1) {
+                if (nh != 0) continue;
+#pragma unroll
+                for (int st = 0; st < W2R; ++st) fetch_w2(st, cb);
+            }
+            const int cm0 = cb * 32 + g * 16;                             // this lane's 16 mid channels
             f32x16b acc[NP];
-            const f32x16b bias2 = load_bias16(kCm + cm0);
-            const unsigned char *L = t1s + ((rh * (TS / 2) + prow) * S * kBT + pcol * S) * kPS + g * 16;
-            uint4 xf[2][NF], wl[2][3];
+            const f32x16b bias2 = load_bias16(CM + cm0);
+            const unsigned char *L = t1s + ((rh * (TS / 2) + prow) * S * kBT + pcol * S) * PS + g * 16;
+            // One set of fragments: a fragment is re-read for the next stage right after the last matrix step of this
+            // stage that takes it (the matrix unit has read its operands by then, the LDS answer comes later still);
+            // its next use is at least four matrix steps away.  (Two sets cost 36 registers more; the phase is the
+            // kernel's register peak.)
+            uint4 xf[NF], wl[2][3];
             // (kW2InLds) fragment r of stage st: tap (r, st / 4), k-step st % 4, this wave's half of the mid channels
             const uint4 *wlp = w2l + nh * 64 + lane;
-            VecIt nit1 = vec_begin(ngeo, NCH > 1 ? 1 : 0);
+            VecIt nit0 = vec_begin(ngeo, 0), nit1 = vec_begin(ngeo, NCH > 1 ? 1 : 0);
             static_assert(S == 1 || NF == 3, "with a stride a pixel block's three tap rows are three fragments of their own");
 #pragma unroll
-            for (int j = 0; j < NF; ++j) xf[0][j] = *(const uint4 *)(L + (j * kBT) * kPS);
+            for (int j = 0; j < NF; ++j) xf[j] = *(const uint4 *)(L + (j * kBT) * PS);
             if (kW2InLds) {
 #pragma unroll
                 for (int r = 0; r < 3; ++r) wl[0][r] = wlp[(r * 3 * 4) * 128];
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int st = 0; st < 12; ++st) {
-                const int tn = (st + 1) / 4, kcn = (st + 1) % 4;
+            for (int st = 0; st < NST; ++st) {
+                const int tn = (st + 1) / KT, kcn = (st + 1) % KT;
 #pragma unroll
                 for (int mm = 0; mm < 3 * NP; ++mm) {
                     const int r = mm / NP, P = mm % NP;
-                    acc[P] = mfma32<DT>(kW2InLds ? wl[st & 1][r] : w2s[st % W2R][r], xf[st & 1][RPF * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
-                    if (kW2InLds && mm < 3 && st + 1 < 12) wl[(st + 1) & 1][mm] = wlp[((mm * 3 + tn) * 4 + kcn) * 128];
-                    if (NCH > 1 && mm == 0 && st < NVX) fetch_vec(ngeo, 1, Slot1{}, st, has_next, nit1);
-                    if (mm < NF && st + 1 < 12)
-                        xf[(st + 1) & 1][mm] = *(const uint4 *)(L + (mm * kBT + tn) * kPS + kcn * 32);
-                    if (!kW2InLds && mm == 3 * NP - 1 && st + W2D < 12) fetch_w2(st + W2D);       // into the slot this stage just freed
+                    constexpr int kNoReload = -1;
+                    acc[P] = mfma32<DT>(kW2InLds ? wl[st & 1][r] : w2s[st % W2R][r], xf[RPF * P + r], (st == 0 && r == 0) ? bias2 : acc[P]);
+                    // fragment f = RPF * P + r also serves (r + RPF, P - 1), later in the stage, if that tap row exists
+                    const int f = RPF * P + r;
+                    const bool last_use = !(r + RPF <= 2 && P >= 1);
+                    const int reload = last_use && st + 1 < NST ? f : kNoReload;
+                    if (kW2InLds && mm < 3 && st + 1 < NST) wl[(st + 1) & 1][mm] = wlp[((mm * 3 + tn) * 4 + kcn) * 128];
+                    if (pass == 0 && mm == 0 && st < NVX) fetch_vec(ngeo, 0, Slot0{}, st, has_next, nit0);
+                    if (NCH > 1 && pass == 0 && mm == 1 && st < NVX) fetch_vec(ngeo, 1, Slot1{}, st, has_next, nit1);
+                    if (reload != kNoReload) xf[reload] = *(const uint4 *)(L + (reload * kBT + tn) * PS + kcn * 32);
+                    if (!kW2InLds && mm == 3 * NP - 1 && st + W2D < NST) fetch_w2(st + W2D, cb);       // into the slot this stage just freed
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -625,7 +658,7 @@ void bottleneck16_kernel(BneckParams p) {
 #pragma unroll
                 for (int k = 0; k < 8; ++k)
                     w[k] = relu_pack2<DT>(acc[P][2 * k], acc[P][2 * k + 1]);
-                uint4 *d = (uint4 *)(xs + po * kPS + cm0 * 2);
+                uint4 *d = (uint4 *)(xs + po * PS + cm0 * 2);
                 d[0] = make_uint4(w[0], w[1], w[2], w[3]);
                 d[1] = make_uint4(w[4], w[5], w[6], w[7]);
             }
@@ -639,10 +672,11 @@ void bottleneck16_kernel(BneckParams p) {
                 for (int j = 0; j < NBW; ++j) {
                     const int nbg = min(wave * NBW + j, NB3 - 1);         // this wave's neighbouring blocks of 32 channels
 #pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];
+                    for (int ks = 0; ks < 4; ++ks) w3r[ks][j] = w3s[(nbg * 4 + ks) * 64 + lane];     // (this form: KT = 4)
                 }
             }
             unsigned char *ost = t1s + wave * (64 * OPS);                 // t1 is dead: the wave's private staging area
+            if (!PRE) set_lane_off();
             // P3 is bound by LDS traffic, and accumulators that start from the bias read it from LDS in every pass (16
             // of a pass's 40 LDS instructions; kept in registers it would take 32 of them).  The bias is added by the
             // matrix unit instead: split into three bf16 / f16 pieces (b = p0 + p1 + p2 exactly for bf16: 3 x 8 bits
@@ -655,7 +689,7 @@ void bottleneck16_kernel(BneckParams p) {
                 onesB = g == 0 ? make_uint4(one | one << 16, one, 0u, 0u) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
                 for (int j = 0; j < NBW; ++j) {
-                    const float b = bias_s[2 * kCm + min(wave * NBW + j, NB3 - 1) * 32 + ol];
+                    const float b = bias_s[2 * CM + min(wave * NBW + j, NB3 - 1) * 32 + ol];
                     const uint32_t w0 = pack2<DT>(b, 0.f);
                     const float r1 = b - unpack_lo<DT>(w0);
                     const uint32_t w1 = pack2<DT>(r1, 0.f);
@@ -686,19 +720,19 @@ void bottleneck16_kernel(BneckParams p) {
             for (int bp = 0; bp < NPASS; ++bp)
 #pragma unroll
             for (int u0 = 0; u0 < 2; u0 += UB) {
-                uint4 tf[2][4];
+                uint4 tf[2][KT];
 #pragma unroll
                 for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
-                    for (int ks = 0; ks < 4; ++ks)
-                        tf[u][ks] = *(const uint4 *)(xs + ((2 * bp + u) * 32 + m) * kPS + ks * 32 + g * 16);
+                    for (int ks = 0; ks < KT; ++ks)
+                        tf[u][ks] = *(const uint4 *)(xs + ((2 * bp + u) * 32 + m) * PS + ks * 32 + g * 16);
                 f32x16b acc[2][NBW];
 #pragma unroll
                 for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
                     for (int j = 0; j < NBW; ++j) acc[u][j] = mfma32<DT>(biasA[j], onesB, zero16);
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
+                for (int ks = 0; ks < KT; ++ks)
 #pragma unroll
                     for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
@@ -747,30 +781,35 @@ void bottleneck16_kernel(BneckParams p) {
                         }
                     }
                 }
-                // MFMA layout -> LDS: lane (g, m) holds channels j*32 + g*16 .. + 16 of pixel u*32 + m
+                // MFMA layout -> LDS: lane (g, m) holds channels j*32 + g*16 .. + 16 of pixel u*32 + m; SB blocks of
+                // channels go through the staging area together (waves with three blocks: one at a time)
 #pragma unroll
-                for (int u = u0; u < u0 + UB; ++u)
+                for (int sg = 0; sg < NSG; ++sg) {
 #pragma unroll
-                    for (int j = 0; j < NBW; ++j) {
-                        uint32_t w[8];
+                    for (int u = u0; u < u0 + UB; ++u)
 #pragma unroll
-                        for (int k = 0; k < 8; ++k) w[k] = pack2<DT>(acc[u][j][2 * k], acc[u][j][2 * k + 1]);
-                        uint4 *d = (uint4 *)(ost + (u * 32 + m) * OPS + j * 64 + g * 32);
-                        d[0] = make_uint4(w[0], w[1], w[2], w[3]);
-                        d[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                        for (int jj = 0; jj < SB; ++jj) {
+                            const int j = sg * SB + jj;
+                            uint32_t w[8];
+#pragma unroll
+                            for (int k = 0; k < 8; ++k) w[k] = pack2<DT>(acc[u][j][2 * k], acc[u][j][2 * k + 1]);
+                            uint4 *d = (uint4 *)(ost + (u * 32 + m) * OPS + jj * 64 + g * 32);
+                            d[0] = make_uint4(w[0], w[1], w[2], w[3]);
+                            d[1] = make_uint4(w[4], w[5], w[6], w[7]);
+                        }
+                    // LDS -> store layout (LDS serves one wave's accesses in order: no wait between the two), add, store
+#pragma unroll
+                    for (int i = u0 * (NI / 2); i < (u0 + UB) * (NI / 2); ++i) {
+                        uint4 v = *(const uint4 *)(ost + (i * PPI + lane / CPP) * OPS + (lane % CPP) * 16);
+                        if (FUSED && !PROJ && PRE) {
+                            const uint4 rv = rres[bp][i];
+                            v.x = pack2<DT>(unpack_lo<DT>(v.x) + unpack_lo<DT>(rv.x), unpack_hi<DT>(v.x) + unpack_hi<DT>(rv.x));
+                            v.y = pack2<DT>(unpack_lo<DT>(v.y) + unpack_lo<DT>(rv.y), unpack_hi<DT>(v.y) + unpack_hi<DT>(rv.y));
+                            v.z = pack2<DT>(unpack_lo<DT>(v.z) + unpack_lo<DT>(rv.z), unpack_hi<DT>(v.z) + unpack_hi<DT>(rv.z));
+                            v.w = pack2<DT>(unpack_lo<DT>(v.w) + unpack_lo<DT>(rv.w), unpack_hi<DT>(v.w) + unpack_hi<DT>(rv.w));
+                        }
+                        bstore16(yrs, out_offset(bp, i) + (uint32_t)(sg * SB * 64), v);     // (out of range stays out of range)
                     }
-                // LDS -> store layout (LDS serves one wave's accesses in order: no wait between the two), add, store
-#pragma unroll
-                for (int i = u0 * (NI / 2); i < (u0 + UB) * (NI / 2); ++i) {
-                    uint4 v = *(const uint4 *)(ost + (i * PPI + lane / CPP) * OPS + (lane % CPP) * 16);
-                    if (FUSED && !PROJ && PRE) {
-                        const uint4 rv = rres[bp][i];
-                        v.x = pack2<DT>(unpack_lo<DT>(v.x) + unpack_lo<DT>(rv.x), unpack_hi<DT>(v.x) + unpack_hi<DT>(rv.x));
-                        v.y = pack2<DT>(unpack_lo<DT>(v.y) + unpack_lo<DT>(rv.y), unpack_hi<DT>(v.y) + unpack_hi<DT>(rv.y));
-                        v.z = pack2<DT>(unpack_lo<DT>(v.z) + unpack_lo<DT>(rv.z), unpack_hi<DT>(v.z) + unpack_hi<DT>(rv.z));
-                        v.w = pack2<DT>(unpack_lo<DT>(v.w) + unpack_lo<DT>(rv.w), unpack_hi<DT>(v.w) + unpack_hi<DT>(rv.w));
-                    }
-                    bstore16(yrs, out_offset(bp, i), v);
                 }
             }
         }
@@ -800,7 +839,13 @@ static sbnet_status launch_bneck_pre(int C, const BneckParams &p, dim3 grid, hip
         case 128: hipLaunchKernelGGL((bottleneck16_kernel<DT, 128, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
         case 192: hipLaunchKernelGGL((bottleneck16_kernel<DT, 192, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
         case 256: hipLaunchKernelGGL((bottleneck16_kernel<DT, 256, FUSED, TS, PRE>), grid, dim3(256), 0, s, p); break;
-        default: return fail(SBNET_EUNSUPPORTED, "%s: C must be 64, 96, 128, 192 or 256", who);
+        case 384:      // the wide form (width 65 .. 96): fused, 8 x 8 sub-tiles, no pre-activation; checked by the caller
+            if constexpr (FUSED && TS == 8 && !PRE) {
+                hipLaunchKernelGGL((bottleneck16_kernel<DT, 384, true, 8, false, 1, false, 384, 96>), grid, dim3(256), 0, s, p);
+                break;
+            }
+            return fail(SBNET_EUNSUPPORTED, "%s: C = 384 only as the fused unit without pre-activation", who);
+        default: return fail(SBNET_EUNSUPPORTED, "%s: C must be 64, 96, 128, 192, 256 or 384", who);
     }
     return launch_status(who);
 }
@@ -834,7 +879,12 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
     if (((uintptr_t)in | (uintptr_t)out | (uintptr_t)w1 | (uintptr_t)w2 | (uintptr_t)w3) & 15)
         return fail(SBNET_EINVAL, "%s: pointers must be 16-byte aligned", who);
     if (dt != SBNET_BF16 && dt != SBNET_F16) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be bf16 or f16", who);
-    if (Cm > kCm || Cm % 8) return fail(SBNET_EUNSUPPORTED, "%s: bottleneck width must be a multiple of 8, at most 64", who);
+    // widths up to 64 run on the kernel built for 64; C = 384 (the backbone's fourth stage, 384 / 96) on the one built for
+    // 96, which needs a width above 64 (its third block of mid channels must exist in the packed weights)
+    const bool wide = C == 384;
+    if (Cm % 8 || (wide ? (Cm <= kCm || Cm > 96) : Cm > kCm))
+        return fail(SBNET_EUNSUPPORTED, "%s: bottleneck width must be a multiple of 8, at most 64 (C = 384: 72 .. 96)", who);
+    if (wide && (!fused || pre_scale)) return fail(SBNET_EUNSUPPORTED, "%s: C = 384 only as the fused unit without pre-activation", who);
     if (g_out->bsize_h % 8 || g_out->bsize_w % 8)
         return fail(SBNET_EUNSUPPORTED, "%s: block sides must be multiples of 8", who);
     if (!packed_is_mfma(dt, C, Cm)) return fail(SBNET_EUNSUPPORTED, "%s: channel counts must be multiples of 8", who);
@@ -859,7 +909,7 @@ static sbnet_status bneck_entry(const char *who, bool fused, const void *in, voi
     // and a shorter latency chain each, which wins where the larger items leave most CUs idle or the last round of
     // them nearly empty.  The device decides from its count (see BneckParams); both variants are launched and one of
     // them returns at once (a few microseconds).
-    const bool can16 = g_out->bsize_h % 16 == 0 && g_out->bsize_w % 16 == 0;
+    const bool can16 = !wide && g_out->bsize_h % 16 == 0 && g_out->bsize_w % 16 == 0;
     const int cost8 = tuning().unit_small_item_cost_eighths;
     hipStream_t s = (hipStream_t)stream;
     for (int ts = 16; ts >= 8; ts -= 8) {
@@ -902,6 +952,10 @@ static sbnet_status launch_down(int C, int CO, const BneckParams &p, dim3 grid, 
     SBNET_DOWN(64, 128)
     SBNET_DOWN(128, 256)
 #undef SBNET_DOWN
+    if (C == 256 && CO == 384) {     // width 65 .. 96 (checked by the caller)
+        hipLaunchKernelGGL((bottleneck16_kernel<DT, 256, true, 8, false, 2, true, 384, 96>), grid, dim3(256), 0, s, p);
+        return launch_status(who);
+    }
     return fail(SBNET_EUNSUPPORTED, "%s: no one-launch downsampling unit for %d -> %d channels", who, C, CO);
 }
 
@@ -912,10 +966,11 @@ sbnet_status unit_down_try(const char *who, const void *x, sbnet_dtype dt, int N
                            void *stream) {
     // (the caller has checked pointers, sizes, that the geometries are those of a 3x3 with stride 2, and overlap)
     if (dt != SBNET_BF16 && dt != SBNET_F16) return fail(SBNET_EUNSUPPORTED, "%s: dtype must be bf16 or f16", who);
-    if (Cm > kCm || Cm % 8 || g_out->bsize_h % 8 || g_out->bsize_w % 8)
-        return fail(SBNET_EUNSUPPORTED, "%s: width a multiple of 8 up to 64 and block sides multiples of 8", who);
+    const bool wide = C == 256 && CO == 384 && Cm > kCm;        // the fourth stage's 256 -> 384 / 96
+    if (Cm % 8 || (wide ? Cm > 96 : Cm > kCm) || g_out->bsize_h % 8 || g_out->bsize_w % 8)
+        return fail(SBNET_EUNSUPPORTED, "%s: width a multiple of 8 up to 64 (256 -> 384: 72 .. 96) and block sides multiples of 8", who);
     const bool pair = (C == 64 && CO == 96) || (C == 96 && CO == 192) || (C == 192 && CO == 256) || (C == 64 && CO == 128) ||
-                      (C == 128 && CO == 256);
+                      (C == 128 && CO == 256) || wide;
     if (!pair) return fail(SBNET_EUNSUPPORTED, "%s: no one-launch downsampling unit for %d -> %d channels", who, C, CO);
     if (((uintptr_t)x | (uintptr_t)y | (uintptr_t)w1 | (uintptr_t)w2 | (uintptr_t)w3 | (uintptr_t)ws) & 15)
         return fail(SBNET_EUNSUPPORTED, "%s: pointers not 16-byte aligned", who);

@@ -275,6 +275,9 @@ GENERAL_UNIT_CASES = [
     (2, 258, 250, 64, 24, 96, 2, 8, True, "bf16"),     # more 8 x 8 items than workgroups: every workgroup loops over tiles
     (1, 100, 90, 128, 64, 256, 2, 24, True, "f16"),    # 3 x 3 sub-tiles per block, blocks over the edge, f16
     (1, 70, 70, 64, 32, 128, 2, 16, True, "f16"),
+    (2, 130, 130, 384, 96, 384, 1, 8, False, "bf16"),  # fourth stage as one launch (width above 64), more items than workgroups
+    (1, 50, 44, 384, 80, 384, 1, 16, False, "f16"),    # width 80, 16 x 16 blocks (8 x 8 sub-tiles)
+    (2, 260, 200, 256, 72, 384, 2, 8, True, "bf16"),   # its downsampling unit, width 72, every workgroup loops
 ]
 # shapes the one-launch downsampling unit serves (it needs no workspace: called without one below)
 ONE_LAUNCH_DOWN = {(64, 96), (96, 192), (192, 256), (64, 128), (128, 256)}
@@ -303,7 +306,9 @@ def test_sparse_unit_any_width_stride_and_shortcut(N, H, W, Cin, Cm, Cout, strid
         assert sb.read_count(d_cnt, d_idx.shape[0]) == len(idx)
         y0 = gen.activations(r, (N, Ho, Wo, Cout), dtype)
         y = to_dev(y0, dtype)
-        one_launch = stride == 2 and proj and (Cin, Cout) in ONE_LAUNCH_DOWN and Cm <= 64 and bo % 8 == 0
+        one_launch = stride == 2 and proj and bo % 8 == 0 and (((Cin, Cout) in ONE_LAUNCH_DOWN and Cm <= 64) or
+                                                               ((Cin, Cout) == (256, 384) and 64 < Cm <= 96))
+        one_launch = one_launch or (stride == 1 and not proj and Cin == 384 and 64 < Cm <= 96 and bo % 8 == 0)
         none = torch.empty((0,), dtype=torch.uint8, device="cuda")
         sb.sparse_unit(dx, d_idx, d_cnt, g_in, g_out, dws, y, stride=stride, shortcut=dsc, workspace=none if one_launch else None)
         got = to_host(y)
