@@ -493,11 +493,15 @@ sbnet_status sbnet_bottleneck_backward_on_tiles(const void *tiles_in, const void
  * stride 1 and Cin == Cout).  Pixels of y outside the active blocks are neither read nor written.
  * x: [N][H][W][Cin]; y: [N][H_out][W_out][Cout]; g_in / g_out from sbnet_geometry(H, W, 3, 3, stride, stride, ...).
  * y may be x only with the identity shortcut (the in-place scatter-add of Sec. 3.4).
- * Stride 1 with the identity, Cin in {64, 96, 128, 192, 256}, Cm <= 64 and y != x run as the one-kernel unit
- * (sbnet_sparse_bottleneck; workspace may then be NULL).  Every other shape runs as gather, the three
- * convolutions on tile stacks, the shortcut and one scatter-add, on tile stacks in `workspace`
- * (sbnet_sparse_unit_workspace_bytes, 256-byte aligned, contents don't-care): t1, t2 and t3 are rounded to
- * `dtype` between the steps, the shortcut is rounded before the branch is added.
+ * One launch, no workspace (it may be NULL), bf16 / f16, block sides multiples of 8, y != x:
+ *   - stride 1 with the identity: the shapes of sbnet_sparse_bottleneck (Cin in {64, 96, 128, 192, 256} with
+ *     Cm <= 64, Cin = 384 with Cm in 72 .. 96);
+ *   - stride 2 with a projected shortcut: Cin -> Cout in {64 -> 96, 96 -> 192, 192 -> 256, 64 -> 128, 128 -> 256}
+ *     with Cm <= 64, and 256 -> 384 with Cm in 72 .. 96 (the four downsampling units of the backbone of Sec. 4).
+ *   There x + branch (or shortcut + branch) is formed in fp32 and rounded once; t1 and t2 are rounded to `dtype`.
+ * Every other shape runs as gather, the three convolutions on tile stacks, the shortcut and one scatter-add, on
+ * tile stacks in `workspace` (sbnet_sparse_unit_workspace_bytes, 256-byte aligned, contents don't-care): t1, t2
+ * and t3 are rounded to `dtype` between the steps, the shortcut is rounded before the branch is added.
  */
 size_t sbnet_sparse_unit_workspace_bytes(sbnet_dtype dtype, int cap, const sbnet_geom *g_in,
                                          const sbnet_geom *g_out, int Cin, int Cm, int Cout);
@@ -532,8 +536,9 @@ sbnet_status sbnet_zero_outside(void *tiles, sbnet_dtype dtype, int H, int W, in
  * rounded to `dtype` between the layers; sums are fp32.
  * Supported: bf16 / f16, C in {64, 96, 128, 192, 256}, Cm a multiple of 8 up to 64 (the unit widths of
  * the detector backbone of Sec. 4 up to its third stage: 96/24, 192/48, 256/64), block sides multiples
- * of 8, input tile = block + one-pixel halo, one tile below 2^30 elements; anything else returns
- * SBNET_EUNSUPPORTED (sbnet_sparse_unit takes every width, strides and projected shortcuts).
+ * of 8, input tile = block + one-pixel halo, one tile below 2^30 elements; the fused call
+ * sbnet_sparse_bottleneck also takes the fourth stage's C = 384 with Cm a multiple of 8 in 72 .. 96; anything
+ * else returns SBNET_EUNSUPPORTED (sbnet_sparse_unit takes every width, strides and projected shortcuts).
  */
 sbnet_status sbnet_bottleneck_on_tiles(const void *tiles_in, sbnet_dtype dtype, int H, int W, int C,
                                        int Cm, const int32_t *indices, const int32_t *count, int cap,
@@ -551,9 +556,11 @@ sbnet_status sbnet_bottleneck_on_tiles(const void *tiles_in, sbnet_dtype dtype, 
  * buffer (SBNET_EINVAL if y == x).  For a stack of units sharing one index list, initialise
  * both buffers with the input once and alternate them: inactive pixels never change, and every
  * active pixel of the buffer being read was written by the previous unit.
- * t3 is rounded to `dtype` before the add, as the tile stack between sbnet_bottleneck_on_tiles and
- * sbnet_sparse_scatter holds it: both routes give the same bits.
- * Same support matrix as sbnet_bottleneck_on_tiles, with one sample (H * W * C) below 2^30 elements.
+ * x + t3 is formed in fp32 and rounded to `dtype` once (the route over sbnet_bottleneck_on_tiles and
+ * sbnet_sparse_scatter rounds t3 for its tile stack and the sum again: at most half a unit in the last place of
+ * t3 plus one of the sum apart).
+ * Support matrix of sbnet_bottleneck_on_tiles plus C = 384 with Cm in 72 .. 96; one sample (H * W * C) below
+ * 2^30 elements.
  */
 sbnet_status sbnet_sparse_bottleneck(const void *x, sbnet_dtype dtype, int N, int H, int W, int C,
                                      int Cm, const int32_t *indices, const int32_t *count, int cap,
@@ -569,7 +576,8 @@ sbnet_status sbnet_sparse_bottleneck(const void *x, sbnet_dtype dtype, int N, in
  * on the active blocks (Sec. 3.3 names the unit's layers - three convolutions, batch
  * normalisation, ReLU - without fixing their order; this is the order of pre-activation
  * residual networks).  pre_scale, pre_shift: device float32 [C].  Everything else as for
- * sbnet_bottleneck_on_tiles / sbnet_sparse_bottleneck, including the support matrix.
+ * sbnet_bottleneck_on_tiles / sbnet_sparse_bottleneck, including the support matrix (without C = 384); the
+ * fused form rounds t3 before the add, as the route over the tile stack does (same bits).
  */
 sbnet_status sbnet_bottleneck_on_tiles_preact(const void *tiles_in, sbnet_dtype dtype, int H, int W,
                                               int C, int Cm, const int32_t *indices,

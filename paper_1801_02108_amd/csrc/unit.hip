@@ -5,9 +5,10 @@
 //     y = shortcut(x) + W3 ReLU(W2 *_s zero_outside(ReLU(W1 x + b1)) + b2) + b3,
 // shortcut = a 1x1 convolution with the unit's stride (ws, bs) or the identity; other pixels of y stay.
 //
-// Shapes the one-kernel unit serves go to it: stride 1 with the identity shortcut, C in {64, 96, 128, 192, 256}, and
-// stride 2 with a projected shortcut, Cin -> Cout in {64->96, 96->192, 192->256, 64->128, 128->256}; width a multiple
-// of 8 up to 64, block sides multiples of 8, bf16 / f16.  Everything else runs as a sequence of the library's own calls on tile stacks in the caller's workspace,
+// Shapes the one-kernel unit serves go to it: stride 1 with the identity shortcut, C in {64, 96, 128, 192, 256} (width
+// a multiple of 8 up to 64) and C = 384 (width 72 .. 96), and stride 2 with a projected shortcut, Cin -> Cout in
+// {64->96, 96->192, 192->256, 64->128, 128->256} (width up to 64) and 256->384 (width 72 .. 96); block sides multiples
+// of 8, bf16 / f16.  Everything else runs as a sequence of the library's own calls on tile stacks in the caller's workspace,
 // no kernel lives here:
 //     gather (input tile) -> 1x1 + ReLU -> zero outside the image -> 3x3 with stride + ReLU -> 1x1
 //     shortcut:  projection: the fused 1x1 convolution with stride writes y's active blocks;
