@@ -1,15 +1,17 @@
 // Sparse residual (bottleneck) unit on tiles (Sec. 3.3, Fig. 4 of arXiv 1801.02108): the three
 // convolutions of a ResNet bottleneck (1x1 C->Cm + ReLU, 3x3 Cm->Cm + ReLU, 1x1 Cm->C; batch norm
 // folded into weights and bias) share one gather and one scatter-add (Sec. 3.4).  C is 64, 96, 128, 192 or
-// 256 (the widths of the detector backbone's stages, Sec. 4, up to its third), Cm any multiple of 8 up to
-// 64 (a narrower unit runs as width 64 on zero-padded weights).  The receptive
-// field of the whole unit is that of its single 3x3, so the input tile is block + 1-pixel halo.
+// 256 with Cm any multiple of 8 up to 64 (a narrower unit runs as width 64 on zero-padded weights), or 384
+// with Cm in 72 .. 96: the widths of the four stages of the detector backbone of Sec. 4.  The receptive
+// field of the whole unit is that of its single 3x3, so the input tile is block + 1-pixel halo.  The same
+// kernel, with a stride of 2 in the 3x3, more output than input channels and a projected shortcut, is the
+// downsampling unit that opens a stage (template parameters S, PROJ, CO below).
 //
 // One kernel per unit; per TS x TS output sub-tile (TS = 16, or 8 for blocks that are no multiple of 16
 // and for problems with too few 16x16 sub-tiles to occupy the device) and workgroup (4 waves, one per
-// SIMD).  The 1x1 weights W1, W3 and the biases stay in LDS for the life of the workgroup (MFMA operand
-// order); W2 (the 3x3, 72 KB) is re-read from L2 for every tile, through a ring of registers a few
-// stages ahead of P2's matrix work:
+// SIMD).  W1 and the biases stay in LDS for the life of the workgroup (MFMA operand order).  16-pixel
+// sub-tiles keep W3 there too and re-read W2 (the 3x3, 72 KB) from L2 for every tile, through a ring of
+// registers a few stages ahead of P2's matrix work; 8-pixel sub-tiles keep W2 in LDS and read W3 from L2:
 //   P1  t1 = ReLU(W1 x + b1) on the (TS+2)^2 input sub-tile.  x passes through LDS in 64-channel
 //       chunks: eight lanes read one pixel's 128 contiguous bytes (8 full cache lines per wave
 //       instruction; loading the 32x32x16 B operand directly touches 32 lines for the same 1 KB and
@@ -397,10 +399,10 @@ void bottleneck16_kernel(BneckParams p) {
     __syncthreads();                                 // weights and biases visible to every wave
 
     for (uint32_t it = first; it < items; it += G) {
-        // conv2's weights for this wave's 32 output channels are re-read from L2 for every tile, three fragments per
-        // stage of P2.  16-pixel sub-tiles: a ring of W2R stages, W2D stages requested ahead (holding all 36 fragments
-        // would cost 144 registers that the residual needs); 8-pixel sub-tiles: a stage is too short for that,
-        // everything is requested before P2.
+        // Where conv2's weights do not live in LDS (16-pixel sub-tiles, the strided and the wide form) they are re-read
+        // from L2 for every tile, three fragments per stage of P2 for this wave's 32 output channels, through a ring of
+        // W2R stages, W2D stages requested ahead (holding all 36 fragments would cost 144 registers that the residual
+        // needs; 8-pixel sub-tiles of the strided form, whose stages are short, hold them all).
         uint4 w2s[W2R][3];
         const uint4 *w2p = (const uint4 *)p.w2 + p.w2_off;                        // wave-uniform
         asm volatile("" : "+s"(w2p));      // opaque per iteration: keeps the loads inside the tile loop
@@ -460,10 +462,10 @@ void bottleneck16_kernel(BneckParams p) {
             // (an out-of-range lane part stays out of range: the sum is below 2^32)
             return lane_off[NCOLV == 2 ? (i & 1) : 0] + (uint32_t)rowc * out_row_bytes;
         };
-        // residual x of the block (fused form), in that layout.  It is requested in the middle of P1, when half of the
-        // tile's chunks have just come through L2 and the other half is about to: each of its cache lines then crosses
-        // the memory fabric once.  (Requested after P1, half of the block had been evicted again: L2 holds about
-        // 3 microseconds of this kernel's traffic, P1 alone takes 7.)
+        // residual x of the block with a pre-activation (the LDS copy of x is the transformed one): read again, in the
+        // store layout, in the middle of P1, when half of the tile's chunks have just come through L2 and the other
+        // half is about to, so that each of its cache lines crosses the memory fabric once.  (Requested after P1, half
+        // of the block had been evicted again: L2 holds about 3 microseconds of this kernel's traffic.)
         constexpr int NPASS = NPB / 2;
         uint4 rres[NPASS][NI];                   // pre-activation form: x in the store layout
         uint4 rb[NPASS][2][NBW][2];              // otherwise: x as MFMA B operands (see below)
@@ -502,7 +504,7 @@ void bottleneck16_kernel(BneckParams p) {
 
         // ================= P1: t1 = ReLU(W1 x + b1), zero outside the image =================
         // x passes through LDS in 64-channel chunks: coalesced global loads -> registers -> xs -> MFMA B operands.
-        // Wave w owns pixel blocks w, w+4, w+8 (32 pixels each, row-major over the 18x18 tile) and all 64 outputs.
+        // Wave w owns pixel blocks w, w+4, w+8 (32 pixels each, row-major over the input sub-tile) and all mid channels.
         {
             f32x16b acc[NBPW1][NMB];
 #pragma unroll
