@@ -132,16 +132,35 @@ def run_units(args):
             m_d = torch.from_numpy(m_np).to(dev)
             n = count_active(m_np)
 
-            def step():
-                if thr_t is not None:   # dynamic mask: threshold the low-resolution logits, upsample x8 (mask source)
-                    md = (logits > thr_t).to(torch.uint8).repeat_interleave(8, 1).repeat_interleave(8, 2)
+            # dynamic mask, two routes to the same block list: (a) threshold the low-resolution logits, upsample x8 by
+            # pixel repetition (torch: the mask source), reduce the full-resolution mask; (b) reduce the logit map itself:
+            # max-pool over the coarse cells each block window touches, against the same threshold (threshold >= 0)
+            coarse = thr_t is not None and thr_t >= 0.0
+            g_coarse = sb.coarse_geometry(g_in, 8) if coarse else None
+
+            def step(lowres=False):
+                if thr_t is not None and lowres:
+                    sb.reduce_mask(logits, g_coarse, sb.POOL_MAX, thr_t, idx, cnt, ws)
                 else:
-                    md = m_d
-                sb.reduce_mask(md, g_in, sb.POOL_AVG, 0.0, idx, cnt, ws)
+                    if thr_t is not None:
+                        md = (logits > thr_t).to(torch.uint8).repeat_interleave(8, 1).repeat_interleave(8, 2)
+                    else:
+                        md = m_d
+                    sb.reduce_mask(md, g_in, sb.POOL_AVG, 0.0, idx, cnt, ws)
                 a, b = bufs
                 for u in units:
                     sb.sparse_bottleneck(a, idx, cnt, g_in, g_out, u, b)
                     a, b = b, a
+
+            ms_coarse = None
+            if coarse:
+                step(False)
+                ref_idx, ref_n = idx.clone(), sb.read_count(cnt, total)
+                step(True)
+                same = ref_n == sb.read_count(cnt, total) and bool((idx[:ref_n] == ref_idx[:ref_n]).all().item())
+                if not same:
+                    raise RuntimeError("coarse-map reduce_mask disagrees with the upsampled mask")
+                bufs[1].copy_(bufs[0])
 
             for _ in range(3):
                 step()
@@ -154,6 +173,15 @@ def run_units(args):
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / iters
+            if coarse:
+                for _ in range(2):
+                    step(True)
+                e0.record()
+                for _ in range(iters):
+                    step(True)
+                e1.record()
+                torch.cuda.synchronize()
+                ms_coarse = e0.elapsed_time(e1) / iters
             # the unit kernel alone, and in pre-activation form (ReLU(scale * x + shift) in front of conv1): device time
             # from graph replays (eager launches of a 10 us kernel would time the host), eager under the profiler
             u0 = units[0]
@@ -181,6 +209,8 @@ def run_units(args):
                          "unit_tflops": round(unit_flops(bo) * n / k_ms / 1e9, 2),
                          "unit_hbm_GBps_algorithmic": round(unit_bytes(bo) * n / k_ms / 1e6, 1),
                          "speedup_vs_own_dense": round(dense_ms / ms, 3), "ideal_speedup": round(total / max(n, 1), 2)})
+            if ms_coarse is not None:      # same block list from the 1/8-resolution logit map without the upsampled mask
+                rows[-1]["step_ms_mask_reduced_at_logit_resolution"] = round(ms_coarse, 5)
             bufs[1].copy_(bufs[0])
     # MIOpen dense unit through torch, external baseline only (3 convs + ReLUs + add)
     miopen_ms = None

@@ -92,6 +92,18 @@ const char *sbnet_last_error(void);
 sbnet_status sbnet_geometry(int H, int W, int kh, int kw, int sh, int sw, int bo_h, int bo_w,
                             sbnet_geom *g_in, sbnet_geom *g_out, int *H_out, int *W_out);
 
+/*
+ * Geometry of the same block windows on a mask that is given `factor` times coarser and meant to be upsampled by
+ * pixel repetition (a mask predicted at lower resolution: Sec. 3.1 reduces "the mask" whatever made it; the
+ * benchmark configuration with a 1/8-resolution logit map is the case in point).  Window b of `g` covers the coarse
+ * cells its pixels fall into, so
+ *     sbnet_reduce_mask(coarse_map, ..., coarse, SBNET_POOL_MAX, t, ...)
+ * lists exactly the blocks that thresholding the coarse map at t, upsampling it and reducing the result with `g`
+ * (either pooling, threshold 0) lists, for t >= 0 (cells outside the map count as 0 in both), without the
+ * upsampled mask ever existing.  Host arithmetic only.  g->bstride_* must be multiples of factor (SBNET_EINVAL).
+ */
+sbnet_status sbnet_coarse_geometry(const sbnet_geom *g, int factor, sbnet_geom *coarse);
+
 /* Bytes of device scratch sbnet_reduce_mask needs for N samples and geometry g (host call). */
 size_t sbnet_workspace_bytes(int N, const sbnet_geom *g);
 

@@ -52,6 +52,7 @@ _SIGNATURES = {
     "sbnet_set_tuning": (_ci, [ctypes.POINTER(Tuning)]),
     "sbnet_get_tuning": (_ci, [ctypes.POINTER(Tuning)]),
     "sbnet_geometry": (_ci, [_ci] * 8 + [_gp, _gp, ctypes.POINTER(_ci), ctypes.POINTER(_ci)]),
+    "sbnet_coarse_geometry": (_ci, [_gp, _ci, _gp]),
     "sbnet_workspace_bytes": (_sz, [_ci, _gp]),
     "sbnet_reduce_mask": (_ci, [_vp, _ci, _ci, _ci, _ci, _gp, _ci, ctypes.c_float, _vp, _vp, _ci, _vp, _sz, _vp]),
     "sbnet_reduce_mask_static": (_ci, [_vp, _ci, _ci, _ci, _ci, _gp, _ci, ctypes.c_float, _vp, _vp, _ci, _vp]),
@@ -190,6 +191,13 @@ def geometry(H, W, k, s, bo):
     g_in, g_out, ho, wo = Geom(), Geom(), _ci(), _ci()
     _check(lib().sbnet_geometry(H, W, k, k, s, s, bo, bo, g_in, g_out, ho, wo))
     return g_in, g_out, ho.value, wo.value
+
+
+def coarse_geometry(g, factor):
+    """Geometry of the same block windows on a map `factor` times coarser (sbnet_coarse_geometry)."""
+    c = Geom()
+    _check(lib().sbnet_coarse_geometry(g, factor, c))
+    return c
 
 
 def workspace_bytes(N, g):

@@ -78,6 +78,27 @@ extern "C" sbnet_status sbnet_geometry(int H, int W, int kh, int kw, int sh, int
     return SBNET_OK;
 }
 
+static int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
+
+extern "C" sbnet_status sbnet_coarse_geometry(const sbnet_geom *g, int factor, sbnet_geom *coarse) {
+    if (!g || !coarse) return fail(SBNET_EINVAL, "sbnet_coarse_geometry: null geometry pointer");
+    if (factor <= 0 || g->bsize_h <= 0 || g->bsize_w <= 0 || g->bstride_h <= 0 || g->bstride_w <= 0)
+        return fail(SBNET_EINVAL, "sbnet_coarse_geometry: sizes must be positive");
+    if (g->bstride_h % factor || g->bstride_w % factor)
+        return fail(SBNET_EINVAL, "sbnet_coarse_geometry: the block stride must be a multiple of the factor");
+    // window b covers pixels [o + b S, o + b S + B): the cells floor(first / f) .. floor(last / f); S is a multiple
+    // of f, so the count of cells is the same for every b
+    coarse->boffset_h = floor_div(g->boffset_h, factor);
+    coarse->boffset_w = floor_div(g->boffset_w, factor);
+    coarse->bsize_h = floor_div(g->boffset_h + g->bsize_h - 1, factor) - coarse->boffset_h + 1;
+    coarse->bsize_w = floor_div(g->boffset_w + g->bsize_w - 1, factor) - coarse->boffset_w + 1;
+    coarse->bstride_h = g->bstride_h / factor;
+    coarse->bstride_w = g->bstride_w / factor;
+    coarse->bcount_h = g->bcount_h;
+    coarse->bcount_w = g->bcount_w;
+    return SBNET_OK;
+}
+
 extern "C" sbnet_status sbnet_read_count(const int32_t *count, int cap, int *host_count, void *stream) {
     if (!count || !host_count) return fail(SBNET_EINVAL, "sbnet_read_count: null pointer");
     int32_t v = 0;

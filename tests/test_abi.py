@@ -42,6 +42,24 @@ def test_geometry_rejects_bad_sizes():
     assert e.value.code == sb.EINVAL and "positive" in str(e.value)
 
 
+@pytest.mark.parametrize("k,s,bo,factor", [(3, 1, 16, 8), (3, 1, 8, 4), (3, 2, 8, 8), (5, 1, 16, 2), (3, 1, 24, 8), (1, 1, 8, 8)])
+def test_coarse_geometry_covers_the_cells_each_window_touches(k, s, bo, factor):
+    """sbnet_coarse_geometry against brute force: the cells a window's pixels fall into, block by block."""
+    g_in, _, _, _ = sb.geometry(160, 96, k, s, bo)
+    c = sb.coarse_geometry(g_in, factor)
+    assert (c.bcount_h, c.bcount_w) == (g_in.bcount_h, g_in.bcount_w)
+    for size, stride, off, csize, cstride, coff, cnt in (
+            (g_in.bsize_h, g_in.bstride_h, g_in.boffset_h, c.bsize_h, c.bstride_h, c.boffset_h, g_in.bcount_h),
+            (g_in.bsize_w, g_in.bstride_w, g_in.boffset_w, c.bsize_w, c.bstride_w, c.boffset_w, g_in.bcount_w)):
+        for b in range(cnt):
+            cells = sorted({(off + b * stride + i) // factor for i in range(size)})     # Python's // floors
+            assert cells == list(range(coff + b * cstride, coff + b * cstride + csize)), (b, cells)
+    # a block stride that is no multiple of the factor has no such geometry
+    g3, _, _, _ = sb.geometry(160, 96, 3, 1, 12)
+    with pytest.raises(sb.SbnetError):
+        sb.coarse_geometry(g3, 8)
+
+
 def test_size_queries():
     g_in, _, _, _ = sb.geometry(800, 704, 3, 1, 16)
     ws = sb.workspace_bytes(8, g_in)

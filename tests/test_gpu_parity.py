@@ -85,6 +85,25 @@ def test_reduce_mask_real_valued_max_and_avg():
         assert list(map(tuple, idx[:n].cpu().numpy())) == sorted(got)
 
 
+@pytest.mark.parametrize("N,h,w,factor,bo,quant", [(2, 25, 22, 8, 16, 0.85), (1, 13, 9, 8, 8, 0.5), (3, 20, 12, 4, 16, 0.97), (1, 10, 11, 8, 16, 0.0)])
+def test_reduce_mask_on_a_coarse_map_equals_reducing_its_upsampled_threshold(N, h, w, factor, bo, quant):
+    """A mask predicted at 1/factor resolution (config 5: a logit map, thresholded and upsampled by pixel repetition):
+    max-pooling the coarse map over sbnet_coarse_geometry's windows lists the blocks of the upsampled binary mask."""
+    step("reduce_mask on a coarse map %s" % ((N, h, w, factor, bo, quant),))
+    r = gen.rng_for(5, 40 + h + w + bo)
+    logits = r.standard_normal((N, h, w)).astype(np.float32)
+    thr = max(float(np.quantile(logits, quant)), 0.0) if quant > 0 else 0.0
+    H, W = h * factor, w * factor
+    g_in, _, _, _ = sb.geometry(H, W, 3, 1, bo)
+    mask = np.repeat(np.repeat((logits > thr).astype(np.uint8), factor, axis=1), factor, axis=2)
+    ref = orc.reduce_mask(mask, ogeom(g_in))
+    i_up, c_up = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in)
+    i_lo, c_lo = sb.reduce_mask(torch.from_numpy(logits).cuda(), sb.coarse_geometry(g_in, factor), sb.POOL_MAX, thr)
+    n = sb.read_count(c_up, i_up.shape[0])
+    assert n == len(ref) == sb.read_count(c_lo, i_lo.shape[0])
+    assert np.array_equal(i_up.cpu().numpy()[:n], ref) and np.array_equal(i_lo.cpu().numpy()[:n], ref)
+
+
 def test_reduce_mask_negative_values_max_pool_counts_outside_as_zero():
     step("reduce_mask negative values")
     H, W, bo = 16, 16, 4
