@@ -76,7 +76,14 @@ struct Chunk3 {
 
 // KH = 3: the 3x3 kernel this file is named for; KH = 1: pointwise convolutions through the same pipeline (one tap,
 // chunks of 64 channels so that a chunk still holds several MFMA steps; of 32 for channel counts that need it).
-template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI, int KH = 3>
+//
+// SPEC: the workgroup has eight waves, two per SIMD, with separate roles.  Waves 0-3 only read fragments from LDS,
+// run the matrix steps and store the results; waves 4-7 only move chunks (memory -> registers -> LDS).  A wave is
+// held at the issue of a load while the CU's address unit is busy and at the wait in front of an LDS write, and with
+// one wave per SIMD the matrix core stood idle through both: per chunk the kernel took about the SUM of its matrix,
+// LDS and load time.  With the roles in different waves of the same SIMD they overlap.  Both roles walk the same
+// chunk sequence and meet at the same barrier per chunk.
+template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI, int KH = 3, bool SPEC = false>
 __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) {
     static_assert(FUSED || !ADD, "adding into the output is part of the fused form");
     // Register sets for chunks in flight.  Two (requests two chunks further ahead) were measured for the small
@@ -98,8 +105,12 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
     constexpr int D = D0 < NS ? D0 : NS - 1;         // steps the fragment reads run ahead of the MFMAs
     extern __shared__ __align__(16) unsigned char lds[];
 
+    constexpr int NT = SPEC ? 512 : 256;             // threads of the workgroup
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool mover = !SPEC || wave_all >= 4;       // stages chunks
+    const int wave = wave_all & 3;                   // number among the waves of its role
+    const int stid = tid & 255;                      // ... thread among the 256 that stage
     const int g = lane >> 5, m = lane & 31;          // k-group / channel half, pixel within a fragment
     const int pw = wave % WP, cw = wave / WP;
     const int M = p.oh * p.ow;
@@ -173,26 +184,26 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
     //      LDS address of a vector = lbase + (buffer number) * lstep.
     uint32_t gdelta[NVI], lbase[NV], lstep[NV], wsrc[NVW];
     int colv[NVI];
-    const int c8 = tid % CV;
+    const int c8 = stid % CV;
     const int cin16 = p.CinP >> 4;
 #pragma unroll
     for (int u = 0; u < NVI; ++u) {
-        const uint32_t v = (uint32_t)tid + 256u * u;
+        const uint32_t v = (uint32_t)stid + 256u * u;
         const uint32_t px = v / CV;
         const uint32_t row = fdiv(px, p.div_tw), col = px - row * p.tw;
         const uint32_t cq = fdiv(col, q.div_sw), cr = col - cq * p.sw;
         const bool ok = v < q.nvec_in;
-        lbase[u] = ok ? ((row * p.sw + cr) * q.cpp + cq) * PS + c8 * 16 : q.dump_off + tid * 16;
+        lbase[u] = ok ? ((row * p.sw + cr) * q.cpp + cq) * PS + c8 * 16 : q.dump_off + stid * 16;
         lstep[u] = ok ? q.buf_bytes : 0u;
         gdelta[u] = (uint32_t)((row * in_w + col) * p.Cin + c8 * 8) * 2u;
         colv[u] = ok ? (int)col : 0x40000000;
     }
 #pragma unroll
     for (int u = 0; u < NVW; ++u) {
-        const uint32_t v = (uint32_t)tid + 256u * u;
+        const uint32_t v = (uint32_t)stid + 256u * u;
         const uint32_t tap = v / (KST * 128), rem = v % (KST * 128);
         const bool ok = v < (uint32_t)WVEC;
-        lbase[NVI + u] = ok ? q.w_off + v * 16 : q.dump_off + tid * 16;
+        lbase[NVI + u] = ok ? q.w_off + v * 16 : q.dump_off + stid * 16;
         lstep[NVI + u] = ok ? q.buf_bytes : 0u;
         wsrc[u] = ok ? (tap * cin16 * 128u + rem) * 16u : kOutOfRange;
     }
@@ -256,17 +267,19 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
 
     // chunk k lives in register set k % RS: chunks 0 .. RS-1 are requested at once, chunk 0 goes to LDS buffer 0 and
     // chunk RS takes its registers
+    if (mover) {
 #pragma unroll
-    for (int r = 0; r < RS; ++r) {
-        const Chunk3 ch = chunk_of(line[r].s, line[r].c);
-        const bool chan_ok = ch.c0 + c8 * 8 < p.Cin;
+        for (int r = 0; r < RS; ++r) {
+            const Chunk3 ch = chunk_of(line[r].s, line[r].c);
+            const bool chan_ok = ch.c0 + c8 * 8 < p.Cin;
 #pragma unroll
-        for (int u = 0; u < NV; ++u) issue1(r, u, ch, chan_ok);
+            for (int u = 0; u < NV; ++u) issue1(r, u, ch, chan_ok);
+        }
     }
     // bias of all groups -> LDS (zeros past Cout or without bias)
     {
         float *bl = (float *)(lds + q.bias_off);
-        for (int i = tid; i < q.ngroups * 64; i += 256) bl[i] = (p.bias && i < p.Cout) ? p.bias[i] : 0.f;
+        for (int i = tid; i < q.ngroups * 64; i += NT) bl[i] = (p.bias && i < p.Cout) ? p.bias[i] : 0.f;
     }
     // tap offsets in the de-interleaved layout
     uint32_t tapoff[TAPS];
@@ -278,9 +291,9 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
     asm volatile("" : "+s"(floor16));
     int floor_i = p.relu ? 0 : (int)0x80000000;
     asm volatile("" : "+s"(floor_i));
+    if (mover) {
 #pragma unroll
-    for (int u = 0; u < NV; ++u) write1(0, u, 0);
-    {
+        for (int u = 0; u < NV; ++u) write1(0, u, 0);
         const Chunk3 ch = chunk_of(line[RS].s, line[RS].c);
         const bool chan_ok = ch.c0 + c8 * 8 < p.Cin;
 #pragma unroll
@@ -293,9 +306,12 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
     f32x16 acc[CBW][PBW];
     uint32_t p_lo = 0;
     uint32_t xbase[PBW];
-    // one chunk: register set R = (gi + 1) % RS holds chunk gi + 1 on entry and chunk gi + RS + 1 on exit
-    auto chunk_body = [&](auto r_tag, uint32_t gi) __attribute__((always_inline)) {
+    // one chunk: register set R = (gi + 1) % RS holds chunk gi + 1 on entry and chunk gi + RS + 1 on exit.
+    // ROLE 0: matrix steps with the staging between them; 1: matrix steps and results only; 2: staging only.
+    auto chunk_body = [&](auto r_tag, auto role_tag, uint32_t gi) __attribute__((always_inline)) {
         constexpr int R = decltype(r_tag)::value;
+        constexpr int ROLE = decltype(role_tag)::value;
+        constexpr bool MM = ROLE != 2, ST = ROLE != 1;
         const Work3 rq = request_chunk(gi + RS + 2);
         const Work3 cur = line[0];
         const bool firstc = cur.c == 0, lastc = cur.c + 1 == q.nchunks;
@@ -303,7 +319,14 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
             const Chunk3 aheadc = chunk_of(line[RS + 1].s, line[RS + 1].c);
             const bool chan_ok = aheadc.c0 + c8 * 8 < p.Cin;
             const unsigned char *B = lds + par * q.buf_bytes;
-            if (firstc) {
+            if (!MM) {
+#pragma unroll
+                for (int u = 0; u < NV; ++u) {
+                    write1(R, u, par ^ 1u);
+                    issue1(R, u, aheadc, chan_ok);
+                }
+            }
+            if (MM && firstc) {
                 // this lane's pixels: block pb of the wave is 32 consecutive output pixels of the pass
                 p_lo = (uint32_t)cur.it.pass * PP;
                 const uint32_t i_lo = fdiv(p_lo, p.div_ow);
@@ -333,7 +356,7 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
             //      B = 32 pixels x 16 k; fragment reads run D steps ahead.  Between the MFMAs of a step: PER
             //      staging vectors of the next chunk go to the other buffer and are requested again for the
             //      chunk after it.
-            {
+            if (MM) {
                 const unsigned char *WL = B + q.w_off + (cw * CBW) * 1024 + lane * 16;
                 uint4 xa[D + 1][CBW], xb[D + 1][PBW];
                 auto read = [&](int s) __attribute__((always_inline)) {
@@ -355,7 +378,7 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
 #pragma unroll
                         for (int pb = 0; pb < PBW; ++pb) {
                             acc[cb][pb] = mfma32x32x16<DT>(xa[s % (D + 1)][cb], xb[s % (D + 1)][pb], acc[cb][pb]);
-                            if (cb * PBW + pb < PER) {
+                            if (ST && cb * PBW + pb < PER) {
                                 const int u = s * PER + cb * PBW + pb;
                                 if (u < NV) {
                                     write1(R, u, par ^ 1u);
@@ -363,7 +386,7 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
                                 }
                             }
                         }
-                    if (PER > NM) {
+                    if (ST && PER > NM) {
 #pragma unroll
                         for (int e = NM; e < PER; ++e) {
                             const int u = s * PER + e;
@@ -382,7 +405,7 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
             //      LDS area and come back as 64 contiguous bytes per four lanes.  Pixels past the end of the tile,
             //      columns outside the image and channels past Cout get the out-of-range offset; rows outside fall
             //      outside the descriptor.
-            if (lastc) {
+            if (MM && lastc) {
                 uint16_t *obase = (uint16_t *)p.out;
                 uint32_t obytes, origin;
                 int ox0 = 0, out_w;
@@ -468,16 +491,21 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
         for (int k = 0; k < RS + 1; ++k) line[k] = line[k + 1];
         line[RS + 1] = nxt;
     };
-    for (uint32_t gi = 0; gi < nwork; gi += RS) {
-        chunk_body(std::integral_constant<int, 1 % RS>{}, gi);
-        if (RS > 1 && gi + 1 < nwork) chunk_body(std::integral_constant<int, 0>{}, gi + 1);
+    static_assert(RS == 1, "the loops below step one chunk at a time");
+    using Set0 = std::integral_constant<int, 0>;
+    if (!SPEC) {
+        for (uint32_t gi = 0; gi < nwork; ++gi) chunk_body(Set0{}, std::integral_constant<int, 0>{}, gi);
+    } else if (wave_all < 4) {
+        for (uint32_t gi = 0; gi < nwork; ++gi) chunk_body(Set0{}, std::integral_constant<int, 1>{}, gi);
+    } else {
+        for (uint32_t gi = 0; gi < nwork; ++gi) chunk_body(Set0{}, std::integral_constant<int, 2>{}, gi);
     }
 }
 
-template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI, int KH = 3>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void conv3_kernel(ConvParams p, Plan3 q) {
-    conv3_body<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI, KH>(p, q);
+    conv3_body<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI, 3, true>(p, q);
 }
 
 // Pointwise convolutions wait on memory, not on the matrix cores: their kernel is built for two workgroups per CU
@@ -485,20 +513,20 @@ void conv3_kernel(ConvParams p, Plan3 q) {
 template <int DT, bool FUSED, bool ADD, int CC, int WP, int CBW, int PBW, int NVI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void conv3_pointwise_kernel(ConvParams p, Plan3 q) {
-    conv3_body<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI, 1>(p, q);
+    conv3_body<DT, FUSED, ADD, CC, WP, CBW, PBW, NVI, 1, false>(p, q);
 }
 
 // The 256-pixel and the 128-pixel tile shape in one launch: the device-side count picks one (rounds of work on 256
 // CUs with either shape; an item of the smaller tile costs about 5/8 of a larger one: half the matrix work, the same
 // weights to stage; the ratio comes with the launch, in eighths).  Two separate launches, of which one returns, cost a launch more.
 template <int DT, bool FUSED, bool ADD, int CCB, int NVIB, int CCS, int NVIS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void conv3_pair_kernel(ConvParams p, Plan3 qb, Plan3 qs) {
     const int nact = max(min(*p.count, p.cap), 0);
     const uint32_t per_big = (uint32_t)qb.mpasses * qb.ngroups, per_small = (uint32_t)qs.mpasses * qs.ngroups;
     const uint32_t rb = ((uint32_t)nact * per_big + 255u) >> 8, rs = ((uint32_t)nact * per_small + 255u) >> 8;
-    if ((unsigned long long)rb * 8u <= (unsigned long long)rs * (uint32_t)p.small_cost8) conv3_body<DT, FUSED, ADD, CCB, 4, 2, 2, NVIB>(p, qb);
-    else conv3_body<DT, FUSED, ADD, CCS, 4, 2, 1, NVIS>(p, qs);
+    if ((unsigned long long)rb * 8u <= (unsigned long long)rs * (uint32_t)p.small_cost8) conv3_body<DT, FUSED, ADD, CCB, 4, 2, 2, NVIB, 3, true>(p, qb);
+    else conv3_body<DT, FUSED, ADD, CCS, 4, 2, 1, NVIS, 3, true>(p, qs);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -573,7 +601,7 @@ static void launch3_cc(const ConvParams &p, const Shape3 &sh, int grid, hipStrea
         if (sh.lds_bytes > 48 * 1024)                                                                          \
             (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,          \
                                       (int)sh.lds_bytes);                                                      \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), sh.lds_bytes, s, p, sh.q);                             \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(512), sh.lds_bytes, s, p, sh.q);                             \
     } while (0)
     if (p.kh == 1) {                                  // pointwise
 #define SBNET_L1(CC, NVI)                                                                                      \
@@ -629,7 +657,7 @@ static void launch3_pair_small(const ConvParams &p, const Shape3 &big, const Sha
             (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         ConvParams pt = p;                                                                                     \
         pt.small_cost8 = tuning().conv3_small_item_cost_eighths;                                               \
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, pt, big.q, small.q);                           \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(512), lds, s, pt, big.q, small.q);                           \
     } while (0)
     if (small.cc == 32 && small.nvi == 3) SBNET_L3P(32, 3);
     else if (small.cc == 32) SBNET_L3P(32, 6);
