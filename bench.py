@@ -42,6 +42,9 @@ def parse():
                          "per-node instrumentation inflates kernels replayed from a graph)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy: a known-size reference for scaling HBM byte counters")
+    ap.add_argument("--stage", type=int, default=-1, help="stages workload: only this entry of its shape list")
+    ap.add_argument("--conv-only", action="store_true",
+                    help="stages workload: only the fused convolution with every block active (for counter runs)")
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "stages", "backward", "tune"],
                     help="cfg2 (default) is the headline single 3x3 conv; cfg3/4/5 are the residual-unit workloads; "
                          "stages = single 3x3 convs, stride 1 and 2, at the backbone's other stage shapes; "
@@ -280,6 +283,8 @@ def run_stages(args):
     torch.cuda.set_device(0)
     shapes = [(800, 704, 64, 96, 2, 16), (400, 352, 96, 96, 1, 16), (400, 352, 96, 192, 2, 16),
               (200, 176, 192, 192, 1, 16), (200, 176, 192, 256, 2, 16), (100, 88, 256, 384, 2, 8)]
+    if args.stage >= 0:
+        shapes = [shapes[args.stage]]
     F = torch.nn.functional
     rows = []
     for (H, W, Cin, Cout, s, bo) in shapes:
@@ -313,7 +318,7 @@ def run_stages(args):
         torch.cuda.synchronize()
         miopen_ms = e0.elapsed_time(e1) / 20
         dense_ms = None
-        for target in (1.0, 0.3, 0.1):
+        for target in ((1.0,) if args.conv_only else (1.0, 0.3, 0.1)):
             if target >= 1.0:
                 m_np = np.ones((1, Ho, Wo), dtype=np.uint8)
             else:
@@ -357,6 +362,11 @@ def run_stages(args):
                 return e0.elapsed_time(e1) / (reps * replays)
             ms = device_ms(step)
             k_ms = device_ms(lambda: sb.sparse_conv(x, idx, cnt, g_in, g_out, wp, bias, y, stride=s, relu=True))
+            if args.conv_only:
+                rows.append({"H": H, "W": W, "Cin": Cin, "Cout": Cout, "stride": s, "block": bo, "target": target,
+                             "active_blocks": n, "total_blocks": total, "step_ms": round(ms, 5), "conv_kernel_ms": round(k_ms, 5),
+                             "conv_tflops": round(2.0 * n * bo * bo * 9 * Cin * Cout / k_ms / 1e9, 2)})
+                continue
             # the two gradients of the same convolution on its tile stacks (unfused: tiles in, tiles out)
             th = g_in.bsize_h
             xt_tiles = torch.randn((max(n, 1), th, th, Cin), device=dev).to(torch.bfloat16)
@@ -421,7 +431,7 @@ def run_stages(args):
                          "active_blocks": n, "total_blocks": total, "step_ms": round(ms, 5), "conv_kernel_ms": round(k_ms, 5),
                          "conv_tflops": round(2.0 * n * bo * bo * 9 * Cin * Cout / k_ms / 1e9, 2),
                          "speedup_vs_own_dense": round(dense_ms / ms, 3), "miopen_dense_ms": round(miopen_ms, 5)})
-    head = [r_ for r_ in rows if r_["H"] == 400 and r_["stride"] == 2 and r_["target"] == 0.3][0]
+    head = ([r_ for r_ in rows if r_["H"] == 400 and r_["stride"] == 2 and r_["target"] == 0.3] or rows)[0]
     print(json.dumps({"metric": "sparse_conv_stage_shapes_ms", "value": head["step_ms"], "unit": "ms", "n_gpus": 1,
                       "steps": 50, "warmup": 3, "ms_per_step": head["step_ms"], "higher_is_better": False, "scaling": "weak",
                       "vs_baseline": None, "dtype": "bf16", "data": "synthetic",

@@ -519,14 +519,21 @@ void conv3_pointwise_kernel(ConvParams p, Plan3 q) {
 // The 256-pixel and the 128-pixel tile shape in one launch: the device-side count picks one (rounds of work on 256
 // CUs with either shape; an item of the smaller tile costs about 5/8 of a larger one: half the matrix work, the same
 // weights to stage; the ratio comes with the launch, in eighths).  Two separate launches, of which one returns, cost a launch more.
-template <int DT, bool FUSED, bool ADD, int CCB, int NVIB, int CCS, int NVIS>
+// PBWB = 3, PBWS = 2: the shapes are 384 and 256 pixels (three / two pixel blocks per wave), for tiles of 257 ... 384
+// output pixels such as the 18x18 of a data gradient on 16x16 blocks: one item per tile instead of three of 128 pixels,
+// each of which staged the tile's rows and the weights again; two items of 256 pixels where those fill the device in
+// one round.
+template <int DT, bool FUSED, bool ADD, int CCB, int NVIB, int CCS, int NVIS, int PBWB = 2, int PBWS = 1>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void conv3_pair_kernel(ConvParams p, Plan3 qb, Plan3 qs) {
     const int nact = max(min(*p.count, p.cap), 0);
     const uint32_t per_big = (uint32_t)qb.mpasses * qb.ngroups, per_small = (uint32_t)qs.mpasses * qs.ngroups;
     const uint32_t rb = ((uint32_t)nact * per_big + 255u) >> 8, rs = ((uint32_t)nact * per_small + 255u) >> 8;
-    if ((unsigned long long)rb * 8u <= (unsigned long long)rs * (uint32_t)p.small_cost8) conv3_body<DT, FUSED, ADD, CCB, 4, 2, 2, NVIB, 3, true>(p, qb);
-    else conv3_body<DT, FUSED, ADD, CCS, 4, 2, 1, NVIS, 3, true>(p, qs);
+    // the ratio is given for the 128- against the 256-pixel item (5/8 as measured); a 256-pixel item against a
+    // 384-pixel one is taken as 6/8 (on the 18x18 outputs of a data gradient one round of either took 12.2 and 14.9 us)
+    const uint32_t cost8 = PBWB == 3 ? ((uint32_t)p.small_cost8 * 6u + 2u) / 5u : (uint32_t)p.small_cost8;
+    if ((unsigned long long)rb * 8u <= (unsigned long long)rs * cost8) conv3_body<DT, FUSED, ADD, CCB, 4, 2, PBWB, NVIB, 3, true>(p, qb);
+    else conv3_body<DT, FUSED, ADD, CCS, 4, 2, PBWS, NVIS, 3, true>(p, qs);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -571,8 +578,13 @@ static Shape3 plan3(const ConvParams &p, int pp) {
         if (CinP % cc) continue;
         const long long nvec = rows * p.tw * (cc / 8);
         const long long need = (nvec + 255) / 256;
-        if (need > (cc == 32 ? 6 : 9)) continue;
-        sh.nvi = cc == 32 ? (need <= 3 ? 3 : 6) : (need <= 5 ? 5 : 9);
+        if (pp == 384) {                              // built for 7 vectors of 32 channels or 5 of 16
+            if (need > (cc == 32 ? 7 : 5)) continue;
+            sh.nvi = cc == 32 ? 7 : 5;
+        } else {
+            if (need > (cc == 32 ? 6 : 9)) continue;
+            sh.nvi = cc == 32 ? (need <= 3 ? 3 : 6) : (need <= 5 ? 5 : 9);
+        }
         const long long in_b = rows * p.sw * q.cpp * (cc * 2 + 16);
         const long long buf = in_b + (long long)taps * (cc / 16) * 2048;
         const long long total = 2 * buf + kDump3 + 4 * kOst3 + (long long)bias_bytes;
@@ -648,11 +660,11 @@ static void launch3(sbnet_dtype dt, bool fused, const ConvParams &p, const Shape
     }
 }
 
-template <int DT, bool FUSED, bool ADD, int CCB, int NVIB>
+template <int DT, bool FUSED, bool ADD, int CCB, int NVIB, int PBWB = 2, int PBWS = 1>
 static void launch3_pair_small(const ConvParams &p, const Shape3 &big, const Shape3 &small, int grid, size_t lds, hipStream_t s) {
 #define SBNET_L3P(CCS, NVIS)                                                                                   \
     do {                                                                                                       \
-        auto kern = conv3_pair_kernel<DT, FUSED, ADD, CCB, NVIB, CCS, NVIS>;                                   \
+        auto kern = conv3_pair_kernel<DT, FUSED, ADD, CCB, NVIB, CCS, NVIS, PBWB, PBWS>;                       \
         if (lds > 48 * 1024)                                                                                   \
             (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         ConvParams pt = p;                                                                                     \
@@ -668,6 +680,13 @@ static void launch3_pair_small(const ConvParams &p, const Shape3 &big, const Sha
 
 template <int DT, bool FUSED, bool ADD>
 static void launch3_pair_big(const ConvParams &p, const Shape3 &big, const Shape3 &small, int grid, size_t lds, hipStream_t s) {
+    if (big.pp == 384) {                              // planned only for the fused form without the add
+        if constexpr (FUSED && !ADD) {
+            if (big.cc == 32) launch3_pair_small<DT, FUSED, ADD, 32, 7, 3, 2>(p, big, small, grid, lds, s);
+            else launch3_pair_small<DT, FUSED, ADD, 16, 5, 3, 2>(p, big, small, grid, lds, s);
+        }
+        return;
+    }
     if (big.cc == 32 && big.nvi == 3) launch3_pair_small<DT, FUSED, ADD, 32, 3>(p, big, small, grid, lds, s);
     else if (big.cc == 32) launch3_pair_small<DT, FUSED, ADD, 32, 6>(p, big, small, grid, lds, s);
     else if (big.nvi == 5) launch3_pair_small<DT, FUSED, ADD, 16, 5>(p, big, small, grid, lds, s);
@@ -717,8 +736,17 @@ bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, 
             if (alt.ok && (!big.ok || 2 * alt.lds_bytes <= (size_t)kLds3)) big = alt;
         }
     } else {
-        if (M > 128) big = plan3(p, 256);
-        small = plan3(p, 128);
+        if (M > 256 && M <= 384 && fused && !p.add) {          // 384 pixels beside 256, if the count can ever pick 384
+            const Shape3 b3 = plan3(p, 384), s2 = plan3(p, 256);
+            if (b3.ok && s2.ok && (long long)p.cap * s2.q.mpasses * s2.q.ngroups > 256) {
+                big = b3;
+                small = s2;
+            }
+        }
+        if (!big.ok) {                                         // 256 pixels beside 128
+            if (M > 128) big = plan3(p, 256);
+            small = plan3(p, 128);
+        }
     }
     if (!big.ok && !small.ok) return false;
     const int most_passes = small.ok ? small.q.mpasses : big.q.mpasses;          // the smaller tile has more of them

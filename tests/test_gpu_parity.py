@@ -1,6 +1,8 @@
 """GPU parity: every entry point of libsbnet_hip.so, called through the C ABI, against the
 fp64 CPU oracle on the same seeded inputs.  Indices, gather and scatter must match bit for
 bit; convolution outputs within the stated relative tolerance."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -708,6 +710,46 @@ def test_sparse_conv_random_shapes(N, H, W, Cin, Cout, s, bo, dtype, add):
     assert_close(got, orc.sparse_conv_dense(x, idx, ogeom(g_out), w, b, y0, stride=s, relu=True, add=add), CONV_TOL[dtype], "fused")
     bm = orc.block_mask(idx, ogeom(g_out), N, Ho, Wo)
     assert np.array_equal(got[~bm], y0[~bm])
+
+
+@pytest.mark.parametrize("H,W,bh,bw,Cin,Cout,dtype", [
+    # sizes at which the 128-pixel items of all blocks outnumber the workgroups: below that the host plans no second shape
+    (110, 130, 18, 18, 96, 64, "bf16"),    # the 18x18 outputs of a data gradient on 16x16 blocks; blocks hang over the edge
+    (80, 120, 13, 28, 40, 72, "f16"),      # 364 pixels whose input rows only fit in 16-channel chunks
+    (120, 120, 19, 19, 32, 32, "bf16"),    # 361 pixels, one chunk
+])
+@pytest.mark.parametrize("choice", ["larger", "smaller", "by count"])
+def test_sparse_conv_blocks_of_257_to_384_pixels(H, W, bh, bw, Cin, Cout, dtype, choice):
+    """Blocks of 257 ... 384 output pixels have a tile shape of their own (one 384-pixel item per block) beside the
+    128-pixel one; the count picks on the device.  Both forced, and the default rule, against the oracle."""
+    step("sparse_conv 384-pixel shape %s %s" % (choice, (H, W, bh, bw, Cin, Cout, dtype)))
+    r = gen.rng_for(5, H * 100 + Cin + bh)
+    g_in, g_out = sb.Geom(), sb.Geom()
+    ho, wo = ctypes.c_int(), ctypes.c_int()
+    assert sb.lib().sbnet_geometry(H, W, 3, 3, 1, 1, bh, bw, g_in, g_out, ho, wo) == 0
+    N = 2
+    x = gen.activations(r, (N, H, W, Cin), dtype)
+    w = gen.conv_weights(r, 3, 3, Cin, Cout, dtype)
+    b = gen.bias_vector(r, Cout, 0.5)
+    y0 = gen.activations(r, (N, H, W, Cout), dtype)
+    wp = sb.pack_weights(to_dev(w, dtype))
+    d_b = torch.from_numpy(b).cuda()
+    try:
+        if choice != "by count":
+            sb.set_tuning(conv3_small_item_cost_eighths=100000 if choice == "larger" else 0)
+        for dens in (0.002, 1.0):
+            mask = (r.random((N, H, W)) < dens).astype(np.uint8)
+            d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in)
+            idx = orc.reduce_mask(mask, ogeom(g_in))
+            ref = orc.sparse_conv_dense(x, idx, ogeom(g_out), w, b, y0, stride=1, relu=True, add=False)
+            bm = orc.block_mask(idx, ogeom(g_out), N, H, W)
+            y = to_dev(y0, dtype)
+            sb.sparse_conv(to_dev(x, dtype), d_idx, d_cnt, g_in, g_out, wp, d_b, y, stride=1, relu=True, add=False)
+            got = to_host(y)
+            assert_close(got, ref, CONV_TOL[dtype], "fused, %s shape" % choice)
+            assert np.array_equal(got[~bm], y0[~bm])
+    finally:
+        sb.set_tuning()
 
 
 @pytest.mark.parametrize("dens", [1.0, 0.35])
