@@ -101,7 +101,7 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
     constexpr int PER = (NV + NS - 1) / NS;          // ... handled per MFMA step
     constexpr int PP = WP * PBW * 32;                // output pixels per pass
     constexpr int NM = CBW * PBW;                    // MFMAs per step
-    constexpr int D0 = NM >= 4 ? 2 : (NM == 2 ? 4 : 8);
+    constexpr int D0 = NM >= 4 ? 2 : (NM == 3 ? 3 : (NM == 2 ? 4 : 8));
     constexpr int D = D0 < NS ? D0 : NS - 1;         // steps the fragment reads run ahead of the MFMAs
     extern __shared__ __align__(16) unsigned char lds[];
 
