@@ -10,13 +10,15 @@
 //     stream.  So nothing has to stay in registers across MFMAs and the matrix loop never waits on memory: a
 //     chunk of CC input channels of the input rows AND of the weights of the workgroup's 64 output channels sits
 //     in LDS, and the loop only reads LDS.
-//   * A work item is (active block, pass of PP output pixels, group of 64 output channels); a workgroup (4 waves,
-//     one per SIMD) walks its items and, inside an item, the chunks of CC input channels.  Chunks are
-//     double-buffered in LDS and pipelined two deep through registers: between the MFMAs of chunk i a thread
-//     writes its vectors of chunk i+1 (loaded during chunk i-1) to the other LDS buffer and, into the registers
-//     this frees, requests the same vectors of chunk i+2 (of a following item past the last chunk).  One or two
-//     vectors per MFMA step: issued all at once they would stall the wave at the memory pipeline (64 B per clock
-//     and CU) with the matrix cores idle behind them.
+//   * A work item is (active block, pass of PP output pixels, group of 64 output channels); a workgroup walks its
+//     items and, inside an item, the chunks of CC input channels.  Chunks are double-buffered in LDS and pipelined
+//     two deep through registers: while the matrix cores work on chunk i, a thread writes its vectors of chunk i+1
+//     (loaded during chunk i-1) to the other LDS buffer and, into the registers this frees, requests the same
+//     vectors of chunk i+2 (of a following item past the last chunk).
+//   * 3x3: eight waves, two per SIMD, with separate roles: four run the matrix steps and store the results, four
+//     do the staging.  (A wave stands at the issue of a load while the CU's address unit is busy; with one wave
+//     per SIMD doing both, one or two staging vectors per MFMA step, a chunk took the sum of its matrix, LDS and
+//     load time.)  1x1: four waves that do both and two workgroups per CU.
 //   * All global traffic goes through buffer descriptors: halo pixels outside the image, vectors past the end of
 //     the staged rows and channels past Cin read as zeros, stores outside the image or past Cout are dropped.  No
 //     branch surrounds a load, so the compiler's wait counts stay exact.
@@ -27,7 +29,8 @@
 //     instruction writes 64-byte runs instead of 16-byte pieces.
 //   * Workgroup tiles: 256 pixels x 64 channels (wave: 64 px x 64 ch, 4 accumulators), 128 x 64 for problems
 //     where that means fewer rounds of work on the device (picked on the device from the active count: one launch
-//     holds both shapes), and 64 x 64 for tiles of at most 64 output pixels.  Chunks of 32 channels where two
+//     holds both shapes), 384 x 64 beside 256 x 64 for blocks of 257 ... 384 output pixels (the 18x18 outputs of a
+//     data gradient on 16x16 blocks), and 64 x 64 for tiles of at most 64 output pixels.  Chunks of 32 channels where two
 //     buffers of that fit in LDS (stride 1), else of 16 (the 33x33 input tile of a strided 16x16 block).
 #include "conv_common.h"
 
