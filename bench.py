@@ -552,18 +552,26 @@ def run_tune(args):
         res = kt.unit_subtiles(x, ws, block=16, counts=(8, 16, 32, 48, 64, 80, 96, 112, 128, 144, 160, 192, 224, 256, 320, 384, 512))
         res.update({"shape": "%dx%dx%d/%d" % (H, W, C, Cm), "ms16": [round(v, 5) for v in res["ms16"]], "ms8": [round(v, 5) for v in res["ms8"]]})
         out["unit_subtiles"].append(res)
-    for (H, W, Cin, Cout, s_) in ((400, 352, 96, 96, 1), (800, 704, 64, 96, 2), (200, 176, 192, 192, 1)):
+    # the last entry has 18 x 18 blocks (324 output pixels, as in a data gradient on 16 x 16 blocks): its two items are
+    # 384 and 256 pixels, one or two per block, and a 256-pixel item is taken as 6/5 of the ratio below
+    for (H, W, Cin, Cout, s_, bo_) in ((400, 352, 96, 96, 1, 16), (800, 704, 64, 96, 2, 16), (200, 176, 192, 192, 1, 16),
+                                       (396, 360, 64, 64, 1, 18)):
         x = torch.randn((1, H, W, Cin), device=dev).to(torch.bfloat16)
         w = torch.from_numpy(gen.conv_weights(r, 3, 3, Cin, Cout, "bf16")).to(torch.bfloat16).to(dev)
-        res = kt.conv3_items(x, w, stride=s_, block=16, counts=(8, 16, 32, 64, 96, 128, 192, 256, 320, 384, 512))
+        res = kt.conv3_items(x, w, stride=s_, block=bo_, counts=(8, 16, 32, 64, 96, 128, 192, 256, 320, 384, 512))
         # what the default cost ratio would have picked at each count (rounds of work over 256 CUs)
         ngroups = (Cout + 63) // 64
+        cost = out["defaults"]["conv3_small_item_cost_eighths"]
+        if bo_ == 18:
+            cost = (cost * 6 + 2) // 5
         picks = []
         for n in res["counts"]:
             rb, rs = (n * 1 * ngroups + 255) // 256, (n * 2 * ngroups + 255) // 256
-            picks.append("256" if rb * 8 <= rs * out["defaults"]["conv3_small_item_cost_eighths"] else "128")
-        res.update({"shape": "%dx%dx%d->%d s%d" % (H, W, Cin, Cout, s_), "ms256": [round(v, 5) for v in res["ms256"]],
-                    "ms128": [round(v, 5) for v in res["ms128"]], "default_picks": picks})
+            picks.append("larger" if rb * 8 <= rs * cost else "smaller")
+        res["faster"] = ["larger" if f == "256" else "smaller" for f in res["faster"]]
+        res.update({"shape": "%dx%dx%d->%d s%d, block %d" % (H, W, Cin, Cout, s_, bo_), "items": "384 / 256" if bo_ == 18 else "256 / 128",
+                    "ms_larger": [round(v, 5) for v in res.pop("ms256")], "ms_smaller": [round(v, 5) for v in res.pop("ms128")],
+                    "default_picks": picks})
         out["conv3_items"].append(res)
     for (k, th, oh, Cin, Cout) in ((3, 18, 16, 64, 64), (1, 18, 18, 256, 64), (3, 18, 16, 96, 96)):
         t = torch.randn((2200, th, th, Cin), device=dev).to(torch.bfloat16)

@@ -243,8 +243,9 @@ class KernelChoiceTuner:
                 "cost_eighths": fit_cost_eighths(used, ms16, ms8, per16, per8)}
 
     def conv3_items(self, x, w_hwio, bias=None, stride=1, block=16, counts=(8, 16, 32, 64, 128, 192, 256, 384, 512, 1024)):
-        """LDS-tiled 3x3 convolution: time with 256-pixel and with 128-pixel work items forced.  Returns the two time
-        rows and, per count, which was faster."""
+        """LDS-tiled 3x3 convolution: time with the larger and with the smaller work item forced (256 and 128 pixels;
+        384 and 256 for blocks of 257 ... 384 output pixels, where the rows keep the names ms256 / ms128 for the larger /
+        smaller item).  Returns the two time rows and, per count, which was faster."""
         N, H, W, Cin = x.shape
         k, _, _, Cout = w_hwio.shape
         wp = pack_weights(w_hwio)
