@@ -74,7 +74,8 @@ struct Chunk3 {
     uint32_t origin;         // ... of channel c0
     int gx0;
     int c0;
-    uint32_t wofs;           // byte offset of (group, tap 0, channel c0) in the packed weights
+    uint32_t wofs;           // byte offset of (group, tap 0, channel c0) in the packed weights (wide groups: of channel c0 only)
+    int nb0;                 // first 32-channel block of the group
 };
 
 // KH = 3: the 3x3 kernel this file is named for; KH = 1: pointwise convolutions through the same pipeline (one tap,
@@ -98,7 +99,9 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
     constexpr int TAPS = KH * KH;
     constexpr int NS = TAPS * KST;                   // MFMA steps per chunk
     constexpr int PS = CC * 2 + 16;                  // LDS bytes per input pixel
-    constexpr int WVEC = NS * 128;                   // vectors of a weight chunk: steps x 2 blocks of 32 channels x 64 lanes
+    constexpr int NB = (4 / WP) * CBW;               // blocks of 32 output channels per group: 2, or 3 / 4 (wide groups)
+    constexpr int GW = NB * 32;                      // output channels per group
+    constexpr int WVEC = NS * NB * 64;               // vectors of a weight chunk: steps x NB blocks of 32 channels x 64 lanes
     constexpr int NVW = (WVEC + 255) / 256;
     constexpr int NV = NVI + NVW;                    // staging vectors per thread and chunk
     constexpr int PER = (NV + NS - 1) / NS;          // ... handled per MFMA step
@@ -201,14 +204,27 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
         gdelta[u] = (uint32_t)((row * in_w + col) * p.Cin + c8 * 8) * 2u;
         colv[u] = ok ? (int)col : 0x40000000;
     }
+    // The packed weights are [group of 64 channels][tap][16-channel step][32-channel half][lane] x 16 bytes; a chunk in
+    // LDS is [step][block of the group][lane].  With 64-channel groups a tap's steps of a chunk are one contiguous run.
+    // Wide groups (96 / 128 channels) take their blocks from two 64-channel groups: block b of group ng is half
+    // (ng NB + b) & 1 of 64-group (ng NB + b) >> 1, worked out per vector when it is requested (wblk: b, or -1 for none).
+    int wblk[NVW];
 #pragma unroll
     for (int u = 0; u < NVW; ++u) {
         const uint32_t v = (uint32_t)stid + 256u * u;
-        const uint32_t tap = v / (KST * 128), rem = v % (KST * 128);
         const bool ok = v < (uint32_t)WVEC;
         lbase[NVI + u] = ok ? q.w_off + v * 16 : q.dump_off + stid * 16;
         lstep[NVI + u] = ok ? q.buf_bytes : 0u;
-        wsrc[u] = ok ? (tap * cin16 * 128u + rem) * 16u : kOutOfRange;
+        if (NB == 2) {
+            const uint32_t tap = v / (KST * 128), rem = v % (KST * 128);
+            wsrc[u] = ok ? (tap * cin16 * 128u + rem) * 16u : kOutOfRange;
+            wblk[u] = 0;
+        } else {
+            const uint32_t st = v / (NB * 64), b = (v / 64) % NB, ln = v % 64;
+            const uint32_t tap = st / KST, k = st % KST;
+            wsrc[u] = (tap * cin16 + k) * 2048u + ln * 16u;
+            wblk[u] = ok ? (int)b : -1;
+        }
     }
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         (void *)((const uint4 *)p.w + p.w32_offset), 0, (int)q.w_bytes, (int)kBufWord3);
@@ -221,8 +237,12 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
             const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)ch.base, 0, (int)in_bytes, (int)kBufWord3);
             const bool ok = chan_ok && (uint32_t)(ch.gx0 + colv[u]) < (uint32_t)in_w;
             stage[r][u] = buf_load16(rs, ok ? ch.origin + gdelta[u] : kOutOfRange);
-        } else {
+        } else if (NB == 2) {
             stage[r][u] = buf_load16(wrs, wsrc[u - NVI] + ch.wofs);
+        } else {
+            const uint32_t nbk = (uint32_t)(ch.nb0 + wblk[u - NVI]);
+            const uint32_t off = (nbk >> 1) * (uint32_t)q.ks16 * 2048u + (nbk & 1u) * 1024u + wsrc[u - NVI] + ch.wofs;
+            stage[r][u] = buf_load16(wrs, wblk[u - NVI] >= 0 ? off : kOutOfRange);
         }
     };
     auto write1 = [&](int r, int u, uint32_t bufno) __attribute__((always_inline)) {
@@ -234,7 +254,8 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
         ch.c0 = c * CC;
         ch.origin = s.origin + (uint32_t)ch.c0 * 2u;
         ch.gx0 = s.gx0;
-        ch.wofs = (uint32_t)(s.ng * q.ks16 + (ch.c0 >> 4)) * 2048u;
+        ch.wofs = NB == 2 ? (uint32_t)(s.ng * q.ks16 + (ch.c0 >> 4)) * 2048u : (uint32_t)(ch.c0 >> 4) * 2048u;
+        ch.nb0 = s.ng * NB;
         return ch;
     };
 
@@ -282,7 +303,7 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
     // bias of all groups -> LDS (zeros past Cout or without bias)
     {
         float *bl = (float *)(lds + q.bias_off);
-        for (int i = tid; i < q.ngroups * 64; i += NT) bl[i] = (p.bias && i < p.Cout) ? p.bias[i] : 0.f;
+        for (int i = tid; i < q.ngroups * GW; i += NT) bl[i] = (p.bias && i < p.Cout) ? p.bias[i] : 0.f;
     }
     // tap offsets in the de-interleaved layout
     uint32_t tapoff[TAPS];
@@ -342,7 +363,7 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
                 // accumulators start from the bias
 #pragma unroll
                 for (int cb = 0; cb < CBW; ++cb) {
-                    const float4 *bl = (const float4 *)(lds + q.bias_off) + (cur.it.ng * 64 + (cw * CBW + cb) * 32 + g * 16) / 4;
+                    const float4 *bl = (const float4 *)(lds + q.bias_off) + (cur.it.ng * GW + (cw * CBW + cb) * 32 + g * 16) / 4;
 #pragma unroll
                     for (int k4 = 0; k4 < 4; ++k4) {
                         const float4 bv = bl[k4];
@@ -365,7 +386,7 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
                 auto read = [&](int s) __attribute__((always_inline)) {
                     const int slot = s % (D + 1);
 #pragma unroll
-                    for (int cb = 0; cb < CBW; ++cb) xa[slot][cb] = *(const uint4 *)(WL + (s * 2 + cb) * 1024);
+                    for (int cb = 0; cb < CBW; ++cb) xa[slot][cb] = *(const uint4 *)(WL + (s * NB + cb) * 1024);
 #pragma unroll
                     for (int pb = 0; pb < PBW; ++pb)
                         xb[slot][pb] = *(const uint4 *)(B + xbase[pb] + tapoff[s / KST] + (s % KST) * 32);
@@ -432,7 +453,7 @@ __device__ __forceinline__ void conv3_body(const ConvParams &p, const Plan3 &q) 
                     ok = px < (uint32_t)M && (!FUSED || (uint32_t)(ox0 + (int)j) < (uint32_t)p.Wo);
                     return origin + (uint32_t)((i * out_w + j) * p.Cout) * 2u;
                 };
-                const int chg = cur.it.ng * 64 + cw * CBW * 32;                    // first channel of the wave
+                const int chg = cur.it.ng * GW + cw * CBW * 32;                    // first channel of the wave
 #pragma unroll
                 for (int pb = 0; pb < PBW; ++pb) {
                     const uint32_t pblock = p_lo + (uint32_t)((pw * PBW + pb) * 32);
@@ -526,7 +547,11 @@ void conv3_pointwise_kernel(ConvParams p, Plan3 q) {
 // output pixels such as the 18x18 of a data gradient on 16x16 blocks: one item per tile instead of three of 128 pixels,
 // each of which staged the tile's rows and the weights again; two items of 256 pixels where those fill the device in
 // one round.
-template <int DT, bool FUSED, bool ADD, int CCB, int NVIB, int CCS, int NVIS, int PBWB = 2, int PBWS = 1>
+// CBWP = 3 / 4: groups of 96 / 128 output channels (three / four channel blocks per wave): the input rows of an item are
+// staged once for 96 / 128 channels instead of once per 64, a 96-channel layer does not pay for a half-empty second
+// group, and a wave reads 5 / 6 fragments per 6 / 8 MFMAs instead of 4 per 4.  Their weight chunks are larger, so
+// these run on 16-channel chunks.
+template <int DT, bool FUSED, bool ADD, int CCB, int NVIB, int CCS, int NVIS, int PBWB = 2, int PBWS = 1, int CBWP = 2>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void conv3_pair_kernel(ConvParams p, Plan3 qb, Plan3 qs) {
     const int nact = max(min(*p.count, p.cap), 0);
@@ -535,8 +560,28 @@ void conv3_pair_kernel(ConvParams p, Plan3 qb, Plan3 qs) {
     // the ratio is given for the 128- against the 256-pixel item (5/8 as measured); a 256-pixel item against a
     // 384-pixel one is taken as 6/8 (on the 18x18 outputs of a data gradient one round of either took 12.2 and 14.9 us)
     const uint32_t cost8 = PBWB == 3 ? ((uint32_t)p.small_cost8 * 6u + 2u) / 5u : (uint32_t)p.small_cost8;
-    if ((unsigned long long)rb * 8u <= (unsigned long long)rs * cost8) conv3_body<DT, FUSED, ADD, CCB, 4, 2, PBWB, NVIB, 3, true>(p, qb);
-    else conv3_body<DT, FUSED, ADD, CCS, 4, 2, PBWS, NVIS, 3, true>(p, qs);
+    if ((unsigned long long)rb * 8u <= (unsigned long long)rs * cost8) conv3_body<DT, FUSED, ADD, CCB, 4, CBWP, PBWB, NVIB, 3, true>(p, qb);
+    // (128 pixels x 128 channels: a wave takes 64 x 64, four fragment reads per four MFMAs, rather than 32 x 128, five)
+    else if (CBWP == 4 && PBWS == 1) conv3_body<DT, FUSED, ADD, CCS, 2, 2, 2, NVIS, 3, true>(p, qs);
+    else conv3_body<DT, FUSED, ADD, CCS, 4, CBWP, PBWS, NVIS, 3, true>(p, qs);
+}
+
+// 128-pixel items with groups of 96 / 128 output channels or of 64 in one launch, for strided tiles whose 256-pixel shape
+// has no room for the wider weight chunks (the 33x33 input tile of a 16x16 block).  Measured (192 -> 256 channels, stride
+// 2): with up to ~25 active blocks the 64-channel items are faster (19 against 22.5 us: more, shorter work items on an
+// otherwise idle device), beyond that the wide ones (41 blocks: 25 against 31 us; 143: 63 against 76), which stage a
+// block's rows once per 128 channels.  The count picks, by the number of wide work items.
+template <int DT, bool FUSED, bool ADD, int NBW>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void conv3_mixed_kernel(ConvParams p, Plan3 qw, Plan3 qn) {
+    const int nact = max(min(*p.count, p.cap), 0);
+    if ((uint32_t)nact * (uint32_t)(qw.mpasses * qw.ngroups) >= (uint32_t)p.wide_min_items) {
+        // (128 pixels x 128 channels: a wave takes 64 x 64, four fragment reads per four MFMAs, rather than 32 x 128, five)
+        if (NBW == 4) conv3_body<DT, FUSED, ADD, 16, 2, 2, 2, 5, 3, true>(p, qw);
+        else conv3_body<DT, FUSED, ADD, 16, 4, NBW, 1, 5, 3, true>(p, qw);
+    } else {
+        conv3_body<DT, FUSED, ADD, 16, 4, 2, 1, 5, 3, true>(p, qn);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -546,20 +591,23 @@ struct Shape3 {
     int pp;          // output pixels per pass
     int cc;          // input channels per chunk
     int nvi;         // input vectors per thread and chunk the kernel is built for
+    int nb;          // 32-channel blocks per output group: 2, or 3 / 4 (wide groups)
     bool ok;
     Plan3 q;
     size_t lds_bytes;
 };
 
-static Shape3 plan3(const ConvParams &p, int pp) {
+static Shape3 plan3(const ConvParams &p, int pp, int nb = 2, bool only16 = false) {
     Shape3 sh;
     sh.pp = pp;
+    sh.nb = nb;
     sh.ok = false;
     Plan3 &q = sh.q;
     const long long M = (long long)p.oh * p.ow;
     const int CinP = (p.Cin + 31) / 32 * 32;
     q.mpasses = (int)((M + pp - 1) / pp);
-    q.ngroups = (p.Cout + 63) / 64;
+    const int gw = nb * 32;
+    q.ngroups = (p.Cout + gw - 1) / gw;
     q.div_pt = make_fastdiv((uint32_t)q.mpasses * q.ngroups);
     q.div_ng = make_fastdiv((uint32_t)q.ngroups);
     q.div_sw = make_fastdiv((uint32_t)p.sw);
@@ -571,25 +619,29 @@ static Shape3 plan3(const ConvParams &p, int pp) {
     q.cpp = (p.tw + p.sw - 1) / p.sw;
     const int taps = p.kh * p.kw;
     q.ks16 = taps * (CinP / 16);
-    q.w_bytes = (uint32_t)((size_t)q.ngroups * q.ks16 * 2048);
-    const size_t bias_bytes = (size_t)q.ngroups * 64 * 4;
+    q.w_bytes = (uint32_t)((size_t)((p.Cout + 63) / 64) * q.ks16 * 2048);      // the packed weights: groups of 64 channels
+    const size_t bias_bytes = (size_t)q.ngroups * gw * 4;
     // chunks of 32 channels with up to 6 input vectors per thread, else of 16 with up to 9 (kernels are built for
     // 3 / 6 and 5 / 9: every vector costs its staging instructions whether it carries data or not); two buffers must fit
     // a pointwise kernel has one tap: chunks of 64 channels (up to 9 vectors per thread; kernels built for 5 / 9) keep
     // four MFMA steps in a chunk; channel counts that are no multiple of 64 take chunks of 32
     for (int cc = (taps == 1 ? 64 : 32); cc >= (taps == 1 ? 32 : 16); cc -= (taps == 1 ? 32 : 16)) {
         if (CinP % cc) continue;
+        if ((nb > 2 || only16) && cc != 16) continue;  // wide groups (and what runs beside them): built for 16-channel chunks of up to 5 vectors
         const long long nvec = rows * p.tw * (cc / 8);
         const long long need = (nvec + 255) / 256;
         if (pp == 384) {                              // built for 7 vectors of 32 channels or 5 of 16
             if (need > (cc == 32 ? 7 : 5)) continue;
             sh.nvi = cc == 32 ? 7 : 5;
+        } else if (nb > 2 || only16) {
+            if (need > 5) continue;
+            sh.nvi = 5;
         } else {
             if (need > (cc == 32 ? 6 : 9)) continue;
             sh.nvi = cc == 32 ? (need <= 3 ? 3 : 6) : (need <= 5 ? 5 : 9);
         }
         const long long in_b = rows * p.sw * q.cpp * (cc * 2 + 16);
-        const long long buf = in_b + (long long)taps * (cc / 16) * 2048;
+        const long long buf = in_b + (long long)taps * (cc / 16) * nb * 1024;
         const long long total = 2 * buf + kDump3 + 4 * kOst3 + (long long)bias_bytes;
         if (total > kLds3) continue;
         sh.cc = cc;
@@ -714,6 +766,50 @@ static void launch3_pair(sbnet_dtype dt, bool fused, const ConvParams &p, const 
     }
 }
 
+// groups of 96 / 128 channels: both tile shapes in one launch, or the 128-pixel shape alone where the 256-pixel one does
+// not fit LDS (the 33x33 input tile of a strided 16x16 block)
+constexpr int kWideMinItems = 96;            // wide groups from this many of their work items (see conv3_mixed_kernel)
+
+template <int DT, bool FUSED, bool ADD, int NBW>
+static void launch3_wide_nb(const ConvParams &p, const Shape3 &big, const Shape3 &small, hipStream_t s) {
+    const long long items = (long long)p.cap * small.q.mpasses * small.q.ngroups;
+    long long g = (items + 7) / 8 * 8;
+    if (g > 256) g = 256;
+    if (big.ok) {
+        const size_t lds = big.lds_bytes > small.lds_bytes ? big.lds_bytes : small.lds_bytes;
+        auto kern = conv3_pair_kernel<DT, FUSED, ADD, 16, 5, 16, 5, 2, 1, NBW>;
+        if (lds > 48 * 1024) (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        ConvParams pt = p;
+        pt.small_cost8 = tuning().conv3_small_item_cost_eighths;
+        hipLaunchKernelGGL(kern, dim3((int)g), dim3(512), lds, s, pt, big.q, small.q);
+    } else {
+        // beside the 128-pixel shape with 64-channel groups (same rows, same chunks: it fits where the wide one does)
+        const Shape3 narrow = plan3(p, 128, 2, true);
+        const long long n_items = (long long)p.cap * narrow.q.mpasses * narrow.q.ngroups;
+        long long gn = (n_items + 7) / 8 * 8;
+        if (gn > 256) gn = 256;
+        const size_t lds = small.lds_bytes > narrow.lds_bytes ? small.lds_bytes : narrow.lds_bytes;
+        auto kern = conv3_mixed_kernel<DT, FUSED, ADD, NBW>;
+        if (lds > 48 * 1024) (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        ConvParams pt = p;
+        pt.wide_min_items = kWideMinItems;
+        hipLaunchKernelGGL(kern, dim3((int)gn), dim3(512), lds, s, pt, small.q, narrow.q);
+    }
+}
+
+template <int DT>
+static void launch3_wide(bool fused, const ConvParams &p, const Shape3 &big, const Shape3 &small, hipStream_t s) {
+#define SBNET_L3W(FU, AD)                                                                   \
+    do {                                                                                    \
+        if (small.nb == 3) launch3_wide_nb<DT, FU, AD, 3>(p, big, small, s);                \
+        else launch3_wide_nb<DT, FU, AD, 4>(p, big, small, s);                              \
+    } while (0)
+    if (fused && p.add) SBNET_L3W(true, true);
+    else if (fused) SBNET_L3W(true, false);
+    else SBNET_L3W(false, false);
+#undef SBNET_L3W
+}
+
 bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, sbnet_status *st, const char *who) {
     if (dt != SBNET_BF16 && dt != SBNET_F16) return false;
     if (p0.kh != p0.kw || (p0.kh != 3 && p0.kh != 1)) return false;
@@ -739,6 +835,24 @@ bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, 
             if (alt.ok && (!big.ok || 2 * alt.lds_bytes <= (size_t)kLds3)) big = alt;
         }
     } else {
+        // Strided tiles of up to 256 pixels whose rows fit in 16-channel chunks of five vectors per thread: groups of 128
+        // output channels where the channel count is a multiple of that, of 96 where that spares a half-empty group of
+        // 64 (96, 288 ...).  Measured on the stage shapes: stride 1 gains nothing from them (96 -> 96) or loses (192 -> 192:
+        // its rows fit 32-channel chunks with 64-channel groups, twice the matrix steps per barrier), 96 -> 192 at
+        // stride 2 is the same with either.
+        const int nbw = p.Cout % 128 == 0 ? 4 : (p.Cout % 96 == 0 && p.Cout % 64 != 0 ? 3 : 2);
+        if (nbw > 2 && M <= 256 && p.sh > 1) {
+            Shape3 wb, ws = plan3(p, 128, nbw);
+            wb.ok = false;
+            if (M > 128) wb = plan3(p, 256, nbw);
+            if (ws.ok && (long long)p.cap * ws.q.mpasses * ((p.Cout + 63) / 64) < (1LL << 31)) {
+                if (wb.ok && (long long)p.cap * ws.q.mpasses * ws.q.ngroups <= 256) wb.ok = false;    // as below
+                if (dt == SBNET_BF16) launch3_wide<SBNET_BF16>(fused, p, wb, ws, s);
+                else launch3_wide<SBNET_F16>(fused, p, wb, ws, s);
+                *st = launch_status(who);
+                return true;
+            }
+        }
         if (M > 256 && M <= 384 && fused && !p.add) {          // 384 pixels beside 256, if the count can ever pick 384
             const Shape3 b3 = plan3(p, 384), s2 = plan3(p, 256);
             if (b3.ok && s2.ok && (long long)p.cap * s2.q.mpasses * s2.q.ngroups > 256) {

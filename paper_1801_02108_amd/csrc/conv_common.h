@@ -49,6 +49,7 @@ struct ConvParams {
     int32_t *count_out;      // [1]
     FastDiv div_bps, div_bw, div_grid;       // blocks per sample, blocks per block row, workgroups along x
     int small_cost8;         // conv3.hip, two tile shapes in one launch: cost of the smaller item in eighths of the larger
+    int wide_min_items;      // conv3.hip, 64-channel or wider output groups in one launch: wide from this many work items
     // MFMA path work decomposition
     int CinP;                // Cin rounded up to 32
     int CC;                  // channels per LDS chunk (multiple of 32)

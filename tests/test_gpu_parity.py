@@ -752,6 +752,48 @@ def test_sparse_conv_blocks_of_257_to_384_pixels(H, W, bh, bw, Cin, Cout, dtype,
         sb.set_tuning()
 
 
+@pytest.mark.parametrize("H,W,Cin,Cout,dtype", [
+    (224, 224, 16, 96, "bf16"),      # groups of 96 output channels
+    (224, 200, 24, 128, "f16"),      # groups of 128; blocks hang over the right edge
+    (224, 224, 32, 256, "bf16"),     # two groups of 128, two chunks
+    (200, 224, 16, 384, "bf16"),     # three groups of 128
+])
+@pytest.mark.parametrize("add", [False, True])
+def test_sparse_conv_strided_wide_channel_groups(H, W, Cin, Cout, dtype, add):
+    """Stride-2 3x3 convolutions on 16x16 blocks whose output channels are a multiple of 96 or 128: one launch holds
+    128-pixel work items with groups of 96 / 128 channels and with groups of 64, and the count picks (wide from 96 work
+    items).  All 49 blocks active runs the wide items, a handful of blocks the 64-channel ones."""
+    step("sparse_conv strided, wide groups add=%s %s" % (add, (H, W, Cin, Cout, dtype)))
+    r = gen.rng_for(5, H * 100 + Cin + Cout)
+    N, s, bo = 1, 2, 16
+    g_in, g_out, Ho, Wo = sb.geometry(H, W, 3, s, bo)
+    assert g_out.bcount_h * g_out.bcount_w * 2 >= 96
+    x = gen.activations(r, (N, H, W, Cin), dtype)
+    w = gen.conv_weights(r, 3, 3, Cin, Cout, dtype)
+    b = gen.bias_vector(r, Cout, 0.5)
+    y0 = gen.activations(r, (N, Ho, Wo, Cout), dtype)
+    wp = sb.pack_weights(to_dev(w, dtype))
+    d_b = torch.from_numpy(b).cuda()
+    for dens in (1.0, 0.0002):
+        mask = (r.random((N, H, W)) < dens).astype(np.uint8)
+        d_idx, d_cnt = sb.reduce_mask(torch.from_numpy(mask).cuda(), g_in)
+        idx = orc.reduce_mask(mask, ogeom(g_in))
+        assert len(idx) > 0
+        ref = orc.sparse_conv_dense(x, idx, ogeom(g_out), w, b, y0, stride=s, relu=True, add=add)
+        bm = orc.block_mask(idx, ogeom(g_out), N, Ho, Wo)
+        y = to_dev(y0, dtype)
+        sb.sparse_conv(to_dev(x, dtype), d_idx, d_cnt, g_in, g_out, wp, d_b, y, stride=s, relu=True, add=add)
+        got = to_host(y)
+        assert_close(got, ref, CONV_TOL[dtype], "fused, %d blocks" % len(idx))
+        assert np.array_equal(got[~bm], y0[~bm])
+        # the unfused call on the gathered tiles takes the same kernels
+        tiles = sb.sparse_gather(to_dev(x, dtype), d_idx, d_cnt, g_in)
+        out = sb.conv_on_tiles(tiles, d_cnt, wp, d_b, stride=s, relu=True)
+        y = to_dev(y0, dtype)
+        sb.sparse_scatter(out, d_idx, d_cnt, g_out, y, add=add)
+        assert_close(to_host(y), ref, CONV_TOL[dtype], "unfused, %d blocks" % len(idx))
+
+
 @pytest.mark.parametrize("dens", [1.0, 0.35])
 @pytest.mark.parametrize("Cin", [32, 40])
 def test_sparse_conv_more_tiles_than_workgroups(dens, Cin):
