@@ -30,7 +30,8 @@
 //   * Workgroup tiles: 256 pixels x 64 channels (wave: 64 px x 64 ch, 4 accumulators), 128 x 64 for problems
 //     where that means fewer rounds of work on the device (picked on the device from the active count: one launch
 //     holds both shapes), 384 x 64 beside 256 x 64 for blocks of 257 ... 384 output pixels (the 18x18 outputs of a
-//     data gradient on 16x16 blocks), and 64 x 64 for tiles of at most 64 output pixels.  Chunks of 32 channels where two
+//     data gradient on 16x16 blocks), 64 x 64 for tiles of at most 64 output pixels, and for strided tiles 128 pixels x
+//     96 / 128 channels where the channel count is a multiple of that (beside 128 x 64 in the same launch).  Chunks of 32 channels where two
 //     buffers of that fit in LDS (stride 1), else of 16 (the 33x33 input tile of a strided 16x16 block).
 #include "conv_common.h"
 
