@@ -552,9 +552,10 @@ def run_tune(args):
         res = kt.unit_subtiles(x, ws, block=16, counts=(8, 16, 32, 48, 64, 80, 96, 112, 128, 144, 160, 192, 224, 256, 320, 384, 512))
         res.update({"shape": "%dx%dx%d/%d" % (H, W, C, Cm), "ms16": [round(v, 5) for v in res["ms16"]], "ms8": [round(v, 5) for v in res["ms8"]]})
         out["unit_subtiles"].append(res)
+    # (strided layers with 96 / 256 ... output channels run 128-pixel items only and have no such choice)
     # the last entry has 18 x 18 blocks (324 output pixels, as in a data gradient on 16 x 16 blocks): its two items are
     # 384 and 256 pixels, one or two per block, and a 256-pixel item is taken as 6/5 of the ratio below
-    for (H, W, Cin, Cout, s_, bo_) in ((400, 352, 96, 96, 1, 16), (800, 704, 64, 96, 2, 16), (200, 176, 192, 192, 1, 16),
+    for (H, W, Cin, Cout, s_, bo_) in ((400, 352, 96, 96, 1, 16), (400, 352, 96, 192, 2, 16), (200, 176, 192, 192, 1, 16),
                                        (396, 360, 64, 64, 1, 18)):
         x = torch.randn((1, H, W, Cin), device=dev).to(torch.bfloat16)
         w = torch.from_numpy(gen.conv_weights(r, 3, 3, Cin, Cout, "bf16")).to(torch.bfloat16).to(dev)
