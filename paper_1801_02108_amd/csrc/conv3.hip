@@ -846,7 +846,9 @@ bool conv3_try(sbnet_dtype dt, bool fused, const ConvParams &p0, hipStream_t s, 
             Shape3 wb, ws = plan3(p, 128, nbw);
             wb.ok = false;
             if (M > 128) wb = plan3(p, 256, nbw);
-            if (ws.ok && (long long)p.cap * ws.q.mpasses * ((p.Cout + 63) / 64) < (1LL << 31)) {
+            // (without a 256-pixel wide shape the launch also holds the 128-pixel shape with 64-channel groups)
+            if (ws.ok && (wb.ok || plan3(p, 128, 2, true).ok) &&
+                (long long)p.cap * ws.q.mpasses * ((p.Cout + 63) / 64) < (1LL << 31)) {
                 if (wb.ok && (long long)p.cap * ws.q.mpasses * ws.q.ngroups <= 256) wb.ok = false;    // as below
                 if (dt == SBNET_BF16) launch3_wide<SBNET_BF16>(fused, p, wb, ws, s);
                 else launch3_wide<SBNET_F16>(fused, p, wb, ws, s);
